@@ -1,0 +1,198 @@
+/*
+ * ssd_magc.h -- C ABI of the MI355X (gfx950) selective state-space scan with Multi-Axis
+ * Gradient Checkpointing.
+ *
+ * One SSD layer computes, for every (batch b, head h) with g the B/C group of h
+ * (paper Sec. 3.1, Eq. 1, in the Mamba-2 form: the transition is exp(dt_t*A_h) times the
+ * identity, the input matrix is dt_t*B_t, and the output carries a skip term D_h*x_t):
+ *
+ *     h_t[p,n]   = exp(dt[b,t,h]*A[h]) * h_{t-1}[p,n] + dt[b,t,h] * x[b,t,h,p] * B[b,t,g,n]
+ *     y[b,t,h,p] = sum_n C[b,t,g,n] * h_t[p,n] + D[h] * x[b,t,h,p]
+ *
+ * The sequence is cut into segments of `segment` tokens.  The forward pass keeps only the
+ * state entering each segment (the sequence-axis checkpoints of Sec. 3.2/3.3, Alg. 1); the
+ * backward pass walks the segments right to left, restores each segment's per-chunk states
+ * from its checkpoint and back-propagates through it, handing the state adjoint to the segment
+ * on its left (Alg. 2).  Because a state depends only on its predecessor (Sec. 3.2) this is
+ * exact: results do not depend on `segment` beyond floating-point summation order.
+ *
+ * General conventions
+ *   - Every data pointer is a DEVICE pointer unless its comment says "host".  The caller owns
+ *     all buffers; the library never allocates, frees or synchronises.  All work is enqueued on
+ *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *   - Tensors are dense row-major with the index order written in brackets; the batch stride
+ *     may be overridden through ssd_shape_t (elements, 0 = dense) so that a token range of a
+ *     longer sequence can be passed as a pointer offset.
+ *   - `dtype` is the storage type of x, dt, B, C, y and of dy, dx, ddt, dB, dC.  A, D, every
+ *     state and state adjoint, dA and dD are always fp32 (App. C keeps SSM states in fp32).
+ *     Arithmetic accumulates in fp32; outputs are rounded once (nearest-even).
+ *   - Every entry point returns 0 on success or a negative ssd_status_t.  Arguments are
+ *     validated before anything is launched; on a validation error nothing was enqueued and no
+ *     output was touched.  SSD_ERR_LAUNCH reports a HIP launch error (outputs undefined).
+ *     No C++ exception crosses this boundary.
+ */
+#ifndef SSD_MAGC_H
+#define SSD_MAGC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum ssd_dtype_t { SSD_F32 = 0, SSD_BF16 = 1 } ssd_dtype_t;
+
+typedef enum ssd_status_t {
+    SSD_OK = 0,
+    SSD_ERR_NULL = -1,         /* a required pointer is NULL */
+    SSD_ERR_SHAPE = -2,        /* a dimension is non-positive or exceeds a kernel limit */
+    SSD_ERR_DIVISIBILITY = -3, /* nheads % ngroups, seqlen % segment or segment % chunk is not 0 */
+    SSD_ERR_DTYPE = -4,        /* unknown dtype */
+    SSD_ERR_WORKSPACE = -5,    /* workspace NULL, misaligned (256 B) or smaller than ssd_workspace_bytes */
+    SSD_ERR_LAUNCH = -6,       /* a HIP call failed; see hipGetLastError */
+    SSD_ERR_BUDGET = -7,       /* magc_plan: no admissible (l, s) fits the budget (min-memory plan returned) */
+    SSD_ERR_ARG = -8           /* any other invalid argument */
+} ssd_status_t;
+
+/* Shape of one SSD layer call.  Limits: chunk in [1, 1024]; headdim, dstate in [1, 256]. */
+typedef struct ssd_shape_t {
+    int32_t dtype;            /* ssd_dtype_t */
+    int32_t nheads;           /* H */
+    int32_t headdim;          /* P */
+    int32_t ngroups;          /* G; H % G == 0; head h uses group h / (H/G) */
+    int32_t dstate;           /* N */
+    int32_t chunk;            /* Q: block length of the dual (quadratic) form; segment % Q == 0 */
+    int64_t batch;            /* Bt */
+    int64_t seqlen;           /* L (the paper's S); L % segment == 0 */
+    int64_t segment;          /* s: sequence-axis checkpoint interval; s == L means no checkpoints */
+    int64_t x_batch_stride;   /* elements between batches of x, y, dy, dx      (0 = L*H*P) */
+    int64_t dt_batch_stride;  /* elements between batches of dt, ddt           (0 = L*H)   */
+    int64_t bc_batch_stride;  /* elements between batches of B, C, dB, dC      (0 = L*G*N) */
+} ssd_shape_t;
+
+/* Flags for ssd_fwd / ssd_bwd. */
+enum {
+    SSD_FLAG_RESIDUAL = 1,        /* fwd: y = x + SSD(x);  bwd: dx = dy + VJP(dy)  (the residual stack's layer) */
+    SSD_FLAG_ACCUM_PARAM = 2,     /* bwd: dA, dD are added to instead of overwritten */
+    SSD_FLAG_GENERIC_KERNELS = 4  /* force the shape-generic fp32-FMA kernels even where the MFMA path applies */
+};
+
+/* Bytes of scratch the call needs for this shape (device memory, 256-byte aligned, contents
+ * undefined before and after).  It scales with `segment`, not with `seqlen`: this is the
+ * per-segment recomputation store (the M_state term of App. C).  Returns 0 for an invalid shape. */
+size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward);
+
+/*
+ * Forward (Layer_j(x, h) -> (x, h) of Alg. 1, for one layer over the whole sequence).
+ *   x  [Bt,L,H,P] dtype      dt [Bt,L,H] dtype (already positive; no bias or softplus is applied)
+ *   A  [H] fp32              B, C [Bt,L,G,N] dtype          D [H] fp32
+ *   init_state      [Bt,H,P,N] fp32, or NULL for zeros
+ *   y               [Bt,L,H,P] dtype, overwritten
+ *   final_state     [Bt,H,P,N] fp32, overwritten; may be NULL
+ *   boundary_states [Bt, L/segment, H, P, N] fp32, overwritten; slot k holds the state entering
+ *                   segment k (slot 0 = init_state or zeros).  May be NULL only if segment == L.
+ */
+int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+            const void* C, const float* D, const float* init_state, void* y, float* final_state,
+            float* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+            void* hip_stream);
+
+/*
+ * Backward (Recompute_Forward + Backward of Alg. 2 over every segment, right to left).
+ * Gradients of  <dy, y> + <dfinal_state, final_state>.
+ *   inputs as in ssd_fwd, plus
+ *   dy              [Bt,L,H,P] dtype
+ *   dfinal_state    [Bt,H,P,N] fp32, or NULL for zeros
+ *   boundary_states as written by ssd_fwd with the same shape (read only); may be NULL only if
+ *                   segment == L (then the single segment restarts from init_state)
+ *   dx [Bt,L,H,P], ddt [Bt,L,H], dB, dC [Bt,L,G,N] dtype, overwritten
+ *   dA, dD [H] fp32, overwritten (added to under SSD_FLAG_ACCUM_PARAM)
+ *   dinit_state     [Bt,H,P,N] fp32, overwritten; may be NULL
+ * dx may alias dy only if SSD_FLAG_RESIDUAL is not needed by the caller afterwards: each (chunk,
+ * head) tile of dy is fully read before the same tile of dx is written, but dB/dC kernels read dy
+ * again, so aliasing is NOT supported; pass distinct buffers.
+ */
+int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+            const void* C, const float* D, const float* init_state, const void* dy,
+            const float* dfinal_state, const float* boundary_states, void* dx, void* ddt, float* dA,
+            void* dB, void* dC, float* dD, float* dinit_state, void* workspace,
+            size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
+/*
+ * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the
+ * MA-GC grid of Sec. 3.2/3.3: layer-axis checkpoints every `layer_interval` layers (l) and
+ * sequence-axis checkpoints every shape->segment tokens (s).
+ *
+ * Per-layer parameters are stacked along a leading layer axis:
+ *   dt [nl,Bt,L,H], A [nl,H], B, C [nl,Bt,L,G,N], D [nl,H]   (batch-stride overrides must be 0)
+ * Checkpoint stores (device, caller-owned):
+ *   s_ckpt [nl, Bt, L/s, H, P, N] fp32 : state of layer j entering segment k          (Alg. 1)
+ *   l_ckpt [ceil(nl/l) - 1, Bt, L, H, P] dtype : input of layers l, 2l, ... ; the input of layer 0
+ *          is x0 itself and is not copied.  May be NULL when layer_interval >= nlayers.
+ * Forward order is segment-major (outer loop over segments, inner loop over layers) as in Alg. 1.
+ */
+size_t magc_stack_workspace_bytes(const ssd_shape_t* shape, int32_t nlayers, int32_t layer_interval,
+                                  int32_t is_backward);
+
+int magc_stack_fwd(const ssd_shape_t* shape, int32_t nlayers, int32_t layer_interval, const void* x0,
+                   const void* dt, const float* A, const void* B, const void* C, const float* D,
+                   void* out /*[Bt,L,H,P] dtype*/, float* final_states /*[nl,Bt,H,P,N] or NULL*/,
+                   float* s_ckpt, void* l_ckpt, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
+
+/*
+ * Backward over the grid (Alg. 2): segments right to left; inside a segment, layer blocks top to
+ * bottom; each cell restores its activations from (l_ckpt, s_ckpt), then back-propagates layer by
+ * layer, carrying grad-x down and the per-layer state adjoints left.
+ *   dout [Bt,L,H,P] dtype : gradient w.r.t. `out`
+ *   dx0  [Bt,L,H,P] dtype, overwritten
+ *   ddt [nl,Bt,L,H], dB, dC [nl,Bt,L,G,N] dtype; dA, dD [nl,H] fp32 : overwritten
+ * Final-state adjoints are taken as zero (the stack's loss depends on `out` only).
+ */
+int magc_stack_bwd(const ssd_shape_t* shape, int32_t nlayers, int32_t layer_interval, const void* x0,
+                   const void* dt, const float* A, const void* B, const void* C, const float* D,
+                   const void* dout, const float* s_ckpt, const void* l_ckpt, void* dx0, void* ddt,
+                   float* dA, void* dB, void* dC, float* dD, void* workspace, size_t workspace_bytes,
+                   void* hip_stream);
+
+/*
+ * Checkpoint-interval planner (host only; no device work).  Memory model of App. C:
+ *     M(l, s) = (L*S/l)*C_Lckpt + (L*S/s)*C_Sckpt + l*s*C_grid + s*C_state
+ * (all constants 1 and C_state 0 give the model of Sec. 3.3).  The search is exhaustive over
+ * l in [1, L] and s in the multiples of s_multiple within [s_multiple, S] when S >= s_multiple
+ * (Sec. 4 keeps s a multiple of 256 once S >= 256), else s in [1, S].  Ties: larger s, then
+ * smaller l.  With budget > 0 the plan with the least recomputation (largest s, then largest l)
+ * among those with M <= budget is returned; if none fits, the minimum-memory plan is filled in
+ * and SSD_ERR_BUDGET returned.  Constants are in whatever unit the caller likes (bytes,
+ * elements); M comes back in the same unit.
+ */
+typedef struct magc_model_t {
+    int64_t n_layers;        /* L */
+    int64_t seqlen;          /* S */
+    double c_lckpt;          /* per layer-checkpointed token */
+    double c_sckpt;          /* per sequence-checkpointed layer state */
+    double c_grid;           /* per (layer, token) alive inside a grid cell */
+    double c_state;          /* per token of the segment being restored */
+    int64_t s_multiple;      /* 256 in the paper; <= 1 disables the rule */
+    double budget;           /* <= 0: minimise M */
+    int32_t integer_counts;  /* 0: L/l and S/s as real quotients (the paper's formula); 1: ceil() of each */
+} magc_model_t;
+
+typedef struct magc_plan_t {
+    int64_t l, s;
+    double m_lckpt, m_sckpt, m_grid, m_state, m_total;
+    int32_t regime;          /* of the unweighted analysis, Sec. 3.3: 0 interior (L <= S^2 and S <= L^2),
+                                1 sequence-dominated (L^2 <= S), 2 layer-dominated (S^2 <= L) */
+    int32_t fits;            /* 1 if budget <= 0 or m_total <= budget */
+} magc_plan_t;
+
+int magc_plan(const magc_model_t* model /*host*/, magc_plan_t* out /*host*/);
+
+/* Static, human-readable text for a status code (host pointer, never NULL). */
+const char* ssd_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SSD_MAGC_H */

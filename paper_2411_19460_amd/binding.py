@@ -1,0 +1,242 @@
+"""Thin ctypes binding over libssd_magc.so: same names as the C ABI, argument marshalling only.
+
+PyTorch supplies device memory (`tensor.data_ptr()`) and the stream; every step of the
+computation runs inside the library's HIP kernels.  There is no CPU fallback: if the
+library is missing, loading fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
+
+SSD_F32, SSD_BF16 = 0, 1
+SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
+
+EXPORTS = ("ssd_workspace_bytes", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "magc_stack_bwd", "magc_plan", "ssd_strerror")
+
+
+class ssd_shape_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("nheads", ctypes.c_int32), ("headdim", ctypes.c_int32),
+                ("ngroups", ctypes.c_int32), ("dstate", ctypes.c_int32), ("chunk", ctypes.c_int32),
+                ("batch", ctypes.c_int64), ("seqlen", ctypes.c_int64), ("segment", ctypes.c_int64),
+                ("x_batch_stride", ctypes.c_int64), ("dt_batch_stride", ctypes.c_int64),
+                ("bc_batch_stride", ctypes.c_int64)]
+
+
+class magc_model_t(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int64), ("seqlen", ctypes.c_int64), ("c_lckpt", ctypes.c_double),
+                ("c_sckpt", ctypes.c_double), ("c_grid", ctypes.c_double), ("c_state", ctypes.c_double),
+                ("s_multiple", ctypes.c_int64), ("budget", ctypes.c_double), ("integer_counts", ctypes.c_int32)]
+
+
+class magc_plan_t(ctypes.Structure):
+    _fields_ = [("l", ctypes.c_int64), ("s", ctypes.c_int64), ("m_lckpt", ctypes.c_double),
+                ("m_sckpt", ctypes.c_double), ("m_grid", ctypes.c_double), ("m_state", ctypes.c_double),
+                ("m_total", ctypes.c_double), ("regime", ctypes.c_int32), ("fits", ctypes.c_int32)]
+
+
+class SSDError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {strerror(status)} (status {status})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads the shared library (once).  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2411_19460_amd.build` "
+                               "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, sz, i32, u32 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_uint32
+        shp = ctypes.POINTER(ssd_shape_t)
+        L.ssd_workspace_bytes.restype = sz
+        L.ssd_workspace_bytes.argtypes = [shp, i32]
+        L.ssd_fwd.restype = ctypes.c_int
+        L.ssd_fwd.argtypes = [shp] + [vp] * 10 + [vp, sz, u32, vp]
+        L.ssd_bwd.restype = ctypes.c_int
+        L.ssd_bwd.argtypes = [shp] + [vp] * 17 + [vp, sz, u32, vp]
+        L.magc_stack_workspace_bytes.restype = sz
+        L.magc_stack_workspace_bytes.argtypes = [shp, i32, i32, i32]
+        L.magc_stack_fwd.restype = ctypes.c_int
+        L.magc_stack_fwd.argtypes = [shp, i32, i32] + [vp] * 10 + [vp, sz, vp]
+        L.magc_stack_bwd.restype = ctypes.c_int
+        L.magc_stack_bwd.argtypes = [shp, i32, i32] + [vp] * 15 + [vp, sz, vp]
+        L.magc_plan.restype = ctypes.c_int
+        L.magc_plan.argtypes = [ctypes.POINTER(magc_model_t), ctypes.POINTER(magc_plan_t)]
+        L.ssd_strerror.restype = ctypes.c_char_p
+        L.ssd_strerror.argtypes = [ctypes.c_int]
+        _lib = L
+    return _lib
+
+
+def strerror(status: int) -> str:
+    return lib().ssd_strerror(int(status)).decode()
+
+
+def _ptr(t) -> Optional[int]:
+    return None if t is None else t.data_ptr()
+
+
+def _stream(t) -> Optional[int]:
+    import torch
+    return torch.cuda.current_stream(t.device).cuda_stream or None
+
+
+def make_shape(x, Bm, chunk: int, segment: Optional[int] = None) -> ssd_shape_t:
+    import torch
+    Bt, L, H, P = x.shape
+    G, N = Bm.shape[2], Bm.shape[3]
+    if x.dtype == torch.bfloat16:
+        dt = SSD_BF16
+    elif x.dtype == torch.float32:
+        dt = SSD_F32
+    else:
+        raise TypeError(f"unsupported dtype {x.dtype}")
+    return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, L if segment is None else segment, 0, 0, 0)
+
+
+def ssd_workspace_bytes(shape: ssd_shape_t, is_backward: bool) -> int:
+    return int(lib().ssd_workspace_bytes(ctypes.byref(shape), 1 if is_backward else 0))
+
+
+def _check_inputs(x, dt, A, Bm, Cm, D, *more):
+    import torch
+    for t in (x, dt, Bm, Cm) + tuple(m for m in more if m is not None):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    for t in (dt, Bm, Cm):
+        if t.dtype != x.dtype:
+            raise TypeError("x, dt, B, C must share one storage dtype")
+    for t in (A, D):
+        if t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise TypeError("A and D must be contiguous fp32 device tensors")
+
+
+def _workspace(nbytes: int, device):
+    import torch
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
+
+
+def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, workspace=None, want_final=True):
+    """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L."""
+    import torch
+    _check_inputs(x, dt, A, B, C, D, init_state)
+    shape = make_shape(x, B, chunk, segment)
+    Bt, L, H, P = x.shape
+    N = B.shape[3]
+    y = torch.empty_like(x)
+    final = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device) if want_final else None
+    nseg = L // shape.segment if L > 0 and shape.segment > 0 and L % shape.segment == 0 else 1
+    bnd = None
+    if segment is not None:
+        bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)
+    need = ssd_workspace_bytes(shape, False)
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    rc = lib().ssd_fwd(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(init_state),
+                       _ptr(y), _ptr(final), _ptr(bnd), _ptr(workspace), workspace.numel(), flags, _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_fwd")
+    return y, final, bnd
+
+
+def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,
+            flags=0, workspace=None, dA=None, dD=None, want_dinit=True):
+    """Returns dict(dx, ddt, dA, dB, dC, dD, dinit_state)."""
+    import torch
+    _check_inputs(x, dt, A, B, C, D, dy, init_state, dfinal_state, boundary_states)
+    shape = make_shape(x, B, chunk, segment)
+    Bt, L, H, P = x.shape
+    N = B.shape[3]
+    dx = torch.empty_like(x)
+    ddt = torch.empty_like(dt)
+    dB = torch.empty_like(B)
+    dC = torch.empty_like(C)
+    if dA is None:
+        dA = torch.empty((H,), dtype=torch.float32, device=x.device)
+    if dD is None:
+        dD = torch.empty((H,), dtype=torch.float32, device=x.device)
+    dinit = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device) if want_dinit else None
+    need = ssd_workspace_bytes(shape, True)
+    if workspace is None:
+        workspace = _workspace(need, x.device)
+    rc = lib().ssd_bwd(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(init_state),
+                       _ptr(dy), _ptr(dfinal_state), _ptr(boundary_states), _ptr(dx), _ptr(ddt), _ptr(dA), _ptr(dB),
+                       _ptr(dC), _ptr(dD), _ptr(dinit), _ptr(workspace), workspace.numel(), flags, _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_bwd")
+    return {"dx": dx, "ddt": ddt, "dA": dA, "dB": dB, "dC": dC, "dD": dD, "dinit_state": dinit}
+
+
+def magc_stack_workspace_bytes(shape: ssd_shape_t, nlayers: int, layer_interval: int, is_backward: bool) -> int:
+    return int(lib().magc_stack_workspace_bytes(ctypes.byref(shape), nlayers, layer_interval, 1 if is_backward else 0))
+
+
+def magc_stack_fwd(x0, dt, A, B, C, D, chunk, segment, layer_interval, workspace=None, want_final=True):
+    """dt [nl,Bt,L,H], A/D [nl,H], B/C [nl,Bt,L,G,N].  Returns dict(out, final_states, s_ckpt, l_ckpt)."""
+    import torch
+    nl = dt.shape[0]
+    _check_inputs(x0, dt, A, B[0], C[0], D)
+    shape = make_shape(x0, B[0], chunk, segment)
+    Bt, L, H, P = x0.shape
+    N = B.shape[4]
+    nseg = L // segment
+    l = min(layer_interval, nl)
+    nlg = (nl + l - 1) // l
+    out = torch.empty_like(x0)
+    finals = torch.empty((nl, Bt, H, P, N), dtype=torch.float32, device=x0.device) if want_final else None
+    s_ckpt = torch.empty((nl, Bt, nseg, H, P, N), dtype=torch.float32, device=x0.device)
+    l_ckpt = torch.empty((nlg - 1, Bt, L, H, P), dtype=x0.dtype, device=x0.device) if nlg > 1 else None
+    if workspace is None:
+        workspace = _workspace(magc_stack_workspace_bytes(shape, nl, layer_interval, False), x0.device)
+    rc = lib().magc_stack_fwd(ctypes.byref(shape), nl, layer_interval, _ptr(x0), _ptr(dt), _ptr(A), _ptr(B), _ptr(C),
+                              _ptr(D), _ptr(out), _ptr(finals), _ptr(s_ckpt), _ptr(l_ckpt), _ptr(workspace),
+                              workspace.numel(), _stream(x0))
+    if rc != 0:
+        raise SSDError(rc, "magc_stack_fwd")
+    return {"out": out, "final_states": finals, "s_ckpt": s_ckpt, "l_ckpt": l_ckpt}
+
+
+def magc_stack_bwd(x0, dt, A, B, C, D, dout, s_ckpt, l_ckpt, chunk, segment, layer_interval, workspace=None):
+    """Returns dict(dx0, ddt, dA, dB, dC, dD) with the per-layer gradients stacked like the inputs."""
+    import torch
+    nl = dt.shape[0]
+    _check_inputs(x0, dt, A, B[0], C[0], D, dout, s_ckpt, l_ckpt)
+    shape = make_shape(x0, B[0], chunk, segment)
+    H = x0.shape[2]
+    dx0 = torch.empty_like(x0)
+    ddt = torch.empty_like(dt)
+    dB = torch.empty_like(B)
+    dC = torch.empty_like(C)
+    dA = torch.empty((nl, H), dtype=torch.float32, device=x0.device)
+    dD = torch.empty((nl, H), dtype=torch.float32, device=x0.device)
+    if workspace is None:
+        workspace = _workspace(magc_stack_workspace_bytes(shape, nl, layer_interval, True), x0.device)
+    rc = lib().magc_stack_bwd(ctypes.byref(shape), nl, layer_interval, _ptr(x0), _ptr(dt), _ptr(A), _ptr(B), _ptr(C),
+                              _ptr(D), _ptr(dout), _ptr(s_ckpt), _ptr(l_ckpt), _ptr(dx0), _ptr(ddt), _ptr(dA),
+                              _ptr(dB), _ptr(dC), _ptr(dD), _ptr(workspace), workspace.numel(), _stream(x0))
+    if rc != 0:
+        raise SSDError(rc, "magc_stack_bwd")
+    return {"dx0": dx0, "ddt": ddt, "dA": dA, "dB": dB, "dC": dC, "dD": dD}
+
+
+def magc_plan(n_layers, seqlen, c_lckpt, c_sckpt, c_grid, c_state, s_multiple=256, budget=0.0, integer_counts=False):
+    """Host-only planner.  Returns (status, dict).  status is 0 or SSD_ERR_BUDGET (-7) with the
+    minimum-memory plan filled in; any other error raises."""
+    m = magc_model_t(n_layers, seqlen, c_lckpt, c_sckpt, c_grid, c_state, s_multiple, budget, 1 if integer_counts else 0)
+    p = magc_plan_t()
+    rc = lib().magc_plan(ctypes.byref(m), ctypes.byref(p))
+    if rc not in (0, -7):
+        raise SSDError(rc, "magc_plan")
+    return rc, {"l": p.l, "s": p.s, "m_lckpt": p.m_lckpt, "m_sckpt": p.m_sckpt, "m_grid": p.m_grid,
+                "m_state": p.m_state, "m_total": p.m_total, "regime": p.regime, "fits": bool(p.fits)}

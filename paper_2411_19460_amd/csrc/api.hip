@@ -1,0 +1,283 @@
+// C-ABI entry points for one SSD layer: argument validation, workspace partitioning and the
+// segment loops of the MA-GC sequence axis (paper Sec. 3.2/3.3, Alg. 1 and Alg. 2).
+#include <string.h>
+
+#include "ssd_internal.h"
+
+namespace ssdk {
+
+inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+// Returns SSD_OK and fills d, or the validation error.
+int check_shape(const ssd_shape_t* sh, Dims* d) {
+    if (!sh) return SSD_ERR_NULL;
+    if (sh->dtype != SSD_F32 && sh->dtype != SSD_BF16) return SSD_ERR_DTYPE;
+    if (sh->batch <= 0 || sh->seqlen < 0 || sh->nheads <= 0 || sh->headdim <= 0 || sh->ngroups <= 0 ||
+        sh->dstate <= 0 || sh->chunk <= 0)
+        return SSD_ERR_SHAPE;
+    if (sh->chunk > 1024 || sh->headdim > 256 || sh->dstate > 256) return SSD_ERR_SHAPE;
+    if (sh->batch > 65535 || sh->nheads > 65535) return SSD_ERR_SHAPE;
+    if (sh->nheads % sh->ngroups != 0) return SSD_ERR_DIVISIBILITY;
+    if (sh->seqlen > 0) {
+        if (sh->segment <= 0) return SSD_ERR_SHAPE;
+        if (sh->seqlen % sh->segment != 0 || sh->segment % sh->chunk != 0) return SSD_ERR_DIVISIBILITY;
+    }
+    d->Bt = sh->batch;
+    d->L = sh->seqlen;
+    d->s = sh->seqlen > 0 ? sh->segment : 0;
+    d->H = sh->nheads;
+    d->P = sh->headdim;
+    d->G = sh->ngroups;
+    d->N = sh->dstate;
+    d->Q = sh->chunk;
+    d->hpg = d->H / d->G;
+    d->nc = sh->seqlen > 0 ? (int)(sh->segment / sh->chunk) : 0;
+    d->nseg = sh->seqlen > 0 ? sh->seqlen / sh->segment : 0;
+    d->bf16 = sh->dtype == SSD_BF16;
+    d->esz = d->bf16 ? 2 : 4;
+    d->xs_b = sh->x_batch_stride ? sh->x_batch_stride : d->L * d->H * d->P;
+    d->dts_b = sh->dt_batch_stride ? sh->dt_batch_stride : d->L * d->H;
+    d->bcs_b = sh->bc_batch_stride ? sh->bc_batch_stride : d->L * d->G * d->N;
+    if (d->xs_b < d->L * d->H * d->P || d->dts_b < d->L * d->H || d->bcs_b < d->L * d->G * d->N) return SSD_ERR_SHAPE;
+    // every launch keeps its largest grid dimension below 2^31
+    const int64_t blocks = d->Bt * (int64_t)d->nc * d->H * 2;
+    if (blocks >= ((int64_t)1 << 31) || (int64_t)sh->segment / sh->chunk >= ((int64_t)1 << 24)) return SSD_ERR_SHAPE;
+    return SSD_OK;
+}
+
+WsLayout ws_layout(const Dims& d, bool bwd) {
+    WsLayout w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        size_t o = off;
+        off += align_up(bytes);
+        return o;
+    };
+    const size_t tok = (size_t)d.Bt * d.H * d.nc * d.Q * 4;
+    const size_t PN = (size_t)d.P * d.N;
+    w.nslice = (int)((PN + 255) / 256);
+    w.cum = take(tok);
+    w.dtf = take(tok);
+    w.states = take((size_t)d.Bt * (d.nc + 1) * d.H * PN * 4);
+    w.Gm = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
+    if (bwd) {
+        w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
+        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
+        w.gterm = take(tok);
+        w.fterm = take(tok);
+        w.dDrow = take(tok);
+        w.tail_part = take((size_t)d.Bt * d.H * d.nc * w.nslice * 4);
+        w.dA_part = take((size_t)d.Bt * d.nc * d.H * 4);
+        w.dD_part = take((size_t)d.Bt * d.nc * d.H * 4);
+        w.dcarry = take((size_t)d.Bt * d.H * PN * 4);
+    }
+    w.total = off;
+    return w;
+}
+
+void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd) {
+    char* base = (char*)workspace;
+    sp.cum = (float*)(base + w.cum);
+    sp.dtf = (float*)(base + w.dtf);
+    sp.states = (float*)(base + w.states);
+    sp.Gm = (float*)(base + w.Gm);
+    sp.nslice = w.nslice;
+    if (bwd) {
+        sp.dstates = (float*)(base + w.dstates);
+        sp.dG = (float*)(base + w.dG);
+        sp.gterm = (float*)(base + w.gterm);
+        sp.fterm = (float*)(base + w.fterm);
+        sp.dDrow = (float*)(base + w.dDrow);
+        sp.tail_part = (float*)(base + w.tail_part);
+        sp.dA_part = (float*)(base + w.dA_part);
+        sp.dD_part = (float*)(base + w.dD_part);
+        sp.dcarry = (float*)(base + w.dcarry);
+    }
+}
+
+void base_params(SegParams& sp, const Dims& d, uint32_t flags) {
+    memset(&sp, 0, sizeof(sp));
+    sp.Bt = (int)d.Bt;
+    sp.H = d.H;
+    sp.P = d.P;
+    sp.G = d.G;
+    sp.N = d.N;
+    sp.Q = d.Q;
+    sp.nc = d.nc;
+    sp.hpg = d.hpg;
+    sp.xs_b = sp.ys_b = sp.dys_b = sp.dxs_b = d.xs_b;
+    sp.dts_b = d.dts_b;
+    sp.bcs_b = d.bcs_b;
+    sp.flags = flags;
+}
+
+static inline const void* off(const void* p, int64_t elems, size_t esz) { return p ? (const char*)p + elems * (int64_t)esz : nullptr; }
+static inline void* off(void* p, int64_t elems, size_t esz) { return p ? (char*)p + elems * (int64_t)esz : nullptr; }
+
+bool use_mfma(const ssd_shape_t& sh, uint32_t flags) {
+    return !(flags & SSD_FLAG_GENERIC_KERNELS) && mfma_path_supported(sh);
+}
+
+// Points the scan of segment k at its entering state and at the places its leaving state goes.
+static void wire_states(SegParams& sp, const Dims& d, int64_t k, const float* init_state, const float* bnd_ro,
+                        float* bnd_rw, float* final_state) {
+    const int64_t HPN = (int64_t)d.H * d.P * d.N;
+    if (k == 0 || !bnd_ro) {
+        sp.state_in = init_state;
+        sp.state_in_bs = HPN;
+    } else {
+        sp.state_in = bnd_ro + k * HPN;
+        sp.state_in_bs = d.nseg * HPN;
+    }
+    sp.bnd_write = nullptr;
+    sp.state_out = nullptr;
+    sp.state_out2 = nullptr;
+    if (bnd_rw) {
+        if (k == 0) {
+            sp.bnd_write = bnd_rw;
+            sp.bnd_write_bs = d.nseg * HPN;
+        }
+        if (k + 1 < d.nseg) {
+            sp.state_out = bnd_rw + (k + 1) * HPN;
+            sp.state_out_bs = d.nseg * HPN;
+        }
+    }
+    if (k + 1 == d.nseg && final_state) {
+        sp.state_out2 = final_state;
+        sp.state_out2_bs = HPN;
+    }
+}
+
+}  // namespace ssdk
+
+using namespace ssdk;
+
+extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward) {
+    Dims d;
+    if (check_shape(shape, &d) != SSD_OK) return 0;
+    // never 0 for a valid shape, so that 0 unambiguously means "invalid"
+    const size_t t = ws_layout(d, is_backward != 0).total;
+    return t ? t : 256;
+}
+
+extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                       const void* C, const float* D, const float* init_state, void* y, float* final_state,
+                       float* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+                       void* hip_stream) {
+    Dims d;
+    int rc = check_shape(shape, &d);
+    if (rc != SSD_OK) return rc;
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM)) return SSD_ERR_ARG;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t HPN = (size_t)d.H * d.P * d.N;
+    if (d.L == 0) {  // empty sequence: the state passes through untouched
+        if (final_state) {
+            hipError_t e = init_state ? launch_copy_f32(final_state, init_state, (size_t)d.Bt * HPN, st)
+                                      : launch_fill_zero(final_state, (size_t)d.Bt * HPN, st);
+            if (e != hipSuccess) return SSD_ERR_LAUNCH;
+        }
+        return SSD_OK;
+    }
+    if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
+    if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
+    const WsLayout w = ws_layout(d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+
+    const bool mfma = use_mfma(*shape, flags);
+    SegParams sp;
+    base_params(sp, d, flags);
+    bind_workspace(sp, w, workspace, false);
+    sp.A = A;
+    sp.D = D;
+    for (int64_t k = 0; k < d.nseg; ++k) {
+        const int64_t t0 = k * d.s;
+        sp.x = off(x, t0 * d.H * d.P, d.esz);
+        sp.y = off(y, t0 * d.H * d.P, d.esz);
+        sp.dt = off(dt, t0 * d.H, d.esz);
+        sp.Bm = off(B, t0 * d.G * d.N, d.esz);
+        sp.Cm = off(C, t0 * d.G * d.N, d.esz);
+        wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
+        hipError_t e = mfma ? mfma_forward_segment(sp, true, st) : generic_forward_segment(sp, d.bf16, true, st);
+        if (e != hipSuccess) return SSD_ERR_LAUNCH;
+    }
+    return SSD_OK;
+}
+
+extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                       const void* C, const float* D, const float* init_state, const void* dy,
+                       const float* dfinal_state, const float* boundary_states, void* dx, void* ddt, float* dA,
+                       void* dB, void* dC, float* dD, float* dinit_state, void* workspace, size_t workspace_bytes,
+                       uint32_t flags, void* hip_stream) {
+    Dims d;
+    int rc = check_shape(shape, &d);
+    if (rc != SSD_OK) return rc;
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM)) return SSD_ERR_ARG;
+    if (!dA || !dD) return SSD_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t HPN = (size_t)d.H * d.P * d.N;
+    if (d.L == 0) {  // empty sequence: the state adjoint passes through, parameter gradients are zero
+        hipError_t e = hipSuccess;
+        if (dinit_state)
+            e = dfinal_state ? launch_copy_f32(dinit_state, dfinal_state, (size_t)d.Bt * HPN, st)
+                             : launch_fill_zero(dinit_state, (size_t)d.Bt * HPN, st);
+        if (e == hipSuccess && !(flags & SSD_FLAG_ACCUM_PARAM)) {
+            e = launch_fill_zero(dA, d.H, st);
+            if (e == hipSuccess) e = launch_fill_zero(dD, d.H, st);
+        }
+        return e == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+    }
+    if (!x || !dt || !A || !B || !C || !D || !dy || !dx || !ddt || !dB || !dC) return SSD_ERR_NULL;
+    if (dx == dy) return SSD_ERR_ARG;
+    if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
+    const WsLayout w = ws_layout(d, true);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+
+    const bool mfma = use_mfma(*shape, flags);
+    SegParams sp;
+    base_params(sp, d, flags);
+    bind_workspace(sp, w, workspace, true);
+    sp.A = A;
+    sp.D = D;
+    sp.dA = dA;
+    sp.dD = dD;
+    hipError_t e = dfinal_state ? launch_copy_f32(sp.dcarry, dfinal_state, (size_t)d.Bt * HPN, st)
+                                : launch_fill_zero(sp.dcarry, (size_t)d.Bt * HPN, st);
+    if (e != hipSuccess) return SSD_ERR_LAUNCH;
+    for (int64_t k = d.nseg - 1; k >= 0; --k) {
+        const int64_t t0 = k * d.s;
+        sp.x = off(x, t0 * d.H * d.P, d.esz);
+        sp.dy = off(dy, t0 * d.H * d.P, d.esz);
+        sp.dx = off(dx, t0 * d.H * d.P, d.esz);
+        sp.dt = off(dt, t0 * d.H, d.esz);
+        sp.ddt = off(ddt, t0 * d.H, d.esz);
+        sp.Bm = off(B, t0 * d.G * d.N, d.esz);
+        sp.Cm = off(C, t0 * d.G * d.N, d.esz);
+        sp.dB = off(dB, t0 * d.G * d.N, d.esz);
+        sp.dC = off(dC, t0 * d.G * d.N, d.esz);
+        // restore: per-chunk entering states of this segment from its checkpoint
+        wire_states(sp, d, k, init_state, boundary_states, nullptr, nullptr);
+        e = mfma ? mfma_forward_segment(sp, false, st) : generic_forward_segment(sp, d.bf16, false, st);
+        if (e != hipSuccess) return SSD_ERR_LAUNCH;
+        sp.dinit_out = (k == 0) ? dinit_state : nullptr;
+        sp.accumulate = (k == d.nseg - 1) ? ((flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0) : 1;
+        e = mfma ? mfma_backward_segment(sp, st) : generic_backward_segment(sp, d.bf16, st);
+        if (e != hipSuccess) return SSD_ERR_LAUNCH;
+    }
+    return SSD_OK;
+}
+
+extern "C" const char* ssd_strerror(int status) {
+    switch (status) {
+        case SSD_OK: return "ok";
+        case SSD_ERR_NULL: return "a required pointer is NULL";
+        case SSD_ERR_SHAPE: return "a dimension is non-positive or exceeds a kernel limit";
+        case SSD_ERR_DIVISIBILITY: return "nheads % ngroups, seqlen % segment or segment % chunk is not zero";
+        case SSD_ERR_DTYPE: return "unknown dtype";
+        case SSD_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
+        case SSD_ERR_LAUNCH: return "a HIP launch failed";
+        case SSD_ERR_BUDGET: return "no admissible checkpoint plan fits the budget";
+        case SSD_ERR_ARG: return "invalid argument";
+        default: return "unknown status";
+    }
+}

@@ -1,0 +1,590 @@
+// Shape-generic kernels of the chunked selective scan: fp32 FMA arithmetic, any P, N, Q within
+// the documented limits, fp32 or bf16 storage.  They serve the fp32 configuration, odd shapes,
+// and as an on-device cross-check of the MFMA kernels.
+//
+// The chunked ("dual") form of the recurrence of Sec. 3.1, Eq. 1, per (batch, head) and per chunk
+// of Q tokens with entering state Hprev (local indices i, j in [0, Q)):
+//     a_j = dt_j A, cum_i = sum_{r<=i} a_r, T = cum_{Q-1}, G[i,j] = C_i . B_j
+//     S      = sum_j exp(T - cum_j) dt_j x_j (x) B_j           Hnext = exp(T) Hprev + S
+//     yhat_i = sum_{j<=i} G[i,j] exp(cum_i - cum_j) dt_j x_j + exp(cum_i) Hprev C_i,   y = yhat + D x
+// and, given dY and dHnext,
+//     dHprev = exp(T) dHnext + sum_i exp(cum_i) dY_i (x) C_i
+//     u_j    = sum_{i>=j} G[i,j] exp(cum_i - cum_j) dY_i + exp(T - cum_j) dHnext B_j,   dx_j = dt_j u_j + D dY_j
+//     dG     = sum_{heads of the group} [exp(cum_i - cum_j) dt_j (dY_i . x_j)]_{j<=i}
+//     dC_i   = sum_j dG[i,j] B_j + sum_heads exp(cum_i) dY_i^T Hprev
+//     dB_j   = sum_i dG[i,j] C_i + sum_heads exp(T - cum_j) dt_j x_j^T dHnext
+//     da_r   = sum_{i>=r} (dY_i . yhat_i - dt_i x_i . u_i) + <dHnext, Hnext>
+//     ddt_j  = A da_j + x_j . u_j,  dA += sum_j dt_j da_j,  dD += sum dY . x
+// Every exponent is formed from a difference that is <= 0, so nothing overflows.
+#include "ssd_internal.h"
+
+namespace ssdk {
+namespace {
+
+template <typename T>
+struct IO;
+template <>
+struct IO<float> {
+    static __device__ __forceinline__ float ld(const void* p, int64_t i) { return ((const float*)p)[i]; }
+    static __device__ __forceinline__ void st(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
+};
+template <>
+struct IO<bf16_t> {
+    static __device__ __forceinline__ float ld(const void* p, int64_t i) { return bf16_to_float(((const bf16_t*)p)[i]); }
+    static __device__ __forceinline__ void st(void* p, int64_t i, float v) { ((bf16_t*)p)[i] = float_to_bf16(v); }
+};
+
+constexpr int TS = 32;        // tile edge
+constexpr int NTHREADS = 256; // 32 x 8 threads, each owning rows ty, ty+8, ty+16, ty+24 of column tx
+
+// acc[r] += sum_{k in [kbeg, kend)} fa(row ty+8r, k) * fb(k, col tx); kbeg is a multiple of 32.
+// fa / fb return 0 outside their domain.  All 256 threads of the block must call this together.
+template <class FA, class FB>
+__device__ __forceinline__ void tile_gemm(float (&acc)[4], int kbeg, int kend, FA fa, FB fb, float (*As)[TS + 1],
+                                          float (*Bs)[TS + 1]) {
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    for (int k0 = kbeg; k0 < kend; k0 += TS) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int row = ty + 8 * r;
+            As[row][tx] = fa(row, k0 + tx);
+            Bs[row][tx] = fb(k0 + row, tx);
+        }
+        __syncthreads();
+#pragma unroll 8
+        for (int k = 0; k < TS; ++k) {
+            const float bv = Bs[k][tx];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] = fmaf(As[ty + 8 * r][k], bv, acc[r]);
+        }
+        __syncthreads();
+    }
+}
+
+__global__ void k_fill_zero(float* p, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) p[i] = 0.f;
+}
+
+__global__ void k_copy_f32(float* dst, const float* src, size_t n) {
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (; i < n; i += stride) dst[i] = src[i];
+}
+
+// cum[b,h,c,i] = inclusive prefix sum over the chunk of dt*A; dtf = dt in fp32, head-major.
+template <typename T>
+__global__ void k_cumsum(SegParams sp) {
+    __shared__ float s[1024];
+    const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    float d = 0.f;
+    if (i < sp.Q) d = IO<T>::ld(sp.dt, (int64_t)b * sp.dts_b + ((int64_t)c * sp.Q + i) * sp.H + h);
+    s[i] = d * sp.A[h];
+    __syncthreads();
+    for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+        const float v = (i >= off) ? s[i - off] : 0.f;
+        __syncthreads();
+        s[i] += v;
+        __syncthreads();
+    }
+    if (i < sp.Q) {
+        const int64_t o = (((int64_t)b * sp.H + h) * sp.nc + c) * sp.Q + i;
+        sp.cum[o] = s[i];
+        sp.dtf[o] = d;
+    }
+}
+
+// Gm[b,c,g,i,j] = C_i . B_j for the tiles that touch the lower triangle.
+template <typename T>
+__global__ void k_cb(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int j0 = blockIdx.y * TS, i0 = blockIdx.z * TS;
+    if (j0 > i0) return;
+    const int z = blockIdx.x, g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int Q = sp.Q, N = sp.N;
+    const int64_t base = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N;  // token stride G*N
+    const int64_t tstride = (int64_t)sp.G * N;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    tile_gemm(
+        acc, 0, N,
+        [&](int r, int k) { return (i0 + r < Q && k < N) ? IO<T>::ld(sp.Cm, base + (int64_t)(i0 + r) * tstride + k) : 0.f; },
+        [&](int k, int col) { return (j0 + col < Q && k < N) ? IO<T>::ld(sp.Bm, base + (int64_t)(j0 + col) * tstride + k) : 0.f; },
+        As, Bs);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    float* out = sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * Q * Q;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + ty + 8 * r, j = j0 + tx;
+        if (i < Q && j < Q) out[(int64_t)i * Q + j] = acc[r];
+    }
+}
+
+// mode 0: states[b,c,h,p,n]  = sum_j exp(T - cum_j) dt_j x_j[p] B_j[n]
+// mode 1: dstates[b,c,h,p,n] = sum_i exp(cum_i) dY_i[p] C_i[n]
+template <typename T, int MODE>
+__global__ void k_chunk_outer(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int n0 = blockIdx.y * TS, p0 = blockIdx.z * TS;
+    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
+    const int Q = sp.Q, N = sp.N, P = sp.P, g = h / sp.hpg;
+    const float* cum = sp.cum + (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float* dtf = sp.dtf + (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float T_ = cum[Q - 1];
+    const void* lhs = MODE == 0 ? sp.x : sp.dy;
+    const void* rhs = MODE == 0 ? sp.Bm : sp.Cm;
+    const int64_t xbase = (int64_t)b * (MODE == 0 ? sp.xs_b : sp.dys_b) + ((int64_t)c * Q * sp.H + h) * P;
+    const int64_t xt = (int64_t)sp.H * P;
+    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N;
+    const int64_t bt = (int64_t)sp.G * N;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    tile_gemm(
+        acc, 0, Q,
+        [&](int r, int k) {
+            if (p0 + r >= P || k >= Q) return 0.f;
+            const float w = MODE == 0 ? expf(T_ - cum[k]) * dtf[k] : expf(cum[k]);
+            return w * IO<T>::ld(lhs, xbase + (int64_t)k * xt + p0 + r);
+        },
+        [&](int k, int col) { return (k < Q && n0 + col < N) ? IO<T>::ld(rhs, bbase + (int64_t)k * bt + n0 + col) : 0.f; },
+        As, Bs);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    float* out = MODE == 0 ? sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * P * N
+                           : sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * P * N;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int p = p0 + ty + 8 * r, n = n0 + tx;
+        if (p < P && n < N) out[(int64_t)p * N + n] = acc[r];
+    }
+}
+
+// Inter-chunk state passing over one segment: one thread per state element, sequential in chunks.
+__global__ void k_state_scan_fwd(SegParams sp) {
+    const int PN = sp.P * sp.N;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+    if (e >= PN) return;
+    const int64_t bh = ((int64_t)h) * PN + e;
+    float hc = sp.state_in ? sp.state_in[(int64_t)b * sp.state_in_bs + bh] : 0.f;
+    if (sp.bnd_write) sp.bnd_write[(int64_t)b * sp.bnd_write_bs + bh] = hc;
+    const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    for (int c = 0; c < sp.nc; ++c) {
+        const int64_t idx = (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e;
+        const float s = sp.states[idx];
+        sp.states[idx] = hc;
+        hc = expf(cum[(int64_t)c * sp.Q + sp.Q - 1]) * hc + s;
+    }
+    sp.states[(((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e] = hc;
+    if (sp.state_out) sp.state_out[(int64_t)b * sp.state_out_bs + bh] = hc;
+    if (sp.state_out2) sp.state_out2[(int64_t)b * sp.state_out2_bs + bh] = hc;
+}
+
+// Reverse pass over the chunk-state adjoints; also emits the partial sums of <dHnext_c, Hnext_c>.
+__global__ void k_state_scan_bwd(SegParams sp) {
+    __shared__ float red[NTHREADS / 64];
+    const int PN = sp.P * sp.N;
+    const int e = blockIdx.x * blockDim.x + threadIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const bool live = e < PN;
+    const int64_t ce = ((int64_t)b * sp.H + h) * PN + e;
+    float g = live ? sp.dcarry[ce] : 0.f;
+    const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    for (int c = sp.nc - 1; c >= 0; --c) {
+        float loc = 0.f, part = 0.f;
+        if (live) {
+            const int64_t idx = (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e;
+            loc = sp.dstates[idx];
+            sp.dstates[idx] = g;
+            part = g * sp.states[(((int64_t)b * (sp.nc + 1) + c + 1) * sp.H + h) * PN + e];
+        }
+        // block reduction of part (fixed order: deterministic)
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = part;
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            float t = 0.f;
+            for (int w = 0; w < NTHREADS / 64; ++w) t += red[w];
+            sp.tail_part[((((int64_t)b * sp.H + h) * sp.nc + c)) * sp.nslice + blockIdx.x] = t;
+        }
+        __syncthreads();
+        g = expf(cum[(int64_t)c * sp.Q + sp.Q - 1]) * g + loc;
+    }
+    if (live) {
+        sp.dcarry[ce] = g;
+        if (sp.dinit_out) sp.dinit_out[ce] = g;
+    }
+}
+
+// y = (G o decay o dt) X + exp(cum) C Hprev^T + D x   (+ x under the residual flag)
+template <typename T>
+__global__ void k_chunk_out(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int p0 = blockIdx.y * TS, i0 = blockIdx.z * TS;
+    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
+    const int Q = sp.Q, N = sp.N, P = sp.P, g = h / sp.hpg;
+    const float* cum = sp.cum + (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float* dtf = sp.dtf + (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float* Gm = sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * Q * Q;
+    const float* Hprev = sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * P * N;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P;
+    const int64_t xbase = (int64_t)b * sp.xs_b + xrow, ybase = (int64_t)b * sp.ys_b + xrow;
+    const int64_t xt = (int64_t)sp.H * P;
+    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N;
+    const int64_t bt = (int64_t)sp.G * N;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    const int kend = (i0 + TS < Q) ? i0 + TS : Q;
+    tile_gemm(
+        acc, 0, kend,
+        [&](int r, int k) {
+            const int i = i0 + r;
+            return (i < Q && k <= i) ? Gm[(int64_t)i * Q + k] * expf(cum[i] - cum[k]) * dtf[k] : 0.f;
+        },
+        [&](int k, int col) { return (k < Q && p0 + col < P) ? IO<T>::ld(sp.x, xbase + (int64_t)k * xt + p0 + col) : 0.f; },
+        As, Bs);
+    tile_gemm(
+        acc, 0, N,
+        [&](int r, int k) {
+            const int i = i0 + r;
+            return (i < Q && k < N) ? expf(cum[i]) * IO<T>::ld(sp.Cm, bbase + (int64_t)i * bt + k) : 0.f;
+        },
+        [&](int k, int col) { return (k < N && p0 + col < P) ? Hprev[(int64_t)(p0 + col) * N + k] : 0.f; }, As, Bs);
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const float Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + ty + 8 * r, p = p0 + tx;
+        if (i < Q && p < P) {
+            const int64_t o = (int64_t)i * xt + p;
+            IO<T>::st(sp.y, ybase + o, acc[r] + Dh * IO<T>::ld(sp.x, xbase + o));
+        }
+    }
+}
+
+// Per (chunk, head, 32-token row tile): yhat, u, dx and the per-token scalars for ddt / dA / dD.
+template <typename T>
+__global__ void k_bwd_main(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int j0 = blockIdx.y * TS;
+    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
+    const int Q = sp.Q, N = sp.N, P = sp.P, g = h / sp.hpg;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float* cum = sp.cum + cbase;
+    const float* dtf = sp.dtf + cbase;
+    const float T_ = cum[Q - 1];
+    const float* Gm = sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * Q * Q;
+    const float* Hprev = sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * P * N;
+    const float* dHnext = sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * P * N;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P;
+    const int64_t xbase = (int64_t)b * sp.xs_b + xrow, dybase = (int64_t)b * sp.dys_b + xrow,
+                  dxbase = (int64_t)b * sp.dxs_b + xrow;
+    const int64_t xt = (int64_t)sp.H * P;
+    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N;
+    const int64_t bt = (int64_t)sp.G * N;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const float Dh = sp.D[h];
+    const float res = (sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f;
+    float s_gy[4] = {0.f, 0.f, 0.f, 0.f}, s_xu[4] = {0.f, 0.f, 0.f, 0.f}, s_dyx[4] = {0.f, 0.f, 0.f, 0.f};
+    const int kend = (j0 + TS < Q) ? j0 + TS : Q;
+    for (int p0 = 0; p0 < P; p0 += TS) {
+        float ay[4] = {0.f, 0.f, 0.f, 0.f}, au[4] = {0.f, 0.f, 0.f, 0.f};
+        // yhat rows j0..: masked scores times X, then the entering-state term
+        tile_gemm(
+            ay, 0, kend,
+            [&](int r, int k) {
+                const int i = j0 + r;
+                return (i < Q && k <= i) ? Gm[(int64_t)i * Q + k] * expf(cum[i] - cum[k]) * dtf[k] : 0.f;
+            },
+            [&](int k, int col) { return (k < Q && p0 + col < P) ? IO<T>::ld(sp.x, xbase + (int64_t)k * xt + p0 + col) : 0.f; },
+            As, Bs);
+        tile_gemm(
+            ay, 0, N,
+            [&](int r, int k) {
+                const int i = j0 + r;
+                return (i < Q && k < N) ? expf(cum[i]) * IO<T>::ld(sp.Cm, bbase + (int64_t)i * bt + k) : 0.f;
+            },
+            [&](int k, int col) { return (k < N && p0 + col < P) ? Hprev[(int64_t)(p0 + col) * N + k] : 0.f; }, As, Bs);
+        // u rows j0..: transposed masked scores (without dt) times dY, then the leaving-adjoint term
+        tile_gemm(
+            au, j0, Q,
+            [&](int r, int k) {
+                const int j = j0 + r;
+                return (j < Q && k < Q && k >= j) ? Gm[(int64_t)k * Q + j] * expf(cum[k] - cum[j]) : 0.f;
+            },
+            [&](int k, int col) { return (k < Q && p0 + col < P) ? IO<T>::ld(sp.dy, dybase + (int64_t)k * xt + p0 + col) : 0.f; },
+            As, Bs);
+        tile_gemm(
+            au, 0, N,
+            [&](int r, int k) {
+                const int j = j0 + r;
+                return (j < Q && k < N) ? expf(T_ - cum[j]) * IO<T>::ld(sp.Bm, bbase + (int64_t)j * bt + k) : 0.f;
+            },
+            [&](int k, int col) { return (k < N && p0 + col < P) ? dHnext[(int64_t)(p0 + col) * N + k] : 0.f; }, As, Bs);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int j = j0 + ty + 8 * r, p = p0 + tx;
+            if (j < Q && p < P) {
+                const int64_t o = (int64_t)j * xt + p;
+                const float dyv = IO<T>::ld(sp.dy, dybase + o), xv = IO<T>::ld(sp.x, xbase + o);
+                IO<T>::st(sp.dx, dxbase + o, dtf[j] * au[r] + (Dh + res) * dyv);
+                s_gy[r] += dyv * ay[r];
+                s_xu[r] += xv * au[r];
+                s_dyx[r] += dyv * xv;
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        float a = s_gy[r], u = s_xu[r], d = s_dyx[r];
+        for (int off = 16; off > 0; off >>= 1) {
+            a += __shfl_xor(a, off, 64);
+            u += __shfl_xor(u, off, 64);
+            d += __shfl_xor(d, off, 64);
+        }
+        const int j = j0 + ty + 8 * r;
+        if (tx == 0 && j < Q) {
+            sp.gterm[cbase + j] = a - dtf[j] * u;
+            sp.fterm[cbase + j] = u;
+            sp.dDrow[cbase + j] = d;
+        }
+    }
+}
+
+// da = reverse cumsum of gterm + tail; ddt = A da + f; per-chunk partial sums for dA and dD.
+template <typename T>
+__global__ void k_ddt_finalize(SegParams sp) {
+    __shared__ float s[1024];
+    __shared__ float s2[1024];
+    const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const int Q = sp.Q;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    // reverse order so that an inclusive forward scan yields the suffix sums
+    const int ri = Q - 1 - i;
+    s[i] = (i < Q) ? sp.gterm[cbase + ri] : 0.f;
+    __syncthreads();
+    for (int off = 1; off < (int)blockDim.x; off <<= 1) {
+        const float v = (i >= off) ? s[i - off] : 0.f;
+        __syncthreads();
+        s[i] += v;
+        __syncthreads();
+    }
+    float tail = 0.f;
+    const float* tp = sp.tail_part + ((((int64_t)b * sp.H + h) * sp.nc + c)) * sp.nslice;
+    for (int k = 0; k < sp.nslice; ++k) tail += tp[k];
+    float pa = 0.f, pd = 0.f;
+    if (i < Q) {
+        const float da = s[i] + tail;  // belongs to token ri
+        const float d = sp.dtf[cbase + ri];
+        IO<T>::st(sp.ddt, (int64_t)b * sp.dts_b + ((int64_t)c * Q + ri) * sp.H + h, sp.A[h] * da + sp.fterm[cbase + ri]);
+        pa = d * da;
+        pd = sp.dDrow[cbase + ri];
+    }
+    __syncthreads();
+    s[i] = pa;
+    s2[i] = pd;
+    __syncthreads();
+    for (int off = blockDim.x >> 1; off > 0; off >>= 1) {
+        if (i < off) {
+            s[i] += s[i + off];
+            s2[i] += s2[i + off];
+        }
+        __syncthreads();
+    }
+    if (i == 0) {
+        sp.dA_part[((int64_t)b * sp.nc + c) * sp.H + h] = s[0];
+        sp.dD_part[((int64_t)b * sp.nc + c) * sp.H + h] = s2[0];
+    }
+}
+
+__global__ void k_param_reduce(SegParams sp) {
+    const int h = blockIdx.x * blockDim.x + threadIdx.x;
+    if (h >= sp.H) return;
+    float a = 0.f, d = 0.f;
+    for (int bc = 0; bc < sp.Bt * sp.nc; ++bc) {
+        a += sp.dA_part[(int64_t)bc * sp.H + h];
+        d += sp.dD_part[(int64_t)bc * sp.H + h];
+    }
+    if (sp.accumulate) {
+        sp.dA[h] += a;
+        sp.dD[h] += d;
+    } else {
+        sp.dA[h] = a;
+        sp.dD[h] = d;
+    }
+}
+
+// dG[b,c,g,i,j] = sum_{h in g} exp(cum_i - cum_j) dt_j (dY_i . x_j), j <= i
+template <typename T>
+__global__ void k_dG(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int j0 = blockIdx.y * TS, i0 = blockIdx.z * TS;
+    if (j0 > i0) return;
+    const int z = blockIdx.x, g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int Q = sp.Q, P = sp.P;
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int64_t xt = (int64_t)sp.H * P;
+    float tot[4] = {0.f, 0.f, 0.f, 0.f};
+    for (int hh = 0; hh < sp.hpg; ++hh) {
+        const int h = g * sp.hpg + hh;
+        const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+        const float* cum = sp.cum + cbase;
+        const float* dtf = sp.dtf + cbase;
+        const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P;
+        const int64_t xbase = (int64_t)b * sp.xs_b + xrow, dybase = (int64_t)b * sp.dys_b + xrow;
+        float acc[4] = {0.f, 0.f, 0.f, 0.f};
+        tile_gemm(
+            acc, 0, P,
+            [&](int r, int k) { return (i0 + r < Q && k < P) ? IO<T>::ld(sp.dy, dybase + (int64_t)(i0 + r) * xt + k) : 0.f; },
+            [&](int k, int col) { return (j0 + col < Q && k < P) ? IO<T>::ld(sp.x, xbase + (int64_t)(j0 + col) * xt + k) : 0.f; },
+            As, Bs);
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int i = i0 + ty + 8 * r, j = j0 + tx;
+            if (i < Q && j <= i) tot[r] += acc[r] * expf(cum[i] - cum[j]) * dtf[j];
+        }
+    }
+    float* out = sp.dG + (((int64_t)b * sp.nc + c) * sp.G + g) * Q * Q;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = i0 + ty + 8 * r, j = j0 + tx;
+        if (i < Q && j < Q) out[(int64_t)i * Q + j] = tot[r];
+    }
+}
+
+// role 0: dC rows; role 1: dB rows (see the formulas at the top of the file)
+template <typename T>
+__global__ void k_dBC(SegParams sp) {
+    __shared__ float As[TS][TS + 1], Bs[TS][TS + 1];
+    const int n0 = blockIdx.y * TS, r0 = blockIdx.z * TS;
+    int z = blockIdx.x;
+    const int role = z & 1;
+    z >>= 1;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int Q = sp.Q, N = sp.N, P = sp.P;
+    const float* dG = sp.dG + (((int64_t)b * sp.nc + c) * sp.G + g) * Q * Q;
+    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N;
+    const int64_t bt = (int64_t)sp.G * N;
+    const int64_t xt = (int64_t)sp.H * P;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};
+    if (role == 0) {
+        const int kend = (r0 + TS < Q) ? r0 + TS : Q;
+        tile_gemm(
+            acc, 0, kend, [&](int r, int k) { return (r0 + r < Q && k <= r0 + r) ? dG[(int64_t)(r0 + r) * Q + k] : 0.f; },
+            [&](int k, int col) { return (k < Q && n0 + col < N) ? IO<T>::ld(sp.Bm, bbase + (int64_t)k * bt + n0 + col) : 0.f; },
+            As, Bs);
+    } else {
+        tile_gemm(
+            acc, r0, Q,
+            [&](int r, int k) { return (r0 + r < Q && k < Q && k >= r0 + r) ? dG[(int64_t)k * Q + r0 + r] : 0.f; },
+            [&](int k, int col) { return (k < Q && n0 + col < N) ? IO<T>::ld(sp.Cm, bbase + (int64_t)k * bt + n0 + col) : 0.f; },
+            As, Bs);
+    }
+    for (int hh = 0; hh < sp.hpg; ++hh) {
+        const int h = g * sp.hpg + hh;
+        const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+        const float* cum = sp.cum + cbase;
+        const float* dtf = sp.dtf + cbase;
+        const float T_ = cum[Q - 1];
+        const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P;
+        const int64_t xbase = (int64_t)b * sp.xs_b + xrow, dybase = (int64_t)b * sp.dys_b + xrow;
+        if (role == 0) {
+            const float* Hprev = sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * P * N;
+            tile_gemm(
+                acc, 0, P,
+                [&](int r, int k) {
+                    const int i = r0 + r;
+                    return (i < Q && k < P) ? expf(cum[i]) * IO<T>::ld(sp.dy, dybase + (int64_t)i * xt + k) : 0.f;
+                },
+                [&](int k, int col) { return (k < P && n0 + col < N) ? Hprev[(int64_t)k * N + n0 + col] : 0.f; }, As, Bs);
+        } else {
+            const float* dHnext = sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * P * N;
+            tile_gemm(
+                acc, 0, P,
+                [&](int r, int k) {
+                    const int j = r0 + r;
+                    return (j < Q && k < P) ? expf(T_ - cum[j]) * dtf[j] * IO<T>::ld(sp.x, xbase + (int64_t)j * xt + k) : 0.f;
+                },
+                [&](int k, int col) { return (k < P && n0 + col < N) ? dHnext[(int64_t)k * N + n0 + col] : 0.f; }, As, Bs);
+        }
+    }
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    void* out = role == 0 ? sp.dC : sp.dB;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int i = r0 + ty + 8 * r, n = n0 + tx;
+        if (i < Q && n < N) IO<T>::st(out, bbase + (int64_t)i * bt + n, acc[r]);
+    }
+}
+
+inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+inline int scan_block(int Q) {
+    int t = 64;
+    while (t < Q) t <<= 1;
+    return t;
+}
+
+#define SSDK_LAUNCH_CHECK()                  \
+    do {                                     \
+        hipError_t e_ = hipGetLastError();   \
+        if (e_ != hipSuccess) return e_;     \
+    } while (0)
+
+template <typename T>
+hipError_t fwd_segment(const SegParams& sp, bool need_y, hipStream_t st) {
+    const int Q = sp.Q, P = sp.P, N = sp.N;
+    hipLaunchKernelGGL(k_cumsum<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL((k_chunk_outer<T, 0>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_state_scan_fwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_cb<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    if (need_y) {
+        hipLaunchKernelGGL(k_chunk_out<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(P, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
+        SSDK_LAUNCH_CHECK();
+    }
+    return hipSuccess;
+}
+
+template <typename T>
+hipError_t bwd_segment(const SegParams& sp, hipStream_t st) {
+    const int Q = sp.Q, P = sp.P, N = sp.N;
+    hipLaunchKernelGGL((k_chunk_outer<T, 1>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_state_scan_bwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_bwd_main<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(Q, TS), 1), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_ddt_finalize<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_dG<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    hipLaunchKernelGGL(k_dBC<T>, dim3(sp.Bt * sp.nc * sp.G * 2, cdiv(N, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
+    SSDK_LAUNCH_CHECK();
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, p, n);
+    return hipGetLastError();
+}
+
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const size_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, dst, src, n);
+    return hipGetLastError();
+}
+
+hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st) {
+    return is_bf16 ? fwd_segment<bf16_t>(sp, need_y, st) : fwd_segment<float>(sp, need_y, st);
+}
+
+hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st) {
+    return is_bf16 ? bwd_segment<bf16_t>(sp, st) : bwd_segment<float>(sp, st);
+}
+
+}  // namespace ssdk

@@ -1,0 +1,123 @@
+// Internal declarations shared by the translation units of libssd_magc (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "ssd_magc.h"
+
+namespace ssdk {
+
+// bf16 storage as raw bits; conversion is round-to-nearest-even.
+struct bf16_t {
+    uint16_t v;
+};
+
+__host__ __device__ inline float bf16_to_float(bf16_t b) {
+    union {
+        uint32_t u;
+        float f;
+    } c;
+    c.u = (uint32_t)b.v << 16;
+    return c.f;
+}
+
+__host__ __device__ inline bf16_t float_to_bf16(float f) {
+    union {
+        uint32_t u;
+        float f;
+    } c;
+    c.f = f;
+    bf16_t o;
+    if ((c.u & 0x7fffffffu) > 0x7f800000u) {  // NaN stays NaN
+        o.v = (uint16_t)((c.u >> 16) | 0x40u);
+    } else {
+        o.v = (uint16_t)((c.u + 0x7fffu + ((c.u >> 16) & 1u)) >> 16);
+    }
+    return o;
+}
+
+// One segment of one layer, as the kernels see it.  Tensor pointers are already offset to the
+// first token of the segment; batch strides are those of the full tensors (elements).
+struct SegParams {
+    int Bt, H, P, G, N, Q, nc, hpg;
+    int64_t xs_b, ys_b, dys_b, dxs_b;  // batch strides of x, y, dy, dx
+    int64_t dts_b, bcs_b;              // of dt/ddt and of B/C/dB/dC
+    uint32_t flags;
+    // inputs / outputs
+    const void* x;
+    const void* dt;
+    const void* Bm;
+    const void* Cm;
+    const void* dy;
+    const float* A;
+    const float* D;
+    void* y;
+    void* dx;
+    void* ddt;
+    void* dB;
+    void* dC;
+    // per-segment workspace (fp32)
+    float* cum;        // [Bt][H][nc][Q]  chunk-local inclusive cumsum of dt*A
+    float* dtf;        // [Bt][H][nc][Q]  dt as fp32, head-major
+    float* states;     // [Bt][nc+1][H][P][N]  slot c: state entering chunk c; slot nc: state leaving the segment
+    float* dstates;    // [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
+    float* Gm;         // [Bt][nc][G][Q][Q]    C_i . B_j   (generic path: fp32)
+    float* dG;         // [Bt][nc][G][Q][Q]    head-summed masked dY X^T
+    float* gterm;      // [Bt][H][nc][Q]
+    float* fterm;      // [Bt][H][nc][Q]
+    float* dDrow;      // [Bt][H][nc][Q]
+    float* tail_part;  // [Bt][H][nc][nslice]
+    float* dA_part;    // [Bt][nc][H]
+    float* dD_part;    // [Bt][nc][H]
+    float* dcarry;     // [Bt][H][P][N] adjoint of the state entering the segment to the right of the current one
+    int nslice;
+    // state plumbing for the scans (all fp32, element strides between batches)
+    const float* state_in;   // state entering the segment, or NULL for zeros
+    int64_t state_in_bs;
+    float* bnd_write;        // where to store that entering state (checkpoint slot), or NULL
+    int64_t bnd_write_bs;
+    float* state_out;        // where to store the state leaving the segment, or NULL
+    int64_t state_out_bs;
+    float* state_out2;       // second copy (final_state when the last segment also has no slot), or NULL
+    int64_t state_out2_bs;
+    float* dinit_out;        // bwd: where the adjoint of the entering state goes at segment 0, or NULL
+    float* dA;
+    float* dD;
+    int accumulate;          // bwd: 1 = add this segment's dA/dD to what is there
+};
+
+// Validated dimensions of one call.
+struct Dims {
+    int64_t Bt, L, s;
+    int H, P, G, N, Q, nc, hpg;
+    int64_t nseg;
+    size_t esz;
+    bool bf16;
+    int64_t xs_b, dts_b, bcs_b;
+};
+
+// Byte offsets of the per-segment scratch arrays inside the caller's workspace.
+struct WsLayout {
+    size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
+    int nslice;
+};
+
+int check_shape(const ssd_shape_t* sh, Dims* d);
+WsLayout ws_layout(const Dims& d, bool bwd);
+void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd);
+void base_params(SegParams& sp, const Dims& d, uint32_t flags);
+bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
+
+// Launchers.  Each returns hipSuccess or the launch error.  is_bf16 selects the storage type.
+hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
+hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
+hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st);
+hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st);
+
+// MFMA path (bf16, P = 64, N = 128, Q in {64, 128, 256}).
+bool mfma_path_supported(const ssd_shape_t& s);
+hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st);
+hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
+
+}  // namespace ssdk

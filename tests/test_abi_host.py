@@ -1,0 +1,130 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the header declares,
+validates arguments before touching the device, and its host-only planner equals the oracle."""
+import ctypes
+import os
+import re
+
+import pytest
+
+import paper_2411_19460_amd as pk
+from paper_2411_19460_amd import binding
+from oracle import magc_ref
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "ssd_magc.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(ssd_\w+|magc_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.lib()
+    names = header_functions()
+    assert set(names) == set(binding.EXPORTS), names
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def shape(**kw):
+    base = dict(dtype=1, nheads=8, headdim=64, ngroups=1, dstate=128, chunk=256, batch=1, seqlen=2048, segment=1024,
+                x_batch_stride=0, dt_batch_stride=0, bc_batch_stride=0)
+    base.update(kw)
+    return pk.ssd_shape_t(**base)
+
+
+def test_workspace_query_and_shape_validation():
+    assert pk.ssd_workspace_bytes(shape(), False) > 0
+    assert pk.ssd_workspace_bytes(shape(), True) > pk.ssd_workspace_bytes(shape(), False)
+    # workspace follows the segment, not the sequence length
+    assert pk.ssd_workspace_bytes(shape(seqlen=1 << 20, segment=1024), True) == pk.ssd_workspace_bytes(shape(), True)
+    for bad in (dict(dtype=7), dict(nheads=0), dict(seqlen=2000), dict(segment=1000), dict(ngroups=3),
+                dict(chunk=2048), dict(headdim=512), dict(batch=0)):
+        assert pk.ssd_workspace_bytes(shape(**bad), True) == 0, bad
+
+
+def call_fwd(sh, ptrs, ws=0x1000, ws_bytes=1 << 40, flags=0):
+    L = binding.lib()
+    return L.ssd_fwd(ctypes.byref(sh), *ptrs, ws, ws_bytes, flags, None)
+
+
+def test_fwd_bwd_reject_bad_arguments_before_any_launch():
+    # Fake non-NULL pointers: validation must fail before anything dereferences them.
+    p = 0x1000
+    ok = [p] * 6 + [None, p, p, p]  # x dt A B C D init y final bnd
+    assert call_fwd(shape(dtype=9), ok) == -4
+    assert call_fwd(shape(seqlen=2000), ok) == -3
+    assert call_fwd(shape(segment=1000), ok) == -3
+    assert call_fwd(shape(ngroups=3), ok) == -3
+    assert call_fwd(shape(nheads=-1), ok) == -2
+    assert call_fwd(shape(), [None] + ok[1:]) == -1
+    assert call_fwd(shape(), ok[:9] + [None]) == -1                       # checkpoints required when segment < L
+    assert call_fwd(shape(), ok, ws=None) == -5
+    assert call_fwd(shape(), ok, ws=0x1001) == -5                          # misaligned
+    assert call_fwd(shape(), ok, ws_bytes=16) == -5
+    assert call_fwd(shape(), ok, flags=1 << 20) == -8
+    L = binding.lib()
+    okb = [p] * 6 + [None, 0x3000, None, p] + [p] * 6 + [None]    # x dt A B C D init dy dfinal bnd dx ddt dA dB dC dD dinit
+    sh = shape()
+    assert L.ssd_bwd(ctypes.byref(sh), *okb, 0x1000, 16, 0, None) == -5
+    bad = list(okb)
+    bad[10] = None                                                          # dx
+    assert L.ssd_bwd(ctypes.byref(sh), *bad, 0x1000, 1 << 40, 0, None) == -1
+    alias = list(okb)
+    alias[7] = alias[10] = 0x2000                                           # dx aliases dy
+    assert L.ssd_bwd(ctypes.byref(sh), *alias, 0x1000, 1 << 40, 0, None) == -8
+    assert L.ssd_fwd(None, *ok, 0x1000, 1 << 40, 0, None) == -1
+    for code in range(-8, 1):
+        assert pk.strerror(code) and pk.strerror(code) != "unknown status"
+    assert pk.strerror(-99) == "unknown status"
+
+
+def test_stack_validation():
+    sh = shape()
+    assert pk.magc_stack_workspace_bytes(sh, 4, 2, True) > pk.magc_stack_workspace_bytes(sh, 4, 2, False) > 0
+    assert pk.magc_stack_workspace_bytes(sh, 0, 2, True) == 0
+    assert pk.magc_stack_workspace_bytes(shape(x_batch_stride=1 << 30), 4, 2, True) == 0
+    # a larger layer interval keeps more restored activations alive inside a cell
+    assert pk.magc_stack_workspace_bytes(sh, 8, 8, True) > pk.magc_stack_workspace_bytes(sh, 8, 2, True)
+
+
+CASES = [
+    (512, 512, 1, 1, 1, 0, 1, 0, False),
+    (4, 1024, 1, 1, 1, 0, 1, 0, False),
+    (1024, 4, 1, 1, 1, 0, 1, 0, False),
+    (64, 1 << 14, 2560, 671488, 15696, 660736, 256, 0, False),
+    (64, 1 << 16, 2560, 671488, 15696, 660736, 256, 0, False),
+    (48, 1 << 15, 1024, 269056, 6432, 264448, 256, 0, True),
+    (16, 1 << 18, 10240, 2621440, 10240, 20480, 256, 0, False),
+    (8, 4096, 10, 1000, 10, 5, 256, 5.0e6, False),
+    (8, 4096, 10, 1000, 10, 5, 256, 1.0e12, False),
+    (5, 100, 3, 7, 2, 1, 256, 0, False),
+    (7, 300, 3, 7, 2, 1, 256, 0, True),
+]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_planner_equals_oracle(case):
+    L, S, cl, cs, cg, ct, mult, budget, ic = case
+    want = magc_ref.plan(L, S, cl, cs, cg, ct, s_multiple=mult, budget=budget, integer_counts=ic)
+    rc, got = pk.magc_plan(L, S, cl, cs, cg, ct, s_multiple=mult, budget=budget, integer_counts=ic)
+    assert (got["l"], got["s"]) == (want["l"], want["s"])
+    assert got["fits"] == want["fits"] and (rc == 0) == want["fits"]
+    for name, w in zip(("m_lckpt", "m_sckpt", "m_grid", "m_state"), want["terms"]):
+        assert abs(got[name] - float(w)) <= 1e-12 * max(1.0, float(w))
+    assert abs(got["m_total"] - float(want["total"])) <= 1e-12 * float(want["total"])
+
+
+def test_planner_budget_too_small_and_regimes():
+    rc, got = pk.magc_plan(8, 4096, 10, 1000, 10, 5, budget=1.0)
+    assert rc == -7 and not got["fits"]
+    free = magc_ref.plan(8, 4096, 10, 1000, 10, 5)
+    assert (got["l"], got["s"]) == (free["l"], free["s"])
+    assert pk.magc_plan(4, 1024, 1, 1, 1, 0)[1]["regime"] == 1     # L^2 <= S
+    assert pk.magc_plan(1024, 4, 1, 1, 1, 0)[1]["regime"] == 2     # S^2 <= L
+    assert pk.magc_plan(512, 512, 1, 1, 1, 0)[1]["regime"] == 0
+    with pytest.raises(pk.SSDError):
+        pk.magc_plan(0, 10, 1, 1, 1, 0)
+    with pytest.raises(pk.SSDError):
+        pk.magc_plan(4, 10, -1, 1, 1, 0)
