@@ -1,0 +1,176 @@
+#!/usr/bin/env python3
+"""Benchmark of the SSD forward+backward hot path under MA-GC on one MI355X.
+
+One "step" = ssd_fwd + ssd_bwd (segment-by-segment restore) of one SSD layer over one batch of
+seeded synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+VALU_FP32_PEAK_TFLOPS = 157.3
+
+
+def kernel_models(cfg, tokens_per_launch):
+    """Algorithmic work of one launch of each kernel: (bound, amount) with amount in flop (MAC = 2)
+    for contractions and in bytes for bandwidth-bound kernels.  Dense Q x Q counts, per token:
+      chunk_state 2NP*H | cb 2QN*G | chunk_out (2QP+2NP)*H | dstate_local 2NP*H
+      bwd_main (4QP+4NP)*H | dG 2QP*H | dBC 4NP*H + 4QN*G
+      state scans: read + write one fp32 state per (chunk, head): 2*4*P*N*H/Q bytes
+    A launch covers one segment: tokens_per_launch = batch * segment."""
+    H, P, N, G, Q = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk
+    t = tokens_per_launch
+    esz = 2 if cfg.dtype == "bf16" else 4
+    scan_bytes = 2 * 4 * P * N * H / Q
+    m = {
+        "chunk_state": ("flop", 2 * N * P * H), "cb": ("flop", 2 * Q * N * G),
+        "chunk_out": ("flop", (2 * Q * P + 2 * N * P) * H), "dstate_local": ("flop", 2 * N * P * H),
+        "bwd_main": ("flop", (4 * Q * P + 4 * N * P) * H), "dG": ("flop", 2 * Q * P * H),
+        "dBC": ("flop", 4 * N * P * H + 4 * Q * N * G),
+        "state_scan_fwd": ("byte", scan_bytes), "state_scan_bwd": ("byte", scan_bytes * 1.5),
+        "cumsum": ("byte", H * esz + 2 * 4 * H), "ddt_finalize": ("byte", 4 * 4 * H + H * esz),
+    }
+    out = {}
+    for k, (kind, per_tok) in m.items():
+        out[k] = (kind, per_tok * t)
+        out["mfma_" + k] = (kind, per_tok * t)
+    return out
+
+
+def cpu_baseline(cfg, seconds_target=15.0):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload."""
+    import numpy as np
+    from oracle import ssd_ref
+    from paper_2411_19460_amd import synth
+    threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
+    hs = min(cfg.nheads, max(1, threads))
+    Ls = min(cfg.seqlen, 65536)
+    sub = cfg.scaled(seqlen=Ls, nheads=hs, segment=min(cfg.segment, Ls), name=cfg.name + "_sample")
+    d = synth.make_layer_inputs(sub)
+    best = None
+    for _ in range(2):
+        t0 = time.perf_counter()
+        ssd_ref.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], None, sub.segment)
+        ssd_ref.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"])
+        dtm = time.perf_counter() - t0
+        best = dtm if best is None else min(best, dtm)
+    tok_s = sub.batch * Ls / best * (hs / cfg.nheads)
+    return {"value": tok_s, "unit": "tokens/s", "cores": min(threads, hs), "kind": "oracle",
+            "sample": f"first {Ls} tokens, heads 0..{hs - 1} of {cfg.nheads}, fwd+bwd fp64, best of 2, "
+                      f"scaled by {hs}/{cfg.nheads} to all heads"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=6)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
+    ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2411_19460_amd as pk
+    from paper_2411_19460_amd import synth
+
+    cfg = synth.CONFIGS[args.config]
+    if cfg.nlayers != 1:
+        print("bench.py: stack configs are measured by tests, not by this bench", file=sys.stderr)
+        sys.exit(2)
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    d = synth.make_layer_inputs_device(cfg, dev)
+    flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0
+    shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
+    Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    nseg = L // cfg.segment
+    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True), dtype=torch.uint8, device=dev)
+    out_f = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev),
+             "boundary_states": torch.empty((Bt, nseg, H, P, N), device=dev)}
+    out_b = {"dx": torch.empty_like(d["x"]), "ddt": torch.empty_like(d["dt"]), "dB": torch.empty_like(d["B"]),
+             "dC": torch.empty_like(d["C"]), "dinit_state": torch.empty((Bt, H, P, N), device=dev)}
+    dA = torch.empty(H, device=dev)
+    dD = torch.empty(H, device=dev)
+
+    def step():
+        pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, cfg.segment, None, flags, ws_f, out=out_f)
+        pk.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], cfg.chunk, cfg.segment, None, None,
+                   out_f["boundary_states"], flags, ws_b, dA, dD, out=out_b)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    pk.ssd_prof_enable(True)          # HIP events around every kernel, on the launch stream
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    prof = pk.ssd_prof_read()
+    pk.ssd_prof_enable(False)
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    tok_s = Bt * L / (ms_per_step * 1e-3)
+
+    models = kernel_models(cfg, Bt * cfg.segment)
+    kernels = {}
+    for name, (ms, n) in prof.items():
+        ent = {"ms_per_step": ms / args.steps, "launches_per_step": n // args.steps, "avg_us": ms * 1e3 / n}
+        if name in models:
+            kind, amount = models[name]
+            rate = amount / (ms / n * 1e-3)
+            ent["achieved"] = rate / 1e12 if kind == "flop" else rate / 1e9
+            ent["unit"] = "TFLOP/s" if kind == "flop" else "GB/s"
+        kernels[name] = ent
+    dom = max((k for k in kernels if k in models), key=lambda k: kernels[k]["ms_per_step"])
+    kind, amount = models[dom]
+    if kind == "byte":
+        bound, peak, unit = "hbm", HBM_PEAK_GBS, "GB/s"
+    elif dom.startswith("mfma_"):
+        bound, peak, unit = "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
+    else:
+        bound, peak, unit = "alu", VALU_FP32_PEAK_TFLOPS, "TFLOP/s"
+    roofline = {"kernel": dom, "bound": bound, "achieved": kernels[dom]["achieved"], "peak": peak, "unit": unit,
+                "frac": kernels[dom]["achieved"] / peak, "traffic": None,
+                "avg_launch_us": kernels[dom]["avg_us"], "share_of_step": kernels[dom]["ms_per_step"] / ms_per_step}
+
+    full = pk.make_shape(d["x"], d["B"], cfg.chunk, None)
+    state_bytes = Bt * H * P * N * 4
+    peak_hbm = {
+        "magc_bytes": pk.ssd_workspace_bytes(shape, True) + nseg * state_bytes,
+        "full_activation_bytes": pk.ssd_workspace_bytes(full, True),
+        "note": "scratch + checkpoints beyond the inputs/outputs: MA-GC (segment checkpoints + one segment's "
+                "chunk states) vs keeping every chunk state of the sequence alive (segment = L)",
+    }
+
+    res = {
+        "metric": "SSD fwd+bwd tokens/sec/layer", "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name, "batch": Bt, "seqlen": L, "nheads": H, "headdim": P, "dstate": N,
+                   "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment,
+                   "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma"},
+        "roofline": roofline, "kernels": kernels, "peak_hbm": peak_hbm,
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(cfg)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

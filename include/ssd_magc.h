@@ -109,9 +109,7 @@ int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  *   dx [Bt,L,H,P], ddt [Bt,L,H], dB, dC [Bt,L,G,N] dtype, overwritten
  *   dA, dD [H] fp32, overwritten (added to under SSD_FLAG_ACCUM_PARAM)
  *   dinit_state     [Bt,H,P,N] fp32, overwritten; may be NULL
- * dx may alias dy only if SSD_FLAG_RESIDUAL is not needed by the caller afterwards: each (chunk,
- * head) tile of dy is fully read before the same tile of dx is written, but dB/dC kernels read dy
- * again, so aliasing is NOT supported; pass distinct buffers.
+ * dx must not alias dy (SSD_ERR_ARG): several kernels read dy after dx has been written.
  */
 int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
             const void* C, const float* D, const float* init_state, const void* dy,
@@ -188,6 +186,19 @@ typedef struct magc_plan_t {
 } magc_plan_t;
 
 int magc_plan(const magc_model_t* model /*host*/, magc_plan_t* out /*host*/);
+
+/*
+ * Per-kernel timing for benchmarks (diagnostics; not part of the method).  While enabled, every
+ * kernel launch of this library is bracketed by two HIP events recorded on the launch stream.
+ * Not thread-safe; leave it off in production.
+ *   ssd_prof_enable(on)      : drops earlier records, then switches recording on (1) or off (0)
+ *   ssd_prof_read(id, ...)   : waits for the recorded events of kernel `id`, returns the sum of
+ *                              their durations in milliseconds and the number of launches (host pointers)
+ *   ssd_prof_kernel_name(id) : static name of kernel `id`, NULL once id is past the last kernel
+ */
+int ssd_prof_enable(int32_t on);
+int ssd_prof_read(int32_t kernel_id, double* total_ms /*host*/, int64_t* launches /*host*/);
+const char* ssd_prof_kernel_name(int32_t kernel_id);
 
 /* Static, human-readable text for a status code (host pointer, never NULL). */
 const char* ssd_strerror(int status);

@@ -17,7 +17,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
-           "magc_stack_bwd", "magc_plan", "ssd_strerror")
+           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name")
 
 
 class ssd_shape_t(ctypes.Structure):
@@ -73,6 +73,12 @@ def lib():
         L.magc_stack_bwd.argtypes = [shp, i32, i32] + [vp] * 15 + [vp, sz, vp]
         L.magc_plan.restype = ctypes.c_int
         L.magc_plan.argtypes = [ctypes.POINTER(magc_model_t), ctypes.POINTER(magc_plan_t)]
+        L.ssd_prof_enable.restype = ctypes.c_int
+        L.ssd_prof_enable.argtypes = [i32]
+        L.ssd_prof_read.restype = ctypes.c_int
+        L.ssd_prof_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+        L.ssd_prof_kernel_name.restype = ctypes.c_char_p
+        L.ssd_prof_kernel_name.argtypes = [i32]
         L.ssd_strerror.restype = ctypes.c_char_p
         L.ssd_strerror.argtypes = [ctypes.c_int]
         _lib = L
@@ -127,18 +133,23 @@ def _workspace(nbytes: int, device):
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
 
 
-def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, workspace=None, want_final=True):
-    """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L."""
+def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, workspace=None, want_final=True,
+            out=None):
+    """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L.
+    `out` may carry preallocated tensors under the keys y, final_state, boundary_states."""
     import torch
     _check_inputs(x, dt, A, B, C, D, init_state)
     shape = make_shape(x, B, chunk, segment)
     Bt, L, H, P = x.shape
     N = B.shape[3]
-    y = torch.empty_like(x)
-    final = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device) if want_final else None
+    out = out or {}
+    y = out["y"] if "y" in out else torch.empty_like(x)
+    final = out.get("final_state")
+    if final is None and want_final:
+        final = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
     nseg = L // shape.segment if L > 0 and shape.segment > 0 and L % shape.segment == 0 else 1
-    bnd = None
-    if segment is not None:
+    bnd = out.get("boundary_states")
+    if bnd is None and segment is not None:
         bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)
     need = ssd_workspace_bytes(shape, False)
     if workspace is None:
@@ -151,22 +162,26 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,
-            flags=0, workspace=None, dA=None, dD=None, want_dinit=True):
-    """Returns dict(dx, ddt, dA, dB, dC, dD, dinit_state)."""
+            flags=0, workspace=None, dA=None, dD=None, want_dinit=True, out=None):
+    """Returns dict(dx, ddt, dA, dB, dC, dD, dinit_state).  `out` may carry preallocated dx, ddt, dB, dC,
+    dinit_state."""
     import torch
     _check_inputs(x, dt, A, B, C, D, dy, init_state, dfinal_state, boundary_states)
     shape = make_shape(x, B, chunk, segment)
     Bt, L, H, P = x.shape
     N = B.shape[3]
-    dx = torch.empty_like(x)
-    ddt = torch.empty_like(dt)
-    dB = torch.empty_like(B)
-    dC = torch.empty_like(C)
+    out = out or {}
+    dx = out["dx"] if "dx" in out else torch.empty_like(x)
+    ddt = out["ddt"] if "ddt" in out else torch.empty_like(dt)
+    dB = out["dB"] if "dB" in out else torch.empty_like(B)
+    dC = out["dC"] if "dC" in out else torch.empty_like(C)
     if dA is None:
         dA = torch.empty((H,), dtype=torch.float32, device=x.device)
     if dD is None:
         dD = torch.empty((H,), dtype=torch.float32, device=x.device)
-    dinit = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device) if want_dinit else None
+    dinit = out.get("dinit_state")
+    if dinit is None and want_dinit:
+        dinit = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
     need = ssd_workspace_bytes(shape, True)
     if workspace is None:
         workspace = _workspace(need, x.device)
@@ -240,3 +255,27 @@ def magc_plan(n_layers, seqlen, c_lckpt, c_sckpt, c_grid, c_state, s_multiple=25
         raise SSDError(rc, "magc_plan")
     return rc, {"l": p.l, "s": p.s, "m_lckpt": p.m_lckpt, "m_sckpt": p.m_sckpt, "m_grid": p.m_grid,
                 "m_state": p.m_state, "m_total": p.m_total, "regime": p.regime, "fits": bool(p.fits)}
+
+
+def ssd_prof_enable(on: bool) -> None:
+    rc = lib().ssd_prof_enable(1 if on else 0)
+    if rc != 0:
+        raise SSDError(rc, "ssd_prof_enable")
+
+
+def ssd_prof_read() -> dict:
+    """{kernel name: (total milliseconds, launches)} for every kernel launched since ssd_prof_enable(True)."""
+    out = {}
+    kid = 0
+    while True:
+        name = lib().ssd_prof_kernel_name(kid)
+        if name is None:
+            break
+        ms, n = ctypes.c_double(0.0), ctypes.c_int64(0)
+        rc = lib().ssd_prof_read(kid, ctypes.byref(ms), ctypes.byref(n))
+        if rc != 0:
+            raise SSDError(rc, "ssd_prof_read")
+        if n.value:
+            out[name.decode()] = (ms.value, n.value)
+        kid += 1
+    return out

@@ -519,47 +519,27 @@ inline int scan_block(int Q) {
     return t;
 }
 
-#define SSDK_LAUNCH_CHECK()                  \
-    do {                                     \
-        hipError_t e_ = hipGetLastError();   \
-        if (e_ != hipSuccess) return e_;     \
-    } while (0)
-
 template <typename T>
 hipError_t fwd_segment(const SegParams& sp, bool need_y, hipStream_t st) {
     const int Q = sp.Q, P = sp.P, N = sp.N;
-    hipLaunchKernelGGL(k_cumsum<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL((k_chunk_outer<T, 0>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_state_scan_fwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_cb<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    if (need_y) {
-        hipLaunchKernelGGL(k_chunk_out<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(P, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
-        SSDK_LAUNCH_CHECK();
-    }
+    SSDK_LAUNCH(K_CUMSUM, st, k_cumsum<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), sp);
+    SSDK_LAUNCH(K_CHUNK_STATE, st, (k_chunk_outer<T, 0>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_SCAN_FWD, st, k_state_scan_fwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_CB, st, k_cb<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
+    if (need_y) SSDK_LAUNCH(K_CHUNK_OUT, st, k_chunk_out<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(P, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
     return hipSuccess;
 }
 
 template <typename T>
 hipError_t bwd_segment(const SegParams& sp, hipStream_t st) {
     const int Q = sp.Q, P = sp.P, N = sp.N;
-    hipLaunchKernelGGL((k_chunk_outer<T, 1>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_state_scan_bwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_bwd_main<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(Q, TS), 1), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_ddt_finalize<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_dG<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
-    hipLaunchKernelGGL(k_dBC<T>, dim3(sp.Bt * sp.nc * sp.G * 2, cdiv(N, TS), cdiv(Q, TS)), dim3(NTHREADS), 0, st, sp);
-    SSDK_LAUNCH_CHECK();
+    SSDK_LAUNCH(K_DSTATE, st, (k_chunk_outer<T, 1>), dim3(sp.Bt * sp.nc * sp.H, cdiv(N, TS), cdiv(P, TS)), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_SCAN_BWD, st, k_state_scan_bwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_BWD_MAIN, st, k_bwd_main<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(Q, TS), 1), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_DDT, st, k_ddt_finalize<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), sp);
+    SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), sp);
+    SSDK_LAUNCH(K_DG, st, k_dG<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
+    SSDK_LAUNCH(K_DBC, st, k_dBC<T>, dim3(sp.Bt * sp.nc * sp.G * 2, cdiv(N, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
     return hipSuccess;
 }
 
@@ -568,15 +548,15 @@ hipError_t bwd_segment(const SegParams& sp, hipStream_t st) {
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
     const size_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(k_fill_zero, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, p, n);
-    return hipGetLastError();
+    SSDK_LAUNCH(K_FILL, st, k_fill_zero, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), p, n);
+    return hipSuccess;
 }
 
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
     const size_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(k_copy_f32, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), 0, st, dst, src, n);
-    return hipGetLastError();
+    SSDK_LAUNCH(K_COPY, st, k_copy_f32, dim3((unsigned)(blocks < 4096 ? blocks : 4096)), dim3(256), dst, src, n);
+    return hipSuccess;
 }
 
 hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st) {

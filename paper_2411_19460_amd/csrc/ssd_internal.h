@@ -109,6 +109,26 @@ void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd)
 void base_params(SegParams& sp, const Dims& d, uint32_t flags);
 bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
 
+// Kernel ids for the optional event timing (see prof.hip).
+enum KernelId {
+    K_CUMSUM, K_CB, K_CHUNK_STATE, K_SCAN_FWD, K_CHUNK_OUT, K_DSTATE, K_SCAN_BWD, K_BWD_MAIN, K_DDT, K_PARAM, K_DG, K_DBC,
+    K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
+    K_MFMA_DBC, K_COUNT
+};
+void prof_begin(int kid, hipStream_t st);
+void prof_end(int kid, hipStream_t st);
+
+// Launch on `st`, bracketed by timing events when enabled; returns the launch error from the
+// enclosing function.
+#define SSDK_LAUNCH(kid, st, kernel, grid, block, ...)                 \
+    do {                                                               \
+        ::ssdk::prof_begin(kid, st);                                   \
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);   \
+        ::ssdk::prof_end(kid, st);                                     \
+        hipError_t e_ = hipGetLastError();                             \
+        if (e_ != hipSuccess) return e_;                               \
+    } while (0)
+
 // Launchers.  Each returns hipSuccess or the launch error.  is_bf16 selects the storage type.
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
