@@ -61,9 +61,14 @@ WsLayout ws_layout(const Dims& d, bool bwd) {
     w.dtf = take(tok);
     w.states = take((size_t)d.Bt * (d.nc + 1) * d.H * PN * 4);
     w.Gm = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
+    w.ein = take(tok);
+    w.eout = take(tok);
+    w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
+    w.dg_split = d.hpg >= 16 ? 4 : 1;
     if (bwd) {
         w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
-        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
+        w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
+        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4 * w.dg_split);
         w.gterm = take(tok);
         w.fterm = take(tok);
         w.dDrow = take(tok);
@@ -83,7 +88,12 @@ void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd)
     sp.states = (float*)(base + w.states);
     sp.Gm = (float*)(base + w.Gm);
     sp.nslice = w.nslice;
+    sp.ein = (float*)(base + w.ein);
+    sp.eout = (float*)(base + w.eout);
+    sp.states_bf = (bf16_t*)(base + w.states_bf);
+    sp.dg_split = w.dg_split;
     if (bwd) {
+        sp.dstates_bf = (bf16_t*)(base + w.dstates_bf);
         sp.dstates = (float*)(base + w.dstates);
         sp.dG = (float*)(base + w.dG);
         sp.gterm = (float*)(base + w.gterm);

@@ -1,8 +1,466 @@
-// MFMA (bf16) fast path -- placeholder until the matrix-core kernels land.
+// Matrix-core (MFMA, bf16 in / fp32 accumulate) kernels of the chunked selective scan for gfx950.
+// Shape: P = 64 channels per head, N = 128 states, chunk Q in {64, 128, 256}; wave64, 4 waves per
+// workgroup; every contraction runs on v_mfma_f32_32x32x16_bf16.
+//
+// Numerical scheme for the decay mask exp(cum_i - cum_j) of the dual form (Sec. 3.1, Eq. 1 unrolled
+// over a chunk).  The chunk is cut into blocks of 64 tokens.  With
+//     ein_i  = exp(cum_i - cum[start of i's block - 1])      (<= 1)
+//     eout_j = exp(cum[end of j's block] - cum_j)            (<= 1)
+//     s_K    = exp(cum[end of block K] - cum[start of K - 1]) (<= 1, the block's total decay)
+// one has, for i in block I and j in block J < I,
+//     exp(cum_i - cum_j) = ein_i * (prod_{J<K<I} s_K) * eout_j,
+// so the off-diagonal blocks are pure MFMA work on the raw scores G = C B^T and on operands that were
+// scaled once per token while being staged into LDS; the product over K is applied Horner-style by
+// scaling the accumulator with the scalar s_K between blocks (this is the state recurrence at
+// 64-token granularity), and ein / eout is applied once per output row.  Only the four diagonal
+// 64 x 64 blocks evaluate exp() per element.  Every exponent is <= 0: nothing can overflow, and an
+// underflow only happens where the exact value underflows too.
+//
+// Operands whose contraction index is the token index live token-major in memory; they are staged
+// in LDS as [token][channel] and read with the LDS transpose load (ds_read_b64_tr_b16), which hands
+// each lane four consecutive tokens of one channel -- the layout an MFMA operand needs.
 #include "ssd_internal.h"
 
 namespace ssdk {
-bool mfma_path_supported(const ssd_shape_t&) { return false; }
-hipError_t mfma_forward_segment(const SegParams&, bool, hipStream_t) { return hipErrorNotSupported; }
-hipError_t mfma_backward_segment(const SegParams&, hipStream_t) { return hipErrorNotSupported; }
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+
+constexpr int P_ = 64, N_ = 128, BLK = 64;
+constexpr int XPITCH = 144;  // bytes per LDS row of a [token][64] bf16 tile (128 + 16 pad)
+constexpr int BPITCH = 272;  // bytes per LDS row of a [token][128] bf16 tile (256 + 16 pad)
+constexpr int NTH = 256;
+constexpr float LOG2E = 1.4426950408889634f;
+
+__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
+}
+
+// Row (of the 32 x 32 result tile) held in accumulator register r of this lane; the column is lane % 32.
+__device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
+
+// MFMA operand out of a row-major matrix (global memory): row = row0 + lane % 32, eight consecutive k
+// starting at k0 + 8 * (lane / 32).
+__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* base, int64_t row_stride, int row0, int k0, int lane) {
+    return *(const bf16x8*)(base + (int64_t)(row0 + (lane & 31)) * row_stride + k0 + 8 * (lane >> 5));
+}
+
+// MFMA operand out of an LDS tile stored [k][m] (pitch in bytes): rows m0 .. m0+31 of the transpose,
+// k0 .. k0+15.  Within a group of 16 lanes the transpose load returns to lane r the four k-rows
+// addressed by lanes {r/4, r/4+4, r/4+8, r/4+12}... arranged so that, with the addresses below, lane r
+// ends up with T[kb .. kb+3][mb + r].
+__device__ __forceinline__ bf16x8 frag_tr(const char* tile, int pitch, int k0, int m0, int lane) {
+    const int g = lane >> 4, r = lane & 15;
+    const char* p = tile + (k0 + 8 * (g >> 1) + (r >> 2)) * pitch + (m0 + 16 * (g & 1) + 4 * (r & 3)) * 2;
+    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
+    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * pitch));
+    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+__device__ __forceinline__ bf16x8 scale8(bf16x8 v, float s) {
+    bf16x8 o;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)v[e] * s);
+    return o;
+}
+
+__device__ __forceinline__ f32x16 zero16() {
+    f32x16 z;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) z[r] = 0.f;
+    return z;
+}
+
+// ---------------------------------------------------------------------------------------------
+// Decay preparation: cum (chunk-local inclusive cumsum of dt*A), dt in fp32, ein, eout.
+template <int Q>
+__global__ __launch_bounds__(Q) void mk_prep(SegParams sp) {
+    __shared__ float s[Q];
+    const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+    const float d = bf16_to_float(((const bf16_t*)sp.dt)[(int64_t)b * sp.dts_b + ((int64_t)c * Q + i) * sp.H + h]);
+    s[i] = d * sp.A[h];
+    __syncthreads();
+    for (int off = 1; off < Q; off <<= 1) {
+        const float v = (i >= off) ? s[i - off] : 0.f;
+        __syncthreads();
+        s[i] += v;
+        __syncthreads();
+    }
+    const int bs = (i / BLK) * BLK;
+    const float before = bs > 0 ? s[bs - 1] : 0.f;
+    const int64_t o = (((int64_t)b * sp.H + h) * sp.nc + c) * Q + i;
+    sp.cum[o] = s[i];
+    sp.dtf[o] = d;
+    sp.ein[o] = __expf(s[i] - before);
+    sp.eout[o] = __expf(s[bs + BLK - 1] - s[i]);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Scores of one chunk and group: G[i][j] = C_i . B_j and its transpose, bf16, for the 64 x 64 blocks
+// on and below the diagonal.  Layout in the scratch area: G [Q][Q] then GT [Q][Q].
+template <int Q>
+__global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
+    constexpr int NB = Q / BLK;
+    const int z = blockIdx.x, g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    int I = 0, rem = blockIdx.y;  // blockIdx.y enumerates the block pairs (I, J <= I)
+    while (rem > I) {
+        rem -= I + 1;
+        ++I;
+    }
+    const int J = rem;
+    if (I >= NB) return;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int i0 = I * BLK + (w >> 1) * 32, j0 = J * BLK + (w & 1) * 32;
+    const int64_t ts = (int64_t)sp.G * N_;
+    const bf16_t* Cm = (const bf16_t*)sp.Cm + (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
+    const bf16_t* Bm = (const bf16_t*)sp.Bm + (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
+    f32x16 a1 = zero16(), a2 = zero16();
+#pragma unroll
+    for (int ks = 0; ks < N_ / 16; ++ks) {
+        const bf16x8 fc = frag_rows(Cm, ts, i0, 16 * ks, lane);
+        const bf16x8 fb = frag_rows(Bm, ts, j0, 16 * ks, lane);
+        a1 = mfma(fc, fb, a1);  // a1[r] = G[i0 + acc_row(r)][j0 + lane%32]
+        a2 = mfma(fb, fc, a2);  // a2[r] = G[i0 + lane%32][j0 + acc_row(r)]
+    }
+    bf16_t* Gd = (bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
+    bf16_t* GTd = Gd + Q * Q;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+        bf16x4 v1, v2;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            v1[e] = (__bf16)a1[4 * q + e];
+            v2[e] = (__bf16)a2[4 * q + e];
+        }
+        const int rr = 8 * q + 4 * (lane >> 5);
+        *(bf16x4*)(GTd + (int64_t)(j0 + (lane & 31)) * Q + i0 + rr) = v1;
+        *(bf16x4*)(Gd + (int64_t)(i0 + (lane & 31)) * Q + j0 + rr) = v2;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// MODE 0: states[b,c,h]  = sum_j exp(T - cum_j) dt_j x_j (x) B_j      (chunk state, fp32 [P][N])
+// MODE 1: dstates[b,c,h] = sum_i exp(cum_i) dY_i (x) C_i              (local state adjoint)
+// Both operands are token-major: staged per 64-token slab in LDS, read with transpose loads.
+template <int Q, int MODE>
+__global__ __launch_bounds__(NTH) void mk_chunk_outer(SegParams sp) {
+    __shared__ __attribute__((aligned(16))) char xs[BLK * XPITCH];
+    __shared__ __attribute__((aligned(16))) char bs[BLK * BPITCH];
+    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
+    const int g = h / sp.hpg, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float* cum = sp.cum + cbase;
+    const float* dtf = sp.dtf + cbase;
+    const float T_ = cum[Q - 1];
+    const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
+    const bf16_t* lhs = MODE == 0 ? (const bf16_t*)sp.x + (int64_t)b * sp.xs_b : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b;
+    lhs += ((int64_t)c * Q * sp.H + h) * P_;
+    const bf16_t* rhs = (MODE == 0 ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
+                        ((int64_t)c * Q * sp.G + g) * N_;
+    f32x16 acc0 = zero16(), acc1 = zero16();
+    for (int s0 = 0; s0 < Q; s0 += BLK) {
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 2; ++k) {  // 64 rows x 8 vectors of 16 B
+            const int v = tid + NTH * k, row = v >> 3, seg = v & 7, tok = s0 + row;
+            const float wgt = MODE == 0 ? __expf(T_ - cum[tok]) * dtf[tok] : __expf(cum[tok]);
+            const bf16x8 in = *(const bf16x8*)(lhs + (int64_t)tok * xt + seg * 8);
+            *(bf16x8*)(xs + row * XPITCH + seg * 16) = scale8(in, wgt);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {  // 64 rows x 16 vectors of 16 B
+            const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
+            *(bf16x8*)(bs + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)(s0 + row) * bt + seg * 8);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int ks = 0; ks < BLK / 16; ++ks) {
+            const bf16x8 fb = frag_tr(bs, BPITCH, 16 * ks, 32 * w, lane);
+            acc0 = mfma(frag_tr(xs, XPITCH, 16 * ks, 0, lane), fb, acc0);
+            acc1 = mfma(frag_tr(xs, XPITCH, 16 * ks, 32, lane), fb, acc1);
+        }
+    }
+    float* out = MODE == 0 ? sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * (P_ * N_)
+                           : sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        const int p = acc_row(r, lane), n = 32 * w + (lane & 31);
+        out[p * N_ + n] = acc0[r];
+        out[(p + 32) * N_ + n] = acc1[r];
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Inter-chunk state passing over a segment (four state elements per thread), also emitting the bf16
+// copy of every entering state that the contraction kernels read.
+__global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
+    constexpr int PN = P_ * N_;
+    const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
+    const int64_t bh = (int64_t)h * PN + e;
+    float4 hc = sp.state_in ? *(const float4*)(sp.state_in + (int64_t)b * sp.state_in_bs + bh) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (sp.bnd_write) *(float4*)(sp.bnd_write + (int64_t)b * sp.bnd_write_bs + bh) = hc;
+    const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    for (int c = 0; c < sp.nc; ++c) {
+        const int64_t idx = (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e;
+        const float4 s = *(const float4*)(sp.states + idx);
+        *(float4*)(sp.states + idx) = hc;
+        bf16x4 hb;
+        hb[0] = (__bf16)hc.x; hb[1] = (__bf16)hc.y; hb[2] = (__bf16)hc.z; hb[3] = (__bf16)hc.w;
+        *(bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = hb;
+        const float a = __expf(cum[(int64_t)c * sp.Q + sp.Q - 1]);
+        hc.x = a * hc.x + s.x; hc.y = a * hc.y + s.y; hc.z = a * hc.z + s.z; hc.w = a * hc.w + s.w;
+    }
+    *(float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e) = hc;
+    if (sp.state_out) *(float4*)(sp.state_out + (int64_t)b * sp.state_out_bs + bh) = hc;
+    if (sp.state_out2) *(float4*)(sp.state_out2 + (int64_t)b * sp.state_out2_bs + bh) = hc;
+}
+
+// Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-block partial sums
+// of <dHnext_c, Hnext_c> (fixed summation order).
+__global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
+    __shared__ float red[NTH / 64];
+    constexpr int PN = P_ * N_;
+    const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
+    const int64_t ce = ((int64_t)b * sp.H + h) * PN + e;
+    float4 g = *(const float4*)(sp.dcarry + ce);
+    const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    for (int c = sp.nc - 1; c >= 0; --c) {
+        const int64_t idx = (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e;
+        const float4 loc = *(const float4*)(sp.dstates + idx);
+        *(float4*)(sp.dstates + idx) = g;
+        bf16x4 gb;
+        gb[0] = (__bf16)g.x; gb[1] = (__bf16)g.y; gb[2] = (__bf16)g.z; gb[3] = (__bf16)g.w;
+        *(bf16x4*)(sp.dstates_bf + idx) = gb;
+        const float4 hn = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + c + 1) * sp.H + h) * PN + e);
+        float part = g.x * hn.x + g.y * hn.y + g.z * hn.z + g.w * hn.w;
+        for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = part;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            sp.tail_part[(((int64_t)b * sp.H + h) * sp.nc + c) * sp.nslice + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
+        __syncthreads();
+        const float a = __expf(cum[(int64_t)c * sp.Q + sp.Q - 1]);
+        g.x = a * g.x + loc.x; g.y = a * g.y + loc.y; g.z = a * g.z + loc.z; g.w = a * g.w + loc.w;
+    }
+    *(float4*)(sp.dcarry + ce) = g;
+    if (sp.dinit_out) *(float4*)(sp.dinit_out + ce) = g;
+}
+
+// ---------------------------------------------------------------------------------------------
+// The two "dual form" passes over one (chunk, head), computed transposed so that a lane owns a token:
+//   EPI 0 (forward output):  yhat^T[p][i] = sum_{j<=i} G[i][j] decay(i,j) dt_j x_j[p] + exp(cum_i) (Hprev C_i)[p];
+//                            y = yhat + D x  (+ x under the residual flag)
+//   EPI 1 (backward, part 1): the same yhat, reduced to gy_i = dY_i . yhat_i
+//   EPI 2 (backward, part 2): u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
+//                            dx = dt u + D dY (+ dY), and the per-token scalars for ddt / dA / dD
+template <int Q, int EPI>
+__global__ __launch_bounds__(NTH) void mk_dual(SegParams sp) {
+    constexpr int NB = Q / BLK, NT = Q / 32;
+    constexpr bool REV = EPI == 2;
+    __shared__ __attribute__((aligned(16))) char raw[Q * XPITCH];     // dt*x (forward) or dY (reverse)
+    __shared__ __attribute__((aligned(16))) char scl[Q * XPITCH];     // eout*dt*x      or ein*dY
+    __shared__ float cum2[Q];   // cum * log2(e)
+    __shared__ float fac[Q];    // ein (forward) or eout (reverse): applied per output token
+    __shared__ float sfac[NB];  // total decay of each 64-token block
+    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
+    const int g = h / sp.hpg, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
+    const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
+    const bf16_t* dyg = EPI == 0 ? nullptr : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
+    // stage the per-token vectors
+    for (int i = tid; i < Q; i += NTH) {
+        const float cv = sp.cum[cbase + i];
+        cum2[i] = cv * LOG2E;
+        fac[i] = REV ? sp.eout[cbase + i] : sp.ein[cbase + i];
+        if (i < NB) {
+            const float e1 = sp.cum[cbase + i * BLK + BLK - 1], e0 = i > 0 ? sp.cum[cbase + i * BLK - 1] : 0.f;
+            sfac[i] = __expf(e1 - e0);
+        }
+    }
+    // stage the token-major operand twice: plain and pre-scaled
+    {
+        const bf16_t* src = REV ? dyg : xg;
+#pragma unroll
+        for (int k = 0; k < Q * 8 / NTH; ++k) {
+            const int v = tid + NTH * k, row = v >> 3, seg = v & 7;
+            const bf16x8 in = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+            if (REV) {
+                *(bf16x8*)(raw + row * XPITCH + seg * 16) = in;
+                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in, sp.ein[cbase + row]);
+            } else {
+                const float d = sp.dtf[cbase + row];
+                *(bf16x8*)(raw + row * XPITCH + seg * 16) = scale8(in, d);
+                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in, d * sp.eout[cbase + row]);
+            }
+        }
+    }
+    __syncthreads();
+
+    // operands read straight from global memory
+    const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
+    const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
+    const bf16_t* Sb = REV ? sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_)
+                           : sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+    const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
+                          ((int64_t)c * Q * sp.G + g) * N_;
+    const float Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
+
+    for (int s = 0; s < 2; ++s) {
+        if (s == 1 && NT < 8) break;
+        const int t = s == 0 ? w : NT - 1 - w;  // tiles w and NT-1-w: equal causal work for every wave
+        if (t >= NT) continue;
+        const int tok0 = 32 * t, I = t / 2, tok = tok0 + (lane & 31);
+        const float lane_c2 = cum2[tok], lane_fac = fac[tok];
+        f32x16 acc0 = zero16(), acc1 = zero16();
+        // term through the chunk's entering state (forward) / leaving adjoint (reverse)
+#pragma unroll
+        for (int ks = 0; ks < N_ / 16; ++ks) {
+            const bf16x8 fb = frag_rows(rowop, bt, tok0, 16 * ks, lane);
+            acc0 = mfma(frag_rows(Sb, N_, 0, 16 * ks, lane), fb, acc0);
+            acc1 = mfma(frag_rows(Sb, N_, 32, 16 * ks, lane), fb, acc1);
+        }
+        // off-diagonal blocks, Horner in the block decays
+        for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
+            const int K = REV ? NB - 1 - n : n;
+            const float sK = sfac[K];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                acc0[r] *= sK;
+                acc1[r] *= sK;
+            }
+#pragma unroll
+            for (int ks = 0; ks < BLK / 16; ++ks) {
+                const int k0 = K * BLK + 16 * ks;
+                const bf16x8 fb = frag_rows(Mat, Q, tok0, k0, lane);
+                acc0 = mfma(frag_tr(scl, XPITCH, k0, 0, lane), fb, acc0);
+                acc1 = mfma(frag_tr(scl, XPITCH, k0, 32, lane), fb, acc1);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc0[r] *= lane_fac;
+            acc1[r] *= lane_fac;
+        }
+        // diagonal block: the mask and the decay are evaluated per element
+#pragma unroll
+        for (int ks = 0; ks < BLK / 16; ++ks) {
+            const int k0 = I * BLK + 16 * ks;
+            if (REV ? (k0 + 15 < tok0) : (k0 > tok0 + 31)) continue;
+            const bf16x8 gv = frag_rows(Mat, Q, tok0, k0, lane);
+            const int kk0 = k0 + 8 * (lane >> 5);
+            bf16x8 fb;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int kk = kk0 + e;
+                const float diff = REV ? cum2[kk] - lane_c2 : lane_c2 - cum2[kk];
+                const bool ok = REV ? kk >= tok : kk <= tok;
+                fb[e] = (__bf16)(ok ? (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f)) : 0.f);
+            }
+            acc0 = mfma(frag_tr(raw, XPITCH, k0, 0, lane), fb, acc0);
+            acc1 = mfma(frag_tr(raw, XPITCH, k0, 32, lane), fb, acc1);
+        }
+        // epilogue: this lane owns token `tok` and, per register group q, four consecutive channels
+        float s_a = 0.f, s_b = 0.f;
+        const float dtok = REV ? sp.dtf[cbase + tok] : 0.f;
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
+                const int64_t o = (int64_t)tok * xt + p4;
+                const bf16x4 xv = *(const bf16x4*)(xg + o);
+                if (EPI == 0) {
+                    bf16x4 yv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) yv[e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + Dh * (float)xv[e]);
+                    *(bf16x4*)((bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow + o) = yv;
+                } else {
+                    const bf16x4 dv = *(const bf16x4*)(dyg + o);
+                    if (EPI == 1) {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) s_a += (float)dv[e] * (pt ? acc1 : acc0)[4 * q + e];
+                    } else {
+                        bf16x4 ov;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) {
+                            const float u = (pt ? acc1 : acc0)[4 * q + e];
+                            ov[e] = (__bf16)(dtok * u + Dh * (float)dv[e]);
+                            s_a += (float)xv[e] * u;
+                            s_b += (float)dv[e] * (float)xv[e];
+                        }
+                        *(bf16x4*)((bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow + o) = ov;
+                    }
+                }
+            }
+        }
+        if (EPI != 0) {
+            s_a += __shfl_xor(s_a, 32, 64);
+            s_b += __shfl_xor(s_b, 32, 64);
+            if (lane < 32) {
+                if (EPI == 1) {
+                    sp.gterm[cbase + tok] = s_a;
+                } else {
+                    sp.gterm[cbase + tok] = sp.gterm[cbase + tok] - dtok * s_a;
+                    sp.fterm[cbase + tok] = s_a;
+                    sp.dDrow[cbase + tok] = s_b;
+                }
+            }
+        }
+    }
+}
+
+template <int Q>
+hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
+    constexpr int NB = Q / BLK;
+    SSDK_LAUNCH(K_CUMSUM, st, mk_prep<Q>, dim3(sp.nc, sp.H, sp.Bt), dim3(Q), sp);
+    SSDK_LAUNCH(K_MFMA_CHUNK_STATE, st, (mk_chunk_outer<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
+    if (need_y) SSDK_LAUNCH(K_MFMA_CHUNK_OUT, st, (mk_dual<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    return hipSuccess;
+}
+
+template <int Q>
+hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
+    SegParams sp = sp0;
+    sp.nslice = P_ * N_ / 4 / NTH;  // partial sums written by mk_scan_bwd
+    SSDK_LAUNCH(K_MFMA_DSTATE, st, (mk_chunk_outer<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    SSDK_LAUNCH(K_MFMA_BWD_MAIN, st, (mk_dual<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    SSDK_LAUNCH(K_MFMA_BWD_MAIN, st, (mk_dual<Q, 2>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    return generic_backward_tail(sp, st);
+}
+
+}  // namespace
+
+bool mfma_path_supported(const ssd_shape_t& s) {
+    return s.dtype == SSD_BF16 && s.headdim == P_ && s.dstate == N_ && (s.chunk == 64 || s.chunk == 128 || s.chunk == 256);
+}
+
+hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st) {
+    switch (sp.Q) {
+        case 64: return fwd_q<64>(sp, need_y, st);
+        case 128: return fwd_q<128>(sp, need_y, st);
+        case 256: return fwd_q<256>(sp, need_y, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st) {
+    switch (sp.Q) {
+        case 64: return bwd_q<64>(sp, st);
+        case 128: return bwd_q<128>(sp, st);
+        case 256: return bwd_q<256>(sp, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace ssdk

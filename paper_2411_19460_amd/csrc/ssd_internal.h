@@ -72,6 +72,12 @@ struct SegParams {
     float* dD_part;    // [Bt][nc][H]
     float* dcarry;     // [Bt][H][P][N] adjoint of the state entering the segment to the right of the current one
     int nslice;
+    // extra scratch of the MFMA path
+    float* ein;        // [Bt][H][nc][Q] exp(cum_i - cum at the start of i's 64-token block)
+    float* eout;       // [Bt][H][nc][Q] exp(cum at the end of j's 64-token block - cum_j)
+    bf16_t* states_bf;   // [Bt][nc][H][P][N] bf16 copy of the entering states
+    bf16_t* dstates_bf;  // [Bt][nc][H][P][N] bf16 copy of the leaving-state adjoints
+    int dg_split;        // number of head slices whose dG partial sums are kept apart
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
     int64_t state_in_bs;
@@ -100,7 +106,8 @@ struct Dims {
 // Byte offsets of the per-segment scratch arrays inside the caller's workspace.
 struct WsLayout {
     size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
-    int nslice;
+    size_t ein, eout, states_bf, dstates_bf;
+    int nslice, dg_split;
 };
 
 int check_shape(const ssd_shape_t* sh, Dims* d);
@@ -134,6 +141,7 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
 hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st);
 hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st);
+hipError_t generic_backward_tail(const SegParams& sp, hipStream_t st);
 
 // MFMA path (bf16, P = 64, N = 128, Q in {64, 128, 256}).
 bool mfma_path_supported(const ssd_shape_t& s);

@@ -81,6 +81,37 @@ def test_empty_sequence_passes_state_through():
     assert torch.equal(g["dinit_state"], init * 2) and float(g["dA"].abs().sum()) == 0.0
 
 
+@pytest.mark.parametrize("shape", [
+    # Bt, L,   H, G, Q,   segment      (P = 64, N = 128: the matrix-core path)
+    (2, 512, 4, 2, 64, 256),
+    (1, 768, 3, 1, 128, 384),
+    (1, 1024, 4, 1, 256, 512),
+    (2, 512, 2, 2, 256, 512),
+])
+def test_mfma_path_small_with_states(shape):
+    Bt, L, H, G, Q, seg = shape
+    d = small_inputs(4, "bf16", Bt, L, H, 64, G, 128)
+    rep = {}
+    dv, (y, fin, bnd, g) = compare_all(d, "bf16", Q, seg, report=rep)
+    print("mfma errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+    # and against the shape-generic kernels on the device (same algorithm, fp32 FMA arithmetic)
+    y2, fin2, bnd2, g2 = run_gpu(dv, Q, seg, flags=pk.SSD_FLAG_GENERIC_KERNELS)
+    check("y vs generic", host(y), host(y2), 2e-2)
+    for k in g:
+        check(k + " vs generic", host(g[k]), host(g2[k]), 2e-2)
+
+
+def test_mfma_residual_flag():
+    d = small_inputs(5, "bf16", 1, 512, 2, 64, 1, 128)
+    compare_all(d, "bf16", 256, 256, flags=pk.SSD_FLAG_RESIDUAL, residual=True)
+
+
+def test_config1_bf16_generic_kernels():
+    cfg = synth.CONFIGS[1]
+    d = synth.make_layer_inputs(cfg)
+    compare_all(d, cfg.dtype, cfg.chunk, cfg.segment, flags=pk.SSD_FLAG_GENERIC_KERNELS)
+
+
 def test_config1_bf16_all_tensors():
     cfg = synth.CONFIGS[1]
     d = synth.make_layer_inputs(cfg)
