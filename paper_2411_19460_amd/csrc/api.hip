@@ -64,11 +64,12 @@ WsLayout ws_layout(const Dims& d, bool bwd) {
     w.ein = take(tok);
     w.eout = take(tok);
     w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
-    w.dg_split = d.hpg >= 16 ? 4 : 1;
+    w.dg_split = (d.hpg >= 16 && d.hpg % 4 == 0) ? 4 : 1;
     if (bwd) {
         w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
         w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
-        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4 * w.dg_split);
+        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4 * 2 * w.dg_split);  // [i][j] and [j][i] per slice
+        w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.dg_split * 2 * d.Q * d.N * 4);
         w.gterm = take(tok);
         w.fterm = take(tok);
         w.dDrow = take(tok);
@@ -94,6 +95,7 @@ void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd)
     sp.dg_split = w.dg_split;
     if (bwd) {
         sp.dstates_bf = (bf16_t*)(base + w.dstates_bf);
+        sp.dbc_part = (float*)(base + w.dbc_part);
         sp.dstates = (float*)(base + w.dstates);
         sp.dG = (float*)(base + w.dG);
         sp.gterm = (float*)(base + w.gterm);

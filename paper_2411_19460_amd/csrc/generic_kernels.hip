@@ -563,15 +563,10 @@ hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_
     return is_bf16 ? fwd_segment<bf16_t>(sp, need_y, st) : fwd_segment<float>(sp, need_y, st);
 }
 
-// ddt / dA / dD finalisation and the dB, dC kernels (bf16 storage), for callers that produced the
-// per-token scalars and the state adjoints themselves.
-hipError_t generic_backward_tail(const SegParams& sp, hipStream_t st) {
-    typedef bf16_t T;
-    const int Q = sp.Q, N = sp.N;
-    SSDK_LAUNCH(K_DDT, st, k_ddt_finalize<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), sp);
+// ddt / dA / dD finalisation (bf16 storage) for callers that produced the per-token scalars themselves.
+hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st) {
+    SSDK_LAUNCH(K_DDT, st, k_ddt_finalize<bf16_t>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(sp.Q)), sp);
     SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), sp);
-    SSDK_LAUNCH(K_DG, st, k_dG<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
-    SSDK_LAUNCH(K_DBC, st, k_dBC<T>, dim3(sp.Bt * sp.nc * sp.G * 2, cdiv(N, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
     return hipSuccess;
 }
 

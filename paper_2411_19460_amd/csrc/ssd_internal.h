@@ -77,7 +77,8 @@ struct SegParams {
     float* eout;       // [Bt][H][nc][Q] exp(cum at the end of j's 64-token block - cum_j)
     bf16_t* states_bf;   // [Bt][nc][H][P][N] bf16 copy of the entering states
     bf16_t* dstates_bf;  // [Bt][nc][H][P][N] bf16 copy of the leaving-state adjoints
-    int dg_split;        // number of head slices whose dG partial sums are kept apart
+    int dg_split;        // number of head slices whose dG / dB / dC partial sums are kept apart
+    float* dbc_part;     // [Bt][nc][G][dg_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
     int64_t state_in_bs;
@@ -106,7 +107,7 @@ struct Dims {
 // Byte offsets of the per-segment scratch arrays inside the caller's workspace.
 struct WsLayout {
     size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
-    size_t ein, eout, states_bf, dstates_bf;
+    size_t ein, eout, states_bf, dstates_bf, dbc_part;
     int nslice, dg_split;
 };
 
@@ -120,7 +121,7 @@ bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
 enum KernelId {
     K_CUMSUM, K_CB, K_CHUNK_STATE, K_SCAN_FWD, K_CHUNK_OUT, K_DSTATE, K_SCAN_BWD, K_BWD_MAIN, K_DDT, K_PARAM, K_DG, K_DBC,
     K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
-    K_MFMA_DBC, K_COUNT
+    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_COUNT
 };
 void prof_begin(int kid, hipStream_t st);
 void prof_end(int kid, hipStream_t st);
@@ -141,7 +142,7 @@ hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
 hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st);
 hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st);
-hipError_t generic_backward_tail(const SegParams& sp, hipStream_t st);
+hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st);
 
 // MFMA path (bf16, P = 64, N = 128, Q in {64, 128, 256}).
 bool mfma_path_supported(const ssd_shape_t& s);
