@@ -259,9 +259,182 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
 //   EPI 1 (backward, part 1): the same yhat, reduced to gy_i = dY_i . yhat_i
 //   EPI 2 (backward, part 2): u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
 //                            dx = dt u + D dY (+ dY), and the per-token scalars for ddt / dA / dD
+// Work split: the chunk has Q/32 token tiles; with Q = 256 wave w owns tiles w and 7-w (equal causal
+// work).  The tile index is a compile-time constant inside tile_load / tile_compute so that every
+// fragment of the score matrix and of C (or B) a wave needs is fetched into registers before the
+// LDS staging, in one round of memory latency.
+constexpr int GF_MAX = 18, RF_MAX = 16;
+
+template <int Q, int EPI, int T>
+struct DualTile {
+    static constexpr bool REV = EPI == 2;
+    static constexpr int NB = Q / BLK, I = T / 2, TOK0 = 32 * T, ODD = T & 1;
+    static constexpr int KS0 = REV ? 2 * T : 0;                         // first 16-token step of the contraction
+    static constexpr int NFR = REV ? 4 * NB - 2 * T : 2 * (T + 1);      // number of 16-token steps
+};
+
+template <int Q, int EPI, int T, int GOFF, int ROFF>
+__device__ __forceinline__ void tile_load(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
+                                          const bf16_t* rowop, int64_t bt, int lane) {
+    typedef DualTile<Q, EPI, T> TI;
+#pragma unroll
+    for (int f = 0; f < TI::NFR; ++f) gf[GOFF + f] = frag_rows(Mat, Q, TI::TOK0, 16 * (TI::KS0 + f), lane);
+#pragma unroll
+    for (int ks = 0; ks < N_ / 16; ++ks) rf[ROFF + ks] = frag_rows(rowop, bt, TI::TOK0, 16 * ks, lane);
+}
+
+struct DualCtx {
+    const char* raw;
+    const char* scl;
+    const float* cum2;
+    const float* fac;
+    const float* sfac;
+    const bf16_t* Sb;
+    const bf16_t* xg;
+    const bf16_t* dyg;
+    bf16_t* outp;  // y (EPI 0) or dx (EPI 2), already offset to the chunk and head
+    float* gterm;
+    float* fterm;
+    float* dDrow;
+    const float* dtf;
+    int64_t xt;
+    float Dh;
+};
+
+template <int Q, int EPI, int T, int GOFF, int ROFF>
+__device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const bf16x8 (&rf)[RF_MAX], const DualCtx& cx,
+                                             int lane) {
+    typedef DualTile<Q, EPI, T> TI;
+    constexpr bool REV = TI::REV;
+    constexpr int NB = TI::NB, I = TI::I;
+    const int tok = TI::TOK0 + (lane & 31);
+    const float lane_c2 = cx.cum2[tok], lane_fac = cx.fac[tok];
+    f32x16 acc0 = zero16(), acc1 = zero16();
+    // term through the chunk's entering state (forward) / leaving adjoint (reverse)
+#pragma unroll
+    for (int ks = 0; ks < N_ / 16; ++ks) {
+        acc0 = mfma(frag_rows(cx.Sb, N_, 0, 16 * ks, lane), rf[ROFF + ks], acc0);
+        acc1 = mfma(frag_rows(cx.Sb, N_, 32, 16 * ks, lane), rf[ROFF + ks], acc1);
+    }
+    // off-diagonal blocks, Horner in the block decays
+#pragma unroll
+    for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
+        const int K = REV ? NB - 1 - n : n;
+        const float sK = cx.sfac[K];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc0[r] *= sK;
+            acc1[r] *= sK;
+        }
+#pragma unroll
+        for (int ks = 0; ks < BLK / 16; ++ks) {
+            const int k0 = K * BLK + 16 * ks;
+            const bf16x8 fb = gf[GOFF + 4 * K + ks - TI::KS0];
+            acc0 = mfma(frag_tr(cx.scl, XPITCH, k0, 0, lane), fb, acc0);
+            acc1 = mfma(frag_tr(cx.scl, XPITCH, k0, 32, lane), fb, acc1);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        acc0[r] *= lane_fac;
+        acc1[r] *= lane_fac;
+    }
+    // diagonal block: the mask and the decay are evaluated per element
+#pragma unroll
+    for (int ks = (REV && TI::ODD) ? 2 : 0; ks < ((!REV && !TI::ODD) ? 2 : 4); ++ks) {
+        const int k0 = I * BLK + 16 * ks;
+        const bf16x8 gv = gf[GOFF + 4 * I + ks - TI::KS0];
+        const int kk0 = k0 + 8 * (lane >> 5);
+        bf16x8 fb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int kk = kk0 + e;
+            const float diff = REV ? cx.cum2[kk] - lane_c2 : lane_c2 - cx.cum2[kk];
+            const bool ok = REV ? kk >= tok : kk <= tok;
+            fb[e] = (__bf16)(ok ? (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f)) : 0.f);
+        }
+        acc0 = mfma(frag_tr(cx.raw, XPITCH, k0, 0, lane), fb, acc0);
+        acc1 = mfma(frag_tr(cx.raw, XPITCH, k0, 32, lane), fb, acc1);
+    }
+    // epilogue: this lane owns token `tok` and, per register group q, four consecutive channels
+    float s_a = 0.f, s_b = 0.f;
+    const float dtok = REV ? cx.dtf[tok] : 0.f;
+#pragma unroll
+    for (int pt = 0; pt < 2; ++pt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
+            const int64_t o = (int64_t)tok * cx.xt + p4;
+            const bf16x4 xv = *(const bf16x4*)(cx.xg + o);
+            if (EPI == 0) {
+                bf16x4 yv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) yv[e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)xv[e]);
+                *(bf16x4*)(cx.outp + o) = yv;
+            } else {
+                const bf16x4 dv = *(const bf16x4*)(cx.dyg + o);
+                if (EPI == 1) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s_a += (float)dv[e] * (pt ? acc1 : acc0)[4 * q + e];
+                } else {
+                    bf16x4 ov;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float u = (pt ? acc1 : acc0)[4 * q + e];
+                        ov[e] = (__bf16)(dtok * u + cx.Dh * (float)dv[e]);
+                        s_a += (float)xv[e] * u;
+                        s_b += (float)dv[e] * (float)xv[e];
+                    }
+                    *(bf16x4*)(cx.outp + o) = ov;
+                }
+            }
+        }
+    }
+    if (EPI != 0) {
+        s_a += __shfl_xor(s_a, 32, 64);
+        s_b += __shfl_xor(s_b, 32, 64);
+        if (lane < 32) {
+            if (EPI == 1) {
+                cx.gterm[tok] = s_a;
+            } else {
+                cx.gterm[tok] = cx.gterm[tok] - dtok * s_a;
+                cx.fterm[tok] = s_a;
+                cx.dDrow[tok] = s_b;
+            }
+        }
+    }
+}
+
+// Dispatch on the wave index: PHASE 0 issues the hoisted loads, PHASE 1 computes.
+template <int Q, int EPI, int PHASE, int TA, int TB>
+__device__ __forceinline__ void wave_tiles(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
+                                           const bf16_t* rowop, int64_t bt, const DualCtx& cx, int lane) {
+    constexpr int NT = Q / 32;
+    if constexpr (TA < NT) {
+        if constexpr (PHASE == 0) tile_load<Q, EPI, TA, 0, 0>(gf, rf, Mat, rowop, bt, lane);
+        else tile_compute<Q, EPI, TA, 0, 0>(gf, rf, cx, lane);
+    }
+    if constexpr (TB >= 0 && TB < NT && NT == 8) {
+        constexpr int GO = DualTile<Q, EPI, (TA < NT ? TA : 0)>::NFR;
+        if constexpr (PHASE == 0) tile_load<Q, EPI, TB, GO, 8>(gf, rf, Mat, rowop, bt, lane);
+        else tile_compute<Q, EPI, TB, GO, 8>(gf, rf, cx, lane);
+    }
+}
+
+template <int Q, int EPI, int PHASE>
+__device__ __forceinline__ void wave_dispatch(int w, bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
+                                              const bf16_t* rowop, int64_t bt, const DualCtx& cx, int lane) {
+    switch (w) {
+        case 0: wave_tiles<Q, EPI, PHASE, 0, 7>(gf, rf, Mat, rowop, bt, cx, lane); break;
+        case 1: wave_tiles<Q, EPI, PHASE, 1, 6>(gf, rf, Mat, rowop, bt, cx, lane); break;
+        case 2: wave_tiles<Q, EPI, PHASE, 2, 5>(gf, rf, Mat, rowop, bt, cx, lane); break;
+        default: wave_tiles<Q, EPI, PHASE, 3, 4>(gf, rf, Mat, rowop, bt, cx, lane); break;
+    }
+}
+
 template <int Q, int EPI>
-__global__ __launch_bounds__(NTH) void mk_dual(SegParams sp) {
-    constexpr int NB = Q / BLK, NT = Q / 32;
+__global__ __launch_bounds__(NTH, 2) void mk_dual(SegParams sp) {
+    constexpr int NB = Q / BLK;
     constexpr bool REV = EPI == 2;
     __shared__ __attribute__((aligned(16))) char raw[Q * XPITCH];     // dt*x (forward) or dY (reverse)
     __shared__ __attribute__((aligned(16))) char scl[Q * XPITCH];     // eout*dt*x      or ein*dY
@@ -275,6 +448,31 @@ __global__ __launch_bounds__(NTH) void mk_dual(SegParams sp) {
     const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
     const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
     const bf16_t* dyg = EPI == 0 ? nullptr : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
+    // operands read straight from global memory: issue those loads first
+    const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
+    const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
+    const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
+                          ((int64_t)c * Q * sp.G + g) * N_;
+    DualCtx cx;
+    cx.raw = raw;
+    cx.scl = scl;
+    cx.cum2 = cum2;
+    cx.fac = fac;
+    cx.sfac = sfac;
+    cx.Sb = REV ? sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_)
+                : sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+    cx.xg = xg;
+    cx.dyg = dyg;
+    cx.outp = EPI == 0 ? (bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow : (EPI == 2 ? (bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow : nullptr);
+    cx.gterm = sp.gterm + cbase;
+    cx.fterm = sp.fterm + cbase;
+    cx.dDrow = sp.dDrow + cbase;
+    cx.dtf = sp.dtf + cbase;
+    cx.xt = xt;
+    cx.Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
+    bf16x8 gf[GF_MAX], rf[RF_MAX];
+    wave_dispatch<Q, EPI, 0>(w, gf, rf, Mat, rowop, bt, cx, lane);
+
     // stage the per-token vectors
     for (int i = tid; i < Q; i += NTH) {
         const float cv = sp.cum[cbase + i];
@@ -288,135 +486,30 @@ __global__ __launch_bounds__(NTH) void mk_dual(SegParams sp) {
     // stage the token-major operand twice: plain and pre-scaled
     {
         const bf16_t* src = REV ? dyg : xg;
+        bf16x8 in[Q * 8 / NTH];
+        float s1[Q * 8 / NTH], s2[Q * 8 / NTH];
 #pragma unroll
         for (int k = 0; k < Q * 8 / NTH; ++k) {
             const int v = tid + NTH * k, row = v >> 3, seg = v & 7;
-            const bf16x8 in = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+            in[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+            s1[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row];
+            s2[k] = REV ? 0.f : sp.eout[cbase + row];
+        }
+#pragma unroll
+        for (int k = 0; k < Q * 8 / NTH; ++k) {
+            const int v = tid + NTH * k, row = v >> 3, seg = v & 7;
             if (REV) {
-                *(bf16x8*)(raw + row * XPITCH + seg * 16) = in;
-                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in, sp.ein[cbase + row]);
+                *(bf16x8*)(raw + row * XPITCH + seg * 16) = in[k];
+                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in[k], s1[k]);
             } else {
-                const float d = sp.dtf[cbase + row];
-                *(bf16x8*)(raw + row * XPITCH + seg * 16) = scale8(in, d);
-                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in, d * sp.eout[cbase + row]);
+                *(bf16x8*)(raw + row * XPITCH + seg * 16) = scale8(in[k], s1[k]);
+                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in[k], s1[k] * s2[k]);
             }
         }
     }
     __syncthreads();
-
-    // operands read straight from global memory
-    const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
-    const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
-    const bf16_t* Sb = REV ? sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_)
-                           : sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
-    const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
-                          ((int64_t)c * Q * sp.G + g) * N_;
-    const float Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
-
-    for (int s = 0; s < 2; ++s) {
-        if (s == 1 && NT < 8) break;
-        const int t = s == 0 ? w : NT - 1 - w;  // tiles w and NT-1-w: equal causal work for every wave
-        if (t >= NT) continue;
-        const int tok0 = 32 * t, I = t / 2, tok = tok0 + (lane & 31);
-        const float lane_c2 = cum2[tok], lane_fac = fac[tok];
-        f32x16 acc0 = zero16(), acc1 = zero16();
-        // term through the chunk's entering state (forward) / leaving adjoint (reverse)
-#pragma unroll
-        for (int ks = 0; ks < N_ / 16; ++ks) {
-            const bf16x8 fb = frag_rows(rowop, bt, tok0, 16 * ks, lane);
-            acc0 = mfma(frag_rows(Sb, N_, 0, 16 * ks, lane), fb, acc0);
-            acc1 = mfma(frag_rows(Sb, N_, 32, 16 * ks, lane), fb, acc1);
-        }
-        // off-diagonal blocks, Horner in the block decays
-        for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
-            const int K = REV ? NB - 1 - n : n;
-            const float sK = sfac[K];
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                acc0[r] *= sK;
-                acc1[r] *= sK;
-            }
-#pragma unroll
-            for (int ks = 0; ks < BLK / 16; ++ks) {
-                const int k0 = K * BLK + 16 * ks;
-                const bf16x8 fb = frag_rows(Mat, Q, tok0, k0, lane);
-                acc0 = mfma(frag_tr(scl, XPITCH, k0, 0, lane), fb, acc0);
-                acc1 = mfma(frag_tr(scl, XPITCH, k0, 32, lane), fb, acc1);
-            }
-        }
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            acc0[r] *= lane_fac;
-            acc1[r] *= lane_fac;
-        }
-        // diagonal block: the mask and the decay are evaluated per element
-#pragma unroll
-        for (int ks = 0; ks < BLK / 16; ++ks) {
-            const int k0 = I * BLK + 16 * ks;
-            if (REV ? (k0 + 15 < tok0) : (k0 > tok0 + 31)) continue;
-            const bf16x8 gv = frag_rows(Mat, Q, tok0, k0, lane);
-            const int kk0 = k0 + 8 * (lane >> 5);
-            bf16x8 fb;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int kk = kk0 + e;
-                const float diff = REV ? cum2[kk] - lane_c2 : lane_c2 - cum2[kk];
-                const bool ok = REV ? kk >= tok : kk <= tok;
-                fb[e] = (__bf16)(ok ? (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f)) : 0.f);
-            }
-            acc0 = mfma(frag_tr(raw, XPITCH, k0, 0, lane), fb, acc0);
-            acc1 = mfma(frag_tr(raw, XPITCH, k0, 32, lane), fb, acc1);
-        }
-        // epilogue: this lane owns token `tok` and, per register group q, four consecutive channels
-        float s_a = 0.f, s_b = 0.f;
-        const float dtok = REV ? sp.dtf[cbase + tok] : 0.f;
-#pragma unroll
-        for (int pt = 0; pt < 2; ++pt) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
-                const int64_t o = (int64_t)tok * xt + p4;
-                const bf16x4 xv = *(const bf16x4*)(xg + o);
-                if (EPI == 0) {
-                    bf16x4 yv;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) yv[e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + Dh * (float)xv[e]);
-                    *(bf16x4*)((bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow + o) = yv;
-                } else {
-                    const bf16x4 dv = *(const bf16x4*)(dyg + o);
-                    if (EPI == 1) {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) s_a += (float)dv[e] * (pt ? acc1 : acc0)[4 * q + e];
-                    } else {
-                        bf16x4 ov;
-#pragma unroll
-                        for (int e = 0; e < 4; ++e) {
-                            const float u = (pt ? acc1 : acc0)[4 * q + e];
-                            ov[e] = (__bf16)(dtok * u + Dh * (float)dv[e]);
-                            s_a += (float)xv[e] * u;
-                            s_b += (float)dv[e] * (float)xv[e];
-                        }
-                        *(bf16x4*)((bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow + o) = ov;
-                    }
-                }
-            }
-        }
-        if (EPI != 0) {
-            s_a += __shfl_xor(s_a, 32, 64);
-            s_b += __shfl_xor(s_b, 32, 64);
-            if (lane < 32) {
-                if (EPI == 1) {
-                    sp.gterm[cbase + tok] = s_a;
-                } else {
-                    sp.gterm[cbase + tok] = sp.gterm[cbase + tok] - dtok * s_a;
-                    sp.fterm[cbase + tok] = s_a;
-                    sp.dDrow[cbase + tok] = s_b;
-                }
-            }
-        }
-    }
+    wave_dispatch<Q, EPI, 1>(w, gf, rf, Mat, rowop, bt, cx, lane);
 }
-
 
 // ---------------------------------------------------------------------------------------------
 // dG[i][j] = sum over the heads of one slice of  decay_h(i,j) dt_h,j (dY_h,i . x_h,j),  j <= i, for one
