@@ -1,0 +1,396 @@
+// The "dual form" passes of the chunked selective scan on the matrix cores (gfx950, bf16 in / fp32
+// accumulate): for one chunk of Q tokens, the quadratic form of Eq. 1 unrolled over the chunk plus
+// the term through the chunk's entering state (forward) or leaving state adjoint (reverse).
+// Computed transposed, so that a lane owns a token:
+//   EPI 0 (forward output):   yhat^T[p][i] = sum_{j<=i} G[i][j] decay(i,j) dt_j x_j[p] + exp(cum_i) (Hprev C_i)[p];
+//                             y = yhat + D x  (+ x under the residual flag)
+//   EPI 1 (backward, part 1): the same yhat, reduced to gy_i = dY_i . yhat_i
+//   EPI 2 (backward, part 2): u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
+//                             dx = dt u + D dY (+ dY), and the per-token scalars for ddt / dA / dD
+//
+// Organisation.  One workgroup owns one (batch, chunk, group) and a slice of that group's heads and
+// walks the heads one after the other.  Each of its waves owns two 32-token tiles of the chunk, t and
+// Q/32 - 1 - t, which together carry the same amount of causal work for every wave.  Everything
+// that does not depend on the head -- the wave's rows of the score matrix G = C B^T (or of its
+// transpose) and of C (or B) -- is fetched once and stays in registers as MFMA operands for all
+// heads of the slice.  Per head, the token-major operand (x or dY, Q x 64) and the state (64 x 128)
+// are prefetched into registers while the previous head is being computed, then staged in LDS
+// (plain and pre-scaled copy of the tile, see the decay factorisation in mfma_kernels.hip); outputs
+// go through a per-wave LDS patch so that global stores are whole 128-byte rows.
+// One wave per SIMD with the whole register file to itself: the persistent fragments take ~140
+// registers per lane.
+#include "mfma_common.h"
+
+namespace ssdk {
+namespace {
+
+using namespace mf;
+
+constexpr int GF_MAX = 18;  // score-matrix fragments a wave keeps for its two tiles (Q = 256: 18 steps of 16 tokens)
+constexpr int RF_N = N_ / 16;
+
+template <int Q>
+struct DualCfg {
+    static constexpr int NT = Q / 32;           // token tiles
+    static constexpr int NW = NT / 2;           // waves: two tiles each
+    static constexpr int NTHR = 64 * NW;
+    static constexpr int NB = Q / BLK;
+    static constexpr int XV = Q * 8 / NTHR;     // 16-byte vectors of the token-major tile per thread (= 8)
+    static constexpr int SV = P_ * 16 / NTHR;   // 16-byte vectors of the state per thread
+};
+
+template <int Q>
+struct DualLds {
+    char raw[Q * XPITCH];    // x (forward) or dY (reverse), token-major
+    char scl[Q * XPITCH];    // eout*dt*x      or ein*dY
+    char st[P_ * BPITCH];    // entering state / leaving adjoint, [p][n] bf16
+    float cum2[Q];           // cum * log2(e)
+    float fac[Q];            // ein (forward) or eout (reverse): applied per output token
+    float dtl[Q];            // dt
+    char priv[Q / 64][32 * XPITCH];  // per-wave patch for the row-major epilogue
+};
+
+template <int Q, int EPI, int T>
+struct DualTile {
+    static constexpr bool REV = EPI == 2;
+    static constexpr int NB = Q / BLK, I = T / 2, TOK0 = 32 * T, ODD = T & 1;
+    static constexpr int KS0 = REV ? 2 * T : 0;                     // first 16-token step of the contraction
+    static constexpr int NFR = REV ? 4 * NB - 2 * T : 2 * (T + 1);  // number of 16-token steps
+};
+
+// Registers holding the next head's operands while the current head is computed.
+template <int Q>
+struct Pre {
+    bf16x8 xt[DualCfg<Q>::XV];
+    float sc[DualCfg<Q>::XV];
+    bf16x8 sv[DualCfg<Q>::SV];
+    float cum, dtf, fac;
+};
+
+struct HeadCtx {
+    const bf16_t* xg;   // x rows of this chunk and head
+    const bf16_t* dyg;  // dY rows (EPI 1, 2)
+    bf16_t* outp;       // y (EPI 0) or dx (EPI 2)
+    float* gterm;
+    float* fterm;
+    float* dDrow;
+    int64_t xt;
+    float Dh;
+};
+
+__device__ __forceinline__ void lds_wave_fence() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ bf16x8 frag_lds_rows(const char* tile, int pitch, int row0, int k0, int lane) {
+    return *(const bf16x8*)(tile + (row0 + (lane & 31)) * pitch + (k0 + 8 * (lane >> 5)) * 2);
+}
+
+template <int Q, bool REV>
+__device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b, int c, int h, int tid) {
+    typedef DualCfg<Q> CF;
+    const int64_t xt = (int64_t)sp.H * P_;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const bf16_t* src = (REV ? (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b : (const bf16_t*)sp.x + (int64_t)b * sp.xs_b) +
+                        ((int64_t)c * Q * sp.H + h) * P_;
+#pragma unroll
+    for (int k = 0; k < CF::XV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
+        pr.xt[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+        pr.sc[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row] * sp.eout[cbase + row];
+    }
+    const bf16_t* S = (REV ? sp.dstates_bf : sp.states_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+#pragma unroll
+    for (int k = 0; k < CF::SV; ++k) {
+        const int v = tid + CF::NTHR * k;
+        pr.sv[k] = *(const bf16x8*)(S + v * 8);
+    }
+    if (tid < Q) {
+        pr.cum = sp.cum[cbase + tid];
+        pr.dtf = sp.dtf[cbase + tid];
+        pr.fac = REV ? sp.eout[cbase + tid] : sp.ein[cbase + tid];
+    }
+}
+
+template <int Q, bool REV>
+__device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int tid) {
+    typedef DualCfg<Q> CF;
+#pragma unroll
+    for (int k = 0; k < CF::XV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
+        *(bf16x8*)(L.raw + row * XPITCH + seg * 16) = pr.xt[k];
+        *(bf16x8*)(L.scl + row * XPITCH + seg * 16) = scale8(pr.xt[k], pr.sc[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < CF::SV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 4, seg = v & 15;
+        *(bf16x8*)(L.st + row * BPITCH + seg * 16) = pr.sv[k];
+    }
+    if (tid < Q) {
+        L.cum2[tid] = pr.cum * LOG2E;
+        L.fac[tid] = pr.fac;
+        L.dtl[tid] = pr.dtf;
+    }
+}
+
+template <int Q, int EPI, int T, int GOFF, int ROFF>
+__device__ __forceinline__ void tile_load(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat, const bf16_t* rowop,
+                                          int64_t bt, int lane) {
+    typedef DualTile<Q, EPI, T> TI;
+#pragma unroll
+    for (int f = 0; f < TI::NFR; ++f) gf[GOFF + f] = frag_rows(Mat, Q, TI::TOK0, 16 * (TI::KS0 + f), lane);
+#pragma unroll
+    for (int ks = 0; ks < RF_N; ++ks) rf[ROFF + ks] = frag_rows(rowop, bt, TI::TOK0, 16 * ks, lane);
+}
+
+template <int Q, int EPI, int T, int GOFF, int ROFF>
+__device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const bf16x8 (&rf)[2 * RF_N], DualLds<Q>& L,
+                                             const HeadCtx& cx, int lane, int w) {
+    typedef DualTile<Q, EPI, T> TI;
+    constexpr bool REV = TI::REV;
+    constexpr int NB = TI::NB, I = TI::I;
+    const int tl = lane & 31, tok = TI::TOK0 + tl;
+    char* priv = L.priv[w];
+    // this wave's own 32 rows of the other token-major tensor, fetched as whole rows (EPI 1: dY, EPI 2: x)
+    bf16x8 own[4];
+    if (EPI != 0) {
+        const bf16_t* src = EPI == 1 ? cx.dyg : cx.xg;
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            own[it] = *(const bf16x8*)(src + (int64_t)(TI::TOK0 + (lane >> 3) + 8 * it) * cx.xt + (lane & 7) * 8);
+    }
+    const float lane_c2 = L.cum2[tok], lane_fac = L.fac[tok];
+    f32x16 acc0 = zero16(), acc1 = zero16();
+    // term through the chunk's entering state (forward) / leaving adjoint (reverse)
+#pragma unroll
+    for (int ks = 0; ks < RF_N; ++ks) {
+        acc0 = mfma(frag_lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ROFF + ks], acc0);
+        acc1 = mfma(frag_lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ROFF + ks], acc1);
+    }
+    // off-diagonal 64-token blocks, Horner in the block decays
+#pragma unroll
+    for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
+        const int K = REV ? NB - 1 - n : n;
+        const float sK = __builtin_amdgcn_exp2f(L.cum2[K * BLK + BLK - 1] - (K > 0 ? L.cum2[K * BLK - 1] : 0.f));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            acc0[r] *= sK;
+            acc1[r] *= sK;
+        }
+#pragma unroll
+        for (int ks = 0; ks < BLK / 16; ++ks) {
+            const int k0 = K * BLK + 16 * ks;
+            const bf16x8 fb = gf[GOFF + 4 * K + ks - TI::KS0];
+            acc0 = mfma(frag_tr(L.scl, XPITCH, k0, 0, lane), fb, acc0);
+            acc1 = mfma(frag_tr(L.scl, XPITCH, k0, 32, lane), fb, acc1);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        acc0[r] *= lane_fac;
+        acc1[r] *= lane_fac;
+    }
+    // diagonal block: the mask and the decay (and, forward, dt_j) are evaluated per element
+#pragma unroll
+    for (int ks = (REV && TI::ODD) ? 2 : 0; ks < ((!REV && !TI::ODD) ? 2 : 4); ++ks) {
+        const int k0 = I * BLK + 16 * ks;
+        const bf16x8 gv = gf[GOFF + 4 * I + ks - TI::KS0];
+        const int kk0 = k0 + 8 * (lane >> 5);
+        const float4 ca = *(const float4*)(L.cum2 + kk0), cb = *(const float4*)(L.cum2 + kk0 + 4);
+        const float cv[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+        float dv[8];
+        if (!REV) {
+            const float4 da = *(const float4*)(L.dtl + kk0), db = *(const float4*)(L.dtl + kk0 + 4);
+            dv[0] = da.x; dv[1] = da.y; dv[2] = da.z; dv[3] = da.w;
+            dv[4] = db.x; dv[5] = db.y; dv[6] = db.z; dv[7] = db.w;
+        }
+        bf16x8 fb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int kk = kk0 + e;
+            const float diff = REV ? cv[e] - lane_c2 : lane_c2 - cv[e];
+            const bool ok = REV ? kk >= tok : kk <= tok;
+            float f = (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f));
+            if (!REV) f *= dv[e];
+            fb[e] = (__bf16)(ok ? f : 0.f);
+        }
+        acc0 = mfma(frag_tr(L.raw, XPITCH, k0, 0, lane), fb, acc0);
+        acc1 = mfma(frag_tr(L.raw, XPITCH, k0, 32, lane), fb, acc1);
+    }
+    // epilogue: in the accumulators this lane owns token `tok` and, per register group q, four
+    // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses
+    if (EPI != 0) {
+#pragma unroll
+        for (int it = 0; it < 4; ++it) *(bf16x8*)(priv + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = own[it];
+        lds_wave_fence();
+    }
+    float s_a = 0.f, s_b = 0.f;
+    const float dtok = REV ? L.dtl[tok] : 0.f;
+    bf16x4 outv[8];
+#pragma unroll
+    for (int pt = 0; pt < 2; ++pt) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
+            const bf16x4 mine = *(const bf16x4*)(L.raw + tok * XPITCH + p4 * 2);  // x (EPI 0, 1) or dY (EPI 2)
+            if (EPI == 0) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) outv[4 * pt + q][e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)mine[e]);
+            } else {
+                const bf16x4 other = *(const bf16x4*)(priv + tl * XPITCH + p4 * 2);  // dY (EPI 1) or x (EPI 2)
+                if (EPI == 1) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) s_a += (float)other[e] * (pt ? acc1 : acc0)[4 * q + e];
+                } else {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        const float u = (pt ? acc1 : acc0)[4 * q + e];
+                        outv[4 * pt + q][e] = (__bf16)(dtok * u + cx.Dh * (float)mine[e]);
+                        s_a += (float)other[e] * u;
+                        s_b += (float)mine[e] * (float)other[e];
+                    }
+                }
+            }
+        }
+    }
+    if (EPI != 1) {
+        if (EPI == 2) lds_wave_fence();  // every read of x from the patch is done
+#pragma unroll
+        for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                *(bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2) = outv[4 * pt + q];
+        lds_wave_fence();
+#pragma unroll
+        for (int it = 0; it < 4; ++it) {
+            const int row = (lane >> 3) + 8 * it;
+            const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
+            *(bf16x8*)(cx.outp + (int64_t)(TI::TOK0 + row) * cx.xt + (lane & 7) * 8) = v;
+        }
+    }
+    if (EPI != 0) {
+        s_a += __shfl_xor(s_a, 32, 64);
+        s_b += __shfl_xor(s_b, 32, 64);
+        if (lane < 32) {
+            if (EPI == 1) {
+                cx.gterm[tok] = s_a;
+            } else {
+                cx.gterm[tok] = cx.gterm[tok] - dtok * s_a;
+                cx.fterm[tok] = s_a;
+                cx.dDrow[tok] = s_b;
+            }
+        }
+    }
+}
+
+// Wave w owns tiles w and NT - 1 - w.  PHASE 0 fetches the persistent fragments, PHASE 1 computes one head.
+template <int Q, int EPI, int PHASE, int W>
+__device__ __forceinline__ void wave_phase(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat, const bf16_t* rowop,
+                                           int64_t bt, DualLds<Q>& L, const HeadCtx& cx, int lane) {
+    constexpr int NT = Q / 32, TA = W, TB = NT - 1 - W;
+    if constexpr (W < NT / 2) {
+        constexpr int GO = DualTile<Q, EPI, TA>::NFR;
+        if constexpr (PHASE == 0) {
+            tile_load<Q, EPI, TA, 0, 0>(gf, rf, Mat, rowop, bt, lane);
+            tile_load<Q, EPI, TB, GO, RF_N>(gf, rf, Mat, rowop, bt, lane);
+        } else {
+            tile_compute<Q, EPI, TA, 0, 0>(gf, rf, L, cx, lane, W);
+            tile_compute<Q, EPI, TB, GO, RF_N>(gf, rf, L, cx, lane, W);
+        }
+    }
+}
+
+template <int Q, int EPI, int PHASE>
+__device__ __forceinline__ void wave_dispatch(int w, bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat,
+                                              const bf16_t* rowop, int64_t bt, DualLds<Q>& L, const HeadCtx& cx, int lane) {
+    switch (w) {
+        case 0: wave_phase<Q, EPI, PHASE, 0>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
+        case 1: wave_phase<Q, EPI, PHASE, 1>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
+        case 2: wave_phase<Q, EPI, PHASE, 2>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
+        default: wave_phase<Q, EPI, PHASE, 3>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
+    }
+}
+
+template <int Q, int EPI>
+__global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
+    constexpr bool REV = EPI == 2;
+    __shared__ __attribute__((aligned(16))) DualLds<Q> L;
+    // workgroups that share a (chunk, group) -- hence G, C, B -- get consecutive logical ids and, when the
+    // grid divides evenly, land on the same XCD (hardware deals workgroup ids round-robin over 8 XCDs)
+    int z = blockIdx.x;
+    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    const int ns = sp.dual_split, slice = z % ns;
+    z /= ns;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
+
+    const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
+    const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
+    const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
+                          ((int64_t)c * Q * sp.G + g) * N_;
+    bf16x8 gf[GF_MAX], rf[2 * RF_N];
+    HeadCtx cx;
+    wave_dispatch<Q, EPI, 0>(w, gf, rf, Mat, rowop, bt, L, cx, lane);
+    Pre<Q> pr;
+    load_pre<Q, REV>(pr, sp, b, c, h0, tid);
+    for (int hh = 0; hh < hps; ++hh) {
+        const int h = h0 + hh;
+        __syncthreads();  // every wave is done with the previous head's tiles
+        store_pre<Q, REV>(pr, L, tid);
+        __syncthreads();
+        if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tid);
+        const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+        const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
+        cx.xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
+        cx.dyg = EPI == 0 ? nullptr : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
+        cx.outp = EPI == 0 ? (bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow
+                           : (EPI == 2 ? (bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow : nullptr);
+        cx.gterm = sp.gterm + cbase;
+        cx.fterm = sp.fterm + cbase;
+        cx.dDrow = sp.dDrow + cbase;
+        cx.xt = xt;
+        cx.Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
+        wave_dispatch<Q, EPI, 1>(w, gf, rf, Mat, rowop, bt, L, cx, lane);
+    }
+}
+
+// Number of head slices per (batch, chunk, group): the smallest divisor of the heads per group that
+// gives every compute unit a workgroup, so that the per-workgroup operands are shared by as many
+// heads as possible.
+int pick_split(const SegParams& sp, int target_wgs) {
+    const int base = sp.Bt * sp.nc * sp.G;
+    for (int ns = 1; ns <= sp.hpg; ++ns)
+        if (sp.hpg % ns == 0 && (int64_t)base * ns >= target_wgs) return ns;
+    return sp.hpg;
+}
+
+template <int Q, int EPI>
+hipError_t launch_dual_q(const SegParams& sp0, int kid, hipStream_t st) {
+    SegParams sp = sp0;
+    sp.dual_split = pick_split(sp, 256);
+    SSDK_LAUNCH(kid, st, (mk_dual<Q, EPI>), dim3(sp.Bt * sp.nc * sp.G * sp.dual_split), dim3(DualCfg<Q>::NTHR), sp);
+    return hipSuccess;
+}
+
+template <int EPI>
+hipError_t launch_dual_epi(const SegParams& sp, int kid, hipStream_t st) {
+    switch (sp.Q) {
+        case 64: return launch_dual_q<64, EPI>(sp, kid, st);
+        case 128: return launch_dual_q<128, EPI>(sp, kid, st);
+        case 256: return launch_dual_q<256, EPI>(sp, kid, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace
+
+hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st) {
+    switch (epi) {
+        case 0: return launch_dual_epi<0>(sp, K_MFMA_CHUNK_OUT, st);
+        case 1: return launch_dual_epi<1>(sp, K_MFMA_BWD_MAIN, st);
+        case 2: return launch_dual_epi<2>(sp, K_MFMA_BWD_MAIN, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ssdk

@@ -19,63 +19,12 @@
 // Operands whose contraction index is the token index live token-major in memory; they are staged
 // in LDS as [token][channel] and read with the LDS transpose load (ds_read_b64_tr_b16), which hands
 // each lane four consecutive tokens of one channel -- the layout an MFMA operand needs.
-#include "ssd_internal.h"
+#include "mfma_common.h"
 
 namespace ssdk {
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-
-constexpr int P_ = 64, N_ = 128, BLK = 64;
-constexpr int XPITCH = 144;  // bytes per LDS row of a [token][64] bf16 tile (128 + 16 pad)
-constexpr int BPITCH = 272;  // bytes per LDS row of a [token][128] bf16 tile (256 + 16 pad)
-constexpr int NTH = 256;
-constexpr float LOG2E = 1.4426950408889634f;
-
-__device__ __forceinline__ f32x16 mfma(bf16x8 a, bf16x8 b, f32x16 c) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b, c, 0, 0, 0);
-}
-
-// Row (of the 32 x 32 result tile) held in accumulator register r of this lane; the column is lane % 32.
-__device__ __forceinline__ int acc_row(int r, int lane) { return (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3); }
-
-// MFMA operand out of a row-major matrix (global memory): row = row0 + lane % 32, eight consecutive k
-// starting at k0 + 8 * (lane / 32).
-__device__ __forceinline__ bf16x8 frag_rows(const bf16_t* base, int64_t row_stride, int row0, int k0, int lane) {
-    return *(const bf16x8*)(base + (int64_t)(row0 + (lane & 31)) * row_stride + k0 + 8 * (lane >> 5));
-}
-
-// MFMA operand out of an LDS tile stored [k][m] (pitch in bytes): rows m0 .. m0+31 of the transpose,
-// k0 .. k0+15.  Within a group of 16 lanes the transpose load returns to lane r the four k-rows
-// addressed by lanes {r/4, r/4+4, r/4+8, r/4+12}... arranged so that, with the addresses below, lane r
-// ends up with T[kb .. kb+3][mb + r].
-__device__ __forceinline__ bf16x8 frag_tr(const char* tile, int pitch, int k0, int m0, int lane) {
-    const int g = lane >> 4, r = lane & 15;
-    const char* p = tile + (k0 + 8 * (g >> 1) + (r >> 2)) * pitch + (m0 + 16 * (g & 1) + 4 * (r & 3)) * 2;
-    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)p);
-    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4*)(p + 4 * pitch));
-    const s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-    return __builtin_bit_cast(bf16x8, v);
-}
-
-__device__ __forceinline__ bf16x8 scale8(bf16x8 v, float s) {
-    bf16x8 o;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)v[e] * s);
-    return o;
-}
-
-__device__ __forceinline__ f32x16 zero16() {
-    f32x16 z;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) z[r] = 0.f;
-    return z;
-}
+using namespace mf;
 
 // ---------------------------------------------------------------------------------------------
 // Decay preparation: cum (chunk-local inclusive cumsum of dt*A), dt in fp32, ein, eout.
@@ -250,265 +199,6 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
     }
     *(float4*)(sp.dcarry + ce) = g;
     if (sp.dinit_out) *(float4*)(sp.dinit_out + ce) = g;
-}
-
-// ---------------------------------------------------------------------------------------------
-// The two "dual form" passes over one (chunk, head), computed transposed so that a lane owns a token:
-//   EPI 0 (forward output):  yhat^T[p][i] = sum_{j<=i} G[i][j] decay(i,j) dt_j x_j[p] + exp(cum_i) (Hprev C_i)[p];
-//                            y = yhat + D x  (+ x under the residual flag)
-//   EPI 1 (backward, part 1): the same yhat, reduced to gy_i = dY_i . yhat_i
-//   EPI 2 (backward, part 2): u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
-//                            dx = dt u + D dY (+ dY), and the per-token scalars for ddt / dA / dD
-// Work split: the chunk has Q/32 token tiles; with Q = 256 wave w owns tiles w and 7-w (equal causal
-// work).  The tile index is a compile-time constant inside tile_load / tile_compute so that every
-// fragment of the score matrix and of C (or B) a wave needs is fetched into registers before the
-// LDS staging, in one round of memory latency.
-constexpr int GF_MAX = 18, RF_MAX = 16;
-
-template <int Q, int EPI, int T>
-struct DualTile {
-    static constexpr bool REV = EPI == 2;
-    static constexpr int NB = Q / BLK, I = T / 2, TOK0 = 32 * T, ODD = T & 1;
-    static constexpr int KS0 = REV ? 2 * T : 0;                         // first 16-token step of the contraction
-    static constexpr int NFR = REV ? 4 * NB - 2 * T : 2 * (T + 1);      // number of 16-token steps
-};
-
-template <int Q, int EPI, int T, int GOFF, int ROFF>
-__device__ __forceinline__ void tile_load(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
-                                          const bf16_t* rowop, int64_t bt, int lane) {
-    typedef DualTile<Q, EPI, T> TI;
-#pragma unroll
-    for (int f = 0; f < TI::NFR; ++f) gf[GOFF + f] = frag_rows(Mat, Q, TI::TOK0, 16 * (TI::KS0 + f), lane);
-#pragma unroll
-    for (int ks = 0; ks < N_ / 16; ++ks) rf[ROFF + ks] = frag_rows(rowop, bt, TI::TOK0, 16 * ks, lane);
-}
-
-struct DualCtx {
-    const char* raw;
-    const char* scl;
-    const float* cum2;
-    const float* fac;
-    const float* sfac;
-    const bf16_t* Sb;
-    const bf16_t* xg;
-    const bf16_t* dyg;
-    bf16_t* outp;  // y (EPI 0) or dx (EPI 2), already offset to the chunk and head
-    float* gterm;
-    float* fterm;
-    float* dDrow;
-    const float* dtf;
-    int64_t xt;
-    float Dh;
-};
-
-template <int Q, int EPI, int T, int GOFF, int ROFF>
-__device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const bf16x8 (&rf)[RF_MAX], const DualCtx& cx,
-                                             int lane) {
-    typedef DualTile<Q, EPI, T> TI;
-    constexpr bool REV = TI::REV;
-    constexpr int NB = TI::NB, I = TI::I;
-    const int tok = TI::TOK0 + (lane & 31);
-    const float lane_c2 = cx.cum2[tok], lane_fac = cx.fac[tok];
-    f32x16 acc0 = zero16(), acc1 = zero16();
-    // term through the chunk's entering state (forward) / leaving adjoint (reverse)
-#pragma unroll
-    for (int ks = 0; ks < N_ / 16; ++ks) {
-        acc0 = mfma(frag_rows(cx.Sb, N_, 0, 16 * ks, lane), rf[ROFF + ks], acc0);
-        acc1 = mfma(frag_rows(cx.Sb, N_, 32, 16 * ks, lane), rf[ROFF + ks], acc1);
-    }
-    // off-diagonal blocks, Horner in the block decays
-#pragma unroll
-    for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
-        const int K = REV ? NB - 1 - n : n;
-        const float sK = cx.sfac[K];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            acc0[r] *= sK;
-            acc1[r] *= sK;
-        }
-#pragma unroll
-        for (int ks = 0; ks < BLK / 16; ++ks) {
-            const int k0 = K * BLK + 16 * ks;
-            const bf16x8 fb = gf[GOFF + 4 * K + ks - TI::KS0];
-            acc0 = mfma(frag_tr(cx.scl, XPITCH, k0, 0, lane), fb, acc0);
-            acc1 = mfma(frag_tr(cx.scl, XPITCH, k0, 32, lane), fb, acc1);
-        }
-    }
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        acc0[r] *= lane_fac;
-        acc1[r] *= lane_fac;
-    }
-    // diagonal block: the mask and the decay are evaluated per element
-#pragma unroll
-    for (int ks = (REV && TI::ODD) ? 2 : 0; ks < ((!REV && !TI::ODD) ? 2 : 4); ++ks) {
-        const int k0 = I * BLK + 16 * ks;
-        const bf16x8 gv = gf[GOFF + 4 * I + ks - TI::KS0];
-        const int kk0 = k0 + 8 * (lane >> 5);
-        bf16x8 fb;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int kk = kk0 + e;
-            const float diff = REV ? cx.cum2[kk] - lane_c2 : lane_c2 - cx.cum2[kk];
-            const bool ok = REV ? kk >= tok : kk <= tok;
-            fb[e] = (__bf16)(ok ? (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f)) : 0.f);
-        }
-        acc0 = mfma(frag_tr(cx.raw, XPITCH, k0, 0, lane), fb, acc0);
-        acc1 = mfma(frag_tr(cx.raw, XPITCH, k0, 32, lane), fb, acc1);
-    }
-    // epilogue: this lane owns token `tok` and, per register group q, four consecutive channels
-    float s_a = 0.f, s_b = 0.f;
-    const float dtok = REV ? cx.dtf[tok] : 0.f;
-#pragma unroll
-    for (int pt = 0; pt < 2; ++pt) {
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
-            const int64_t o = (int64_t)tok * cx.xt + p4;
-            const bf16x4 xv = *(const bf16x4*)(cx.xg + o);
-            if (EPI == 0) {
-                bf16x4 yv;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) yv[e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)xv[e]);
-                *(bf16x4*)(cx.outp + o) = yv;
-            } else {
-                const bf16x4 dv = *(const bf16x4*)(cx.dyg + o);
-                if (EPI == 1) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) s_a += (float)dv[e] * (pt ? acc1 : acc0)[4 * q + e];
-                } else {
-                    bf16x4 ov;
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float u = (pt ? acc1 : acc0)[4 * q + e];
-                        ov[e] = (__bf16)(dtok * u + cx.Dh * (float)dv[e]);
-                        s_a += (float)xv[e] * u;
-                        s_b += (float)dv[e] * (float)xv[e];
-                    }
-                    *(bf16x4*)(cx.outp + o) = ov;
-                }
-            }
-        }
-    }
-    if (EPI != 0) {
-        s_a += __shfl_xor(s_a, 32, 64);
-        s_b += __shfl_xor(s_b, 32, 64);
-        if (lane < 32) {
-            if (EPI == 1) {
-                cx.gterm[tok] = s_a;
-            } else {
-                cx.gterm[tok] = cx.gterm[tok] - dtok * s_a;
-                cx.fterm[tok] = s_a;
-                cx.dDrow[tok] = s_b;
-            }
-        }
-    }
-}
-
-// Dispatch on the wave index: PHASE 0 issues the hoisted loads, PHASE 1 computes.
-template <int Q, int EPI, int PHASE, int TA, int TB>
-__device__ __forceinline__ void wave_tiles(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
-                                           const bf16_t* rowop, int64_t bt, const DualCtx& cx, int lane) {
-    constexpr int NT = Q / 32;
-    if constexpr (TA < NT) {
-        if constexpr (PHASE == 0) tile_load<Q, EPI, TA, 0, 0>(gf, rf, Mat, rowop, bt, lane);
-        else tile_compute<Q, EPI, TA, 0, 0>(gf, rf, cx, lane);
-    }
-    if constexpr (TB >= 0 && TB < NT && NT == 8) {
-        constexpr int GO = DualTile<Q, EPI, (TA < NT ? TA : 0)>::NFR;
-        if constexpr (PHASE == 0) tile_load<Q, EPI, TB, GO, 8>(gf, rf, Mat, rowop, bt, lane);
-        else tile_compute<Q, EPI, TB, GO, 8>(gf, rf, cx, lane);
-    }
-}
-
-template <int Q, int EPI, int PHASE>
-__device__ __forceinline__ void wave_dispatch(int w, bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[RF_MAX], const bf16_t* Mat,
-                                              const bf16_t* rowop, int64_t bt, const DualCtx& cx, int lane) {
-    switch (w) {
-        case 0: wave_tiles<Q, EPI, PHASE, 0, 7>(gf, rf, Mat, rowop, bt, cx, lane); break;
-        case 1: wave_tiles<Q, EPI, PHASE, 1, 6>(gf, rf, Mat, rowop, bt, cx, lane); break;
-        case 2: wave_tiles<Q, EPI, PHASE, 2, 5>(gf, rf, Mat, rowop, bt, cx, lane); break;
-        default: wave_tiles<Q, EPI, PHASE, 3, 4>(gf, rf, Mat, rowop, bt, cx, lane); break;
-    }
-}
-
-template <int Q, int EPI>
-__global__ __launch_bounds__(NTH, 2) void mk_dual(SegParams sp) {
-    constexpr int NB = Q / BLK;
-    constexpr bool REV = EPI == 2;
-    __shared__ __attribute__((aligned(16))) char raw[Q * XPITCH];     // dt*x (forward) or dY (reverse)
-    __shared__ __attribute__((aligned(16))) char scl[Q * XPITCH];     // eout*dt*x      or ein*dY
-    __shared__ float cum2[Q];   // cum * log2(e)
-    __shared__ float fac[Q];    // ein (forward) or eout (reverse): applied per output token
-    __shared__ float sfac[NB];  // total decay of each 64-token block
-    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
-    const int g = h / sp.hpg, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-    const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
-    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
-    const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
-    const bf16_t* dyg = EPI == 0 ? nullptr : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
-    // operands read straight from global memory: issue those loads first
-    const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
-    const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
-    const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
-                          ((int64_t)c * Q * sp.G + g) * N_;
-    DualCtx cx;
-    cx.raw = raw;
-    cx.scl = scl;
-    cx.cum2 = cum2;
-    cx.fac = fac;
-    cx.sfac = sfac;
-    cx.Sb = REV ? sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_)
-                : sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
-    cx.xg = xg;
-    cx.dyg = dyg;
-    cx.outp = EPI == 0 ? (bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow : (EPI == 2 ? (bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow : nullptr);
-    cx.gterm = sp.gterm + cbase;
-    cx.fterm = sp.fterm + cbase;
-    cx.dDrow = sp.dDrow + cbase;
-    cx.dtf = sp.dtf + cbase;
-    cx.xt = xt;
-    cx.Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
-    bf16x8 gf[GF_MAX], rf[RF_MAX];
-    wave_dispatch<Q, EPI, 0>(w, gf, rf, Mat, rowop, bt, cx, lane);
-
-    // stage the per-token vectors
-    for (int i = tid; i < Q; i += NTH) {
-        const float cv = sp.cum[cbase + i];
-        cum2[i] = cv * LOG2E;
-        fac[i] = REV ? sp.eout[cbase + i] : sp.ein[cbase + i];
-        if (i < NB) {
-            const float e1 = sp.cum[cbase + i * BLK + BLK - 1], e0 = i > 0 ? sp.cum[cbase + i * BLK - 1] : 0.f;
-            sfac[i] = __expf(e1 - e0);
-        }
-    }
-    // stage the token-major operand twice: plain and pre-scaled
-    {
-        const bf16_t* src = REV ? dyg : xg;
-        bf16x8 in[Q * 8 / NTH];
-        float s1[Q * 8 / NTH], s2[Q * 8 / NTH];
-#pragma unroll
-        for (int k = 0; k < Q * 8 / NTH; ++k) {
-            const int v = tid + NTH * k, row = v >> 3, seg = v & 7;
-            in[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-            s1[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row];
-            s2[k] = REV ? 0.f : sp.eout[cbase + row];
-        }
-#pragma unroll
-        for (int k = 0; k < Q * 8 / NTH; ++k) {
-            const int v = tid + NTH * k, row = v >> 3, seg = v & 7;
-            if (REV) {
-                *(bf16x8*)(raw + row * XPITCH + seg * 16) = in[k];
-                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in[k], s1[k]);
-            } else {
-                *(bf16x8*)(raw + row * XPITCH + seg * 16) = scale8(in[k], s1[k]);
-                *(bf16x8*)(scl + row * XPITCH + seg * 16) = scale8(in[k], s1[k] * s2[k]);
-            }
-        }
-    }
-    __syncthreads();
-    wave_dispatch<Q, EPI, 1>(w, gf, rf, Mat, rowop, bt, cx, lane);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -726,7 +416,10 @@ hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
     SSDK_LAUNCH(K_MFMA_CHUNK_STATE, st, (mk_chunk_outer<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
     SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
     SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
-    if (need_y) SSDK_LAUNCH(K_MFMA_CHUNK_OUT, st, (mk_dual<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    if (need_y) {
+        hipError_t e = mfma_launch_dual(sp, 0, st);
+        if (e != hipSuccess) return e;
+    }
     return hipSuccess;
 }
 
@@ -736,9 +429,11 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     sp.nslice = P_ * N_ / 4 / NTH;  // partial sums written by mk_scan_bwd
     SSDK_LAUNCH(K_MFMA_DSTATE, st, (mk_chunk_outer<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
     SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
-    SSDK_LAUNCH(K_MFMA_BWD_MAIN, st, (mk_dual<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
-    SSDK_LAUNCH(K_MFMA_BWD_MAIN, st, (mk_dual<Q, 2>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
-    hipError_t e = generic_backward_scalars(sp, st);
+    hipError_t e = mfma_launch_dual(sp, 1, st);
+    if (e != hipSuccess) return e;
+    e = mfma_launch_dual(sp, 2, st);
+    if (e != hipSuccess) return e;
+    e = generic_backward_scalars(sp, st);
     if (e != hipSuccess) return e;
     constexpr int NB = Q / BLK;
     SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(sp.Bt * sp.nc * sp.G * sp.dg_split, NB * (NB + 1) / 2), dim3(NTH), sp);

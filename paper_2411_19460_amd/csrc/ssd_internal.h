@@ -78,6 +78,7 @@ struct SegParams {
     bf16_t* states_bf;   // [Bt][nc][H][P][N] bf16 copy of the entering states
     bf16_t* dstates_bf;  // [Bt][nc][H][P][N] bf16 copy of the leaving-state adjoints
     int dg_split;        // number of head slices whose dG / dB / dC partial sums are kept apart
+    int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
     float* dbc_part;     // [Bt][nc][G][dg_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
@@ -148,5 +149,7 @@ hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st);
 bool mfma_path_supported(const ssd_shape_t& s);
 hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st);
 hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
+// One dual-form pass over a segment: epi 0 = forward output, 1 and 2 = the two backward passes.
+hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st);
 
 }  // namespace ssdk
