@@ -191,7 +191,8 @@ int magc_plan(const magc_model_t* model /*host*/, magc_plan_t* out /*host*/);
  * Per-kernel timing for benchmarks (diagnostics; not part of the method).  While enabled, every
  * kernel launch of this library is bracketed by two HIP events recorded on the launch stream.
  * Not thread-safe; leave it off in production.
- *   ssd_prof_enable(on)      : drops earlier records, then switches recording on (1) or off (0)
+ *   ssd_prof_enable(on)      : drops earlier records, then switches recording off (0), on for every
+ *                              kernel (1), or on for kernel id `on - 2` only (on >= 2)
  *   ssd_prof_read(id, ...)   : waits for the recorded events of kernel `id`, returns the sum of
  *                              their durations in milliseconds and the number of launches (host pointers)
  *   ssd_prof_kernel_name(id) : static name of kernel `id`, NULL once id is past the last kernel

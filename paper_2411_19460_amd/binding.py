@@ -257,8 +257,21 @@ def magc_plan(n_layers, seqlen, c_lckpt, c_sckpt, c_grid, c_state, s_multiple=25
                 "m_state": p.m_state, "m_total": p.m_total, "regime": p.regime, "fits": bool(p.fits)}
 
 
-def ssd_prof_enable(on: bool) -> None:
-    rc = lib().ssd_prof_enable(1 if on else 0)
+def ssd_prof_kernel_id(name: str) -> int:
+    kid = 0
+    while True:
+        n = lib().ssd_prof_kernel_name(kid)
+        if n is None:
+            raise KeyError(name)
+        if n.decode() == name:
+            return kid
+        kid += 1
+
+
+def ssd_prof_enable(on, only: Optional[str] = None) -> None:
+    """on: record every kernel launch; only=name: record launches of that kernel alone."""
+    mode = (2 + ssd_prof_kernel_id(only)) if (on and only is not None) else (1 if on else 0)
+    rc = lib().ssd_prof_enable(mode)
     if rc != 0:
         raise SSDError(rc, "ssd_prof_enable")
 

@@ -13,6 +13,7 @@ struct Rec {
 };
 
 bool g_on = false;
+int g_only = -1;  // >= 0: record this kernel id only
 std::vector<Rec> g_recs;
 std::vector<hipEvent_t> g_pool;
 const char* const g_names[K_COUNT] = {
@@ -34,15 +35,15 @@ hipEvent_t take_event() {
 }  // namespace
 
 void prof_begin(int kid, hipStream_t st) {
-    if (!g_on) return;
+    if (!g_on || (g_only >= 0 && kid != g_only)) return;
     Rec r{kid, take_event(), take_event()};
     if (!r.a || !r.b) return;
     (void)hipEventRecord(r.a, st);
     g_recs.push_back(r);
 }
 
-void prof_end(int, hipStream_t st) {
-    if (!g_on || g_recs.empty()) return;
+void prof_end(int kid, hipStream_t st) {
+    if (!g_on || g_recs.empty() || (g_only >= 0 && kid != g_only)) return;
     (void)hipEventRecord(g_recs.back().b, st);
 }
 
@@ -58,6 +59,8 @@ extern "C" int ssd_prof_enable(int32_t on) {
     }
     g_recs.clear();
     g_on = on != 0;
+    g_only = on >= 2 ? on - 2 : -1;
+    if (g_only >= K_COUNT) return SSD_ERR_ARG;
     return SSD_OK;
 }
 
