@@ -18,8 +18,11 @@
  *
  * General conventions
  *   - Every data pointer is a DEVICE pointer unless its comment says "host".  The caller owns
- *     all buffers; the library never allocates, frees or synchronises.  All work is enqueued on
- *     `hip_stream` (a hipStream_t passed as void*; NULL = the default stream).
+ *     all buffers; the library never allocates or frees device memory and never blocks the host.
+ *     All work is ordered after what is already in `hip_stream` (a hipStream_t passed as void*;
+ *     NULL = the default stream) and before anything enqueued there after the call returns; with
+ *     more than one segment part of it runs on a library-owned stream of default priority, forked
+ *     from and joined back into `hip_stream` with events (created on the first such call).
  *   - Tensors are dense row-major with the index order written in brackets; the batch stride
  *     may be overridden through ssd_shape_t (elements, 0 = dense) so that a token range of a
  *     longer sequence can be passed as a pointer offset.
@@ -80,7 +83,10 @@ enum {
 
 /* Bytes of scratch the call needs for this shape (device memory, 256-byte aligned, contents
  * undefined before and after).  It scales with `segment`, not with `seqlen`: this is the
- * per-segment recomputation store (the M_state term of App. C).  Returns 0 for an invalid shape. */
+ * per-segment recomputation store (the M_state term of App. C) -- two of them when there is more
+ * than one segment, because two segments are kept in flight -- plus, for the backward pass, eight
+ * bytes per (chunk, head) of the whole sequence for the partial sums of dA and dD.
+ * Returns 0 for an invalid shape. */
 size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward);
 
 /*

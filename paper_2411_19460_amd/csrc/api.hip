@@ -8,6 +8,12 @@ namespace ssdk {
 
 inline size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
 
+int pick_split(int heads_per_group, int64_t base, int target) {
+    for (int ns = 1; ns <= heads_per_group; ++ns)
+        if (heads_per_group % ns == 0 && base * ns >= target) return ns;
+    return heads_per_group;
+}
+
 // Returns SSD_OK and fills d, or the validation error.
 int check_shape(const ssd_shape_t* sh, Dims* d) {
     if (!sh) return SSD_ERR_NULL;
@@ -64,12 +70,17 @@ WsLayout ws_layout(const Dims& d, bool bwd) {
     w.ein = take(tok);
     w.eout = take(tok);
     w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
-    w.dg_split = (d.hpg >= 16 && d.hpg % 4 == 0) ? 4 : 1;
+    const int64_t groups = d.Bt * (int64_t)d.nc * d.G;
+    w.dg_split = pick_split(d.hpg, groups, 256);
+    w.part_split = pick_split(d.hpg, groups * 2, 256);
     if (bwd) {
         w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
         w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
-        w.dG = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4 * 2 * w.dg_split);  // [i][j] and [j][i] per slice
-        w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.dg_split * 2 * d.Q * d.N * 4);
+        {   // fp32 head sum (generic kernels) or one bf16 partial sum per head slice (MFMA kernels)
+            const size_t per = (size_t)d.Q * d.Q * 2 * w.dg_split;
+            w.dG = take((size_t)d.Bt * d.nc * d.G * (per > (size_t)d.Q * d.Q * 4 ? per : (size_t)d.Q * d.Q * 4));
+        }
+        w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.part_split * 2 * d.Q * d.N * 4);
         w.gterm = take(tok);
         w.fterm = take(tok);
         w.dDrow = take(tok);
@@ -93,6 +104,7 @@ void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd)
     sp.eout = (float*)(base + w.eout);
     sp.states_bf = (bf16_t*)(base + w.states_bf);
     sp.dg_split = w.dg_split;
+    sp.part_split = w.part_split;
     if (bwd) {
         sp.dstates_bf = (bf16_t*)(base + w.dstates_bf);
         sp.dbc_part = (float*)(base + w.dbc_part);
@@ -122,6 +134,7 @@ void base_params(SegParams& sp, const Dims& d, uint32_t flags) {
     sp.dts_b = d.dts_b;
     sp.bcs_b = d.bcs_b;
     sp.flags = flags;
+    sp.nc_total = d.nc;
 }
 
 static inline const void* off(const void* p, int64_t elems, size_t esz) { return p ? (const char*)p + elems * (int64_t)esz : nullptr; }
@@ -161,6 +174,37 @@ static void wire_states(SegParams& sp, const Dims& d, int64_t k, const float* in
     }
 }
 
+// ---- two segments in flight ------------------------------------------------------------------
+// Consecutive segments depend on each other only through the state scan.  With more than one
+// segment, even segments run on the caller's stream and odd segments on an internal stream (default
+// priority), each with its own per-segment scratch; events order the scans.  This overlaps one
+// segment's launch gaps, tails and bandwidth-bound kernels with the other's matrix work.
+struct Pipe {
+    hipStream_t aux = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr, scan[2] = {nullptr, nullptr};
+    bool ok = false;
+};
+
+static Pipe* pipe_for_current_device() {
+    static Pipe pipes[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    Pipe& p = pipes[dev];
+    if (!p.ok) {
+        if (hipStreamCreateWithFlags(&p.aux, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        hipEvent_t* ev[4] = {&p.fork, &p.join, &p.scan[0], &p.scan[1]};
+        for (hipEvent_t* e : ev)
+            if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        p.ok = true;
+    }
+    return &p;
+}
+
+// Bytes of the arrays shared by both scratch blocks: the dA / dD partial sums of every chunk.
+static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d.nseg * d.nc * d.H * 4); }
+
+static bool pipelined(const Dims& d, bool mfma) { return mfma && d.nseg > 1; }
+
 }  // namespace ssdk
 
 using namespace ssdk;
@@ -169,7 +213,8 @@ extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backw
     Dims d;
     if (check_shape(shape, &d) != SSD_OK) return 0;
     // never 0 for a valid shape, so that 0 unambiguously means "invalid"
-    const size_t t = ws_layout(d, is_backward != 0).total;
+    const size_t block = align_up(ws_layout(d, is_backward != 0).total);
+    const size_t t = (pipelined(d, use_mfma(*shape, 0)) ? 2 : 1) * block + (is_backward ? shared_bytes(d) : 0);
     return t ? t : 256;
 }
 
@@ -194,15 +239,25 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const WsLayout w = ws_layout(d, false);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
-
     const bool mfma = use_mfma(*shape, flags);
-    SegParams sp;
-    base_params(sp, d, flags);
-    bind_workspace(sp, w, workspace, false);
-    sp.A = A;
-    sp.D = D;
+    const bool two = pipelined(d, mfma);
+    const size_t block = align_up(w.total);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (two ? 2 : 1) * block) return SSD_ERR_WORKSPACE;
+    Pipe* pp = two ? pipe_for_current_device() : nullptr;
+    if (two && !pp) return SSD_ERR_LAUNCH;
+
+    SegParams sps[2];
+    for (int i = 0; i < (two ? 2 : 1); ++i) {
+        base_params(sps[i], d, flags);
+        bind_workspace(sps[i], w, (char*)workspace + i * block, false);
+        sps[i].A = A;
+        sps[i].D = D;
+    }
+    if (two && (hipEventRecord(pp->fork, st) != hipSuccess || hipStreamWaitEvent(pp->aux, pp->fork, 0) != hipSuccess))
+        return SSD_ERR_LAUNCH;
     for (int64_t k = 0; k < d.nseg; ++k) {
+        SegParams& sp = sps[two ? (k & 1) : 0];
+        hipStream_t sk = (two && (k & 1)) ? pp->aux : st;
         const int64_t t0 = k * d.s;
         sp.x = off(x, t0 * d.H * d.P, d.esz);
         sp.y = off(y, t0 * d.H * d.P, d.esz);
@@ -210,9 +265,13 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.Bm = off(B, t0 * d.G * d.N, d.esz);
         sp.Cm = off(C, t0 * d.G * d.N, d.esz);
         wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
-        hipError_t e = mfma ? mfma_forward_segment(sp, true, st) : generic_forward_segment(sp, d.bf16, true, st);
+        sp.ev_wait = (two && k > 0) ? pp->scan[(k - 1) & 1] : nullptr;
+        sp.ev_record = (two && k + 1 < d.nseg) ? pp->scan[k & 1] : nullptr;
+        hipError_t e = mfma ? mfma_forward_segment(sp, true, sk) : generic_forward_segment(sp, d.bf16, true, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
     }
+    if (two && (hipEventRecord(pp->join, pp->aux) != hipSuccess || hipStreamWaitEvent(st, pp->join, 0) != hipSuccess))
+        return SSD_ERR_LAUNCH;
     return SSD_OK;
 }
 
@@ -243,20 +302,39 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (dx == dy) return SSD_ERR_ARG;
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const WsLayout w = ws_layout(d, true);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
-
     const bool mfma = use_mfma(*shape, flags);
-    SegParams sp;
-    base_params(sp, d, flags);
-    bind_workspace(sp, w, workspace, true);
-    sp.A = A;
-    sp.D = D;
-    sp.dA = dA;
-    sp.dD = dD;
-    hipError_t e = dfinal_state ? launch_copy_f32(sp.dcarry, dfinal_state, (size_t)d.Bt * HPN, st)
-                                : launch_fill_zero(sp.dcarry, (size_t)d.Bt * HPN, st);
+    const bool two = pipelined(d, mfma);
+    const size_t block = align_up(w.total);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (two ? 2 : 1) * block + shared_bytes(d))
+        return SSD_ERR_WORKSPACE;
+    Pipe* pp = two ? pipe_for_current_device() : nullptr;
+    if (two && !pp) return SSD_ERR_LAUNCH;
+
+    // shared by both scratch blocks: the carried state adjoint and the dA / dD partial sums of every chunk
+    float* part_all = (float*)((char*)workspace + (two ? 2 : 1) * block);
+    SegParams sps[2];
+    for (int i = 0; i < (two ? 2 : 1); ++i) {
+        SegParams& sp = sps[i];
+        base_params(sp, d, flags);
+        bind_workspace(sp, w, (char*)workspace + i * block, true);
+        sp.A = A;
+        sp.D = D;
+        sp.dA = dA;
+        sp.dD = dD;
+        sp.dcarry = sps[0].dcarry;
+        sp.dA_part = part_all;
+        sp.dD_part = (float*)((char*)part_all + shared_bytes(d) / 2);
+        sp.nc_total = (int)(d.nseg * d.nc);
+        sp.defer_param = 1;
+    }
+    hipError_t e = dfinal_state ? launch_copy_f32(sps[0].dcarry, dfinal_state, (size_t)d.Bt * HPN, st)
+                                : launch_fill_zero(sps[0].dcarry, (size_t)d.Bt * HPN, st);
     if (e != hipSuccess) return SSD_ERR_LAUNCH;
-    for (int64_t k = d.nseg - 1; k >= 0; --k) {
+    if (two && (hipEventRecord(pp->fork, st) != hipSuccess || hipStreamWaitEvent(pp->aux, pp->fork, 0) != hipSuccess))
+        return SSD_ERR_LAUNCH;
+    for (int64_t k = d.nseg - 1, it = 0; k >= 0; --k, ++it) {
+        SegParams& sp = sps[two ? (it & 1) : 0];
+        hipStream_t sk = (two && (it & 1)) ? pp->aux : st;
         const int64_t t0 = k * d.s;
         sp.x = off(x, t0 * d.H * d.P, d.esz);
         sp.dy = off(dy, t0 * d.H * d.P, d.esz);
@@ -267,15 +345,22 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.Cm = off(C, t0 * d.G * d.N, d.esz);
         sp.dB = off(dB, t0 * d.G * d.N, d.esz);
         sp.dC = off(dC, t0 * d.G * d.N, d.esz);
+        sp.chunk0 = (int)(k * d.nc);
         // restore: per-chunk entering states of this segment from its checkpoint
         wire_states(sp, d, k, init_state, boundary_states, nullptr, nullptr);
-        e = mfma ? mfma_forward_segment(sp, false, st) : generic_forward_segment(sp, d.bf16, false, st);
+        sp.ev_wait = sp.ev_record = nullptr;
+        e = mfma ? mfma_forward_segment(sp, false, sk) : generic_forward_segment(sp, d.bf16, false, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
         sp.dinit_out = (k == 0) ? dinit_state : nullptr;
-        sp.accumulate = (k == d.nseg - 1) ? ((flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0) : 1;
-        e = mfma ? mfma_backward_segment(sp, st) : generic_backward_segment(sp, d.bf16, st);
+        sp.ev_wait = (two && it > 0) ? pp->scan[(it - 1) & 1] : nullptr;
+        sp.ev_record = (two && k > 0) ? pp->scan[it & 1] : nullptr;
+        e = mfma ? mfma_backward_segment(sp, sk) : generic_backward_segment(sp, d.bf16, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
     }
+    if (two && (hipEventRecord(pp->join, pp->aux) != hipSuccess || hipStreamWaitEvent(st, pp->join, 0) != hipSuccess))
+        return SSD_ERR_LAUNCH;
+    sps[0].accumulate = (flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0;
+    if (launch_param_reduce(sps[0], st) != hipSuccess) return SSD_ERR_LAUNCH;
     return SSD_OK;
 }
 

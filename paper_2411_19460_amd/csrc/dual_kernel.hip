@@ -354,20 +354,12 @@ __global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
     }
 }
 
-// Number of head slices per (batch, chunk, group): the smallest divisor of the heads per group that
-// gives every compute unit a workgroup, so that the per-workgroup operands are shared by as many
-// heads as possible.
-int pick_split(const SegParams& sp, int target_wgs) {
-    const int base = sp.Bt * sp.nc * sp.G;
-    for (int ns = 1; ns <= sp.hpg; ++ns)
-        if (sp.hpg % ns == 0 && (int64_t)base * ns >= target_wgs) return ns;
-    return sp.hpg;
-}
-
 template <int Q, int EPI>
 hipError_t launch_dual_q(const SegParams& sp0, int kid, hipStream_t st) {
     SegParams sp = sp0;
-    sp.dual_split = pick_split(sp, 256);
+    // as few head slices as still give every compute unit a workgroup: the persistent operands are then
+    // shared by as many heads as possible
+    sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G, 256);
     SSDK_LAUNCH(kid, st, (mk_dual<Q, EPI>), dim3(sp.Bt * sp.nc * sp.G * sp.dual_split), dim3(DualCfg<Q>::NTHR), sp);
     return hipSuccess;
 }

@@ -387,25 +387,38 @@ __global__ void k_ddt_finalize(SegParams sp) {
         __syncthreads();
     }
     if (i == 0) {
-        sp.dA_part[((int64_t)b * sp.nc + c) * sp.H + h] = s[0];
-        sp.dD_part[((int64_t)b * sp.nc + c) * sp.H + h] = s2[0];
+        sp.dA_part[((int64_t)b * sp.nc_total + sp.chunk0 + c) * sp.H + h] = s[0];
+        sp.dD_part[((int64_t)b * sp.nc_total + sp.chunk0 + c) * sp.H + h] = s2[0];
     }
 }
 
+// One block per head: strided partial sums, then a fixed-shape tree (deterministic).
 __global__ void k_param_reduce(SegParams sp) {
-    const int h = blockIdx.x * blockDim.x + threadIdx.x;
-    if (h >= sp.H) return;
+    __shared__ float sa[256], sd[256];
+    const int h = blockIdx.x, t = threadIdx.x;
     float a = 0.f, d = 0.f;
-    for (int bc = 0; bc < sp.Bt * sp.nc; ++bc) {
-        a += sp.dA_part[(int64_t)bc * sp.H + h];
-        d += sp.dD_part[(int64_t)bc * sp.H + h];
+    for (int64_t bc = t; bc < (int64_t)sp.Bt * sp.nc_total; bc += 256) {
+        a += sp.dA_part[bc * sp.H + h];
+        d += sp.dD_part[bc * sp.H + h];
     }
-    if (sp.accumulate) {
-        sp.dA[h] += a;
-        sp.dD[h] += d;
-    } else {
-        sp.dA[h] = a;
-        sp.dD[h] = d;
+    sa[t] = a;
+    sd[t] = d;
+    __syncthreads();
+    for (int off = 128; off > 0; off >>= 1) {
+        if (t < off) {
+            sa[t] += sa[t + off];
+            sd[t] += sd[t + off];
+        }
+        __syncthreads();
+    }
+    if (t == 0) {
+        if (sp.accumulate) {
+            sp.dA[h] += sa[0];
+            sp.dD[h] += sd[0];
+        } else {
+            sp.dA[h] = sa[0];
+            sp.dD[h] = sd[0];
+        }
     }
 }
 
@@ -537,7 +550,7 @@ hipError_t bwd_segment(const SegParams& sp, hipStream_t st) {
     SSDK_LAUNCH(K_SCAN_BWD, st, k_state_scan_bwd, dim3(cdiv(P * N, NTHREADS), sp.H, sp.Bt), dim3(NTHREADS), sp);
     SSDK_LAUNCH(K_BWD_MAIN, st, k_bwd_main<T>, dim3(sp.Bt * sp.nc * sp.H, cdiv(Q, TS), 1), dim3(NTHREADS), sp);
     SSDK_LAUNCH(K_DDT, st, k_ddt_finalize<T>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(Q)), sp);
-    SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), sp);
+    if (!sp.defer_param) SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(sp.H), dim3(256), sp);
     SSDK_LAUNCH(K_DG, st, k_dG<T>, dim3(sp.Bt * sp.nc * sp.G, cdiv(Q, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
     SSDK_LAUNCH(K_DBC, st, k_dBC<T>, dim3(sp.Bt * sp.nc * sp.G * 2, cdiv(N, TS), cdiv(Q, TS)), dim3(NTHREADS), sp);
     return hipSuccess;
@@ -566,7 +579,12 @@ hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_
 // ddt / dA / dD finalisation (bf16 storage) for callers that produced the per-token scalars themselves.
 hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st) {
     SSDK_LAUNCH(K_DDT, st, k_ddt_finalize<bf16_t>, dim3(sp.nc, sp.H, sp.Bt), dim3(scan_block(sp.Q)), sp);
-    SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(cdiv(sp.H, 64)), dim3(64), sp);
+    if (!sp.defer_param) SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(sp.H), dim3(256), sp);
+    return hipSuccess;
+}
+
+hipError_t launch_param_reduce(const SegParams& sp, hipStream_t st) {
+    SSDK_LAUNCH(K_PARAM, st, k_param_reduce, dim3(sp.H), dim3(256), sp);
     return hipSuccess;
 }
 

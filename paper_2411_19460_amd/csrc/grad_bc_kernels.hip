@@ -1,0 +1,407 @@
+// Gradients of B and C for one segment on the matrix cores (gfx950, bf16 in / fp32 accumulate).
+// With M = the masked, decayed score matrix of a chunk (Sec. 3.1, Eq. 1 unrolled over the chunk),
+//   dG[i][j] = sum over the heads of the group of  dt_j decay(i,j) (dY_i . x_j),   j <= i
+//   dC_i     = sum_j dG[i][j] B_j  +  sum_heads exp(cum_i) dY_i^T Hprev
+//   dB_j     = sum_i dG[i][j] C_i  +  sum_heads exp(T - cum_j) dt_j x_j^T dHnext
+// Three kernels:
+//   mk_dG       : one workgroup per (batch, chunk, group, head slice); the whole lower triangle of dG
+//                 (36 tiles of 32 x 32 when Q = 256, four or five per wave) stays in accumulators while the workgroup walks
+//                 the heads of its slice; dY and x tiles are staged in LDS once per head (next head
+//                 prefetched in registers).  Writes one bf16 partial sum per slice.
+//   mk_dBC_part : the two head sums on the right, same organisation, accumulators [Q x 128] per
+//                 (chunk, role, slice); the per-token weight is folded into the staged operand.
+//   mk_dBC_final: sums the slices, contracts dG with B / dG^T with C, adds the head sums, rounds once.
+// The decay of an off-diagonal tile is the product of a per-row factor, a per-column factor and a
+// per-tile scalar, all <= 1 (32-token granularity); diagonal tiles evaluate exp() per element.
+#include "mfma_common.h"
+
+namespace ssdk {
+namespace {
+
+using namespace mf;
+
+constexpr int TP = 80;  // bytes per LDS row of a [32][32] bf16 tile (64 + 16 pad)
+
+__device__ __forceinline__ bf16x8 lds_rows(const char* tile, int pitch, int row0, int k0, int lane) {
+    return *(const bf16x8*)(tile + (row0 + (lane & 31)) * pitch + (k0 + 8 * (lane >> 5)) * 2);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Which 32 x 32 tiles (ti, tj <= ti) of the lower triangle each wave of mk_dG owns.  Q = 256: sixteen
+// waves of two or three tiles (many light waves per SIMD hide the LDS and MFMA latencies that one
+// heavy wave exposes).  Smaller chunks: wave v owns tile row v.
+template <int Q>
+struct DgMap {
+    static constexpr int NT = Q / 32, NWV = NT, MAXT = NT;
+    static __device__ __forceinline__ int count(int v) { return v + 1; }
+    static __device__ __forceinline__ int ti(int v, int) { return v; }
+    static __device__ __forceinline__ int tj(int, int k) { return k; }
+};
+template <>
+struct DgMap<256> {
+    // sixteen waves; the four waves of a SIMD (v, v + 4, v + 8, v + 12) hold nine tiles, two of them diagonal
+    static constexpr int NT = 8, NWV = 16, MAXT = 3;
+    static constexpr int CNT[16] = {2, 2, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 2, 2, 2, 2};
+    static constexpr int TI[16][3] = {{0, 1, 0}, {1, 2, 0}, {2, 2, 0}, {3, 3, 0}, {4, 4, 0}, {5, 5, 0}, {6, 6, 0}, {7, 7, 0}, {3, 3, 4}, {4, 4, 5}, {5, 5, 5}, {6, 6, 6}, {6, 6, 0}, {7, 7, 0}, {7, 7, 0}, {7, 7, 0}};
+    static constexpr int TJ[16][3] = {{0, 0, 0}, {1, 1, 0}, {2, 0, 0}, {3, 2, 0}, {4, 3, 0}, {5, 4, 0}, {6, 5, 0}, {7, 6, 0}, {0, 1, 0}, {1, 2, 0}, {1, 2, 3}, {0, 1, 2}, {3, 4, 0}, {0, 1, 0}, {2, 3, 0}, {4, 5, 0}};
+    static __device__ __forceinline__ int count(int v) { return CNT[v]; }
+    static __device__ __forceinline__ int ti(int v, int k) { return TI[v][k]; }
+    static __device__ __forceinline__ int tj(int v, int k) { return TJ[v][k]; }
+};
+
+template <int Q>
+struct DgLds {
+    char dy[Q * XPITCH];
+    char x[Q * XPITCH];
+    float c2[Q];    // cum * log2(e)
+    float dtl[Q];   // dt
+    float rowf[Q];  // exp(cum_i - cum[start of i's 32-token tile - 1])
+    float colf[Q];  // exp(cum[end of j's tile] - cum_j) * dt_j
+};
+
+template <int Q>
+struct DgPre {
+    static constexpr int NV = Q * 8 / (64 * DgMap<Q>::NWV);  // 16-byte vectors of each tile per thread
+    bf16x8 dy[NV], x[NV];
+    float cum, dtf, cstart, cend;
+};
+
+template <int Q>
+__device__ __forceinline__ void dg_load(DgPre<Q>& pr, const SegParams& sp, int b, int c, int h, int tid) {
+    constexpr int NTHR = 64 * DgMap<Q>::NWV;
+    const int64_t xt = (int64_t)sp.H * P_;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
+    const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
+    const bf16_t* dyg = (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
+#pragma unroll
+    for (int k = 0; k < DgPre<Q>::NV; ++k) {
+        const int v = tid + NTHR * k, row = v >> 3, seg = v & 7;
+        pr.dy[k] = *(const bf16x8*)(dyg + (int64_t)row * xt + seg * 8);
+        pr.x[k] = *(const bf16x8*)(xg + (int64_t)row * xt + seg * 8);
+    }
+    if (tid < Q) {
+        const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+        const float* cum = sp.cum + cbase;
+        const int t0 = tid & ~31;
+        pr.cum = cum[tid];
+        pr.dtf = sp.dtf[cbase + tid];
+        pr.cstart = t0 > 0 ? cum[t0 - 1] : 0.f;
+        pr.cend = cum[t0 + 31];
+    }
+}
+
+template <int Q>
+__device__ __forceinline__ void dg_store(const DgPre<Q>& pr, DgLds<Q>& L, int tid) {
+    constexpr int NTHR = 64 * DgMap<Q>::NWV;
+#pragma unroll
+    for (int k = 0; k < DgPre<Q>::NV; ++k) {
+        const int v = tid + NTHR * k, row = v >> 3, seg = v & 7;
+        *(bf16x8*)(L.dy + row * XPITCH + seg * 16) = pr.dy[k];
+        *(bf16x8*)(L.x + row * XPITCH + seg * 16) = pr.x[k];
+    }
+    if (tid < Q) {
+        L.c2[tid] = pr.cum * LOG2E;
+        L.dtl[tid] = pr.dtf;
+        L.rowf[tid] = __builtin_amdgcn_exp2f((pr.cum - pr.cstart) * LOG2E);
+        L.colf[tid] = __builtin_amdgcn_exp2f((pr.cend - pr.cum) * LOG2E) * pr.dtf;
+    }
+}
+
+// One tile (ti, tj) of one head: t = dY[ti] x[tj]^T, then acc += t (.) decay (.) dt.  ti and tj are
+// wave-uniform run-time values (one code path for every wave: no per-wave specialisation).
+template <int Q>
+__device__ __forceinline__ void dg_tile(f32x16& acc, int ti, int tj, const DgLds<Q>& L, int lane) {
+    const char* pa = L.dy + (32 * ti + (lane & 31)) * XPITCH + 16 * (lane >> 5);
+    const char* pb = L.x + (32 * tj + (lane & 31)) * XPITCH + 16 * (lane >> 5);
+    f32x16 t = zero16();
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) t = mfma(*(const bf16x8*)(pa + 32 * ks), *(const bf16x8*)(pb + 32 * ks), t);
+    const int j = 32 * tj + (lane & 31);
+    const float* rowp = (ti != tj ? L.rowf : L.c2) + 32 * ti + 4 * (lane >> 5);
+    if (ti != tj) {
+        const float m = __builtin_amdgcn_exp2f(L.c2[32 * ti - 1] - L.c2[32 * tj + 31]);
+        const float f = L.colf[j] * m;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 rf = *(const float4*)(rowp + 8 * q);
+            acc[4 * q + 0] += t[4 * q + 0] * (rf.x * f);
+            acc[4 * q + 1] += t[4 * q + 1] * (rf.y * f);
+            acc[4 * q + 2] += t[4 * q + 2] * (rf.z * f);
+            acc[4 * q + 3] += t[4 * q + 3] * (rf.w * f);
+        }
+    } else {
+        const float cj = L.c2[j], dj = L.dtl[j];
+        const int il = (lane & 31) - 4 * (lane >> 5);  // j - (first row of register group 0), tile-local
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const float4 ci = *(const float4*)(rowp + 8 * q);
+            const float cv[4] = {ci.x, ci.y, ci.z, ci.w};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float f = __builtin_amdgcn_exp2f(fminf(cv[e] - cj, 0.f)) * dj;
+                acc[4 * q + e] += (il <= 8 * q + e) ? t[4 * q + e] * f : 0.f;
+            }
+        }
+    }
+}
+
+template <int Q>
+__global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
+    constexpr int MAXT = DgMap<Q>::MAXT;
+    __shared__ __attribute__((aligned(16))) DgLds<Q> L;
+    int z = blockIdx.x;
+    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    const int ns = sp.dg_split, slice = z % ns;
+    z /= ns;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int cnt = DgMap<Q>::count(w);
+    f32x16 acc[MAXT];
+#pragma unroll
+    for (int k = 0; k < MAXT; ++k) acc[k] = zero16();
+    DgPre<Q> pr;
+    dg_load<Q>(pr, sp, b, c, h0, tid);
+    for (int hh = 0; hh < hps; ++hh) {
+        __syncthreads();
+        dg_store<Q>(pr, L, tid);
+        __syncthreads();
+        if (hh + 1 < hps) dg_load<Q>(pr, sp, b, c, h0 + hh + 1, tid);
+#pragma unroll
+        for (int k = 0; k < MAXT; ++k)
+            if (k < cnt) dg_tile<Q>(acc[k], DgMap<Q>::ti(w, k), DgMap<Q>::tj(w, k), L, lane);
+    }
+    __bf16* out = (__bf16*)sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * ((int64_t)Q * Q);
+    // partial sum of this slice, bf16 [Q][Q] row-major (tiles above the diagonal are never touched)
+#pragma unroll
+    for (int k = 0; k < MAXT; ++k)
+        if (k < cnt) {
+            __bf16* o = out + (int64_t)(32 * DgMap<Q>::ti(w, k) + 4 * (lane >> 5)) * Q + 32 * DgMap<Q>::tj(w, k) + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) o[(int64_t)(8 * (r >> 2) + (r & 3)) * Q] = (__bf16)acc[k][r];
+        }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Head sums of dC (role 0) and dB (role 1):
+//   role 0:  part[i][n] = sum_h exp(cum_h,i) (dY_h,i . Hprev_h[:, n])
+//   role 1:  part[j][n] = sum_h exp(T_h - cum_h,j) dt_h,j (x_h,j . dHnext_h[:, n])
+// Wave w owns RT row tiles (row group w / 2) and one half of the state columns (w % 2).
+template <int Q>
+struct PartCfg {
+    static constexpr int RT = Q >= 256 ? 2 : 1;       // 32-row tiles per wave
+    static constexpr int NWV = 2 * (Q / 32) / RT;     // waves
+    static constexpr int NTHR = 64 * NWV;
+    static constexpr int TV = Q * 8 / NTHR;           // 16-byte vectors of the token tile per thread
+    static constexpr int SV = P_ * 16 / NTHR;         // of the state
+};
+
+template <int Q>
+struct PartLds {
+    char tile[Q * XPITCH];  // weight * dY or weight * x, token-major
+    char st[P_ * BPITCH];   // Hprev or dHnext, [p][n] bf16
+};
+
+template <int Q>
+struct PartPre {
+    bf16x8 t[PartCfg<Q>::TV];
+    float sc[PartCfg<Q>::TV];
+    bf16x8 sv[PartCfg<Q>::SV];
+};
+
+template <int Q>
+__device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, int role, int b, int c, int h, int tid) {
+    typedef PartCfg<Q> CF;
+    const int64_t xt = (int64_t)sp.H * P_;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
+    const bf16_t* src = role == 0 ? (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow
+                                  : (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
+    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
+    const float T_ = sp.cum[cbase + Q - 1];
+#pragma unroll
+    for (int k = 0; k < CF::TV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
+        pr.t[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+        const float cv = sp.cum[cbase + row];
+        pr.sc[k] = role == 0 ? __expf(cv) : __expf(T_ - cv) * sp.dtf[cbase + row];
+    }
+    const bf16_t* S = (role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+#pragma unroll
+    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)(S + (tid + CF::NTHR * k) * 8);
+}
+
+template <int Q>
+__device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, int tid) {
+    typedef PartCfg<Q> CF;
+#pragma unroll
+    for (int k = 0; k < CF::TV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
+        *(bf16x8*)(L.tile + row * XPITCH + seg * 16) = scale8(pr.t[k], pr.sc[k]);
+    }
+#pragma unroll
+    for (int k = 0; k < CF::SV; ++k) {
+        const int v = tid + CF::NTHR * k, row = v >> 4, seg = v & 15;
+        *(bf16x8*)(L.st + row * BPITCH + seg * 16) = pr.sv[k];
+    }
+}
+
+template <int Q>
+__global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
+    typedef PartCfg<Q> CF;
+    constexpr int RT = CF::RT;
+    __shared__ __attribute__((aligned(16))) PartLds<Q> L;
+    int z = blockIdx.x;
+    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    const int ns = sp.part_split, slice = z % ns;
+    z /= ns;
+    const int role = z & 1;
+    z >>= 1;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, rg = w >> 1, nh = w & 1;
+    f32x16 acc[RT][2];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) acc[rt][0] = acc[rt][1] = zero16();
+    PartPre<Q> pr;
+    part_load<Q>(pr, sp, role, b, c, h0, tid);
+    for (int hh = 0; hh < hps; ++hh) {
+        __syncthreads();
+        part_store<Q>(pr, L, tid);
+        __syncthreads();
+        if (hh + 1 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 1, tid);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            const bf16x8 fb0 = frag_tr(L.st, BPITCH, 16 * ks, 64 * nh, lane);
+            const bf16x8 fb1 = frag_tr(L.st, BPITCH, 16 * ks, 64 * nh + 32, lane);
+#pragma unroll
+            for (int rt = 0; rt < RT; ++rt) {
+                const bf16x8 fa = lds_rows(L.tile, XPITCH, 32 * (rg * RT + rt), 16 * ks, lane);
+                acc[rt][0] = mfma(fa, fb0, acc[rt][0]);
+                acc[rt][1] = mfma(fa, fb1, acc[rt][1]);
+            }
+        }
+    }
+    float* part = sp.dbc_part + (((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * 2 + role) * ((int64_t)Q * N_);
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt)
+#pragma unroll
+            for (int r = 0; r < 16; ++r)
+                part[(int64_t)(32 * (rg * RT + rt) + acc_row(r, lane)) * N_ + 64 * nh + 32 * nt + (lane & 31)] = acc[rt][nt][r];
+}
+
+// ---------------------------------------------------------------------------------------------
+// dC rows (role 0) / dB rows (role 1) of one 32-token tile R of one (chunk, group):
+//   role 0: out[i][n] = sum_{tj <= R} dG[R-tile rows][tj-tile cols] B[tj-tile rows][n] + head sums
+//   role 1: out[j][n] = sum_{ti >= R} dG[ti-tile rows][R-tile cols]^T C[ti-tile rows][n] + head sums
+// Wave w sums the slices of tiles w, w + 4 into LDS (bf16); then every wave owns 32 state columns.
+template <int Q>
+struct FinLds {
+    char tiles[Q / 32][32 * TP];
+    char slab[Q * BPITCH];
+};
+
+template <int Q>
+__global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
+    constexpr int NT = Q / 32;
+    __shared__ __attribute__((aligned(16))) FinLds<Q> L;
+    int z = blockIdx.x;
+    const int R = z % NT;
+    z /= NT;
+    const int role = z & 1;
+    z >>= 1;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int64_t bcg = ((int64_t)b * sp.nc + c) * sp.G + g;
+    const int64_t bt = (int64_t)sp.G * N_;
+    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
+    const bf16_t* rhs = (role == 0 ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + bbase;
+    const int k_lo = role == 0 ? 0 : R, k_hi = role == 0 ? R : NT - 1;  // tiles along the contraction
+    const int ns = sp.dg_split;
+    const bf16_t* dg = (const bf16_t*)sp.dG + bcg * ns * ((int64_t)Q * Q);
+    // sum the slices of the needed dG tiles
+    for (int tk = k_lo + w; tk <= k_hi; tk += NTH / 64) {
+        const int ti = role == 0 ? R : tk, tj = role == 0 ? tk : R;
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            const int v = lane + 64 * half, row = v >> 2, seg = v & 3;
+            const bf16_t* src = dg + (int64_t)(32 * ti + row) * Q + 32 * tj + seg * 8;
+            float s[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] = 0.f;
+            int sl = 0;
+            for (; sl + 4 <= ns; sl += 4) {  // four loads in flight; summation order stays slice 0, 1, 2, ...
+                bf16x8 vv[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) vv[u] = *(const bf16x8*)(src + (int64_t)(sl + u) * Q * Q);
+#pragma unroll
+                for (int u = 0; u < 4; ++u)
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) s[e] += (float)vv[u][e];
+            }
+            for (; sl < ns; ++sl) {
+                const bf16x8 vv = *(const bf16x8*)(src + (int64_t)sl * Q * Q);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] += (float)vv[e];
+            }
+            bf16x8 o;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)s[e];
+            *(bf16x8*)(L.tiles[tk] + row * TP + seg * 16) = o;
+        }
+    }
+    // rows of B (role 0) / C (role 1) along the contraction
+    for (int v = tid; v < (k_hi - k_lo + 1) * 32 * 16; v += NTH) {
+        const int row = 32 * k_lo + (v >> 4), seg = v & 15;
+        *(bf16x8*)(L.slab + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)row * bt + seg * 8);
+    }
+    __syncthreads();
+    f32x16 acc = zero16();
+    for (int tk = k_lo; tk <= k_hi; ++tk) {
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            // role 0: tile is [i][j], operand rows i, contraction j: plain rows.
+            // role 1: tile is [i][j], operand rows j, contraction i: transpose load.
+            const bf16x8 fa = role == 0 ? lds_rows(L.tiles[tk], TP, 0, 16 * ks, lane) : frag_tr(L.tiles[tk], TP, 16 * ks, 0, lane);
+            const bf16x8 fb = frag_tr(L.slab, BPITCH, 32 * tk + 16 * ks, 32 * w, lane);
+            acc = mfma(fa, fb, acc);
+        }
+    }
+    bf16_t* out = (role == 0 ? (bf16_t*)sp.dC : (bf16_t*)sp.dB) + bbase;
+    const int ps = sp.part_split;
+    const float* part = sp.dbc_part + (bcg * ps * 2 + role) * ((int64_t)Q * N_);
+    // the head sums arrive slice by slice, all 16 rows of a slice in flight at once
+    for (int s = 0; s < ps; ++s) {
+        float pv[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            pv[r] = part[(int64_t)s * 2 * Q * N_ + (int64_t)(32 * R + acc_row(r, lane)) * N_ + 32 * w + (lane & 31)];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] += pv[r];
+    }
+#pragma unroll
+    for (int r = 0; r < 16; ++r)
+        out[(int64_t)(32 * R + acc_row(r, lane)) * bt + 32 * w + (lane & 31)] = float_to_bf16(acc[r]);
+}
+
+template <int Q>
+hipError_t grad_bc_q(const SegParams& sp, hipStream_t st) {
+    SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(sp.Bt * sp.nc * sp.G * sp.dg_split), dim3(64 * DgMap<Q>::NWV), sp);
+    SSDK_LAUNCH(K_MFMA_DBC, st, mk_dBC_part<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * sp.part_split), dim3(PartCfg<Q>::NTHR), sp);
+    SSDK_LAUNCH(K_MFMA_DBC_FINAL, st, mk_dBC_final<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * (Q / 32)), dim3(NTH), sp);
+    return hipSuccess;
+}
+
+}  // namespace
+
+hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st) {
+    switch (sp.Q) {
+        case 64: return grad_bc_q<64>(sp, st);
+        case 128: return grad_bc_q<128>(sp, st);
+        case 256: return grad_bc_q<256>(sp, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ssdk

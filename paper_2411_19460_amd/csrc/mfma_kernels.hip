@@ -201,221 +201,16 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
     if (sp.dinit_out) *(float4*)(sp.dinit_out + ce) = g;
 }
 
-// ---------------------------------------------------------------------------------------------
-// dG[i][j] = sum over the heads of one slice of  decay_h(i,j) dt_h,j (dY_h,i . x_h,j),  j <= i, for one
-// 64 x 64 block (I, J <= I) of one (chunk, group).  Both operands are read straight from global
-// memory (the contraction runs over the channel index, which is contiguous).  Off-diagonal blocks
-// use the factored decay ein_i * exp(cum[start of I - 1] - cum[end of J]) * eout_j applied to the
-// per-head product; the diagonal block evaluates exp() per element.  Written twice, as [i][j] and
-// transposed [j][i], fp32, one copy per head slice (summed by the consumer: fixed order).
-template <int Q>
-__global__ __launch_bounds__(NTH) void mk_dG(SegParams sp) {
-    constexpr int NB = Q / BLK;
-    int z = blockIdx.x;
-    const int ns = sp.dg_split, split = z % ns;
-    z /= ns;
-    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
-    int I = 0, rem = blockIdx.y;
-    while (rem > I) {
-        rem -= I + 1;
-        ++I;
-    }
-    const int J = rem;
-    if (I >= NB) return;
-    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int i0 = I * BLK + (w >> 1) * 32, j0 = J * BLK + (w & 1) * 32, j = j0 + (lane & 31);
-    const bool diag = I == J;
-    const int hps = sp.hpg / ns;
-    const int64_t xt = (int64_t)sp.H * P_;
-    f32x16 acc = zero16();
-    if (!(diag && w == 1)) {  // that sub-tile lies strictly above the diagonal
-        for (int hh = 0; hh < hps; ++hh) {
-            const int h = g * sp.hpg + split * hps + hh;
-            const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-            const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
-            const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
-            const bf16_t* dyg = (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
-            f32x16 t = zero16();
-#pragma unroll
-            for (int ks = 0; ks < P_ / 16; ++ks)
-                t = mfma(frag_rows(dyg, xt, i0, 16 * ks, lane), frag_rows(xg, xt, j0, 16 * ks, lane), t);
-            const float dtj = sp.dtf[cbase + j];
-            if (!diag) {
-                const float m = __expf(sp.cum[cbase + I * BLK - 1] - sp.cum[cbase + J * BLK + BLK - 1]);
-                const float cf = sp.eout[cbase + j] * dtj * m;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 rf = *(const float4*)(sp.ein + cbase + i0 + 8 * q + 4 * (lane >> 5));
-                    acc[4 * q + 0] += t[4 * q + 0] * (rf.x * cf);
-                    acc[4 * q + 1] += t[4 * q + 1] * (rf.y * cf);
-                    acc[4 * q + 2] += t[4 * q + 2] * (rf.z * cf);
-                    acc[4 * q + 3] += t[4 * q + 3] * (rf.w * cf);
-                }
-            } else {
-                const float cj = sp.cum[cbase + j] * LOG2E;
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int ib = i0 + 8 * q + 4 * (lane >> 5);
-                    const float4 ci = *(const float4*)(sp.cum + cbase + ib);
-                    const float cv[4] = {ci.x, ci.y, ci.z, ci.w};
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float f = (j <= ib + e) ? __builtin_amdgcn_exp2f(fminf(cv[e] * LOG2E - cj, 0.f)) * dtj : 0.f;
-                        acc[4 * q + e] += t[4 * q + e] * f;
-                    }
-                }
-            }
-        }
-    }
-    float* base = sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + split) * (2 * Q * Q);
-    float* dGT = base + Q * Q;
-#pragma unroll
-    for (int q = 0; q < 4; ++q) {
-        const int ib = i0 + 8 * q + 4 * (lane >> 5);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) base[(int64_t)(ib + e) * Q + j] = acc[4 * q + e];
-        *(float4*)(dGT + (int64_t)j * Q + ib) = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Per-head terms of dC and dB, summed over the heads of one slice, for one 64-token row block:
-//   role 0:  part[i][n] = sum_h exp(cum_h,i) (dY_h,i . Hprev_h[:, n])
-//   role 1:  part[j][n] = sum_h exp(T_h - cum_h,j) dt_h,j (x_h,j . dHnext_h[:, n])
-// The state is staged [p][n] in LDS and read with transpose loads (the contraction runs over p).
-template <int Q>
-__global__ __launch_bounds__(NTH) void mk_dBC_part(SegParams sp) {
-    __shared__ __attribute__((aligned(16))) char Hs[P_ * BPITCH];
-    int z = blockIdx.x;
-    const int ns = sp.dg_split, split = z % ns;
-    z /= ns;
-    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
-    const int role = blockIdx.y & 1, r0 = (blockIdx.y >> 1) * BLK;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int hps = sp.hpg / ns;
-    const int64_t xt = (int64_t)sp.H * P_;
-    f32x16 acc0 = zero16(), acc1 = zero16();
-    for (int hh = 0; hh < hps; ++hh) {
-        const int h = g * sp.hpg + split * hps + hh;
-        const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-        const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
-        const bf16_t* st = (role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
-        const bf16_t* lhs = role == 0 ? (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow
-                                      : (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
-            *(bf16x8*)(Hs + row * BPITCH + seg * 16) = *(const bf16x8*)(st + row * N_ + seg * 8);
-        }
-        __syncthreads();
-        f32x16 t0 = zero16(), t1 = zero16();
-#pragma unroll
-        for (int ks = 0; ks < P_ / 16; ++ks) {
-            const bf16x8 fb = frag_tr(Hs, BPITCH, 16 * ks, 32 * w, lane);
-            t0 = mfma(frag_rows(lhs, xt, r0, 16 * ks, lane), fb, t0);
-            t1 = mfma(frag_rows(lhs, xt, r0 + 32, 16 * ks, lane), fb, t1);
-        }
-        const float scal = role == 0 ? (r0 > 0 ? __expf(sp.cum[cbase + r0 - 1]) : 1.f)
-                                     : __expf(sp.cum[cbase + Q - 1] - sp.cum[cbase + r0 + BLK - 1]);
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            const int rb = r0 + 8 * q + 4 * (lane >> 5);
-            float4 f0, f1;
-            if (role == 0) {
-                f0 = *(const float4*)(sp.ein + cbase + rb);
-                f1 = *(const float4*)(sp.ein + cbase + rb + 32);
-            } else {
-                const float4 e0 = *(const float4*)(sp.eout + cbase + rb), d0 = *(const float4*)(sp.dtf + cbase + rb);
-                const float4 e1 = *(const float4*)(sp.eout + cbase + rb + 32), d1 = *(const float4*)(sp.dtf + cbase + rb + 32);
-                f0 = make_float4(e0.x * d0.x, e0.y * d0.y, e0.z * d0.z, e0.w * d0.w);
-                f1 = make_float4(e1.x * d1.x, e1.y * d1.y, e1.z * d1.z, e1.w * d1.w);
-            }
-            acc0[4 * q + 0] += t0[4 * q + 0] * (f0.x * scal);
-            acc0[4 * q + 1] += t0[4 * q + 1] * (f0.y * scal);
-            acc0[4 * q + 2] += t0[4 * q + 2] * (f0.z * scal);
-            acc0[4 * q + 3] += t0[4 * q + 3] * (f0.w * scal);
-            acc1[4 * q + 0] += t1[4 * q + 0] * (f1.x * scal);
-            acc1[4 * q + 1] += t1[4 * q + 1] * (f1.y * scal);
-            acc1[4 * q + 2] += t1[4 * q + 2] * (f1.z * scal);
-            acc1[4 * q + 3] += t1[4 * q + 3] * (f1.w * scal);
-        }
-    }
-    float* part = sp.dbc_part + (((((int64_t)b * sp.nc + c) * sp.G + g) * ns + split) * 2 + role) * (Q * N_);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = r0 + acc_row(r, lane), n = 32 * w + (lane & 31);
-        part[(int64_t)row * N_ + n] = acc0[r];
-        part[(int64_t)(row + 32) * N_ + n] = acc1[r];
-    }
-}
-
-// dC = tril(dG) B + sum of the per-slice parts;  dB = tril(dG)^T C + parts.  One 64-row block per workgroup.
-template <int Q>
-__global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
-    constexpr int NB = Q / BLK;
-    __shared__ __attribute__((aligned(16))) char slab[BLK * BPITCH];
-    const int z = blockIdx.x, g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
-    const int role = blockIdx.y & 1, R = blockIdx.y >> 1, r0 = R * BLK;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, ns = sp.dg_split;
-    const int64_t bcg = ((int64_t)b * sp.nc + c) * sp.G + g;
-    const int64_t bt = (int64_t)sp.G * N_;
-    const int64_t bbase = (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
-    const bf16_t* rhs = (role == 0 ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + bbase;
-    const float* dg = sp.dG + bcg * ns * (2 * Q * Q) + (role == 0 ? 0 : Q * Q);  // [i][j] or its transpose
-    f32x16 acc0 = zero16(), acc1 = zero16();
-    const int Kbeg = role == 0 ? 0 : R, Kend = role == 0 ? R : NB - 1;
-    for (int K = Kbeg; K <= Kend; ++K) {
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
-            *(bf16x8*)(slab + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)(K * BLK + row) * bt + seg * 8);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < BLK / 16; ++ks) {
-            const int k0 = K * BLK + 16 * ks + 8 * (lane >> 5);
-            bf16x8 fa[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const float* src = dg + (int64_t)(r0 + 32 * t + (lane & 31)) * Q + k0;
-                float4 lo = *(const float4*)src, hi = *(const float4*)(src + 4);
-                for (int s = 1; s < ns; ++s) {
-                    const float4 l2 = *(const float4*)(src + (int64_t)s * 2 * Q * Q), h2 = *(const float4*)(src + (int64_t)s * 2 * Q * Q + 4);
-                    lo.x += l2.x; lo.y += l2.y; lo.z += l2.z; lo.w += l2.w;
-                    hi.x += h2.x; hi.y += h2.y; hi.z += h2.z; hi.w += h2.w;
-                }
-                fa[t][0] = (__bf16)lo.x; fa[t][1] = (__bf16)lo.y; fa[t][2] = (__bf16)lo.z; fa[t][3] = (__bf16)lo.w;
-                fa[t][4] = (__bf16)hi.x; fa[t][5] = (__bf16)hi.y; fa[t][6] = (__bf16)hi.z; fa[t][7] = (__bf16)hi.w;
-            }
-            const bf16x8 fb = frag_tr(slab, BPITCH, 16 * ks, 32 * w, lane);
-            acc0 = mfma(fa[0], fb, acc0);
-            acc1 = mfma(fa[1], fb, acc1);
-        }
-    }
-    bf16_t* out = (role == 0 ? (bf16_t*)sp.dC : (bf16_t*)sp.dB) + bbase;
-    const float* part = sp.dbc_part + (bcg * ns * 2 + role) * (Q * N_);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = r0 + acc_row(r, lane), n = 32 * w + (lane & 31);
-        float v0 = acc0[r], v1 = acc1[r];
-        for (int s = 0; s < ns; ++s) {
-            v0 += part[(int64_t)s * 2 * Q * N_ + (int64_t)row * N_ + n];
-            v1 += part[(int64_t)s * 2 * Q * N_ + (int64_t)(row + 32) * N_ + n];
-        }
-        out[(int64_t)row * bt + n] = float_to_bf16(v0);
-        out[(int64_t)(row + 32) * bt + n] = float_to_bf16(v1);
-    }
-}
-
 template <int Q>
 hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
     constexpr int NB = Q / BLK;
     SSDK_LAUNCH(K_CUMSUM, st, mk_prep<Q>, dim3(sp.nc, sp.H, sp.Bt), dim3(Q), sp);
     SSDK_LAUNCH(K_MFMA_CHUNK_STATE, st, (mk_chunk_outer<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
-    SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
     SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
+    // the scan is the only step that needs the previous segment (its leaving state)
+    if (need_y && sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
+    SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    if (need_y && sp.ev_record && hipEventRecord(sp.ev_record, st) != hipSuccess) return hipErrorUnknown;
     if (need_y) {
         hipError_t e = mfma_launch_dual(sp, 0, st);
         if (e != hipSuccess) return e;
@@ -428,17 +223,18 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     SegParams sp = sp0;
     sp.nslice = P_ * N_ / 4 / NTH;  // partial sums written by mk_scan_bwd
     SSDK_LAUNCH(K_MFMA_DSTATE, st, (mk_chunk_outer<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    // the reverse scan is the only step that needs the segment to the right (its entering-state adjoint)
+    if (sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
     SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    if (sp.ev_record && hipEventRecord(sp.ev_record, st) != hipSuccess) return hipErrorUnknown;
     hipError_t e = mfma_launch_dual(sp, 1, st);
     if (e != hipSuccess) return e;
     e = mfma_launch_dual(sp, 2, st);
     if (e != hipSuccess) return e;
     e = generic_backward_scalars(sp, st);
     if (e != hipSuccess) return e;
-    constexpr int NB = Q / BLK;
-    SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(sp.Bt * sp.nc * sp.G * sp.dg_split, NB * (NB + 1) / 2), dim3(NTH), sp);
-    SSDK_LAUNCH(K_MFMA_DBC, st, mk_dBC_part<Q>, dim3(sp.Bt * sp.nc * sp.G * sp.dg_split, 2 * NB), dim3(NTH), sp);
-    SSDK_LAUNCH(K_MFMA_DBC_FINAL, st, mk_dBC_final<Q>, dim3(sp.Bt * sp.nc * sp.G, 2 * NB), dim3(NTH), sp);
+    e = mfma_launch_grad_bc(sp, st);
+    if (e != hipSuccess) return e;
     return hipSuccess;
 }
 

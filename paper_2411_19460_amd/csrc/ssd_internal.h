@@ -63,7 +63,7 @@ struct SegParams {
     float* states;     // [Bt][nc+1][H][P][N]  slot c: state entering chunk c; slot nc: state leaving the segment
     float* dstates;    // [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
     float* Gm;         // [Bt][nc][G][Q][Q]    C_i . B_j   (generic path: fp32)
-    float* dG;         // [Bt][nc][G][Q][Q]    head-summed masked dY X^T
+    float* dG;         // generic path: [Bt][nc][G][Q][Q] fp32 head-summed masked dY X^T; MFMA path: [Bt][nc][G][dg_split][Q][Q] bf16 per-slice sums
     float* gterm;      // [Bt][H][nc][Q]
     float* fterm;      // [Bt][H][nc][Q]
     float* dDrow;      // [Bt][H][nc][Q]
@@ -79,7 +79,8 @@ struct SegParams {
     bf16_t* dstates_bf;  // [Bt][nc][H][P][N] bf16 copy of the leaving-state adjoints
     int dg_split;        // number of head slices whose dG / dB / dC partial sums are kept apart
     int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
-    float* dbc_part;     // [Bt][nc][G][dg_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
+    int part_split;      // number of head slices of the dB / dC head sums
+    float* dbc_part;     // [Bt][nc][G][part_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
     int64_t state_in_bs;
@@ -93,6 +94,13 @@ struct SegParams {
     float* dA;
     float* dD;
     int accumulate;          // bwd: 1 = add this segment's dA/dD to what is there
+    // dA / dD partial sums: slot (b, chunk0 + c, h) of an array with nc_total chunks per batch.  The
+    // defaults (chunk0 = 0, nc_total = nc) keep them per segment; defer_param = 1 leaves the final
+    // reduction over all chunks to the caller (launch_param_reduce), so segments may run concurrently.
+    int chunk0, nc_total, defer_param;
+    // optional cross-stream ordering of the state scans (segments alternate between two streams):
+    // the scan waits for ev_wait and records ev_record when it has been enqueued
+    hipEvent_t ev_wait, ev_record;
 };
 
 // Validated dimensions of one call.
@@ -109,7 +117,7 @@ struct Dims {
 struct WsLayout {
     size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
     size_t ein, eout, states_bf, dstates_bf, dbc_part;
-    int nslice, dg_split;
+    int nslice, dg_split, part_split;
 };
 
 int check_shape(const ssd_shape_t* sh, Dims* d);
@@ -144,6 +152,8 @@ hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t s
 hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st);
 hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st);
 hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st);
+// dA, dD = (or +=, under sp.accumulate) the sum of the partial sums of all sp.nc_total chunks.
+hipError_t launch_param_reduce(const SegParams& sp, hipStream_t st);
 
 // MFMA path (bf16, P = 64, N = 128, Q in {64, 128, 256}).
 bool mfma_path_supported(const ssd_shape_t& s);
@@ -151,5 +161,9 @@ hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st
 hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
 // One dual-form pass over a segment: epi 0 = forward output, 1 and 2 = the two backward passes.
 hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st);
+// dG, the head sums and the final contraction that give dB and dC of one segment.
+hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st);
+// Smallest divisor ns of heads_per_group with base * ns >= target workgroups (else heads_per_group).
+int pick_split(int heads_per_group, int64_t base, int target);
 
 }  // namespace ssdk
