@@ -23,6 +23,7 @@
  *     NULL = the default stream) and before anything enqueued there after the call returns; with
  *     more than one segment part of it runs on a library-owned stream of default priority, forked
  *     from and joined back into `hip_stream` with events (created on the first such call).
+ *     Setting SSD_MAGC_SERIAL=1 in the environment keeps everything on `hip_stream` (diagnostics).
  *   - Tensors are dense row-major with the index order written in brackets; the batch stride
  *     may be overridden through ssd_shape_t (elements, 0 = dense) so that a token range of a
  *     longer sequence can be passed as a pointer offset.

@@ -1,5 +1,6 @@
 // C-ABI entry points for one SSD layer: argument validation, workspace partitioning and the
 // segment loops of the MA-GC sequence axis (paper Sec. 3.2/3.3, Alg. 1 and Alg. 2).
+#include <stdlib.h>
 #include <string.h>
 
 #include "ssd_internal.h"
@@ -203,7 +204,15 @@ static Pipe* pipe_for_current_device() {
 // Bytes of the arrays shared by both scratch blocks: the dA / dD partial sums of every chunk.
 static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d.nseg * d.nc * d.H * 4); }
 
-static bool pipelined(const Dims& d, bool mfma) { return mfma && d.nseg > 1; }
+// SSD_MAGC_SERIAL=1 in the environment keeps every segment on the caller's stream (diagnostics: per-kernel
+// timings are only meaningful when kernels do not overlap).
+static bool pipelined(const Dims& d, bool mfma) {
+    static const bool serial = [] {
+        const char* v = getenv("SSD_MAGC_SERIAL");
+        return v && v[0] == '1';
+    }();
+    return mfma && d.nseg > 1 && !serial;
+}
 
 }  // namespace ssdk
 

@@ -146,8 +146,9 @@ __global__ __launch_bounds__(NTH) void mk_chunk_outer(SegParams sp) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// Inter-chunk state passing over a segment (four state elements per thread), also emitting the bf16
-// copy of every entering state that the contraction kernels read.
+// Inter-chunk state passing over a segment (four state elements per thread).  The running state is
+// carried in fp32 registers (checkpoints and the final state are stored from them); the state
+// entering each chunk is emitted as the bf16 copy the contraction kernels read, nothing else.
 __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
@@ -155,47 +156,75 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     float4 hc = sp.state_in ? *(const float4*)(sp.state_in + (int64_t)b * sp.state_in_bs + bh) : make_float4(0.f, 0.f, 0.f, 0.f);
     if (sp.bnd_write) *(float4*)(sp.bnd_write + (int64_t)b * sp.bnd_write_bs + bh) = hc;
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
-    for (int c = 0; c < sp.nc; ++c) {
-        const int64_t idx = (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e;
-        const float4 s = *(const float4*)(sp.states + idx);
-        *(float4*)(sp.states + idx) = hc;
-        bf16x4 hb;
-        hb[0] = (__bf16)hc.x; hb[1] = (__bf16)hc.y; hb[2] = (__bf16)hc.z; hb[3] = (__bf16)hc.w;
-        *(bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = hb;
-        const float a = __expf(cum[(int64_t)c * sp.Q + sp.Q - 1]);
-        hc.x = a * hc.x + s.x; hc.y = a * hc.y + s.y; hc.z = a * hc.z + s.z; hc.w = a * hc.w + s.w;
+    constexpr int U = 8;  // chunks whose loads are in flight together (the recurrence itself is serial)
+    for (int c0 = 0; c0 < sp.nc; c0 += U) {
+        float4 sv[U];
+        float av[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u < sp.nc ? c0 + u : sp.nc - 1;
+            sv[u] = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e);  // chunk state
+            av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 + u;
+            if (c < sp.nc) {
+                bf16x4 hb;  // the entering state is kept in bf16 only
+                hb[0] = (__bf16)hc.x; hb[1] = (__bf16)hc.y; hb[2] = (__bf16)hc.z; hb[3] = (__bf16)hc.w;
+                *(bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = hb;
+                const float a = __expf(av[u]);
+                const float4 s = sv[u];
+                hc.x = a * hc.x + s.x; hc.y = a * hc.y + s.y; hc.z = a * hc.z + s.z; hc.w = a * hc.w + s.w;
+            }
+        }
     }
     *(float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e) = hc;
     if (sp.state_out) *(float4*)(sp.state_out + (int64_t)b * sp.state_out_bs + bh) = hc;
     if (sp.state_out2) *(float4*)(sp.state_out2 + (int64_t)b * sp.state_out2_bs + bh) = hc;
 }
 
-// Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-block partial sums
+// Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-wave partial sums
 // of <dHnext_c, Hnext_c> (fixed summation order).
 __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
-    __shared__ float red[NTH / 64];
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
     const int64_t ce = ((int64_t)b * sp.H + h) * PN + e;
     float4 g = *(const float4*)(sp.dcarry + ce);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
-    for (int c = sp.nc - 1; c >= 0; --c) {
-        const int64_t idx = (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e;
-        const float4 loc = *(const float4*)(sp.dstates + idx);
-        *(float4*)(sp.dstates + idx) = g;
-        bf16x4 gb;
-        gb[0] = (__bf16)g.x; gb[1] = (__bf16)g.y; gb[2] = (__bf16)g.z; gb[3] = (__bf16)g.w;
-        *(bf16x4*)(sp.dstates_bf + idx) = gb;
-        const float4 hn = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + c + 1) * sp.H + h) * PN + e);
-        float part = g.x * hn.x + g.y * hn.y + g.z * hn.z + g.w * hn.w;
-        for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
-        if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = part;
-        __syncthreads();
-        if (threadIdx.x == 0)
-            sp.tail_part[(((int64_t)b * sp.H + h) * sp.nc + c) * sp.nslice + blockIdx.x] = red[0] + red[1] + red[2] + red[3];
-        __syncthreads();
-        const float a = __expf(cum[(int64_t)c * sp.Q + sp.Q - 1]);
-        g.x = a * g.x + loc.x; g.y = a * g.y + loc.y; g.z = a * g.z + loc.z; g.w = a * g.w + loc.w;
+    constexpr int U = 4;  // chunks whose loads are in flight together
+    for (int c0 = sp.nc - 1; c0 >= 0; c0 -= U) {
+        float4 lv[U], hv[U];
+        float av[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 - u >= 0 ? c0 - u : 0;
+            lv[u] = *(const float4*)(sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);  // local adjoint
+            av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
+            // state leaving chunk c: fp32 for the last chunk of the segment, else the bf16 copy
+            if (c + 1 == sp.nc) {
+                hv[u] = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e);
+            } else {
+                const bf16x4 hb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c + 1) * sp.H + h) * PN + e);
+                hv[u] = make_float4((float)hb[0], (float)hb[1], (float)hb[2], (float)hb[3]);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int c = c0 - u;
+            if (c < 0) break;  // uniform
+            bf16x4 gb;  // the total adjoint is kept in bf16 only
+            gb[0] = (__bf16)g.x; gb[1] = (__bf16)g.y; gb[2] = (__bf16)g.z; gb[3] = (__bf16)g.w;
+            *(bf16x4*)(sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = gb;
+            const float4 hn = hv[u];
+            float part = g.x * hn.x + g.y * hn.y + g.z * hn.z + g.w * hn.w;
+            for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
+            if ((threadIdx.x & 63) == 0)  // one partial sum per wave; summed later in a fixed order
+                sp.tail_part[(((int64_t)b * sp.H + h) * sp.nc + c) * sp.nslice + blockIdx.x * (NTH / 64) + (threadIdx.x >> 6)] = part;
+            const float a = __expf(av[u]);
+            const float4 loc = lv[u];
+            g.x = a * g.x + loc.x; g.y = a * g.y + loc.y; g.z = a * g.z + loc.z; g.w = a * g.w + loc.w;
+        }
     }
     *(float4*)(sp.dcarry + ce) = g;
     if (sp.dinit_out) *(float4*)(sp.dinit_out + ce) = g;
@@ -221,7 +250,7 @@ hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
 template <int Q>
 hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     SegParams sp = sp0;
-    sp.nslice = P_ * N_ / 4 / NTH;  // partial sums written by mk_scan_bwd
+    sp.nslice = P_ * N_ / 4 / 64;  // partial sums written by mk_scan_bwd: one per wave
     SSDK_LAUNCH(K_MFMA_DSTATE, st, (mk_chunk_outer<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
     // the reverse scan is the only step that needs the segment to the right (its entering-state adjoint)
     if (sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
