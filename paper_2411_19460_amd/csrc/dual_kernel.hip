@@ -9,16 +9,16 @@
 //                             dx = dt u + D dY (+ dY), and the per-token scalars for ddt / dA / dD
 //
 // Organisation.  One workgroup owns one (batch, chunk, group) and a slice of that group's heads and
-// walks the heads one after the other.  Each of its waves owns two 32-token tiles of the chunk, t and
-// Q/32 - 1 - t, which together carry the same amount of causal work for every wave.  Everything
+// walks the heads one after the other.  It has one wave per 32-token tile of the chunk; the tile
+// index is a wave-uniform run-time value (one code path for every wave).  Everything
 // that does not depend on the head -- the wave's rows of the score matrix G = C B^T (or of its
 // transpose) and of C (or B) -- is fetched once and stays in registers as MFMA operands for all
 // heads of the slice.  Per head, the token-major operand (x or dY, Q x 64) and the state (64 x 128)
 // are prefetched into registers while the previous head is being computed, then staged in LDS
 // (plain and pre-scaled copy of the tile, see the decay factorisation in mfma_kernels.hip); outputs
 // go through a per-wave LDS patch so that global stores are whole 128-byte rows.
-// One wave per SIMD with the whole register file to itself: the persistent fragments take ~140
-// registers per lane.
+// With Q = 256 the eight waves are paired on the four SIMDs so that each SIMD sees the same amount
+// of causal work (tiles t and 7 - t).
 #include "mfma_common.h"
 
 namespace ssdk {
@@ -26,16 +26,15 @@ namespace {
 
 using namespace mf;
 
-constexpr int GF_MAX = 18;  // score-matrix fragments a wave keeps for its two tiles (Q = 256: 18 steps of 16 tokens)
+constexpr int GO_MAX = 12;  // score-matrix fragments of the off-diagonal blocks a wave keeps (three blocks of four steps)
 constexpr int RF_N = N_ / 16;
 
 template <int Q>
 struct DualCfg {
-    static constexpr int NT = Q / 32;           // token tiles
-    static constexpr int NW = NT / 2;           // waves: two tiles each
-    static constexpr int NTHR = 64 * NW;
+    static constexpr int NT = Q / 32;           // token tiles = waves
+    static constexpr int NTHR = 64 * NT;
     static constexpr int NB = Q / BLK;
-    static constexpr int XV = Q * 8 / NTHR;     // 16-byte vectors of the token-major tile per thread (= 8)
+    static constexpr int XV = Q * 8 / NTHR;     // 16-byte vectors of the token-major tile per thread (= 4)
     static constexpr int SV = P_ * 16 / NTHR;   // 16-byte vectors of the state per thread
 };
 
@@ -47,15 +46,7 @@ struct DualLds {
     float cum2[Q];           // cum * log2(e)
     float fac[Q];            // ein (forward) or eout (reverse): applied per output token
     float dtl[Q];            // dt
-    char priv[Q / 64][32 * XPITCH];  // per-wave patch for the row-major epilogue
-};
-
-template <int Q, int EPI, int T>
-struct DualTile {
-    static constexpr bool REV = EPI == 2;
-    static constexpr int NB = Q / BLK, I = T / 2, TOK0 = 32 * T, ODD = T & 1;
-    static constexpr int KS0 = REV ? 2 * T : 0;                     // first 16-token step of the contraction
-    static constexpr int NFR = REV ? 4 * NB - 2 * T : 2 * (T + 1);  // number of 16-token steps
+    char priv[Q / 32][32 * XPITCH];  // per-wave patch for the row-major epilogue
 };
 
 // Registers holding the next head's operands while the current head is computed.
@@ -131,56 +122,63 @@ __device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int t
     }
 }
 
-template <int Q, int EPI, int T, int GOFF, int ROFF>
-__device__ __forceinline__ void tile_load(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat, const bf16_t* rowop,
-                                          int64_t bt, int lane) {
-    typedef DualTile<Q, EPI, T> TI;
+// Persistent operands of tile T (wave-uniform run-time value): the rows TOK0 .. TOK0+31 of the score
+// matrix (forward: G, columns = earlier tokens; reverse: G^T, columns = later tokens) for the diagonal
+// 64-token block (gd) and for the off-diagonal blocks (go, block K at go[4K + ks] forward and at
+// go[4(K-1) + ks] reverse), and the same rows of C (forward) or B (reverse).
+template <int Q, bool REV>
+__device__ __forceinline__ void tile_load(bf16x8 (&go)[GO_MAX], bf16x8 (&gd)[4], bf16x8 (&rf)[RF_N], const bf16_t* Mat,
+                                          const bf16_t* rowop, int64_t bt, int T, int lane) {
+    constexpr int NB = Q / BLK;
+    const int I = T >> 1, tok0 = 32 * T;
 #pragma unroll
-    for (int f = 0; f < TI::NFR; ++f) gf[GOFF + f] = frag_rows(Mat, Q, TI::TOK0, 16 * (TI::KS0 + f), lane);
+    for (int n = 0; n < NB - 1; ++n) {
+        const int K = REV ? n + 1 : n;
+        if (REV ? K > I : K < I) {
 #pragma unroll
-    for (int ks = 0; ks < RF_N; ++ks) rf[ROFF + ks] = frag_rows(rowop, bt, TI::TOK0, 16 * ks, lane);
+            for (int ks = 0; ks < 4; ++ks) go[4 * n + ks] = frag_rows(Mat, Q, tok0, 16 * (4 * K + ks), lane);
+        }
+    }
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) gd[ks] = frag_rows(Mat, Q, tok0, 16 * (4 * I + ks), lane);
+#pragma unroll
+    for (int ks = 0; ks < RF_N; ++ks) rf[ks] = frag_rows(rowop, bt, tok0, 16 * ks, lane);
 }
 
-template <int Q, int EPI, int T, int GOFF, int ROFF>
-__device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const bf16x8 (&rf)[2 * RF_N], DualLds<Q>& L,
-                                             const HeadCtx& cx, int lane, int w) {
-    typedef DualTile<Q, EPI, T> TI;
-    constexpr bool REV = TI::REV;
-    constexpr int NB = TI::NB, I = TI::I;
-    const int tl = lane & 31, tok = TI::TOK0 + tl;
+template <int Q, int EPI>
+__device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const bf16x8 (&gd)[4], const bf16x8 (&rf)[RF_N],
+                                             DualLds<Q>& L, const HeadCtx& cx, int T, int lane, int w) {
+    constexpr bool REV = EPI == 2;
+    constexpr int NB = Q / BLK;
+    const int I = T >> 1, odd = T & 1, tok0 = 32 * T;
+    const int tl = lane & 31, tok = tok0 + tl;
     char* priv = L.priv[w];
-    // this wave's own 32 rows of the other token-major tensor, fetched as whole rows (EPI 1: dY, EPI 2: x)
-    bf16x8 own[4];
-    if (EPI != 0) {
-        const bf16_t* src = EPI == 1 ? cx.dyg : cx.xg;
-#pragma unroll
-        for (int it = 0; it < 4; ++it)
-            own[it] = *(const bf16x8*)(src + (int64_t)(TI::TOK0 + (lane >> 3) + 8 * it) * cx.xt + (lane & 7) * 8);
-    }
     const float lane_c2 = L.cum2[tok], lane_fac = L.fac[tok];
     f32x16 acc0 = zero16(), acc1 = zero16();
     // term through the chunk's entering state (forward) / leaving adjoint (reverse)
 #pragma unroll
     for (int ks = 0; ks < RF_N; ++ks) {
-        acc0 = mfma(frag_lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ROFF + ks], acc0);
-        acc1 = mfma(frag_lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ROFF + ks], acc1);
+        acc0 = mfma(frag_lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ks], acc0);
+        acc1 = mfma(frag_lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ks], acc1);
     }
-    // off-diagonal 64-token blocks, Horner in the block decays
+    // off-diagonal 64-token blocks, Horner in the block decays (forward: K = 0 .. I-1; reverse: K = NB-1 .. I+1)
 #pragma unroll
-    for (int n = 0; n < (REV ? NB - 1 - I : I); ++n) {
+    for (int n = 0; n < NB - 1; ++n) {
         const int K = REV ? NB - 1 - n : n;
-        const float sK = __builtin_amdgcn_exp2f(L.cum2[K * BLK + BLK - 1] - (K > 0 ? L.cum2[K * BLK - 1] : 0.f));
+        if (REV ? K > I : K < I) {
+            const float sK = __builtin_amdgcn_exp2f(L.cum2[K * BLK + BLK - 1] - (K > 0 ? L.cum2[K * BLK - 1] : 0.f));
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            acc0[r] *= sK;
-            acc1[r] *= sK;
-        }
+            for (int r = 0; r < 16; ++r) {
+                acc0[r] *= sK;
+                acc1[r] *= sK;
+            }
 #pragma unroll
-        for (int ks = 0; ks < BLK / 16; ++ks) {
-            const int k0 = K * BLK + 16 * ks;
-            const bf16x8 fb = gf[GOFF + 4 * K + ks - TI::KS0];
-            acc0 = mfma(frag_tr(L.scl, XPITCH, k0, 0, lane), fb, acc0);
-            acc1 = mfma(frag_tr(L.scl, XPITCH, k0, 32, lane), fb, acc1);
+            for (int ks = 0; ks < BLK / 16; ++ks) {
+                const int k0 = K * BLK + 16 * ks;
+                const bf16x8 fb = go[4 * (REV ? K - 1 : K) + ks];
+                acc0 = mfma(frag_tr(L.scl, XPITCH, k0, 0, lane), fb, acc0);
+                acc1 = mfma(frag_tr(L.scl, XPITCH, k0, 32, lane), fb, acc1);
+            }
         }
     }
 #pragma unroll
@@ -188,11 +186,13 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const b
         acc0[r] *= lane_fac;
         acc1[r] *= lane_fac;
     }
-    // diagonal block: the mask and the decay (and, forward, dt_j) are evaluated per element
+    // diagonal block: the mask and the decay (and, forward, dt_j) are evaluated per element.  Forward,
+    // an even tile stops after its own 32 tokens; reverse, an odd tile starts at its own.
 #pragma unroll
-    for (int ks = (REV && TI::ODD) ? 2 : 0; ks < ((!REV && !TI::ODD) ? 2 : 4); ++ks) {
+    for (int ks = 0; ks < 4; ++ks) {
+        if (REV ? (odd && ks < 2) : (!odd && ks >= 2)) continue;
         const int k0 = I * BLK + 16 * ks;
-        const bf16x8 gv = gf[GOFF + 4 * I + ks - TI::KS0];
+        const bf16x8 gv = gd[ks];
         const int kk0 = k0 + 8 * (lane >> 5);
         const float4 ca = *(const float4*)(L.cum2 + kk0), cb = *(const float4*)(L.cum2 + kk0 + 4);
         const float cv[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
@@ -216,14 +216,21 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const b
         acc1 = mfma(frag_tr(L.raw, XPITCH, k0, 32, lane), fb, acc1);
     }
     // epilogue: in the accumulators this lane owns token `tok` and, per register group q, four
-    // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses
+    // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses.
+    // The wave's own 32 rows of the other token-major tensor come in as whole rows (EPI 1: dY, EPI 2: x).
     if (EPI != 0) {
+        const bf16_t* src = EPI == 1 ? cx.dyg : cx.xg;
+        bf16x8 own[4];
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            own[it] = *(const bf16x8*)(src + (int64_t)(tok0 + (lane >> 3) + 8 * it) * cx.xt + (lane & 7) * 8);
 #pragma unroll
         for (int it = 0; it < 4; ++it) *(bf16x8*)(priv + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = own[it];
         lds_wave_fence();
     }
     float s_a = 0.f, s_b = 0.f;
     const float dtok = REV ? L.dtl[tok] : 0.f;
+    const float gt_old = EPI == 2 ? cx.gterm[tok] : 0.f;
     bf16x4 outv[8];
 #pragma unroll
     for (int pt = 0; pt < 2; ++pt) {
@@ -263,7 +270,7 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const b
         for (int it = 0; it < 4; ++it) {
             const int row = (lane >> 3) + 8 * it;
             const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
-            *(bf16x8*)(cx.outp + (int64_t)(TI::TOK0 + row) * cx.xt + (lane & 7) * 8) = v;
+            *(bf16x8*)(cx.outp + (int64_t)(tok0 + row) * cx.xt + (lane & 7) * 8) = v;
         }
     }
     if (EPI != 0) {
@@ -273,39 +280,11 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&gf)[GF_MAX], const b
             if (EPI == 1) {
                 cx.gterm[tok] = s_a;
             } else {
-                cx.gterm[tok] = cx.gterm[tok] - dtok * s_a;
+                cx.gterm[tok] = gt_old - dtok * s_a;
                 cx.fterm[tok] = s_a;
                 cx.dDrow[tok] = s_b;
             }
         }
-    }
-}
-
-// Wave w owns tiles w and NT - 1 - w.  PHASE 0 fetches the persistent fragments, PHASE 1 computes one head.
-template <int Q, int EPI, int PHASE, int W>
-__device__ __forceinline__ void wave_phase(bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat, const bf16_t* rowop,
-                                           int64_t bt, DualLds<Q>& L, const HeadCtx& cx, int lane) {
-    constexpr int NT = Q / 32, TA = W, TB = NT - 1 - W;
-    if constexpr (W < NT / 2) {
-        constexpr int GO = DualTile<Q, EPI, TA>::NFR;
-        if constexpr (PHASE == 0) {
-            tile_load<Q, EPI, TA, 0, 0>(gf, rf, Mat, rowop, bt, lane);
-            tile_load<Q, EPI, TB, GO, RF_N>(gf, rf, Mat, rowop, bt, lane);
-        } else {
-            tile_compute<Q, EPI, TA, 0, 0>(gf, rf, L, cx, lane, W);
-            tile_compute<Q, EPI, TB, GO, RF_N>(gf, rf, L, cx, lane, W);
-        }
-    }
-}
-
-template <int Q, int EPI, int PHASE>
-__device__ __forceinline__ void wave_dispatch(int w, bf16x8 (&gf)[GF_MAX], bf16x8 (&rf)[2 * RF_N], const bf16_t* Mat,
-                                              const bf16_t* rowop, int64_t bt, DualLds<Q>& L, const HeadCtx& cx, int lane) {
-    switch (w) {
-        case 0: wave_phase<Q, EPI, PHASE, 0>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
-        case 1: wave_phase<Q, EPI, PHASE, 1>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
-        case 2: wave_phase<Q, EPI, PHASE, 2>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
-        default: wave_phase<Q, EPI, PHASE, 3>(gf, rf, Mat, rowop, bt, L, cx, lane); break;
     }
 }
 
@@ -321,16 +300,18 @@ __global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
     z /= ns;
     const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
     const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
+    // Q = 256: waves w and w + 4 share a SIMD and take tiles t and 7 - t (equal causal work per SIMD)
+    const int T = (Q == 256 && w >= 4) ? 11 - w : w;
     const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
 
     const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
     const bf16_t* Mat = REV ? Gd + Q * Q : Gd;  // rows = output token, columns = contraction token
     const bf16_t* rowop = (REV ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
                           ((int64_t)c * Q * sp.G + g) * N_;
-    bf16x8 gf[GF_MAX], rf[2 * RF_N];
+    bf16x8 go[GO_MAX], gd[4], rf[RF_N];
     HeadCtx cx;
-    wave_dispatch<Q, EPI, 0>(w, gf, rf, Mat, rowop, bt, L, cx, lane);
+    tile_load<Q, REV>(go, gd, rf, Mat, rowop, bt, T, lane);
     Pre<Q> pr;
     load_pre<Q, REV>(pr, sp, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
@@ -350,7 +331,7 @@ __global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
         cx.dDrow = sp.dDrow + cbase;
         cx.xt = xt;
         cx.Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
-        wave_dispatch<Q, EPI, 1>(w, gf, rf, Mat, rowop, bt, L, cx, lane);
+        tile_compute<Q, EPI>(go, gd, rf, L, cx, T, lane, w);
     }
 }
 
