@@ -53,7 +53,7 @@ struct DualLds {
 template <int Q>
 struct Pre {
     bf16x8 xt[DualCfg<Q>::XV];
-    float sc[DualCfg<Q>::XV];
+    float sc[DualCfg<Q>::XV], sc2[DualCfg<Q>::XV];  // per-token scale factors, multiplied at staging time
     bf16x8 sv[DualCfg<Q>::SV];
     float cum, dtf, fac;
 };
@@ -86,7 +86,8 @@ __device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b,
     for (int k = 0; k < CF::XV; ++k) {
         const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
         pr.xt[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-        pr.sc[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row] * sp.eout[cbase + row];
+        pr.sc[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row];
+        if (!REV) pr.sc2[k] = sp.eout[cbase + row];
     }
     const bf16_t* S = (REV ? sp.dstates_bf : sp.states_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
 #pragma unroll
@@ -108,7 +109,7 @@ __device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int t
     for (int k = 0; k < CF::XV; ++k) {
         const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
         *(bf16x8*)(L.raw + row * XPITCH + seg * 16) = pr.xt[k];
-        *(bf16x8*)(L.scl + row * XPITCH + seg * 16) = scale8(pr.xt[k], pr.sc[k]);
+        *(bf16x8*)(L.scl + row * XPITCH + seg * 16) = scale8(pr.xt[k], REV ? pr.sc[k] : pr.sc[k] * pr.sc2[k]);
     }
 #pragma unroll
     for (int k = 0; k < CF::SV; ++k) {

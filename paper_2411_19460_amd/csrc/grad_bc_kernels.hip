@@ -205,7 +205,8 @@ struct PartLds {
 template <int Q>
 struct PartPre {
     bf16x8 t[PartCfg<Q>::TV];
-    float sc[PartCfg<Q>::TV];
+    float cv[PartCfg<Q>::TV], dv[PartCfg<Q>::TV];  // cum and dt of the vector's token
+    float T;                                       // cum at the end of the chunk
     bf16x8 sv[PartCfg<Q>::SV];
 };
 
@@ -217,13 +218,14 @@ __device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, i
     const bf16_t* src = role == 0 ? (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow
                                   : (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-    const float T_ = sp.cum[cbase + Q - 1];
+    // loads only: no arithmetic on the loaded values here, so that nothing waits for them early
+    pr.T = sp.cum[cbase + Q - 1];
 #pragma unroll
     for (int k = 0; k < CF::TV; ++k) {
         const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
         pr.t[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-        const float cv = sp.cum[cbase + row];
-        pr.sc[k] = role == 0 ? __expf(cv) : __expf(T_ - cv) * sp.dtf[cbase + row];
+        pr.cv[k] = sp.cum[cbase + row];
+        pr.dv[k] = sp.dtf[cbase + row];
     }
     const bf16_t* S = (role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
 #pragma unroll
@@ -231,12 +233,13 @@ __device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, i
 }
 
 template <int Q>
-__device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, int tid) {
+__device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, int role, int tid) {
     typedef PartCfg<Q> CF;
 #pragma unroll
     for (int k = 0; k < CF::TV; ++k) {
         const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
-        *(bf16x8*)(L.tile + row * XPITCH + seg * 16) = scale8(pr.t[k], pr.sc[k]);
+        const float wgt = role == 0 ? __expf(pr.cv[k]) : __expf(pr.T - pr.cv[k]) * pr.dv[k];
+        *(bf16x8*)(L.tile + row * XPITCH + seg * 16) = scale8(pr.t[k], wgt);
     }
 #pragma unroll
     for (int k = 0; k < CF::SV; ++k) {
@@ -266,7 +269,7 @@ __global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
     part_load<Q>(pr, sp, role, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
         __syncthreads();
-        part_store<Q>(pr, L, tid);
+        part_store<Q>(pr, L, role, tid);
         __syncthreads();
         if (hh + 1 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 1, tid);
 #pragma unroll

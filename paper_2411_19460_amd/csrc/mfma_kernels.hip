@@ -94,54 +94,96 @@ __global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// MODE 0: states[b,c,h]  = sum_j exp(T - cum_j) dt_j x_j (x) B_j      (chunk state, fp32 [P][N])
-// MODE 1: dstates[b,c,h] = sum_i exp(cum_i) dY_i (x) C_i              (local state adjoint)
-// Both operands are token-major: staged per 64-token slab in LDS, read with transpose loads.
-template <int Q, int MODE>
-__global__ __launch_bounds__(NTH) void mk_chunk_outer(SegParams sp) {
-    __shared__ __attribute__((aligned(16))) char xs[BLK * XPITCH];
-    __shared__ __attribute__((aligned(16))) char bs[BLK * BPITCH];
-    const int z = blockIdx.x, h = z % sp.H, c = (z / sp.H) % sp.nc, b = z / (sp.H * sp.nc);
-    const int g = h / sp.hpg, tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+// role 0: states[b,c,h]  = sum_j exp(T - cum_j) dt_j x_j (x) B_j      (chunk state, fp32 [P][N])
+// role 1: dstates[b,c,h] = sum_i exp(cum_i) dY_i (x) C_i              (local state adjoint)
+// One workgroup per (batch, chunk, group, role, head slice); eight waves, wave w owning the 32 x 32
+// output tile (p half w / 4, state columns 32 (w % 4)).  The B (or C) rows of the chunk do not depend on
+// the head: they go through LDS once and each wave keeps its Q/16 operand fragments in registers
+// for every head of the slice.  Per head the token-major tile (x or dY, weighted per token) is
+// prefetched in registers during the previous head, staged in LDS and read with transpose loads.
+template <int Q>
+struct OuterLds {
+    char bc[Q * BPITCH];  // B or C rows of the chunk (prologue only)
+    char xt[Q * XPITCH];  // weight * x or weight * dY
+};
+
+constexpr int OUTER_THR = 512;
+
+template <int Q>
+struct OuterPre {
+    static constexpr int NV = Q * 8 / OUTER_THR > 0 ? Q * 8 / OUTER_THR : 1;
+    bf16x8 t[NV];
+    float cv[NV], dv[NV];  // cum and dt of the vector's token
+    float T;               // cum at the end of the chunk
+};
+
+// Loads only: no arithmetic on the loaded values here, so that nothing waits for them before the
+// next head's staging (the weights are formed in outer_weight at that point).
+template <int Q>
+__device__ __forceinline__ void outer_load(OuterPre<Q>& pr, const SegParams& sp, int role, int b, int c, int h, int tid) {
+    const int64_t xt = (int64_t)sp.H * P_;
+    const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
+    const bf16_t* src = role == 0 ? (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow
+                                  : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-    const float* cum = sp.cum + cbase;
-    const float* dtf = sp.dtf + cbase;
-    const float T_ = cum[Q - 1];
-    const int64_t xt = (int64_t)sp.H * P_, bt = (int64_t)sp.G * N_;
-    const bf16_t* lhs = MODE == 0 ? (const bf16_t*)sp.x + (int64_t)b * sp.xs_b : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b;
-    lhs += ((int64_t)c * Q * sp.H + h) * P_;
-    const bf16_t* rhs = (MODE == 0 ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b +
-                        ((int64_t)c * Q * sp.G + g) * N_;
-    f32x16 acc0 = zero16(), acc1 = zero16();
-    for (int s0 = 0; s0 < Q; s0 += BLK) {
-        __syncthreads();
+    pr.T = sp.cum[cbase + Q - 1];
 #pragma unroll
-        for (int k = 0; k < 2; ++k) {  // 64 rows x 8 vectors of 16 B
-            const int v = tid + NTH * k, row = v >> 3, seg = v & 7, tok = s0 + row;
-            const float wgt = MODE == 0 ? __expf(T_ - cum[tok]) * dtf[tok] : __expf(cum[tok]);
-            const bf16x8 in = *(const bf16x8*)(lhs + (int64_t)tok * xt + seg * 8);
-            *(bf16x8*)(xs + row * XPITCH + seg * 16) = scale8(in, wgt);
-        }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {  // 64 rows x 16 vectors of 16 B
-            const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
-            *(bf16x8*)(bs + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)(s0 + row) * bt + seg * 8);
-        }
-        __syncthreads();
-#pragma unroll
-        for (int ks = 0; ks < BLK / 16; ++ks) {
-            const bf16x8 fb = frag_tr(bs, BPITCH, 16 * ks, 32 * w, lane);
-            acc0 = mfma(frag_tr(xs, XPITCH, 16 * ks, 0, lane), fb, acc0);
-            acc1 = mfma(frag_tr(xs, XPITCH, 16 * ks, 32, lane), fb, acc1);
-        }
+    for (int k = 0; k < OuterPre<Q>::NV; ++k) {
+        const int v = (tid + OUTER_THR * k) % (Q * 8), row = v >> 3, seg = v & 7;
+        pr.t[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
+        pr.cv[k] = sp.cum[cbase + row];
+        pr.dv[k] = sp.dtf[cbase + row];
     }
-    float* out = MODE == 0 ? sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * (P_ * N_)
-                           : sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+}
+
+template <int Q>
+__device__ __forceinline__ float outer_weight(const OuterPre<Q>& pr, int role, int k) {
+    return role == 0 ? __expf(pr.T - pr.cv[k]) * pr.dv[k] : __expf(pr.cv[k]);
+}
+
+template <int Q>
+__global__ __launch_bounds__(OUTER_THR) void mk_chunk_outer(SegParams sp, int nroles) {
+    constexpr int KS = Q / 16;
+    __shared__ __attribute__((aligned(16))) OuterLds<Q> L;
+    int z = blockIdx.x;
+    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    const int ns = sp.outer_split, slice = z % ns;
+    z /= ns;
+    const int role = z % nroles;
+    z /= nroles;
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), ph = w >> 2, nt = w & 3;
+    const int64_t bt = (int64_t)sp.G * N_;
+    OuterPre<Q> pr;
+    outer_load<Q>(pr, sp, role, b, c, h0, tid);
+    // prologue: B (role 0) or C (role 1) rows -> LDS -> this wave's fragments
+    const bf16_t* rhs = (role == 0 ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
+    for (int v = tid; v < Q * 16; v += OUTER_THR) {
+        const int row = v >> 4, seg = v & 15;
+        *(bf16x8*)(L.bc + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)row * bt + seg * 8);
+    }
+    __syncthreads();
+    bf16x8 fb[KS];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int p = acc_row(r, lane), n = 32 * w + (lane & 31);
-        out[p * N_ + n] = acc0[r];
-        out[(p + 32) * N_ + n] = acc1[r];
+    for (int ks = 0; ks < KS; ++ks) fb[ks] = frag_tr(L.bc, BPITCH, 16 * ks, 32 * nt, lane);
+    for (int hh = 0; hh < hps; ++hh) {
+        const int h = h0 + hh;
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < OuterPre<Q>::NV; ++k) {
+            const int v = tid + OUTER_THR * k, row = v >> 3, seg = v & 7;
+            if (v < Q * 8) *(bf16x8*)(L.xt + row * XPITCH + seg * 16) = scale8(pr.t[k], outer_weight<Q>(pr, role, k));
+        }
+        __syncthreads();
+        if (hh + 1 < hps) outer_load<Q>(pr, sp, role, b, c, h + 1, tid);
+        f32x16 acc = zero16();
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) acc = mfma(frag_tr(L.xt, XPITCH, 16 * ks, 32 * ph, lane), fb[ks], acc);
+        float* out = role == 0 ? sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * (P_ * N_)
+                               : sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = acc[r];
     }
 }
 
@@ -234,7 +276,12 @@ template <int Q>
 hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
     constexpr int NB = Q / BLK;
     SSDK_LAUNCH(K_CUMSUM, st, mk_prep<Q>, dim3(sp.nc, sp.H, sp.Bt), dim3(Q), sp);
-    SSDK_LAUNCH(K_MFMA_CHUNK_STATE, st, (mk_chunk_outer<Q, 0>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
+    {   // chunk states; on the backward path (need_y false) the local state adjoints ride in the same launch
+        SegParams so = sp;
+        const int nroles = need_y ? 1 : 2;
+        so.outer_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G * nroles, 256);
+        SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, mk_chunk_outer<Q>, dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
+    }
     SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
     // the scan is the only step that needs the previous segment (its leaving state)
     if (need_y && sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
@@ -251,7 +298,6 @@ template <int Q>
 hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     SegParams sp = sp0;
     sp.nslice = P_ * N_ / 4 / 64;  // partial sums written by mk_scan_bwd: one per wave
-    SSDK_LAUNCH(K_MFMA_DSTATE, st, (mk_chunk_outer<Q, 1>), dim3(sp.Bt * sp.nc * sp.H), dim3(NTH), sp);
     // the reverse scan is the only step that needs the segment to the right (its entering-state adjoint)
     if (sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
     SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);

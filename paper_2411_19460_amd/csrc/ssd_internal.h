@@ -80,6 +80,7 @@ struct SegParams {
     int dg_split;        // number of head slices whose dG / dB / dC partial sums are kept apart
     int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
     int part_split;      // number of head slices of the dB / dC head sums
+    int outer_split;     // number of head slices of the chunk-state / local-adjoint kernel
     float* dbc_part;     // [Bt][nc][G][part_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
