@@ -84,8 +84,8 @@ enum {
 
 /* Bytes of scratch the call needs for this shape (device memory, 256-byte aligned, contents
  * undefined before and after).  It scales with `segment`, not with `seqlen`: this is the
- * per-segment recomputation store (the M_state term of App. C) -- two of them when there is more
- * than one segment, because two segments are kept in flight -- plus, for the backward pass, eight
+ * per-segment recomputation store (the M_state term of App. C) -- one per segment in flight, up
+ * to four when the sequence has that many segments -- plus, for the backward pass, eight
  * bytes per (chunk, head) of the whole sequence for the partial sums of dA and dD.
  * Returns 0 for an invalid shape. */
 size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward);

@@ -175,14 +175,15 @@ static void wire_states(SegParams& sp, const Dims& d, int64_t k, const float* in
     }
 }
 
-// ---- two segments in flight ------------------------------------------------------------------
+// ---- several segments in flight ---------------------------------------------------------------
 // Consecutive segments depend on each other only through the state scan.  With more than one
-// segment, even segments run on the caller's stream and odd segments on an internal stream (default
-// priority), each with its own per-segment scratch; events order the scans.  This overlaps one
-// segment's launch gaps, tails and bandwidth-bound kernels with the other's matrix work.
+// segment, segment k runs on lane k % NPIPE -- lane 0 is the caller's stream, the others are internal
+// streams (default priority) -- each lane with its own per-segment scratch; events order the scans.
+// This overlaps one segment's launch gaps, tails and bandwidth-bound kernels with another's matrix work.
+constexpr int NPIPE = 4;  // segments in flight (the caller's stream + NPIPE - 1 internal ones)
 struct Pipe {
-    hipStream_t aux = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr, scan[2] = {nullptr, nullptr};
+    hipStream_t aux[NPIPE] = {};       // aux[0] is unused: lane 0 is the caller's stream
+    hipEvent_t fork = nullptr, join[NPIPE] = {}, scan[NPIPE] = {};
     bool ok = false;
 };
 
@@ -192,10 +193,12 @@ static Pipe* pipe_for_current_device() {
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
     Pipe& p = pipes[dev];
     if (!p.ok) {
-        if (hipStreamCreateWithFlags(&p.aux, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        hipEvent_t* ev[4] = {&p.fork, &p.join, &p.scan[0], &p.scan[1]};
-        for (hipEvent_t* e : ev)
-            if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&p.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+        for (int i = 0; i < NPIPE; ++i) {
+            if (i > 0 && hipStreamCreateWithFlags(&p.aux[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&p.join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+            if (hipEventCreateWithFlags(&p.scan[i], hipEventDisableTiming) != hipSuccess) return nullptr;
+        }
         p.ok = true;
     }
     return &p;
@@ -206,12 +209,27 @@ static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d
 
 // SSD_MAGC_SERIAL=1 in the environment keeps every segment on the caller's stream (diagnostics: per-kernel
 // timings are only meaningful when kernels do not overlap).
-static bool pipelined(const Dims& d, bool mfma) {
+static int lanes(const Dims& d, bool mfma) {
     static const bool serial = [] {
         const char* v = getenv("SSD_MAGC_SERIAL");
         return v && v[0] == '1';
     }();
-    return mfma && d.nseg > 1 && !serial;
+    if (!mfma || serial || d.nseg <= 1) return 1;
+    return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
+}
+
+static bool fork_lanes(Pipe* pp, int n, hipStream_t st) {
+    if (n <= 1) return true;
+    if (hipEventRecord(pp->fork, st) != hipSuccess) return false;
+    for (int i = 1; i < n; ++i)
+        if (hipStreamWaitEvent(pp->aux[i], pp->fork, 0) != hipSuccess) return false;
+    return true;
+}
+
+static bool join_lanes(Pipe* pp, int n, hipStream_t st) {
+    for (int i = 1; i < n; ++i)
+        if (hipEventRecord(pp->join[i], pp->aux[i]) != hipSuccess || hipStreamWaitEvent(st, pp->join[i], 0) != hipSuccess) return false;
+    return true;
 }
 
 }  // namespace ssdk
@@ -223,7 +241,7 @@ extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backw
     if (check_shape(shape, &d) != SSD_OK) return 0;
     // never 0 for a valid shape, so that 0 unambiguously means "invalid"
     const size_t block = align_up(ws_layout(d, is_backward != 0).total);
-    const size_t t = (pipelined(d, use_mfma(*shape, 0)) ? 2 : 1) * block + (is_backward ? shared_bytes(d) : 0);
+    const size_t t = lanes(d, use_mfma(*shape, 0)) * block + (is_backward ? shared_bytes(d) : 0);
     return t ? t : 256;
 }
 
@@ -249,24 +267,24 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const WsLayout w = ws_layout(d, false);
     const bool mfma = use_mfma(*shape, flags);
-    const bool two = pipelined(d, mfma);
+    const int nl = lanes(d, mfma);
     const size_t block = align_up(w.total);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (two ? 2 : 1) * block) return SSD_ERR_WORKSPACE;
-    Pipe* pp = two ? pipe_for_current_device() : nullptr;
-    if (two && !pp) return SSD_ERR_LAUNCH;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block) return SSD_ERR_WORKSPACE;
+    Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
+    if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
 
-    SegParams sps[2];
-    for (int i = 0; i < (two ? 2 : 1); ++i) {
+    SegParams sps[NPIPE];
+    for (int i = 0; i < nl; ++i) {
         base_params(sps[i], d, flags);
         bind_workspace(sps[i], w, (char*)workspace + i * block, false);
         sps[i].A = A;
         sps[i].D = D;
     }
-    if (two && (hipEventRecord(pp->fork, st) != hipSuccess || hipStreamWaitEvent(pp->aux, pp->fork, 0) != hipSuccess))
-        return SSD_ERR_LAUNCH;
+    if (!fork_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     for (int64_t k = 0; k < d.nseg; ++k) {
-        SegParams& sp = sps[two ? (k & 1) : 0];
-        hipStream_t sk = (two && (k & 1)) ? pp->aux : st;
+        const int ln = (int)(k % nl);
+        SegParams& sp = sps[ln];
+        hipStream_t sk = ln ? pp->aux[ln] : st;
         const int64_t t0 = k * d.s;
         sp.x = off(x, t0 * d.H * d.P, d.esz);
         sp.y = off(y, t0 * d.H * d.P, d.esz);
@@ -274,13 +292,12 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.Bm = off(B, t0 * d.G * d.N, d.esz);
         sp.Cm = off(C, t0 * d.G * d.N, d.esz);
         wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
-        sp.ev_wait = (two && k > 0) ? pp->scan[(k - 1) & 1] : nullptr;
-        sp.ev_record = (two && k + 1 < d.nseg) ? pp->scan[k & 1] : nullptr;
+        sp.ev_wait = (nl > 1 && k > 0) ? pp->scan[(k - 1) % nl] : nullptr;
+        sp.ev_record = (nl > 1 && k + 1 < d.nseg) ? pp->scan[ln] : nullptr;
         hipError_t e = mfma ? mfma_forward_segment(sp, true, sk) : generic_forward_segment(sp, d.bf16, true, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
     }
-    if (two && (hipEventRecord(pp->join, pp->aux) != hipSuccess || hipStreamWaitEvent(st, pp->join, 0) != hipSuccess))
-        return SSD_ERR_LAUNCH;
+    if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     return SSD_OK;
 }
 
@@ -312,17 +329,16 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const WsLayout w = ws_layout(d, true);
     const bool mfma = use_mfma(*shape, flags);
-    const bool two = pipelined(d, mfma);
+    const int nl = lanes(d, mfma);
     const size_t block = align_up(w.total);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (two ? 2 : 1) * block + shared_bytes(d))
-        return SSD_ERR_WORKSPACE;
-    Pipe* pp = two ? pipe_for_current_device() : nullptr;
-    if (two && !pp) return SSD_ERR_LAUNCH;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d)) return SSD_ERR_WORKSPACE;
+    Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
+    if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
 
     // shared by both scratch blocks: the carried state adjoint and the dA / dD partial sums of every chunk
-    float* part_all = (float*)((char*)workspace + (two ? 2 : 1) * block);
-    SegParams sps[2];
-    for (int i = 0; i < (two ? 2 : 1); ++i) {
+    float* part_all = (float*)((char*)workspace + nl * block);
+    SegParams sps[NPIPE];
+    for (int i = 0; i < nl; ++i) {
         SegParams& sp = sps[i];
         base_params(sp, d, flags);
         bind_workspace(sp, w, (char*)workspace + i * block, true);
@@ -339,11 +355,11 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     hipError_t e = dfinal_state ? launch_copy_f32(sps[0].dcarry, dfinal_state, (size_t)d.Bt * HPN, st)
                                 : launch_fill_zero(sps[0].dcarry, (size_t)d.Bt * HPN, st);
     if (e != hipSuccess) return SSD_ERR_LAUNCH;
-    if (two && (hipEventRecord(pp->fork, st) != hipSuccess || hipStreamWaitEvent(pp->aux, pp->fork, 0) != hipSuccess))
-        return SSD_ERR_LAUNCH;
+    if (!fork_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     for (int64_t k = d.nseg - 1, it = 0; k >= 0; --k, ++it) {
-        SegParams& sp = sps[two ? (it & 1) : 0];
-        hipStream_t sk = (two && (it & 1)) ? pp->aux : st;
+        const int ln = (int)(it % nl);
+        SegParams& sp = sps[ln];
+        hipStream_t sk = ln ? pp->aux[ln] : st;
         const int64_t t0 = k * d.s;
         sp.x = off(x, t0 * d.H * d.P, d.esz);
         sp.dy = off(dy, t0 * d.H * d.P, d.esz);
@@ -361,13 +377,12 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         e = mfma ? mfma_forward_segment(sp, false, sk) : generic_forward_segment(sp, d.bf16, false, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
         sp.dinit_out = (k == 0) ? dinit_state : nullptr;
-        sp.ev_wait = (two && it > 0) ? pp->scan[(it - 1) & 1] : nullptr;
-        sp.ev_record = (two && k > 0) ? pp->scan[it & 1] : nullptr;
+        sp.ev_wait = (nl > 1 && it > 0) ? pp->scan[(it - 1) % nl] : nullptr;
+        sp.ev_record = (nl > 1 && k > 0) ? pp->scan[ln] : nullptr;
         e = mfma ? mfma_backward_segment(sp, sk) : generic_backward_segment(sp, d.bf16, sk);
         if (e != hipSuccess) return SSD_ERR_LAUNCH;
     }
-    if (two && (hipEventRecord(pp->join, pp->aux) != hipSuccess || hipStreamWaitEvent(st, pp->join, 0) != hipSuccess))
-        return SSD_ERR_LAUNCH;
+    if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     sps[0].accumulate = (flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0;
     if (launch_param_reduce(sps[0], st) != hipSuccess) return SSD_ERR_LAUNCH;
     return SSD_OK;

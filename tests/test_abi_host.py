@@ -39,8 +39,10 @@ def test_workspace_query_and_shape_validation():
     assert pk.ssd_workspace_bytes(shape(), True) > pk.ssd_workspace_bytes(shape(), False)
     # workspace follows the segment, not the sequence length: forward exactly; backward up to the two
     # per-chunk partial sums of dA and dD (8 bytes per chunk and head, 256-byte rounding)
-    assert pk.ssd_workspace_bytes(shape(seqlen=1 << 20, segment=1024), False) == pk.ssd_workspace_bytes(shape(), False)
-    extra = pk.ssd_workspace_bytes(shape(seqlen=1 << 20, segment=1024), True) - pk.ssd_workspace_bytes(shape(), True)
+    # (compared at the same number of segments in flight: both sequences have at least four segments)
+    short, long_ = shape(seqlen=8192, segment=1024), shape(seqlen=1 << 20, segment=1024)
+    assert pk.ssd_workspace_bytes(long_, False) == pk.ssd_workspace_bytes(short, False)
+    extra = pk.ssd_workspace_bytes(long_, True) - pk.ssd_workspace_bytes(short, True)
     assert 0 <= extra <= 2 * 4 * 8 * ((1 << 20) // 256) + 512
     for bad in (dict(dtype=7), dict(nheads=0), dict(seqlen=2000), dict(segment=1000), dict(ngroups=3),
                 dict(chunk=2048), dict(headdim=512), dict(batch=0)):
