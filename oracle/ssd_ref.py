@@ -97,9 +97,11 @@ def ssd_bwd(x, dt, A, B, C, D, dy, init_state=None, dfinal_state=None, head_grou
     return {"dx": dx, "ddt": ddt, "dA": dA, "dB": dB, "dC": dC, "dD": dD, "dinit_state": dinit}
 
 
-def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None):
+def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None, store=None):
     """Residual stack: x_{j+1} = x_j + SSD_j(x_j).  `layers` is a list of dicts with
-    dt, A, B, C, D.  Everything stays in fp64 between layers.
+    dt, A, B, C, D.  `store`, if given, is the rounding of the storage dtype (e.g. round to
+    bf16): the stack keeps its activations in that dtype, so every x_{j+1} is rounded once
+    when it is stored; with store=None everything stays in fp64 between layers.
     Returns dict(out, xs=[x_0..x_{n-1}], final_states, boundary_states)."""
     x = _f64(x0)
     xs, fins, bnds = [], [], []
@@ -108,13 +110,16 @@ def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None):
         r = ssd_fwd(x, lay["dt"], lay["A"], lay["B"], lay["C"], lay["D"],
                     None if init_states is None else init_states[j], segment, head_group)
         x = x + r["y"]
+        if store is not None:
+            x = _f64(store(x))
         fins.append(r["final_state"])
         bnds.append(r["boundary_states"])
     return {"out": x, "xs": xs, "final_states": fins, "boundary_states": bnds}
 
 
-def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group=None):
-    """Backward of stack_fwd given the layer inputs xs[j]: dx_j = dx_{j+1} + VJP_j(dx_{j+1}).
+def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group=None, store=None):
+    """Backward of stack_fwd given the layer inputs xs[j]: dx_j = dx_{j+1} + VJP_j(dx_{j+1}),
+    each dx_j rounded once by `store` (the storage dtype of the activation gradients) if given.
     Returns dict(dx0, grads=[per-layer dict of ddt, dA, dB, dC, dD, dinit_state])."""
     g = _f64(dout)
     grads = [None] * len(layers)
@@ -124,5 +129,7 @@ def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group
                     None if init_states is None else init_states[j],
                     None if dfinal_states is None else dfinal_states[j], head_group)
         g = g + r.pop("dx")
+        if store is not None:
+            g = _f64(store(g))
         grads[j] = r
     return {"dx0": g, "grads": grads}

@@ -83,6 +83,8 @@ WsLayout ws_layout(const Dims& d, bool bwd) {
         }
         w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.part_split * 2 * d.Q * d.N * 4);
         w.gterm = take(tok);
+        w.sterm = take(tok);
+        w.gintra = take(tok);
         w.fterm = take(tok);
         w.dDrow = take(tok);
         w.tail_part = take((size_t)d.Bt * d.H * d.nc * w.nslice * 4);
@@ -112,6 +114,8 @@ void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd)
         sp.dstates = (float*)(base + w.dstates);
         sp.dG = (float*)(base + w.dG);
         sp.gterm = (float*)(base + w.gterm);
+        sp.sterm = (float*)(base + w.sterm);
+        sp.gintra = (float*)(base + w.gintra);
         sp.fterm = (float*)(base + w.fterm);
         sp.dDrow = (float*)(base + w.dDrow);
         sp.tail_part = (float*)(base + w.tail_part);

@@ -356,7 +356,30 @@ __global__ void k_ddt_finalize(SegParams sp) {
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
     // reverse order so that an inclusive forward scan yields the suffix sums
     const int ri = Q - 1 - i;
-    s[i] = (i < Q) ? sp.gterm[cbase + ri] : 0.f;
+    // Matrix-core path: the gradient of cum_i arrives as gterm_i + gintra_i - sterm_i, and the gradient of
+    // cum at the chunk end carries + sum_j sterm_j (the chunk state depends on T - cum_j): the very same
+    // sterm values enter with both signs, so their cancellation in the suffix sums is exact.
+    float gt = 0.f, st_sum = 0.f;
+    const bool split = sp.flags & SSD_INTERNAL_SPLIT_GTERM;
+    if (i < Q) {
+        gt = sp.gterm[cbase + ri];
+        if (split) {
+            const float sv = sp.sterm[cbase + ri];
+            gt += sp.gintra[cbase + ri] - sv;
+            st_sum = sv;
+        }
+    }
+    if (split) {
+        s2[i] = st_sum;
+        __syncthreads();
+        for (int off = blockDim.x >> 1; off > 0; off >>= 1) {
+            if (i < off) s2[i] += s2[i + off];
+            __syncthreads();
+        }
+        st_sum = s2[0];
+        __syncthreads();
+    }
+    s[i] = gt;
     __syncthreads();
     for (int off = 1; off < (int)blockDim.x; off <<= 1) {
         const float v = (i >= off) ? s[i - off] : 0.f;
@@ -367,6 +390,7 @@ __global__ void k_ddt_finalize(SegParams sp) {
     float tail = 0.f;
     const float* tp = sp.tail_part + ((((int64_t)b * sp.H + h) * sp.nc + c)) * sp.nslice;
     for (int k = 0; k < sp.nslice; ++k) tail += tp[k];
+    tail += st_sum;
     float pa = 0.f, pd = 0.f;
     if (i < Q) {
         const float da = s[i] + tail;  // belongs to token ri

@@ -7,7 +7,10 @@
 //   mk_dG       : one workgroup per (batch, chunk, group, head slice); the whole lower triangle of dG
 //                 (36 tiles of 32 x 32 when Q = 256, four or five per wave) stays in accumulators while the workgroup walks
 //                 the heads of its slice; dY and x tiles are staged in LDS once per head (next head
-//                 prefetched in registers).  Writes one bf16 partial sum per slice.
+//                 prefetched in registers).  Writes one bf16 partial sum per slice and, per head, the
+//                 chunk-local part of the gradient of cum: row sums minus column sums of
+//                 E = (dY x^T) (.) M, each element entering both with the same value, so that their
+//                 cancellation in the reverse cumulative sum is exact.
 //   mk_dBC_part : the two head sums on the right, same organisation, accumulators [Q x 128] per
 //                 (chunk, role, slice); the per-token weight is folded into the staged operand.
 //   mk_dBC_final: sums the slices, contracts dG with B / dG^T with C, adds the head sums, rounds once.
@@ -27,26 +30,31 @@ __device__ __forceinline__ bf16x8 lds_rows(const char* tile, int pitch, int row0
 }
 
 // ---------------------------------------------------------------------------------------------
-// Which 32 x 32 tiles (ti, tj <= ti) of the lower triangle each wave of mk_dG owns.  Q = 256: sixteen
-// waves of two or three tiles (many light waves per SIMD hide the LDS and MFMA latencies that one
-// heavy wave exposes).  Smaller chunks: wave v owns tile row v.
+// Which 32 x 32 tiles (ti, tj <= ti) of the lower triangle each wave of mk_dG owns, as runs of tiles
+// of one tile row (at most two runs per wave).  Q = 256: eight waves; waves v and v + 4 run on the same
+// SIMD and together hold tile rows 7 - v and v (nine tiles per SIMD, at most five per wave).  Smaller
+// chunks: wave v owns tile row v.  slot0(v) is the index of the wave's first tile in a flat numbering.
 template <int Q>
 struct DgMap {
-    static constexpr int NT = Q / 32, NWV = NT, MAXT = NT;
+    static constexpr int NT = Q / 32, NWV = NT, MAXT = NT, NSLOT = NT * (NT + 1) / 2;
     static __device__ __forceinline__ int count(int v) { return v + 1; }
     static __device__ __forceinline__ int ti(int v, int) { return v; }
     static __device__ __forceinline__ int tj(int, int k) { return k; }
+    static __device__ __forceinline__ int slot0(int v) { return v * (v + 1) / 2; }
 };
 template <>
 struct DgMap<256> {
-    // sixteen waves; the four waves of a SIMD (v, v + 4, v + 8, v + 12) hold nine tiles, two of them diagonal
-    static constexpr int NT = 8, NWV = 16, MAXT = 3;
-    static constexpr int CNT[16] = {2, 2, 2, 2, 2, 2, 2, 2, 3, 3, 3, 3, 2, 2, 2, 2};
-    static constexpr int TI[16][3] = {{0, 1, 0}, {1, 2, 0}, {2, 2, 0}, {3, 3, 0}, {4, 4, 0}, {5, 5, 0}, {6, 6, 0}, {7, 7, 0}, {3, 3, 4}, {4, 4, 5}, {5, 5, 5}, {6, 6, 6}, {6, 6, 0}, {7, 7, 0}, {7, 7, 0}, {7, 7, 0}};
-    static constexpr int TJ[16][3] = {{0, 0, 0}, {1, 1, 0}, {2, 0, 0}, {3, 2, 0}, {4, 3, 0}, {5, 4, 0}, {6, 5, 0}, {7, 6, 0}, {0, 1, 0}, {1, 2, 0}, {1, 2, 3}, {0, 1, 2}, {3, 4, 0}, {0, 1, 0}, {2, 3, 0}, {4, 5, 0}};
+    static constexpr int NT = 8, NWV = 8, MAXT = 5, NSLOT = 36;
+    static constexpr int CNT[8] = {5, 4, 4, 5, 4, 5, 5, 4};
+    static constexpr int SLOT0[8] = {0, 5, 9, 13, 18, 22, 27, 32};
+    static constexpr int TI[8][5] = {{7, 7, 7, 7, 0}, {6, 6, 6, 6, 0}, {5, 5, 5, 5, 0}, {4, 4, 4, 4, 4},
+                                     {7, 7, 7, 7, 0}, {6, 6, 6, 1, 1}, {5, 5, 2, 2, 2}, {3, 3, 3, 3, 0}};
+    static constexpr int TJ[8][5] = {{0, 1, 2, 3, 0}, {0, 1, 2, 3, 0}, {0, 1, 2, 3, 0}, {0, 1, 2, 3, 4},
+                                     {4, 5, 6, 7, 0}, {4, 5, 6, 0, 1}, {4, 5, 0, 1, 2}, {0, 1, 2, 3, 0}};
     static __device__ __forceinline__ int count(int v) { return CNT[v]; }
     static __device__ __forceinline__ int ti(int v, int k) { return TI[v][k]; }
     static __device__ __forceinline__ int tj(int v, int k) { return TJ[v][k]; }
+    static __device__ __forceinline__ int slot0(int v) { return SLOT0[v]; }
 };
 
 template <int Q>
@@ -57,6 +65,11 @@ struct DgLds {
     float dtl[Q];   // dt
     float rowf[Q];  // exp(cum_i - cum[start of i's 32-token tile - 1])
     float colf[Q];  // exp(cum[end of j's tile] - cum_j) * dt_j
+    uint32_t gq[DgMap<Q>::NSLOT][8][64];         // scores G of every owned tile in accumulator layout, two bf16 per word
+    float rsum[DgMap<Q>::NWV][2][32];            // per wave and tile-row run: row sums of E over the run's tiles
+    float csum[DgMap<Q>::NSLOT][32];             // per tile: column sums of E
+    int run_row[DgMap<Q>::NWV][2];               // tile row of each run (-1: none)
+    int slot_of[DgMap<Q>::NT][DgMap<Q>::NT];     // flat tile index of (ti, tj)
 };
 
 template <int Q>
@@ -85,7 +98,7 @@ __device__ __forceinline__ void dg_load(DgPre<Q>& pr, const SegParams& sp, int b
         const int t0 = tid & ~31;
         pr.cum = cum[tid];
         pr.dtf = sp.dtf[cbase + tid];
-        pr.cstart = t0 > 0 ? cum[t0 - 1] : 0.f;
+        pr.cstart = cum[t0 > 0 ? t0 - 1 : 0];
         pr.cend = cum[t0 + 31];
     }
 }
@@ -102,15 +115,18 @@ __device__ __forceinline__ void dg_store(const DgPre<Q>& pr, DgLds<Q>& L, int ti
     if (tid < Q) {
         L.c2[tid] = pr.cum * LOG2E;
         L.dtl[tid] = pr.dtf;
-        L.rowf[tid] = __builtin_amdgcn_exp2f((pr.cum - pr.cstart) * LOG2E);
+        L.rowf[tid] = __builtin_amdgcn_exp2f((pr.cum - (tid >= 32 ? pr.cstart : 0.f)) * LOG2E);
         L.colf[tid] = __builtin_amdgcn_exp2f((pr.cend - pr.cum) * LOG2E) * pr.dtf;
     }
 }
 
-// One tile (ti, tj) of one head: t = dY[ti] x[tj]^T, then acc += t (.) decay (.) dt.  ti and tj are
-// wave-uniform run-time values (one code path for every wave: no per-wave specialisation).
+// One tile (ti, tj) of one head: t = dY[ti] x[tj]^T; w = t (.) decay (.) dt is added to the dG
+// accumulator; E = w (.) G are the element-wise products whose row sums minus column sums give the
+// chunk-local part of the gradient of cum -- every E[i][j] enters both sums with the same rounded
+// value.  Row sums go into rowacc (still per lane), column sums into csum[slot].
+// ti and tj are wave-uniform run-time values (one code path for every wave).
 template <int Q>
-__device__ __forceinline__ void dg_tile(f32x16& acc, int ti, int tj, const DgLds<Q>& L, int lane) {
+__device__ __forceinline__ void dg_tile(f32x16& acc, f32x16& rowacc, int ti, int tj, int slot, DgLds<Q>& L, int lane) {
     const char* pa = L.dy + (32 * ti + (lane & 31)) * XPITCH + 16 * (lane >> 5);
     const char* pb = L.x + (32 * tj + (lane & 31)) * XPITCH + 16 * (lane >> 5);
     f32x16 t = zero16();
@@ -124,10 +140,10 @@ __device__ __forceinline__ void dg_tile(f32x16& acc, int ti, int tj, const DgLds
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const float4 rf = *(const float4*)(rowp + 8 * q);
-            acc[4 * q + 0] += t[4 * q + 0] * (rf.x * f);
-            acc[4 * q + 1] += t[4 * q + 1] * (rf.y * f);
-            acc[4 * q + 2] += t[4 * q + 2] * (rf.z * f);
-            acc[4 * q + 3] += t[4 * q + 3] * (rf.w * f);
+            t[4 * q + 0] *= rf.x * f;
+            t[4 * q + 1] *= rf.y * f;
+            t[4 * q + 2] *= rf.z * f;
+            t[4 * q + 3] *= rf.w * f;
         }
     } else {
         const float cj = L.c2[j], dj = L.dtl[j];
@@ -139,15 +155,81 @@ __device__ __forceinline__ void dg_tile(f32x16& acc, int ti, int tj, const DgLds
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 const float f = __builtin_amdgcn_exp2f(fminf(cv[e] - cj, 0.f)) * dj;
-                acc[4 * q + e] += (il <= 8 * q + e) ? t[4 * q + e] * f : 0.f;
+                t[4 * q + e] = (il <= 8 * q + e) ? t[4 * q + e] * f : 0.f;
             }
         }
+    }
+    float cs = 0.f;
+#pragma unroll
+    for (int r2 = 0; r2 < 8; ++r2) {
+        const uint32_t g2 = L.gq[slot][r2][lane];
+        const float g0 = __builtin_bit_cast(float, g2 << 16), g1 = __builtin_bit_cast(float, g2 & 0xffff0000u);
+        acc[2 * r2] += t[2 * r2];
+        acc[2 * r2 + 1] += t[2 * r2 + 1];
+        const float e0 = t[2 * r2] * g0, e1 = t[2 * r2 + 1] * g1;
+        rowacc[2 * r2] += e0;
+        rowacc[2 * r2 + 1] += e1;
+        cs += e0 + e1;
+    }
+    cs += __shfl_xor(cs, 32, 64);
+    if (lane < 32) L.csum[slot][lane] = cs;
+}
+
+// Sum of each of the 16 registers over the 32 lanes of a half wave, by recursive halving: after the
+// five steps lane l holds the total of one register (selected by bits 4..1 of l).  The result goes to
+// dst[row], row being the tile-local row of that register for the lane's half (even lanes write).
+__device__ __forceinline__ void row_reduce_store(const f32x16& v, float* dst, int lane) {
+    float a[8], b4[4], c2[2], d1;
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const bool hi = lane & 16;
+        const float keep = hi ? v[r + 8] : v[r], send = hi ? v[r] : v[r + 8];
+        a[r] = keep + __shfl_xor(send, 16, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const bool hi = lane & 8;
+        const float keep = hi ? a[r + 4] : a[r], send = hi ? a[r] : a[r + 4];
+        b4[r] = keep + __shfl_xor(send, 8, 64);
+    }
+#pragma unroll
+    for (int r = 0; r < 2; ++r) {
+        const bool hi = lane & 4;
+        const float keep = hi ? b4[r + 2] : b4[r], send = hi ? b4[r] : b4[r + 2];
+        c2[r] = keep + __shfl_xor(send, 4, 64);
+    }
+    {
+        const bool hi = lane & 2;
+        const float keep = hi ? c2[1] : c2[0], send = hi ? c2[0] : c2[1];
+        d1 = keep + __shfl_xor(send, 2, 64);
+    }
+    d1 += __shfl_xor(d1, 1, 64);
+    const int r = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
+    if (!(lane & 1)) dst[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = d1;
+}
+
+// Chunk-local part of the gradient of cum for head h, from the E sums of the head just finished:
+// gintra_i = sum_{j<=i} E[i][j] - sum_{i'>=i} E[i'][i], summed in a fixed order.
+template <int Q>
+__device__ __forceinline__ void dg_emit_sums(const SegParams& sp, const DgLds<Q>& L, int b, int c, int h, int tid) {
+    typedef DgMap<Q> M;
+    if (tid < Q) {
+        const int tl = tid & 31, tt = tid >> 5;
+        float rs = 0.f, cs = 0.f;
+#pragma unroll
+        for (int w = 0; w < M::NWV; ++w)
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                if (L.run_row[w][u] == tt) rs += L.rsum[w][u][tl];
+        for (int ti = tt; ti < M::NT; ++ti) cs += L.csum[L.slot_of[ti][tt]][tl];
+        sp.gintra[(((int64_t)b * sp.H + h) * sp.nc + c) * Q + tid] = rs - cs;
     }
 }
 
 template <int Q>
 __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
-    constexpr int MAXT = DgMap<Q>::MAXT;
+    typedef DgMap<Q> M;
+    constexpr int MAXT = M::MAXT;
     __shared__ __attribute__((aligned(16))) DgLds<Q> L;
     int z = blockIdx.x;
     if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
@@ -156,7 +238,31 @@ __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
     const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
     const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int cnt = DgMap<Q>::count(w);
+    const int cnt = M::count(w), slot0 = M::slot0(w);
+    // prologue: the scores of the owned tiles in accumulator layout, and the maps used when the sums are combined
+    {
+        const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
+        int prev = -1, run = -1;
+        if (lane == 0) L.run_row[w][0] = L.run_row[w][1] = -1;
+#pragma unroll
+        for (int k = 0; k < MAXT; ++k)
+            if (k < cnt) {
+                const int ti = M::ti(w, k), tj = M::tj(w, k);
+                const bf16_t* gp = Gd + (int64_t)(32 * ti + 4 * (lane >> 5)) * Q + 32 * tj + (lane & 31);
+#pragma unroll
+                for (int r2 = 0; r2 < 8; ++r2) {
+                    const int r = 2 * r2, row = 8 * (r >> 2) + (r & 3);
+                    const uint32_t lo = gp[(int64_t)row * Q].v, hi = gp[(int64_t)(row + 1) * Q].v;
+                    L.gq[slot0 + k][r2][lane] = lo | (hi << 16);
+                }
+                if (ti != prev) {
+                    ++run;
+                    prev = ti;
+                    if (lane == 0) L.run_row[w][run] = ti;
+                }
+                if (lane == 0) L.slot_of[ti][tj] = slot0 + k;
+            }
+    }
     f32x16 acc[MAXT];
 #pragma unroll
     for (int k = 0; k < MAXT; ++k) acc[k] = zero16();
@@ -164,19 +270,34 @@ __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
     dg_load<Q>(pr, sp, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
         __syncthreads();
+        if (hh > 0) dg_emit_sums<Q>(sp, L, b, c, h0 + hh - 1, tid);
         dg_store<Q>(pr, L, tid);
         __syncthreads();
         if (hh + 1 < hps) dg_load<Q>(pr, sp, b, c, h0 + hh + 1, tid);
+        f32x16 rowacc = zero16();
+        int prev = M::ti(w, 0), run = 0;
 #pragma unroll
         for (int k = 0; k < MAXT; ++k)
-            if (k < cnt) dg_tile<Q>(acc[k], DgMap<Q>::ti(w, k), DgMap<Q>::tj(w, k), L, lane);
+            if (k < cnt) {
+                const int ti = M::ti(w, k);
+                if (ti != prev) {  // a new tile row starts: flush the row sums of the finished run
+                    row_reduce_store(rowacc, L.rsum[w][run], lane);
+                    rowacc = zero16();
+                    prev = ti;
+                    ++run;
+                }
+                dg_tile<Q>(acc[k], rowacc, ti, M::tj(w, k), slot0 + k, L, lane);
+            }
+        row_reduce_store(rowacc, L.rsum[w][run], lane);
     }
-    __bf16* out = (__bf16*)sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * ((int64_t)Q * Q);
+    __syncthreads();
+    dg_emit_sums<Q>(sp, L, b, c, h0 + hps - 1, tid);
     // partial sum of this slice, bf16 [Q][Q] row-major (tiles above the diagonal are never touched)
+    __bf16* out = (__bf16*)sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * ((int64_t)Q * Q);
 #pragma unroll
     for (int k = 0; k < MAXT; ++k)
         if (k < cnt) {
-            __bf16* o = out + (int64_t)(32 * DgMap<Q>::ti(w, k) + 4 * (lane >> 5)) * Q + 32 * DgMap<Q>::tj(w, k) + (lane & 31);
+            __bf16* o = out + (int64_t)(32 * M::ti(w, k) + 4 * (lane >> 5)) * Q + 32 * M::tj(w, k) + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) o[(int64_t)(8 * (r >> 2) + (r & 3)) * Q] = (__bf16)acc[k][r];
         }

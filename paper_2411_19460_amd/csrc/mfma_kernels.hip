@@ -221,13 +221,13 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
             }
         }
     }
-    *(float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e) = hc;
     if (sp.state_out) *(float4*)(sp.state_out + (int64_t)b * sp.state_out_bs + bh) = hc;
     if (sp.state_out2) *(float4*)(sp.state_out2 + (int64_t)b * sp.state_out2_bs + bh) = hc;
 }
 
 // Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-wave partial sums
-// of <dHnext_c, Hnext_c> (fixed summation order).
+// of exp(T_c) <dHnext_c, Hprev_c>, the gradient of the chunk's total decay through the carried state
+// (fixed summation order).
 __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
@@ -243,11 +243,9 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
             const int c = c0 - u >= 0 ? c0 - u : 0;
             lv[u] = *(const float4*)(sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);  // local adjoint
             av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
-            // state leaving chunk c: fp32 for the last chunk of the segment, else the bf16 copy
-            if (c + 1 == sp.nc) {
-                hv[u] = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e);
-            } else {
-                const bf16x4 hb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c + 1) * sp.H + h) * PN + e);
+            // state entering chunk c (bf16 copy)
+            {
+                const bf16x4 hb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
                 hv[u] = make_float4((float)hb[0], (float)hb[1], (float)hb[2], (float)hb[3]);
             }
         }
@@ -258,12 +256,12 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
             bf16x4 gb;  // the total adjoint is kept in bf16 only
             gb[0] = (__bf16)g.x; gb[1] = (__bf16)g.y; gb[2] = (__bf16)g.z; gb[3] = (__bf16)g.w;
             *(bf16x4*)(sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = gb;
-            const float4 hn = hv[u];
-            float part = g.x * hn.x + g.y * hn.y + g.z * hn.z + g.w * hn.w;
+            const float a = __expf(av[u]);
+            const float4 hp = hv[u];
+            float part = a * (g.x * hp.x + g.y * hp.y + g.z * hp.z + g.w * hp.w);
             for (int off = 32; off > 0; off >>= 1) part += __shfl_down(part, off, 64);
             if ((threadIdx.x & 63) == 0)  // one partial sum per wave; summed later in a fixed order
                 sp.tail_part[(((int64_t)b * sp.H + h) * sp.nc + c) * sp.nslice + blockIdx.x * (NTH / 64) + (threadIdx.x >> 6)] = part;
-            const float a = __expf(av[u]);
             const float4 loc = lv[u];
             g.x = a * g.x + loc.x; g.y = a * g.y + loc.y; g.z = a * g.z + loc.z; g.w = a * g.w + loc.w;
         }
@@ -306,9 +304,10 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     if (e != hipSuccess) return e;
     e = mfma_launch_dual(sp, 2, st);
     if (e != hipSuccess) return e;
-    e = generic_backward_scalars(sp, st);
+    e = mfma_launch_grad_bc(sp, st);  // also writes the chunk-local part of the gradient of cum
     if (e != hipSuccess) return e;
-    e = mfma_launch_grad_bc(sp, st);
+    sp.flags |= SSD_INTERNAL_SPLIT_GTERM;
+    e = generic_backward_scalars(sp, st);
     if (e != hipSuccess) return e;
     return hipSuccess;
 }

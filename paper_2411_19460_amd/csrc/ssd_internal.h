@@ -8,6 +8,10 @@
 
 namespace ssdk {
 
+// Internal flag (never accepted from callers): the gradient of cum arrives in three pieces,
+// gterm - sterm + gintra (matrix-core path).
+constexpr uint32_t SSD_INTERNAL_SPLIT_GTERM = 1u << 31;
+
 // bf16 storage as raw bits; conversion is round-to-nearest-even.
 struct bf16_t {
     uint16_t v;
@@ -64,7 +68,9 @@ struct SegParams {
     float* dstates;    // [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
     float* Gm;         // [Bt][nc][G][Q][Q]    C_i . B_j   (generic path: fp32)
     float* dG;         // generic path: [Bt][nc][G][Q][Q] fp32 head-summed masked dY X^T; MFMA path: [Bt][nc][G][dg_split][Q][Q] bf16 per-slice sums
-    float* gterm;      // [Bt][H][nc][Q]
+    float* gterm;      // [Bt][H][nc][Q]  gradient of cum, per token (MFMA path: the part through the entering state)
+    float* sterm;      // [Bt][H][nc][Q]  MFMA path: dt_j x_j . (part of u_j through the leaving adjoint); subtracted
+    float* gintra;     // [Bt][H][nc][Q]  MFMA path: chunk-local part (row sums minus column sums of E); added
     float* fterm;      // [Bt][H][nc][Q]
     float* dDrow;      // [Bt][H][nc][Q]
     float* tail_part;  // [Bt][H][nc][nslice]
@@ -117,7 +123,7 @@ struct Dims {
 // Byte offsets of the per-segment scratch arrays inside the caller's workspace.
 struct WsLayout {
     size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
-    size_t ein, eout, states_bf, dstates_bf, dbc_part;
+    size_t ein, eout, states_bf, dstates_bf, dbc_part, sterm, gintra;
     int nslice, dg_split, part_split;
 };
 
@@ -131,7 +137,7 @@ bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
 enum KernelId {
     K_CUMSUM, K_CB, K_CHUNK_STATE, K_SCAN_FWD, K_CHUNK_OUT, K_DSTATE, K_SCAN_BWD, K_BWD_MAIN, K_DDT, K_PARAM, K_DG, K_DBC,
     K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
-    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_COUNT
+    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_MFMA_STATE_DOTS, K_COUNT
 };
 void prof_begin(int kid, hipStream_t st);
 void prof_end(int kid, hipStream_t st);
@@ -160,7 +166,8 @@ hipError_t launch_param_reduce(const SegParams& sp, hipStream_t st);
 bool mfma_path_supported(const ssd_shape_t& s);
 hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st);
 hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
-// One dual-form pass over a segment: epi 0 = forward output, 1 and 2 = the two backward passes.
+// One pass over a segment: epi 0 = forward output, 2 = the backward dual-form pass, 1 = the two per-token
+// dot products through the chunk-boundary states (gterm, sterm).
 hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st);
 // dG, the head sums and the final contraction that give dB and dC of one segment.
 hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st);
