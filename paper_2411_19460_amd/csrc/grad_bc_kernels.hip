@@ -175,35 +175,56 @@ __device__ __forceinline__ void dg_tile(f32x16& acc, f32x16& rowacc, int ti, int
     if (lane < 32) L.csum[slot][lane] = cs;
 }
 
-// Sum of each of the 16 registers over the 32 lanes of a half wave, by recursive halving: after the
-// five steps lane l holds the total of one register (selected by bits 4..1 of l).  The result goes to
-// dst[row], row being the tile-local row of that register for the lane's half (even lanes write).
+// Lane exchanges without LDS addressing: DPP within a row of 16 lanes, ds_swizzle across rows.
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, false));
+}
+__device__ __forceinline__ float xor16_f(float v) {  // lane ^ 16 (bit-mask swizzle: and 0x1F, or 0, xor 0x10)
+    return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
+}
+
+// Sum of each of the 16 registers over the 32 lanes of a half wave, by recursive halving: at every
+// step a lane keeps half of its registers, hands the other half to a partner whose matching lane bit
+// differs, and adds what it receives.  Partners: lane ^ 16, lane ^ 8 (row_ror:8), lane ^ 7
+// (row_half_mirror: bit 2 differs, and the pairs of the last two steps still cover every lane once),
+// lane ^ 2, lane ^ 1 (quad_perm).  After the five steps lane l holds the total of the register selected
+// by bits 4..1 of l.  The result goes to dst[row], row being the tile-local row of that register for
+// the lane's half (even lanes write).
+// (sel() hides its operands from the optimiser for a moment: a select between two elements of one
+// register vector would otherwise be rewritten as a dynamically indexed element, i.e. a chain of
+// sixteen compare-and-select instructions.)
+__device__ __forceinline__ float sel(bool c, float a, float b) {
+    asm volatile("" : "+v"(a), "+v"(b));
+    return c ? a : b;
+}
+
 __device__ __forceinline__ void row_reduce_store(const f32x16& v, float* dst, int lane) {
     float a[8], b4[4], c2[2], d1;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
         const bool hi = lane & 16;
-        const float keep = hi ? v[r + 8] : v[r], send = hi ? v[r] : v[r + 8];
-        a[r] = keep + __shfl_xor(send, 16, 64);
+        const float keep = sel(hi, v[r + 8], v[r]), send = sel(hi, v[r], v[r + 8]);
+        a[r] = keep + xor16_f(send);
     }
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const bool hi = lane & 8;
-        const float keep = hi ? a[r + 4] : a[r], send = hi ? a[r] : a[r + 4];
-        b4[r] = keep + __shfl_xor(send, 8, 64);
+        const float keep = sel(hi, a[r + 4], a[r]), send = sel(hi, a[r], a[r + 4]);
+        b4[r] = keep + dpp_f<0x128>(send);
     }
 #pragma unroll
     for (int r = 0; r < 2; ++r) {
         const bool hi = lane & 4;
-        const float keep = hi ? b4[r + 2] : b4[r], send = hi ? b4[r] : b4[r + 2];
-        c2[r] = keep + __shfl_xor(send, 4, 64);
+        const float keep = sel(hi, b4[r + 2], b4[r]), send = sel(hi, b4[r], b4[r + 2]);
+        c2[r] = keep + dpp_f<0x141>(send);
     }
     {
         const bool hi = lane & 2;
-        const float keep = hi ? c2[1] : c2[0], send = hi ? c2[0] : c2[1];
-        d1 = keep + __shfl_xor(send, 2, 64);
+        const float keep = sel(hi, c2[1], c2[0]), send = sel(hi, c2[0], c2[1]);
+        d1 = keep + dpp_f<0x4E>(send);
     }
-    d1 += __shfl_xor(d1, 1, 64);
+    d1 += dpp_f<0xB1>(d1);
     const int r = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
     if (!(lane & 1)) dst[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = d1;
 }
@@ -279,14 +300,17 @@ __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
 #pragma unroll
         for (int k = 0; k < MAXT; ++k)
             if (k < cnt) {
-                const int ti = M::ti(w, k);
+                int ti = M::ti(w, k), tj = M::tj(w, k);
+                // keep the per-tile address arithmetic inside the head loop (hoisted out, it costs more
+                // registers than it saves instructions)
+                asm volatile("" : "+s"(ti), "+s"(tj));
                 if (ti != prev) {  // a new tile row starts: flush the row sums of the finished run
                     row_reduce_store(rowacc, L.rsum[w][run], lane);
                     rowacc = zero16();
                     prev = ti;
                     ++run;
                 }
-                dg_tile<Q>(acc[k], rowacc, ti, M::tj(w, k), slot0 + k, L, lane);
+                dg_tile<Q>(acc[k], rowacc, ti, tj, slot0 + k, L, lane);
             }
         row_reduce_store(rowacc, L.rsum[w][run], lane);
     }
