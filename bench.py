@@ -24,27 +24,31 @@ VALU_FP32_PEAK_TFLOPS = 157.3
 def kernel_models(cfg, tokens_per_launch):
     """Algorithmic work of one launch of each kernel: (bound, amount) with amount in flop (MAC = 2)
     for contractions and in bytes for bandwidth-bound kernels.  Dense Q x Q counts, per token:
-      chunk_state 2NP*H | cb 2QN*G | chunk_out (2QP+2NP)*H | dstate_local 2NP*H
-      bwd_main (4QP+4NP)*H | dG 2QP*H | dBC 4NP*H + 4QN*G
-      state scans: read + write one fp32 state per (chunk, head): 2*4*P*N*H/Q bytes
+      chunk_state 2NP*H | cb 2QN*G | chunk_out (2QP+2NP)*H | dstate_local (restore + local adjoint) 4NP*H
+      bwd_main (2QP+2NP)*H | state_dots 4NP*H | dG 2QP*H | dBC 4NP*H | dBC_final 4QN*G
+      state scans, per (chunk, head) state of P*N elements: forward reads fp32 and writes bf16
+      (6 B/element), reverse reads fp32 + bf16 and writes bf16 (8 B/element).
     A launch covers one segment: tokens_per_launch = batch * segment."""
     H, P, N, G, Q = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk
     t = tokens_per_launch
     esz = 2 if cfg.dtype == "bf16" else 4
-    scan_bytes = 2 * 4 * P * N * H / Q
+    st = P * N * H / Q
     m = {
+        "mfma_chunk_state": ("flop", 2 * N * P * H), "mfma_cb": ("flop", 2 * Q * N * G),
+        "mfma_chunk_out": ("flop", (2 * Q * P + 2 * N * P) * H), "mfma_dstate_local": ("flop", 4 * N * P * H),
+        "mfma_bwd_main": ("flop", (2 * Q * P + 2 * N * P) * H), "mfma_state_dots": ("flop", 4 * N * P * H),
+        "mfma_dG": ("flop", 2 * Q * P * H), "mfma_dBC": ("flop", 4 * N * P * H), "mfma_dBC_final": ("flop", 4 * Q * N * G),
+        # shape-generic fp32 FMA kernels
         "chunk_state": ("flop", 2 * N * P * H), "cb": ("flop", 2 * Q * N * G),
         "chunk_out": ("flop", (2 * Q * P + 2 * N * P) * H), "dstate_local": ("flop", 2 * N * P * H),
         "bwd_main": ("flop", (4 * Q * P + 4 * N * P) * H), "dG": ("flop", 2 * Q * P * H),
         "dBC": ("flop", 4 * N * P * H + 4 * Q * N * G),
-        "state_scan_fwd": ("byte", scan_bytes), "state_scan_bwd": ("byte", scan_bytes * 1.5),
-        "cumsum": ("byte", H * esz + 2 * 4 * H), "ddt_finalize": ("byte", 4 * 4 * H + H * esz),
+        "cumsum": ("byte", H * esz + 4 * 4 * H), "ddt_finalize": ("byte", 6 * 4 * H + H * esz),
     }
-    out = {}
-    for k, (kind, per_tok) in m.items():
-        out[k] = (kind, per_tok * t)
-        out["mfma_" + k] = (kind, per_tok * t)
-    return out
+    mfma = cfg.dtype == "bf16"   # matrix-core path keeps only bf16 copies of the scanned states
+    m["state_scan_fwd"] = ("byte", (6 if mfma else 8) * st)
+    m["state_scan_bwd"] = ("byte", (8 if mfma else 12) * st)
+    return {k: (kind, per_tok * t) for k, (kind, per_tok) in m.items()}
 
 
 def measured_traffic(kernel, workload):
@@ -89,6 +93,8 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on exactly one GPU (no collectives, no sharding); use --gpus 1", file=sys.stderr)
@@ -98,6 +104,19 @@ def main():
     import paper_2411_19460_amd as pk
     from paper_2411_19460_amd import synth
 
+    if args.calibrate_copy:
+        torch.cuda.set_device(0)
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda:0").normal_()
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        dtc = (time.perf_counter() - t0) / 5
+        print(json.dumps({"copy_bytes_read": a.numel() * 4, "copy_bytes_written": a.numel() * 4, "copies": 5,
+                          "GB_per_s_read_plus_write": 2 * a.numel() * 4 / dtc / 1e9}))
+        return
     cfg = synth.CONFIGS[args.config]
     if cfg.nlayers != 1:
         print("bench.py: stack configs are measured by tests, not by this bench", file=sys.stderr)
@@ -126,18 +145,24 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
-    # Pass 1 (not the timed region): HIP events around every kernel launch, for the per-kernel table
-    # and to find the dominant kernel.  Event records between kernels cost several microseconds each,
-    # so this pass is slower than the real thing.
+    # Pass 1 (not the timed region): HIP events around every kernel launch, with every segment kept on
+    # one stream so that kernels do not overlap: the per-kernel table, and the dominant kernel.  Event
+    # records between kernels cost several microseconds each, so this pass is slower than the real thing.
+    pk.ssd_prof_serialize(True)
     pk.ssd_prof_enable(True)
     for _ in range(max(1, min(args.steps, 3))):
         step()
     torch.cuda.synchronize()
     prof_all = pk.ssd_prof_read()
     pk.ssd_prof_enable(False)
+    pk.ssd_prof_serialize(False)
+    for _ in range(max(1, args.warmup)):
+        step()
+    torch.cuda.synchronize()
     models = kernel_models(cfg, Bt * cfg.segment)
     dom = max((k for k in prof_all if k in models), key=lambda k: prof_all[k][0])
-    # Pass 2, the timed region: exactly `steps` steps, events only around the dominant kernel.
+    # Pass 2, the timed region: exactly `steps` steps, up to four segments in flight, events only around
+    # the dominant kernel (its launches then share the GPU with kernels of the other segments).
     pk.ssd_prof_enable(True, only=dom)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -188,8 +213,9 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": Bt, "seqlen": L, "nheads": H, "headdim": P, "dstate": N,
                    "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment,
-                   "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma"},
-        "roofline": roofline, "kernels": kernels, "peak_hbm": peak_hbm,
+                   "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma",
+                   "segments_in_flight": min(4, nseg) if not args.generic else 1},
+        "roofline": roofline, "kernels_serialized": kernels, "peak_hbm": peak_hbm,
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)

@@ -203,8 +203,12 @@ int magc_plan(const magc_model_t* model /*host*/, magc_plan_t* out /*host*/);
  *   ssd_prof_read(id, ...)   : waits for the recorded events of kernel `id`, returns the sum of
  *                              their durations in milliseconds and the number of launches (host pointers)
  *   ssd_prof_kernel_name(id) : static name of kernel `id`, NULL once id is past the last kernel
+ *   ssd_prof_serialize(on)   : on = 1 keeps every segment on the caller's stream (kernels then never overlap,
+ *                              which is what per-kernel durations need to mean something); 0 restores the
+ *                              default.  The workspace size does not change.
  */
 int ssd_prof_enable(int32_t on);
+int ssd_prof_serialize(int32_t on);
 int ssd_prof_read(int32_t kernel_id, double* total_ms /*host*/, int64_t* launches /*host*/);
 const char* ssd_prof_kernel_name(int32_t kernel_id);
 

@@ -17,7 +17,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
-           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name")
+           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
 class ssd_shape_t(ctypes.Structure):
@@ -75,6 +75,8 @@ def lib():
         L.magc_plan.argtypes = [ctypes.POINTER(magc_model_t), ctypes.POINTER(magc_plan_t)]
         L.ssd_prof_enable.restype = ctypes.c_int
         L.ssd_prof_enable.argtypes = [i32]
+        L.ssd_prof_serialize.restype = ctypes.c_int
+        L.ssd_prof_serialize.argtypes = [i32]
         L.ssd_prof_read.restype = ctypes.c_int
         L.ssd_prof_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
         L.ssd_prof_kernel_name.restype = ctypes.c_char_p
@@ -274,6 +276,11 @@ def ssd_prof_enable(on, only: Optional[str] = None) -> None:
     rc = lib().ssd_prof_enable(mode)
     if rc != 0:
         raise SSDError(rc, "ssd_prof_enable")
+
+
+def ssd_prof_serialize(on: bool) -> None:
+    """Keep every segment on the caller's stream (no overlap between kernels) while `on`."""
+    lib().ssd_prof_serialize(1 if on else 0)
 
 
 def ssd_prof_read() -> dict:

@@ -213,12 +213,14 @@ static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d
 
 // SSD_MAGC_SERIAL=1 in the environment keeps every segment on the caller's stream (diagnostics: per-kernel
 // timings are only meaningful when kernels do not overlap).
+static bool g_serial = false;  // ssd_prof_serialize
+
 static int lanes(const Dims& d, bool mfma) {
     static const bool serial = [] {
         const char* v = getenv("SSD_MAGC_SERIAL");
         return v && v[0] == '1';
     }();
-    if (!mfma || serial || d.nseg <= 1) return 1;
+    if (!mfma || serial || g_serial || d.nseg <= 1) return 1;
     return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
 }
 
@@ -389,6 +391,11 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     sps[0].accumulate = (flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0;
     if (launch_param_reduce(sps[0], st) != hipSuccess) return SSD_ERR_LAUNCH;
+    return SSD_OK;
+}
+
+extern "C" int ssd_prof_serialize(int32_t on) {
+    g_serial = on != 0;
     return SSD_OK;
 }
 
