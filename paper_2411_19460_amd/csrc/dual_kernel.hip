@@ -6,8 +6,8 @@
 //                             y = yhat + D x  (+ x under the residual flag)
 //   EPI 2 (backward):         u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
 //                             dx = dt u + D dY (+ dY), f_j = x_j . u_j (the direct part of ddt) and dY_j . x_j (for dD)
-// (EPI 1, the forward form reduced to dY_i . yhat_i, is kept for reference but no longer launched: the
-// gradient of cum is assembled from mk_state_dots below and from the E sums of the dG kernel.)
+// (EPI 1, the forward form reduced to dY_i . yhat_i, is kept for reference but not launched: the gradient
+// of cum is assembled from the E sums of the dG kernel and the state dot products of the head-sum kernel.)
 //
 // Organisation.  One workgroup owns one (batch, chunk, group) and a slice of that group's heads and
 // walks the heads one after the other.  It has one wave per 32-token tile of the chunk; the tile
@@ -335,103 +335,6 @@ __global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// The two per-token dot products through the chunk-boundary states that enter the gradient of cum:
-//   role 0:  gterm_i = exp(cum_i)            dY_i . (Hprev  C_i)      (= dY_i . Yoff_i)
-//   role 1:  sterm_j = exp(T - cum_j) dt_j   x_j  . (dHnext B_j)
-// One workgroup per (batch, chunk, group, role, head slice), one wave per 32-token tile; the wave's
-// rows of C (or B) stay in registers; per head the state goes through LDS and the wave's own rows of
-// dY (or x) come in as whole rows through its LDS patch.  Everything of the next head is prefetched.
-template <int Q>
-struct DotsLds {
-    char st[P_ * BPITCH];
-    char priv[Q / 32][32 * XPITCH];
-};
-
-template <int Q>
-struct DotsPre {
-    bf16x8 sv[DualCfg<Q>::SV];
-    bf16x8 own[4];
-    float cum, dtf, T;
-};
-
-template <int Q>
-__device__ __forceinline__ void dots_load(DotsPre<Q>& pr, const SegParams& sp, int role, int b, int c, int h, int tok0,
-                                          int tid, int lane) {
-    typedef DualCfg<Q> CF;
-    const int64_t xt = (int64_t)sp.H * P_;
-    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-    const bf16_t* S = (role ? sp.dstates_bf : sp.states_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
-#pragma unroll
-    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)(S + (tid + CF::NTHR * k) * 8);
-    const bf16_t* src = (role ? (const bf16_t*)sp.x + (int64_t)b * sp.xs_b : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b) +
-                        ((int64_t)c * Q * sp.H + h) * P_;
-#pragma unroll
-    for (int it = 0; it < 4; ++it)
-        pr.own[it] = *(const bf16x8*)(src + (int64_t)(tok0 + (lane >> 3) + 8 * it) * xt + (lane & 7) * 8);
-    pr.cum = sp.cum[cbase + tok0 + (lane & 31)];
-    pr.dtf = sp.dtf[cbase + tok0 + (lane & 31)];
-    pr.T = sp.cum[cbase + Q - 1];
-}
-
-template <int Q>
-__global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_state_dots(SegParams sp) {
-    typedef DualCfg<Q> CF;
-    __shared__ __attribute__((aligned(16))) DotsLds<Q> L;
-    int z = blockIdx.x;
-    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
-    const int ns = sp.dual_split, slice = z % ns;
-    z /= ns;
-    const int role = z & 1;
-    z >>= 1;
-    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
-    const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
-    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int tok0 = 32 * w, tl = lane & 31;
-    const int64_t bt = (int64_t)sp.G * N_;
-    const bf16_t* rowop = (role ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
-    bf16x8 rf[RF_N];
-#pragma unroll
-    for (int ks = 0; ks < RF_N; ++ks) rf[ks] = frag_rows(rowop, bt, tok0, 16 * ks, lane);
-    char* priv = L.priv[w];
-    DotsPre<Q> pr;
-    dots_load<Q>(pr, sp, role, b, c, h0, tok0, tid, lane);
-    for (int hh = 0; hh < hps; ++hh) {
-        const int h = h0 + hh;
-        __syncthreads();
-#pragma unroll
-        for (int k = 0; k < CF::SV; ++k) {
-            const int v = tid + CF::NTHR * k, row = v >> 4, seg = v & 15;
-            *(bf16x8*)(L.st + row * BPITCH + seg * 16) = pr.sv[k];
-        }
-#pragma unroll
-        for (int it = 0; it < 4; ++it) *(bf16x8*)(priv + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = pr.own[it];
-        const float wgt = role ? __expf(pr.T - pr.cum) * pr.dtf : __expf(pr.cum);
-        __syncthreads();
-        if (hh + 1 < hps) dots_load<Q>(pr, sp, role, b, c, h + 1, tok0, tid, lane);
-        f32x16 acc0 = zero16(), acc1 = zero16();
-#pragma unroll
-        for (int ks = 0; ks < RF_N; ++ks) {
-            acc0 = mfma(frag_lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ks], acc0);
-            acc1 = mfma(frag_lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ks], acc1);
-        }
-        float s = 0.f;
-#pragma unroll
-        for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const bf16x4 o = *(const bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2);
-#pragma unroll
-                for (int e = 0; e < 4; ++e) s += (float)o[e] * (pt ? acc1 : acc0)[4 * q + e];
-            }
-        s += __shfl_xor(s, 32, 64);
-        if (lane < 32) {
-            float* dst = (role ? sp.sterm : sp.gterm) + (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-            dst[tok0 + tl] = s * wgt;
-        }
-    }
-}
-
 template <int Q, int EPI>
 hipError_t launch_dual_q(const SegParams& sp0, int kid, hipStream_t st) {
     SegParams sp = sp0;
@@ -452,29 +355,11 @@ hipError_t launch_dual_epi(const SegParams& sp, int kid, hipStream_t st) {
     }
 }
 
-template <int Q>
-hipError_t launch_state_dots_q(const SegParams& sp0, hipStream_t st) {
-    SegParams sp = sp0;
-    sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G * 2, 256);
-    SSDK_LAUNCH(K_MFMA_STATE_DOTS, st, mk_state_dots<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * sp.dual_split), dim3(DualCfg<Q>::NTHR), sp);
-    return hipSuccess;
-}
-
-hipError_t launch_state_dots(const SegParams& sp, hipStream_t st) {
-    switch (sp.Q) {
-        case 64: return launch_state_dots_q<64>(sp, st);
-        case 128: return launch_state_dots_q<128>(sp, st);
-        case 256: return launch_state_dots_q<256>(sp, st);
-        default: return hipErrorInvalidValue;
-    }
-}
-
 }  // namespace
 
 hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st) {
     switch (epi) {
         case 0: return launch_dual_epi<0>(sp, K_MFMA_CHUNK_OUT, st);
-        case 1: return launch_state_dots(sp, st);
         case 2: return launch_dual_epi<2>(sp, K_MFMA_BWD_MAIN, st);
         default: return hipErrorInvalidValue;
     }

@@ -331,6 +331,10 @@ __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
 // Head sums of dC (role 0) and dB (role 1):
 //   role 0:  part[i][n] = sum_h exp(cum_h,i) (dY_h,i . Hprev_h[:, n])
 //   role 1:  part[j][n] = sum_h exp(T_h - cum_h,j) dt_h,j (x_h,j . dHnext_h[:, n])
+// and, per head, the two per-token dot products through the chunk-boundary states that enter the
+// gradient of cum (same staged operands, contracted the other way round):
+//   role 0:  gterm_i = exp(cum_i)          dY_i . (Hprev  C_i)
+//   role 1:  sterm_j = exp(T - cum_j) dt_j x_j  . (dHnext B_j)
 // Wave w owns RT row tiles (row group w / 2) and one half of the state columns (w % 2).
 template <int Q>
 struct PartCfg {
@@ -406,10 +410,20 @@ __global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
     z >>= 1;
     const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
     const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6, rg = w >> 1, nh = w & 1;
+    const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6), rg = w >> 1, nh = w & 1;
     f32x16 acc[RT][2];
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) acc[rt][0] = acc[rt][1] = zero16();
+    // wave w < Q/32 also owns token tile w of the per-token dot product through the state:
+    // its rows of C (role 0) or B (role 1) stay in registers
+    const bool has_dots = w < Q / 32;
+    bf16x8 rf[N_ / 16];
+    if (has_dots) {
+        const int64_t bt = (int64_t)sp.G * N_;
+        const bf16_t* rowop = (role ? (const bf16_t*)sp.Bm : (const bf16_t*)sp.Cm) + (int64_t)b * sp.bcs_b + ((int64_t)c * Q * sp.G + g) * N_;
+#pragma unroll
+        for (int ks = 0; ks < N_ / 16; ++ks) rf[ks] = frag_rows(rowop, bt, 32 * w, 16 * ks, lane);
+    }
     PartPre<Q> pr;
     part_load<Q>(pr, sp, role, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
@@ -427,6 +441,27 @@ __global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
                 acc[rt][0] = mfma(fa, fb0, acc[rt][0]);
                 acc[rt][1] = mfma(fa, fb1, acc[rt][1]);
             }
+        }
+        if (has_dots) {
+            // z^T[p][i] = (state C_i)[p] (role 1: (state B_j)[p]); the staged tile already carries the token's weight
+            f32x16 z0 = zero16(), z1 = zero16();
+#pragma unroll
+            for (int ks = 0; ks < N_ / 16; ++ks) {
+                z0 = mfma(lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ks], z0);
+                z1 = mfma(lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ks], z1);
+            }
+            const int tok = 32 * w + (lane & 31);
+            float sdot = 0.f;
+#pragma unroll
+            for (int pt = 0; pt < 2; ++pt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const bf16x4 o = *(const bf16x4*)(L.tile + tok * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2);
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) sdot += (float)o[e] * (pt ? z1 : z0)[4 * q + e];
+                }
+            sdot += __shfl_xor(sdot, 32, 64);
+            if (lane < 32) (role ? sp.sterm : sp.gterm)[(((int64_t)b * sp.H + h0 + hh) * sp.nc + c) * Q + tok] = sdot;
         }
     }
     float* part = sp.dbc_part + (((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * 2 + role) * ((int64_t)Q * N_);

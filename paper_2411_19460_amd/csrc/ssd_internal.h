@@ -166,8 +166,7 @@ hipError_t launch_param_reduce(const SegParams& sp, hipStream_t st);
 bool mfma_path_supported(const ssd_shape_t& s);
 hipError_t mfma_forward_segment(const SegParams& sp, bool need_y, hipStream_t st);
 hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
-// One pass over a segment: epi 0 = forward output, 2 = the backward dual-form pass, 1 = the two per-token
-// dot products through the chunk-boundary states (gterm, sterm).
+// One dual-form pass over a segment: epi 0 = forward output, 2 = the backward pass.
 hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st);
 // dG, the head sums and the final contraction that give dB and dC of one segment.
 hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st);
