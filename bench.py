@@ -26,8 +26,9 @@ def kernel_models(cfg, tokens_per_launch):
     for contractions and in bytes for bandwidth-bound kernels.  Dense Q x Q counts, per token:
       chunk_state 2NP*H | cb 2QN*G | chunk_out (2QP+2NP)*H | dstate_local (restore + local adjoint) 4NP*H
       bwd_main (2QP+2NP)*H | state_dots 4NP*H | dG 2QP*H | dBC 4NP*H | dBC_final 4QN*G
-      state scans, per (chunk, head) state of P*N elements: forward reads fp32 and writes bf16
-      (6 B/element), reverse reads fp32 + bf16 and writes bf16 (8 B/element).
+      state scans, per (chunk, head) state of P*N elements (matrix-core path, everything bf16 in memory):
+      forward reads the chunk state and writes the entering state (4 B/element), reverse reads the
+      local adjoint and the entering state and writes the total adjoint (6 B/element).
     A launch covers one segment: tokens_per_launch = batch * segment."""
     H, P, N, G, Q = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk
     t = tokens_per_launch
@@ -46,8 +47,8 @@ def kernel_models(cfg, tokens_per_launch):
         "cumsum": ("byte", H * esz + 4 * 4 * H), "ddt_finalize": ("byte", 6 * 4 * H + H * esz),
     }
     mfma = cfg.dtype == "bf16"   # matrix-core path keeps only bf16 copies of the scanned states
-    m["state_scan_fwd"] = ("byte", (6 if mfma else 8) * st)
-    m["state_scan_bwd"] = ("byte", (8 if mfma else 12) * st)
+    m["state_scan_fwd"] = ("byte", (4 if mfma else 8) * st)
+    m["state_scan_bwd"] = ("byte", (6 if mfma else 12) * st)
     return {k: (kind, per_tok * t) for k, (kind, per_tok) in m.items()}
 
 
