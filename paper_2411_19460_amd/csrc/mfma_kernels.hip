@@ -94,8 +94,10 @@ __global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
 }
 
 // ---------------------------------------------------------------------------------------------
-// role 0: states[b,c,h]  = sum_j exp(T - cum_j) dt_j x_j (x) B_j      (chunk state, fp32 [P][N])
-// role 1: dstates[b,c,h] = sum_i exp(cum_i) dY_i (x) C_i              (local state adjoint)
+// role 0: states_bf[b,c,h]  = sum_j exp(T - cum_j) dt_j x_j (x) B_j      (chunk state, bf16 [P][N])
+// role 1: dstates_bf[b,c,h] = sum_i exp(cum_i) dY_i (x) C_i              (local state adjoint)
+// (fp32 accumulation, one rounding to bf16: the consumers take these as bf16 MFMA operands anyway,
+// and the scans carry the running state in fp32 registers.)
 // One workgroup per (batch, chunk, group, role, head slice); eight waves, wave w owning the 32 x 32
 // output tile (p half w / 4, state columns 32 (w % 4)).  The B (or C) rows of the chunk do not depend on
 // the head: they go through LDS once and each wave keeps its Q/16 operand fragments in registers
@@ -180,10 +182,10 @@ __global__ __launch_bounds__(OUTER_THR) void mk_chunk_outer(SegParams sp, int nr
         f32x16 acc = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma(frag_tr(L.xt, XPITCH, 16 * ks, 32 * ph, lane), fb[ks], acc);
-        float* out = role == 0 ? sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * (P_ * N_)
-                               : sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+        // bf16, into the slot where the scan will put the state entering the chunk (total adjoint leaving it)
+        __bf16* out = (__bf16*)(role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = acc[r];
+        for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = (__bf16)acc[r];
     }
 }
 
@@ -205,7 +207,9 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u < sp.nc ? c0 + u : sp.nc - 1;
-            sv[u] = *(const float4*)(sp.states + (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e);  // chunk state
+            // chunk state (bf16), about to be replaced in place by the state entering the chunk
+            const bf16x4 sb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+            sv[u] = make_float4((float)sb[0], (float)sb[1], (float)sb[2], (float)sb[3]);
             av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
         }
 #pragma unroll
@@ -241,7 +245,9 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 - u >= 0 ? c0 - u : 0;
-            lv[u] = *(const float4*)(sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);  // local adjoint
+            // local adjoint (bf16), about to be replaced in place by the total adjoint leaving the chunk
+            const bf16x4 lb = *(const bf16x4*)(sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+            lv[u] = make_float4((float)lb[0], (float)lb[1], (float)lb[2], (float)lb[3]);
             av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
             // state entering chunk c (bf16 copy)
             {
