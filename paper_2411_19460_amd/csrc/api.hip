@@ -52,7 +52,7 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     return SSD_OK;
 }
 
-WsLayout ws_layout(const Dims& d, bool bwd) {
+WsLayout ws_layout(const Dims& d, bool bwd, int wg_target) {
     WsLayout w;
     memset(&w, 0, sizeof(w));
     size_t off = 0;
@@ -72,8 +72,8 @@ WsLayout ws_layout(const Dims& d, bool bwd) {
     w.eout = take(tok);
     w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
     const int64_t groups = d.Bt * (int64_t)d.nc * d.G;
-    w.dg_split = pick_split(d.hpg, groups, 256);
-    w.part_split = pick_split(d.hpg, groups * 2, 256);
+    w.dg_split = pick_split(d.hpg, groups, wg_target);
+    w.part_split = pick_split(d.hpg, groups * 2, wg_target);
     if (bwd) {
         w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
         w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
@@ -140,6 +140,7 @@ void base_params(SegParams& sp, const Dims& d, uint32_t flags) {
     sp.bcs_b = d.bcs_b;
     sp.flags = flags;
     sp.nc_total = d.nc;
+    sp.wg_target = 256;
 }
 
 static inline const void* off(const void* p, int64_t elems, size_t esz) { return p ? (const char*)p + elems * (int64_t)esz : nullptr; }
@@ -224,6 +225,11 @@ static int lanes(const Dims& d, bool mfma) {
     return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
 }
 
+// Workgroups a launch should have at least.  One segment at a time: one per compute unit.  Several
+// segments in flight: half as many, twice as long -- launches of the other lanes fill the machine, and
+// the per-workgroup prologue (fetching the operands shared by all heads) is paid half as often.
+static int wg_target(int nlanes) { return nlanes > 1 ? 128 : 256; }
+
 static bool fork_lanes(Pipe* pp, int n, hipStream_t st) {
     if (n <= 1) return true;
     if (hipEventRecord(pp->fork, st) != hipSuccess) return false;
@@ -246,8 +252,9 @@ extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backw
     Dims d;
     if (check_shape(shape, &d) != SSD_OK) return 0;
     // never 0 for a valid shape, so that 0 unambiguously means "invalid"
-    const size_t block = align_up(ws_layout(d, is_backward != 0).total);
-    const size_t t = lanes(d, use_mfma(*shape, 0)) * block + (is_backward ? shared_bytes(d) : 0);
+    const int nl = lanes(d, use_mfma(*shape, 0));
+    const size_t block = align_up(ws_layout(d, is_backward != 0, wg_target(nl)).total);
+    const size_t t = nl * block + (is_backward ? shared_bytes(d) : 0);
     return t ? t : 256;
 }
 
@@ -271,9 +278,9 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     }
     if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
-    const WsLayout w = ws_layout(d, false);
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
+    const WsLayout w = ws_layout(d, false, wg_target(nl));
     const size_t block = align_up(w.total);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block) return SSD_ERR_WORKSPACE;
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
@@ -282,6 +289,7 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     SegParams sps[NPIPE];
     for (int i = 0; i < nl; ++i) {
         base_params(sps[i], d, flags);
+        sps[i].wg_target = wg_target(nl);
         bind_workspace(sps[i], w, (char*)workspace + i * block, false);
         sps[i].A = A;
         sps[i].D = D;
@@ -333,9 +341,9 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!x || !dt || !A || !B || !C || !D || !dy || !dx || !ddt || !dB || !dC) return SSD_ERR_NULL;
     if (dx == dy) return SSD_ERR_ARG;
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
-    const WsLayout w = ws_layout(d, true);
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
+    const WsLayout w = ws_layout(d, true, wg_target(nl));
     const size_t block = align_up(w.total);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d)) return SSD_ERR_WORKSPACE;
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
@@ -347,6 +355,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     for (int i = 0; i < nl; ++i) {
         SegParams& sp = sps[i];
         base_params(sp, d, flags);
+        sp.wg_target = wg_target(nl);
         bind_workspace(sp, w, (char*)workspace + i * block, true);
         sp.A = A;
         sp.D = D;

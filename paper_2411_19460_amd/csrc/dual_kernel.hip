@@ -340,7 +340,7 @@ hipError_t launch_dual_q(const SegParams& sp0, int kid, hipStream_t st) {
     SegParams sp = sp0;
     // as few head slices as still give every compute unit a workgroup: the persistent operands are then
     // shared by as many heads as possible
-    sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G, 256);
+    sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G, sp.wg_target);
     SSDK_LAUNCH(kid, st, (mk_dual<Q, EPI>), dim3(sp.Bt * sp.nc * sp.G * sp.dual_split), dim3(DualCfg<Q>::NTHR), sp);
     return hipSuccess;
 }

@@ -283,7 +283,7 @@ hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
     {   // chunk states; on the backward path (need_y false) the local state adjoints ride in the same launch
         SegParams so = sp;
         const int nroles = need_y ? 1 : 2;
-        so.outer_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G * nroles, 256);
+        so.outer_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G * nroles, sp.wg_target);
         SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, mk_chunk_outer<Q>, dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
     }
     SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);

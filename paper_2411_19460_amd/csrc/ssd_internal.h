@@ -87,6 +87,7 @@ struct SegParams {
     int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
     int part_split;      // number of head slices of the dB / dC head sums
     int outer_split;     // number of head slices of the chunk-state / local-adjoint kernel
+    int wg_target;       // least number of workgroups a persistent-over-heads launch should have
     float* dbc_part;     // [Bt][nc][G][part_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
     const float* state_in;   // state entering the segment, or NULL for zeros
@@ -128,7 +129,7 @@ struct WsLayout {
 };
 
 int check_shape(const ssd_shape_t* sh, Dims* d);
-WsLayout ws_layout(const Dims& d, bool bwd);
+WsLayout ws_layout(const Dims& d, bool bwd, int wg_target = 256);
 void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd);
 void base_params(SegParams& sp, const Dims& d, uint32_t flags);
 bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
