@@ -21,35 +21,65 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 VALU_FP32_PEAK_TFLOPS = 157.3
 
 
-def kernel_models(cfg, tokens_per_launch):
-    """Algorithmic work of one launch of each kernel: (bound, amount) with amount in flop (MAC = 2)
-    for contractions and in bytes for bandwidth-bound kernels.  Dense Q x Q counts, per token:
-      chunk_state 2NP*H | cb 2QN*G | chunk_out (2QP+2NP)*H | dstate_local (restore + local adjoint) 4NP*H
-      bwd_main (2QP+2NP)*H | state_dots 4NP*H | dG 2QP*H | dBC 4NP*H | dBC_final 4QN*G
-      state scans, per (chunk, head) state of P*N elements (matrix-core path, everything bf16 in memory):
+def kernel_models(cfg, tokens_per_launch, generic=False):
+    """Algorithmic work of one launch of each kernel: (flop, bytes), MAC = 2 flop, dense Q x Q counts.
+    Bytes are the tensors the step must read and write once (operands and results of that step; not
+    the partial sums a launch configuration adds).  Per token, with X = H*P*e (one x-shaped tensor of
+    element size e), S = H*P*N*2/Q (chunk states, bf16 in memory on the matrix-core path), R = 4H (one
+    fp32 per-(token, head) array), b = G*N*e (B or C), g = G*Q*e (one row of the Q x Q matrix G):
+      chunk_state   2NP*H   | x, cum, w, B -> states                      X + 2R + b + S
+      cb            2QN*G   | B, C -> G and its transpose                 2b + 2g
+      chunk_out  (2QP+2NP)H | x, states, G, C, cum, dt -> y               2X + S + g + b + 2R
+      dstate_local  4NP*H   | x, dy, cum, w, B, C -> states, local adj.   2X + 2R + 2b + 2S
+      bwd_main   (2QP+2NP)H | dy, x, adjoints, G^T, B, cum, dt -> dx + 3 scalar rows   3X + S + g + b + 5R
+      dG            2QP*H   | x, dy, cum, dt, G -> dG, row-minus-column sums of E       2X + 2R + 2g + R
+      dBC           4NP*H   | x, dy, states, adjoints, cum, w, B, C -> dB/dC state terms (fp32), two dot rows
+                                                                          2X + 2S + 2R + 2b + 2*G*N*4 + 2R
+      dBC_final     4QN*G   | dG, B, C, state terms -> dB, dC             g + 2b + 2*G*N*4 + 2b
+      state scans, per (chunk, head) state of P*N elements (matrix-core path, bf16 in memory):
       forward reads the chunk state and writes the entering state (4 B/element), reverse reads the
       local adjoint and the entering state and writes the total adjoint (6 B/element).
     A launch covers one segment: tokens_per_launch = batch * segment."""
     H, P, N, G, Q = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk
     t = tokens_per_launch
     esz = 2 if cfg.dtype == "bf16" else 4
+    mfma = cfg.dtype == "bf16" and not generic   # the matrix-core path keeps only bf16 copies of the scanned states
+    X, R, b, g = H * P * esz, 4 * H, G * N * esz, G * Q * esz
+    S, S4 = H * P * N * 2 / Q, H * P * N * 4 / Q
     st = P * N * H / Q
     m = {
-        "mfma_chunk_state": ("flop", 2 * N * P * H), "mfma_cb": ("flop", 2 * Q * N * G),
-        "mfma_chunk_out": ("flop", (2 * Q * P + 2 * N * P) * H), "mfma_dstate_local": ("flop", 4 * N * P * H),
-        "mfma_bwd_main": ("flop", (2 * Q * P + 2 * N * P) * H), "mfma_state_dots": ("flop", 4 * N * P * H),
-        "mfma_dG": ("flop", 2 * Q * P * H), "mfma_dBC": ("flop", 4 * N * P * H), "mfma_dBC_final": ("flop", 4 * Q * N * G),
-        # shape-generic fp32 FMA kernels
-        "chunk_state": ("flop", 2 * N * P * H), "cb": ("flop", 2 * Q * N * G),
-        "chunk_out": ("flop", (2 * Q * P + 2 * N * P) * H), "dstate_local": ("flop", 2 * N * P * H),
-        "bwd_main": ("flop", (4 * Q * P + 4 * N * P) * H), "dG": ("flop", 2 * Q * P * H),
-        "dBC": ("flop", 4 * N * P * H + 4 * Q * N * G),
-        "cumsum": ("byte", H * esz + 4 * 4 * H), "ddt_finalize": ("byte", 6 * 4 * H + H * esz),
+        "mfma_chunk_state": (2 * N * P * H, X + 2 * R + b + S), "mfma_cb": (2 * Q * N * G, 2 * b + 2 * g),
+        "mfma_chunk_out": ((2 * Q * P + 2 * N * P) * H, 2 * X + S + g + b + 2 * R),
+        "mfma_dstate_local": (4 * N * P * H, 2 * X + 2 * R + 2 * b + 2 * S),
+        "mfma_bwd_main": ((2 * Q * P + 2 * N * P) * H, 3 * X + S + g + b + 5 * R),
+        "mfma_dG": (2 * Q * P * H, 2 * X + 3 * R + 2 * g),
+        "mfma_dBC": (4 * N * P * H, 2 * X + 2 * S + 4 * R + 2 * b + 8 * G * N),
+        "mfma_dBC_final": (4 * Q * N * G, g + 4 * b + 8 * G * N),
+        # shape-generic fp32 FMA kernels (same operands; their states are fp32)
+        "chunk_state": (2 * N * P * H, X + 2 * R + b + S4), "cb": (2 * Q * N * G, 2 * b + 2 * g),
+        "chunk_out": ((2 * Q * P + 2 * N * P) * H, 2 * X + S4 + g + b + 2 * R),
+        "dstate_local": (2 * N * P * H, X + R + b + S4),
+        "bwd_main": ((4 * Q * P + 4 * N * P) * H, 3 * X + 2 * S4 + 2 * g + 2 * b + 5 * R),
+        "dG": (2 * Q * P * H, 2 * X + 2 * R + g),
+        "dBC": (4 * N * P * H + 4 * Q * N * G, 2 * X + 2 * S4 + 2 * R + g + 4 * b),
+        "cumsum": (0, H * esz + 4 * 4 * H), "ddt_finalize": (0, 6 * 4 * H + H * esz),
+        "state_scan_fwd": (0, (4 if mfma else 8) * st), "state_scan_bwd": (0, (6 if mfma else 12) * st),
     }
-    mfma = cfg.dtype == "bf16"   # matrix-core path keeps only bf16 copies of the scanned states
-    m["state_scan_fwd"] = ("byte", (4 if mfma else 8) * st)
-    m["state_scan_bwd"] = ("byte", (6 if mfma else 12) * st)
-    return {k: (kind, per_tok * t) for k, (kind, per_tok) in m.items()}
+    return {k: (fl * t, by * t) for k, (fl, by) in m.items()}
+
+
+def path_model(cfg):
+    """Algorithmic work of the whole path per token of one layer (forward, restore, backward):
+    flop = (2QP + 4NP)H + 2QN*G forward, twice that backward, (2NP)H + 2QN*G restore;
+    bytes = forward reads x, dt, B, C and writes y; backward reads x, dt, B, C, dy and writes dx, ddt,
+    dB, dC; the restore re-reads x, dt, B, C; the fp32 segment checkpoints are written and read once."""
+    H, P, N, G, Q = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups, cfg.chunk
+    esz = 2 if cfg.dtype == "bf16" else 4
+    X, d, b = H * P * esz, H * esz, G * N * esz
+    fwd_fl = (2 * Q * P + 4 * N * P) * H + 2 * Q * N * G
+    flop = 3 * fwd_fl + 2 * N * P * H + 2 * Q * N * G
+    byte = (2 * X + d + 2 * b) + (3 * X + 2 * d + 4 * b) + (X + d + 2 * b) + 2 * H * P * N * 4 / cfg.segment
+    return flop, byte
 
 
 def measured_traffic(kernel, workload):
@@ -160,7 +190,7 @@ def main():
     for _ in range(max(1, args.warmup)):
         step()
     torch.cuda.synchronize()
-    models = kernel_models(cfg, Bt * cfg.segment)
+    models = kernel_models(cfg, Bt * cfg.segment, args.generic)
     dom = max((k for k in prof_all if k in models), key=lambda k: prof_all[k][0])
     # Pass 2, the timed region: exactly `steps` steps, up to four segments in flight, events only around
     # the dominant kernel (its launches then share the GPU with kernels of the other segments).
@@ -176,28 +206,40 @@ def main():
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     tok_s = Bt * L / (ms_per_step * 1e-3)
 
+    def bound_of(name):
+        """The roofline that binds a kernel: the matrix cores (fp32 vector ALUs for the shape-generic
+        kernels) if its flop/byte is above the machine's ridge for that unit, HBM otherwise."""
+        fl, by = models[name]
+        peak_fl = MFMA_BF16_PEAK_TFLOPS if name.startswith("mfma_") else VALU_FP32_PEAK_TFLOPS
+        if fl and fl / by >= peak_fl * 1e12 / (HBM_PEAK_GBS * 1e9):
+            return ("mfma" if name.startswith("mfma_") else "alu"), peak_fl, "TFLOP/s", fl / 1e12
+        return "hbm", HBM_PEAK_GBS, "GB/s", by / 1e9
+
     def entry(name, ms, n, nsteps):
         ent = {"ms_per_step": ms / nsteps, "launches_per_step": n // nsteps, "avg_us": ms * 1e3 / n}
         if name in models:
-            kind, amount = models[name]
-            rate = amount / (ms / n * 1e-3)
-            ent["achieved"] = rate / 1e12 if kind == "flop" else rate / 1e9
-            ent["unit"] = "TFLOP/s" if kind == "flop" else "GB/s"
+            bound, peak, unit, amount = bound_of(name)
+            sec = ms / n * 1e-3
+            ent.update({"bound": bound, "achieved": amount / sec, "unit": unit, "frac": amount / sec / peak})
+            fl, by = models[name]
+            if fl:
+                ent["tflops"] = fl / sec / 1e12
+            ent["algorithmic_gbs"] = by / sec / 1e9
         return ent
 
     nsteps1 = max(1, min(args.steps, 3))
     kernels = {name: entry(name, ms, n, nsteps1) for name, (ms, n) in prof_all.items()}
     dment = entry(dom, prof_dom[dom][0], prof_dom[dom][1], args.steps)   # from the timed region
-    kind, amount = models[dom]
-    if kind == "byte":
-        bound, peak, unit = "hbm", HBM_PEAK_GBS, "GB/s"
-    elif dom.startswith("mfma_"):
-        bound, peak, unit = "mfma", MFMA_BF16_PEAK_TFLOPS, "TFLOP/s"
-    else:
-        bound, peak, unit = "alu", VALU_FP32_PEAK_TFLOPS, "TFLOP/s"
+    bound, peak, unit, _ = bound_of(dom)
     roofline = {"kernel": dom, "bound": bound, "achieved": dment["achieved"], "peak": peak, "unit": unit,
-                "frac": dment["achieved"] / peak, "traffic": measured_traffic(dom, cfg.name),
-                "avg_launch_us": dment["avg_us"], "share_of_step": dment["ms_per_step"] / ms_per_step}
+                "frac": dment["frac"], "traffic": measured_traffic(dom, cfg.name),
+                "avg_launch_us": dment["avg_us"], "share_of_step": dment["ms_per_step"] / ms_per_step,
+                "serialized_avg_launch_us": kernels[dom]["avg_us"], "serialized_frac": kernels[dom]["frac"]}
+    pfl, pby = path_model(cfg)
+    roofline_path = {"bound": "hbm" if pfl / pby < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) else "mfma",
+                     "algorithmic_bytes_per_token": pby, "algorithmic_flop_per_token": pfl,
+                     "achieved_gbs": pby * tok_s / 1e9, "frac_hbm": pby * tok_s / 1e9 / HBM_PEAK_GBS,
+                     "achieved_tflops": pfl * tok_s / 1e12, "frac_mfma": pfl * tok_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
     full = pk.make_shape(d["x"], d["B"], cfg.chunk, None)
     state_bytes = Bt * H * P * N * 4
@@ -216,7 +258,7 @@ def main():
                    "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment,
                    "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma",
                    "segments_in_flight": min(4, nseg) if not args.generic else 1},
-        "roofline": roofline, "kernels_serialized": kernels, "peak_hbm": peak_hbm,
+        "roofline": roofline, "roofline_path": roofline_path, "kernels_serialized": kernels, "peak_hbm": peak_hbm,
     }
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)

@@ -6,8 +6,8 @@
 //                             y = yhat + D x  (+ x under the residual flag)
 //   EPI 2 (backward):         u^T[p][j] = sum_{i>=j} G[i][j] decay(i,j) dY_i[p] + exp(T - cum_j) (dHnext B_j)[p];
 //                             dx = dt u + D dY (+ dY), f_j = x_j . u_j (the direct part of ddt) and dY_j . x_j (for dD)
-// (EPI 1, the forward form reduced to dY_i . yhat_i, is kept for reference but not launched: the gradient
-// of cum is assembled from the E sums of the dG kernel and the state dot products of the head-sum kernel.)
+// (The gradient of cum is not formed here: it is assembled from the E sums of the dG kernel and the
+// state dot products of the head-sum kernel.)
 //
 // Organisation.  One workgroup owns one (batch, chunk, group) and a slice of that group's heads and
 // walks the heads one after the other.  It has one wave per 32-token tile of the chunk; the tile
@@ -61,9 +61,8 @@ struct Pre {
 
 struct HeadCtx {
     const bf16_t* xg;   // x rows of this chunk and head
-    const bf16_t* dyg;  // dY rows (EPI 1, 2)
+    const bf16_t* dyg;  // dY rows (EPI 2)
     bf16_t* outp;       // y (EPI 0) or dx (EPI 2)
-    float* gterm;
     float* fterm;
     float* dDrow;
     int64_t xt;
@@ -219,9 +218,9 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     }
     // epilogue: in the accumulators this lane owns token `tok` and, per register group q, four
     // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses.
-    // The wave's own 32 rows of the other token-major tensor come in as whole rows (EPI 1: dY, EPI 2: x).
+    // Reverse, the wave's own 32 rows of x come in as whole rows.
     if (EPI != 0) {
-        const bf16_t* src = EPI == 1 ? cx.dyg : cx.xg;
+        const bf16_t* src = cx.xg;
         bf16x8 own[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it)
@@ -238,52 +237,41 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
-            const bf16x4 mine = *(const bf16x4*)(L.raw + tok * XPITCH + p4 * 2);  // x (EPI 0, 1) or dY (EPI 2)
+            const bf16x4 mine = *(const bf16x4*)(L.raw + tok * XPITCH + p4 * 2);  // x (EPI 0) or dY (EPI 2)
             if (EPI == 0) {
 #pragma unroll
                 for (int e = 0; e < 4; ++e) outv[4 * pt + q][e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)mine[e]);
             } else {
-                const bf16x4 other = *(const bf16x4*)(priv + tl * XPITCH + p4 * 2);  // dY (EPI 1) or x (EPI 2)
-                if (EPI == 1) {
+                const bf16x4 other = *(const bf16x4*)(priv + tl * XPITCH + p4 * 2);  // x
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) s_a += (float)other[e] * (pt ? acc1 : acc0)[4 * q + e];
-                } else {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const float u = (pt ? acc1 : acc0)[4 * q + e];
-                        outv[4 * pt + q][e] = (__bf16)(dtok * u + cx.Dh * (float)mine[e]);
-                        s_a += (float)other[e] * u;
-                        s_b += (float)mine[e] * (float)other[e];
-                    }
+                for (int e = 0; e < 4; ++e) {
+                    const float u = (pt ? acc1 : acc0)[4 * q + e];
+                    outv[4 * pt + q][e] = (__bf16)(dtok * u + cx.Dh * (float)mine[e]);
+                    s_a += (float)other[e] * u;
+                    s_b += (float)mine[e] * (float)other[e];
                 }
             }
         }
     }
-    if (EPI != 1) {
-        if (EPI == 2) lds_wave_fence();  // every read of x from the patch is done
+    if (EPI == 2) lds_wave_fence();  // every read of x from the patch is done
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt)
+    for (int pt = 0; pt < 2; ++pt)
 #pragma unroll
-            for (int q = 0; q < 4; ++q)
-                *(bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2) = outv[4 * pt + q];
-        lds_wave_fence();
+        for (int q = 0; q < 4; ++q)
+            *(bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2) = outv[4 * pt + q];
+    lds_wave_fence();
 #pragma unroll
-        for (int it = 0; it < 4; ++it) {
-            const int row = (lane >> 3) + 8 * it;
-            const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
-            *(bf16x8*)(cx.outp + (int64_t)(tok0 + row) * cx.xt + (lane & 7) * 8) = v;
-        }
+    for (int it = 0; it < 4; ++it) {
+        const int row = (lane >> 3) + 8 * it;
+        const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
+        *(bf16x8*)(cx.outp + (int64_t)(tok0 + row) * cx.xt + (lane & 7) * 8) = v;
     }
     if (EPI != 0) {
         s_a += __shfl_xor(s_a, 32, 64);
         s_b += __shfl_xor(s_b, 32, 64);
         if (lane < 32) {
-            if (EPI == 1) {
-                cx.gterm[tok] = s_a;
-            } else {
-                cx.fterm[tok] = s_a;
-                cx.dDrow[tok] = s_b;
-            }
+            cx.fterm[tok] = s_a;
+            cx.dDrow[tok] = s_b;
         }
     }
 }
@@ -324,9 +312,7 @@ __global__ __launch_bounds__(DualCfg<Q>::NTHR) void mk_dual(SegParams sp) {
         const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
         cx.xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
         cx.dyg = EPI == 0 ? nullptr : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
-        cx.outp = EPI == 0 ? (bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow
-                           : (EPI == 2 ? (bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow : nullptr);
-        cx.gterm = sp.gterm + cbase;
+        cx.outp = EPI == 0 ? (bf16_t*)sp.y + (int64_t)b * sp.ys_b + xrow : (bf16_t*)sp.dx + (int64_t)b * sp.dxs_b + xrow;
         cx.fterm = sp.fterm + cbase;
         cx.dDrow = sp.dDrow + cbase;
         cx.xt = xt;
