@@ -36,6 +36,7 @@ def kernel_models(cfg, tokens_per_launch, generic=False):
       dBC           4NP*H   | x, dy, states, adjoints, cum, w, B, C -> dB/dC state terms (fp32), two dot rows
                                                                           2X + 2S + 2R + 2b + 2*G*N*4 + 2R
       dBC_final     4QN*G   | dG, B, C, state terms -> dB, dC             g + 2b + 2*G*N*4 + 2b
+      bwd_trio = bwd_main + dG + dBC as one launch (chunk 256): flop add up; x and dY count once
       state scans, per (chunk, head) state of P*N elements (matrix-core path, bf16 in memory):
       forward reads the chunk state and writes the entering state (4 B/element), reverse reads the
       local adjoint and the entering state and writes the total adjoint (6 B/element).
@@ -55,6 +56,8 @@ def kernel_models(cfg, tokens_per_launch, generic=False):
         "mfma_dG": (2 * Q * P * H, 2 * X + 3 * R + 2 * g),
         "mfma_dBC": (4 * N * P * H, 2 * X + 2 * S + 4 * R + 2 * b + 8 * G * N),
         "mfma_dBC_final": (4 * Q * N * G, g + 4 * b + 8 * G * N),
+        # bwd_main + dG + dBC in one launch (Q = 256): x and dY are read once for the three
+        "mfma_bwd_trio": ((4 * Q * P + 6 * N * P) * H, 3 * X + 3 * S + 3 * g + 3 * b + 12 * R + 8 * G * N),
         # shape-generic fp32 FMA kernels (same operands; their states are fp32)
         "chunk_state": (2 * N * P * H, X + 2 * R + b + S4), "cb": (2 * Q * N * G, 2 * b + 2 * g),
         "chunk_out": ((2 * Q * P + 2 * N * P) * H, 2 * X + S4 + g + b + 2 * R),

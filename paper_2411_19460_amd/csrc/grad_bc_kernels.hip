@@ -16,6 +16,7 @@
 //   mk_dBC_final: sums the slices, contracts dG with B / dG^T with C, adds the head sums, rounds once.
 // The decay of an off-diagonal tile is the product of a per-row factor, a per-column factor and a
 // per-tile scalar, all <= 1 (32-token granularity); diagonal tiles evaluate exp() per element.
+#include "dual_body.h"
 #include "mfma_common.h"
 
 namespace ssdk {
@@ -248,12 +249,10 @@ __device__ __forceinline__ void dg_emit_sums(const SegParams& sp, const DgLds<Q>
 }
 
 template <int Q>
-__global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
+__device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z, int nblk) {
     typedef DgMap<Q> M;
     constexpr int MAXT = M::MAXT;
-    __shared__ __attribute__((aligned(16))) DgLds<Q> L;
-    int z = blockIdx.x;
-    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    if ((nblk & 7) == 0) z = (z & 7) * (nblk >> 3) + (z >> 3);
     const int ns = sp.dg_split, slice = z % ns;
     z /= ns;
     const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
@@ -327,6 +326,12 @@ __global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
         }
 }
 
+template <int Q>
+__global__ __launch_bounds__(64 * DgMap<Q>::NWV) void mk_dG(SegParams sp) {
+    __shared__ __attribute__((aligned(16))) DgLds<Q> L;
+    dg_body<Q>(sp, L, blockIdx.x, gridDim.x);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Head sums of dC (role 0) and dB (role 1):
 //   role 0:  part[i][n] = sum_h exp(cum_h,i) (dY_h,i . Hprev_h[:, n])
@@ -398,12 +403,10 @@ __device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, 
 }
 
 template <int Q>
-__global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
+__device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, int z, int nblk) {
     typedef PartCfg<Q> CF;
     constexpr int RT = CF::RT;
-    __shared__ __attribute__((aligned(16))) PartLds<Q> L;
-    int z = blockIdx.x;
-    if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
+    if ((nblk & 7) == 0) z = (z & 7) * (nblk >> 3) + (z >> 3);
     const int ns = sp.part_split, slice = z % ns;
     z /= ns;
     const int role = z & 1;
@@ -472,6 +475,47 @@ __global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
 #pragma unroll
             for (int r = 0; r < 16; ++r)
                 part[(int64_t)(32 * (rg * RT + rt) + acc_row(r, lane)) * N_ + 64 * nh + 32 * nt + (lane & 31)] = acc[rt][nt][r];
+}
+
+template <int Q>
+__global__ __launch_bounds__(PartCfg<Q>::NTHR) void mk_dBC_part(SegParams sp) {
+    __shared__ __attribute__((aligned(16))) PartLds<Q> L;
+    part_body<Q>(sp, L, blockIdx.x, gridDim.x);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The three head-walking passes of the backward sweep that follow the state scans -- dx (reverse dual
+// form), dG and the dB / dC head sums -- as one launch: they read the same dY and x tiles, and
+// workgroups that run side by side find in cache what their neighbours fetched.  Needs the three
+// passes to use the same workgroup size (Q = 256).  With equal workgroup counts, a multiple of 8, the
+// passes alternate in groups of 8 consecutive workgroup ids, so that the workgroups of the three
+// passes that work on one chunk land on the same XCD (ids are dealt round-robin over the 8 XCDs) and are
+// dispatched together.
+template <int Q>
+union TrioLds {
+    dualk::DualLds<Q> dual;
+    DgLds<Q> dg;
+    PartLds<Q> part;
+};
+
+template <int Q>
+__global__ __launch_bounds__(512) void mk_bwd_trio(SegParams sp, int n_dual, int n_dg, int n_part) {
+    static_assert(dualk::DualCfg<Q>::NTHR == 512 && 64 * DgMap<Q>::NWV == 512 && PartCfg<Q>::NTHR == 512, "one workgroup size");
+    __shared__ __attribute__((aligned(16))) TrioLds<Q> L;
+    int z = blockIdx.x, pass;
+    if (n_dual == n_dg && n_dg == n_part && (n_dual & 7) == 0) {
+        pass = (z >> 3) % 3;
+        z = ((z >> 3) / 3) * 8 + (z & 7);
+    } else {
+        pass = z < n_dual ? 0 : (z < n_dual + n_dg ? 1 : 2);
+        z -= pass == 0 ? 0 : (pass == 1 ? n_dual : n_dual + n_dg);
+    }
+    if (pass == 0)
+        dualk::dual_body<Q, 2>(sp, L.dual, z, n_dual);
+    else if (pass == 1)
+        dg_body<Q>(sp, L.dg, z, n_dg);
+    else
+        part_body<Q>(sp, L.part, z, n_part);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -569,20 +613,29 @@ __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
 }
 
 template <int Q>
-hipError_t grad_bc_q(const SegParams& sp, hipStream_t st) {
-    SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(sp.Bt * sp.nc * sp.G * sp.dg_split), dim3(64 * DgMap<Q>::NWV), sp);
-    SSDK_LAUNCH(K_MFMA_DBC, st, mk_dBC_part<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * sp.part_split), dim3(PartCfg<Q>::NTHR), sp);
+hipError_t grad_bc_q(const SegParams& sp0, bool with_dual, hipStream_t st) {
+    SegParams sp = sp0;
+    const int n_dg = sp.Bt * sp.nc * sp.G * sp.dg_split, n_part = sp.Bt * sp.nc * sp.G * 2 * sp.part_split;
+    if (with_dual) {
+        if (Q != 256) return hipErrorInvalidValue;
+        sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G, sp.wg_target);
+        const int n_dual = sp.Bt * sp.nc * sp.G * sp.dual_split;
+        SSDK_LAUNCH(K_MFMA_BWD_TRIO, st, mk_bwd_trio<256>, dim3(n_dual + n_dg + n_part), dim3(512), sp, n_dual, n_dg, n_part);
+    } else {
+        SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(n_dg), dim3(64 * DgMap<Q>::NWV), sp);
+        SSDK_LAUNCH(K_MFMA_DBC, st, mk_dBC_part<Q>, dim3(n_part), dim3(PartCfg<Q>::NTHR), sp);
+    }
     SSDK_LAUNCH(K_MFMA_DBC_FINAL, st, mk_dBC_final<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * (Q / 32)), dim3(NTH), sp);
     return hipSuccess;
 }
 
 }  // namespace
 
-hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st) {
+hipError_t mfma_launch_grad_bc(const SegParams& sp, bool with_dual, hipStream_t st) {
     switch (sp.Q) {
-        case 64: return grad_bc_q<64>(sp, st);
-        case 128: return grad_bc_q<128>(sp, st);
-        case 256: return grad_bc_q<256>(sp, st);
+        case 64: return grad_bc_q<64>(sp, with_dual, st);
+        case 128: return grad_bc_q<128>(sp, with_dual, st);
+        case 256: return grad_bc_q<256>(sp, with_dual, st);
         default: return hipErrorInvalidValue;
     }
 }

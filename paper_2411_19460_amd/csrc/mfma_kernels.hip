@@ -306,9 +306,12 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     if (sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
     SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
     if (sp.ev_record && hipEventRecord(sp.ev_record, st) != hipSuccess) return hipErrorUnknown;
-    hipError_t e = mfma_launch_dual(sp, 2, st);
+    // dx, dG and the dB / dC head sums (which also write the chunk-local part of the gradient of cum
+    // and the state dot products): one launch when the three share a workgroup size
+    const bool trio = Q == 256;
+    hipError_t e = trio ? hipSuccess : mfma_launch_dual(sp, 2, st);
     if (e != hipSuccess) return e;
-    e = mfma_launch_grad_bc(sp, st);  // also writes the chunk-local part of the gradient of cum
+    e = mfma_launch_grad_bc(sp, trio, st);
     if (e != hipSuccess) return e;
     sp.flags |= SSD_INTERNAL_SPLIT_GTERM;
     e = generic_backward_scalars(sp, st);

@@ -138,7 +138,7 @@ bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
 enum KernelId {
     K_CUMSUM, K_CB, K_CHUNK_STATE, K_SCAN_FWD, K_CHUNK_OUT, K_DSTATE, K_SCAN_BWD, K_BWD_MAIN, K_DDT, K_PARAM, K_DG, K_DBC,
     K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
-    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_COUNT
+    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_MFMA_BWD_TRIO, K_COUNT
 };
 void prof_begin(int kid, hipStream_t st);
 void prof_end(int kid, hipStream_t st);
@@ -170,7 +170,7 @@ hipError_t mfma_backward_segment(const SegParams& sp, hipStream_t st);
 // One dual-form pass over a segment: epi 0 = forward output, 2 = the backward pass.
 hipError_t mfma_launch_dual(const SegParams& sp, int epi, hipStream_t st);
 // dG, the head sums and the final contraction that give dB and dC of one segment.
-hipError_t mfma_launch_grad_bc(const SegParams& sp, hipStream_t st);
+hipError_t mfma_launch_grad_bc(const SegParams& sp, bool with_dual, hipStream_t st);
 // Smallest divisor ns of heads_per_group with base * ns >= target workgroups (else heads_per_group).
 int pick_split(int heads_per_group, int64_t base, int target);
 
