@@ -162,8 +162,8 @@ def main():
     shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
     Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
     nseg = L // cfg.segment
-    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True), dtype=torch.uint8, device=dev)
+    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False, flags), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True, flags), dtype=torch.uint8, device=dev)
     out_f = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev),
              "boundary_states": torch.empty((Bt, nseg, H, P, N), device=dev)}
     out_b = {"dx": torch.empty_like(d["x"]), "ddt": torch.empty_like(d["dt"]), "dB": torch.empty_like(d["B"]),
@@ -247,8 +247,8 @@ def main():
     full = pk.make_shape(d["x"], d["B"], cfg.chunk, None)
     state_bytes = Bt * H * P * N * 4
     peak_hbm = {
-        "magc_bytes": pk.ssd_workspace_bytes(shape, True) + nseg * state_bytes,
-        "full_activation_bytes": pk.ssd_workspace_bytes(full, True),
+        "magc_bytes": pk.ssd_workspace_bytes(shape, True, flags) + nseg * state_bytes,
+        "full_activation_bytes": pk.ssd_workspace_bytes(full, True, flags),
         "note": "scratch + checkpoints beyond the inputs/outputs: MA-GC (segment checkpoints + one segment's "
                 "chunk states) vs keeping every chunk state of the sequence alive (segment = L)",
     }

@@ -87,8 +87,12 @@ enum {
  * per-segment recomputation store (the M_state term of App. C) -- one per segment in flight, up
  * to four when the sequence has that many segments -- plus, for the backward pass, eight
  * bytes per (chunk, head) of the whole sequence for the partial sums of dA and dD.
- * Returns 0 for an invalid shape. */
+ * Returns 0 for an invalid shape.  The figure is for flags = 0; a call that passes
+ * SSD_FLAG_GENERIC_KERNELS needs ssd_workspace_bytes_flags (the shape-generic kernels keep their
+ * chunk states in fp32 and lay the scratch out differently). */
 size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward);
+/* The same for a call made with `flags` (only SSD_FLAG_GENERIC_KERNELS changes the result). */
+size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, uint32_t flags);
 
 /*
  * Forward (Layer_j(x, h) -> (x, h) of Alg. 1, for one layer over the whole sequence).

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
 SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
 
-EXPORTS = ("ssd_workspace_bytes", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -61,6 +61,8 @@ def lib():
         shp = ctypes.POINTER(ssd_shape_t)
         L.ssd_workspace_bytes.restype = sz
         L.ssd_workspace_bytes.argtypes = [shp, i32]
+        L.ssd_workspace_bytes_flags.restype = sz
+        L.ssd_workspace_bytes_flags.argtypes = [shp, i32, u32]
         L.ssd_fwd.restype = ctypes.c_int
         L.ssd_fwd.argtypes = [shp] + [vp] * 10 + [vp, sz, u32, vp]
         L.ssd_bwd.restype = ctypes.c_int
@@ -113,8 +115,8 @@ def make_shape(x, Bm, chunk: int, segment: Optional[int] = None) -> ssd_shape_t:
     return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, L if segment is None else segment, 0, 0, 0)
 
 
-def ssd_workspace_bytes(shape: ssd_shape_t, is_backward: bool) -> int:
-    return int(lib().ssd_workspace_bytes(ctypes.byref(shape), 1 if is_backward else 0))
+def ssd_workspace_bytes(shape: ssd_shape_t, is_backward: bool, flags: int = 0) -> int:
+    return int(lib().ssd_workspace_bytes_flags(ctypes.byref(shape), 1 if is_backward else 0, flags))
 
 
 def _check_inputs(x, dt, A, Bm, Cm, D, *more):
@@ -153,7 +155,7 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     bnd = out.get("boundary_states")
     if bnd is None and segment is not None:
         bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)
-    need = ssd_workspace_bytes(shape, False)
+    need = ssd_workspace_bytes(shape, False, flags)
     if workspace is None:
         workspace = _workspace(need, x.device)
     rc = lib().ssd_fwd(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(init_state),
@@ -184,7 +186,7 @@ def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_
     dinit = out.get("dinit_state")
     if dinit is None and want_dinit:
         dinit = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
-    need = ssd_workspace_bytes(shape, True)
+    need = ssd_workspace_bytes(shape, True, flags)
     if workspace is None:
         workspace = _workspace(need, x.device)
     rc = lib().ssd_bwd(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(init_state),

@@ -52,7 +52,7 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     return SSD_OK;
 }
 
-WsLayout ws_layout(const Dims& d, bool bwd, int wg_target) {
+WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target) {
     WsLayout w;
     memset(&w, 0, sizeof(w));
     size_t off = 0;
@@ -66,22 +66,23 @@ WsLayout ws_layout(const Dims& d, bool bwd, int wg_target) {
     w.nslice = (int)((PN + 255) / 256);
     w.cum = take(tok);
     w.dtf = take(tok);
-    w.states = take((size_t)d.Bt * (d.nc + 1) * d.H * PN * 4);
+    w.states = w.states_bf = w.dstates = w.dstates_bf = w.dbc_part = WS_NONE;  // present on one path only
+    if (!mfma) w.states = take((size_t)d.Bt * (d.nc + 1) * d.H * PN * 4);
     w.Gm = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
     w.ein = take(tok);
     w.eout = take(tok);
-    w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
+    if (mfma) w.states_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
     const int64_t groups = d.Bt * (int64_t)d.nc * d.G;
     w.dg_split = pick_split(d.hpg, groups, wg_target);
     w.part_split = pick_split(d.hpg, groups * 2, wg_target);
     if (bwd) {
-        w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
-        w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
+        if (!mfma) w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
+        if (mfma) w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
         {   // fp32 head sum (generic kernels) or one bf16 partial sum per head slice (MFMA kernels)
-            const size_t per = (size_t)d.Q * d.Q * 2 * w.dg_split;
-            w.dG = take((size_t)d.Bt * d.nc * d.G * (per > (size_t)d.Q * d.Q * 4 ? per : (size_t)d.Q * d.Q * 4));
+            const size_t per = mfma ? (size_t)d.Q * d.Q * 2 * w.dg_split : (size_t)d.Q * d.Q * 4;
+            w.dG = take((size_t)d.Bt * d.nc * d.G * per);
         }
-        w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.part_split * 2 * d.Q * d.N * 4);
+        if (mfma) w.dbc_part = take((size_t)d.Bt * d.nc * d.G * w.part_split * 2 * d.Q * d.N * 4);
         w.gterm = take(tok);
         w.sterm = take(tok);
         w.gintra = take(tok);
@@ -98,20 +99,21 @@ WsLayout ws_layout(const Dims& d, bool bwd, int wg_target) {
 
 void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd) {
     char* base = (char*)workspace;
+    auto at = [&](size_t off) { return off == WS_NONE ? nullptr : base + off; };
     sp.cum = (float*)(base + w.cum);
     sp.dtf = (float*)(base + w.dtf);
-    sp.states = (float*)(base + w.states);
+    sp.states = (float*)at(w.states);
     sp.Gm = (float*)(base + w.Gm);
     sp.nslice = w.nslice;
     sp.ein = (float*)(base + w.ein);
     sp.eout = (float*)(base + w.eout);
-    sp.states_bf = (bf16_t*)(base + w.states_bf);
+    sp.states_bf = (bf16_t*)at(w.states_bf);
     sp.dg_split = w.dg_split;
     sp.part_split = w.part_split;
     if (bwd) {
-        sp.dstates_bf = (bf16_t*)(base + w.dstates_bf);
-        sp.dbc_part = (float*)(base + w.dbc_part);
-        sp.dstates = (float*)(base + w.dstates);
+        sp.dstates_bf = (bf16_t*)at(w.dstates_bf);
+        sp.dbc_part = (float*)at(w.dbc_part);
+        sp.dstates = (float*)at(w.dstates);
         sp.dG = (float*)(base + w.dG);
         sp.gterm = (float*)(base + w.gterm);
         sp.sterm = (float*)(base + w.sterm);
@@ -248,14 +250,19 @@ static bool join_lanes(Pipe* pp, int n, hipStream_t st) {
 
 using namespace ssdk;
 
-extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward) {
+extern "C" size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, uint32_t flags) {
     Dims d;
     if (check_shape(shape, &d) != SSD_OK) return 0;
     // never 0 for a valid shape, so that 0 unambiguously means "invalid"
-    const int nl = lanes(d, use_mfma(*shape, 0));
-    const size_t block = align_up(ws_layout(d, is_backward != 0, wg_target(nl)).total);
+    const bool mfma = use_mfma(*shape, flags);
+    const int nl = lanes(d, mfma);
+    const size_t block = align_up(ws_layout(d, is_backward != 0, mfma, wg_target(nl)).total);
     const size_t t = nl * block + (is_backward ? shared_bytes(d) : 0);
     return t ? t : 256;
+}
+
+extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward) {
+    return ssd_workspace_bytes_flags(shape, is_backward, 0);
 }
 
 extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
@@ -280,7 +287,7 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
-    const WsLayout w = ws_layout(d, false, wg_target(nl));
+    const WsLayout w = ws_layout(d, false, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block) return SSD_ERR_WORKSPACE;
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
@@ -343,7 +350,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
-    const WsLayout w = ws_layout(d, true, wg_target(nl));
+    const WsLayout w = ws_layout(d, true, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d)) return SSD_ERR_WORKSPACE;
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;

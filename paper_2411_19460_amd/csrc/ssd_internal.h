@@ -121,7 +121,9 @@ struct Dims {
     int64_t xs_b, dts_b, bcs_b;
 };
 
-// Byte offsets of the per-segment scratch arrays inside the caller's workspace.
+// Byte offsets of the per-segment scratch arrays inside the caller's workspace (WS_NONE: the array
+// does not exist on the chosen kernel path and its pointer stays null).
+constexpr size_t WS_NONE = ~(size_t)0;
 struct WsLayout {
     size_t cum, dtf, states, Gm, dstates, dG, gterm, fterm, dDrow, tail_part, dA_part, dD_part, dcarry, total;
     size_t ein, eout, states_bf, dstates_bf, dbc_part, sterm, gintra;
@@ -129,7 +131,9 @@ struct WsLayout {
 };
 
 int check_shape(const ssd_shape_t* sh, Dims* d);
-WsLayout ws_layout(const Dims& d, bool bwd, int wg_target = 256);
+// mfma: the layout for the matrix-core kernels, which keep the chunk states and their adjoints in
+// bf16 only (the fp32 arrays of the shape-generic kernels are left out).
+WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target = 256);
 void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd);
 void base_params(SegParams& sp, const Dims& d, uint32_t flags);
 bool use_mfma(const ssd_shape_t& sh, uint32_t flags);

@@ -16,6 +16,7 @@ struct StackDims {
     Dims full;  // whole sequence
     Dims cell;  // one segment as its own call (seqlen = segment)
     int nl, l, nlg;
+    bool mfma;         // the cell runs on the matrix-core kernels
     size_t act_bytes;  // one [Bt, s, H, P] activation buffer
     size_t HPN;
 };
@@ -35,6 +36,7 @@ int check_stack(const ssd_shape_t* shape, int32_t nlayers, int32_t layer_interva
     sd->cell.xs_b = sd->full.xs_b;
     sd->cell.dts_b = sd->full.dts_b;
     sd->cell.bcs_b = sd->full.bcs_b;
+    sd->mfma = use_mfma(*shape, 0);
     sd->nl = nlayers;
     sd->l = layer_interval < nlayers ? layer_interval : nlayers;
     sd->nlg = (nlayers + sd->l - 1) / sd->l;
@@ -51,7 +53,7 @@ StackWs stack_ws(const StackDims& sd, bool bwd) {
     StackWs w;
     size_t o = 0;
     w.ssd = o;
-    o += align_up(ws_layout(sd.cell, bwd).total);
+    o += align_up(ws_layout(sd.cell, bwd, sd.mfma).total);
     w.act0 = o;
     // fwd: two ping-pong activation buffers; bwd: the cell's (l - 1) restored layer inputs plus two gradient buffers
     w.nact = bwd ? (size_t)(sd.l - 1) + 2 : 2;
@@ -89,7 +91,7 @@ extern "C" int magc_stack_fwd(const ssd_shape_t* shape, int32_t nlayers, int32_t
     const Dims& f = sd.full;
     const Dims& c = sd.cell;
     const bool mfma = use_mfma(*shape, 0);
-    const WsLayout wl = ws_layout(c, false);
+    const WsLayout wl = ws_layout(c, false, mfma);
     char* wsb = (char*)workspace;
     void* act[2] = {wsb + w.act0, wsb + w.act0 + sd.act_bytes};
     const int64_t cell_bs = f.s * f.H * f.P;  // batch stride of a workspace activation buffer
@@ -162,7 +164,7 @@ extern "C" int magc_stack_bwd(const ssd_shape_t* shape, int32_t nlayers, int32_t
     const Dims& f = sd.full;
     const Dims& c = sd.cell;
     const bool mfma = use_mfma(*shape, 0);
-    const WsLayout wl = ws_layout(c, true);
+    const WsLayout wl = ws_layout(c, true, mfma);
     char* wsb = (char*)workspace;
     const int64_t cell_bs = f.s * f.H * f.P;
     const int64_t HPN = (int64_t)sd.HPN;
