@@ -1,5 +1,5 @@
-// Optional per-kernel timing with HIP events recorded on the caller's stream (diagnostics for the
-// benchmark: off by default, not thread-safe, costs two event records per launch when on).
+// Optional per-kernel timing (diagnostics for the benchmark: off by default, not thread-safe).  Each
+// timed launch carries a start and a stop event that receive the kernel's own begin and end stamps.
 #include <vector>
 
 #include "ssd_internal.h"
@@ -34,17 +34,14 @@ hipEvent_t take_event() {
 
 }  // namespace
 
-void prof_begin(int kid, hipStream_t st) {
-    if (!g_on || (g_only >= 0 && kid != g_only)) return;
+bool prof_events(int kid, hipEvent_t* start, hipEvent_t* stop) {
+    if (!g_on || (g_only >= 0 && kid != g_only)) return false;
     Rec r{kid, take_event(), take_event()};
-    if (!r.a || !r.b) return;
-    (void)hipEventRecord(r.a, st);
+    if (!r.a || !r.b) return false;
     g_recs.push_back(r);
-}
-
-void prof_end(int kid, hipStream_t st) {
-    if (!g_on || g_recs.empty() || (g_only >= 0 && kid != g_only)) return;
-    (void)hipEventRecord(g_recs.back().b, st);
+    *start = r.a;
+    *stop = r.b;
+    return true;
 }
 
 }  // namespace ssdk

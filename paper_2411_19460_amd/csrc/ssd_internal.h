@@ -1,5 +1,6 @@
 // Internal declarations shared by the translation units of libssd_magc (not part of the ABI).
 #pragma once
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 #include <stdint.h>
@@ -144,18 +145,21 @@ enum KernelId {
     K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
     K_MFMA_DBC, K_MFMA_DBC_FINAL, K_MFMA_BWD_TRIO, K_COUNT
 };
-void prof_begin(int kid, hipStream_t st);
-void prof_end(int kid, hipStream_t st);
+// When timing of kernel `kid` is enabled: a pair of events for the launch to fill in (kernel start
+// and end, as the command processor stamps them -- the time the launch waits behind other work is
+// not part of it); otherwise false.
+bool prof_events(int kid, hipEvent_t* start, hipEvent_t* stop);
 
-// Launch on `st`, bracketed by timing events when enabled; returns the launch error from the
-// enclosing function.
-#define SSDK_LAUNCH(kid, st, kernel, grid, block, ...)                 \
-    do {                                                               \
-        ::ssdk::prof_begin(kid, st);                                   \
-        hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);   \
-        ::ssdk::prof_end(kid, st);                                     \
-        hipError_t e_ = hipGetLastError();                             \
-        if (e_ != hipSuccess) return e_;                               \
+// Launch on `st`, timed when enabled; returns the launch error from the enclosing function.
+#define SSDK_LAUNCH(kid, st, kernel, grid, block, ...)                                        \
+    do {                                                                                      \
+        hipEvent_t ea_ = nullptr, eb_ = nullptr;                                              \
+        if (::ssdk::prof_events(kid, &ea_, &eb_))                                             \
+            hipExtLaunchKernelGGL(kernel, grid, block, 0, st, ea_, eb_, 0, __VA_ARGS__);      \
+        else                                                                                  \
+            hipLaunchKernelGGL(kernel, grid, block, 0, st, __VA_ARGS__);                      \
+        hipError_t e_ = hipGetLastError();                                                    \
+        if (e_ != hipSuccess) return e_;                                                      \
     } while (0)
 
 // Launchers.  Each returns hipSuccess or the launch error.  is_bf16 selects the storage type.
