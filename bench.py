@@ -119,6 +119,58 @@ def cpu_baseline(cfg, seconds_target=15.0):
                       f"scaled by {hs}/{cfg.nheads} to all heads"}
 
 
+def inference_bench(args, cfg, pk, synth, torch, dev):
+    """Forward-only use of the path: prefill of the whole sequence in segments without checkpoints
+    (memory independent of L), then single-token recurrent steps from its final state."""
+    d = synth.make_layer_inputs_device(cfg, dev, with_dy=False)
+    Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
+    ws = torch.empty(pk.ssd_workspace_bytes(shape, False), dtype=torch.uint8, device=dev)
+    out = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev)}
+
+    def prefill():
+        pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, cfg.segment, None, 0, ws, out=out,
+                   want_boundary=False)
+
+    for _ in range(args.warmup):
+        prefill()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        prefill()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    one = {k: d[k][:, :1].contiguous() for k in ("x", "dt", "B", "C")}
+    y1 = torch.empty_like(one["x"])
+    state = out["final_state"].clone()
+    ntok = 200
+    for _ in range(10):
+        pk.ssd_decode(one["x"], one["dt"], d["A"], one["B"], one["C"], d["D"], state, out=y1)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(ntok):
+        pk.ssd_decode(one["x"], one["dt"], d["A"], one["B"], one["C"], d["D"], state, out=y1)
+    torch.cuda.synchronize()
+    us_tok = (time.perf_counter() - t0) * 1e6 / ntok
+    esz = 2 if cfg.dtype == "bf16" else 4
+    pre_bytes = (2 * H * P + H + 2 * G * N) * esz            # x, dt, B, C read, y written, per token
+    dec_bytes = 2 * H * P * N * 4                            # fp32 state read and written, per token
+    print(json.dumps({
+        "metric": "SSD prefill tokens/sec/layer (forward only, no checkpoints)", "value": Bt * L / (ms * 1e-3),
+        "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + "_prefill", "batch": Bt, "seqlen": L, "nheads": H, "headdim": P, "dstate": N,
+                   "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment},
+        "roofline": {"bound": "hbm", "achieved": pre_bytes * Bt * L / (ms * 1e-3) / 1e9, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": pre_bytes * Bt * L / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "note": "whole prefill: algorithmic bytes (x, dt, B, C read once, y written) over the step time"},
+        "workspace_bytes": int(ws.numel()),
+        "decode": {"us_per_token": us_tok, "tokens_per_call": 1, "state_bytes_per_token": dec_bytes,
+                   "achieved_gbs": dec_bytes * Bt / (us_tok * 1e-6) / 1e9,
+                   "note": "one launch per token from the host; bound by launch latency, not by the 5 MB of state"},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -127,6 +179,9 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--inference", action="store_true",
+                    help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
+                         "token-by-token recurrent step (us per token) at the same layer shape")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -157,6 +212,9 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.inference:
+        inference_bench(args, cfg, pk, synth, torch, dev)
+        return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0
     shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)

@@ -102,12 +102,30 @@ size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, 
  *   y               [Bt,L,H,P] dtype, overwritten
  *   final_state     [Bt,H,P,N] fp32, overwritten; may be NULL
  *   boundary_states [Bt, L/segment, H, P, N] fp32, overwritten; slot k holds the state entering
- *                   segment k (slot 0 = init_state or zeros).  May be NULL only if segment == L.
+ *                   segment k (slot 0 = init_state or zeros).  NULL: forward only (prefill) -- no
+ *                   checkpoint is kept, the state travels from segment to segment inside the
+ *                   workspace and memory use is independent of L; a later ssd_bwd is then possible
+ *                   only with segment == L.
  */
 int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
             const void* C, const float* D, const float* init_state, void* y, float* final_state,
             float* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
             void* hip_stream);
+
+/*
+ * Recurrent form (Sec. 3.1, Eq. 1, token by token): for t = 0 .. seqlen-1
+ *     state <- exp(dt_t A) state + dt_t x_t (x) B_t ;   y_t = C_t state + D x_t
+ * The constant-memory step that continues a sequence after a prefill by ssd_fwd (whose
+ * final_state is this call's state); seqlen = 1 is single-token generation.
+ *   shape: dtype, batch, seqlen (tokens in this call, >= 0), nheads, headdim, ngroups, dstate and
+ *          the batch strides are used; chunk and segment are ignored
+ *   x, y [Bt,T,H,P] dtype; dt [Bt,T,H] dtype; B, C [Bt,T,G,N] dtype; A, D [H] fp32 (all device)
+ *   state [Bt,H,P,N] fp32, device, updated in place (never NULL)
+ *   flags: SSD_FLAG_RESIDUAL only (y = x + layer(x))
+ * Needs no workspace and allocates nothing; work is enqueued on hip_stream.  Errors as elsewhere.
+ */
+int ssd_decode(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+               const void* C, const float* D, float* state, void* y, uint32_t flags, void* hip_stream);
 
 /*
  * Backward (Recompute_Forward + Backward of Alg. 2 over every segment, right to left).

@@ -16,7 +16,7 @@ LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
 SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
 
-EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -67,6 +67,8 @@ def lib():
         L.ssd_fwd.argtypes = [shp] + [vp] * 10 + [vp, sz, u32, vp]
         L.ssd_bwd.restype = ctypes.c_int
         L.ssd_bwd.argtypes = [shp] + [vp] * 17 + [vp, sz, u32, vp]
+        L.ssd_decode.restype = ctypes.c_int
+        L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
         L.magc_stack_workspace_bytes.argtypes = [shp, i32, i32, i32]
         L.magc_stack_fwd.restype = ctypes.c_int
@@ -138,8 +140,9 @@ def _workspace(nbytes: int, device):
 
 
 def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, workspace=None, want_final=True,
-            out=None):
-    """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L.
+            out=None, want_boundary=True):
+    """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L,
+    or with want_boundary=False (forward only: no checkpoint is kept).
     `out` may carry preallocated tensors under the keys y, final_state, boundary_states."""
     import torch
     _check_inputs(x, dt, A, B, C, D, init_state)
@@ -153,7 +156,7 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
         final = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
     nseg = L // shape.segment if L > 0 and shape.segment > 0 and L % shape.segment == 0 else 1
     bnd = out.get("boundary_states")
-    if bnd is None and segment is not None:
+    if bnd is None and segment is not None and want_boundary:
         bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)
     need = ssd_workspace_bytes(shape, False, flags)
     if workspace is None:
@@ -163,6 +166,22 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     if rc != 0:
         raise SSDError(rc, "ssd_fwd")
     return y, final, bnd
+
+
+def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None):
+    """y = ssd_decode(...): the recurrence token by token over x's T tokens; `state` [Bt,H,P,N] fp32 is
+    updated in place."""
+    import torch
+    _check_inputs(x, dt, A, B, C, D, state)
+    if state.dtype != torch.float32:
+        raise TypeError("state must be fp32")
+    shape = make_shape(x, B, 1, None)
+    y = out if out is not None else torch.empty_like(x)
+    rc = lib().ssd_decode(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(state),
+                          _ptr(y), flags, _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_decode")
+    return y
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,

@@ -211,6 +211,11 @@ static Pipe* pipe_for_current_device() {
     return &p;
 }
 
+// Forward without checkpoints (boundary_states == NULL, several segments): the state leaving one
+// segment reaches the next through two buffers used alternately (the scans are ordered by events, so
+// a buffer is rewritten only after its reader has finished).
+static size_t carry_bytes(const Dims& d) { return d.nseg > 1 ? 2 * align_up((size_t)d.Bt * d.H * d.P * d.N * 4) : 0; }
+
 // Bytes of the arrays shared by both scratch blocks: the dA / dD partial sums of every chunk.
 static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d.nseg * d.nc * d.H * 4); }
 
@@ -257,7 +262,7 @@ extern "C" size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
     const size_t block = align_up(ws_layout(d, is_backward != 0, mfma, wg_target(nl)).total);
-    const size_t t = nl * block + (is_backward ? shared_bytes(d) : 0);
+    const size_t t = nl * block + (is_backward ? shared_bytes(d) : carry_bytes(d));
     return t ? t : 256;
 }
 
@@ -284,12 +289,12 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         return SSD_OK;
     }
     if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
-    if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
     const WsLayout w = ws_layout(d, false, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block) return SSD_ERR_WORKSPACE;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + carry_bytes(d)) return SSD_ERR_WORKSPACE;
+    float* carry[2] = {(float*)((char*)workspace + nl * block), (float*)((char*)workspace + nl * block + carry_bytes(d) / 2)};
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
     if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
 
@@ -313,6 +318,16 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.Bm = off(B, t0 * d.G * d.N, d.esz);
         sp.Cm = off(C, t0 * d.G * d.N, d.esz);
         wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
+        if (!boundary_states && d.nseg > 1) {  // no checkpoints kept: hand the state on through the carry buffers
+            if (k > 0) {
+                sp.state_in = carry[k & 1];
+                sp.state_in_bs = (int64_t)HPN;
+            }
+            if (k + 1 < d.nseg) {
+                sp.state_out = carry[(k + 1) & 1];
+                sp.state_out_bs = (int64_t)HPN;
+            }
+        }
         sp.ev_wait = (nl > 1 && k > 0) ? pp->scan[(k - 1) % nl] : nullptr;
         sp.ev_record = (nl > 1 && k + 1 < d.nseg) ? pp->scan[ln] : nullptr;
         hipError_t e = mfma ? mfma_forward_segment(sp, true, sk) : generic_forward_segment(sp, d.bf16, true, sk);

@@ -1,0 +1,107 @@
+// Recurrent form of the layer (Sec. 3.1, Eq. 1 in the Mamba-2 form), token by token:
+//     state <- exp(dt_t A) state + dt_t x_t (x) B_t ;   y_t = C_t state + D x_t
+// the constant-memory step that continues a sequence after a prefill (ssd_fwd's final_state).
+// Any P, N, fp32 or bf16 storage; bound by the read-modify-write of the fp32 state
+// (8 bytes per state element and token).
+#include "ssd_internal.h"
+
+namespace ssdk {
+namespace {
+
+struct DecodeParams {
+    const void *x, *dt, *Bm, *Cm;
+    const float *A, *D;
+    float* state;
+    void* y;
+    int64_t T, xs_b, dts_b, bcs_b;
+    int H, P, G, N, hpg;
+    float skip_add;  // 1 under the residual flag: y = x + layer(x)
+};
+
+template <typename T>
+__device__ __forceinline__ float ld(const void* p, int64_t i);
+template <>
+__device__ __forceinline__ float ld<float>(const void* p, int64_t i) { return ((const float*)p)[i]; }
+template <>
+__device__ __forceinline__ float ld<bf16_t>(const void* p, int64_t i) { return bf16_to_float(((const bf16_t*)p)[i]); }
+template <typename T>
+__device__ __forceinline__ void st(void* p, int64_t i, float v);
+template <>
+__device__ __forceinline__ void st<float>(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
+template <>
+__device__ __forceinline__ void st<bf16_t>(void* p, int64_t i, float v) { ((bf16_t*)p)[i] = float_to_bf16(v); }
+
+// Workgroup (head, batch, z) owns the state rows p = 4 z + w (wave w), and further rows in steps of
+// 4 gridDim.z; lane l the columns n = l, l + 64, ...  A lane only ever touches its own state elements
+// and rows are independent recurrences, so the token loop needs no synchronisation at all.
+template <typename T>
+__global__ __launch_bounds__(256) void k_decode(DecodeParams dp) {
+    const int h = blockIdx.x, b = blockIdx.y, g = h / dp.hpg;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const float Ah = dp.A[h], Dh = dp.D[h] + dp.skip_add;
+    float* S = dp.state + ((int64_t)b * dp.H + h) * dp.P * dp.N;
+    for (int64_t t = 0; t < dp.T; ++t) {
+        const float dtv = ld<T>(dp.dt, (int64_t)b * dp.dts_b + t * dp.H + h);
+        const float a = __expf(dtv * Ah);
+        const int64_t bc = (int64_t)b * dp.bcs_b + (t * dp.G + g) * dp.N;
+        const int64_t xo = (int64_t)b * dp.xs_b + (t * dp.H + h) * dp.P;
+        for (int p = 4 * blockIdx.z + w; p < dp.P; p += 4 * gridDim.z) {
+            const float xv = ld<T>(dp.x, xo + p);
+            const float dx = dtv * xv;
+            float acc = 0.f;
+            for (int n = lane; n < dp.N; n += 64) {
+                const float hn = a * S[(int64_t)p * dp.N + n] + dx * ld<T>(dp.Bm, bc + n);
+                S[(int64_t)p * dp.N + n] = hn;
+                acc += ld<T>(dp.Cm, bc + n) * hn;
+            }
+            for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+            if (lane == 0) st<T>(dp.y, xo + p, acc + Dh * xv);
+        }
+    }
+}
+
+}  // namespace
+}  // namespace ssdk
+
+using namespace ssdk;
+
+extern "C" int ssd_decode(const ssd_shape_t* sh, const void* x, const void* dt, const float* A, const void* B,
+                          const void* C, const float* D, float* state, void* y, uint32_t flags, void* hip_stream) {
+    if (!sh) return SSD_ERR_NULL;
+    if (sh->dtype != SSD_F32 && sh->dtype != SSD_BF16) return SSD_ERR_DTYPE;
+    if (sh->batch <= 0 || sh->seqlen < 0 || sh->nheads <= 0 || sh->headdim <= 0 || sh->ngroups <= 0 || sh->dstate <= 0)
+        return SSD_ERR_SHAPE;
+    if (sh->batch > 65535 || sh->nheads > 65535) return SSD_ERR_SHAPE;
+    if (sh->nheads % sh->ngroups != 0) return SSD_ERR_DIVISIBILITY;
+    if (flags & ~(uint32_t)SSD_FLAG_RESIDUAL) return SSD_ERR_ARG;
+    if (sh->seqlen == 0) return SSD_OK;
+    if (!x || !dt || !A || !B || !C || !D || !state || !y) return SSD_ERR_NULL;
+    DecodeParams dp;
+    dp.x = x;
+    dp.dt = dt;
+    dp.Bm = B;
+    dp.Cm = C;
+    dp.A = A;
+    dp.D = D;
+    dp.state = state;
+    dp.y = y;
+    dp.T = sh->seqlen;
+    dp.H = sh->nheads;
+    dp.P = sh->headdim;
+    dp.G = sh->ngroups;
+    dp.N = sh->dstate;
+    dp.hpg = dp.H / dp.G;
+    dp.xs_b = sh->x_batch_stride ? sh->x_batch_stride : dp.T * dp.H * dp.P;
+    dp.dts_b = sh->dt_batch_stride ? sh->dt_batch_stride : dp.T * dp.H;
+    dp.bcs_b = sh->bc_batch_stride ? sh->bc_batch_stride : dp.T * dp.G * dp.N;
+    if (dp.xs_b < dp.T * dp.H * dp.P || dp.dts_b < dp.T * dp.H || dp.bcs_b < dp.T * dp.G * dp.N) return SSD_ERR_SHAPE;
+    dp.skip_add = (flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f;
+    hipStream_t s = (hipStream_t)hip_stream;
+    const int rows4 = (dp.P + 3) / 4;
+    const dim3 grid(dp.H, (unsigned)sh->batch, rows4 < 64 ? rows4 : 64);
+    if (sh->dtype == SSD_BF16)
+        hipLaunchKernelGGL(k_decode<bf16_t>, grid, dim3(256), 0, s, dp);
+    else
+        hipLaunchKernelGGL(k_decode<float>, grid, dim3(256), 0, s, dp);
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+}
