@@ -24,6 +24,8 @@
  *     more than one segment part of it runs on a library-owned stream of default priority, forked
  *     from and joined back into `hip_stream` with events (created on the first such call).
  *     Setting SSD_MAGC_SERIAL=1 in the environment keeps everything on `hip_stream` (diagnostics).
+ *     Those streams and events exist once per device: calls on one device must not overlap in time
+ *     across host threads (calls on different devices, or one after the other, are fine).
  *   - Tensors are dense row-major with the index order written in brackets; the batch stride
  *     may be overridden through ssd_shape_t (elements, 0 = dense) so that a token range of a
  *     longer sequence can be passed as a pointer offset.

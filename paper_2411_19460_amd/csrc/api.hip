@@ -331,7 +331,10 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.ev_wait = (nl > 1 && k > 0) ? pp->scan[(k - 1) % nl] : nullptr;
         sp.ev_record = (nl > 1 && k + 1 < d.nseg) ? pp->scan[ln] : nullptr;
         hipError_t e = mfma ? mfma_forward_segment(sp, true, sk) : generic_forward_segment(sp, d.bf16, true, sk);
-        if (e != hipSuccess) return SSD_ERR_LAUNCH;
+        if (e != hipSuccess) {
+            (void)join_lanes(pp, nl, st);  // whatever was enqueued on the library's streams still ends before the caller's next work
+            return SSD_ERR_LAUNCH;
+        }
     }
     if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     return SSD_OK;
@@ -412,12 +415,16 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         wire_states(sp, d, k, init_state, boundary_states, nullptr, nullptr);
         sp.ev_wait = sp.ev_record = nullptr;
         e = mfma ? mfma_forward_segment(sp, false, sk) : generic_forward_segment(sp, d.bf16, false, sk);
-        if (e != hipSuccess) return SSD_ERR_LAUNCH;
-        sp.dinit_out = (k == 0) ? dinit_state : nullptr;
-        sp.ev_wait = (nl > 1 && it > 0) ? pp->scan[(it - 1) % nl] : nullptr;
-        sp.ev_record = (nl > 1 && k > 0) ? pp->scan[ln] : nullptr;
-        e = mfma ? mfma_backward_segment(sp, sk) : generic_backward_segment(sp, d.bf16, sk);
-        if (e != hipSuccess) return SSD_ERR_LAUNCH;
+        if (e == hipSuccess) {
+            sp.dinit_out = (k == 0) ? dinit_state : nullptr;
+            sp.ev_wait = (nl > 1 && it > 0) ? pp->scan[(it - 1) % nl] : nullptr;
+            sp.ev_record = (nl > 1 && k > 0) ? pp->scan[ln] : nullptr;
+            e = mfma ? mfma_backward_segment(sp, sk) : generic_backward_segment(sp, d.bf16, sk);
+        }
+        if (e != hipSuccess) {
+            (void)join_lanes(pp, nl, st);  // whatever was enqueued on the library's streams still ends before the caller's next work
+            return SSD_ERR_LAUNCH;
+        }
     }
     if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     sps[0].accumulate = (flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0;
