@@ -118,9 +118,13 @@ __device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int t
         *(bf16x8*)(L.st + row * BPITCH + seg * 16) = pr.sv[k];
     }
     if (tid < Q) {
-        L.cum2[tid] = pr.cum * LOG2E;
-        L.fac[tid] = pr.fac;
-        L.dtl[tid] = pr.dtf;
+        // one address, three immediate offsets: cum2, fac and dtl lie one after the other
+        static_assert(offsetof(DualLds<Q>, fac) == offsetof(DualLds<Q>, cum2) + Q * sizeof(float) &&
+                      offsetof(DualLds<Q>, dtl) == offsetof(DualLds<Q>, cum2) + 2 * Q * sizeof(float), "contiguous per-token rows");
+        float* row = L.cum2 + tid;
+        row[0] = pr.cum * LOG2E;
+        row[Q] = pr.fac;
+        row[2 * Q] = pr.dtf;
     }
 }
 
@@ -232,34 +236,33 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     }
     float s_a = 0.f, s_b = 0.f;
     const float dtok = REV ? L.dtl[tok] : 0.f;
-    bf16x4 outv[8];
+    // one half of the channels at a time: the results of a half replace, in the patch, the x values of
+    // that half, which nothing reads any more (fewer values held in registers at once)
 #pragma unroll
     for (int pt = 0; pt < 2; ++pt) {
+        bf16x4 outv[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int p4 = 32 * pt + 8 * q + 4 * (lane >> 5);
             const bf16x4 mine = *(const bf16x4*)(L.raw + tok * XPITCH + p4 * 2);  // x (EPI 0) or dY (EPI 2)
             if (EPI == 0) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) outv[4 * pt + q][e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)mine[e]);
+                for (int e = 0; e < 4; ++e) outv[q][e] = (__bf16)((pt ? acc1 : acc0)[4 * q + e] + cx.Dh * (float)mine[e]);
             } else {
                 const bf16x4 other = *(const bf16x4*)(priv + tl * XPITCH + p4 * 2);  // x
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const float u = (pt ? acc1 : acc0)[4 * q + e];
-                    outv[4 * pt + q][e] = (__bf16)(dtok * u + cx.Dh * (float)mine[e]);
+                    outv[q][e] = (__bf16)(dtok * u + cx.Dh * (float)mine[e]);
                     s_a += (float)other[e] * u;
                     s_b += (float)mine[e] * (float)other[e];
                 }
             }
         }
+        if (EPI == 2) lds_wave_fence();  // every read of this half's x from the patch is done
+#pragma unroll
+        for (int q = 0; q < 4; ++q) *(bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2) = outv[q];
     }
-    if (EPI == 2) lds_wave_fence();  // every read of x from the patch is done
-#pragma unroll
-    for (int pt = 0; pt < 2; ++pt)
-#pragma unroll
-        for (int q = 0; q < 4; ++q)
-            *(bf16x4*)(priv + tl * XPITCH + (32 * pt + 8 * q + 4 * (lane >> 5)) * 2) = outv[4 * pt + q];
     lds_wave_fence();
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
@@ -304,10 +307,14 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
     load_pre<Q, REV>(pr, sp, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
         const int h = h0 + hh;
+        // the thread index as the optimiser cannot see through: addresses derived from it are formed anew
+        // for every head instead of being kept in registers across the whole loop
+        int tv = tid;
+        asm volatile("" : "+v"(tv));
         __syncthreads();  // every wave is done with the previous head's tiles
-        store_pre<Q, REV>(pr, L, tid);
+        store_pre<Q, REV>(pr, L, tv);
         __syncthreads();
-        if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tid);
+        if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tv);
         const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
         const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
         cx.xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
