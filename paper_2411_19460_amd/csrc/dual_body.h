@@ -83,19 +83,21 @@ __device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b,
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
     const bf16_t* src = (REV ? (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b : (const bf16_t*)sp.x + (int64_t)b * sp.xs_b) +
                         ((int64_t)c * Q * sp.H + h) * P_;
+    // addresses = a wave-uniform base (scalar registers) + one 32-bit byte offset per lane
+    const uint32_t rowbytes = (uint32_t)xt * 2;
+    const uint32_t xoff = (uint32_t)(tid >> 3) * rowbytes + (uint32_t)(tid & 7) * 16, roff = (uint32_t)(tid >> 3) * 4;
+    constexpr int RSTEP = CF::NTHR / 8;  // rows between a thread's consecutive vectors
 #pragma unroll
     for (int k = 0; k < CF::XV; ++k) {
-        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
-        pr.xt[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-        pr.sc[k] = REV ? sp.ein[cbase + row] : sp.dtf[cbase + row];
-        if (!REV) pr.sc2[k] = sp.eout[cbase + row];
+        pr.xt[k] = *(const bf16x8*)((const char*)src + (size_t)k * RSTEP * rowbytes + (size_t)xoff);
+        const float* f1 = (REV ? sp.ein : sp.dtf) + cbase + k * RSTEP;
+        pr.sc[k] = *(const float*)((const char*)f1 + (size_t)roff);
+        if (!REV) pr.sc2[k] = *(const float*)((const char*)(sp.eout + cbase + k * RSTEP) + (size_t)roff);
     }
     const bf16_t* S = (REV ? sp.dstates_bf : sp.states_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+    const uint32_t soff = (uint32_t)tid * 16;
 #pragma unroll
-    for (int k = 0; k < CF::SV; ++k) {
-        const int v = tid + CF::NTHR * k;
-        pr.sv[k] = *(const bf16x8*)(S + v * 8);
-    }
+    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff);
     if (tid < Q) {
         pr.cum = sp.cum[cbase + tid];
         pr.dtf = sp.dtf[cbase + tid];
@@ -221,15 +223,16 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
         acc0 = mfma(frag_tr(L.raw, XPITCH, k0, 0, lane), fb, acc0);
         acc1 = mfma(frag_tr(L.raw, XPITCH, k0, 32, lane), fb, acc1);
     }
+    // whole-row global accesses of the epilogue: lane -> (row lane / 8, 16-byte piece lane % 8) of an 8-row group
+    const uint32_t rowoff = ((uint32_t)(lane >> 3) * (uint32_t)cx.xt + (uint32_t)(lane & 7) * 8) * 2;
     // epilogue: in the accumulators this lane owns token `tok` and, per register group q, four
     // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses.
     // Reverse, the wave's own 32 rows of x come in as whole rows.
     if (EPI != 0) {
-        const bf16_t* src = cx.xg;
         bf16x8 own[4];
 #pragma unroll
         for (int it = 0; it < 4; ++it)
-            own[it] = *(const bf16x8*)(src + (int64_t)(tok0 + (lane >> 3) + 8 * it) * cx.xt + (lane & 7) * 8);
+            own[it] = *(const bf16x8*)((const char*)(cx.xg + (int64_t)(tok0 + 8 * it) * cx.xt) + (size_t)rowoff);
 #pragma unroll
         for (int it = 0; it < 4; ++it) *(bf16x8*)(priv + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = own[it];
         lds_wave_fence();
@@ -268,7 +271,7 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     for (int it = 0; it < 4; ++it) {
         const int row = (lane >> 3) + 8 * it;
         const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
-        *(bf16x8*)(cx.outp + (int64_t)(tok0 + row) * cx.xt + (lane & 7) * 8) = v;
+        *(bf16x8*)((char*)(cx.outp + (int64_t)(tok0 + 8 * it) * cx.xt) + (size_t)rowoff) = v;
     }
     if (EPI != 0) {
         s_a += __shfl_xor(s_a, 32, 64);
