@@ -58,6 +58,7 @@ struct Pre {
     float sc[DualCfg<Q>::XV], sc2[DualCfg<Q>::XV];  // per-token scale factors, multiplied at staging time
     bf16x8 sv[DualCfg<Q>::SV];
     float cum, dtf, fac;
+    bf16x8 own[4];  // reverse: the wave's own 32 rows of x as whole rows (for the epilogue's dot products)
 };
 
 struct HeadCtx {
@@ -77,7 +78,7 @@ __device__ __forceinline__ bf16x8 frag_lds_rows(const char* tile, int pitch, int
 }
 
 template <int Q, bool REV>
-__device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b, int c, int h, int tid) {
+__device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b, int c, int h, int tid, int tok0) {
     typedef DualCfg<Q> CF;
     const int64_t xt = (int64_t)sp.H * P_;
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
@@ -103,11 +104,23 @@ __device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b,
         pr.dtf = sp.dtf[cbase + tid];
         pr.fac = REV ? sp.eout[cbase + tid] : sp.ein[cbase + tid];
     }
+    if (REV) {  // lane -> (row lane / 8, 16-byte piece lane % 8) of each 8-row group of the wave's tile
+        const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + ((int64_t)c * Q * sp.H + h) * P_;
+        const uint32_t ooff = (uint32_t)((tid >> 3) & 7) * rowbytes + (uint32_t)(tid & 7) * 16;
+#pragma unroll
+        for (int it = 0; it < 4; ++it)
+            pr.own[it] = *(const bf16x8*)((const char*)(xg + (int64_t)(tok0 + 8 * it) * xt) + (size_t)ooff);
+    }
 }
 
 template <int Q, bool REV>
-__device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int tid) {
+__device__ __forceinline__ void store_pre(const Pre<Q>& pr, DualLds<Q>& L, int tid, int w) {
     typedef DualCfg<Q> CF;
+    if (REV) {  // the wave's own x rows wait in its patch for the epilogue (the patch is idle until then)
+        const int lane = tid & 63;
+#pragma unroll
+        for (int it = 0; it < 4; ++it) *(bf16x8*)(L.priv[w] + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = pr.own[it];
+    }
 #pragma unroll
     for (int k = 0; k < CF::XV; ++k) {
         const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
@@ -227,16 +240,7 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     const uint32_t rowoff = ((uint32_t)(lane >> 3) * (uint32_t)cx.xt + (uint32_t)(lane & 7) * 8) * 2;
     // epilogue: in the accumulators this lane owns token `tok` and, per register group q, four
     // consecutive channels; rows travel through the wave's LDS patch to and from whole-row accesses.
-    // Reverse, the wave's own 32 rows of x come in as whole rows.
-    if (EPI != 0) {
-        bf16x8 own[4];
-#pragma unroll
-        for (int it = 0; it < 4; ++it)
-            own[it] = *(const bf16x8*)((const char*)(cx.xg + (int64_t)(tok0 + 8 * it) * cx.xt) + (size_t)rowoff);
-#pragma unroll
-        for (int it = 0; it < 4; ++it) *(bf16x8*)(priv + ((lane >> 3) + 8 * it) * XPITCH + (lane & 7) * 16) = own[it];
-        lds_wave_fence();
-    }
+    // Reverse, the wave's own 32 rows of x have been waiting in its patch since the staging phase.
     float s_a = 0.f, s_b = 0.f;
     const float dtok = REV ? L.dtl[tok] : 0.f;
     // one half of the channels at a time: the results of a half replace, in the patch, the x values of
@@ -307,7 +311,7 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
     HeadCtx cx;
     tile_load<Q, REV>(go, gd, rf, Mat, rowop, bt, T, lane);
     Pre<Q> pr;
-    load_pre<Q, REV>(pr, sp, b, c, h0, tid);
+    load_pre<Q, REV>(pr, sp, b, c, h0, tid, 32 * T);
     for (int hh = 0; hh < hps; ++hh) {
         const int h = h0 + hh;
         // the thread index as the optimiser cannot see through: addresses derived from it are formed anew
@@ -315,9 +319,9 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
         int tv = tid;
         asm volatile("" : "+v"(tv));
         __syncthreads();  // every wave is done with the previous head's tiles
-        store_pre<Q, REV>(pr, L, tv);
+        store_pre<Q, REV>(pr, L, tv, w);
         __syncthreads();
-        if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tv);
+        if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tv, 32 * T);
         const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
         const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
         cx.xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
