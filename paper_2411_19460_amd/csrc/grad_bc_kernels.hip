@@ -87,11 +87,13 @@ __device__ __forceinline__ void dg_load(DgPre<Q>& pr, const SegParams& sp, int b
     const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
     const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
     const bf16_t* dyg = (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
+    // addresses = a wave-uniform base (scalar registers) + one 32-bit byte offset per lane
+    const uint32_t rowbytes = (uint32_t)xt * 2, off = (uint32_t)(tid >> 3) * rowbytes + (uint32_t)(tid & 7) * 16;
 #pragma unroll
     for (int k = 0; k < DgPre<Q>::NV; ++k) {
-        const int v = tid + NTHR * k, row = v >> 3, seg = v & 7;
-        pr.dy[k] = *(const bf16x8*)(dyg + (int64_t)row * xt + seg * 8);
-        pr.x[k] = *(const bf16x8*)(xg + (int64_t)row * xt + seg * 8);
+        const size_t step = (size_t)k * (NTHR / 8) * rowbytes;
+        pr.dy[k] = *(const bf16x8*)((const char*)dyg + step + (size_t)off);
+        pr.x[k] = *(const bf16x8*)((const char*)xg + step + (size_t)off);
     }
     if (tid < Q) {
         const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
@@ -374,16 +376,19 @@ __device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, i
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
     // loads only: no arithmetic on the loaded values here, so that nothing waits for them early
     pr.T = sp.cum[cbase + Q - 1];
+    // addresses = a wave-uniform base (scalar registers) + one 32-bit byte offset per lane
+    const uint32_t rowbytes = (uint32_t)xt * 2, off = (uint32_t)(tid >> 3) * rowbytes + (uint32_t)(tid & 7) * 16;
+    const uint32_t roff = (uint32_t)(tid >> 3) * 4;
 #pragma unroll
     for (int k = 0; k < CF::TV; ++k) {
-        const int v = tid + CF::NTHR * k, row = v >> 3, seg = v & 7;
-        pr.t[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-        pr.cv[k] = sp.cum[cbase + row];
-        pr.dv[k] = sp.dtf[cbase + row];
+        pr.t[k] = *(const bf16x8*)((const char*)src + (size_t)k * (CF::NTHR / 8) * rowbytes + (size_t)off);
+        pr.cv[k] = *(const float*)((const char*)(sp.cum + cbase + k * (CF::NTHR / 8)) + (size_t)roff);
+        pr.dv[k] = *(const float*)((const char*)(sp.dtf + cbase + k * (CF::NTHR / 8)) + (size_t)roff);
     }
     const bf16_t* S = (role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+    const uint32_t soff = (uint32_t)tid * 16;
 #pragma unroll
-    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)(S + (tid + CF::NTHR * k) * 8);
+    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff);
 }
 
 template <int Q>

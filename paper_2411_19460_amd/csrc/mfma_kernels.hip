@@ -129,12 +129,15 @@ __device__ __forceinline__ void outer_load(OuterPre<Q>& pr, const SegParams& sp,
                                   : (const bf16_t*)sp.dy + (int64_t)b * sp.dys_b + xrow;
     const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
     pr.T = sp.cum[cbase + Q - 1];
+    // addresses = a wave-uniform base (scalar registers) + one 32-bit byte offset per lane
+    const int t8 = tid % (Q * 8);  // Q = 64: one vector per thread
+    const uint32_t rowbytes = (uint32_t)xt * 2, off = (uint32_t)(t8 >> 3) * rowbytes + (uint32_t)(t8 & 7) * 16;
+    const uint32_t roff = (uint32_t)(t8 >> 3) * 4;
 #pragma unroll
     for (int k = 0; k < OuterPre<Q>::NV; ++k) {
-        const int v = (tid + OUTER_THR * k) % (Q * 8), row = v >> 3, seg = v & 7;
-        pr.t[k] = *(const bf16x8*)(src + (int64_t)row * xt + seg * 8);
-        pr.cv[k] = sp.cum[cbase + row];
-        pr.dv[k] = sp.dtf[cbase + row];
+        pr.t[k] = *(const bf16x8*)((const char*)src + (size_t)k * (OUTER_THR / 8) * rowbytes + (size_t)off);
+        pr.cv[k] = *(const float*)((const char*)(sp.cum + cbase + k * (OUTER_THR / 8)) + (size_t)roff);
+        pr.dv[k] = *(const float*)((const char*)(sp.dtf + cbase + k * (OUTER_THR / 8)) + (size_t)roff);
     }
 }
 
