@@ -118,3 +118,23 @@ def test_config1_bf16_all_tensors():
     rep = {}
     compare_all(d, cfg.dtype, cfg.chunk, cfg.segment, report=rep)
     print("config1 errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+
+
+@pytest.mark.parametrize("path", ["mfma", "generic"])
+def test_padding_tokens_and_extreme_decay(path):
+    """dt = 0 tokens (padding: the state passes through, the token adds nothing) and dt of order 5 (the
+    state is forgotten within a token or two; cum reaches -2e4 inside a chunk): every factor of the
+    decay mask stays <= 1, so nothing may overflow or turn into NaN, and the results still match."""
+    Bt, L, H, G, Q, seg = 1, 512, 4, 1, 256, 256
+    d = small_inputs(9, "bf16", Bt, L, H, 64, G, 128)
+    rng = np.random.default_rng(5)
+    dt = d["dt"].copy()
+    dt[:, 100:140] = 0.0                      # a run of padding tokens inside a chunk
+    dt[:, 250:262] = 0.0                      # ... and across a chunk boundary
+    dt[:, 300:330, 1] = 5.0                   # head 1: extreme decay for a while
+    dt[:, :, 3] = np.where(rng.random((Bt, L)) < 0.3, 4.0, dt[:, :, 3])   # head 3: extreme decay at random tokens
+    d["dt"] = synth.round_bf16(dt)
+    flags = pk.SSD_FLAG_GENERIC_KERNELS if path == "generic" else 0
+    rep = {}
+    compare_all(d, "bf16", Q, seg, flags=flags, report=rep)
+    print("padding/extreme-decay errors:", {k: f"{v:.2e}" for k, v in rep.items()})
