@@ -42,6 +42,10 @@ struct DgMap {
     static __device__ __forceinline__ int ti(int v, int) { return v; }
     static __device__ __forceinline__ int tj(int, int k) { return k; }
     static __device__ __forceinline__ int slot0(int v) { return v * (v + 1) / 2; }
+    // flat index of tile (ti, tj); the (wave, run) pairs that hold the row sums of tile row r (second: -1 = none)
+    static __device__ __forceinline__ int slot_of(int ti, int tj) { return ti * (ti + 1) / 2 + tj; }
+    static __device__ __forceinline__ int row_wave(int r, int) { return r; }
+    static __device__ __forceinline__ int row_run(int, int which) { return which == 0 ? 0 : -1; }
 };
 template <>
 struct DgMap<256> {
@@ -56,6 +60,21 @@ struct DgMap<256> {
     static __device__ __forceinline__ int ti(int v, int k) { return TI[v][k]; }
     static __device__ __forceinline__ int tj(int v, int k) { return TJ[v][k]; }
     static __device__ __forceinline__ int slot0(int v) { return SLOT0[v]; }
+    // Tile row r: rows 5..7 are split over waves 7 - r (columns 0..3) and 11 - r (the rest), both as their
+    // first run; row 4 is wave 3's only run, row 3 wave 7's; rows 0, 1, 2 are the second run of waves 0, 5, 6.
+    static __device__ __forceinline__ int low_wave(int r) { return r == 0 ? 0 : 4 + r; }
+    static __device__ __forceinline__ int row_wave(int r, int which) {
+        return r >= 5 ? (which == 0 ? 7 - r : 11 - r) : (r == 4 ? 3 : (r == 3 ? 7 : low_wave(r)));
+    }
+    static __device__ __forceinline__ int row_run(int r, int which) {
+        return r >= 5 ? 0 : (which == 1 ? -1 : (r >= 3 ? 0 : 1));
+    }
+    // flat index of tile (ti, tj): the position of the tile in its wave's list
+    static __device__ __forceinline__ int slot_of(int ti, int tj) {
+        const int v = ti >= 5 ? (tj < 4 ? 7 - ti : 11 - ti) : (ti == 4 ? 3 : (ti == 3 ? 7 : low_wave(ti)));
+        const int k = ti >= 5 ? (tj < 4 ? tj : tj - 4) : (ti >= 3 ? tj : CNT[v] - (ti + 1) + tj);
+        return SLOT0[v] + k;
+    }
 };
 
 template <int Q>
@@ -69,8 +88,6 @@ struct DgLds {
     uint32_t gq[DgMap<Q>::NSLOT][8][64];         // scores G of every owned tile in accumulator layout, two bf16 per word
     float rsum[DgMap<Q>::NWV][2][32];            // per wave and tile-row run: row sums of E over the run's tiles
     float csum[DgMap<Q>::NSLOT][32];             // per tile: column sums of E
-    int run_row[DgMap<Q>::NWV][2];               // tile row of each run (-1: none)
-    int slot_of[DgMap<Q>::NT][DgMap<Q>::NT];     // flat tile index of (ti, tj)
 };
 
 template <int Q>
@@ -232,21 +249,42 @@ __device__ __forceinline__ void row_reduce_store(const f32x16& v, float* dst, in
     if (!(lane & 1)) dst[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = d1;
 }
 
-// Chunk-local part of the gradient of cum for head h, from the E sums of the head just finished:
-// gintra_i = sum_{j<=i} E[i][j] - sum_{i'>=i} E[i'][i], summed in a fixed order.
+// Where the partial sums of one tile row lie in LDS (wave-uniform; worked out once per workgroup).
 template <int Q>
-__device__ __forceinline__ void dg_emit_sums(const SegParams& sp, const DgLds<Q>& L, int b, int c, int h, int tid) {
+struct DgRowSrc {
+    int cs[DgMap<Q>::NT];  // float offsets of the column sums of tiles (ti, row), ti = row .. NT-1, into csum; -1: none
+    int rs0, rs1;          // float offsets of the (at most two) row-sum runs into rsum; rs1 = -1: none
+};
+
+template <int Q>
+__device__ __forceinline__ DgRowSrc<Q> dg_row_src(int tt) {
     typedef DgMap<Q> M;
-    if (tid < Q) {
-        const int tl = tid & 31, tt = tid >> 5;
-        float rs = 0.f, cs = 0.f;
+    DgRowSrc<Q> r;
 #pragma unroll
-        for (int w = 0; w < M::NWV; ++w)
+    for (int ti = 0; ti < M::NT; ++ti) r.cs[ti] = ti >= tt ? M::slot_of(ti, tt) * 32 : -1;
+    r.rs0 = (M::row_wave(tt, 0) * 2 + M::row_run(tt, 0)) * 32;
+    r.rs1 = M::row_run(tt, 1) >= 0 ? (M::row_wave(tt, 1) * 2 + M::row_run(tt, 1)) * 32 : -1;
+    return r;
+}
+
+// Chunk-local part of the gradient of cum for head h, from the E sums of the head just finished:
+// gintra_i = sum_{j<=i} E[i][j] - sum_{i'>=i} E[i'][i], summed in a fixed order.  Wave w combines tile
+// row w (32 tokens, one per lane of its first half); the reads are independent of each other.
+template <int Q>
+__device__ __forceinline__ void dg_emit_sums(const SegParams& sp, const DgLds<Q>& L, const DgRowSrc<Q>& src, int b, int c, int h,
+                                             int w, int lane) {
+    typedef DgMap<Q> M;
+    static_assert(M::NWV == M::NT, "one wave per tile row");
+    if (lane < 32) {
+        const float* rsum = &L.rsum[0][0][0];
+        const float* csum = &L.csum[0][0];
+        float rs = rsum[src.rs0 + lane];
+        if (src.rs1 >= 0) rs += rsum[src.rs1 + lane];
+        float cs = 0.f;
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
-                if (L.run_row[w][u] == tt) rs += L.rsum[w][u][tl];
-        for (int ti = tt; ti < M::NT; ++ti) cs += L.csum[L.slot_of[ti][tt]][tl];
-        sp.gintra[(((int64_t)b * sp.H + h) * sp.nc + c) * Q + tid] = rs - cs;
+        for (int ti = 0; ti < M::NT; ++ti)
+            if (src.cs[ti] >= 0) cs += csum[src.cs[ti] + lane];
+        sp.gintra[(((int64_t)b * sp.H + h) * sp.nc + c) * Q + 32 * w + lane] = rs - cs;
     }
 }
 
@@ -261,11 +299,9 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
     const int hps = sp.hpg / ns, h0 = g * sp.hpg + slice * hps;
     const int tid = threadIdx.x, lane = tid & 63, w = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int cnt = M::count(w), slot0 = M::slot0(w);
-    // prologue: the scores of the owned tiles in accumulator layout, and the maps used when the sums are combined
+    // prologue: the scores of the owned tiles in accumulator layout
     {
         const bf16_t* Gd = (const bf16_t*)sp.Gm + (((int64_t)b * sp.nc + c) * sp.G + g) * (2 * Q * Q);
-        int prev = -1, run = -1;
-        if (lane == 0) L.run_row[w][0] = L.run_row[w][1] = -1;
 #pragma unroll
         for (int k = 0; k < MAXT; ++k)
             if (k < cnt) {
@@ -277,14 +313,9 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
                     const uint32_t lo = gp[(int64_t)row * Q].v, hi = gp[(int64_t)(row + 1) * Q].v;
                     L.gq[slot0 + k][r2][lane] = lo | (hi << 16);
                 }
-                if (ti != prev) {
-                    ++run;
-                    prev = ti;
-                    if (lane == 0) L.run_row[w][run] = ti;
-                }
-                if (lane == 0) L.slot_of[ti][tj] = slot0 + k;
             }
     }
+    const DgRowSrc<Q> rsrc = dg_row_src<Q>(w);
     f32x16 acc[MAXT];
 #pragma unroll
     for (int k = 0; k < MAXT; ++k) acc[k] = zero16();
@@ -292,7 +323,7 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
     dg_load<Q>(pr, sp, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
         __syncthreads();
-        if (hh > 0) dg_emit_sums<Q>(sp, L, b, c, h0 + hh - 1, tid);
+        if (hh > 0) dg_emit_sums<Q>(sp, L, rsrc, b, c, h0 + hh - 1, w, lane);
         dg_store<Q>(pr, L, tid);
         __syncthreads();
         if (hh + 1 < hps) dg_load<Q>(pr, sp, b, c, h0 + hh + 1, tid);
@@ -316,7 +347,7 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
         row_reduce_store(rowacc, L.rsum[w][run], lane);
     }
     __syncthreads();
-    dg_emit_sums<Q>(sp, L, b, c, h0 + hps - 1, tid);
+    dg_emit_sums<Q>(sp, L, rsrc, b, c, h0 + hps - 1, w, lane);
     // partial sum of this slice, bf16 [Q][Q] row-major (tiles above the diagonal are never touched)
     __bf16* out = (__bf16*)sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * ((int64_t)Q * Q);
 #pragma unroll
