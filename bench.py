@@ -177,6 +177,7 @@ def main():
     ap.add_argument("--steps", type=int, default=6)
     ap.add_argument("--warmup", type=int, default=2)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
+    ap.add_argument("--segment", type=int, default=0, help="checkpoint interval in tokens (default: the config's)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--inference", action="store_true",
@@ -207,6 +208,8 @@ def main():
                           "GB_per_s_read_plus_write": 2 * a.numel() * 4 / dtc / 1e9}))
         return
     cfg = synth.CONFIGS[args.config]
+    if args.segment:
+        cfg = cfg.scaled(segment=args.segment)
     if cfg.nlayers != 1:
         print("bench.py: stack configs are measured by tests, not by this bench", file=sys.stderr)
         sys.exit(2)
