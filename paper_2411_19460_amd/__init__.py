@@ -5,3 +5,11 @@ from . import synth  # noqa: F401
 from .binding import (SSD_BF16, SSD_F32, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_RESIDUAL,  # noqa: F401
                       SSDError, lib, magc_plan, magc_stack_bwd, magc_stack_fwd, magc_stack_workspace_bytes, make_shape,
                       ssd_bwd, ssd_decode, ssd_fwd, ssd_prof_enable, ssd_prof_read, ssd_prof_serialize, ssd_shape_t, ssd_workspace_bytes, strerror)
+
+
+def __getattr__(name):
+    # the autograd wrapper imports torch: load it on first use only
+    if name == "ssd_scan":
+        from .autograd import ssd_scan
+        return ssd_scan
+    raise AttributeError(name)

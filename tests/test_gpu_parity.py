@@ -6,7 +6,7 @@ import torch
 
 import paper_2411_19460_amd as pk
 from paper_2411_19460_amd import synth
-from parity_util import TOL, check, compare_all, dev_inputs, host, run_gpu
+from parity_util import TOL, check, compare_all, dev_inputs, host, run_gpu, run_oracle
 
 pytestmark = pytest.mark.gpu
 
@@ -138,3 +138,19 @@ def test_padding_tokens_and_extreme_decay(path):
     rep = {}
     compare_all(d, "bf16", Q, seg, flags=flags, report=rep)
     print("padding/extreme-decay errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+
+
+def test_autograd_wrapper_matches_the_direct_calls_and_the_oracle():
+    d = small_inputs(11, "bf16", 2, 512, 4, 64, 2, 128)
+    dv = dev_inputs(d, "bf16")
+    leaf = {k: dv[k].clone().requires_grad_(True) for k in ("x", "dt", "A", "B", "C", "D", "init_state")}
+    y, fin = pk.ssd_scan(leaf["x"], leaf["dt"], leaf["A"], leaf["B"], leaf["C"], leaf["D"], 256, 256, leaf["init_state"])
+    loss = (y.float() * dv["dy"].float()).sum() + (fin * dv["dfinal_state"]).sum()
+    loss.backward()
+    torch.cuda.synchronize()
+    _, _, _, g = run_gpu(dv, 256, 256)
+    for k, gk in (("x", "dx"), ("dt", "ddt"), ("A", "dA"), ("B", "dB"), ("C", "dC"), ("D", "dD"), ("init_state", "dinit_state")):
+        assert torch.equal(leaf[k].grad, g[gk]), k
+    _, go = run_oracle(d, 256)
+    check("dx via autograd", host(leaf["x"].grad), go["dx"], TOL["bf16"])
+    check("dA via autograd", host(leaf["A"].grad), go["dA"], TOL["bf16"])
