@@ -9,7 +9,8 @@
  *     h_t[p,n]   = exp(dt[b,t,h]*A[h]) * h_{t-1}[p,n] + dt[b,t,h] * x[b,t,h,p] * B[b,t,g,n]
  *     y[b,t,h,p] = sum_n C[b,t,g,n] * h_t[p,n] + D[h] * x[b,t,h,p]
  *
- * The sequence is cut into segments of `segment` tokens.  The forward pass keeps only the
+ * The sequence is cut into segments of `segment` tokens (the last one shorter when seqlen is not a
+ * multiple of segment; nseg = ceil(seqlen / segment) below).  The forward pass keeps only the
  * state entering each segment (the sequence-axis checkpoints of Sec. 3.2/3.3, Alg. 1); the
  * backward pass walks the segments right to left, restores each segment's per-chunk states
  * from its checkpoint and back-propagates through it, handing the state adjoint to the segment
@@ -53,7 +54,7 @@ typedef enum ssd_status_t {
     SSD_OK = 0,
     SSD_ERR_NULL = -1,         /* a required pointer is NULL */
     SSD_ERR_SHAPE = -2,        /* a dimension is non-positive or exceeds a kernel limit */
-    SSD_ERR_DIVISIBILITY = -3, /* nheads % ngroups, seqlen % segment or segment % chunk is not 0 */
+    SSD_ERR_DIVISIBILITY = -3, /* nheads % ngroups or segment % chunk is not 0 (stack: seqlen % segment) */
     SSD_ERR_DTYPE = -4,        /* unknown dtype */
     SSD_ERR_WORKSPACE = -5,    /* workspace NULL, misaligned (256 B) or smaller than ssd_workspace_bytes */
     SSD_ERR_LAUNCH = -6,       /* a HIP call failed; see hipGetLastError */
@@ -70,8 +71,10 @@ typedef struct ssd_shape_t {
     int32_t dstate;           /* N */
     int32_t chunk;            /* Q: block length of the dual (quadratic) form; segment % Q == 0 */
     int64_t batch;            /* Bt */
-    int64_t seqlen;           /* L (the paper's S); L % segment == 0 */
-    int64_t segment;          /* s: sequence-axis checkpoint interval; s == L means no checkpoints */
+    int64_t seqlen;           /* L (the paper's S), any length >= 0: a short last segment (and a short last chunk
+                                 inside it) is run on zero-padded copies kept in the workspace; the stack driver
+                                 needs L % segment == 0 */
+    int64_t segment;          /* s: sequence-axis checkpoint interval; s >= L means no checkpoints */
     int64_t x_batch_stride;   /* elements between batches of x, y, dy, dx      (0 = L*H*P) */
     int64_t dt_batch_stride;  /* elements between batches of dt, ddt           (0 = L*H)   */
     int64_t bc_batch_stride;  /* elements between batches of B, C, dB, dC      (0 = L*G*N) */
@@ -103,11 +106,11 @@ size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, 
  *   init_state      [Bt,H,P,N] fp32, or NULL for zeros
  *   y               [Bt,L,H,P] dtype, overwritten
  *   final_state     [Bt,H,P,N] fp32, overwritten; may be NULL
- *   boundary_states [Bt, L/segment, H, P, N] fp32, overwritten; slot k holds the state entering
+ *   boundary_states [Bt, nseg, H, P, N] fp32, overwritten; slot k holds the state entering
  *                   segment k (slot 0 = init_state or zeros).  NULL: forward only (prefill) -- no
  *                   checkpoint is kept, the state travels from segment to segment inside the
  *                   workspace and memory use is independent of L; a later ssd_bwd is then possible
- *                   only with segment == L.
+ *                   only with segment >= L.
  */
 int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
             const void* C, const float* D, const float* init_state, void* y, float* final_state,
@@ -136,7 +139,7 @@ int ssd_decode(const ssd_shape_t* shape, const void* x, const void* dt, const fl
  *   dy              [Bt,L,H,P] dtype
  *   dfinal_state    [Bt,H,P,N] fp32, or NULL for zeros
  *   boundary_states as written by ssd_fwd with the same shape (read only); may be NULL only if
- *                   segment == L (then the single segment restarts from init_state)
+ *                   segment >= L (then the single segment restarts from init_state)
  *   dx [Bt,L,H,P], ddt [Bt,L,H], dB, dC [Bt,L,G,N] dtype, overwritten
  *   dA, dD [H] fp32, overwritten (added to under SSD_FLAG_ACCUM_PARAM)
  *   dinit_state     [Bt,H,P,N] fp32, overwritten; may be NULL

@@ -114,7 +114,9 @@ def make_shape(x, Bm, chunk: int, segment: Optional[int] = None) -> ssd_shape_t:
         dt = SSD_F32
     else:
         raise TypeError(f"unsupported dtype {x.dtype}")
-    return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, L if segment is None else segment, 0, 0, 0)
+    if segment is None:   # one segment: the sequence rounded up to whole chunks
+        segment = max(chunk, -(-L // chunk) * chunk)
+    return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, segment, 0, 0, 0)
 
 
 def ssd_workspace_bytes(shape: ssd_shape_t, is_backward: bool, flags: int = 0) -> int:
@@ -154,7 +156,7 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     final = out.get("final_state")
     if final is None and want_final:
         final = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
-    nseg = L // shape.segment if L > 0 and shape.segment > 0 and L % shape.segment == 0 else 1
+    nseg = -(-L // shape.segment) if L > 0 and shape.segment > 0 else 1
     bnd = out.get("boundary_states")
     if bnd is None and segment is not None and want_boundary:
         bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)

@@ -27,7 +27,7 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     if (sh->nheads % sh->ngroups != 0) return SSD_ERR_DIVISIBILITY;
     if (sh->seqlen > 0) {
         if (sh->segment <= 0) return SSD_ERR_SHAPE;
-        if (sh->seqlen % sh->segment != 0 || sh->segment % sh->chunk != 0) return SSD_ERR_DIVISIBILITY;
+        if (sh->segment % sh->chunk != 0) return SSD_ERR_DIVISIBILITY;
     }
     d->Bt = sh->batch;
     d->L = sh->seqlen;
@@ -39,7 +39,9 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     d->Q = sh->chunk;
     d->hpg = d->H / d->G;
     d->nc = sh->seqlen > 0 ? (int)(sh->segment / sh->chunk) : 0;
-    d->nseg = sh->seqlen > 0 ? sh->seqlen / sh->segment : 0;
+    d->nseg = sh->seqlen > 0 ? (sh->seqlen + sh->segment - 1) / sh->segment : 0;
+    d->tail = sh->seqlen > 0 ? sh->seqlen % sh->segment : 0;
+    d->nc_tail = (int)((d->tail + sh->chunk - 1) / sh->chunk);
     d->bf16 = sh->dtype == SSD_BF16;
     d->esz = d->bf16 ? 2 : 4;
     d->xs_b = sh->x_batch_stride ? sh->x_batch_stride : d->L * d->H * d->P;
@@ -216,6 +218,42 @@ static Pipe* pipe_for_current_device() {
 // a buffer is rewritten only after its reader has finished).
 static size_t carry_bytes(const Dims& d) { return d.nseg > 1 ? 2 * align_up((size_t)d.Bt * d.H * d.P * d.N * 4) : 0; }
 
+// A short last segment (seqlen not a multiple of segment, or of chunk) is run on padded copies of its
+// tokens: the padding tokens have dt = 0 and x = B = C = dy = 0, i.e. they are identity steps of the
+// recurrence that add nothing to any gradient.  Offsets (bytes) of the copies behind the scratch blocks.
+struct TailStage {
+    size_t x, dt, B, C, y, dy, dx, ddt, dB, dC, total;
+    int64_t T;  // tokens of the padded segment
+};
+static TailStage tail_stage(const Dims& d, bool bwd) {
+    TailStage t;
+    memset(&t, 0, sizeof(t));
+    if (!d.tail) return t;
+    t.T = (int64_t)d.nc_tail * d.Q;
+    size_t off = 0;
+    auto take = [&](size_t row_elems) {
+        size_t o = off;
+        off += align_up((size_t)d.Bt * t.T * row_elems * d.esz);
+        return o;
+    };
+    const size_t hp = (size_t)d.H * d.P, gn = (size_t)d.G * d.N;
+    t.x = take(hp);
+    t.dt = take(d.H);
+    t.B = take(gn);
+    t.C = take(gn);
+    if (!bwd) {
+        t.y = take(hp);
+    } else {
+        t.dy = take(hp);
+        t.dx = take(hp);
+        t.ddt = take(d.H);
+        t.dB = take(gn);
+        t.dC = take(gn);
+    }
+    t.total = off;
+    return t;
+}
+
 // Bytes of the arrays shared by both scratch blocks: the dA / dD partial sums of every chunk.
 static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d.nseg * d.nc * d.H * 4); }
 
@@ -262,7 +300,7 @@ extern "C" size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
     const size_t block = align_up(ws_layout(d, is_backward != 0, mfma, wg_target(nl)).total);
-    const size_t t = nl * block + (is_backward ? shared_bytes(d) : carry_bytes(d));
+    const size_t t = nl * block + (is_backward ? shared_bytes(d) : carry_bytes(d)) + tail_stage(d, is_backward != 0).total;
     return t ? t : 256;
 }
 
@@ -293,7 +331,9 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     const int nl = lanes(d, mfma);
     const WsLayout w = ws_layout(d, false, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + carry_bytes(d)) return SSD_ERR_WORKSPACE;
+    const TailStage ts = tail_stage(d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + carry_bytes(d) + ts.total) return SSD_ERR_WORKSPACE;
+    char* stage = (char*)workspace + nl * block + carry_bytes(d);
     float* carry[2] = {(float*)((char*)workspace + nl * block), (float*)((char*)workspace + nl * block + carry_bytes(d) / 2)};
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
     if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
@@ -312,11 +352,38 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         SegParams& sp = sps[ln];
         hipStream_t sk = ln ? pp->aux[ln] : st;
         const int64_t t0 = k * d.s;
-        sp.x = off(x, t0 * d.H * d.P, d.esz);
-        sp.y = off(y, t0 * d.H * d.P, d.esz);
-        sp.dt = off(dt, t0 * d.H, d.esz);
-        sp.Bm = off(B, t0 * d.G * d.N, d.esz);
-        sp.Cm = off(C, t0 * d.G * d.N, d.esz);
+        const bool short_seg = d.tail && k + 1 == d.nseg;
+        const int HP = d.H * d.P, GN = d.G * d.N;
+        if (!short_seg) {
+            sp.x = off(x, t0 * HP, d.esz);
+            sp.y = off(y, t0 * HP, d.esz);
+            sp.dt = off(dt, t0 * d.H, d.esz);
+            sp.Bm = off(B, t0 * GN, d.esz);
+            sp.Cm = off(C, t0 * GN, d.esz);
+            sp.xs_b = sp.ys_b = d.xs_b;
+            sp.dts_b = d.dts_b;
+            sp.bcs_b = d.bcs_b;
+            sp.nc = d.nc;
+        } else {  // padded copies of the last tokens (see TailStage)
+            const int tv = (int)d.tail, T = (int)ts.T;
+            hipError_t es = launch_stage_rows(stage + ts.x, (int64_t)T * HP, off(x, t0 * HP, d.esz), d.xs_b, tv, T, HP, sp.Bt, d.esz, sk);
+            if (es == hipSuccess) es = launch_stage_rows(stage + ts.dt, (int64_t)T * d.H, off(dt, t0 * d.H, d.esz), d.dts_b, tv, T, d.H, sp.Bt, d.esz, sk);
+            if (es == hipSuccess) es = launch_stage_rows(stage + ts.B, (int64_t)T * GN, off(B, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (es == hipSuccess) es = launch_stage_rows(stage + ts.C, (int64_t)T * GN, off(C, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (es != hipSuccess) {
+                (void)join_lanes(pp, nl, st);
+                return SSD_ERR_LAUNCH;
+            }
+            sp.x = stage + ts.x;
+            sp.y = stage + ts.y;
+            sp.dt = stage + ts.dt;
+            sp.Bm = stage + ts.B;
+            sp.Cm = stage + ts.C;
+            sp.xs_b = sp.ys_b = (int64_t)T * HP;
+            sp.dts_b = (int64_t)T * d.H;
+            sp.bcs_b = (int64_t)T * GN;
+            sp.nc = d.nc_tail;
+        }
         wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
         if (!boundary_states && d.nseg > 1) {  // no checkpoints kept: hand the state on through the carry buffers
             if (k > 0) {
@@ -331,6 +398,8 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.ev_wait = (nl > 1 && k > 0) ? pp->scan[(k - 1) % nl] : nullptr;
         sp.ev_record = (nl > 1 && k + 1 < d.nseg) ? pp->scan[ln] : nullptr;
         hipError_t e = mfma ? mfma_forward_segment(sp, true, sk) : generic_forward_segment(sp, d.bf16, true, sk);
+        if (e == hipSuccess && short_seg)  // the valid rows of y go back to the caller's tensor
+            e = launch_stage_rows(off(y, t0 * HP, d.esz), d.xs_b, stage + ts.y, (int64_t)ts.T * HP, (int)d.tail, (int)d.tail, HP, sp.Bt, d.esz, sk);
         if (e != hipSuccess) {
             (void)join_lanes(pp, nl, st);  // whatever was enqueued on the library's streams still ends before the caller's next work
             return SSD_ERR_LAUNCH;
@@ -370,7 +439,9 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     const int nl = lanes(d, mfma);
     const WsLayout w = ws_layout(d, true, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d)) return SSD_ERR_WORKSPACE;
+    const TailStage ts = tail_stage(d, true);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d) + ts.total) return SSD_ERR_WORKSPACE;
+    char* stage = (char*)workspace + nl * block + shared_bytes(d);
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
     if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
 
@@ -389,7 +460,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         sp.dcarry = sps[0].dcarry;
         sp.dA_part = part_all;
         sp.dD_part = (float*)((char*)part_all + shared_bytes(d) / 2);
-        sp.nc_total = (int)(d.nseg * d.nc);
+        sp.nc_total = (int)(d.tail ? (d.nseg - 1) * d.nc + d.nc_tail : d.nseg * d.nc);  // chunks that write dA / dD partial sums
         sp.defer_param = 1;
     }
     hipError_t e = dfinal_state ? launch_copy_f32(sps[0].dcarry, dfinal_state, (size_t)d.Bt * HPN, st)
@@ -401,15 +472,47 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         SegParams& sp = sps[ln];
         hipStream_t sk = ln ? pp->aux[ln] : st;
         const int64_t t0 = k * d.s;
-        sp.x = off(x, t0 * d.H * d.P, d.esz);
-        sp.dy = off(dy, t0 * d.H * d.P, d.esz);
-        sp.dx = off(dx, t0 * d.H * d.P, d.esz);
-        sp.dt = off(dt, t0 * d.H, d.esz);
-        sp.ddt = off(ddt, t0 * d.H, d.esz);
-        sp.Bm = off(B, t0 * d.G * d.N, d.esz);
-        sp.Cm = off(C, t0 * d.G * d.N, d.esz);
-        sp.dB = off(dB, t0 * d.G * d.N, d.esz);
-        sp.dC = off(dC, t0 * d.G * d.N, d.esz);
+        const bool short_seg = d.tail && k + 1 == d.nseg;
+        const int HP = d.H * d.P, GN = d.G * d.N;
+        if (!short_seg) {
+            sp.x = off(x, t0 * HP, d.esz);
+            sp.dy = off(dy, t0 * HP, d.esz);
+            sp.dx = off(dx, t0 * HP, d.esz);
+            sp.dt = off(dt, t0 * d.H, d.esz);
+            sp.ddt = off(ddt, t0 * d.H, d.esz);
+            sp.Bm = off(B, t0 * GN, d.esz);
+            sp.Cm = off(C, t0 * GN, d.esz);
+            sp.dB = off(dB, t0 * GN, d.esz);
+            sp.dC = off(dC, t0 * GN, d.esz);
+            sp.xs_b = sp.ys_b = sp.dys_b = sp.dxs_b = d.xs_b;
+            sp.dts_b = d.dts_b;
+            sp.bcs_b = d.bcs_b;
+            sp.nc = d.nc;
+        } else {  // padded copies of the last tokens (see TailStage); results come back after the segment
+            const int tv = (int)d.tail, T = (int)ts.T;
+            e = launch_stage_rows(stage + ts.x, (int64_t)T * HP, off(x, t0 * HP, d.esz), d.xs_b, tv, T, HP, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(stage + ts.dy, (int64_t)T * HP, off(dy, t0 * HP, d.esz), d.xs_b, tv, T, HP, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(stage + ts.dt, (int64_t)T * d.H, off(dt, t0 * d.H, d.esz), d.dts_b, tv, T, d.H, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(stage + ts.B, (int64_t)T * GN, off(B, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(stage + ts.C, (int64_t)T * GN, off(C, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (e != hipSuccess) {
+                (void)join_lanes(pp, nl, st);
+                return SSD_ERR_LAUNCH;
+            }
+            sp.x = stage + ts.x;
+            sp.dy = stage + ts.dy;
+            sp.dx = stage + ts.dx;
+            sp.dt = stage + ts.dt;
+            sp.ddt = stage + ts.ddt;
+            sp.Bm = stage + ts.B;
+            sp.Cm = stage + ts.C;
+            sp.dB = stage + ts.dB;
+            sp.dC = stage + ts.dC;
+            sp.xs_b = sp.ys_b = sp.dys_b = sp.dxs_b = (int64_t)T * HP;
+            sp.dts_b = (int64_t)T * d.H;
+            sp.bcs_b = (int64_t)T * GN;
+            sp.nc = d.nc_tail;
+        }
         sp.chunk0 = (int)(k * d.nc);
         // restore: per-chunk entering states of this segment from its checkpoint
         wire_states(sp, d, k, init_state, boundary_states, nullptr, nullptr);
@@ -420,6 +523,13 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.ev_wait = (nl > 1 && it > 0) ? pp->scan[(it - 1) % nl] : nullptr;
             sp.ev_record = (nl > 1 && k > 0) ? pp->scan[ln] : nullptr;
             e = mfma ? mfma_backward_segment(sp, sk) : generic_backward_segment(sp, d.bf16, sk);
+        }
+        if (e == hipSuccess && short_seg) {  // the valid rows of the results go back to the caller's tensors
+            const int tv = (int)d.tail;
+            e = launch_stage_rows(off(dx, t0 * HP, d.esz), d.xs_b, stage + ts.dx, (int64_t)ts.T * HP, tv, tv, HP, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(off(ddt, t0 * d.H, d.esz), d.dts_b, stage + ts.ddt, (int64_t)ts.T * d.H, tv, tv, d.H, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(off(dB, t0 * GN, d.esz), d.bcs_b, stage + ts.dB, (int64_t)ts.T * GN, tv, tv, GN, sp.Bt, d.esz, sk);
+            if (e == hipSuccess) e = launch_stage_rows(off(dC, t0 * GN, d.esz), d.bcs_b, stage + ts.dC, (int64_t)ts.T * GN, tv, tv, GN, sp.Bt, d.esz, sk);
         }
         if (e != hipSuccess) {
             (void)join_lanes(pp, nl, st);  // whatever was enqueued on the library's streams still ends before the caller's next work
@@ -442,7 +552,7 @@ extern "C" const char* ssd_strerror(int status) {
         case SSD_OK: return "ok";
         case SSD_ERR_NULL: return "a required pointer is NULL";
         case SSD_ERR_SHAPE: return "a dimension is non-positive or exceeds a kernel limit";
-        case SSD_ERR_DIVISIBILITY: return "nheads % ngroups, seqlen % segment or segment % chunk is not zero";
+        case SSD_ERR_DIVISIBILITY: return "nheads % ngroups or segment % chunk is not zero (stack: seqlen % segment)";
         case SSD_ERR_DTYPE: return "unknown dtype";
         case SSD_ERR_WORKSPACE: return "workspace is NULL, not 256-byte aligned, or too small";
         case SSD_ERR_LAUNCH: return "a HIP launch failed";

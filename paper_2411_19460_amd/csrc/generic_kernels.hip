@@ -582,6 +582,34 @@ hipError_t bwd_segment(const SegParams& sp, hipStream_t st) {
 
 }  // namespace
 
+// Rows (tokens) of a [Bt][rows][row_elems] tensor between the caller's buffer and a padded staging
+// buffer: rows >= rows_valid of the staging buffer are zero (copy in) / are not copied (copy out).
+template <typename E>
+__global__ __launch_bounds__(256) void k_stage_rows(E* dst, int64_t dst_bs, const E* src, int64_t src_bs, int rows_valid,
+                                                    int rows_dst, int row_elems, int Bt) {
+    const int64_t per_b = (int64_t)rows_dst * row_elems, total = per_b * Bt;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int64_t b = i / per_b, r = i - b * per_b;
+        const int row = (int)(r / row_elems);
+        dst[b * dst_bs + r] = row < rows_valid ? src[b * src_bs + r] : (E)0;
+    }
+}
+
+hipError_t launch_stage_rows(void* dst, int64_t dst_bs, const void* src, int64_t src_bs, int rows_valid, int rows_dst,
+                             int row_elems, int Bt, size_t esz, hipStream_t st) {
+    const int64_t total = (int64_t)rows_dst * row_elems * Bt;
+    if (total == 0) return hipSuccess;
+    const int64_t blocks = (total + 255) / 256;
+    const dim3 grid((unsigned)(blocks < 65536 ? blocks : 65536));
+    if (esz == 2)
+        SSDK_LAUNCH(K_COPY, st, k_stage_rows<uint16_t>, grid, dim3(256), (uint16_t*)dst, dst_bs, (const uint16_t*)src, src_bs,
+                    rows_valid, rows_dst, row_elems, Bt);
+    else
+        SSDK_LAUNCH(K_COPY, st, k_stage_rows<uint32_t>, grid, dim3(256), (uint32_t*)dst, dst_bs, (const uint32_t*)src, src_bs,
+                    rows_valid, rows_dst, row_elems, Bt);
+    return hipSuccess;
+}
+
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st) {
     if (n == 0) return hipSuccess;
     const size_t blocks = (n + 255) / 256;

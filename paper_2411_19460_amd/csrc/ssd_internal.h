@@ -116,7 +116,9 @@ struct SegParams {
 struct Dims {
     int64_t Bt, L, s;
     int H, P, G, N, Q, nc, hpg;
-    int64_t nseg;
+    int64_t nseg;       // segments, the last one possibly short
+    int64_t tail;       // tokens of a short last segment (0: every segment is full)
+    int nc_tail;        // chunks of that segment (the last one padded with identity tokens)
     size_t esz;
     bool bf16;
     int64_t xs_b, dts_b, bcs_b;
@@ -165,6 +167,9 @@ bool prof_events(int kid, hipEvent_t* start, hipEvent_t* stop);
 // Launchers.  Each returns hipSuccess or the launch error.  is_bf16 selects the storage type.
 hipError_t launch_fill_zero(float* p, size_t n, hipStream_t st);
 hipError_t launch_copy_f32(float* dst, const float* src, size_t n, hipStream_t st);
+// dst[b][row][:] = row < rows_valid ? src[b][row][:] : 0 for row < rows_dst (batch strides in elements of esz bytes).
+hipError_t launch_stage_rows(void* dst, int64_t dst_bs, const void* src, int64_t src_bs, int rows_valid, int rows_dst,
+                             int row_elems, int Bt, size_t esz, hipStream_t st);
 hipError_t generic_forward_segment(const SegParams& sp, bool is_bf16, bool need_y, hipStream_t st);
 hipError_t generic_backward_segment(const SegParams& sp, bool is_bf16, hipStream_t st);
 hipError_t generic_backward_scalars(const SegParams& sp, hipStream_t st);

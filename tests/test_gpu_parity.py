@@ -5,6 +5,7 @@ import pytest
 import torch
 
 import paper_2411_19460_amd as pk
+from oracle import ssd_ref
 from paper_2411_19460_amd import synth
 from parity_util import TOL, check, compare_all, dev_inputs, host, run_gpu, run_oracle
 
@@ -154,3 +155,36 @@ def test_autograd_wrapper_matches_the_direct_calls_and_the_oracle():
     _, go = run_oracle(d, 256)
     check("dx via autograd", host(leaf["x"].grad), go["dx"], TOL["bf16"])
     check("dA via autograd", host(leaf["A"].grad), go["dA"], TOL["bf16"])
+
+
+@pytest.mark.parametrize("case", [
+    # dtype, Bt, L,    H, P,  G, N,   Q,   segment, flags
+    ("f32", 2, 200, 3, 16, 1, 16, 64, 128, 0),                                 # short last segment, short last chunk
+    ("bf16", 2, 1000, 4, 64, 2, 128, 256, 512, 0),                             # matrix-core path, two segments in flight
+    ("bf16", 1, 300, 2, 64, 1, 128, 256, None, 0),                             # one segment, shorter than two chunks
+    ("bf16", 1, 2148, 2, 64, 1, 128, 128, 512, 0),                             # five segments on four lanes, tail of 100
+    ("bf16", 1, 700, 2, 64, 1, 128, 128, 256, pk.SSD_FLAG_GENERIC_KERNELS),
+])
+def test_sequence_length_need_not_be_a_multiple_of_segment_or_chunk(case):
+    dtype, Bt, L, H, P, G, N, Q, seg, flags = case
+    d = small_inputs(13, dtype, Bt, L, H, P, G, N)
+    dv = dev_inputs(d, dtype)
+    y, fin, bnd, g = run_gpu(dv, Q, seg, flags)
+    f, go = run_oracle(d, None)
+    tol = TOL[dtype]
+    check("y", host(y), f["y"], tol)
+    check("final_state", host(fin), f["final_state"], tol)
+    if seg is not None:
+        nseg = -(-L // seg)
+        assert bnd.shape[1] == nseg
+        for k in range(1, nseg):   # the state entering segment k = the final state of the first k segments
+            fk = ssd_ref.ssd_fwd(d["x"][:, :k * seg], d["dt"][:, :k * seg], d["A"], d["B"][:, :k * seg], d["C"][:, :k * seg],
+                                 d["D"], d["init_state"])
+            check(f"boundary_states[{k}]", host(bnd[:, k]), fk["final_state"], tol)
+    for k in ("dx", "ddt", "dA", "dB", "dC", "dD", "dinit_state"):
+        check(k, host(g[k]), go[k], tol)
+    # prefill without checkpoints agrees
+    y2, fin2, _ = pk.ssd_fwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], Q, seg, dv["init_state"], flags,
+                             want_boundary=False)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2) and torch.equal(fin, fin2)
