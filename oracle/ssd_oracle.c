@@ -39,9 +39,8 @@ static int group_of(int h, int H, int G, const int *head_group) {
 }
 
 /* One token of the recurrence for one (batch, head): updates h in place, writes y_t. */
-static void step_forward(int P, int N, double a_coef, double dt, double Dh, const double *xt,
+static void step_forward(int P, int N, double alpha, double dt, double Dh, const double *xt,
                          const double *Bt, const double *Ct, double *h, double *yt) {
-    const double alpha = exp(dt * a_coef);
     for (int p = 0; p < P; ++p) {
         const double dtx = dt * xt[p];
         double acc = 0.0;
@@ -54,10 +53,16 @@ static void step_forward(int P, int N, double a_coef, double dt, double Dh, cons
     }
 }
 
-int ssd_oracle_fwd(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
-                   const double *A, const double *Bm, const double *Cm, const double *D,
-                   const double *init_state, const int *head_group, double *y,
-                   double *final_state, long segment, double *boundary_states) {
+/* Decay factor of token t: exp(dt_t A_h), or 0 where a new packed sequence starts (reset[b,t] != 0):
+ * that token sees no state from the tokens before it. */
+static double decay_of(const unsigned char *reset, size_t tok, double dt, double a_coef) {
+    return (reset && reset[tok]) ? 0.0 : exp(dt * a_coef);
+}
+
+int ssd_oracle_fwd_packed(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
+                          const double *A, const double *Bm, const double *Cm, const double *D,
+                          const double *init_state, const int *head_group, const unsigned char *reset, double *y,
+                          double *final_state, long segment, double *boundary_states) {
     if (Bt <= 0 || L < 0 || H <= 0 || P <= 0 || G <= 0 || N <= 0) return -1;
     if (!head_group && H % G != 0) return -1;
     if (boundary_states && (segment <= 0 || L % segment != 0)) return -1;
@@ -77,8 +82,8 @@ int ssd_oracle_fwd(long Bt, long L, int H, int P, int G, int N, const double *x,
                     memcpy(boundary_states + (((size_t)b * nseg + t / segment) * H + h) * PN, st,
                            PN * sizeof(double));
                 const size_t tok = (size_t)b * L + t;
-                step_forward(P, N, A[h], dt[tok * H + h], D[h], x + (tok * H + h) * P,
-                             Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, st,
+                step_forward(P, N, decay_of(reset, tok, dt[tok * H + h], A[h]), dt[tok * H + h], D[h],
+                             x + (tok * H + h) * P, Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, st,
                              y ? y + (tok * H + h) * P : NULL);
             }
             if (final_state) memcpy(final_state + ((size_t)b * H + h) * PN, st, PN * sizeof(double));
@@ -88,11 +93,19 @@ int ssd_oracle_fwd(long Bt, long L, int H, int P, int G, int N, const double *x,
     return fail ? -2 : 0;
 }
 
-int ssd_oracle_bwd(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
+int ssd_oracle_fwd(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
                    const double *A, const double *Bm, const double *Cm, const double *D,
-                   const double *init_state, const int *head_group, const double *dy,
-                   const double *dfinal_state, double *dx, double *ddt, double *dA, double *dB,
-                   double *dC, double *dD, double *dinit_state, long ckpt_every) {
+                   const double *init_state, const int *head_group, double *y,
+                   double *final_state, long segment, double *boundary_states) {
+    return ssd_oracle_fwd_packed(Bt, L, H, P, G, N, x, dt, A, Bm, Cm, D, init_state, head_group, NULL, y, final_state,
+                                 segment, boundary_states);
+}
+
+int ssd_oracle_bwd_packed(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
+                          const double *A, const double *Bm, const double *Cm, const double *D,
+                          const double *init_state, const int *head_group, const unsigned char *reset,
+                          const double *dy, const double *dfinal_state, double *dx, double *ddt, double *dA,
+                          double *dB, double *dC, double *dD, double *dinit_state, long ckpt_every) {
     if (Bt <= 0 || L < 0 || H <= 0 || P <= 0 || G <= 0 || N <= 0) return -1;
     if (!head_group && H % G != 0) return -1;
     if (ckpt_every <= 0) ckpt_every = 256;
@@ -126,8 +139,8 @@ int ssd_oracle_bwd(long Bt, long L, int H, int P, int G, int N, const double *x,
             for (long t = 0; t < L; ++t) {
                 if (t % ckpt_every == 0) memcpy(entering + (t / ckpt_every) * PN, traj, PN * sizeof(double));
                 const size_t tok = (size_t)b * L + t;
-                step_forward(P, N, a_coef, dt[tok * H + h], Dh, x + (tok * H + h) * P,
-                             Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, traj, NULL);
+                step_forward(P, N, decay_of(reset, tok, dt[tok * H + h], a_coef), dt[tok * H + h], Dh,
+                             x + (tok * H + h) * P, Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, traj, NULL);
             }
             /* adjoint flowing into h_{L-1} from beyond the sequence */
             if (dfinal_state) memcpy(carry, dfinal_state + ((size_t)b * H + h) * PN, PN * sizeof(double));
@@ -142,13 +155,13 @@ int ssd_oracle_bwd(long Bt, long L, int H, int P, int G, int N, const double *x,
                     double *nxt = traj + (size_t)(t - t0 + 1) * PN;
                     memcpy(nxt, traj + (size_t)(t - t0) * PN, PN * sizeof(double));
                     const size_t tok = (size_t)b * L + t;
-                    step_forward(P, N, a_coef, dt[tok * H + h], Dh, x + (tok * H + h) * P,
-                                 Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, nxt, NULL);
+                    step_forward(P, N, decay_of(reset, tok, dt[tok * H + h], a_coef), dt[tok * H + h], Dh,
+                                 x + (tok * H + h) * P, Bm + (tok * G + g) * N, Cm + (tok * G + g) * N, nxt, NULL);
                 }
                 for (long t = t1 - 1; t >= t0; --t) {
                     const size_t tok = (size_t)b * L + t;
                     const double dtt = dt[tok * H + h];
-                    const double alpha = exp(dtt * a_coef);
+                    const double alpha = decay_of(reset, tok, dtt, a_coef); /* 0 at a sequence start: da = 0 there too */
                     const double *xt = x + (tok * H + h) * P;
                     const double *dyt = dy + (tok * H + h) * P;
                     const double *Bt_ = Bm + (tok * G + g) * N;
@@ -197,4 +210,13 @@ int ssd_oracle_bwd(long Bt, long L, int H, int P, int G, int N, const double *x,
         }
     }
     return fail ? -2 : 0;
+}
+
+int ssd_oracle_bwd(long Bt, long L, int H, int P, int G, int N, const double *x, const double *dt,
+                   const double *A, const double *Bm, const double *Cm, const double *D,
+                   const double *init_state, const int *head_group, const double *dy,
+                   const double *dfinal_state, double *dx, double *ddt, double *dA, double *dB,
+                   double *dC, double *dD, double *dinit_state, long ckpt_every) {
+    return ssd_oracle_bwd_packed(Bt, L, H, P, G, N, x, dt, A, Bm, Cm, D, init_state, head_group, NULL, dy, dfinal_state,
+                                 dx, ddt, dA, dB, dC, dD, dinit_state, ckpt_every);
 }

@@ -36,6 +36,13 @@ def _lib():
         lib.ssd_oracle_bwd.restype = ctypes.c_int
         lib.ssd_oracle_bwd.argtypes = [ctypes.c_long, ctypes.c_long] + [ctypes.c_int] * 4 + [_dp] * 7 + [
             _ip, _dp, _dp] + [_dp] * 7 + [ctypes.c_long]
+        _bp = ctypes.POINTER(ctypes.c_ubyte)
+        lib.ssd_oracle_fwd_packed.restype = ctypes.c_int
+        lib.ssd_oracle_fwd_packed.argtypes = [ctypes.c_long, ctypes.c_long] + [ctypes.c_int] * 4 + [_dp] * 7 + [
+            _ip, _bp, _dp, _dp, ctypes.c_long, _dp]
+        lib.ssd_oracle_bwd_packed.restype = ctypes.c_int
+        lib.ssd_oracle_bwd_packed.argtypes = [ctypes.c_long, ctypes.c_long] + [ctypes.c_int] * 4 + [_dp] * 7 + [
+            _ip, _bp, _dp, _dp] + [_dp] * 7 + [ctypes.c_long]
         _LIB = lib
     return _LIB
 
@@ -54,11 +61,20 @@ def _dims(x, Bm):
     return Bt, L, H, P, G, N
 
 
-def ssd_fwd(x, dt, A, B, C, D, init_state=None, segment=None, head_group=None):
+def _reset_ptr(reset, Bt, L):
+    if reset is None:
+        return None, None
+    r = np.ascontiguousarray(reset, dtype=np.uint8)
+    assert r.shape == (Bt, L)
+    return r, r.ctypes.data_as(ctypes.POINTER(ctypes.c_ubyte))
+
+
+def ssd_fwd(x, dt, A, B, C, D, init_state=None, segment=None, head_group=None, reset=None):
     """Returns dict(y, final_state, boundary_states) in fp64.
 
     boundary_states[b, k] = state entering segment k (k = 0 is the initial state);
-    it is None when `segment` is None."""
+    it is None when `segment` is None.  reset [Bt, L] (0/1), optional: packed sequences -- a token with
+    reset = 1 starts a new sequence and sees no state from the tokens before it."""
     x, dt, A, B, C, D, init_state = map(_f64, (x, dt, A, B, C, D, init_state))
     Bt, L, H, P, G, N = _dims(x, B)
     hg = None if head_group is None else np.ascontiguousarray(head_group, dtype=np.int32)
@@ -68,15 +84,16 @@ def ssd_fwd(x, dt, A, B, C, D, init_state=None, segment=None, head_group=None):
     if segment is not None:
         assert L % segment == 0
         bnd = np.empty((Bt, L // segment, H, P, N))
-    rc = _lib().ssd_oracle_fwd(Bt, L, H, P, G, N, _p(x), _p(dt), _p(A), _p(B), _p(C), _p(D), _p(init_state),
-                               None if hg is None else hg.ctypes.data_as(_ip), _p(y), _p(fin),
-                               0 if segment is None else segment, _p(bnd))
+    keep, rp = _reset_ptr(reset, Bt, L)
+    rc = _lib().ssd_oracle_fwd_packed(Bt, L, H, P, G, N, _p(x), _p(dt), _p(A), _p(B), _p(C), _p(D), _p(init_state),
+                                      None if hg is None else hg.ctypes.data_as(_ip), rp, _p(y), _p(fin),
+                                      0 if segment is None else segment, _p(bnd))
     if rc != 0:
         raise RuntimeError(f"ssd_oracle_fwd failed: {rc}")
     return {"y": y, "final_state": fin, "boundary_states": bnd}
 
 
-def ssd_bwd(x, dt, A, B, C, D, dy, init_state=None, dfinal_state=None, head_group=None, ckpt_every=256):
+def ssd_bwd(x, dt, A, B, C, D, dy, init_state=None, dfinal_state=None, head_group=None, ckpt_every=256, reset=None):
     """Reverse-mode gradients of <dy, y> + <dfinal_state, final_state>, fp64."""
     x, dt, A, B, C, D, dy, init_state, dfinal_state = map(
         _f64, (x, dt, A, B, C, D, dy, init_state, dfinal_state))
@@ -89,9 +106,10 @@ def ssd_bwd(x, dt, A, B, C, D, dy, init_state=None, dfinal_state=None, head_grou
     dB = np.empty_like(B)
     dC = np.empty_like(C)
     dinit = np.empty((Bt, H, P, N))
-    rc = _lib().ssd_oracle_bwd(Bt, L, H, P, G, N, _p(x), _p(dt), _p(A), _p(B), _p(C), _p(D), _p(init_state),
-                               None if hg is None else hg.ctypes.data_as(_ip), _p(dy), _p(dfinal_state),
-                               _p(dx), _p(ddt), _p(dA), _p(dB), _p(dC), _p(dD), _p(dinit), ckpt_every)
+    keep, rp = _reset_ptr(reset, Bt, L)
+    rc = _lib().ssd_oracle_bwd_packed(Bt, L, H, P, G, N, _p(x), _p(dt), _p(A), _p(B), _p(C), _p(D), _p(init_state),
+                                      None if hg is None else hg.ctypes.data_as(_ip), rp, _p(dy), _p(dfinal_state),
+                                      _p(dx), _p(ddt), _p(dA), _p(dB), _p(dC), _p(dD), _p(dinit), ckpt_every)
     if rc != 0:
         raise RuntimeError(f"ssd_oracle_bwd failed: {rc}")
     return {"dx": dx, "ddt": ddt, "dA": dA, "dB": dB, "dC": dC, "dD": dD, "dinit_state": dinit}

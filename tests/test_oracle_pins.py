@@ -332,3 +332,43 @@ def test_stack_gradients_and_cell_order():
     sub_layers = [dict(q, dt=q["dt"][:, :, [1]], A=q["A"][[1]], D=q["D"][[1]]) for q in layers]
     fs = ssd_ref.stack_fwd(x0[:, :, [1]], sub_layers, head_group=[0])
     close(fs["out"], f["out"][:, :, [1]], 0.0)
+
+
+def test_packed_sequences_equal_separate_runs():
+    """reset[b, t] = 1 starts a new sequence at token t: the packed run must give, piece by piece, what
+    separate runs of the pieces give (each from a zero state; the first piece from init_state), in the
+    forward pass and in every gradient.  The pieces are checked with the plain (unpacked) entry points."""
+    d = draw(21, Bt=2, L=14, H=4, P=3, G=2, N=5)
+    cuts = [[0, 5, 6, 14], [0, 9, 14]]        # piece boundaries per batch row (a one-token piece included)
+    reset = np.zeros((2, 14), dtype=np.uint8)
+    for b, cs in enumerate(cuts):
+        for c in cs[1:-1]:
+            reset[b, c] = 1
+    f = fwd(d, reset=reset)
+    g = bwd(d, reset=reset)
+    dA, dD = np.zeros(4), np.zeros(4)
+    for b, cs in enumerate(cuts):
+        for i in range(len(cs) - 1):
+            lo, hi = cs[i], cs[i + 1]
+            first, last = i == 0, i == len(cs) - 2
+            piece = {k: d[k][b:b + 1, lo:hi] for k in ("x", "dt", "B", "C", "dy")}
+            piece.update(A=d["A"], D=d["D"], init_state=d["init_state"][b:b + 1] if first else None,
+                         dfinal_state=d["dfinal_state"][b:b + 1] if last else None)
+            fp, gp = fwd(piece), bwd(piece)
+            close(f["y"][b:b + 1, lo:hi], fp["y"])
+            for k in ("dx", "ddt", "dB", "dC"):
+                close(g[k][b:b + 1, lo:hi], gp[k])
+            dA += gp["dA"]
+            dD += gp["dD"]
+            if last:
+                close(f["final_state"][b:b + 1], fp["final_state"])
+            if first:
+                close(g["dinit_state"][b:b + 1], gp["dinit_state"])
+    close(g["dA"], dA)
+    close(g["dD"], dD)
+    # a reset at token 0 discards the initial state
+    r0 = np.zeros((2, 14), dtype=np.uint8)
+    r0[:, 0] = 1
+    d0 = dict(d, init_state=None)
+    close(fwd(d, reset=r0)["y"], fwd(d0)["y"])
+    assert float(np.max(np.abs(bwd(d, reset=r0)["dinit_state"]))) == 0.0
