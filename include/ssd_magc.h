@@ -78,6 +78,11 @@ typedef struct ssd_shape_t {
     int64_t x_batch_stride;   /* elements between batches of x, y, dy, dx      (0 = L*H*P) */
     int64_t dt_batch_stride;  /* elements between batches of dt, ddt           (0 = L*H)   */
     int64_t bc_batch_stride;  /* elements between batches of B, C, dB, dC      (0 = L*G*N) */
+    const uint8_t* seq_reset; /* optional, device, [Bt, L] (dense): packed sequences.  A token with a non-zero
+                                 flag starts a new sequence: its decay factor exp(dt A) carries an extra
+                                 exp(-100) (< 4e-44), i.e. the state from the tokens before it is cut off --
+                                 in y, in the states and in every gradient.  NULL: one sequence per batch row.
+                                 Not used by the stack driver. */
 } ssd_shape_t;
 
 /* Flags for ssd_fwd / ssd_bwd. */

@@ -25,7 +25,7 @@ class ssd_shape_t(ctypes.Structure):
                 ("ngroups", ctypes.c_int32), ("dstate", ctypes.c_int32), ("chunk", ctypes.c_int32),
                 ("batch", ctypes.c_int64), ("seqlen", ctypes.c_int64), ("segment", ctypes.c_int64),
                 ("x_batch_stride", ctypes.c_int64), ("dt_batch_stride", ctypes.c_int64),
-                ("bc_batch_stride", ctypes.c_int64)]
+                ("bc_batch_stride", ctypes.c_int64), ("seq_reset", ctypes.c_void_p)]
 
 
 class magc_model_t(ctypes.Structure):
@@ -104,7 +104,7 @@ def _stream(t) -> Optional[int]:
     return torch.cuda.current_stream(t.device).cuda_stream or None
 
 
-def make_shape(x, Bm, chunk: int, segment: Optional[int] = None) -> ssd_shape_t:
+def make_shape(x, Bm, chunk: int, segment: Optional[int] = None, seq_reset=None) -> ssd_shape_t:
     import torch
     Bt, L, H, P = x.shape
     G, N = Bm.shape[2], Bm.shape[3]
@@ -116,7 +116,10 @@ def make_shape(x, Bm, chunk: int, segment: Optional[int] = None) -> ssd_shape_t:
         raise TypeError(f"unsupported dtype {x.dtype}")
     if segment is None:   # one segment: the sequence rounded up to whole chunks
         segment = max(chunk, -(-L // chunk) * chunk)
-    return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, segment, 0, 0, 0)
+    if seq_reset is not None:
+        if seq_reset.dtype != torch.uint8 or tuple(seq_reset.shape) != (Bt, L) or not seq_reset.is_cuda or not seq_reset.is_contiguous():
+            raise TypeError("seq_reset must be a contiguous uint8 device tensor [Bt, L]")
+    return ssd_shape_t(dt, H, P, G, N, chunk, Bt, L, segment, 0, 0, 0, _ptr(seq_reset))
 
 
 def ssd_workspace_bytes(shape: ssd_shape_t, is_backward: bool, flags: int = 0) -> int:
@@ -142,13 +145,13 @@ def _workspace(nbytes: int, device):
 
 
 def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, workspace=None, want_final=True,
-            out=None, want_boundary=True):
+            out=None, want_boundary=True, seq_reset=None):
     """y, final_state, boundary_states = ssd_fwd(...).  boundary_states is None when segment is None/L,
     or with want_boundary=False (forward only: no checkpoint is kept).
     `out` may carry preallocated tensors under the keys y, final_state, boundary_states."""
     import torch
     _check_inputs(x, dt, A, B, C, D, init_state)
-    shape = make_shape(x, B, chunk, segment)
+    shape = make_shape(x, B, chunk, segment, seq_reset)
     Bt, L, H, P = x.shape
     N = B.shape[3]
     out = out or {}
@@ -170,14 +173,14 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     return y, final, bnd
 
 
-def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None):
+def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None, seq_reset=None):
     """y = ssd_decode(...): the recurrence token by token over x's T tokens; `state` [Bt,H,P,N] fp32 is
     updated in place."""
     import torch
     _check_inputs(x, dt, A, B, C, D, state)
     if state.dtype != torch.float32:
         raise TypeError("state must be fp32")
-    shape = make_shape(x, B, 1, None)
+    shape = make_shape(x, B, 1, None, seq_reset)
     y = out if out is not None else torch.empty_like(x)
     rc = lib().ssd_decode(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(state),
                           _ptr(y), flags, _stream(x))
@@ -187,12 +190,12 @@ def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None):
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,
-            flags=0, workspace=None, dA=None, dD=None, want_dinit=True, out=None):
+            flags=0, workspace=None, dA=None, dD=None, want_dinit=True, out=None, seq_reset=None):
     """Returns dict(dx, ddt, dA, dB, dC, dD, dinit_state).  `out` may carry preallocated dx, ddt, dB, dC,
     dinit_state."""
     import torch
     _check_inputs(x, dt, A, B, C, D, dy, init_state, dfinal_state, boundary_states)
-    shape = make_shape(x, B, chunk, segment)
+    shape = make_shape(x, B, chunk, segment, seq_reset)
     Bt, L, H, P = x.shape
     N = B.shape[3]
     out = out or {}

@@ -47,6 +47,7 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     d->xs_b = sh->x_batch_stride ? sh->x_batch_stride : d->L * d->H * d->P;
     d->dts_b = sh->dt_batch_stride ? sh->dt_batch_stride : d->L * d->H;
     d->bcs_b = sh->bc_batch_stride ? sh->bc_batch_stride : d->L * d->G * d->N;
+    d->reset = sh->seq_reset;
     if (d->xs_b < d->L * d->H * d->P || d->dts_b < d->L * d->H || d->bcs_b < d->L * d->G * d->N) return SSD_ERR_SHAPE;
     // every launch keeps its largest grid dimension below 2^31
     const int64_t blocks = d->Bt * (int64_t)d->nc * d->H * 2;
@@ -222,7 +223,7 @@ static size_t carry_bytes(const Dims& d) { return d.nseg > 1 ? 2 * align_up((siz
 // tokens: the padding tokens have dt = 0 and x = B = C = dy = 0, i.e. they are identity steps of the
 // recurrence that add nothing to any gradient.  Offsets (bytes) of the copies behind the scratch blocks.
 struct TailStage {
-    size_t x, dt, B, C, y, dy, dx, ddt, dB, dC, total;
+    size_t x, dt, B, C, y, dy, dx, ddt, dB, dC, reset, total;
     int64_t T;  // tokens of the padded segment
 };
 static TailStage tail_stage(const Dims& d, bool bwd) {
@@ -249,6 +250,10 @@ static TailStage tail_stage(const Dims& d, bool bwd) {
         t.ddt = take(d.H);
         t.dB = take(gn);
         t.dC = take(gn);
+    }
+    if (d.reset) {
+        t.reset = off;
+        off += align_up((size_t)d.Bt * t.T);
     }
     t.total = off;
     return t;
@@ -364,12 +369,15 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.dts_b = d.dts_b;
             sp.bcs_b = d.bcs_b;
             sp.nc = d.nc;
+            sp.reset = d.reset ? d.reset + t0 : nullptr;
+            sp.reset_bs = d.L;
         } else {  // padded copies of the last tokens (see TailStage)
             const int tv = (int)d.tail, T = (int)ts.T;
             hipError_t es = launch_stage_rows(stage + ts.x, (int64_t)T * HP, off(x, t0 * HP, d.esz), d.xs_b, tv, T, HP, sp.Bt, d.esz, sk);
             if (es == hipSuccess) es = launch_stage_rows(stage + ts.dt, (int64_t)T * d.H, off(dt, t0 * d.H, d.esz), d.dts_b, tv, T, d.H, sp.Bt, d.esz, sk);
             if (es == hipSuccess) es = launch_stage_rows(stage + ts.B, (int64_t)T * GN, off(B, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
             if (es == hipSuccess) es = launch_stage_rows(stage + ts.C, (int64_t)T * GN, off(C, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (es == hipSuccess && d.reset) es = launch_stage_rows(stage + ts.reset, T, d.reset + t0, d.L, tv, T, 1, sp.Bt, 1, sk);
             if (es != hipSuccess) {
                 (void)join_lanes(pp, nl, st);
                 return SSD_ERR_LAUNCH;
@@ -383,6 +391,8 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.dts_b = (int64_t)T * d.H;
             sp.bcs_b = (int64_t)T * GN;
             sp.nc = d.nc_tail;
+            sp.reset = d.reset ? (const uint8_t*)(stage + ts.reset) : nullptr;
+            sp.reset_bs = T;
         }
         wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
         if (!boundary_states && d.nseg > 1) {  // no checkpoints kept: hand the state on through the carry buffers
@@ -488,6 +498,8 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.dts_b = d.dts_b;
             sp.bcs_b = d.bcs_b;
             sp.nc = d.nc;
+            sp.reset = d.reset ? d.reset + t0 : nullptr;
+            sp.reset_bs = d.L;
         } else {  // padded copies of the last tokens (see TailStage); results come back after the segment
             const int tv = (int)d.tail, T = (int)ts.T;
             e = launch_stage_rows(stage + ts.x, (int64_t)T * HP, off(x, t0 * HP, d.esz), d.xs_b, tv, T, HP, sp.Bt, d.esz, sk);
@@ -495,6 +507,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             if (e == hipSuccess) e = launch_stage_rows(stage + ts.dt, (int64_t)T * d.H, off(dt, t0 * d.H, d.esz), d.dts_b, tv, T, d.H, sp.Bt, d.esz, sk);
             if (e == hipSuccess) e = launch_stage_rows(stage + ts.B, (int64_t)T * GN, off(B, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
             if (e == hipSuccess) e = launch_stage_rows(stage + ts.C, (int64_t)T * GN, off(C, t0 * GN, d.esz), d.bcs_b, tv, T, GN, sp.Bt, d.esz, sk);
+            if (e == hipSuccess && d.reset) e = launch_stage_rows(stage + ts.reset, T, d.reset + t0, d.L, tv, T, 1, sp.Bt, 1, sk);
             if (e != hipSuccess) {
                 (void)join_lanes(pp, nl, st);
                 return SSD_ERR_LAUNCH;
@@ -512,6 +525,8 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.dts_b = (int64_t)T * d.H;
             sp.bcs_b = (int64_t)T * GN;
             sp.nc = d.nc_tail;
+            sp.reset = d.reset ? (const uint8_t*)(stage + ts.reset) : nullptr;
+            sp.reset_bs = T;
         }
         sp.chunk0 = (int)(k * d.nc);
         // restore: per-chunk entering states of this segment from its checkpoint

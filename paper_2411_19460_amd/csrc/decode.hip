@@ -10,6 +10,7 @@ namespace {
 
 struct DecodeParams {
     const void *x, *dt, *Bm, *Cm;
+    const uint8_t* reset;  // optional [Bt][T]: non-zero = the state is dropped before this token
     const float *A, *D;
     float* state;
     void* y;
@@ -42,7 +43,7 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams dp) {
     float* S = dp.state + ((int64_t)b * dp.H + h) * dp.P * dp.N;
     for (int64_t t = 0; t < dp.T; ++t) {
         const float dtv = ld<T>(dp.dt, (int64_t)b * dp.dts_b + t * dp.H + h);
-        const float a = __expf(dtv * Ah);
+        const float a = (dp.reset && dp.reset[(int64_t)b * dp.T + t]) ? 0.f : __expf(dtv * Ah);
         const int64_t bc = (int64_t)b * dp.bcs_b + (t * dp.G + g) * dp.N;
         const int64_t xo = (int64_t)b * dp.xs_b + (t * dp.H + h) * dp.P;
         for (int p = 4 * blockIdx.z + w; p < dp.P; p += 4 * gridDim.z) {
@@ -84,6 +85,7 @@ extern "C" int ssd_decode(const ssd_shape_t* sh, const void* x, const void* dt, 
     dp.A = A;
     dp.D = D;
     dp.state = state;
+    dp.reset = sh->seq_reset;
     dp.y = y;
     dp.T = sh->seqlen;
     dp.H = sh->nheads;

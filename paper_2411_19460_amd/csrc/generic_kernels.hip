@@ -81,6 +81,7 @@ __global__ void k_cumsum(SegParams sp) {
     float d = 0.f;
     if (i < sp.Q) d = IO<T>::ld(sp.dt, (int64_t)b * sp.dts_b + ((int64_t)c * sp.Q + i) * sp.H + h);
     s[i] = d * sp.A[h];
+    if (i < sp.Q && sp.reset && sp.reset[(int64_t)b * sp.reset_bs + (int64_t)c * sp.Q + i]) s[i] += RESET_LOG_DECAY;
     __syncthreads();
     for (int off = 1; off < (int)blockDim.x; off <<= 1) {
         const float v = (i >= off) ? s[i - off] : 0.f;
@@ -601,7 +602,10 @@ hipError_t launch_stage_rows(void* dst, int64_t dst_bs, const void* src, int64_t
     if (total == 0) return hipSuccess;
     const int64_t blocks = (total + 255) / 256;
     const dim3 grid((unsigned)(blocks < 65536 ? blocks : 65536));
-    if (esz == 2)
+    if (esz == 1)
+        SSDK_LAUNCH(K_COPY, st, k_stage_rows<uint8_t>, grid, dim3(256), (uint8_t*)dst, dst_bs, (const uint8_t*)src, src_bs,
+                    rows_valid, rows_dst, row_elems, Bt);
+    else if (esz == 2)
         SSDK_LAUNCH(K_COPY, st, k_stage_rows<uint16_t>, grid, dim3(256), (uint16_t*)dst, dst_bs, (const uint16_t*)src, src_bs,
                     rows_valid, rows_dst, row_elems, Bt);
     else

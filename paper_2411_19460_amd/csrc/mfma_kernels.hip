@@ -33,7 +33,7 @@ __global__ __launch_bounds__(Q) void mk_prep(SegParams sp) {
     __shared__ float s[Q];
     const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
     const float d = bf16_to_float(((const bf16_t*)sp.dt)[(int64_t)b * sp.dts_b + ((int64_t)c * Q + i) * sp.H + h]);
-    s[i] = d * sp.A[h];
+    s[i] = d * sp.A[h] + ((sp.reset && sp.reset[(int64_t)b * sp.reset_bs + (int64_t)c * Q + i]) ? RESET_LOG_DECAY : 0.f);
     __syncthreads();
     for (int off = 1; off < Q; off <<= 1) {
         const float v = (i >= off) ? s[i - off] : 0.f;

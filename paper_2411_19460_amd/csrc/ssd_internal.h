@@ -48,6 +48,8 @@ struct SegParams {
     int Bt, H, P, G, N, Q, nc, hpg;
     int64_t xs_b, ys_b, dys_b, dxs_b;  // batch strides of x, y, dy, dx
     int64_t dts_b, bcs_b;              // of dt/ddt and of B/C/dB/dC
+    const uint8_t* reset;              // optional [Bt][tokens of the segment]: non-zero = a packed sequence starts here
+    int64_t reset_bs;                  // its batch stride
     uint32_t flags;
     // inputs / outputs
     const void* x;
@@ -122,7 +124,12 @@ struct Dims {
     size_t esz;
     bool bf16;
     int64_t xs_b, dts_b, bcs_b;
+    const uint8_t* reset;  // optional packed-sequence flags [Bt][L]
 };
+
+// What a packed-sequence start adds to the token's log-decay dt*A: exp(-100) < 4e-44 cuts the state off
+// (and with it every gradient path through it) while every decay factor stays a product of factors <= 1.
+constexpr float RESET_LOG_DECAY = -100.f;
 
 // Byte offsets of the per-segment scratch arrays inside the caller's workspace (WS_NONE: the array
 // does not exist on the chosen kernel path and its pointer stays null).

@@ -29,6 +29,7 @@ int check_stack(const ssd_shape_t* shape, int32_t nlayers, int32_t layer_interva
     if (shape->seqlen <= 0) return SSD_ERR_SHAPE;
     if (shape->x_batch_stride || shape->dt_batch_stride || shape->bc_batch_stride) return SSD_ERR_ARG;
     if (shape->segment > 0 && shape->seqlen % shape->segment != 0) return SSD_ERR_DIVISIBILITY;  // the grid has whole cells only
+    if (shape->seq_reset) return SSD_ERR_ARG;  // packed sequences are not wired through the stack
     ssd_shape_t cs = *shape;
     cs.seqlen = shape->segment;
     rc = check_shape(&cs, &sd->cell);

@@ -106,6 +106,7 @@ def test_stack_validation():
     assert pk.magc_stack_workspace_bytes(sh, 0, 2, True) == 0
     assert pk.magc_stack_workspace_bytes(shape(x_batch_stride=1 << 30), 4, 2, True) == 0
     assert pk.magc_stack_workspace_bytes(shape(seqlen=2000), 4, 2, True) == 0        # the grid has whole cells only
+    assert pk.magc_stack_workspace_bytes(shape(seq_reset=0x1000), 4, 2, True) == 0    # no packed sequences in the stack
     # a larger layer interval keeps more restored activations alive inside a cell
     assert pk.magc_stack_workspace_bytes(sh, 8, 8, True) > pk.magc_stack_workspace_bytes(sh, 8, 2, True)
 

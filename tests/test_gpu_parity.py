@@ -188,3 +188,49 @@ def test_sequence_length_need_not_be_a_multiple_of_segment_or_chunk(case):
                              want_boundary=False)
     torch.cuda.synchronize()
     assert torch.equal(y, y2) and torch.equal(fin, fin2)
+
+
+@pytest.mark.parametrize("case", [
+    # dtype, Bt, L,   H, P,  G, N,   Q,   segment, flags
+    ("f32", 2, 256, 3, 16, 1, 16, 64, 128, 0),
+    ("bf16", 2, 1024, 4, 64, 2, 128, 256, 512, 0),
+    ("bf16", 1, 1100, 2, 64, 1, 128, 128, 256, 0),                             # five segments in flight, short tail
+    ("bf16", 1, 768, 2, 64, 1, 128, 256, 256, pk.SSD_FLAG_GENERIC_KERNELS),
+])
+def test_packed_sequences(case):
+    """seq_reset marks the first token of every packed sequence: starts inside a chunk, on a chunk
+    boundary, on a segment boundary, two in a row, and at token 0 (which discards init_state)."""
+    dtype, Bt, L, H, P, G, N, Q, seg, flags = case
+    d = small_inputs(17, dtype, Bt, L, H, P, G, N)
+    reset = np.zeros((Bt, L), dtype=np.uint8)
+    for t in (37, Q, Q + 1, seg, seg + Q // 2, L - 3):
+        reset[0, t] = 1
+    if Bt > 1:
+        reset[1, 0] = 1
+        reset[1, L // 2 + 5] = 1
+    dv = dev_inputs(d, dtype)
+    rdev = torch.from_numpy(reset).cuda()
+    y, fin, bnd = pk.ssd_fwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], Q, seg, dv["init_state"], flags,
+                             seq_reset=rdev)
+    g = pk.ssd_bwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], dv["dy"], Q, seg, dv["init_state"],
+                   dv["dfinal_state"], bnd, flags, seq_reset=rdev)
+    torch.cuda.synchronize()
+    f = ssd_ref.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["init_state"], reset=reset)
+    go = ssd_ref.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], d["init_state"], d["dfinal_state"],
+                         reset=reset)
+    tol = TOL[dtype]
+    rep = {}
+    check("y", host(y), f["y"], tol, rep)
+    check("final_state", host(fin), f["final_state"], tol, rep)
+    for k in ("dx", "ddt", "dA", "dB", "dC", "dD", "dinit_state"):
+        check(k, host(g[k]), go[k], tol, rep)
+    print("packed errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+    # row 1 starts with a reset: its initial state must not matter at all
+    if Bt > 1:
+        assert float(g["dinit_state"][1].abs().max()) <= 1e-30
+    # the recurrent step honours the flags too
+    state = dv["init_state"].clone()
+    yd = pk.ssd_decode(dv["x"][:, :70].contiguous(), dv["dt"][:, :70].contiguous(), dv["A"], dv["B"][:, :70].contiguous(),
+                       dv["C"][:, :70].contiguous(), dv["D"], state, seq_reset=rdev[:, :70].contiguous())
+    torch.cuda.synchronize()
+    check("y (decode)", host(yd), f["y"][:, :70], tol)
