@@ -234,3 +234,45 @@ def test_packed_sequences(case):
                        dv["C"][:, :70].contiguous(), dv["D"], state, seq_reset=rdev[:, :70].contiguous())
     torch.cuda.synchronize()
     check("y (decode)", host(yd), f["y"][:, :70], tol)
+
+
+def test_forward_and_backward_can_be_captured_in_a_graph():
+    """The calls enqueue only kernels and event record/wait pairs (no memset, no allocation, no host
+    synchronisation), on the caller's stream and on the library's own streams forked from it: a stream
+    capture therefore records them all.  Replays, with eager work in between, must reproduce the eager
+    results bit for bit."""
+    d = small_inputs(19, "bf16", 1, 2048, 4, 64, 1, 128)       # four segments of 512: several in flight
+    dv = dev_inputs(d, "bf16")
+    Q, seg = 256, 512
+    shape = pk.make_shape(dv["x"], dv["B"], Q, seg)
+    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False), dtype=torch.uint8, device="cuda")
+    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True), dtype=torch.uint8, device="cuda")
+    of = {"y": torch.empty_like(dv["x"]), "final_state": torch.empty((1, 4, 64, 128), device="cuda"),
+          "boundary_states": torch.empty((1, 4, 4, 64, 128), device="cuda")}
+    ob = {"dx": torch.empty_like(dv["x"]), "ddt": torch.empty_like(dv["dt"]), "dB": torch.empty_like(dv["B"]),
+          "dC": torch.empty_like(dv["C"]), "dinit_state": torch.empty((1, 4, 64, 128), device="cuda")}
+    dA, dD = torch.empty(4, device="cuda"), torch.empty(4, device="cuda")
+
+    def step():
+        pk.ssd_fwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], Q, seg, dv["init_state"], 0, ws_f, out=of)
+        pk.ssd_bwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], dv["dy"], Q, seg, dv["init_state"],
+                   dv["dfinal_state"], of["boundary_states"], 0, ws_b, dA, dD, out=ob)
+
+    step()                                    # eager: creates the library's streams and events
+    torch.cuda.synchronize()
+    want = {k: v.clone() for k, v in {**of, **ob, "dA": dA, "dD": dD}.items()}
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        for t in list(of.values()) + list(ob.values()) + [dA, dD]:
+            t.zero_()                         # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for k, v in {**of, **ob, "dA": dA, "dD": dD}.items():
+            assert torch.equal(v, want[k]), (rep, k)
