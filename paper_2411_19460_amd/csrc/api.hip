@@ -259,7 +259,7 @@ static TailStage tail_stage(const Dims& d, bool bwd) {
     return t;
 }
 
-// Bytes of the arrays shared by both scratch blocks: the dA / dD partial sums of every chunk.
+// Bytes of the arrays shared by all scratch blocks: the dA / dD partial sums of every chunk.
 static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d.nseg * d.nc * d.H * 4); }
 
 // SSD_MAGC_SERIAL=1 in the environment keeps every segment on the caller's stream (diagnostics: per-kernel
@@ -455,7 +455,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     Pipe* pp = nl > 1 ? pipe_for_current_device() : nullptr;
     if (nl > 1 && !pp) return SSD_ERR_LAUNCH;
 
-    // shared by both scratch blocks: the carried state adjoint and the dA / dD partial sums of every chunk
+    // shared by all scratch blocks: the carried state adjoint and the dA / dD partial sums of every chunk
     float* part_all = (float*)((char*)workspace + nl * block);
     SegParams sps[NPIPE];
     for (int i = 0; i < nl; ++i) {

@@ -1,6 +1,6 @@
 // Matrix-core (MFMA, bf16 in / fp32 accumulate) kernels of the chunked selective scan for gfx950.
-// Shape: P = 64 channels per head, N = 128 states, chunk Q in {64, 128, 256}; wave64, 4 waves per
-// workgroup; every contraction runs on v_mfma_f32_32x32x16_bf16.
+// Shape: P = 64 channels per head, N = 128 states, chunk Q in {64, 128, 256}; wave64; every contraction
+// runs on v_mfma_f32_32x32x16_bf16.
 //
 // Numerical scheme for the decay mask exp(cum_i - cum_j) of the dual form (Sec. 3.1, Eq. 1 unrolled
 // over a chunk).  The chunk is cut into blocks of 64 tokens.  With

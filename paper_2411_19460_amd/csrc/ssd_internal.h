@@ -67,8 +67,8 @@ struct SegParams {
     // per-segment workspace (fp32)
     float* cum;        // [Bt][H][nc][Q]  chunk-local inclusive cumsum of dt*A
     float* dtf;        // [Bt][H][nc][Q]  dt as fp32, head-major
-    float* states;     // [Bt][nc+1][H][P][N]  slot c: state entering chunk c; slot nc: state leaving the segment
-    float* dstates;    // [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
+    float* states;     // generic path only: [Bt][nc+1][H][P][N]  slot c: state entering chunk c; slot nc: state leaving the segment
+    float* dstates;    // generic path only: [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
     float* Gm;         // [Bt][nc][G][Q][Q]    C_i . B_j   (generic path: fp32)
     float* dG;         // generic path: [Bt][nc][G][Q][Q] fp32 head-summed masked dY X^T; MFMA path: [Bt][nc][G][dg_split][Q][Q] bf16 per-slice sums
     float* gterm;      // [Bt][H][nc][Q]  gradient of cum, per token (MFMA path: the part through the entering state)
@@ -84,8 +84,8 @@ struct SegParams {
     // extra scratch of the MFMA path
     float* ein;        // [Bt][H][nc][Q] exp(cum_i - cum at the start of i's 64-token block)
     float* eout;       // [Bt][H][nc][Q] exp(cum at the end of j's 64-token block - cum_j)
-    bf16_t* states_bf;   // [Bt][nc][H][P][N] bf16 copy of the entering states
-    bf16_t* dstates_bf;  // [Bt][nc][H][P][N] bf16 copy of the leaving-state adjoints
+    bf16_t* states_bf;   // [Bt][nc][H][P][N] chunk states, replaced in place by the states entering the chunks (bf16 only)
+    bf16_t* dstates_bf;  // [Bt][nc][H][P][N] local state adjoints, replaced in place by the adjoints of the leaving states
     int dg_split;        // number of head slices whose dG / dB / dC partial sums are kept apart
     int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
     int part_split;      // number of head slices of the dB / dC head sums
@@ -109,7 +109,7 @@ struct SegParams {
     // defaults (chunk0 = 0, nc_total = nc) keep them per segment; defer_param = 1 leaves the final
     // reduction over all chunks to the caller (launch_param_reduce), so segments may run concurrently.
     int chunk0, nc_total, defer_param;
-    // optional cross-stream ordering of the state scans (segments alternate between two streams):
+    // optional cross-stream ordering of the state scans (consecutive segments run on different streams):
     // the scan waits for ev_wait and records ev_record when it has been enqueued
     hipEvent_t ev_wait, ev_record;
 };
