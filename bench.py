@@ -171,6 +171,47 @@ def inference_bench(args, cfg, pk, synth, torch, dev):
     }))
 
 
+def conv_bench(args, cfg, pk, torch, dev):
+    """Causal depthwise convolution (kernel 4) + SiLU of the block in front of the scan: channels =
+    d_inner + 2 G N, one call over the whole sequence, forward then backward.  HBM-bound: the forward
+    reads u and writes out, the backward reads u and dout and writes du (weights and states are noise)."""
+    Bt, L = cfg.batch, cfg.seqlen
+    C = cfg.nheads * cfg.headdim + 2 * cfg.ngroups * cfg.dstate
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed(0) + 7)
+    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    u = torch.randn((Bt, L, C), device=dev, generator=g, dtype=torch.float32).to(td)
+    dout = torch.randn((Bt, L, C), device=dev, generator=g, dtype=torch.float32).to(td)
+    w = torch.randn((C, 4), device=dev, generator=g) * 0.5
+    bias = torch.randn((C,), device=dev, generator=g)
+    st = torch.randn((Bt, 3, C), device=dev, generator=g, dtype=torch.float32).to(td)
+    dso = torch.randn((Bt, 3, C), device=dev, generator=g)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_f = timed(lambda: pk.ssd_conv1d_fwd(u, w, bias, st))
+    ms_b = timed(lambda: pk.ssd_conv1d_bwd(u, w, bias, st, dout, dso))
+    esz = 2 if cfg.dtype == "bf16" else 4
+    by_f, by_b = 2 * Bt * L * C * esz, 3 * Bt * L * C * esz
+    print(json.dumps({
+        "metric": "block conv1d+SiLU fwd+bwd tokens/sec/layer", "value": Bt * L / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + "_conv1d", "batch": Bt, "seqlen": L, "channels": C},
+        "roofline": {"bound": "hbm", "achieved": (by_f + by_b) / ((ms_f + ms_b) * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (by_f + by_b) / ((ms_f + ms_b) * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "forward": {"ms": ms_f, "GB/s": by_f / (ms_f * 1e-3) / 1e9}, "backward": {"ms": ms_b, "GB/s": by_b / (ms_b * 1e-3) / 1e9}},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -183,6 +224,9 @@ def main():
     ap.add_argument("--inference", action="store_true",
                     help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
                          "token-by-token recurrent step (us per token) at the same layer shape")
+    ap.add_argument("--conv", action="store_true",
+                    help="instead of the scan: the block's causal depthwise convolution + SiLU (forward and backward) at the "
+                         "2.7B block's width, against the HBM roofline")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -217,6 +261,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.inference:
         inference_bench(args, cfg, pk, synth, torch, dev)
+        return
+    if args.conv:
+        conv_bench(args, cfg, pk, torch, dev)
         return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0

@@ -138,6 +138,37 @@ int ssd_decode(const ssd_shape_t* shape, const void* x, const void* dt, const fl
                const void* C, const float* D, float* state, void* y, uint32_t flags, void* hip_stream);
 
 /*
+ * The block's causal depthwise convolution (kernel 4) + bias + SiLU in front of the scan, with the
+ * three-token state that a sequence checkpoint holds next to the SSM state (App. C, Tab. 7: the
+ * per-checkpoint constant is the SSM state plus three tokens of the convolution's channels).  Like the
+ * scan, a segment restarts exactly from its stored state:
+ *     pre[t,c] = bias[c] + sum_{k=0..3} w[c,k] u[t-3+k, c],   u[-3..-1] = state_in (zeros if NULL)
+ *     out[t,c] = pre / (1 + exp(-pre));    state_out = the last three rows of [state_in ; u]
+ *   u, out, dout, du [Bt,L,C] dtype (batch stride overridable, 0 = L*C); w [C,4] fp32; bias [C] fp32 or NULL
+ *   state_in, state_out [Bt,3,C] dtype (oldest row first), either may be NULL
+ * Backward: gradients of <dout, out> + <dstate_out, state_out>.
+ *   dstate_out, dstate_in [Bt,3,C] fp32, either may be NULL; dw [C,4], dbias [C] (may be NULL) fp32,
+ *   overwritten, or added to under SSD_FLAG_ACCUM_PARAM (the only flag); du must not alias dout.
+ *   workspace: ssd_conv1d_workspace_bytes bytes, 256-byte aligned (partial sums of dw and dbias).
+ * All pointers are device pointers; nothing is allocated; work is enqueued on hip_stream.
+ */
+typedef struct ssd_conv_shape_t {
+    int32_t dtype;         /* ssd_dtype_t of u, out, dout, du and the states */
+    int32_t channels;      /* C */
+    int64_t batch;         /* Bt */
+    int64_t seqlen;        /* L >= 0 (an empty segment hands the state on) */
+    int64_t batch_stride;  /* elements between batches of u, out, dout, du (0 = L*C) */
+} ssd_conv_shape_t;
+
+size_t ssd_conv1d_workspace_bytes(const ssd_conv_shape_t* shape);
+int ssd_conv1d_fwd(const ssd_conv_shape_t* shape, const void* u, const float* w, const float* bias,
+                   const void* state_in, void* out, void* state_out, void* hip_stream);
+int ssd_conv1d_bwd(const ssd_conv_shape_t* shape, const void* u, const float* w, const float* bias,
+                   const void* state_in, const void* dout, const float* dstate_out, void* du, float* dw,
+                   float* dbias, float* dstate_in, void* workspace, size_t workspace_bytes, uint32_t flags,
+                   void* hip_stream);
+
+/*
  * Backward (Recompute_Forward + Backward of Alg. 2 over every segment, right to left).
  * Gradients of  <dy, y> + <dfinal_state, final_state>.
  *   inputs as in ssd_fwd, plus

@@ -16,7 +16,8 @@ LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
 SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
 
-EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode", "magc_stack_workspace_bytes", "magc_stack_fwd",
+EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
+           "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -26,6 +27,11 @@ class ssd_shape_t(ctypes.Structure):
                 ("batch", ctypes.c_int64), ("seqlen", ctypes.c_int64), ("segment", ctypes.c_int64),
                 ("x_batch_stride", ctypes.c_int64), ("dt_batch_stride", ctypes.c_int64),
                 ("bc_batch_stride", ctypes.c_int64), ("seq_reset", ctypes.c_void_p)]
+
+
+class ssd_conv_shape_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("channels", ctypes.c_int32), ("batch", ctypes.c_int64),
+                ("seqlen", ctypes.c_int64), ("batch_stride", ctypes.c_int64)]
 
 
 class magc_model_t(ctypes.Structure):
@@ -67,6 +73,13 @@ def lib():
         L.ssd_fwd.argtypes = [shp] + [vp] * 10 + [vp, sz, u32, vp]
         L.ssd_bwd.restype = ctypes.c_int
         L.ssd_bwd.argtypes = [shp] + [vp] * 17 + [vp, sz, u32, vp]
+        cshp = ctypes.POINTER(ssd_conv_shape_t)
+        L.ssd_conv1d_workspace_bytes.restype = sz
+        L.ssd_conv1d_workspace_bytes.argtypes = [cshp]
+        L.ssd_conv1d_fwd.restype = ctypes.c_int
+        L.ssd_conv1d_fwd.argtypes = [cshp] + [vp] * 6 + [vp]
+        L.ssd_conv1d_bwd.restype = ctypes.c_int
+        L.ssd_conv1d_bwd.argtypes = [cshp] + [vp] * 10 + [vp, sz, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -187,6 +200,63 @@ def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None, seq_reset=None):
     if rc != 0:
         raise SSDError(rc, "ssd_decode")
     return y
+
+
+def _conv_shape(u):
+    import torch
+    Bt, L, C = u.shape
+    if u.dtype == torch.bfloat16:
+        dt = SSD_BF16
+    elif u.dtype == torch.float32:
+        dt = SSD_F32
+    else:
+        raise TypeError(f"unsupported dtype {u.dtype}")
+    return ssd_conv_shape_t(dt, C, Bt, L, 0)
+
+
+def _conv_check(u, w, bias, *more):
+    import torch
+    for t in (u,) + tuple(m for m in more if m is not None):
+        if not t.is_cuda or not t.is_contiguous():
+            raise ValueError("tensors must be contiguous device tensors")
+    for t in (w, bias):
+        if t is not None and (t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous()):
+            raise TypeError("w and bias must be contiguous fp32 device tensors")
+
+
+def ssd_conv1d_fwd(u, w, bias=None, state_in=None, want_state=True):
+    """out, state_out = causal depthwise conv (kernel 4) + bias + SiLU of u [Bt,L,C] from state_in [Bt,3,C]."""
+    import torch
+    _conv_check(u, w, bias, state_in)
+    shape = _conv_shape(u)
+    out = torch.empty_like(u)
+    state_out = torch.empty((u.shape[0], 3, u.shape[2]), dtype=u.dtype, device=u.device) if want_state else None
+    rc = lib().ssd_conv1d_fwd(ctypes.byref(shape), _ptr(u), _ptr(w), _ptr(bias), _ptr(state_in), _ptr(out),
+                              _ptr(state_out), _stream(u))
+    if rc != 0:
+        raise SSDError(rc, "ssd_conv1d_fwd")
+    return out, state_out
+
+
+def ssd_conv1d_bwd(u, w, bias, state_in, dout, dstate_out=None, want_dstate=True, flags=0, dw=None, dbias=None):
+    """dict(du, dw, dbias, dstate_in) for the loss <dout, out> + <dstate_out, state_out>."""
+    import torch
+    _conv_check(u, w, bias, state_in, dout, dstate_out)
+    shape = _conv_shape(u)
+    Bt, L, C = u.shape
+    du = torch.empty_like(u)
+    if dw is None:
+        dw = torch.empty((C, 4), dtype=torch.float32, device=u.device)
+    if dbias is None and bias is not None:
+        dbias = torch.empty((C,), dtype=torch.float32, device=u.device)
+    dstate_in = torch.empty((Bt, 3, C), dtype=torch.float32, device=u.device) if want_dstate else None
+    ws = _workspace(int(lib().ssd_conv1d_workspace_bytes(ctypes.byref(shape))), u.device)
+    rc = lib().ssd_conv1d_bwd(ctypes.byref(shape), _ptr(u), _ptr(w), _ptr(bias), _ptr(state_in), _ptr(dout),
+                              _ptr(dstate_out), _ptr(du), _ptr(dw), _ptr(dbias), _ptr(dstate_in), _ptr(ws), ws.numel(),
+                              flags, _stream(u))
+    if rc != 0:
+        raise SSDError(rc, "ssd_conv1d_bwd")
+    return {"du": du, "dw": dw, "dbias": dbias, "dstate_in": dstate_in}
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,
