@@ -220,6 +220,7 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
     ap.add_argument("--segment", type=int, default=0, help="checkpoint interval in tokens (default: the config's)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
+    ap.add_argument("--bf16-checkpoints", action="store_true", help="keep the segment checkpoints in bf16 (half the bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--inference", action="store_true",
                     help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
@@ -267,13 +268,16 @@ def main():
         return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0
+    if args.bf16_checkpoints:
+        flags |= pk.SSD_FLAG_BF16_CHECKPOINTS
+    ck_dtype = torch.bfloat16 if args.bf16_checkpoints else torch.float32
     shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
     Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
     nseg = L // cfg.segment
     ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False, flags), dtype=torch.uint8, device=dev)
     ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True, flags), dtype=torch.uint8, device=dev)
     out_f = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev),
-             "boundary_states": torch.empty((Bt, nseg, H, P, N), device=dev)}
+             "boundary_states": torch.empty((Bt, nseg, H, P, N), dtype=ck_dtype, device=dev)}
     out_b = {"dx": torch.empty_like(d["x"]), "ddt": torch.empty_like(d["dt"]), "dB": torch.empty_like(d["B"]),
              "dC": torch.empty_like(d["C"]), "dinit_state": torch.empty((Bt, H, P, N), device=dev)}
     dA = torch.empty(H, device=dev)
@@ -353,7 +357,7 @@ def main():
                      "achieved_tflops": pfl * tok_s / 1e12, "frac_mfma": pfl * tok_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
 
     full = pk.make_shape(d["x"], d["B"], cfg.chunk, None)
-    state_bytes = Bt * H * P * N * 4
+    state_bytes = Bt * H * P * N * (2 if args.bf16_checkpoints else 4)
     peak_hbm = {
         "magc_bytes": pk.ssd_workspace_bytes(shape, True, flags) + nseg * state_bytes,
         "full_activation_bytes": pk.ssd_workspace_bytes(full, True, flags),
@@ -367,6 +371,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
         "config": {"workload": cfg.name, "batch": Bt, "seqlen": L, "nheads": H, "headdim": P, "dstate": N,
                    "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment,
+                   "checkpoints": "bf16" if args.bf16_checkpoints else "f32",
                    "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma",
                    "segments_in_flight": min(4, nseg) if not args.generic else 1},
         "roofline": roofline, "roofline_path": roofline_path, "kernels_serialized": kernels, "peak_hbm": peak_hbm,

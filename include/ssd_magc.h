@@ -89,7 +89,9 @@ typedef struct ssd_shape_t {
 enum {
     SSD_FLAG_RESIDUAL = 1,        /* fwd: y = x + SSD(x);  bwd: dx = dy + VJP(dy)  (the residual stack's layer) */
     SSD_FLAG_ACCUM_PARAM = 2,     /* bwd: dA, dD are added to instead of overwritten */
-    SSD_FLAG_GENERIC_KERNELS = 4  /* force the shape-generic fp32-FMA kernels even where the MFMA path applies */
+    SSD_FLAG_GENERIC_KERNELS = 4, /* force the shape-generic fp32-FMA kernels even where the MFMA path applies */
+    SSD_FLAG_BF16_CHECKPOINTS = 8 /* boundary_states holds bf16 instead of fp32 elements: half the S-checkpoint
+                                     term of App. C (Tab. 7 counts an fp32 state element as two); see ssd_fwd */
 };
 
 /* Bytes of scratch the call needs for this shape (device memory, 256-byte aligned, contents
@@ -116,10 +118,15 @@ size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, 
  *                   checkpoint is kept, the state travels from segment to segment inside the
  *                   workspace and memory use is independent of L; a later ssd_bwd is then possible
  *                   only with segment >= L.
+ *                   Under SSD_FLAG_BF16_CHECKPOINTS the buffer holds [Bt, nseg, H, P, N] bf16 elements:
+ *                   each checkpoint is the fp32 state rounded once (to nearest even).  The forward
+ *                   pass itself still hands the fp32 state from segment to segment, so y and
+ *                   final_state do not depend on the flag; ssd_bwd, given the same flag, restarts
+ *                   every segment but the first from the rounded state (segment 0 from init_state).
  */
 int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
             const void* C, const float* D, const float* init_state, void* y, float* final_state,
-            float* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+            void* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
             void* hip_stream);
 
 /*
@@ -174,8 +181,9 @@ int ssd_conv1d_bwd(const ssd_conv_shape_t* shape, const void* u, const float* w,
  *   inputs as in ssd_fwd, plus
  *   dy              [Bt,L,H,P] dtype
  *   dfinal_state    [Bt,H,P,N] fp32, or NULL for zeros
- *   boundary_states as written by ssd_fwd with the same shape (read only); may be NULL only if
- *                   segment >= L (then the single segment restarts from init_state)
+ *   boundary_states as written by ssd_fwd with the same shape and the same SSD_FLAG_BF16_CHECKPOINTS
+ *                   (read only); may be NULL only if segment >= L (then the single segment restarts
+ *                   from init_state)
  *   dx [Bt,L,H,P], ddt [Bt,L,H], dB, dC [Bt,L,G,N] dtype, overwritten
  *   dA, dD [H] fp32, overwritten (added to under SSD_FLAG_ACCUM_PARAM)
  *   dinit_state     [Bt,H,P,N] fp32, overwritten; may be NULL
@@ -183,7 +191,7 @@ int ssd_conv1d_bwd(const ssd_conv_shape_t* shape, const void* u, const float* w,
  */
 int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
             const void* C, const float* D, const float* init_state, const void* dy,
-            const float* dfinal_state, const float* boundary_states, void* dx, void* ddt, float* dA,
+            const float* dfinal_state, const void* boundary_states, void* dx, void* ddt, float* dA,
             void* dB, void* dC, float* dD, float* dinit_state, void* workspace,
             size_t workspace_bytes, uint32_t flags, void* hip_stream);
 

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
 
 SSD_F32, SSD_BF16 = 0, 1
-SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS = 1, 2, 4
+SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16_CHECKPOINTS = 1, 2, 4, 8
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
@@ -152,6 +152,13 @@ def _check_inputs(x, dt, A, Bm, Cm, D, *more):
             raise TypeError("A and D must be contiguous fp32 device tensors")
 
 
+def _check_boundary(bnd, flags):
+    import torch
+    want = torch.bfloat16 if flags & SSD_FLAG_BF16_CHECKPOINTS else torch.float32
+    if bnd is not None and bnd.dtype != want:
+        raise TypeError(f"boundary_states must be {want} for these flags")
+
+
 def _workspace(nbytes: int, device):
     import torch
     return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=device)
@@ -175,7 +182,9 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     nseg = -(-L // shape.segment) if L > 0 and shape.segment > 0 else 1
     bnd = out.get("boundary_states")
     if bnd is None and segment is not None and want_boundary:
-        bnd = torch.empty((Bt, nseg, H, P, N), dtype=torch.float32, device=x.device)
+        ck = torch.bfloat16 if flags & SSD_FLAG_BF16_CHECKPOINTS else torch.float32
+        bnd = torch.empty((Bt, nseg, H, P, N), dtype=ck, device=x.device)
+    _check_boundary(bnd, flags)
     need = ssd_workspace_bytes(shape, False, flags)
     if workspace is None:
         workspace = _workspace(need, x.device)
@@ -280,6 +289,7 @@ def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_
     dinit = out.get("dinit_state")
     if dinit is None and want_dinit:
         dinit = torch.empty((Bt, H, P, N), dtype=torch.float32, device=x.device)
+    _check_boundary(boundary_states, flags)
     need = ssd_workspace_bytes(shape, True, flags)
     if workspace is None:
         workspace = _workspace(need, x.device)

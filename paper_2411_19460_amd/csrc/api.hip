@@ -169,6 +169,9 @@ static void wire_states(SegParams& sp, const Dims& d, int64_t k, const float* in
     sp.bnd_write = nullptr;
     sp.state_out = nullptr;
     sp.state_out2 = nullptr;
+    sp.state_in16 = nullptr;
+    sp.bnd_write16 = nullptr;
+    sp.state_out16 = nullptr;
     if (bnd_rw) {
         if (k == 0) {
             sp.bnd_write = bnd_rw;
@@ -315,12 +318,16 @@ extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backw
 
 extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
                        const void* C, const float* D, const float* init_state, void* y, float* final_state,
-                       float* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+                       void* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
                        void* hip_stream) {
     Dims d;
     int rc = check_shape(shape, &d);
     if (rc != SSD_OK) return rc;
-    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM)) return SSD_ERR_ARG;
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS))
+        return SSD_ERR_ARG;
+    const bool ck16 = (flags & SSD_FLAG_BF16_CHECKPOINTS) && boundary_states;
+    float* bnd32 = ck16 ? nullptr : (float*)boundary_states;
+    bf16_t* bnd16 = ck16 ? (bf16_t*)boundary_states : nullptr;
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t HPN = (size_t)d.H * d.P * d.N;
     if (d.L == 0) {  // empty sequence: the state passes through untouched
@@ -394,8 +401,18 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
             sp.reset = d.reset ? (const uint8_t*)(stage + ts.reset) : nullptr;
             sp.reset_bs = T;
         }
-        wire_states(sp, d, k, init_state, boundary_states, boundary_states, final_state);
-        if (!boundary_states && d.nseg > 1) {  // no checkpoints kept: hand the state on through the carry buffers
+        wire_states(sp, d, k, init_state, bnd32, bnd32, final_state);
+        if (bnd16) {  // bf16 checkpoints: rounded copies; the fp32 state itself travels through the carry buffers
+            if (k == 0) {
+                sp.bnd_write16 = bnd16;
+                sp.bnd_write_bs = d.nseg * (int64_t)HPN;
+            }
+            if (k + 1 < d.nseg) {
+                sp.state_out16 = bnd16 + (k + 1) * (int64_t)HPN;
+                sp.state_out16_bs = d.nseg * (int64_t)HPN;
+            }
+        }
+        if (!bnd32 && d.nseg > 1) {  // no fp32 checkpoints: hand the state on through the carry buffers
             if (k > 0) {
                 sp.state_in = carry[k & 1];
                 sp.state_in_bs = (int64_t)HPN;
@@ -421,13 +438,15 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
 
 extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
                        const void* C, const float* D, const float* init_state, const void* dy,
-                       const float* dfinal_state, const float* boundary_states, void* dx, void* ddt, float* dA,
+                       const float* dfinal_state, const void* boundary_states, void* dx, void* ddt, float* dA,
                        void* dB, void* dC, float* dD, float* dinit_state, void* workspace, size_t workspace_bytes,
                        uint32_t flags, void* hip_stream) {
     Dims d;
     int rc = check_shape(shape, &d);
     if (rc != SSD_OK) return rc;
-    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM)) return SSD_ERR_ARG;
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS))
+        return SSD_ERR_ARG;
+    const bool ck16 = (flags & SSD_FLAG_BF16_CHECKPOINTS) && boundary_states;
     if (!dA || !dD) return SSD_ERR_NULL;
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t HPN = (size_t)d.H * d.P * d.N;
@@ -530,7 +549,12 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
         }
         sp.chunk0 = (int)(k * d.nc);
         // restore: per-chunk entering states of this segment from its checkpoint
-        wire_states(sp, d, k, init_state, boundary_states, nullptr, nullptr);
+        wire_states(sp, d, k, init_state, ck16 ? nullptr : (const float*)boundary_states, nullptr, nullptr);
+        if (ck16 && k > 0) {  // restart from the rounded checkpoint
+            sp.state_in = nullptr;
+            sp.state_in16 = (const bf16_t*)boundary_states + k * (int64_t)HPN;
+            sp.state_in_bs = d.nseg * (int64_t)HPN;
+        }
         sp.ev_wait = sp.ev_record = nullptr;
         e = mfma ? mfma_forward_segment(sp, false, sk) : generic_forward_segment(sp, d.bf16, false, sk);
         if (e == hipSuccess) {

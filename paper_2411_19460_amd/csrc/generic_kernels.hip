@@ -165,7 +165,9 @@ __global__ void k_state_scan_fwd(SegParams sp) {
     if (e >= PN) return;
     const int64_t bh = ((int64_t)h) * PN + e;
     float hc = sp.state_in ? sp.state_in[(int64_t)b * sp.state_in_bs + bh] : 0.f;
+    if (!sp.state_in && sp.state_in16) hc = bf16_to_float(sp.state_in16[(int64_t)b * sp.state_in_bs + bh]);  // bf16 checkpoint
     if (sp.bnd_write) sp.bnd_write[(int64_t)b * sp.bnd_write_bs + bh] = hc;
+    if (sp.bnd_write16) sp.bnd_write16[(int64_t)b * sp.bnd_write_bs + bh] = float_to_bf16(hc);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
     for (int c = 0; c < sp.nc; ++c) {
         const int64_t idx = (((int64_t)b * (sp.nc + 1) + c) * sp.H + h) * PN + e;
@@ -176,6 +178,7 @@ __global__ void k_state_scan_fwd(SegParams sp) {
     sp.states[(((int64_t)b * (sp.nc + 1) + sp.nc) * sp.H + h) * PN + e] = hc;
     if (sp.state_out) sp.state_out[(int64_t)b * sp.state_out_bs + bh] = hc;
     if (sp.state_out2) sp.state_out2[(int64_t)b * sp.state_out2_bs + bh] = hc;
+    if (sp.state_out16) sp.state_out16[(int64_t)b * sp.state_out16_bs + bh] = float_to_bf16(hc);
 }
 
 // Reverse pass over the chunk-state adjoints; also emits the partial sums of <dHnext_c, Hnext_c>.

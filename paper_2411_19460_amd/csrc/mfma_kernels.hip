@@ -196,12 +196,23 @@ __global__ __launch_bounds__(OUTER_THR) void mk_chunk_outer(SegParams sp, int nr
 // Inter-chunk state passing over a segment (four state elements per thread).  The running state is
 // carried in fp32 registers (checkpoints and the final state are stored from them); the state
 // entering each chunk is emitted as the bf16 copy the contraction kernels read, nothing else.
+__device__ __forceinline__ bf16x4 to_bf16x4(const float4 v) {
+    bf16x4 r;
+    r[0] = (__bf16)v.x; r[1] = (__bf16)v.y; r[2] = (__bf16)v.z; r[3] = (__bf16)v.w;
+    return r;
+}
+
 __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
     const int64_t bh = (int64_t)h * PN + e;
     float4 hc = sp.state_in ? *(const float4*)(sp.state_in + (int64_t)b * sp.state_in_bs + bh) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if (!sp.state_in && sp.state_in16) {  // bf16 checkpoint
+        const bf16x4 v = *(const bf16x4*)(sp.state_in16 + (int64_t)b * sp.state_in_bs + bh);
+        hc = make_float4((float)v[0], (float)v[1], (float)v[2], (float)v[3]);
+    }
     if (sp.bnd_write) *(float4*)(sp.bnd_write + (int64_t)b * sp.bnd_write_bs + bh) = hc;
+    if (sp.bnd_write16) *(bf16x4*)(sp.bnd_write16 + (int64_t)b * sp.bnd_write_bs + bh) = to_bf16x4(hc);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
     constexpr int U = 8;  // chunks whose loads are in flight together (the recurrence itself is serial)
     for (int c0 = 0; c0 < sp.nc; c0 += U) {
@@ -219,8 +230,7 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u;
             if (c < sp.nc) {
-                bf16x4 hb;  // the entering state is kept in bf16 only
-                hb[0] = (__bf16)hc.x; hb[1] = (__bf16)hc.y; hb[2] = (__bf16)hc.z; hb[3] = (__bf16)hc.w;
+                const bf16x4 hb = to_bf16x4(hc);  // the entering state is kept in bf16 only
                 *(bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e) = hb;
                 const float a = __expf(av[u]);
                 const float4 s = sv[u];
@@ -230,6 +240,7 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     }
     if (sp.state_out) *(float4*)(sp.state_out + (int64_t)b * sp.state_out_bs + bh) = hc;
     if (sp.state_out2) *(float4*)(sp.state_out2 + (int64_t)b * sp.state_out2_bs + bh) = hc;
+    if (sp.state_out16) *(bf16x4*)(sp.state_out16 + (int64_t)b * sp.state_out16_bs + bh) = to_bf16x4(hc);
 }
 
 // Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-wave partial sums

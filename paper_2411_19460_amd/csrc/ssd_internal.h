@@ -101,6 +101,12 @@ struct SegParams {
     int64_t state_out_bs;
     float* state_out2;       // second copy (final_state when the last segment also has no slot), or NULL
     int64_t state_out2_bs;
+    // bf16 checkpoints: the entering state comes from (state_in16, used when state_in is NULL) or goes to
+    // (bnd_write16, state_out16) a bf16 slot; strides as for their fp32 counterparts
+    const bf16_t* state_in16;
+    bf16_t* bnd_write16;
+    bf16_t* state_out16;
+    int64_t state_out16_bs;
     float* dinit_out;        // bwd: where the adjoint of the entering state goes at segment 0, or NULL
     float* dA;
     float* dD;

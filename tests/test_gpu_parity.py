@@ -236,6 +236,59 @@ def test_packed_sequences(case):
     check("y (decode)", host(yd), f["y"][:, :70], tol)
 
 
+def _oracle_bwd_from_checkpoints(d, segment, ckpt):
+    """The backward sweep of Alg. 2 written out with the oracle: segments right to left, each restarted
+    from the stored checkpoint `ckpt[:, k]` (segment 0 from the initial state), the state adjoint handed
+    to the left."""
+    L = d["x"].shape[1]
+    nseg = L // segment
+    dstate = d.get("dfinal_state")
+    segs = [None] * nseg
+    for k in reversed(range(nseg)):
+        sl = slice(k * segment, (k + 1) * segment)
+        init = d.get("init_state") if k == 0 else ckpt[:, k]
+        segs[k] = ssd_ref.ssd_bwd(d["x"][:, sl], d["dt"][:, sl], d["A"], d["B"][:, sl], d["C"][:, sl], d["D"],
+                                  d["dy"][:, sl], init, dstate)
+        dstate = segs[k]["dinit_state"]
+    out = {k: np.concatenate([g[k] for g in segs], axis=1) for k in ("dx", "ddt", "dB", "dC")}
+    out.update({k: sum(g[k] for g in segs) for k in ("dA", "dD")})
+    out["dinit_state"] = dstate
+    return out
+
+
+@pytest.mark.parametrize("case", [
+    # dtype, Bt, L, H, P, G, N, Q, segment, flags
+    ("f32", 2, 512, 3, 16, 1, 16, 64, 128, 0),                      # shape-generic kernels
+    ("bf16", 1, 2048, 4, 64, 2, 128, 256, 512, 0),                  # matrix-core kernels
+    ("bf16", 1, 1024, 2, 64, 1, 128, 128, 256, pk.SSD_FLAG_GENERIC_KERNELS),
+])
+def test_bf16_checkpoints(case):
+    # App. C: the S-checkpoint may be kept in bf16 (half the bytes).  The forward pass does not change;
+    # the backward pass restarts every segment but the first from the rounded state.
+    dtype, Bt, L, H, P, G, N, Q, seg, fl = case
+    d = small_inputs(17, dtype, Bt, L, H, P, G, N)
+    dv = dev_inputs(d, dtype)
+    y32, fin32, bnd32, g32 = run_gpu(dv, Q, seg, fl)
+    y16, fin16, bnd16, g16 = run_gpu(dv, Q, seg, fl | pk.SSD_FLAG_BF16_CHECKPOINTS)
+    assert bnd16.dtype == torch.bfloat16 and bnd16.shape == bnd32.shape
+    assert torch.equal(y16, y32) and torch.equal(fin16, fin32)
+    assert torch.equal(bnd16, bnd32.to(torch.bfloat16))          # one rounding of the same fp32 state
+    f = ssd_ref.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d.get("init_state"), seg)
+    check("boundary_states", host(bnd16), f["boundary_states"], max(TOL[dtype], 2.0 ** -8))
+    ref = _oracle_bwd_from_checkpoints(d, seg, synth.round_bf16(f["boundary_states"]).astype(np.float64))
+    plain = ssd_ref.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], d.get("init_state"), d.get("dfinal_state"))
+    rep = {}
+    for k in ("dx", "ddt", "dA", "dB", "dC", "dD", "dinit_state"):
+        check(k, host(g16[k]), ref[k], TOL[dtype], rep)
+    print("bf16 checkpoints, error against the segment-wise oracle:", {k: f"{v:.2e}" for k, v in rep.items()})
+    print("distance of that oracle from the exact gradients:",
+          {k: f"{np.max(np.abs(ref[k] - plain[k])) / np.max(np.abs(plain[k])):.2e}" for k in ("dx", "ddt", "dA", "dC", "dinit_state")})
+    # the wrong dtype for the flags is refused before anything is launched
+    with pytest.raises(TypeError):
+        pk.ssd_bwd(dv["x"], dv["dt"], dv["A"], dv["B"], dv["C"], dv["D"], dv["dy"], Q, seg, dv.get("init_state"),
+                   dv.get("dfinal_state"), bnd32, fl | pk.SSD_FLAG_BF16_CHECKPOINTS)
+
+
 def test_forward_and_backward_can_be_captured_in_a_graph():
     """The calls enqueue only kernels and event record/wait pairs (no memset, no allocation, no host
     synchronisation), on the caller's stream and on the library's own streams forked from it: a stream
