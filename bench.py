@@ -212,6 +212,44 @@ def conv_bench(args, cfg, pk, torch, dev):
     }))
 
 
+def norm_bench(args, cfg, pk, torch, dev):
+    """Gated RMS normalisation of the block behind the scan: d_inner channels, one call over the whole
+    sequence, forward then backward.  HBM-bound: the forward reads y and z and writes out, the backward
+    reads y, z and dout and writes dy and dz."""
+    T = cfg.batch * cfg.seqlen
+    C = cfg.nheads * cfg.headdim
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed(0) + 11)
+    td = torch.bfloat16 if cfg.dtype == "bf16" else torch.float32
+    y, z, dout = (torch.randn((T, C), device=dev, generator=g, dtype=torch.float32).to(td) for _ in range(3))
+    w = 1.0 + 0.3 * torch.randn((C,), device=dev, generator=g)
+    dy, dz, dw = torch.empty_like(y), torch.empty_like(z), torch.empty_like(w)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_f = timed(lambda: pk.ssd_gated_norm_fwd(y, z, w, 1e-5, cfg.ngroups))
+    ms_b = timed(lambda: pk.ssd_gated_norm_bwd(y, z, w, dout, 1e-5, cfg.ngroups, dy=dy, dz=dz, dw=dw))
+    esz = 2 if cfg.dtype == "bf16" else 4
+    by_f, by_b = 3 * T * C * esz, 5 * T * C * esz
+    print(json.dumps({
+        "metric": "block gated RMSNorm fwd+bwd tokens/sec/layer", "value": T / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": cfg.dtype, "data": "synthetic",
+        "config": {"workload": cfg.name + "_gated_norm", "rows": T, "dim": C, "ngroups": cfg.ngroups},
+        "roofline": {"bound": "hbm", "achieved": (by_f + by_b) / ((ms_f + ms_b) * 1e-3) / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": (by_f + by_b) / ((ms_f + ms_b) * 1e-3) / 1e9 / HBM_PEAK_GBS, "traffic": None,
+                     "forward": {"ms": ms_f, "GB/s": by_f / (ms_f * 1e-3) / 1e9}, "backward": {"ms": ms_b, "GB/s": by_b / (ms_b * 1e-3) / 1e9}},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -228,6 +266,8 @@ def main():
     ap.add_argument("--conv", action="store_true",
                     help="instead of the scan: the block's causal depthwise convolution + SiLU (forward and backward) at the "
                          "2.7B block's width, against the HBM roofline")
+    ap.add_argument("--norm", action="store_true",
+                    help="time the block's gated RMS normalisation (forward + backward) at the config's width instead")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -265,6 +305,9 @@ def main():
         return
     if args.conv:
         conv_bench(args, cfg, pk, torch, dev)
+        return
+    if args.norm:
+        norm_bench(args, cfg, pk, torch, dev)
         return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0

@@ -176,6 +176,40 @@ int ssd_conv1d_bwd(const ssd_conv_shape_t* shape, const void* u, const float* w,
                    void* hip_stream);
 
 /*
+ * Gated RMS normalisation of the block (between the SSD output and the output projection of the
+ * Mamba-2 backbone of Sec. 3.1), token by token:
+ *     g = y * z * sigmoid(z);   out[t,c] = g[t,c] / sqrt(mean over c's group of g[t,.]^2 + eps) * w[c]
+ * The channels form `ngroups` contiguous groups of dim / ngroups channels, each normalised on its own.
+ * y and z are what a grid cell keeps per token (App. C, Tab. 7: C_grid = the input projection's
+ * output, which holds z, plus the d_inner values of y); the backward call recomputes the rest from them.
+ *   y, z   [rows, dim] dtype, rows `y_row_stride` / `z_row_stride` elements apart (0 = dense): z may
+ *          be a column slice of the input projection's output
+ *   w      [dim] fp32                     out, dout [rows, dim] dtype, dense
+ *   dy, dz as y and z (same strides), overwritten;  dw [dim] fp32, overwritten, or added to under
+ *          SSD_FLAG_ACCUM_PARAM (the only flag)
+ *   workspace: ssd_gated_norm_workspace_bytes(shape) bytes of device scratch, 256-byte aligned
+ *          (partial sums of dw; backward only)
+ * Tokens are independent: a segment of the sequence is a row range, no state is carried.  Inputs and
+ * outputs must not overlap.  rows == 0 is allowed.
+ * Errors: SSD_ERR_NULL, SSD_ERR_DTYPE, SSD_ERR_SHAPE (sizes, strides below dim), SSD_ERR_DIVISIBILITY
+ * (dim % ngroups), SSD_ERR_ARG (negative eps, unknown flag), SSD_ERR_WORKSPACE, SSD_ERR_LAUNCH.
+ */
+typedef struct {
+    int32_t dtype;   /* ssd_dtype_t of y, z, out and their gradients */
+    int32_t dim;     /* channels (d_inner) */
+    int32_t ngroups; /* normalisation groups */
+    float eps;
+    int64_t rows;    /* tokens, batch folded in */
+    int64_t y_row_stride, z_row_stride;
+} ssd_norm_shape_t;
+size_t ssd_gated_norm_workspace_bytes(const ssd_norm_shape_t* shape);
+int ssd_gated_norm_fwd(const ssd_norm_shape_t* shape, const void* y, const void* z, const float* w, void* out,
+                       void* hip_stream);
+int ssd_gated_norm_bwd(const ssd_norm_shape_t* shape, const void* y, const void* z, const float* w,
+                       const void* dout, void* dy, void* dz, float* dw, void* workspace, size_t workspace_bytes,
+                       uint32_t flags, void* hip_stream);
+
+/*
  * Backward (Recompute_Forward + Backward of Alg. 2 over every segment, right to left).
  * Gradients of  <dy, y> + <dfinal_state, final_state>.
  *   inputs as in ssd_fwd, plus

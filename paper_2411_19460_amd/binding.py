@@ -17,7 +17,8 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16_CHECKPOINTS = 1, 2, 4, 8
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
-           "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
+           "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -32,6 +33,11 @@ class ssd_shape_t(ctypes.Structure):
 class ssd_conv_shape_t(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("channels", ctypes.c_int32), ("batch", ctypes.c_int64),
                 ("seqlen", ctypes.c_int64), ("batch_stride", ctypes.c_int64)]
+
+
+class ssd_norm_shape_t(ctypes.Structure):
+    _fields_ = [("dtype", ctypes.c_int32), ("dim", ctypes.c_int32), ("ngroups", ctypes.c_int32), ("eps", ctypes.c_float),
+                ("rows", ctypes.c_int64), ("y_row_stride", ctypes.c_int64), ("z_row_stride", ctypes.c_int64)]
 
 
 class magc_model_t(ctypes.Structure):
@@ -80,6 +86,13 @@ def lib():
         L.ssd_conv1d_fwd.argtypes = [cshp] + [vp] * 6 + [vp]
         L.ssd_conv1d_bwd.restype = ctypes.c_int
         L.ssd_conv1d_bwd.argtypes = [cshp] + [vp] * 10 + [vp, sz, u32, vp]
+        nshp = ctypes.POINTER(ssd_norm_shape_t)
+        L.ssd_gated_norm_workspace_bytes.restype = sz
+        L.ssd_gated_norm_workspace_bytes.argtypes = [nshp]
+        L.ssd_gated_norm_fwd.restype = ctypes.c_int
+        L.ssd_gated_norm_fwd.argtypes = [nshp] + [vp] * 4 + [vp]
+        L.ssd_gated_norm_bwd.restype = ctypes.c_int
+        L.ssd_gated_norm_bwd.argtypes = [nshp] + [vp] * 7 + [vp, sz, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -266,6 +279,61 @@ def ssd_conv1d_bwd(u, w, bias, state_in, dout, dstate_out=None, want_dstate=True
     if rc != 0:
         raise SSDError(rc, "ssd_conv1d_bwd")
     return {"du": du, "dw": dw, "dbias": dbias, "dstate_in": dstate_in}
+
+
+def _norm_shape(y, z, ngroups, eps, *same_as):
+    """y, z: [rows, dim] with unit stride along dim (rows may be a column slice of a wider tensor)."""
+    import torch
+    for t in (y, z):
+        if t.dim() != 2 or not t.is_cuda or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape != y.shape or t.dtype != y.dtype:
+            raise ValueError("y and z must be [rows, dim] device tensors of one dtype with unit stride along dim")
+    for t, like in same_as:
+        if t.shape != like.shape or t.stride() != like.stride() or t.dtype != like.dtype or not t.is_cuda:
+            raise ValueError("gradient tensors must match the layout of what they are gradients of")
+    dt = SSD_BF16 if y.dtype == torch.bfloat16 else SSD_F32
+    if dt == SSD_F32 and y.dtype != torch.float32:
+        raise TypeError("dtype must be float32 or bfloat16")
+    T, C = y.shape
+    return ssd_norm_shape_t(dt, C, ngroups, eps, T, y.stride(0) if T > 1 else C, z.stride(0) if T > 1 else C)
+
+
+def _norm_weight(w, C):
+    import torch
+    if w.dtype != torch.float32 or not w.is_cuda or not w.is_contiguous() or w.numel() != C:
+        raise TypeError("w must be a contiguous fp32 device tensor of dim elements")
+
+
+def ssd_gated_norm_fwd(y, z, w, eps=1e-5, ngroups=1):
+    """out = RMSNorm_groups(y * silu(z)) * w for y, z [rows, dim]; out is dense."""
+    import torch
+    shape = _norm_shape(y, z, ngroups, eps)
+    _norm_weight(w, y.shape[1])
+    out = torch.empty(y.shape, dtype=y.dtype, device=y.device)
+    rc = lib().ssd_gated_norm_fwd(ctypes.byref(shape), _ptr(y), _ptr(z), _ptr(w), _ptr(out), _stream(y))
+    if rc != 0:
+        raise SSDError(rc, "ssd_gated_norm_fwd")
+    return out
+
+
+def ssd_gated_norm_bwd(y, z, w, dout, eps=1e-5, ngroups=1, flags=0, dy=None, dz=None, dw=None):
+    """dict(dy, dz, dw) for the loss <dout, out>.  dy / dz may be given (laid out as y / z, e.g. column slices)."""
+    import torch
+    if dy is None:
+        dy = torch.empty_strided(y.shape, y.stride(), dtype=y.dtype, device=y.device)
+    if dz is None:
+        dz = torch.empty_strided(z.shape, z.stride(), dtype=z.dtype, device=z.device)
+    shape = _norm_shape(y, z, ngroups, eps, (dy, y), (dz, z))
+    _norm_weight(w, y.shape[1])
+    if not dout.is_cuda or not dout.is_contiguous() or dout.shape != y.shape or dout.dtype != y.dtype:
+        raise ValueError("dout must be a dense [rows, dim] device tensor of y's dtype")
+    if dw is None:
+        dw = torch.empty((y.shape[1],), dtype=torch.float32, device=y.device)
+    ws = _workspace(int(lib().ssd_gated_norm_workspace_bytes(ctypes.byref(shape))), y.device)
+    rc = lib().ssd_gated_norm_bwd(ctypes.byref(shape), _ptr(y), _ptr(z), _ptr(w), _ptr(dout), _ptr(dy), _ptr(dz), _ptr(dw),
+                                  _ptr(ws), ws.numel(), flags, _stream(y))
+    if rc != 0:
+        raise SSDError(rc, "ssd_gated_norm_bwd")
+    return {"dy": dy, "dz": dz, "dw": dw}
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,

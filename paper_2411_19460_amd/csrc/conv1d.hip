@@ -71,10 +71,13 @@ struct Vec<bf16_t, 8> {
     }
 };
 
-__device__ __forceinline__ float silu(float z) { return z / (1.f + __expf(-z)); }
+// sigmoid through the hardware reciprocal (1 ulp) instead of an IEEE division: the kernels here are close
+// enough to the VALU limit for the ten extra instructions per element to show
+__device__ __forceinline__ float sigmoid_fast(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
+__device__ __forceinline__ float silu(float z) { return z * sigmoid_fast(z); }
 // d silu / dz = s (1 + z (1 - s)), s = sigmoid(z)
 __device__ __forceinline__ float dsilu(float z) {
-    const float s = 1.f / (1.f + __expf(-z));
+    const float s = sigmoid_fast(z);
     return s * (1.f + z * (1.f - s));
 }
 
