@@ -250,6 +250,54 @@ def norm_bench(args, cfg, pk, torch, dev):
     }))
 
 
+def linear_bench(args, cfg, pk, torch, dev):
+    """The block's two projections at the config's width (d_model = d_inner / 2; the input projection
+    widens to 2 d_inner + 2 G N + H, the output projection maps d_inner back), forward, input gradient
+    and weight gradient over the whole sequence.  Dense contractions: priced against the bf16 matrix-core peak."""
+    T = cfg.batch * cfg.seqlen
+    d_inner = cfg.nheads * cfg.headdim
+    d_model = d_inner // 2
+    d_in_proj = 2 * d_inner + 2 * cfg.ngroups * cfg.dstate + cfg.nheads
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed(0) + 13)
+    rnd = lambda *s: torch.randn(s, device=dev, generator=g, dtype=torch.float32).to(torch.bfloat16)
+    res = {}
+    total_ms, total_flop = 0.0, 0.0
+    for name, I, O in (("in_proj", d_model, d_in_proj), ("out_proj", d_inner, d_model)):
+        x, w, dout = rnd(T, I), (rnd(O, I).float() / I ** 0.5).to(torch.bfloat16), rnd(T, O)
+        out, dx, dw = torch.empty_like(dout), torch.empty_like(x), torch.empty((O, I), device=dev)
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / args.steps
+
+        ms_f = timed(lambda: pk.ssd_linear_fwd(x, w, out))
+        ms_dx = timed(lambda: pk.ssd_linear_bwd(x, w, dout, want_dw=False, dx=dx))
+        ms_dw = timed(lambda: pk.ssd_linear_bwd(x, w, dout, want_dx=False, dw=dw))
+        fl = 2.0 * T * I * O
+        res[name] = {"in_dim": I, "out_dim": O, "forward": {"ms": ms_f, "TFLOP/s": fl / (ms_f * 1e-3) / 1e12},
+                     "dx": {"ms": ms_dx, "TFLOP/s": fl / (ms_dx * 1e-3) / 1e12},
+                     "dw": {"ms": ms_dw, "TFLOP/s": fl / (ms_dw * 1e-3) / 1e12}}
+        total_ms += ms_f + ms_dx + ms_dw
+        total_flop += 3 * fl
+        del x, w, dout, out, dx, dw
+    ach = total_flop / (total_ms * 1e-3) / 1e12
+    print(json.dumps({
+        "metric": "block projections fwd+bwd tokens/sec/layer", "value": T / (total_ms * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": total_ms, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name + "_projections", "rows": T, "d_model": d_model, "d_in_proj": d_in_proj, "d_inner": d_inner},
+        "roofline": {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                     "frac": ach / MFMA_BF16_PEAK_TFLOPS, "traffic": None, **res},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -268,6 +316,8 @@ def main():
                          "2.7B block's width, against the HBM roofline")
     ap.add_argument("--norm", action="store_true",
                     help="time the block's gated RMS normalisation (forward + backward) at the config's width instead")
+    ap.add_argument("--linear", action="store_true",
+                    help="time the block's input and output projections (forward, input and weight gradients) instead")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -308,6 +358,9 @@ def main():
         return
     if args.norm:
         norm_bench(args, cfg, pk, torch, dev)
+        return
+    if args.linear:
+        linear_bench(args, cfg, pk, torch, dev)
         return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0

@@ -210,6 +210,27 @@ int ssd_gated_norm_bwd(const ssd_norm_shape_t* shape, const void* y, const void*
                        uint32_t flags, void* hip_stream);
 
 /*
+ * The block's projections (dense layers without bias in the Mamba-2 backbone of Sec. 3.1: the input
+ * projection, whose output width is the larger part of C_grid in App. C, Tab. 7, and the output
+ * projection), bf16 storage, fp32 accumulation on the matrix cores:
+ *     out[t,o] = sum_i x[t,i] w[o,i]
+ *     dx[t,i]  = sum_o dout[t,o] w[o,i]        dw[o,i] = sum_t dout[t,o] x[t,i]
+ *   x    [rows, in_dim] bf16, rows x_row_stride elements apart (0 = dense); likewise out / dout
+ *        [rows, out_dim] and dx [rows, in_dim] with their strides: any of them may be a column slice
+ *   w    [out_dim, in_dim] bf16, dense         dw [out_dim, in_dim] fp32, dense, overwritten or added
+ *        to under SSD_FLAG_ACCUM_PARAM (the only flag)
+ *   dx or dw may be NULL (that product is skipped; w resp. x may then be NULL too).
+ * in_dim, out_dim and the strides must be multiples of 8, all pointers 16-byte aligned (SSD_ERR_ARG);
+ * rows is arbitrary (rows == 0: dw is zeroed or left).  No workspace.  Tokens are independent: a segment
+ * is a row range.  Errors: SSD_ERR_NULL, SSD_ERR_SHAPE, SSD_ERR_DIVISIBILITY, SSD_ERR_ARG, SSD_ERR_LAUNCH.
+ */
+int ssd_linear_fwd(int64_t rows, int32_t in_dim, int32_t out_dim, const void* x, int64_t x_row_stride,
+                   const void* w, void* out, int64_t out_row_stride, void* hip_stream);
+int ssd_linear_bwd(int64_t rows, int32_t in_dim, int32_t out_dim, const void* x, int64_t x_row_stride,
+                   const void* w, const void* dout, int64_t dout_row_stride, void* dx, int64_t dx_row_stride,
+                   float* dw, uint32_t flags, void* hip_stream);
+
+/*
  * Backward (Recompute_Forward + Backward of Alg. 2 over every segment, right to left).
  * Gradients of  <dy, y> + <dfinal_state, final_state>.
  *   inputs as in ssd_fwd, plus

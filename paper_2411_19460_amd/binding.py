@@ -18,7 +18,7 @@ SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
-           "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -93,6 +93,11 @@ def lib():
         L.ssd_gated_norm_fwd.argtypes = [nshp] + [vp] * 4 + [vp]
         L.ssd_gated_norm_bwd.restype = ctypes.c_int
         L.ssd_gated_norm_bwd.argtypes = [nshp] + [vp] * 7 + [vp, sz, u32, vp]
+        i64 = ctypes.c_int64
+        L.ssd_linear_fwd.restype = ctypes.c_int
+        L.ssd_linear_fwd.argtypes = [i64, i32, i32, vp, i64, vp, vp, i64, vp]
+        L.ssd_linear_bwd.restype = ctypes.c_int
+        L.ssd_linear_bwd.argtypes = [i64, i32, i32, vp, i64, vp, vp, i64, vp, i64, vp, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -334,6 +339,53 @@ def ssd_gated_norm_bwd(y, z, w, dout, eps=1e-5, ngroups=1, flags=0, dy=None, dz=
     if rc != 0:
         raise SSDError(rc, "ssd_gated_norm_bwd")
     return {"dy": dy, "dz": dz, "dw": dw}
+
+
+def _rows_view(t, name):
+    import torch
+    if t.dim() != 2 or not t.is_cuda or t.dtype != torch.bfloat16 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{name} must be a [rows, dim] bf16 device tensor with unit stride along dim")
+    return t.stride(0) if t.shape[0] > 1 else t.shape[1]
+
+
+def ssd_linear_fwd(x, w, out=None):
+    """out [rows, out_dim] = x [rows, in_dim] @ w[out_dim, in_dim]^T (bf16, fp32 accumulation)."""
+    import torch
+    ldx = _rows_view(x, "x")
+    if w.dim() != 2 or not w.is_cuda or w.dtype != torch.bfloat16 or not w.is_contiguous() or w.shape[1] != x.shape[1]:
+        raise ValueError("w must be a dense [out_dim, in_dim] bf16 device tensor")
+    if out is None:
+        out = torch.empty((x.shape[0], w.shape[0]), dtype=torch.bfloat16, device=x.device)
+    ldo = _rows_view(out, "out")
+    if out.shape != (x.shape[0], w.shape[0]):
+        raise ValueError("out must be [rows, out_dim]")
+    rc = lib().ssd_linear_fwd(x.shape[0], x.shape[1], w.shape[0], _ptr(x), ldx, _ptr(w), _ptr(out), ldo, _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_linear_fwd")
+    return out
+
+
+def ssd_linear_bwd(x, w, dout, want_dx=True, want_dw=True, flags=0, dx=None, dw=None):
+    """dict(dx, dw) for the loss <dout, out>; dw is fp32 [out_dim, in_dim]."""
+    import torch
+    ldx = _rows_view(x, "x")
+    ldd = _rows_view(dout, "dout")
+    rows, in_dim = x.shape
+    out_dim = w.shape[0]
+    if w.dtype != torch.bfloat16 or not w.is_contiguous() or w.shape != (out_dim, in_dim) or dout.shape != (rows, out_dim):
+        raise ValueError("w must be dense bf16 [out_dim, in_dim] and dout [rows, out_dim]")
+    if dx is None and want_dx:
+        dx = torch.empty((rows, in_dim), dtype=torch.bfloat16, device=x.device)
+    lddx = _rows_view(dx, "dx") if dx is not None else 0
+    if dw is None and want_dw:
+        dw = torch.empty((out_dim, in_dim), dtype=torch.float32, device=x.device)
+    if dw is not None and (dw.dtype != torch.float32 or not dw.is_contiguous() or dw.shape != (out_dim, in_dim)):
+        raise ValueError("dw must be a dense fp32 [out_dim, in_dim] device tensor")
+    rc = lib().ssd_linear_bwd(rows, in_dim, out_dim, _ptr(x), ldx, _ptr(w), _ptr(dout), ldd, _ptr(dx), lddx, _ptr(dw), flags,
+                              _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_linear_bwd")
+    return {"dx": dx, "dw": dw}
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,
