@@ -13,6 +13,7 @@
 // registers): 6 operand reads per 8 MFMAs keeps the LDS below its bandwidth.  The next K step's global
 // loads are in flight while the current one is multiplied.  Workgroup ids are remapped so that each XCD
 // works on a compact block of the tile grid (its L2 then holds the A and B panels that block shares).
+#include <stdlib.h>
 #include <string.h>
 
 #include "mfma_common.h"
@@ -22,10 +23,8 @@ namespace {
 
 using namespace mf;
 
-constexpr int BM = 256, BN = 128, BKK = 64;
+constexpr int BKK = 64;            // K step
 constexpr int KPITCH = 144;        // bytes per LDS row of a k-major tile: 64 k (128 bytes) + 16 pad
-constexpr int APITCH_T = 2 * BM + 16;  // bytes per LDS row (one k) of a tile stored [k][m]
-constexpr int BPITCH_T = 2 * BN + 16;
 
 struct GemmParams {
     const bf16_t* A;
@@ -53,39 +52,56 @@ __device__ __forceinline__ void tile_of(const GemmParams& gp, int& tm, int& tn) 
     tn = in / gsz;
 }
 
-// Global -> registers for one K step of one operand.  ROWS = tile extent along the operand's own index (m
-// or n).  k-major: ROWS rows of 8 vectors; otherwise 64 k-rows of ROWS / 8 vectors.  Out-of-range vectors
-// are zeros (all extents are multiples of 8, so a vector is inside or outside as a whole).
+// bytes of one operand tile in LDS: k-major [ROWS][64 k] (rows padded by 16 bytes) or [64 k][ROWS] (by 64)
 template <int ROWS, bool KMAJOR>
-__device__ __forceinline__ void load_tile(const bf16_t* base, int64_t ld, int r0, int rmax, int k0, int kmax, int tid,
+constexpr int tile_bytes() { return KMAJOR ? ROWS * KPITCH : BKK * (2 * ROWS + 64); }
+// Row pitch of a tile stored [k][ROWS]: 64 bytes of padding put consecutive k rows 16 banks apart, so the four
+// k rows (32 bytes each per half-wave) that one transposing read touches fall into distinct banks.
+template <int ROWS>
+constexpr int tpitch() { return 2 * ROWS + 64; }
+
+// Global -> registers for one K step of one operand.  ROWS = tile extent along the operand's own index (m
+// or n).  k-major: ROWS rows of 8 vectors; otherwise 64 k-rows of ROWS / 8 vectors.  `origin` points at the
+// tile's first element of this K step (wave-uniform: scalar registers); a thread's vectors lie a fixed
+// number of rows apart, so one 32-bit byte offset per thread addresses them all.  MASK: vectors outside
+// rows_left x k_left are zeros (all extents are multiples of 8: a vector is inside or outside as a whole).
+template <int ROWS, bool KMAJOR>
+__device__ __forceinline__ uint32_t tile_voff(int64_t ld, int tid) {
+    constexpr int VPR = KMAJOR ? 8 : ROWS / 8;  // vectors per memory row of the tile
+    return (uint32_t)(tid / VPR) * (uint32_t)(ld * 2) + (uint32_t)(tid % VPR) * 16;
+}
+
+template <int ROWS, bool KMAJOR, bool MASK, int I0 = 0, int I1 = ROWS / 32>
+__device__ __forceinline__ void load_tile(const bf16_t* origin, int64_t ld, uint32_t voff, int rows_left, int k_left, int tid,
                                           bf16x8 (&reg)[ROWS / 32]) {
-    bf16x8 zero;
+    constexpr int VPR = KMAJOR ? 8 : ROWS / 8;
+    constexpr int RSTEP = 256 / VPR;  // memory rows between a thread's consecutive vectors
 #pragma unroll
-    for (int e = 0; e < 8; ++e) zero[e] = (__bf16)0.f;
-#pragma unroll
-    for (int i = 0; i < ROWS / 32; ++i) {
-        const int v = tid + 256 * i;
-        if (KMAJOR) {
-            const int row = r0 + (v >> 3), k = k0 + (v & 7) * 8;
-            reg[i] = (row < rmax && k < kmax) ? *(const bf16x8*)(base + (int64_t)row * ld + k) : zero;
+    for (int i = I0; i < I1; ++i) {
+        bool in = true;
+        if (MASK) {
+            const int mrow = tid / VPR + RSTEP * i, mcol = (tid % VPR) * 8;  // memory row / first column of the vector
+            in = KMAJOR ? (mrow < rows_left && mcol < k_left) : (mrow < k_left && mcol < rows_left);
+        }
+        if (in) {
+            reg[i] = *(const bf16x8*)((const char*)origin + (size_t)i * RSTEP * (size_t)(ld * 2) + (size_t)voff);
         } else {
-            constexpr int VPR = ROWS / 8;
-            const int k = k0 + v / VPR, row = r0 + (v % VPR) * 8;
-            reg[i] = (row < rmax && k < kmax) ? *(const bf16x8*)(base + (int64_t)k * ld + row) : zero;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) reg[i][e] = (__bf16)0.f;
         }
     }
 }
 
-template <int ROWS, bool KMAJOR>
+template <int ROWS, bool KMAJOR, int I0 = 0, int I1 = ROWS / 32>
 __device__ __forceinline__ void store_tile(char* lds, int tid, const bf16x8 (&reg)[ROWS / 32]) {
 #pragma unroll
-    for (int i = 0; i < ROWS / 32; ++i) {
+    for (int i = I0; i < I1; ++i) {
         const int v = tid + 256 * i;
         if (KMAJOR) {
             *(bf16x8*)(lds + (v >> 3) * KPITCH + (v & 7) * 16) = reg[i];
         } else {
             constexpr int VPR = ROWS / 8;
-            *(bf16x8*)(lds + (v / VPR) * (2 * ROWS + 16) + (v % VPR) * 16) = reg[i];
+            *(bf16x8*)(lds + (v / VPR) * tpitch<ROWS>() + (v % VPR) * 16) = reg[i];
         }
     }
 }
@@ -94,70 +110,39 @@ __device__ __forceinline__ void store_tile(char* lds, int tid, const bf16x8 (&re
 template <int ROWS, bool KMAJOR>
 __device__ __forceinline__ bf16x8 operand(const char* lds, int r0, int kk, int lane) {
     if (KMAJOR) return *(const bf16x8*)(lds + (r0 + (lane & 31)) * KPITCH + (kk + 8 * (lane >> 5)) * 2);
-    return frag_tr(lds, 2 * ROWS + 16, kk, r0, lane);
+    return frag_tr(lds, tpitch<ROWS>(), kk, r0, lane);
 }
 
-template <bool AK, bool BK>
-__global__ __launch_bounds__(256, 2) void k_gemm(GemmParams gp) {
-    constexpr int A_BYTES = AK ? BM * KPITCH : BKK * APITCH_T;
-    constexpr int B_BYTES = BK ? BN * KPITCH : BKK * BPITCH_T;
-    __shared__ __attribute__((aligned(16))) char lds[A_BYTES + B_BYTES];
-    char* As = lds;
-    char* Bs = lds + A_BYTES;
-    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
-    const int wm = w >> 1, wn = w & 1;
-    int tm, tn;
-    tile_of(gp, tm, tn);
-    const int m0 = tm * BM, n0 = tn * BN;
-
-    f32x16 acc[4][2];
+// The MFMAs are issued with the B operand first, so an accumulator tile holds the transposed product: lane
+// -> row m = lane % 32 of C, registers 4q .. 4q+3 -> the four consecutive columns 8q + 4 (lane / 32) + 0..3.
+// Every lane thus stores 8 bytes (bf16) or 16 bytes (fp32) at a time.  `whole`: the workgroup's tile lies
+// inside C (no bounds checks; N is a multiple of 8, so a group of four columns is inside or outside as one).
+template <int WI, int WJ>
+__device__ __forceinline__ void store_acc(const GemmParams& gp, const f32x16 (&acc)[WI][WJ], int row0, int col0, int lane, bool whole) {
+    const int row_l = row0 + (lane & 31), col_l = col0 + (lane >> 5) * 4;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < WI; ++i) {
+        const int row = row_l + i * 32;
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = zero16();
-
-    bf16x8 ra[BM / 32], rb[BN / 32];
-    load_tile<BM, AK>(gp.A, gp.lda, m0, gp.M, 0, gp.K, tid, ra);
-    load_tile<BN, BK>(gp.B, gp.ldb, n0, gp.N, 0, gp.K, tid, rb);
-    for (int k0 = 0; k0 < gp.K; k0 += BKK) {
-        store_tile<BM, AK>(As, tid, ra);
-        store_tile<BN, BK>(Bs, tid, rb);
-        __syncthreads();
-        if (k0 + BKK < gp.K) {  // next step's loads fly during the products
-            load_tile<BM, AK>(gp.A, gp.lda, m0, gp.M, k0 + BKK, gp.K, tid, ra);
-            load_tile<BN, BK>(gp.B, gp.ldb, n0, gp.N, k0 + BKK, gp.K, tid, rb);
-        }
+        for (int j = 0; j < WJ; ++j) {
 #pragma unroll
-        for (int kk = 0; kk < BKK; kk += 16) {
-            bf16x8 a[4], b[2];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) a[i] = operand<BM, AK>(As, wm * 128 + i * 32, kk, lane);
-#pragma unroll
-            for (int j = 0; j < 2; ++j) b[j] = operand<BN, BK>(Bs, wn * 64 + j * 32, kk, lane);
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int j = 0; j < 2; ++j) acc[i][j] = mfma(a[i], b[j], acc[i][j]);
-        }
-        __syncthreads();
-    }
-
-    // accumulator register r of a lane: row acc_row(r, lane), column lane % 32 of its 32 x 32 tile
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-        for (int j = 0; j < 2; ++j) {
-            const int col = n0 + wn * 64 + j * 32 + (lane & 31);
-#pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int row = m0 + wm * 128 + i * 32 + acc_row(r, lane);
-                if (row < gp.M && col < gp.N) {
+            for (int q = 0; q < 4; ++q) {
+                const int col = col_l + j * 32 + q * 8;
+                if (whole || (row < gp.M && col < gp.N)) {
                     const int64_t o = (int64_t)row * gp.ldc + col;
+                    const f32x16& t = acc[i][j];
                     if (gp.c_f32) {
-                        float* c = (float*)gp.C + o;
-                        *c = gp.accumulate ? *c + acc[i][j][r] : acc[i][j][r];
+                        float4* c = (float4*)((float*)gp.C + o);
+                        float4 v = make_float4(t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]);
+                        if (gp.accumulate) {
+                            const float4 old = *c;
+                            v.x += old.x; v.y += old.y; v.z += old.z; v.w += old.w;
+                        }
+                        *c = v;
                     } else {
-                        ((__bf16*)gp.C)[o] = (__bf16)acc[i][j][r];
+                        bf16x4 v;
+                        v[0] = (__bf16)t[4 * q]; v[1] = (__bf16)t[4 * q + 1]; v[2] = (__bf16)t[4 * q + 2]; v[3] = (__bf16)t[4 * q + 3];
+                        *(bf16x4*)((__bf16*)gp.C + o) = v;
                     }
                 }
             }
@@ -165,22 +150,288 @@ __global__ __launch_bounds__(256, 2) void k_gemm(GemmParams gp) {
     }
 }
 
-bool ok_ptr(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
+// WI x WJ MFMA tiles per wave, 2 x 2 waves: workgroup tile (64 WI) x (64 WJ).  DB: two LDS buffers, one
+// barrier per K step (the tile of step k+1 is written while step k is multiplied); otherwise one buffer
+// and two barriers, for configurations whose registers and LDS leave room for two workgroups per compute unit.
+template <bool AK, bool BK, int WI, int WJ, bool DB>
+__global__ __launch_bounds__(256, DB ? 1 : 2) void k_gemm(GemmParams gp) {
+    constexpr int BM = 64 * WI, BN = 64 * WJ;
+    constexpr int A_BYTES = tile_bytes<BM, AK>(), B_BYTES = tile_bytes<BN, BK>();
+    extern __shared__ __attribute__((aligned(16))) char lds[];  // (DB ? 2 : 1) x (A tile, B tile)
+    const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
+    const int wm = w >> 1, wn = w & 1;
+    int tm, tn;
+    tile_of(gp, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[WI][WJ];
+#pragma unroll
+    for (int i = 0; i < WI; ++i)
+#pragma unroll
+        for (int j = 0; j < WJ; ++j) acc[i][j] = zero16();
+
+    // tiles that lie wholly inside the matrices take the unmasked loads for every whole K step
+    const bool interior = m0 + BM <= gp.M && n0 + BN <= gp.N;
+    const uint32_t va = tile_voff<BM, AK>(gp.lda, tid), vb = tile_voff<BN, BK>(gp.ldb, tid);
+    bf16x8 ra[BM / 32], rb[BN / 32];
+    auto fetch = [&](int k0) {
+        const bf16_t* ao = AK ? gp.A + (int64_t)m0 * gp.lda + k0 : gp.A + (int64_t)k0 * gp.lda + m0;
+        const bf16_t* bo = BK ? gp.B + (int64_t)n0 * gp.ldb + k0 : gp.B + (int64_t)k0 * gp.ldb + n0;
+        if (interior && k0 + BKK <= gp.K) {
+            load_tile<BM, AK, false>(ao, gp.lda, va, 0, 0, tid, ra);
+            load_tile<BN, BK, false>(bo, gp.ldb, vb, 0, 0, tid, rb);
+        } else {
+            load_tile<BM, AK, true>(ao, gp.lda, va, gp.M - m0, gp.K - k0, tid, ra);
+            load_tile<BN, BK, true>(bo, gp.ldb, vb, gp.N - n0, gp.K - k0, tid, rb);
+        }
+    };
+    fetch(0);
+    if (DB) {
+        store_tile<BM, AK>(lds, tid, ra);
+        store_tile<BN, BK>(lds + A_BYTES, tid, rb);
+        __syncthreads();
+    }
+    int cur = 0;
+    for (int k0 = 0; k0 < gp.K; k0 += BKK) {
+        char* As = lds + (DB ? cur * (A_BYTES + B_BYTES) : 0);
+        char* Bs = As + A_BYTES;
+        const bool more = k0 + BKK < gp.K;
+        if (!DB) {
+            store_tile<BM, AK>(As, tid, ra);
+            store_tile<BN, BK>(Bs, tid, rb);
+            __syncthreads();
+        }
+        if (more) fetch(k0 + BKK);  // next step's loads fly during the products
+#pragma unroll
+        for (int kk = 0; kk < BKK; kk += 16) {
+            bf16x8 a[WI], b[WJ];
+#pragma unroll
+            for (int i = 0; i < WI; ++i) a[i] = operand<BM, AK>(As, wm * 32 * WI + i * 32, kk, lane);
+#pragma unroll
+            for (int j = 0; j < WJ; ++j) b[j] = operand<BN, BK>(Bs, wn * 32 * WJ + j * 32, kk, lane);
+#pragma unroll
+            for (int i = 0; i < WI; ++i)
+#pragma unroll
+                for (int j = 0; j < WJ; ++j) acc[i][j] = mfma(b[j], a[i], acc[i][j]);
+        }
+        if (DB) {
+            if (more) {
+                char* An = lds + (cur ^ 1) * (A_BYTES + B_BYTES);
+                store_tile<BM, AK>(An, tid, ra);
+                store_tile<BN, BK>(An + A_BYTES, tid, rb);
+            }
+            cur ^= 1;
+        }
+        __syncthreads();
+    }
+
+    store_acc<WI, WJ>(gp, acc, m0 + wm * 32 * WI, n0 + wn * 32 * WJ, lane, m0 + BM <= gp.M && n0 + BN <= gp.N);
+}
+
+// 256 x 256 tile, four waves of 128 x 128 (4 x 4 MFMA tiles: the whole accumulator register file), one
+// workgroup per compute unit, two LDS buffers.  With a single wave per SIMD nothing else hides latency, so
+// the K step is laid out by hand as 16 units of four MFMAs (one A operand against the four B operands of
+// its k slice): each unit first issues the LDS reads of the next unit's operands, then (last four units)
+// its share of the next tile's LDS writes and of the global loads for the tile after that, then its MFMAs.
+// Registers thus hold the tile two K steps ahead of the one being multiplied: a vector is written to LDS
+// in the second half of a step and its register is refilled at once, so that a load has a whole step of
+// MFMA time to arrive.
+struct BigCtx {
+    const bf16_t* a_org;  // tile origin at k = 0
+    const bf16_t* b_org;
+    int64_t lda, ldb, a_kstep, b_kstep;
+    uint32_t va, vb;
+    int rows_a, rows_b, K;  // extents left from the tile origin (masks)
+    int tid, lane, wm, wn;
+};
+
+// One K step.  STEADY: the registers hold a next tile, there is one after it, and neither needs masks --
+// straight-line code (no branches: the compiler then counts outstanding loads exactly instead of draining
+// them at every join).  Otherwise the same step with run-time conditions, for the last steps and edge tiles.
+template <bool AK, bool BK, bool STEADY>
+__device__ __forceinline__ void big_step(const BigCtx& cx, f32x16 (&acc)[4][4], bf16x8 (&ra)[8], bf16x8 (&rb)[8], const char* As,
+                                         char* An, int k0) {
+    constexpr int BM = 256, BN = 256;
+    constexpr int A_BYTES = tile_bytes<BM, AK>();
+    const char* Bs = As + A_BYTES;
+    char* Bn = An + A_BYTES;
+    const int k2 = k0 + 2 * BKK;
+    const bool more = STEADY || k0 + BKK < cx.K;
+    const bool more2 = STEADY || k2 < cx.K;
+    const bf16_t* ao = cx.a_org + (int64_t)k2 * cx.a_kstep;
+    const bf16_t* bo = cx.b_org + (int64_t)k2 * cx.b_kstep;
+    const int lane = cx.lane, tid = cx.tid;
+    bf16x8 aq[2], bq[2][4];
+    aq[0] = operand<BM, AK>(As, cx.wm * 128, 0, lane);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) bq[0][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, 0, lane);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) {
+        const int kk = u >> 2, i = u & 3;
+        if (u + 1 < 16) aq[(u + 1) & 1] = operand<BM, AK>(As, cx.wm * 128 + ((u + 1) & 3) * 32, ((u + 1) >> 2) * 16, lane);
+        if (i == 1 && kk < 3) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) bq[(kk + 1) & 1][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, (kk + 1) * 16, lane);
+        }
+        if (STEADY) {
+            // units 12..15: two vectors of each operand per unit
+#define GEMM_PART(P)                                                                     \
+    if (u == 12 + P / 2) {                                                               \
+        store_tile<BM, AK, P, P + 2>(An, tid, ra);                                       \
+        store_tile<BN, BK, P, P + 2>(Bn, tid, rb);                                       \
+        load_tile<BM, AK, false, P, P + 2>(ao, cx.lda, cx.va, 0, 0, tid, ra);            \
+        load_tile<BN, BK, false, P, P + 2>(bo, cx.ldb, cx.vb, 0, 0, tid, rb);            \
+    }
+            GEMM_PART(0)
+            GEMM_PART(2)
+            GEMM_PART(4)
+            GEMM_PART(6)
+#undef GEMM_PART
+        } else if (u == 8 && more) {
+            store_tile<BM, AK>(An, tid, ra);
+            store_tile<BN, BK>(Bn, tid, rb);
+            if (more2) {
+                load_tile<BM, AK, true>(ao, cx.lda, cx.va, cx.rows_a, cx.K - k2, tid, ra);
+                load_tile<BN, BK, true>(bo, cx.ldb, cx.vb, cx.rows_b, cx.K - k2, tid, rb);
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = mfma(bq[kk & 1][j], aq[u & 1], acc[i][j]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+}
 
 template <bool AK, bool BK>
-hipError_t launch_gemm(GemmParams gp, hipStream_t st) {
+__global__ __launch_bounds__(256, 1) void k_gemm_big(GemmParams gp) {
+    constexpr int BM = 256, BN = 256;
+    constexpr int A_BYTES = tile_bytes<BM, AK>(), B_BYTES = tile_bytes<BN, BK>();
+    extern __shared__ __attribute__((aligned(16))) char lds[];  // 2 x (A tile, B tile)
+    const int tid = threadIdx.x, w = tid >> 6;
+    int tm, tn;
+    tile_of(gp, tm, tn);
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    f32x16 acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = zero16();
+
+    const bool interior = m0 + BM <= gp.M && n0 + BN <= gp.N;
+    BigCtx cx;
+    cx.a_org = AK ? gp.A + (int64_t)m0 * gp.lda : gp.A + m0;
+    cx.b_org = BK ? gp.B + (int64_t)n0 * gp.ldb : gp.B + n0;
+    cx.lda = gp.lda;
+    cx.ldb = gp.ldb;
+    cx.a_kstep = AK ? 1 : gp.lda;  // elements per unit of k
+    cx.b_kstep = BK ? 1 : gp.ldb;
+    cx.va = tile_voff<BM, AK>(gp.lda, tid);
+    cx.vb = tile_voff<BN, BK>(gp.ldb, tid);
+    cx.rows_a = gp.M - m0;
+    cx.rows_b = gp.N - n0;
+    cx.K = gp.K;
+    cx.tid = tid;
+    cx.lane = tid & 63;
+    cx.wm = w >> 1;
+    cx.wn = w & 1;
+    const int lane = cx.lane, wm = cx.wm, wn = cx.wn;
+
+    bf16x8 ra[8], rb[8];
+    const bool steady = interior && 3 * BKK <= gp.K;  // at least one step of the straight-line loop
+    if (steady) {
+        // the same order of loads (A and B vector by vector) as inside the loop, so that the count of
+        // loads still outstanding at the loop's first LDS write is the same on entry and on every repeat
+#define GEMM_PRO(P, KOFF)                                                                                          \
+    load_tile<BM, AK, false, P, P + 2>(cx.a_org + (int64_t)(KOFF) * cx.a_kstep, gp.lda, cx.va, 0, 0, tid, ra);      \
+    load_tile<BN, BK, false, P, P + 2>(cx.b_org + (int64_t)(KOFF) * cx.b_kstep, gp.ldb, cx.vb, 0, 0, tid, rb);
+        GEMM_PRO(0, 0) GEMM_PRO(2, 0) GEMM_PRO(4, 0) GEMM_PRO(6, 0)
+        store_tile<BM, AK>(lds, tid, ra);
+        store_tile<BN, BK>(lds + A_BYTES, tid, rb);
+        GEMM_PRO(0, BKK) GEMM_PRO(2, BKK) GEMM_PRO(4, BKK) GEMM_PRO(6, BKK)
+#undef GEMM_PRO
+    } else {
+        load_tile<BM, AK, true>(cx.a_org, gp.lda, cx.va, cx.rows_a, gp.K, tid, ra);
+        load_tile<BN, BK, true>(cx.b_org, gp.ldb, cx.vb, cx.rows_b, gp.K, tid, rb);
+        store_tile<BM, AK>(lds, tid, ra);
+        store_tile<BN, BK>(lds + A_BYTES, tid, rb);
+        if (BKK < gp.K) {
+            load_tile<BM, AK, true>(cx.a_org + (int64_t)BKK * cx.a_kstep, gp.lda, cx.va, cx.rows_a, gp.K - BKK, tid, ra);
+            load_tile<BN, BK, true>(cx.b_org + (int64_t)BKK * cx.b_kstep, gp.ldb, cx.vb, cx.rows_b, gp.K - BKK, tid, rb);
+        }
+    }
+    __syncthreads();
+    int cur = 0, k0 = 0;
+    if (steady) {  // steps whose next two tiles are whole
+        for (; k0 + 3 * BKK <= gp.K; k0 += BKK) {
+            big_step<AK, BK, true>(cx, acc, ra, rb, lds + cur * (A_BYTES + B_BYTES), lds + (cur ^ 1) * (A_BYTES + B_BYTES), k0);
+            cur ^= 1;
+            __syncthreads();
+        }
+    }
+    for (; k0 < gp.K; k0 += BKK) {
+        big_step<AK, BK, false>(cx, acc, ra, rb, lds + cur * (A_BYTES + B_BYTES), lds + (cur ^ 1) * (A_BYTES + B_BYTES), k0);
+        cur ^= 1;
+        __syncthreads();
+    }
+
+    store_acc<4, 4>(gp, acc, m0 + wm * 128, n0 + wn * 128, lane, interior);
+}
+
+bool ok_ptr(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
+
+template <bool AK, bool BK, int WI, int WJ, bool DB>
+hipError_t launch_cfg(GemmParams gp, hipStream_t st) {
+    constexpr int BM = 64 * WI, BN = 64 * WJ;
+    constexpr int LDS = (DB ? 2 : 1) * (tile_bytes<BM, AK>() + tile_bytes<BN, BK>());
+    static_assert(LDS <= 65536, "beyond the default dynamic LDS limit");
     gp.tiles_m = (gp.M + BM - 1) / BM;
     gp.tiles_n = (gp.N + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm<AK, BK>), dim3(gp.tiles_m * gp.tiles_n), dim3(256), 0, st, gp);
+    hipLaunchKernelGGL((k_gemm<AK, BK, WI, WJ, DB>), dim3(gp.tiles_m * gp.tiles_n), dim3(256), LDS, st, gp);
     return hipGetLastError();
+}
+
+template <bool AK, bool BK>
+hipError_t launch_big(GemmParams gp, hipStream_t st) {
+    constexpr int LDS = 2 * (tile_bytes<256, AK>() + tile_bytes<256, BK>());
+    static bool raised[64];  // per device: the kernel uses more dynamic LDS than the default limit
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return hipErrorInvalidDevice;
+    if (!raised[dev]) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_gemm_big<AK, BK>, hipFuncAttributeMaxDynamicSharedMemorySize, LDS);
+        if (e != hipSuccess) return e;
+        raised[dev] = true;
+    }
+    gp.tiles_m = (gp.M + 255) / 256;
+    gp.tiles_n = (gp.N + 255) / 256;
+    hipLaunchKernelGGL((k_gemm_big<AK, BK>), dim3(gp.tiles_m * gp.tiles_n), dim3(256), LDS, st, gp);
+    return hipGetLastError();
+}
+
+// 256 x 256 tiles (double-buffered, one workgroup per compute unit) when they fill the machine about as
+// well as 256 x 128 tiles (two workgroups per compute unit) would; SSD_MAGC_GEMM_TILE=128 / 256 in the
+// environment forces one of the two (a diagnostic).
+template <bool AK, bool BK>
+hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
+    static const int forced = [] {
+        const char* e = getenv("SSD_MAGC_GEMM_TILE");
+        return e ? atoi(e) : 0;
+    }();
+    bool big = true;
+    if (forced == 128) big = false;
+    if (forced != 128 && forced != 256) {
+        const int64_t t = (int64_t)((gp.M + 255) / 256) * ((gp.N + 255) / 256);
+        const int64_t rounds = (t + 255) / 256;
+        big = t >= 256 && (double)t / (double)(rounds * 256) >= 0.8;
+    }
+    return big ? launch_big<AK, BK>(gp, st) : launch_cfg<AK, BK, 4, 2, false>(gp, st);
 }
 
 int check(int64_t rows, int32_t in_dim, int32_t out_dim, int64_t ldx, int64_t ldo) {
     if (rows < 0 || rows > 0x7fffffff || in_dim <= 0 || out_dim <= 0) return SSD_ERR_SHAPE;
     if ((in_dim | out_dim) & 7) return SSD_ERR_DIVISIBILITY;  // 16-byte vectors of bf16
     if ((ldx && (ldx < in_dim || (ldx & 7))) || (ldo && (ldo < out_dim || (ldo & 7)))) return SSD_ERR_SHAPE;
-    const int64_t tiles = ((rows + BM - 1) / BM) * (((int64_t)out_dim + BN - 1) / BN);
-    const int64_t tiles_w = (((int64_t)out_dim + BM - 1) / BM) * (((int64_t)in_dim + BN - 1) / BN);
+    const int64_t tiles = ((rows + 255) / 256) * (((int64_t)out_dim + 127) / 128);
+    const int64_t tiles_w = (((int64_t)out_dim + 255) / 256) * (((int64_t)in_dim + 127) / 128);
     if (tiles > 0x7fffffff || tiles_w > 0x7fffffff) return SSD_ERR_SHAPE;
     return SSD_OK;
 }
