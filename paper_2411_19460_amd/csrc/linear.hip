@@ -407,8 +407,8 @@ hipError_t launch_big(GemmParams gp, hipStream_t st) {
     return hipGetLastError();
 }
 
-// 256 x 256 tiles (double-buffered, one workgroup per compute unit) when they fill the machine about as
-// well as 256 x 128 tiles (two workgroups per compute unit) would; SSD_MAGC_GEMM_TILE=128 / 256 in the
+// 256 x 256 tiles (one workgroup per compute unit) unless there are too few of them to occupy half the
+// machine; then 256 x 128 tiles, two workgroups per compute unit.  SSD_MAGC_GEMM_TILE=128 / 256 in the
 // environment forces one of the two (a diagnostic).
 template <bool AK, bool BK>
 hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
@@ -419,9 +419,7 @@ hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
     bool big = true;
     if (forced == 128) big = false;
     if (forced != 128 && forced != 256) {
-        const int64_t t = (int64_t)((gp.M + 255) / 256) * ((gp.N + 255) / 256);
-        const int64_t rounds = (t + 255) / 256;
-        big = t >= 256 && (double)t / (double)(rounds * 256) >= 0.8;
+        big = (int64_t)((gp.M + 255) / 256) * ((gp.N + 255) / 256) >= 128;
     }
     return big ? launch_big<AK, BK>(gp, st) : launch_cfg<AK, BK, 4, 2, false>(gp, st);
 }
