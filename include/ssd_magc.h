@@ -164,7 +164,9 @@ typedef struct ssd_conv_shape_t {
     int32_t channels;      /* C */
     int64_t batch;         /* Bt */
     int64_t seqlen;        /* L >= 0 (an empty segment hands the state on) */
-    int64_t batch_stride;  /* elements between batches of u, out, dout, du (0 = L*C) */
+    int64_t batch_stride;  /* elements between batches of u, out, dout, du (0 = dense) */
+    int64_t u_row_stride;  /* elements between tokens of u and du (0 = C): u may be a column slice of a wider
+                              tensor (the input projection's output); out and dout are always dense */
 } ssd_conv_shape_t;
 
 size_t ssd_conv1d_workspace_bytes(const ssd_conv_shape_t* shape);
@@ -249,6 +251,62 @@ int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
             const float* dfinal_state, const void* boundary_states, void* dx, void* ddt, float* dA,
             void* dB, void* dC, float* dD, float* dinit_state, void* workspace,
             size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
+/*
+ * One whole Mamba-2 block (the backbone layer of Sec. 3.1) under the sequence-axis checkpoints of MA-GC
+ * (Sec. 3.2; Alg. 1 and 2 with a single layer), bf16 storage, one sequence:
+ *     zxbcdt = u W_in^T = (z | xBC | dt_raw)          [L, 2 d_inner + 2 G N + H],  d_inner = H P
+ *     xBC = silu(conv4(xBC) + conv_b);   dt = softplus(dt_raw + dt_bias);   (x | B | C) = xBC
+ *     y = SSD(x, dt, A, B, C, D);        out = RMSNorm_G(y silu(z)) norm_w  W_out^T
+ * Forward: segment by segment; what is kept per segment is exactly a sequence checkpoint of App. C,
+ * Tab. 7 -- the SSM state and the three-token convolution state entering the segment.  Backward:
+ * segments right to left, each recomputed from its two states into the workspace (zxbcdt and y, the
+ * activations C_grid counts, live there for one segment at a time), then differentiated step by
+ * step; the adjoints of the two states travel left.
+ *   u, out, dout, du [L, d_model] bf16, dense
+ *   ssm_ckpt  [nseg, H, P, N] fp32 and conv_ckpt [nseg, 3, d_inner + 2 G N] bf16: slot k = the states
+ *             entering segment k (slot 0 is not used: the sequence starts from zero states); written
+ *             by magc_block_fwd, read by magc_block_bwd; may be NULL when nseg == 1
+ *   final_ssm [H,P,N] fp32, final_conv [3, d_inner + 2 G N] bf16: the states leaving the sequence, may be NULL
+ *   params: W_in [d_in_proj, d_model] bf16, conv_w [conv_dim, 4], conv_b [conv_dim], dt_bias [H], A [H],
+ *           D [H], norm_w [d_inner] fp32, W_out [d_model, d_inner] bf16
+ *   grads:  the same shapes, all fp32, overwritten or added to under SSD_FLAG_ACCUM_PARAM (the only flag)
+ *   workspace: magc_block_workspace_bytes bytes, 256-byte aligned; scales with `segment`, not seqlen
+ * d_model, d_inner, G N and H must be multiples of 8 (SSD_ERR_DIVISIBILITY), segment a multiple of chunk;
+ * seqlen is arbitrary.  Everything is enqueued on hip_stream; nothing is allocated.  Errors as elsewhere.
+ */
+typedef struct {
+    int32_t d_model, nheads, headdim, ngroups, dstate, chunk;
+    float eps;          /* of the gated normalisation */
+    int64_t seqlen, segment;
+} magc_block_shape_t;
+typedef struct {
+    const void* W_in;
+    const float* conv_w;
+    const float* conv_b;
+    const float* dt_bias;
+    const float* A;
+    const float* D;
+    const float* norm_w;
+    const void* W_out;
+} magc_block_params_t;
+typedef struct {
+    float* dW_in;
+    float* dconv_w;
+    float* dconv_b;
+    float* ddt_bias;
+    float* dA;
+    float* dD;
+    float* dnorm_w;
+    float* dW_out;
+} magc_block_grads_t;
+size_t magc_block_workspace_bytes(const magc_block_shape_t* shape, int32_t is_backward);
+int magc_block_fwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u, void* out,
+                   float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv, void* workspace,
+                   size_t workspace_bytes, void* hip_stream);
+int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u, const void* dout,
+                   const float* ssm_ckpt, const void* conv_ckpt, void* du, const magc_block_grads_t* grads,
+                   void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /*
  * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the

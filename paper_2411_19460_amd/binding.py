@@ -18,7 +18,8 @@ SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
-           "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
+           "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -32,12 +33,29 @@ class ssd_shape_t(ctypes.Structure):
 
 class ssd_conv_shape_t(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("channels", ctypes.c_int32), ("batch", ctypes.c_int64),
-                ("seqlen", ctypes.c_int64), ("batch_stride", ctypes.c_int64)]
+                ("seqlen", ctypes.c_int64), ("batch_stride", ctypes.c_int64), ("u_row_stride", ctypes.c_int64)]
 
 
 class ssd_norm_shape_t(ctypes.Structure):
     _fields_ = [("dtype", ctypes.c_int32), ("dim", ctypes.c_int32), ("ngroups", ctypes.c_int32), ("eps", ctypes.c_float),
                 ("rows", ctypes.c_int64), ("y_row_stride", ctypes.c_int64), ("z_row_stride", ctypes.c_int64)]
+
+
+class magc_block_shape_t(ctypes.Structure):
+    _fields_ = [("d_model", ctypes.c_int32), ("nheads", ctypes.c_int32), ("headdim", ctypes.c_int32), ("ngroups", ctypes.c_int32),
+                ("dstate", ctypes.c_int32), ("chunk", ctypes.c_int32), ("eps", ctypes.c_float), ("seqlen", ctypes.c_int64),
+                ("segment", ctypes.c_int64)]
+
+
+BLOCK_PARAMS = ("W_in", "conv_w", "conv_b", "dt_bias", "A", "D", "norm_w", "W_out")
+
+
+class magc_block_params_t(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_void_p) for k in BLOCK_PARAMS]
+
+
+class magc_block_grads_t(ctypes.Structure):
+    _fields_ = [("d" + k, ctypes.c_void_p) for k in BLOCK_PARAMS]
 
 
 class magc_model_t(ctypes.Structure):
@@ -98,6 +116,13 @@ def lib():
         L.ssd_linear_fwd.argtypes = [i64, i32, i32, vp, i64, vp, vp, i64, vp]
         L.ssd_linear_bwd.restype = ctypes.c_int
         L.ssd_linear_bwd.argtypes = [i64, i32, i32, vp, i64, vp, vp, i64, vp, i64, vp, u32, vp]
+        bshp, bpar, bgr = (ctypes.POINTER(t) for t in (magc_block_shape_t, magc_block_params_t, magc_block_grads_t))
+        L.magc_block_workspace_bytes.restype = sz
+        L.magc_block_workspace_bytes.argtypes = [bshp, i32]
+        L.magc_block_fwd.restype = ctypes.c_int
+        L.magc_block_fwd.argtypes = [bshp, bpar] + [vp] * 6 + [vp, sz, vp]
+        L.magc_block_bwd.restype = ctypes.c_int
+        L.magc_block_bwd.argtypes = [bshp, bpar] + [vp] * 5 + [bgr, vp, sz, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -238,7 +263,7 @@ def _conv_shape(u):
         dt = SSD_F32
     else:
         raise TypeError(f"unsupported dtype {u.dtype}")
-    return ssd_conv_shape_t(dt, C, Bt, L, 0)
+    return ssd_conv_shape_t(dt, C, Bt, L, 0, 0)
 
 
 def _conv_check(u, w, bias, *more):
@@ -386,6 +411,70 @@ def ssd_linear_bwd(x, w, dout, want_dx=True, want_dw=True, flags=0, dx=None, dw=
     if rc != 0:
         raise SSDError(rc, "ssd_linear_bwd")
     return {"dx": dx, "dw": dw}
+
+
+def _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps):
+    import torch
+    if u.dim() != 2 or u.dtype != torch.bfloat16 or not u.is_cuda or not u.is_contiguous():
+        raise ValueError("u must be a dense [L, d_model] bf16 device tensor")
+    L, dm = u.shape
+    d_inner, gn = nheads * headdim, ngroups * dstate
+    conv_dim, d_in_proj = d_inner + 2 * gn, 2 * d_inner + 2 * gn + nheads
+    want = {"W_in": ((d_in_proj, dm), torch.bfloat16), "conv_w": ((conv_dim, 4), torch.float32), "conv_b": ((conv_dim,), torch.float32),
+            "dt_bias": ((nheads,), torch.float32), "A": ((nheads,), torch.float32), "D": ((nheads,), torch.float32),
+            "norm_w": ((d_inner,), torch.float32), "W_out": ((dm, d_inner), torch.bfloat16)}
+    for k, (shp, dty) in want.items():
+        t = params[k]
+        if tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"params[{k!r}] must be a dense {dty} device tensor of shape {shp}")
+    seg = segment if segment is not None else max(chunk, -(-L // chunk) * chunk)
+    shape = magc_block_shape_t(dm, nheads, headdim, ngroups, dstate, chunk, eps, L, seg)
+    par = magc_block_params_t(*[_ptr(params[k]) for k in BLOCK_PARAMS])
+    nseg = max(1, -(-L // seg))
+    return shape, par, want, nseg, conv_dim
+
+
+def magc_block_fwd(u, params, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5):
+    """One Mamba-2 block over u [L, d_model] with sequence checkpoints every `segment` tokens.
+    Returns dict(out, ssm_ckpt, conv_ckpt, final_ssm, final_conv)."""
+    import torch
+    shape, par, _, nseg, conv_dim = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    dev = u.device
+    out = torch.empty_like(u)
+    ssm_ckpt = torch.zeros((nseg, nheads, headdim, dstate), dtype=torch.float32, device=dev)
+    conv_ckpt = torch.zeros((nseg, 3, conv_dim), dtype=torch.bfloat16, device=dev)
+    final_ssm = torch.empty((nheads, headdim, dstate), dtype=torch.float32, device=dev)
+    final_conv = torch.empty((3, conv_dim), dtype=torch.bfloat16, device=dev)
+    ws = _workspace(int(lib().magc_block_workspace_bytes(ctypes.byref(shape), 0)), dev)
+    rc = lib().magc_block_fwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(out), _ptr(ssm_ckpt), _ptr(conv_ckpt),
+                              _ptr(final_ssm), _ptr(final_conv), _ptr(ws), ws.numel(), _stream(u))
+    if rc != 0:
+        raise SSDError(rc, "magc_block_fwd")
+    return {"out": out, "ssm_ckpt": ssm_ckpt, "conv_ckpt": conv_ckpt, "final_ssm": final_ssm, "final_conv": final_conv}
+
+
+def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5,
+                   flags=0, grads=None):
+    """dict(du, dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out) for the loss <dout, out>."""
+    import torch
+    shape, par, want, nseg, _ = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    if dout.shape != u.shape or dout.dtype != u.dtype or not dout.is_cuda or not dout.is_contiguous():
+        raise ValueError("dout must match u")
+    dev = u.device
+    if grads is None:
+        grads = {"d" + k: torch.empty(shp, dtype=torch.float32, device=dev) for k, (shp, _) in want.items()}
+    for k, (shp, _) in want.items():
+        t = grads["d" + k]
+        if tuple(t.shape) != shp or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"grads['d{k}'] must be a dense fp32 device tensor of shape {shp}")
+    gr = magc_block_grads_t(*[_ptr(grads["d" + k]) for k in BLOCK_PARAMS])
+    du = torch.empty_like(u)
+    ws = _workspace(int(lib().magc_block_workspace_bytes(ctypes.byref(shape), 1)), dev)
+    rc = lib().magc_block_bwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(dout), _ptr(ssm_ckpt), _ptr(conv_ckpt), _ptr(du),
+                              ctypes.byref(gr), _ptr(ws), ws.numel(), flags, _stream(u))
+    if rc != 0:
+        raise SSDError(rc, "magc_block_bwd")
+    return {"du": du, **grads}
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,

@@ -1,0 +1,364 @@
+// One Mamba-2 block (the backbone layer of Sec. 3.1) under MA-GC's sequence-axis checkpoints (Sec. 3.2,
+// Alg. 1/2 with one layer): per segment of `segment` tokens
+//     zxbcdt = u W_in^T = (z | xBC | dt_raw);   xBC = silu(conv4(xBC) + b);   dt = softplus(dt_raw + dt_bias)
+//     y = SSD(x, dt, A, B, C, D) with (x | B | C) = xBC;   out = RMSNorm_G(y silu(z)) norm_w  W_out^T
+// The forward pass keeps, per segment, only what a sequence checkpoint holds in App. C, Tab. 7: the SSM
+// state and the three-token convolution state entering the segment.  The backward pass walks the segments
+// right to left, redoes a segment's forward from its two states (Recompute_Forward of Alg. 2) into the
+// workspace -- zxbcdt and y are the per-token activations C_grid counts -- and then runs the reverse of
+// every step, handing the two state adjoints to the segment on the left.
+// Everything is a sequence of calls to the library's own entry points plus three small kernels (column
+// slices in and out of the (x | B | C) layout, and softplus of dt); all on the caller's stream.
+#include <string.h>
+
+#include "ssd_internal.h"
+
+namespace ssdk {
+namespace {
+
+typedef __bf16 b8 __attribute__((ext_vector_type(8)));
+
+// dst[r, 0..cols) = src[r, 0..cols) for r < rows; 16-byte vectors (cols, strides: multiples of 8 elements)
+__global__ __launch_bounds__(256) void k_copy_cols(bf16_t* dst, int64_t dst_rs, const bf16_t* src, int64_t src_rs, int64_t rows, int cols8) {
+    const int64_t n = rows * cols8;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
+        const int64_t r = i / cols8;
+        const int c = (int)(i - r * cols8) * 8;
+        *(b8*)((__bf16*)dst + r * dst_rs + c) = *(const b8*)((const __bf16*)src + r * src_rs + c);
+    }
+}
+
+hipError_t copy_cols(void* dst, int64_t dst_rs, const void* src, int64_t src_rs, int64_t rows, int cols, hipStream_t st) {
+    if (rows == 0 || cols == 0) return hipSuccess;
+    const int64_t n = rows * (cols / 8);
+    const int64_t blocks = (n + 255) / 256;
+    hipLaunchKernelGGL(k_copy_cols, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st, (bf16_t*)dst, dst_rs,
+                       (const bf16_t*)src, src_rs, rows, cols / 8);
+    return hipGetLastError();
+}
+
+constexpr int DT_ROWS = 64;  // rows per workgroup of the dt kernels (granularity of the ddt_bias partial sums)
+
+// dt[r,h] = softplus(raw[r,h] + bias[h]); raw is a column slice (rows raw_rs apart), dt dense
+__global__ __launch_bounds__(256) void k_dt_fwd(const bf16_t* raw, int64_t raw_rs, const float* bias, bf16_t* dt, int64_t rows, int H) {
+    const int64_t r0 = (int64_t)blockIdx.x * DT_ROWS;
+    for (int i = threadIdx.x; i < DT_ROWS * H; i += 256) {
+        const int64_t r = r0 + i / H;
+        const int h = i % H;
+        if (r < rows) {
+            const float v = bf16_to_float(raw[r * raw_rs + h]) + bias[h];
+            // log(1 + e^v) without overflow: max(v, 0) + log1p(e^-|v|)
+            dt[r * H + h] = float_to_bf16(fmaxf(v, 0.f) + log1pf(__expf(-fabsf(v))));
+        }
+    }
+}
+
+// draw[r,h] = ddt[r,h] sigmoid(raw[r,h] + bias[h]) into a column slice; part[tile][h] = sum over the tile's rows
+__global__ __launch_bounds__(256) void k_dt_bwd(const bf16_t* raw, int64_t raw_rs, const float* bias, const bf16_t* ddt, bf16_t* draw,
+                                               int64_t draw_rs, float* part, int64_t rows, int H) {
+    const int64_t r0 = (int64_t)blockIdx.x * DT_ROWS;
+    for (int h = threadIdx.x; h < H; h += 256) {
+        const float bh = bias[h];
+        float s = 0.f;
+        for (int rr = 0; rr < DT_ROWS; ++rr) {
+            const int64_t r = r0 + rr;
+            if (r >= rows) break;
+            const float v = bf16_to_float(raw[r * raw_rs + h]) + bh;
+            const float g = bf16_to_float(ddt[r * H + h]) * __builtin_amdgcn_rcpf(1.f + __expf(-v));
+            draw[r * draw_rs + h] = float_to_bf16(g);
+            s += g;
+        }
+        part[(int64_t)blockIdx.x * H + h] = s;
+    }
+}
+
+// out[h] (+)= sum_p part[p][h], in a fixed order
+__global__ __launch_bounds__(256) void k_colsum(const float* part, int64_t nparts, int H, float* out, int accumulate) {
+    const int h = blockIdx.x * 256 + threadIdx.x;
+    if (h >= H) return;
+    float s = 0.f;
+    for (int64_t p = 0; p < nparts; ++p) s += part[p * H + h];
+    out[h] = accumulate ? out[h] + s : s;
+}
+
+struct BlockDims {
+    int64_t L, s, nseg;
+    int dm, H, P, G, N, Q, d_inner, conv_dim, gn, d_in_proj, off_xbc, off_dt;
+    size_t HPN;
+};
+
+int check(const magc_block_shape_t* sh, BlockDims* d) {
+    if (!sh) return SSD_ERR_NULL;
+    if (sh->d_model <= 0 || sh->nheads <= 0 || sh->headdim <= 0 || sh->ngroups <= 0 || sh->dstate <= 0 || sh->chunk <= 0 ||
+        sh->seqlen < 0 || sh->segment <= 0)
+        return SSD_ERR_SHAPE;
+    if (sh->nheads % sh->ngroups) return SSD_ERR_DIVISIBILITY;
+    if (sh->segment % sh->chunk) return SSD_ERR_DIVISIBILITY;
+    if (!(sh->eps >= 0.f)) return SSD_ERR_ARG;
+    d->L = sh->seqlen;
+    d->s = sh->segment;
+    d->nseg = sh->seqlen > 0 ? (sh->seqlen + sh->segment - 1) / sh->segment : 0;
+    d->dm = sh->d_model;
+    d->H = sh->nheads;
+    d->P = sh->headdim;
+    d->G = sh->ngroups;
+    d->N = sh->dstate;
+    d->Q = sh->chunk;
+    d->d_inner = d->H * d->P;
+    d->gn = d->G * d->N;
+    d->conv_dim = d->d_inner + 2 * d->gn;
+    d->d_in_proj = 2 * d->d_inner + 2 * d->gn + d->H;
+    d->off_xbc = d->d_inner;
+    d->off_dt = d->d_inner + d->conv_dim;
+    d->HPN = (size_t)d->H * d->P * d->N;
+    // 16-byte vectors of bf16 everywhere: every column range starts and ends on a multiple of 8
+    if ((d->dm | d->d_inner | d->gn | d->H) & 7) return SSD_ERR_DIVISIBILITY;
+    return SSD_OK;
+}
+
+ssd_shape_t seg_shape(const BlockDims& d, int64_t rows) {
+    ssd_shape_t sh;
+    memset(&sh, 0, sizeof(sh));
+    sh.dtype = SSD_BF16;
+    sh.nheads = d.H;
+    sh.headdim = d.P;
+    sh.ngroups = d.G;
+    sh.dstate = d.N;
+    sh.chunk = d.Q;
+    sh.batch = 1;
+    sh.seqlen = rows;
+    sh.segment = d.s;  // one segment per call: the block's own loop is the sequence axis
+    return sh;
+}
+
+ssd_conv_shape_t conv_shape(const BlockDims& d, int64_t rows) {
+    ssd_conv_shape_t c;
+    memset(&c, 0, sizeof(c));
+    c.dtype = SSD_BF16;
+    c.channels = d.conv_dim;
+    c.batch = 1;
+    c.seqlen = rows;
+    c.u_row_stride = d.d_in_proj;
+    return c;
+}
+
+ssd_norm_shape_t norm_shape(const BlockDims& d, int64_t rows, float eps) {
+    ssd_norm_shape_t n;
+    memset(&n, 0, sizeof(n));
+    n.dtype = SSD_BF16;
+    n.dim = d.d_inner;
+    n.ngroups = d.G;
+    n.eps = eps;
+    n.rows = rows;
+    n.z_row_stride = d.d_in_proj;
+    return n;
+}
+
+size_t al(size_t n) { return (n + 255) & ~(size_t)255; }
+
+// Workspace: one segment's activations (and, backward, their gradients), the scratch of the inner calls.
+struct BlockWs {
+    size_t zx, xbc, x, B, C, dt, y, yn;                     // forward activations of the segment
+    size_t dyn, dy, dzx, dxbc, dx, dB, dC, ddt;             // backward
+    size_t dssm[2], dconv[2], dtpart, inner, total;
+    size_t inner_bytes;
+};
+
+BlockWs layout(const BlockDims& d, bool bwd) {
+    BlockWs w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += al(bytes);
+        return o;
+    };
+    const size_t s = (size_t)d.s;
+    w.zx = take(s * d.d_in_proj * 2);
+    w.xbc = take(s * d.conv_dim * 2);
+    w.x = take(s * d.d_inner * 2);
+    w.B = take(s * d.gn * 2);
+    w.C = take(s * d.gn * 2);
+    w.dt = take(s * d.H * 2);
+    w.y = take(s * d.d_inner * 2);
+    w.yn = take(s * d.d_inner * 2);
+    // scratch of the inner calls: for a whole segment and for the short last one (which the scan pads)
+    const ssd_shape_t ss = seg_shape(d, d.s);
+    const ssd_shape_t st = seg_shape(d, d.L % d.s ? d.L % d.s : d.s);
+    size_t inner = 0;  // the backward pass also runs the forward scan (recomputation)
+    for (int pass = 0; pass <= (bwd ? 1 : 0); ++pass) {
+        const size_t a = ssd_workspace_bytes(&ss, pass), b = ssd_workspace_bytes(&st, pass);
+        inner = a > inner ? a : inner;
+        inner = b > inner ? b : inner;
+    }
+    if (bwd) {
+        w.dyn = take(s * d.d_inner * 2);
+        w.dy = take(s * d.d_inner * 2);
+        w.dzx = take(s * d.d_in_proj * 2);
+        w.dxbc = take(s * d.conv_dim * 2);
+        w.dx = take(s * d.d_inner * 2);
+        w.dB = take(s * d.gn * 2);
+        w.dC = take(s * d.gn * 2);
+        w.ddt = take(s * d.H * 2);
+        for (int i = 0; i < 2; ++i) w.dssm[i] = take(d.HPN * 4);
+        for (int i = 0; i < 2; ++i) w.dconv[i] = take((size_t)3 * d.conv_dim * 4);
+        w.dtpart = take(((s + DT_ROWS - 1) / DT_ROWS) * d.H * 4);
+        const ssd_conv_shape_t cs = conv_shape(d, d.s);
+        const ssd_norm_shape_t ns = norm_shape(d, d.s, 0.f);
+        const size_t b = ssd_conv1d_workspace_bytes(&cs), c = ssd_gated_norm_workspace_bytes(&ns);
+        inner = b > inner ? b : inner;
+        inner = c > inner ? c : inner;
+    }
+    w.inner = take(inner);
+    w.inner_bytes = inner;
+    w.total = off;
+    return w;
+}
+
+#define BLK_TRY(expr)                   \
+    do {                                \
+        const int rc_ = (expr);         \
+        if (rc_ != SSD_OK) return rc_;  \
+    } while (0)
+#define BLK_HIP(expr)                                   \
+    do {                                                \
+        if ((expr) != hipSuccess) return SSD_ERR_LAUNCH; \
+    } while (0)
+
+// Steps 1-5 of a segment (everything up to y and the normalised y), from the two states entering it.
+int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
+                    const void* u_seg, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out,
+                    hipStream_t st) {
+    char* zx = ws + w.zx;
+    BLK_TRY(ssd_linear_fwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, zx, 0, st));
+    const ssd_conv_shape_t cs = conv_shape(d, rows);
+    BLK_TRY(ssd_conv1d_fwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.xbc, conv_out, st));
+    BLK_HIP(copy_cols(ws + w.x, d.d_inner, ws + w.xbc, d.conv_dim, rows, d.d_inner, st));
+    BLK_HIP(copy_cols(ws + w.B, d.gn, ws + w.xbc + (size_t)d.d_inner * 2, d.conv_dim, rows, d.gn, st));
+    BLK_HIP(copy_cols(ws + w.C, d.gn, ws + w.xbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, rows, d.gn, st));
+    hipLaunchKernelGGL(k_dt_fwd, dim3((unsigned)((rows + DT_ROWS - 1) / DT_ROWS)), dim3(256), 0, st,
+                       (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj, p->dt_bias, (bf16_t*)(ws + w.dt), rows, d.H);
+    BLK_HIP(hipGetLastError());
+    const ssd_shape_t ss = seg_shape(d, rows);
+    BLK_TRY(ssd_fwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.y, ssm_out, nullptr, ws + w.inner,
+                    w.inner_bytes, 0, st));
+    const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
+    BLK_TRY(ssd_gated_norm_fwd(&ns, ws + w.y, zx, p->norm_w, ws + w.yn, st));
+    return SSD_OK;
+}
+
+}  // namespace
+}  // namespace ssdk
+
+using namespace ssdk;
+
+extern "C" size_t magc_block_workspace_bytes(const magc_block_shape_t* sh, int32_t is_backward) {
+    BlockDims d;
+    if (check(sh, &d) != SSD_OK) return 0;
+    const ssd_shape_t ss = seg_shape(d, d.s);
+    if (ssd_workspace_bytes(&ss, is_backward) == 0) return 0;
+    return layout(d, is_backward != 0).total;
+}
+
+extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, void* out, float* ssm_ckpt,
+                              void* conv_ckpt, float* final_ssm, void* final_conv, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+    BlockDims d;
+    BLK_TRY(check(sh, &d));
+    if (!p || !p->W_in || !p->conv_w || !p->conv_b || !p->dt_bias || !p->A || !p->D || !p->norm_w || !p->W_out) return SSD_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (d.L == 0) {  // nothing to do: the (zero) states pass through
+        if (final_ssm) BLK_HIP(launch_fill_zero(final_ssm, d.HPN, st));
+        if (final_conv) BLK_HIP(launch_fill_zero((float*)final_conv, (size_t)3 * d.conv_dim / 2, st));  // bf16 zeros
+        return SSD_OK;
+    }
+    if (!u || !out || (d.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
+    const BlockWs w = layout(d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    const size_t conv_state_bytes = (size_t)3 * d.conv_dim * 2;
+    for (int64_t k = 0; k < d.nseg; ++k) {
+        const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
+        const bool last = k + 1 == d.nseg;
+        const float* ssm_in = k ? ssm_ckpt + (size_t)k * d.HPN : nullptr;  // segment 0 starts from zeros
+        const void* conv_in = k ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : nullptr;
+        float* ssm_out = last ? final_ssm : ssm_ckpt + (size_t)(k + 1) * d.HPN;
+        void* conv_out = last ? final_conv : (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes;
+        BLK_TRY(forward_segment(d, sh, p, ws, w, (const char*)u + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, ssm_out, conv_out, st));
+        BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (char*)out + (size_t)t0 * d.dm * 2, 0, st));
+    }
+    return SSD_OK;
+}
+
+extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const void* dout,
+                              const float* ssm_ckpt, const void* conv_ckpt, void* du, const magc_block_grads_t* g, void* workspace,
+                              size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+    BlockDims d;
+    BLK_TRY(check(sh, &d));
+    if (flags & ~(uint32_t)SSD_FLAG_ACCUM_PARAM) return SSD_ERR_ARG;
+    if (!p || !p->W_in || !p->conv_w || !p->conv_b || !p->dt_bias || !p->A || !p->D || !p->norm_w || !p->W_out) return SSD_ERR_NULL;
+    if (!g || !g->dW_in || !g->dconv_w || !g->dconv_b || !g->ddt_bias || !g->dA || !g->dD || !g->dnorm_w || !g->dW_out) return SSD_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (!(flags & SSD_FLAG_ACCUM_PARAM)) {  // every segment adds to the parameter gradients
+        BLK_HIP(launch_fill_zero(g->dW_in, (size_t)d.d_in_proj * d.dm, st));
+        BLK_HIP(launch_fill_zero(g->dconv_w, (size_t)d.conv_dim * 4, st));
+        BLK_HIP(launch_fill_zero(g->dconv_b, (size_t)d.conv_dim, st));
+        BLK_HIP(launch_fill_zero(g->ddt_bias, (size_t)d.H, st));
+        BLK_HIP(launch_fill_zero(g->dA, (size_t)d.H, st));
+        BLK_HIP(launch_fill_zero(g->dD, (size_t)d.H, st));
+        BLK_HIP(launch_fill_zero(g->dnorm_w, (size_t)d.d_inner, st));
+        BLK_HIP(launch_fill_zero(g->dW_out, (size_t)d.dm * d.d_inner, st));
+    }
+    if (d.L == 0) return SSD_OK;
+    if (!u || !dout || !du || (d.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
+    const BlockWs w = layout(d, true);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    char* zx = ws + w.zx;
+    char* dzx = ws + w.dzx;
+    const size_t conv_state_bytes = (size_t)3 * d.conv_dim * 2;
+    const uint32_t acc = SSD_FLAG_ACCUM_PARAM;
+    for (int64_t k = d.nseg - 1; k >= 0; --k) {
+        const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
+        const bool last = k + 1 == d.nseg;
+        const float* ssm_in = k ? ssm_ckpt + (size_t)k * d.HPN : nullptr;
+        const void* conv_in = k ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : nullptr;
+        // adjoints of the states leaving this segment (none behind the last one) / entering it
+        const float* dssm_out = last ? nullptr : (const float*)(ws + w.dssm[(k + 1) & 1]);
+        const float* dconv_out = last ? nullptr : (const float*)(ws + w.dconv[(k + 1) & 1]);
+        float* dssm_in = k ? (float*)(ws + w.dssm[k & 1]) : nullptr;
+        float* dconv_in = k ? (float*)(ws + w.dconv[k & 1]) : nullptr;
+        const void* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
+        // Recompute_Forward: zxbcdt, (x | B | C), dt, y, normalised y of this segment
+        BLK_TRY(forward_segment(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, nullptr, nullptr, st));
+        // output projection
+        BLK_TRY(ssd_linear_bwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (const char*)dout + (size_t)t0 * d.dm * 2, 0, ws + w.dyn, 0,
+                               g->dW_out, acc, st));
+        // gated normalisation: dy, and dz straight into its columns of d zxbcdt
+        const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
+        BLK_TRY(ssd_gated_norm_bwd(&ns, ws + w.y, zx, p->norm_w, ws + w.dyn, ws + w.dy, dzx, g->dnorm_w, ws + w.inner, w.inner_bytes, acc, st));
+        // scan
+        const ssd_shape_t ss = seg_shape(d, rows);
+        BLK_TRY(ssd_bwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.dy, dssm_out, nullptr, ws + w.dx,
+                        ws + w.ddt, g->dA, ws + w.dB, ws + w.dC, g->dD, dssm_in, ws + w.inner, w.inner_bytes, acc, st));
+        // softplus of dt: into the dt columns of d zxbcdt
+        const int ntile = (int)((rows + DT_ROWS - 1) / DT_ROWS);
+        hipLaunchKernelGGL(k_dt_bwd, dim3(ntile), dim3(256), 0, st, (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
+                           p->dt_bias, (const bf16_t*)(ws + w.ddt), (bf16_t*)(dzx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
+                           (float*)(ws + w.dtpart), rows, d.H);
+        BLK_HIP(hipGetLastError());
+        hipLaunchKernelGGL(k_colsum, dim3((d.H + 255) / 256), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H,
+                           g->ddt_bias, 1);
+        BLK_HIP(hipGetLastError());
+        // convolution: (dx | dB | dC) side by side, du into the xBC columns of d zxbcdt
+        BLK_HIP(copy_cols(ws + w.dxbc, d.conv_dim, ws + w.dx, d.d_inner, rows, d.d_inner, st));
+        BLK_HIP(copy_cols(ws + w.dxbc + (size_t)d.d_inner * 2, d.conv_dim, ws + w.dB, d.gn, rows, d.gn, st));
+        BLK_HIP(copy_cols(ws + w.dxbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, ws + w.dC, d.gn, rows, d.gn, st));
+        const ssd_conv_shape_t cs = conv_shape(d, rows);
+        BLK_TRY(ssd_conv1d_bwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.dxbc, dconv_out,
+                               dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
+        // input projection
+        BLK_TRY(ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, (char*)du + (size_t)t0 * d.dm * 2, 0, g->dW_in, acc, st));
+    }
+    return SSD_OK;
+}

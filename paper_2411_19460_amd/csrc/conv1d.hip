@@ -29,7 +29,8 @@ struct ConvParams {
     const float* w;     // [C][4]
     const float* bias;  // [C] or null
     float* part;        // [Bt][ntiles][5][C] partial sums of dw (k = 0..3) and dbias
-    int64_t L, u_bs;    // tokens, batch stride of u / out / dout / du in elements
+    int64_t L, u_bs, o_bs;  // tokens; batch stride of u / du and of out / dout in elements
+    int64_t u_rs;           // elements between consecutive tokens of u / du (out / dout: C)
     int C, ntiles;
 };
 
@@ -85,7 +86,7 @@ __device__ __forceinline__ float dsilu(float z) {
 template <typename T, int V>
 __device__ __forceinline__ void load_row(const ConvParams& cp, int64_t b, int64_t t, int c0, float (&v)[V]) {
     if (t >= 0 && t < cp.L) {
-        Vec<T, V>::ld(cp.u, b * cp.u_bs + t * cp.C + c0, v);
+        Vec<T, V>::ld(cp.u, b * cp.u_bs + t * cp.u_rs + c0, v);
     } else if (t < 0 && t >= -3 && cp.state_in) {
         Vec<T, V>::ld(cp.state_in, (b * 3 + (t + 3)) * cp.C + c0, v);
     } else {
@@ -115,7 +116,7 @@ __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
         float cur[U][V];
 #pragma unroll
         for (int j = 0; j < U; ++j)
-            if (t + j < t1) Vec<T, V>::ld(cp.u, b * cp.u_bs + (t + j) * cp.C + c0, cur[j]);
+            if (t + j < t1) Vec<T, V>::ld(cp.u, b * cp.u_bs + (t + j) * cp.u_rs + c0, cur[j]);
 #pragma unroll
         for (int j = 0; j < U; ++j) {
             if (t + j >= t1) break;
@@ -128,7 +129,7 @@ __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
                 win[1][e] = win[2][e];
                 win[2][e] = cur[j][e];
             }
-            Vec<T, V>::st(cp.out, b * cp.u_bs + (t + j) * cp.C + c0, o);
+            Vec<T, V>::st(cp.out, b * cp.o_bs + (t + j) * cp.C + c0, o);
         }
     }
     // the state leaving the segment: the last three rows of [state_in ; u]
@@ -204,7 +205,7 @@ __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
 #pragma unroll
                     for (int e = 0; e < V; ++e) o[e] += cp.dstate_out[(b * 3 + j) * cp.C + c0 + e];
                 }
-                Vec<T, V>::st(cp.du, b * cp.u_bs + to * cp.C + c0, o);
+                Vec<T, V>::st(cp.du, b * cp.u_bs + to * cp.u_rs + c0, o);
             } else {
                 // a row of the entering state; when the sequence is shorter than three tokens, part of the
                 // state passes straight through to state_out and takes dstate_out's gradient with it
@@ -231,8 +232,8 @@ __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
     for (int64_t t = t0; t < t1 + 3; ++t) {
         float cur[V], dv[V];
         if (t < cp.L) {
-            Vec<T, V>::ld(cp.u, b * cp.u_bs + t * cp.C + c0, cur);
-            Vec<T, V>::ld(cp.dout, b * cp.u_bs + t * cp.C + c0, dv);
+            Vec<T, V>::ld(cp.u, b * cp.u_bs + t * cp.u_rs + c0, cur);
+            Vec<T, V>::ld(cp.dout, b * cp.o_bs + t * cp.C + c0, dv);
         } else {
 #pragma unroll
             for (int e = 0; e < V; ++e) cur[e] = dv[e] = 0.f;
@@ -287,7 +288,8 @@ int check(const ssd_conv_shape_t* sh) {
     if (sh->dtype != SSD_F32 && sh->dtype != SSD_BF16) return SSD_ERR_DTYPE;
     if (sh->batch <= 0 || sh->batch > 65535 || sh->seqlen < 0 || sh->channels <= 0) return SSD_ERR_SHAPE;
     if ((sh->seqlen + FWD_TT - 1) / FWD_TT > 65535) return SSD_ERR_SHAPE;  // grid.y
-    if (sh->batch_stride && sh->batch_stride < sh->seqlen * sh->channels) return SSD_ERR_SHAPE;
+    if (sh->u_row_stride && sh->u_row_stride < sh->channels) return SSD_ERR_SHAPE;
+    if (sh->batch_stride && sh->batch_stride < sh->seqlen * (sh->u_row_stride ? sh->u_row_stride : sh->channels)) return SSD_ERR_SHAPE;
     return SSD_OK;
 }
 
@@ -320,10 +322,12 @@ extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const f
     cp.bias = bias;
     cp.L = sh->seqlen;
     cp.C = sh->channels;
-    cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
+    cp.u_rs = sh->u_row_stride ? sh->u_row_stride : sh->channels;
+    cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * cp.u_rs;
+    cp.o_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = sh->dtype == SSD_BF16;
-    const int V = bf ? (cp.C % 8 == 0 ? 8 : 1) : (cp.C % 4 == 0 ? 4 : 1);
+    const int V = bf ? ((cp.C | cp.u_rs) % 8 == 0 ? 8 : 1) : ((cp.C | cp.u_rs) % 4 == 0 ? 4 : 1);
     // an empty sequence still hands the state on: one tile, whose token loop is empty
     const dim3 grid((cp.C / V + 63) / 64, (unsigned)(cp.L > 0 ? (cp.L + FWD_TT - 1) / FWD_TT : 1), (unsigned)sh->batch);
     if (bf && V == 8) hipLaunchKernelGGL((k_conv_fwd<bf16_t, 8>), grid, dim3(64), 0, st, cp);
@@ -357,11 +361,13 @@ extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const f
     cp.part = (float*)workspace;
     cp.L = sh->seqlen;
     cp.C = sh->channels;
-    cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
+    cp.u_rs = sh->u_row_stride ? sh->u_row_stride : sh->channels;
+    cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * cp.u_rs;
+    cp.o_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
     cp.ntiles = ntiles_bwd(sh) > 0 ? ntiles_bwd(sh) : 1;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = sh->dtype == SSD_BF16;
-    const int V = bf ? (cp.C % 8 == 0 ? 8 : 1) : (cp.C % 4 == 0 ? 4 : 1);
+    const int V = bf ? ((cp.C | cp.u_rs) % 8 == 0 ? 8 : 1) : ((cp.C | cp.u_rs) % 4 == 0 ? 4 : 1);
     const dim3 grid((cp.C / V + 63) / 64, (unsigned)cp.ntiles, (unsigned)sh->batch);
     if (bf && V == 8) hipLaunchKernelGGL((k_conv_bwd<bf16_t, 8>), grid, dim3(64), 0, st, cp);
     else if (bf) hipLaunchKernelGGL((k_conv_bwd<bf16_t, 1>), grid, dim3(64), 0, st, cp);

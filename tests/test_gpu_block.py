@@ -1,0 +1,88 @@
+"""GPU parity of one whole Mamba-2 block under sequence checkpoints (forward, and the backward sweep that
+recomputes every segment from its two states) against the fp64 block oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2411_19460_amd as pk
+from oracle import block_ref
+from paper_2411_19460_amd import synth
+from parity_util import TOL, check, host
+
+pytestmark = pytest.mark.gpu
+
+BF = lambda a: np.asarray(synth.round_bf16(a), dtype=np.float64)
+F32 = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
+
+
+def draw(seed, L, dm, H, P, G, N):
+    r = np.random.default_rng(4000 + seed)
+    d_inner, conv_dim, d_in = block_ref.dims(None, H, P, G, N)
+    dt0 = np.exp(r.uniform(np.log(1e-3), np.log(0.1), H))           # the step sizes the bias alone would give
+    p = dict(W_in=BF(r.standard_normal((d_in, dm)) / np.sqrt(dm)), conv_w=F32(r.standard_normal((conv_dim, 4)) * 0.5),
+             conv_b=F32(r.standard_normal(conv_dim) * 0.2), dt_bias=F32(dt0 + np.log(-np.expm1(-dt0))),
+             A=F32(-np.exp(r.uniform(0.0, np.log(16.0), H))), D=F32(r.standard_normal(H)),
+             norm_w=F32(1.0 + 0.3 * r.standard_normal(d_inner)), W_out=BF(r.standard_normal((dm, d_inner)) / np.sqrt(d_inner)))
+    return dict(u=BF(r.standard_normal((L, dm))), dout=BF(r.standard_normal((L, dm))), p=p)
+
+
+def to_dev(p):
+    out = {}
+    for k, v in p.items():
+        t = torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).cuda()
+        out[k] = t.to(torch.bfloat16) if k in ("W_in", "W_out") else t
+    return out
+
+
+def dev_bf16(a):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda().to(torch.bfloat16)
+
+
+GRADS = ("dW_in", "dconv_w", "dconv_b", "ddt_bias", "dA", "dD", "dnorm_w", "dW_out")
+
+
+@pytest.mark.parametrize("case", [
+    # L,   d_model, H, P,  G, N,   chunk, segment
+    (1024, 256, 8, 64, 1, 128, 128, 256),     # matrix-core scan kernels, four segments
+    (700, 128, 8, 64, 2, 128, 256, 256),      # two groups; ragged: the last segment has 188 tokens
+    (300, 64, 8, 16, 1, 16, 64, 128),         # small heads and states: the scan's shape-generic kernels
+])
+def test_block_forward_backward(case):
+    L, dm, H, P, G, N, Q, seg = case
+    d = draw(1, L, dm, H, P, G, N)
+    u, dout, par = dev_bf16(d["u"]), dev_bf16(d["dout"]), to_dev(d["p"])
+    f = pk.magc_block_fwd(u, par, H, P, G, N, Q, seg)
+    g = pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg)
+    torch.cuda.synchronize()
+    fo = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 1e-5, store=synth.round_bf16)
+    go = block_ref.block_bwd(d["u"], d["p"], H, P, G, N, d["dout"], 1e-5, store=synth.round_bf16)
+    tol = TOL["bf16"]
+    rep = {}
+    check("out", host(f["out"]), fo["out"], tol, rep)
+    check("final_ssm", host(f["final_ssm"]), fo["ssm_state"], tol, rep)
+    check("final_conv", host(f["final_conv"]), fo["conv_state"], tol, rep)
+    check("du", host(g["du"]), go["du"], tol, rep)
+    for k in GRADS:
+        check(k, host(g[k]), go[k], tol, rep)
+    print("block errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+    # the checkpoint interval does not change the result (both states are carried exactly): one segment
+    f1 = pk.magc_block_fwd(u, par, H, P, G, N, Q, None)
+    g1 = pk.magc_block_bwd(u, par, dout, None, None, H, P, G, N, Q, None)
+    torch.cuda.synchronize()
+    assert torch.equal(f1["out"], f["out"])
+    for k in ("du",) + GRADS:
+        a, b = g[k].float(), g1[k].float()
+        assert float((a - b).abs().max()) <= 2.0 ** -6 * float(b.abs().max()), k
+    # accumulation into existing parameter gradients
+    g2 = pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg, flags=pk.SSD_FLAG_ACCUM_PARAM,
+                           grads={k: g[k].clone() for k in GRADS})
+    torch.cuda.synchronize()
+    for k in GRADS:
+        check(k + " accumulated", host(g2[k]), 2 * host(g[k]), 1e-5)
+
+
+def test_block_rejects_bad_shapes():
+    u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
+    d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
+    with pytest.raises(pk.SSDError):
+        pk.magc_block_fwd(u, to_dev(d["p"]), 4, 16, 1, 16, 64, 64)
