@@ -7,7 +7,9 @@ seeded synthetic inputs that are already resident in HBM.  Prints ONE JSON line.
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 2] [--no-cpu-baseline]
 """
 import argparse
+import ctypes
 import json
+import math
 import os
 import sys
 import time
@@ -298,6 +300,67 @@ def linear_bench(args, cfg, pk, torch, dev):
     }))
 
 
+def block_bench(args, cfg, pk, torch, dev):
+    """One whole Mamba-2 block (projections, convolution, scan, gated norm) at the config's shape, forward
+    + backward under sequence checkpoints every cfg.segment tokens.  The projections dominate (about 300 of
+    the 316 MFLOP per token), so the step is priced against the bf16 matrix-core peak."""
+    L, H, P, G, N = cfg.batch * cfg.seqlen, cfg.nheads, cfg.headdim, cfg.ngroups, cfg.dstate
+    d_inner, dm = H * P, H * P // 2
+    gn = G * N
+    conv_dim, d_in_proj = d_inner + 2 * gn, 2 * d_inner + 2 * gn + H
+    g = torch.Generator(device=dev)
+    g.manual_seed(cfg.seed(0) + 17)
+    rn = lambda *s: torch.randn(s, device=dev, generator=g, dtype=torch.float32)
+    dt0 = torch.exp(torch.empty(H, device=dev).uniform_(math.log(1e-3), math.log(0.1), generator=g))
+    par = {"W_in": (rn(d_in_proj, dm) / dm ** 0.5).to(torch.bfloat16), "conv_w": rn(conv_dim, 4) * 0.5, "conv_b": rn(conv_dim) * 0.2,
+           "dt_bias": dt0 + torch.log(-torch.expm1(-dt0)), "A": -torch.exp(torch.empty(H, device=dev).uniform_(0.0, math.log(16.0), generator=g)),
+           "D": rn(H), "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5).to(torch.bfloat16)}
+    u, dout = rn(L, dm).to(torch.bfloat16), rn(L, dm).to(torch.bfloat16)
+    grads = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in par.items()}
+    f = {}
+
+    def fwd():
+        f.update(pk.magc_block_fwd(u, par, H, P, G, N, cfg.chunk, cfg.segment))
+
+    def bwd():
+        pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, cfg.chunk, cfg.segment, grads=grads)
+
+    def timed(fn):
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) * 1e3 / args.steps
+
+    ms_f, ms_b = timed(fwd), timed(bwd)
+    assert bool(torch.isfinite(grads["dW_in"].sum())) and bool(torch.isfinite(f["out"].float().sum()))
+    proj = 2.0 * (dm * d_in_proj + d_inner * dm)                       # per token, forward
+    ssd_f = (2 * cfg.chunk * P + 4 * N * P) * H + 2 * cfg.chunk * N * G   # the scan's forward contractions per token
+    # forward; input and weight gradients; the recomputed input projection; the scan forward, recomputed, backward
+    flop_tok = proj + 2 * proj + 2.0 * dm * d_in_proj + 4 * ssd_f
+    ach = flop_tok * L / ((ms_f + ms_b) * 1e-3) / 1e12
+    shp = pk.binding.magc_block_shape_t(dm, H, P, G, N, cfg.chunk, 1e-5, L, cfg.segment)
+    full = pk.binding.magc_block_shape_t(dm, H, P, G, N, cfg.chunk, 1e-5, L, L)
+    nseg = -(-L // cfg.segment)
+    ckpt = nseg * (H * P * N * 4 + 3 * conv_dim * 2)
+    print(json.dumps({
+        "metric": "Mamba-2 block fwd+bwd tokens/sec/layer", "value": L / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": cfg.name + "_block", "seqlen": L, "d_model": dm, "nheads": H, "headdim": P, "ngroups": G, "dstate": N,
+                   "chunk": cfg.chunk, "segment": cfg.segment},
+        "roofline": {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
+                     "traffic": None, "flop_per_token": flop_tok, "forward_ms": ms_f, "backward_ms": ms_b},
+        "peak_hbm": {"magc_bytes": int(pk.lib().magc_block_workspace_bytes(ctypes.byref(shp), 1)) + ckpt,
+                     "full_activation_bytes": int(pk.lib().magc_block_workspace_bytes(ctypes.byref(full), 1)),
+                     "note": "workspace + checkpoints beyond inputs, outputs and parameter gradients: checkpoints every "
+                             "segment vs one segment = the whole sequence (every activation of the block alive)"},
+    }))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -318,6 +381,8 @@ def main():
                     help="time the block's gated RMS normalisation (forward + backward) at the config's width instead")
     ap.add_argument("--linear", action="store_true",
                     help="time the block's input and output projections (forward, input and weight gradients) instead")
+    ap.add_argument("--block", action="store_true",
+                    help="time one whole Mamba-2 block (projections, convolution, scan, gated norm) under sequence checkpoints instead")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -361,6 +426,9 @@ def main():
         return
     if args.linear:
         linear_bench(args, cfg, pk, torch, dev)
+        return
+    if args.block:
+        block_bench(args, cfg, pk, torch, dev)
         return
     d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0

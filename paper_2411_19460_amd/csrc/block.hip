@@ -37,7 +37,7 @@ hipError_t copy_cols(void* dst, int64_t dst_rs, const void* src, int64_t src_rs,
     return hipGetLastError();
 }
 
-constexpr int DT_ROWS = 64;  // rows per workgroup of the dt kernels (granularity of the ddt_bias partial sums)
+constexpr int DT_ROWS = 16;  // rows per workgroup of the dt kernels (granularity of the ddt_bias partial sums)
 
 // dt[r,h] = softplus(raw[r,h] + bias[h]); raw is a column slice (rows raw_rs apart), dt dense
 __global__ __launch_bounds__(256) void k_dt_fwd(const bf16_t* raw, int64_t raw_rs, const float* bias, bf16_t* dt, int64_t rows, int H) {
@@ -72,13 +72,21 @@ __global__ __launch_bounds__(256) void k_dt_bwd(const bf16_t* raw, int64_t raw_r
     }
 }
 
-// out[h] (+)= sum_p part[p][h], in a fixed order
+// out[h] (+)= sum_p part[p][h], in a fixed order: a workgroup owns 64 columns, its four waves sum every
+// fourth part each, wave 0 adds the four results
 __global__ __launch_bounds__(256) void k_colsum(const float* part, int64_t nparts, int H, float* out, int accumulate) {
-    const int h = blockIdx.x * 256 + threadIdx.x;
-    if (h >= H) return;
+    __shared__ float red[4][64];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int h = blockIdx.x * 64 + lane;
     float s = 0.f;
-    for (int64_t p = 0; p < nparts; ++p) s += part[p * H + h];
-    out[h] = accumulate ? out[h] + s : s;
+    if (h < H)
+        for (int64_t p = wv; p < nparts; p += 4) s += part[p * H + h];
+    red[wv][lane] = s;
+    __syncthreads();
+    if (wv == 0 && h < H) {
+        s = (red[0][lane] + red[1][lane]) + (red[2][lane] + red[3][lane]);
+        out[h] = accumulate ? out[h] + s : s;
+    }
 }
 
 struct BlockDims {
@@ -347,7 +355,7 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
                            p->dt_bias, (const bf16_t*)(ws + w.ddt), (bf16_t*)(dzx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
                            (float*)(ws + w.dtpart), rows, d.H);
         BLK_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_colsum, dim3((d.H + 255) / 256), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H,
+        hipLaunchKernelGGL(k_colsum, dim3((d.H + 63) / 64), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H,
                            g->ddt_bias, 1);
         BLK_HIP(hipGetLastError());
         // convolution: (dx | dB | dC) side by side, du into the xBC columns of d zxbcdt

@@ -14,8 +14,9 @@ namespace ssdk {
 namespace {
 
 constexpr int CONV_K = 4;
-constexpr int FWD_TT = 64;    // tokens per thread, forward
-constexpr int BWD_TT = 256;   // tokens per thread, backward (also the granularity of the dw / dbias partial sums)
+constexpr int FWD_TT = 64;    // most tokens per thread, forward
+constexpr int BWD_TT = 256;   // most tokens per thread, backward (also the granularity of the dw / dbias partial sums)
+constexpr int MIN_TT = 16;    // shorter runs re-read too much of the three-token halo
 
 struct ConvParams {
     const void* u;
@@ -32,6 +33,7 @@ struct ConvParams {
     int64_t L, u_bs, o_bs;  // tokens; batch stride of u / du and of out / dout in elements
     int64_t u_rs;           // elements between consecutive tokens of u / du (out / dout: C)
     int C, ntiles;
+    int tt;             // tokens per thread of this launch
 };
 
 template <typename T, int V>
@@ -99,7 +101,7 @@ template <typename T, int V>
 __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
     const int c0 = (blockIdx.x * 64 + threadIdx.x) * V;
     if (c0 >= cp.C) return;
-    const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * FWD_TT;
+    const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * cp.tt;
     float w[V][CONV_K], bias[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
     float win[3][V];  // u[t-3], u[t-2], u[t-1]
 #pragma unroll
     for (int j = 0; j < 3; ++j) load_row<T, V>(cp, b, t0 - 3 + j, c0, win[j]);
-    const int64_t t1 = t0 + FWD_TT < cp.L ? t0 + FWD_TT : cp.L;
+    const int64_t t1 = t0 + cp.tt < cp.L ? t0 + cp.tt : cp.L;
     constexpr int U = 4;  // four rows requested together, then consumed in order
     for (int64_t t = t0; t < t1; t += U) {
         float cur[U][V];
@@ -146,7 +148,7 @@ template <typename T, int V>
 __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
     const int c0 = (blockIdx.x * 64 + threadIdx.x) * V;
     if (c0 >= cp.C) return;
-    const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * BWD_TT;
+    const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * cp.tt;
     float w[V][CONV_K], bias[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
@@ -167,7 +169,7 @@ __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
     for (int j = 0; j < 3; ++j)
 #pragma unroll
         for (int e = 0; e < V; ++e) gw[j][e] = 0.f;
-    const int64_t t1 = t0 + BWD_TT < cp.L ? t0 + BWD_TT : cp.L;  // own tokens: [t0, t1)
+    const int64_t t1 = t0 + cp.tt < cp.L ? t0 + cp.tt : cp.L;  // own tokens: [t0, t1)
     // the first tile also produces the gradient of the entering state, du[-3..-1]; its g window starts at 0 anyway
     const int64_t first_out = (t0 == 0 && cp.dstate_in) ? -3 : t0;
     // one token: g[t] from its rows of u and dout (zeros beyond the sequence), then du[t-3]
@@ -287,13 +289,24 @@ int check(const ssd_conv_shape_t* sh) {
     if (!sh) return SSD_ERR_NULL;
     if (sh->dtype != SSD_F32 && sh->dtype != SSD_BF16) return SSD_ERR_DTYPE;
     if (sh->batch <= 0 || sh->batch > 65535 || sh->seqlen < 0 || sh->channels <= 0) return SSD_ERR_SHAPE;
-    if ((sh->seqlen + FWD_TT - 1) / FWD_TT > 65535) return SSD_ERR_SHAPE;  // grid.y
+    if ((sh->seqlen + FWD_TT - 1) / FWD_TT > 65535) return SSD_ERR_SHAPE;  // grid.y (long sequences run FWD_TT tokens per thread)
     if (sh->u_row_stride && sh->u_row_stride < sh->channels) return SSD_ERR_SHAPE;
     if (sh->batch_stride && sh->batch_stride < sh->seqlen * (sh->u_row_stride ? sh->u_row_stride : sh->channels)) return SSD_ERR_SHAPE;
     return SSD_OK;
 }
 
-int ntiles_bwd(const ssd_conv_shape_t* sh) { return (int)((sh->seqlen + BWD_TT - 1) / BWD_TT); }
+// Tokens per thread: the most (fewest halo re-reads, fewest partial sums) that still gives the launch about
+// 2048 waves -- a segment-sized call would otherwise leave most of the machine idle.
+int pick_tt(const ssd_conv_shape_t* sh, int most) {
+    const int64_t col_waves = ((int64_t)sh->channels / 8 + 63) / 64 * sh->batch;  // waves per token tile
+    int tt = most;
+    while (tt > MIN_TT && (sh->seqlen + tt - 1) / tt * col_waves < 2048) tt >>= 1;
+    return tt;
+}
+int ntiles_bwd(const ssd_conv_shape_t* sh) {
+    const int tt = pick_tt(sh, BWD_TT);
+    return (int)((sh->seqlen + tt - 1) / tt);
+}
 
 }  // namespace
 }  // namespace ssdk
@@ -329,7 +342,8 @@ extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const f
     const bool bf = sh->dtype == SSD_BF16;
     const int V = bf ? ((cp.C | cp.u_rs) % 8 == 0 ? 8 : 1) : ((cp.C | cp.u_rs) % 4 == 0 ? 4 : 1);
     // an empty sequence still hands the state on: one tile, whose token loop is empty
-    const dim3 grid((cp.C / V + 63) / 64, (unsigned)(cp.L > 0 ? (cp.L + FWD_TT - 1) / FWD_TT : 1), (unsigned)sh->batch);
+    cp.tt = pick_tt(sh, FWD_TT);
+    const dim3 grid((cp.C / V + 63) / 64, (unsigned)(cp.L > 0 ? (cp.L + cp.tt - 1) / cp.tt : 1), (unsigned)sh->batch);
     if (bf && V == 8) hipLaunchKernelGGL((k_conv_fwd<bf16_t, 8>), grid, dim3(64), 0, st, cp);
     else if (bf) hipLaunchKernelGGL((k_conv_fwd<bf16_t, 1>), grid, dim3(64), 0, st, cp);
     else if (V == 4) hipLaunchKernelGGL((k_conv_fwd<float, 4>), grid, dim3(64), 0, st, cp);
@@ -364,6 +378,7 @@ extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const f
     cp.u_rs = sh->u_row_stride ? sh->u_row_stride : sh->channels;
     cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * cp.u_rs;
     cp.o_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
+    cp.tt = pick_tt(sh, BWD_TT);
     cp.ntiles = ntiles_bwd(sh) > 0 ? ntiles_bwd(sh) : 1;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = sh->dtype == SSD_BF16;

@@ -340,16 +340,18 @@ FastCfg pick_fast(const NormDims& d, std::initializer_list<const void*> ptrs) {
 // Tiling of the rows for the register-resident kernels.  Backward: 64-row tiles, every tile its own
 // workgroup up to about three workgroups per compute unit, beyond that equal shares of tiles (fewer partial
 // sums of dw, the weight loaded once per workgroup).  Forward: no partial sums, registers for five
-// workgroups per compute unit: 16-row tiles.
+// workgroups per compute unit: 16-row tiles.  Short calls take smaller tiles.
 struct FastGrid {
     int tile_rows, ntiles, nwg;
 };
 FastGrid fast_grid(const NormDims& d, bool bwd) {
     FastGrid g;
-    g.tile_rows = bwd ? ROWS_PER_WG : ROWS_PER_WG_FWD;
-    g.ntiles = (int)((d.T + g.tile_rows - 1) / g.tile_rows);
     const int per_cu = bwd ? 3 : 5;
     const int target = 256 * per_cu / d.G > 0 ? 256 * per_cu / d.G : 1;
+    // fewer rows per tile when the call is short (a segment at a time), so that it still fills the machine
+    g.tile_rows = bwd ? ROWS_PER_WG : ROWS_PER_WG_FWD;
+    while (g.tile_rows > 4 && (d.T + g.tile_rows - 1) / g.tile_rows < target) g.tile_rows >>= 1;
+    g.ntiles = (int)((d.T + g.tile_rows - 1) / g.tile_rows);
     if (g.ntiles <= target) {
         g.nwg = g.ntiles;
     } else {
@@ -418,7 +420,11 @@ using namespace ssdk;
 extern "C" size_t ssd_gated_norm_workspace_bytes(const ssd_norm_shape_t* sh) {
     NormDims d;
     if (check(sh, &d) != SSD_OK) return 0;
-    const size_t n = (size_t)(d.ntiles > 0 ? d.ntiles : 1) * 4 * (size_t)d.C * 4;
+    // partial rows of dw: four per 64-row tile (element-wise kernel) or up to four per workgroup (register-resident one)
+    size_t rows = (size_t)(d.ntiles > 0 ? d.ntiles : 1);
+    const size_t fast = d.T > 0 ? (size_t)fast_grid(d, true).nwg : 0;
+    rows = fast > rows ? fast : rows;
+    const size_t n = rows * 4 * (size_t)d.C * 4;
     return (n + 255) & ~(size_t)255;
 }
 
@@ -462,8 +468,9 @@ extern "C" int ssd_gated_norm_bwd(const ssd_norm_shape_t* sh, const void* y, con
     np.dz = dz;
     np.part = (float*)workspace;
     const FastCfg f = pick_fast(d, {y, z, dout, dy, dz});
-    if (launch<true>(d, np, f, st) != hipSuccess) return SSD_ERR_LAUNCH;
     const int64_t nparts = f.vpl ? (int64_t)fast_grid(d, true).nwg * (4 / f.wps) : (int64_t)d.ntiles * 4;
+    if ((size_t)nparts * d.C * 4 > workspace_bytes) return SSD_ERR_WORKSPACE;  // cannot happen with the documented size
+    if (launch<true>(d, np, f, st) != hipSuccess) return SSD_ERR_LAUNCH;
     hipLaunchKernelGGL(k_norm_reduce, dim3((d.C + 63) / 64), dim3(256), 0, st, np.part, nparts, d.C, dw, accumulate);
     return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
 }
