@@ -111,6 +111,43 @@ def test_stack_validation():
     assert pk.magc_stack_workspace_bytes(sh, 8, 8, True) > pk.magc_stack_workspace_bytes(sh, 8, 2, True)
 
 
+ERR_NULL, ERR_SHAPE, ERR_DIVISIBILITY, ERR_ARG = -1, -2, -3, -8   # as in include/ssd_magc.h
+
+
+def test_block_pieces_validate_before_any_launch():
+    # every check below fails (or sizes a workspace) on the host; nothing is launched
+    L = binding.lib()
+    fake = ctypes.c_void_p(0x1000)
+    cs = binding.ssd_conv_shape_t(1, 64, 1, 128, 0, 0)
+    assert L.ssd_conv1d_workspace_bytes(ctypes.byref(cs)) > 0
+    assert L.ssd_conv1d_workspace_bytes(ctypes.byref(binding.ssd_conv_shape_t(7, 64, 1, 128, 0, 0))) == 0      # dtype
+    assert L.ssd_conv1d_workspace_bytes(ctypes.byref(binding.ssd_conv_shape_t(1, 64, 1, 128, 0, 32))) == 0     # row stride below C
+    assert L.ssd_conv1d_fwd(ctypes.byref(cs), fake, None, None, None, fake, None, None) == ERR_NULL
+    ns = binding.ssd_norm_shape_t(1, 64, 4, 1e-5, 128, 0, 0)
+    assert L.ssd_gated_norm_workspace_bytes(ctypes.byref(ns)) > 0
+    assert L.ssd_gated_norm_workspace_bytes(ctypes.byref(binding.ssd_norm_shape_t(1, 64, 5, 1e-5, 128, 0, 0))) == 0   # 64 % 5
+    assert L.ssd_gated_norm_workspace_bytes(ctypes.byref(binding.ssd_norm_shape_t(1, 64, 4, -1.0, 128, 0, 0))) == 0   # eps < 0
+    assert L.ssd_gated_norm_fwd(ctypes.byref(binding.ssd_norm_shape_t(1, 64, 4, 1e-5, 128, 32, 0)), fake, fake, fake, fake, None) \
+        == ERR_SHAPE                                                                                   # stride below dim
+    assert L.ssd_gated_norm_fwd(ctypes.byref(ns), None, fake, fake, fake, None) == ERR_NULL
+    assert L.ssd_linear_fwd(16, 12, 8, fake, 0, fake, fake, 0, None) == ERR_DIVISIBILITY             # 12 % 8
+    assert L.ssd_linear_fwd(16, 16, 8, fake, 8, fake, fake, 0, None) == ERR_SHAPE                     # stride below in_dim
+    assert L.ssd_linear_fwd(16, 16, 8, ctypes.c_void_p(0x1004), 0, fake, fake, 0, None) == ERR_ARG    # alignment
+    assert L.ssd_linear_fwd(16, 16, 8, None, 0, fake, fake, 0, None) == ERR_NULL
+    assert L.ssd_linear_bwd(16, 16, 8, fake, 0, fake, fake, 0, fake, 0, fake, 64, None) == ERR_ARG    # unknown flag
+    bs = binding.magc_block_shape_t(2560, 80, 64, 1, 128, 256, 1e-5, 65536, 4096)
+    full = binding.magc_block_shape_t(2560, 80, 64, 1, 128, 256, 1e-5, 65536, 65536)
+    w_seg, w_full = (L.magc_block_workspace_bytes(ctypes.byref(x), 1) for x in (bs, full))
+    assert 0 < w_seg < w_full / 8                                     # the workspace scales with the segment
+    assert L.magc_block_workspace_bytes(ctypes.byref(bs), 0) < w_seg
+    assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 4, 64, 1, 128, 256, 1e-5, 1024, 512)), 1) == 0   # H % 8
+    assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 80, 64, 1, 128, 256, 1e-5, 1024, 300)), 1) == 0  # segment % chunk
+    par, gr = binding.magc_block_params_t(), binding.magc_block_grads_t()
+    assert L.magc_block_fwd(ctypes.byref(bs), ctypes.byref(par), fake, fake, fake, fake, None, None, fake, 1 << 40, None) == ERR_NULL
+    assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(par), fake, fake, fake, fake, fake, ctypes.byref(gr), fake, 1 << 40, 0, None) \
+        == ERR_NULL
+
+
 CASES = [
     (512, 512, 1, 1, 1, 0, 1, 0, False),
     (4, 1024, 1, 1, 1, 0, 1, 0, False),
