@@ -231,8 +231,8 @@ __global__ __launch_bounds__(256, DB ? 1 : 2) void k_gemm(GemmParams gp) {
 // 256 x 256 tile, four waves of 128 x 128 (4 x 4 MFMA tiles: the whole accumulator register file), one
 // workgroup per compute unit, two LDS buffers.  With a single wave per SIMD nothing else hides latency, so
 // the K step is laid out by hand as 16 units of four MFMAs (one A operand against the four B operands of
-// its k slice): each unit first issues the LDS reads of the next unit's operands, then (last four units)
-// its share of the next tile's LDS writes and of the global loads for the tile after that, then its MFMAs.
+// its k slice); behind each MFMA sit the LDS reads of later operands and (last four units) one vector of
+// the next tile's LDS writes with the global load that refills its register for the tile after that.
 // Registers thus hold the tile two K steps ahead of the one being multiplied: a vector is written to LDS
 // in the second half of a step and its register is refilled at once, so that a load has a whole step of
 // MFMA time to arrive.
@@ -265,39 +265,44 @@ __device__ __forceinline__ void big_step(const BigCtx& cx, f32x16 (&acc)[4][4], 
     aq[0] = operand<BM, AK>(As, cx.wm * 128, 0, lane);
 #pragma unroll
     for (int j = 0; j < 4; ++j) bq[0][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, 0, lane);
+    // An MFMA keeps the matrix pipe busy for 32 cycles but takes only a few to issue: every memory
+    // instruction is placed right behind an MFMA, so that it issues in that MFMA's shadow.
 #pragma unroll
     for (int u = 0; u < 16; ++u) {
         const int kk = u >> 2, i = u & 3;
-        if (u + 1 < 16) aq[(u + 1) & 1] = operand<BM, AK>(As, cx.wm * 128 + ((u + 1) & 3) * 32, ((u + 1) >> 2) * 16, lane);
-        if (i == 1 && kk < 3) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j) bq[(kk + 1) & 1][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, (kk + 1) * 16, lane);
-        }
-        if (STEADY) {
-            // units 12..15: two vectors of each operand per unit
-#define GEMM_PART(P)                                                                     \
-    if (u == 12 + P / 2) {                                                               \
-        store_tile<BM, AK, P, P + 2>(An, tid, ra);                                       \
-        store_tile<BN, BK, P, P + 2>(Bn, tid, rb);                                       \
-        load_tile<BM, AK, false, P, P + 2>(ao, cx.lda, cx.va, 0, 0, tid, ra);            \
-        load_tile<BN, BK, false, P, P + 2>(bo, cx.ldb, cx.vb, 0, 0, tid, rb);            \
+        for (int j = 0; j < 4; ++j) {
+            acc[i][j] = mfma(bq[kk & 1][j], aq[u & 1], acc[i][j]);
+            // operand reads: the next unit's A operand, and over unit 1 of a k slice the next slice's B operands
+            if (j == 0 && u + 1 < 16) aq[(u + 1) & 1] = operand<BM, AK>(As, cx.wm * 128 + ((u + 1) & 3) * 32, ((u + 1) >> 2) * 16, lane);
+            if (i == 1 && kk < 3) bq[(kk + 1) & 1][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, (kk + 1) * 16, lane);
+            if (STEADY) {
+                // units 12..15: one vector per MFMA goes to LDS and its register is refilled (A, A, B, B per unit)
+#define GEMM_PART(U, J, OP_A, V)                                                                  \
+    if (u == U && j == J) {                                                                       \
+        if (OP_A) {                                                                               \
+            store_tile<BM, AK, V, V + 1>(An, tid, ra);                                            \
+            load_tile<BM, AK, false, V, V + 1>(ao, cx.lda, cx.va, 0, 0, tid, ra);                 \
+        } else {                                                                                  \
+            store_tile<BN, BK, V, V + 1>(Bn, tid, rb);                                            \
+            load_tile<BN, BK, false, V, V + 1>(bo, cx.ldb, cx.vb, 0, 0, tid, rb);                 \
+        }                                                                                         \
     }
-            GEMM_PART(0)
-            GEMM_PART(2)
-            GEMM_PART(4)
-            GEMM_PART(6)
+                GEMM_PART(12, 0, true, 0) GEMM_PART(12, 1, true, 1) GEMM_PART(12, 2, false, 0) GEMM_PART(12, 3, false, 1)
+                GEMM_PART(13, 0, true, 2) GEMM_PART(13, 1, true, 3) GEMM_PART(13, 2, false, 2) GEMM_PART(13, 3, false, 3)
+                GEMM_PART(14, 0, true, 4) GEMM_PART(14, 1, true, 5) GEMM_PART(14, 2, false, 4) GEMM_PART(14, 3, false, 5)
+                GEMM_PART(15, 0, true, 6) GEMM_PART(15, 1, true, 7) GEMM_PART(15, 2, false, 6) GEMM_PART(15, 3, false, 7)
 #undef GEMM_PART
-        } else if (u == 8 && more) {
-            store_tile<BM, AK>(An, tid, ra);
-            store_tile<BN, BK>(Bn, tid, rb);
-            if (more2) {
-                load_tile<BM, AK, true>(ao, cx.lda, cx.va, cx.rows_a, cx.K - k2, tid, ra);
-                load_tile<BN, BK, true>(bo, cx.ldb, cx.vb, cx.rows_b, cx.K - k2, tid, rb);
+            } else if (u == 8 && j == 0 && more) {
+                store_tile<BM, AK>(An, tid, ra);
+                store_tile<BN, BK>(Bn, tid, rb);
+                if (more2) {
+                    load_tile<BM, AK, true>(ao, cx.lda, cx.va, cx.rows_a, cx.K - k2, tid, ra);
+                    load_tile<BN, BK, true>(bo, cx.ldb, cx.vb, cx.rows_b, cx.K - k2, tid, rb);
+                }
             }
+            __builtin_amdgcn_sched_barrier(0);
         }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = mfma(bq[kk & 1][j], aq[u & 1], acc[i][j]);
-        __builtin_amdgcn_sched_barrier(0);
     }
 }
 
@@ -374,7 +379,34 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(GemmParams gp) {
         __syncthreads();
     }
 
-    store_acc<4, 4>(gp, acc, m0 + wm * 128, n0 + wn * 128, lane, interior);
+    if (gp.c_f32) {  // weight gradients: K is the token count, the epilogue does not matter
+        store_acc<4, 4>(gp, acc, m0 + wm * 128, n0 + wn * 128, lane, interior);
+        return;
+    }
+    // bf16 result: through LDS (free now; every wave has left the K loop behind the last barrier), so that
+    // a store instruction writes whole 256-byte row pieces instead of 32 scattered 16-byte ones.  Each wave
+    // transposes its own 128 x 128 tile in a private patch: lane -> row lane % 32, four consecutive columns
+    // per register group (see store_acc) on the way in, 16-byte vectors of a row on the way out.
+    constexpr int EPITCH = 256 + 16;
+    char* patch = lds + w * (128 * EPITCH);
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const f32x16& t = acc[i][j];
+                bf16x4 v;
+                v[0] = (__bf16)t[4 * q]; v[1] = (__bf16)t[4 * q + 1]; v[2] = (__bf16)t[4 * q + 2]; v[3] = (__bf16)t[4 * q + 3];
+                *(bf16x4*)(patch + (i * 32 + (lane & 31)) * EPITCH + (j * 32 + q * 8 + (lane >> 5) * 4) * 2) = v;
+            }
+    const int col = n0 + wn * 128 + (lane & 15) * 8;
+#pragma unroll 8
+    for (int it = 0; it < 32; ++it) {
+        const int r = it * 4 + (lane >> 4), row = m0 + wm * 128 + r;
+        const bf16x8 v = *(const bf16x8*)(patch + r * EPITCH + (lane & 15) * 16);
+        if (interior || (row < gp.M && col < gp.N)) *(bf16x8*)((__bf16*)gp.C + (int64_t)row * gp.ldc + col) = v;
+    }
 }
 
 bool ok_ptr(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
