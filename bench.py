@@ -316,6 +316,42 @@ def block_bench(args, cfg, pk, torch, dev):
            "dt_bias": dt0 + torch.log(-torch.expm1(-dt0)), "A": -torch.exp(torch.empty(H, device=dev).uniform_(0.0, math.log(16.0), generator=g)),
            "D": rn(H), "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5).to(torch.bfloat16)}
     u, dout = rn(L, dm).to(torch.bfloat16), rn(L, dm).to(torch.bfloat16)
+    if args.inference:
+        # forward only, no checkpoint kept: the prompt in segments, then one token per call from the carried states
+        def prefill():
+            return pk.magc_block_fwd(u, par, H, P, G, N, cfg.chunk, cfg.segment, checkpoints=False)
+        for _ in range(args.warmup):
+            prefill()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            f = prefill()
+        torch.cuda.synchronize()
+        ms_p = (time.perf_counter() - t0) * 1e3 / args.steps
+        ntok = 64
+        tok = u[:1].contiguous()
+        for rep in range(2):   # the second pass is the timed one
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            st = f
+            for _ in range(ntok):
+                st = pk.magc_block_fwd(tok, par, H, P, G, N, cfg.chunk, cfg.segment, init_ssm=st["final_ssm"],
+                                       init_conv=st["final_conv"], checkpoints=False)
+            torch.cuda.synchronize()
+            us_tok = (time.perf_counter() - t0) * 1e6 / ntok
+        shp = pk.binding.magc_block_shape_t(dm, H, P, G, N, cfg.chunk, 1e-5, L, cfg.segment)
+        print(json.dumps({
+            "metric": "Mamba-2 block prefill tokens/sec/layer", "value": L / (ms_p * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+            "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_p, "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": cfg.name + "_block_prefill", "seqlen": L, "d_model": dm, "segment": cfg.segment},
+            "roofline": {"bound": "mfma", "achieved": 2.0 * (dm * d_in_proj + d_inner * dm) * L / (ms_p * 1e-3) / 1e12,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": 2.0 * (dm * d_in_proj + d_inner * dm) * L / (ms_p * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+            "generation": {"us_per_token": us_tok, "tokens": ntok, "note": "one call per token from the host, ten launches each"},
+            "workspace_bytes": int(pk.lib().magc_block_workspace_bytes(ctypes.byref(shp), 0)),
+        }))
+        return
     grads = {"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in par.items()}
     f = {}
 
@@ -415,6 +451,9 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.block:
+        block_bench(args, cfg, pk, torch, dev)
+        return
     if args.inference:
         inference_bench(args, cfg, pk, synth, torch, dev)
         return

@@ -264,10 +264,18 @@ int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  * activations C_grid counts, live there for one segment at a time), then differentiated step by
  * step; the adjoints of the two states travel left.
  *   u, out, dout, du [L, d_model] bf16, dense
+ *   init_ssm [H,P,N] fp32, init_conv [3, d_inner + 2 G N] bf16: the states entering the sequence, NULL = zeros
+ *   final_ssm, final_conv: the states leaving it (same shapes), may be NULL; must not alias the initial ones
  *   ssm_ckpt  [nseg, H, P, N] fp32 and conv_ckpt [nseg, 3, d_inner + 2 G N] bf16: slot k = the states
- *             entering segment k (slot 0 is not used: the sequence starts from zero states); written
- *             by magc_block_fwd, read by magc_block_bwd; may be NULL when nseg == 1
- *   final_ssm [H,P,N] fp32, final_conv [3, d_inner + 2 G N] bf16: the states leaving the sequence, may be NULL
+ *             entering segment k (slot 0 is not used); written by magc_block_fwd, read by magc_block_bwd.
+ *             Both NULL in magc_block_fwd: no checkpoint is kept (inference; the states travel from segment
+ *             to segment inside the workspace, memory does not grow with seqlen) -- prefill of a long
+ *             sequence, and with seqlen of a few tokens and init = the previous call's final states,
+ *             generation (calls of at most 16 tokens run the scan as the plain recurrence of Eq. 1).
+ *             magc_block_bwd needs them unless nseg == 1.
+ *   dfinal_ssm [H,P,N], dfinal_conv [3, d_inner + 2 G N] fp32: adjoints of the final states, NULL = zeros;
+ *   dinit_ssm, dinit_conv: adjoints of the initial states (same shapes, fp32), may be NULL.  With them a
+ *             caller can cut a sequence into pieces of its own and chain the calls, as the block does inside.
  *   params: W_in [d_in_proj, d_model] bf16, conv_w [conv_dim, 4], conv_b [conv_dim], dt_bias [H], A [H],
  *           D [H], norm_w [d_inner] fp32, W_out [d_model, d_inner] bf16
  *   grads:  the same shapes, all fp32, overwritten or added to under SSD_FLAG_ACCUM_PARAM (the only flag)
@@ -301,12 +309,14 @@ typedef struct {
     float* dW_out;
 } magc_block_grads_t;
 size_t magc_block_workspace_bytes(const magc_block_shape_t* shape, int32_t is_backward);
-int magc_block_fwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u, void* out,
-                   float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv, void* workspace,
-                   size_t workspace_bytes, void* hip_stream);
-int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u, const void* dout,
-                   const float* ssm_ckpt, const void* conv_ckpt, void* du, const magc_block_grads_t* grads,
-                   void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
+int magc_block_fwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u,
+                   const float* init_ssm, const void* init_conv, void* out, float* ssm_ckpt, void* conv_ckpt,
+                   float* final_ssm, void* final_conv, void* workspace, size_t workspace_bytes, void* hip_stream);
+int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u,
+                   const float* init_ssm, const void* init_conv, const void* dout, const float* dfinal_ssm,
+                   const float* dfinal_conv, const float* ssm_ckpt, const void* conv_ckpt, void* du,
+                   const magc_block_grads_t* grads, float* dinit_ssm, float* dinit_conv, void* workspace,
+                   size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /*
  * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the

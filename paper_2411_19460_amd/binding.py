@@ -120,9 +120,9 @@ def lib():
         L.magc_block_workspace_bytes.restype = sz
         L.magc_block_workspace_bytes.argtypes = [bshp, i32]
         L.magc_block_fwd.restype = ctypes.c_int
-        L.magc_block_fwd.argtypes = [bshp, bpar] + [vp] * 6 + [vp, sz, vp]
+        L.magc_block_fwd.argtypes = [bshp, bpar] + [vp] * 8 + [vp, sz, vp]
         L.magc_block_bwd.restype = ctypes.c_int
-        L.magc_block_bwd.argtypes = [bshp, bpar] + [vp] * 5 + [bgr, vp, sz, u32, vp]
+        L.magc_block_bwd.argtypes = [bshp, bpar] + [vp] * 9 + [bgr, vp, vp, vp, sz, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -434,30 +434,43 @@ def _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, ep
     return shape, par, want, nseg, conv_dim
 
 
-def magc_block_fwd(u, params, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5):
-    """One Mamba-2 block over u [L, d_model] with sequence checkpoints every `segment` tokens.
+def _block_states(init_ssm, init_conv, nheads, headdim, dstate, conv_dim, conv_dtype):
+    import torch
+    for t, shp, dty in ((init_ssm, (nheads, headdim, dstate), torch.float32), (init_conv, (3, conv_dim), conv_dtype)):
+        if t is not None and (tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous()):
+            raise ValueError(f"state tensor must be a dense {dty} device tensor of shape {shp}")
+
+
+def magc_block_fwd(u, params, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5, init_ssm=None, init_conv=None,
+                   checkpoints=True):
+    """One Mamba-2 block over u [L, d_model] from the states (init_ssm, init_conv) (None = zeros), with sequence
+    checkpoints every `segment` tokens, or none at all (checkpoints=False: prefill / generation).
     Returns dict(out, ssm_ckpt, conv_ckpt, final_ssm, final_conv)."""
     import torch
     shape, par, _, nseg, conv_dim = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    _block_states(init_ssm, init_conv, nheads, headdim, dstate, conv_dim, torch.bfloat16)
     dev = u.device
     out = torch.empty_like(u)
-    ssm_ckpt = torch.zeros((nseg, nheads, headdim, dstate), dtype=torch.float32, device=dev)
-    conv_ckpt = torch.zeros((nseg, 3, conv_dim), dtype=torch.bfloat16, device=dev)
+    ssm_ckpt = torch.zeros((nseg, nheads, headdim, dstate), dtype=torch.float32, device=dev) if checkpoints else None
+    conv_ckpt = torch.zeros((nseg, 3, conv_dim), dtype=torch.bfloat16, device=dev) if checkpoints else None
     final_ssm = torch.empty((nheads, headdim, dstate), dtype=torch.float32, device=dev)
     final_conv = torch.empty((3, conv_dim), dtype=torch.bfloat16, device=dev)
     ws = _workspace(int(lib().magc_block_workspace_bytes(ctypes.byref(shape), 0)), dev)
-    rc = lib().magc_block_fwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(out), _ptr(ssm_ckpt), _ptr(conv_ckpt),
-                              _ptr(final_ssm), _ptr(final_conv), _ptr(ws), ws.numel(), _stream(u))
+    rc = lib().magc_block_fwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(init_ssm), _ptr(init_conv), _ptr(out),
+                              _ptr(ssm_ckpt), _ptr(conv_ckpt), _ptr(final_ssm), _ptr(final_conv), _ptr(ws), ws.numel(), _stream(u))
     if rc != 0:
         raise SSDError(rc, "magc_block_fwd")
     return {"out": out, "ssm_ckpt": ssm_ckpt, "conv_ckpt": conv_ckpt, "final_ssm": final_ssm, "final_conv": final_conv}
 
 
 def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5,
-                   flags=0, grads=None):
-    """dict(du, dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out) for the loss <dout, out>."""
+                   flags=0, grads=None, init_ssm=None, init_conv=None, dfinal_ssm=None, dfinal_conv=None, want_dinit=False):
+    """dict(du, dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out[, dinit_ssm, dinit_conv]) for the loss
+    <dout, out> + <dfinal_ssm, final_ssm> + <dfinal_conv, final_conv>."""
     import torch
-    shape, par, want, nseg, _ = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    shape, par, want, nseg, conv_dim = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    _block_states(init_ssm, init_conv, nheads, headdim, dstate, conv_dim, torch.bfloat16)
+    _block_states(dfinal_ssm, dfinal_conv, nheads, headdim, dstate, conv_dim, torch.float32)
     if dout.shape != u.shape or dout.dtype != u.dtype or not dout.is_cuda or not dout.is_contiguous():
         raise ValueError("dout must match u")
     dev = u.device
@@ -469,12 +482,18 @@ def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroup
             raise ValueError(f"grads['d{k}'] must be a dense fp32 device tensor of shape {shp}")
     gr = magc_block_grads_t(*[_ptr(grads["d" + k]) for k in BLOCK_PARAMS])
     du = torch.empty_like(u)
+    dinit_ssm = torch.empty((nheads, headdim, dstate), dtype=torch.float32, device=dev) if want_dinit else None
+    dinit_conv = torch.empty((3, conv_dim), dtype=torch.float32, device=dev) if want_dinit else None
     ws = _workspace(int(lib().magc_block_workspace_bytes(ctypes.byref(shape), 1)), dev)
-    rc = lib().magc_block_bwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(dout), _ptr(ssm_ckpt), _ptr(conv_ckpt), _ptr(du),
-                              ctypes.byref(gr), _ptr(ws), ws.numel(), flags, _stream(u))
+    rc = lib().magc_block_bwd(ctypes.byref(shape), ctypes.byref(par), _ptr(u), _ptr(init_ssm), _ptr(init_conv), _ptr(dout),
+                              _ptr(dfinal_ssm), _ptr(dfinal_conv), _ptr(ssm_ckpt), _ptr(conv_ckpt), _ptr(du), ctypes.byref(gr),
+                              _ptr(dinit_ssm), _ptr(dinit_conv), _ptr(ws), ws.numel(), flags, _stream(u))
     if rc != 0:
         raise SSDError(rc, "magc_block_bwd")
-    return {"du": du, **grads}
+    res = {"du": du, **grads}
+    if want_dinit:
+        res.update(dinit_ssm=dinit_ssm, dinit_conv=dinit_conv)
+    return res
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,

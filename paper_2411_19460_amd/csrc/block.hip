@@ -37,6 +37,7 @@ hipError_t copy_cols(void* dst, int64_t dst_rs, const void* src, int64_t src_rs,
     return hipGetLastError();
 }
 
+constexpr int DECODE_ROWS = 16;  // calls of at most this many tokens run the scan as the plain recurrence
 constexpr int DT_ROWS = 16;  // rows per workgroup of the dt kernels (granularity of the ddt_bias partial sums)
 
 // dt[r,h] = softplus(raw[r,h] + bias[h]); raw is a column slice (rows raw_rs apart), dt dense
@@ -169,6 +170,7 @@ struct BlockWs {
     size_t zx, xbc, x, B, C, dt, y, yn;                     // forward activations of the segment
     size_t dyn, dy, dzx, dxbc, dx, dB, dC, ddt;             // backward
     size_t dssm[2], dconv[2], dtpart, inner, total;
+    size_t cssm[2], cconv[2];                               // states handed from segment to segment when no checkpoints are kept
     size_t inner_bytes;
 };
 
@@ -217,6 +219,8 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         inner = b > inner ? b : inner;
         inner = c > inner ? c : inner;
     }
+    for (int i = 0; i < 2; ++i) w.cssm[i] = take(d.HPN * 4);
+    for (int i = 0; i < 2; ++i) w.cconv[i] = take((size_t)3 * d.conv_dim * 2);
     w.inner = take(inner);
     w.inner_bytes = inner;
     w.total = off;
@@ -248,8 +252,15 @@ int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc
                        (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj, p->dt_bias, (bf16_t*)(ws + w.dt), rows, d.H);
     BLK_HIP(hipGetLastError());
     const ssd_shape_t ss = seg_shape(d, rows);
-    BLK_TRY(ssd_fwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.y, ssm_out, nullptr, ws + w.inner,
-                    w.inner_bytes, 0, st));
+    if (rows <= DECODE_ROWS && ssm_out) {
+        // a few tokens (generation): the recurrence token by token on the state itself instead of a padded chunk
+        if (ssm_in != ssm_out)
+            BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
+        BLK_TRY(ssd_decode(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, ws + w.y, 0, st));
+    } else {
+        BLK_TRY(ssd_fwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.y, ssm_out, nullptr, ws + w.inner,
+                        w.inner_bytes, 0, st));
+    }
     const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
     BLK_TRY(ssd_gated_norm_fwd(&ns, ws + w.y, zx, p->norm_w, ws + w.yn, st));
     return SSD_OK;
@@ -268,39 +279,44 @@ extern "C" size_t magc_block_workspace_bytes(const magc_block_shape_t* sh, int32
     return layout(d, is_backward != 0).total;
 }
 
-extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, void* out, float* ssm_ckpt,
-                              void* conv_ckpt, float* final_ssm, void* final_conv, void* workspace, size_t workspace_bytes,
-                              void* hip_stream) {
+extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
+                              const void* init_conv, void* out, float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
     BlockDims d;
     BLK_TRY(check(sh, &d));
     if (!p || !p->W_in || !p->conv_w || !p->conv_b || !p->dt_bias || !p->A || !p->D || !p->norm_w || !p->W_out) return SSD_ERR_NULL;
+    if ((ssm_ckpt == nullptr) != (conv_ckpt == nullptr)) return SSD_ERR_NULL;  // both kinds of checkpoint or none
     hipStream_t st = (hipStream_t)hip_stream;
-    if (d.L == 0) {  // nothing to do: the (zero) states pass through
-        if (final_ssm) BLK_HIP(launch_fill_zero(final_ssm, d.HPN, st));
-        if (final_conv) BLK_HIP(launch_fill_zero((float*)final_conv, (size_t)3 * d.conv_dim / 2, st));  // bf16 zeros
+    const size_t conv_state_bytes = (size_t)3 * d.conv_dim * 2;
+    if (d.L == 0) {  // nothing to do: the states pass through
+        if (final_ssm) BLK_HIP(init_ssm ? launch_copy_f32(final_ssm, init_ssm, d.HPN, st) : launch_fill_zero(final_ssm, d.HPN, st));
+        if (final_conv)  // bf16 values moved as 32-bit words
+            BLK_HIP(init_conv ? launch_copy_f32((float*)final_conv, (const float*)init_conv, conv_state_bytes / 4, st)
+                              : launch_fill_zero((float*)final_conv, conv_state_bytes / 4, st));
         return SSD_OK;
     }
-    if (!u || !out || (d.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
+    if (!u || !out) return SSD_ERR_NULL;
     const BlockWs w = layout(d, false);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
     char* ws = (char*)workspace;
-    const size_t conv_state_bytes = (size_t)3 * d.conv_dim * 2;
     for (int64_t k = 0; k < d.nseg; ++k) {
         const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
         const bool last = k + 1 == d.nseg;
-        const float* ssm_in = k ? ssm_ckpt + (size_t)k * d.HPN : nullptr;  // segment 0 starts from zeros
-        const void* conv_in = k ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : nullptr;
-        float* ssm_out = last ? final_ssm : ssm_ckpt + (size_t)(k + 1) * d.HPN;
-        void* conv_out = last ? final_conv : (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes;
+        // entering states: the caller's for segment 0, else the checkpoint, or (none kept) what the last segment left
+        const float* ssm_in = k == 0 ? init_ssm : ssm_ckpt ? ssm_ckpt + (size_t)k * d.HPN : (const float*)(ws + w.cssm[k & 1]);
+        const void* conv_in = k == 0 ? init_conv : conv_ckpt ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : ws + w.cconv[k & 1];
+        float* ssm_out = last ? final_ssm : ssm_ckpt ? ssm_ckpt + (size_t)(k + 1) * d.HPN : (float*)(ws + w.cssm[(k + 1) & 1]);
+        void* conv_out = last ? final_conv : conv_ckpt ? (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes : ws + w.cconv[(k + 1) & 1];
         BLK_TRY(forward_segment(d, sh, p, ws, w, (const char*)u + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, ssm_out, conv_out, st));
         BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (char*)out + (size_t)t0 * d.dm * 2, 0, st));
     }
     return SSD_OK;
 }
 
-extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const void* dout,
-                              const float* ssm_ckpt, const void* conv_ckpt, void* du, const magc_block_grads_t* g, void* workspace,
-                              size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
+                              const void* init_conv, const void* dout, const float* dfinal_ssm, const float* dfinal_conv,
+                              const float* ssm_ckpt, const void* conv_ckpt, void* du, const magc_block_grads_t* g, float* dinit_ssm,
+                              float* dinit_conv, void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream) {
     BlockDims d;
     BLK_TRY(check(sh, &d));
     if (flags & ~(uint32_t)SSD_FLAG_ACCUM_PARAM) return SSD_ERR_ARG;
@@ -317,7 +333,13 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
         BLK_HIP(launch_fill_zero(g->dnorm_w, (size_t)d.d_inner, st));
         BLK_HIP(launch_fill_zero(g->dW_out, (size_t)d.dm * d.d_inner, st));
     }
-    if (d.L == 0) return SSD_OK;
+    if (d.L == 0) {  // the state adjoints pass through
+        if (dinit_ssm) BLK_HIP(dfinal_ssm ? launch_copy_f32(dinit_ssm, dfinal_ssm, d.HPN, st) : launch_fill_zero(dinit_ssm, d.HPN, st));
+        if (dinit_conv)
+            BLK_HIP(dfinal_conv ? launch_copy_f32(dinit_conv, dfinal_conv, (size_t)3 * d.conv_dim, st)
+                                : launch_fill_zero(dinit_conv, (size_t)3 * d.conv_dim, st));
+        return SSD_OK;
+    }
     if (!u || !dout || !du || (d.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
     const BlockWs w = layout(d, true);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
@@ -329,13 +351,13 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
     for (int64_t k = d.nseg - 1; k >= 0; --k) {
         const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
         const bool last = k + 1 == d.nseg;
-        const float* ssm_in = k ? ssm_ckpt + (size_t)k * d.HPN : nullptr;
-        const void* conv_in = k ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : nullptr;
-        // adjoints of the states leaving this segment (none behind the last one) / entering it
-        const float* dssm_out = last ? nullptr : (const float*)(ws + w.dssm[(k + 1) & 1]);
-        const float* dconv_out = last ? nullptr : (const float*)(ws + w.dconv[(k + 1) & 1]);
-        float* dssm_in = k ? (float*)(ws + w.dssm[k & 1]) : nullptr;
-        float* dconv_in = k ? (float*)(ws + w.dconv[k & 1]) : nullptr;
+        const float* ssm_in = k ? ssm_ckpt + (size_t)k * d.HPN : init_ssm;
+        const void* conv_in = k ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : init_conv;
+        // adjoints of the states leaving this segment (the caller's behind the last one) / entering it
+        const float* dssm_out = last ? dfinal_ssm : (const float*)(ws + w.dssm[(k + 1) & 1]);
+        const float* dconv_out = last ? dfinal_conv : (const float*)(ws + w.dconv[(k + 1) & 1]);
+        float* dssm_in = k ? (float*)(ws + w.dssm[k & 1]) : dinit_ssm;
+        float* dconv_in = k ? (float*)(ws + w.dconv[k & 1]) : dinit_conv;
         const void* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
         // Recompute_Forward: zxbcdt, (x | B | C), dt, y, normalised y of this segment
         BLK_TRY(forward_segment(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, nullptr, nullptr, st));

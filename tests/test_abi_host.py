@@ -143,8 +143,8 @@ def test_block_pieces_validate_before_any_launch():
     assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 4, 64, 1, 128, 256, 1e-5, 1024, 512)), 1) == 0   # H % 8
     assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 80, 64, 1, 128, 256, 1e-5, 1024, 300)), 1) == 0  # segment % chunk
     par, gr = binding.magc_block_params_t(), binding.magc_block_grads_t()
-    assert L.magc_block_fwd(ctypes.byref(bs), ctypes.byref(par), fake, fake, fake, fake, None, None, fake, 1 << 40, None) == ERR_NULL
-    assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(par), fake, fake, fake, fake, fake, ctypes.byref(gr), fake, 1 << 40, 0, None) \
+    assert L.magc_block_fwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, fake, fake, None, None, fake, 1 << 40, None) == ERR_NULL
+    assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, None, None, fake, fake, fake, ctypes.byref(gr), None, None, fake, 1 << 40, 0, None) \
         == ERR_NULL
 
 

@@ -82,6 +82,58 @@ def test_block_forward_backward(case):
         check(k + " accumulated", host(g2[k]), 2 * host(g[k]), 1e-5)
 
 
+def test_block_prefill_then_generation_without_checkpoints():
+    # forward only: a prompt in segments with no checkpoint kept, then tokens one at a time (and three at
+    # once) from the states the previous call left -- against the oracle run over the whole sequence
+    L0, dm, H, P, G, N, Q, seg = 600, 128, 8, 64, 1, 128, 128, 256
+    gen = [1, 1, 1, 3, 1]
+    L = L0 + sum(gen)
+    d = draw(3, L, dm, H, P, G, N)
+    u, par = dev_bf16(d["u"]), to_dev(d["p"])
+    fo = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 1e-5, store=synth.round_bf16)
+    f = pk.magc_block_fwd(u[:L0].contiguous(), par, H, P, G, N, Q, seg, checkpoints=False)
+    assert f["ssm_ckpt"] is None
+    tol = TOL["bf16"]
+    check("prefill out", host(f["out"]), fo["out"][:L0], tol)
+    # the same prompt with checkpoints gives the same output and states
+    fc = pk.magc_block_fwd(u[:L0].contiguous(), par, H, P, G, N, Q, seg)
+    assert torch.equal(fc["out"], f["out"]) and torch.equal(fc["final_ssm"], f["final_ssm"]) and torch.equal(fc["final_conv"], f["final_conv"])
+    t, outs = L0, []
+    for n in gen:
+        f = pk.magc_block_fwd(u[t:t + n].contiguous(), par, H, P, G, N, Q, seg, init_ssm=f["final_ssm"], init_conv=f["final_conv"],
+                              checkpoints=False)
+        outs.append(f["out"])
+        t += n
+    torch.cuda.synchronize()
+    check("generated out", host(torch.cat(outs)), fo["out"][L0:], tol)
+    check("final ssm", host(f["final_ssm"]), fo["ssm_state"], tol)
+    check("final conv", host(f["final_conv"]), fo["conv_state"], tol)
+
+
+def test_block_state_adjoints_chain_two_calls():
+    # a sequence cut in two by the caller: the second call starts from the first call's states, its state
+    # adjoints feed the first call's backward -- together they are the whole sequence's gradients
+    L, dm, H, P, G, N, Q, seg = 768, 128, 8, 64, 1, 128, 128, 256
+    cut = 512
+    d = draw(4, L, dm, H, P, G, N)
+    u, dout, par = dev_bf16(d["u"]), dev_bf16(d["dout"]), to_dev(d["p"])
+    ua, ub, da, db = (t.contiguous() for t in (u[:cut], u[cut:], dout[:cut], dout[cut:]))
+    fa = pk.magc_block_fwd(ua, par, H, P, G, N, Q, seg)
+    fb = pk.magc_block_fwd(ub, par, H, P, G, N, Q, seg, init_ssm=fa["final_ssm"], init_conv=fa["final_conv"])
+    gb = pk.magc_block_bwd(ub, par, db, fb["ssm_ckpt"], fb["conv_ckpt"], H, P, G, N, Q, seg, init_ssm=fa["final_ssm"],
+                           init_conv=fa["final_conv"], want_dinit=True)
+    ga = pk.magc_block_bwd(ua, par, da, fa["ssm_ckpt"], fa["conv_ckpt"], H, P, G, N, Q, seg, dfinal_ssm=gb["dinit_ssm"],
+                           dfinal_conv=gb["dinit_conv"], flags=pk.SSD_FLAG_ACCUM_PARAM, grads={k: gb[k] for k in GRADS})
+    torch.cuda.synchronize()
+    fo = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 1e-5, store=synth.round_bf16)
+    go = block_ref.block_bwd(d["u"], d["p"], H, P, G, N, d["dout"], 1e-5, store=synth.round_bf16)
+    tol = TOL["bf16"]
+    check("out", host(torch.cat([fa["out"], fb["out"]])), fo["out"], tol)
+    check("du", host(torch.cat([ga["du"], gb["du"]])), go["du"], tol)
+    for k in GRADS:
+        check(k, host(ga[k]), go[k], tol)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
