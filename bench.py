@@ -316,6 +316,50 @@ def block_bench(args, cfg, pk, torch, dev):
            "dt_bias": dt0 + torch.log(-torch.expm1(-dt0)), "A": -torch.exp(torch.empty(H, device=dev).uniform_(0.0, math.log(16.0), generator=g)),
            "D": rn(H), "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5).to(torch.bfloat16)}
     u, dout = rn(L, dm).to(torch.bfloat16), rn(L, dm).to(torch.bfloat16)
+    if args.layers > 1:
+        # a stack of such blocks with residual adds on the two-axis grid: layer inputs kept every
+        # --layer-interval layers, both states of every layer every cfg.segment tokens
+        NL, li = args.layers, args.layer_interval
+        layers = [par] + [{k: (v + 0.01 * torch.randn(v.shape, device=dev, generator=g, dtype=torch.float32).to(v.dtype)) if k in ("W_in", "W_out") else v.clone()
+                           for k, v in par.items()} for _ in range(NL - 1)]
+        grads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in par.items()} for _ in range(NL)]
+        f = {}
+
+        def sfwd():
+            f.update(pk.magc_blockstack_fwd(u, layers, H, P, G, N, cfg.chunk, cfg.segment, li))
+
+        def sbwd():
+            pk.magc_blockstack_bwd(u, layers, dout, f["l_ckpt"], f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, cfg.chunk, cfg.segment, li, grads=grads)
+
+        def timed(fn):
+            for _ in range(args.warmup):
+                fn()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                fn()
+            torch.cuda.synchronize()
+            return (time.perf_counter() - t0) * 1e3 / args.steps
+
+        ms_f, ms_b = timed(sfwd), timed(sbwd)
+        assert bool(torch.isfinite(grads[0]["dW_in"].sum())) and bool(torch.isfinite(f["out"].float().sum()))
+        sshp = pk.binding.magc_blockstack_shape_t(pk.binding.magc_block_shape_t(dm, H, P, G, N, cfg.chunk, 1e-5, L, cfg.segment), NL, li)
+        nseg, ngl = -(-L // cfg.segment), -(-NL // li)
+        kept = NL * nseg * (H * P * N * 4 + 3 * conv_dim * 2) + (ngl - 1) * L * dm * 2
+        print(json.dumps({
+            "metric": "Mamba-2 block stack fwd+bwd tokens/sec/layer", "value": NL * L / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
+            "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
+            "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+            "config": {"workload": cfg.name + "_block_stack", "seqlen": L, "layers": NL, "layer_interval": li, "d_model": dm,
+                       "segment": cfg.segment},
+            "roofline": {"bound": "mfma", "achieved": None, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": None, "traffic": None,
+                         "forward_ms": ms_f, "backward_ms": ms_b},
+            "peak_hbm": {"checkpoint_bytes": kept, "workspace_bytes": int(pk.lib().magc_blockstack_workspace_bytes(ctypes.byref(sshp), 1)),
+                         "per_layer_input_bytes": NL * L * dm * 2,
+                         "note": "kept between the passes: state checkpoints of every layer + layer inputs every layer_interval layers; "
+                                 "per_layer_input_bytes is what keeping every layer's input (plain per-layer checkpointing) would hold"},
+        }))
+        return
     if args.inference:
         # forward only, no checkpoint kept: the prompt in segments, then one token per call from the carried states
         def prefill():
@@ -419,6 +463,8 @@ def main():
                     help="time the block's input and output projections (forward, input and weight gradients) instead")
     ap.add_argument("--block", action="store_true",
                     help="time one whole Mamba-2 block (projections, convolution, scan, gated norm) under sequence checkpoints instead")
+    ap.add_argument("--layers", type=int, default=1, help="with --block: a residual stack of this many blocks on the two-axis grid")
+    ap.add_argument("--layer-interval", type=int, default=4, help="with --block --layers: layer inputs kept every this many layers")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()

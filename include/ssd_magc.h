@@ -319,6 +319,35 @@ int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* p
                    size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /*
+ * A stack of whole blocks with residual adds, x_{j+1} = x_j + Block_j(x_j), on the two-axis grid of MA-GC
+ * (Sec. 3.2 / 3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole
+ * sequence, the SSM and convolution states of every layer every `segment` tokens (block.seqlen, block.segment);
+ * the backward pass walks the grid cell by cell, restores a cell's layer inputs from its two kinds of
+ * checkpoint and back-propagates through it.
+ *   params, grads: host arrays of `nlayers` structs of device pointers (one per layer)
+ *   x0, out, dout, dx0 [L, d_model] bf16
+ *   l_ckpt   [ceil(nlayers / layer_interval) - 1, L, d_model] bf16: slot m - 1 = the input of layer
+ *            m * layer_interval (the first group restarts from x0); may be NULL if there is one group
+ *   ssm_ckpt [nlayers, nseg, H, P, N] fp32, conv_ckpt [nlayers, nseg, 3, d_inner + 2 G N] bf16 (slot 0 of
+ *            every layer unused: zero initial states); may be NULL if nseg == 1
+ *   workspace: magc_blockstack_workspace_bytes bytes, 256-byte aligned: the activations of one cell
+ * The sequence starts from zero states in every layer; parameter gradients are overwritten or added to under
+ * SSD_FLAG_ACCUM_PARAM.  Errors as for magc_block_*; layer_interval must lie in 1 .. nlayers.
+ */
+typedef struct {
+    magc_block_shape_t block;
+    int32_t nlayers, layer_interval;
+} magc_blockstack_shape_t;
+size_t magc_blockstack_workspace_bytes(const magc_blockstack_shape_t* shape, int32_t is_backward);
+int magc_blockstack_fwd(const magc_blockstack_shape_t* shape, const magc_block_params_t* params, const void* x0, void* out,
+                        void* l_ckpt, float* ssm_ckpt, void* conv_ckpt, void* workspace, size_t workspace_bytes,
+                        void* hip_stream);
+int magc_blockstack_bwd(const magc_blockstack_shape_t* shape, const magc_block_params_t* params, const void* x0,
+                        const void* dout, const void* l_ckpt, const float* ssm_ckpt, const void* conv_ckpt, void* dx0,
+                        const magc_block_grads_t* grads, void* workspace, size_t workspace_bytes, uint32_t flags,
+                        void* hip_stream);
+
+/*
  * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the
  * MA-GC grid of Sec. 3.2/3.3: layer-axis checkpoints every `layer_interval` layers (l) and
  * sequence-axis checkpoints every shape->segment tokens (s).

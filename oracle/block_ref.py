@@ -84,3 +84,26 @@ def block_bwd(u, p, H, P, G, N, dout, eps=1e-5, conv_state=None, ssm_state=None,
     return {"du": _st(store, gi["dx"]), "dW_in": gi["dw"], "dconv_w": gc["dw"], "dconv_b": gc["dbias"],
             "ddt_bias": draw.sum(axis=0), "dA": gs["dA"], "dD": gs["dD"], "dnorm_w": gn["dw"], "dW_out": go["dw"],
             "dconv_state_in": gc["dstate_in"][0], "dssm_state_in": gs["dinit_state"][0]}
+
+
+def stack_fwd(x0, layers, H, P, G, N, eps=1e-5, store=None):
+    """Residual stack of blocks: x_{j+1} = x_j + Block_j(x_j), zero initial states; `layers` is a list of
+    parameter dicts.  Every x_{j+1} is rounded once by `store` where it is stored.  Returns dict(out, xs)."""
+    x = np.asarray(x0, dtype=np.float64)
+    xs = []
+    for p in layers:
+        xs.append(x)
+        x = _st(store, x + block_fwd(x, p, H, P, G, N, eps, store=store)["out"])
+    return {"out": x, "xs": xs}
+
+
+def stack_bwd(xs, layers, H, P, G, N, dout, eps=1e-5, store=None):
+    """Backward of stack_fwd given the layer inputs: dx_j = dx_{j+1} + Block_j^T(dx_{j+1}), each rounded once
+    by `store`.  Returns dict(dx0, grads=[per-layer dict])."""
+    g = np.asarray(dout, dtype=np.float64)
+    grads = [None] * len(layers)
+    for j in range(len(layers) - 1, -1, -1):
+        r = block_bwd(xs[j], layers[j], H, P, G, N, g, eps, store=store)
+        g = _st(store, g + r.pop("du"))
+        grads[j] = r
+    return {"dx0": g, "grads": grads}

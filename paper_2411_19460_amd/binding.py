@@ -19,7 +19,8 @@ SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
            "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
-           "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
+           "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
 
 
@@ -56,6 +57,10 @@ class magc_block_params_t(ctypes.Structure):
 
 class magc_block_grads_t(ctypes.Structure):
     _fields_ = [("d" + k, ctypes.c_void_p) for k in BLOCK_PARAMS]
+
+
+class magc_blockstack_shape_t(ctypes.Structure):
+    _fields_ = [("block", magc_block_shape_t), ("nlayers", ctypes.c_int32), ("layer_interval", ctypes.c_int32)]
 
 
 class magc_model_t(ctypes.Structure):
@@ -123,6 +128,13 @@ def lib():
         L.magc_block_fwd.argtypes = [bshp, bpar] + [vp] * 8 + [vp, sz, vp]
         L.magc_block_bwd.restype = ctypes.c_int
         L.magc_block_bwd.argtypes = [bshp, bpar] + [vp] * 9 + [bgr, vp, vp, vp, sz, u32, vp]
+        sshp = ctypes.POINTER(magc_blockstack_shape_t)
+        L.magc_blockstack_workspace_bytes.restype = sz
+        L.magc_blockstack_workspace_bytes.argtypes = [sshp, i32]
+        L.magc_blockstack_fwd.restype = ctypes.c_int
+        L.magc_blockstack_fwd.argtypes = [sshp, bpar] + [vp] * 5 + [vp, sz, vp]
+        L.magc_blockstack_bwd.restype = ctypes.c_int
+        L.magc_blockstack_bwd.argtypes = [sshp, bpar] + [vp] * 6 + [bgr, vp, sz, u32, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz
@@ -494,6 +506,59 @@ def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroup
     if want_dinit:
         res.update(dinit_ssm=dinit_ssm, dinit_conv=dinit_conv)
     return res
+
+
+def _blockstack_setup(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, layer_interval, eps):
+    shape, _, want, nseg, conv_dim = _block_setup(x0, layers[0], nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    for p in layers[1:]:
+        _block_setup(x0, p, nheads, headdim, ngroups, dstate, chunk, segment, eps)
+    pars = (magc_block_params_t * len(layers))(*[magc_block_params_t(*[_ptr(p[k]) for k in BLOCK_PARAMS]) for p in layers])
+    sshape = magc_blockstack_shape_t(shape, len(layers), layer_interval)
+    return sshape, pars, want, nseg, conv_dim
+
+
+def magc_blockstack_fwd(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, layer_interval, eps=1e-5):
+    """Residual stack of whole blocks (layers: list of parameter dicts) on the two-axis checkpoint grid.
+    Returns dict(out, l_ckpt, ssm_ckpt, conv_ckpt)."""
+    import torch
+    sshape, pars, _, nseg, conv_dim = _blockstack_setup(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, layer_interval, eps)
+    dev, (L, dm), NL = x0.device, x0.shape, len(layers)
+    ngl = -(-NL // layer_interval)
+    out = torch.empty_like(x0)
+    l_ckpt = torch.empty((max(ngl - 1, 1), L, dm), dtype=torch.bfloat16, device=dev)
+    ssm_ckpt = torch.zeros((NL, nseg, nheads, headdim, dstate), dtype=torch.float32, device=dev)
+    conv_ckpt = torch.zeros((NL, nseg, 3, conv_dim), dtype=torch.bfloat16, device=dev)
+    ws = _workspace(int(lib().magc_blockstack_workspace_bytes(ctypes.byref(sshape), 0)), dev)
+    rc = lib().magc_blockstack_fwd(ctypes.byref(sshape), pars, _ptr(x0), _ptr(out), _ptr(l_ckpt), _ptr(ssm_ckpt), _ptr(conv_ckpt),
+                                   _ptr(ws), ws.numel(), _stream(x0))
+    if rc != 0:
+        raise SSDError(rc, "magc_blockstack_fwd")
+    return {"out": out, "l_ckpt": l_ckpt, "ssm_ckpt": ssm_ckpt, "conv_ckpt": conv_ckpt}
+
+
+def magc_blockstack_bwd(x0, layers, dout, l_ckpt, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment,
+                        layer_interval, eps=1e-5, flags=0, grads=None):
+    """dict(dx0, grads=[per-layer dict of dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out])."""
+    import torch
+    sshape, pars, want, _, _ = _blockstack_setup(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, layer_interval, eps)
+    dev = x0.device
+    if grads is None:
+        grads = [{"d" + k: torch.empty(shp, dtype=torch.float32, device=dev) for k, (shp, _) in want.items()} for _ in layers]
+    for g in grads:
+        for k, (shp, _) in want.items():
+            t = g["d" + k]
+            if tuple(t.shape) != shp or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"grads['d{k}'] must be a dense fp32 device tensor of shape {shp}")
+    grs = (magc_block_grads_t * len(layers))(*[magc_block_grads_t(*[_ptr(g["d" + k]) for k in BLOCK_PARAMS]) for g in grads])
+    if dout.shape != x0.shape or dout.dtype != x0.dtype or not dout.is_cuda or not dout.is_contiguous():
+        raise ValueError("dout must match x0")
+    dx0 = torch.empty_like(x0)
+    ws = _workspace(int(lib().magc_blockstack_workspace_bytes(ctypes.byref(sshape), 1)), dev)
+    rc = lib().magc_blockstack_bwd(ctypes.byref(sshape), pars, _ptr(x0), _ptr(dout), _ptr(l_ckpt), _ptr(ssm_ckpt), _ptr(conv_ckpt),
+                                   _ptr(dx0), grs, _ptr(ws), ws.numel(), flags, _stream(x0))
+    if rc != 0:
+        raise SSDError(rc, "magc_blockstack_bwd")
+    return {"dx0": dx0, "grads": grads}
 
 
 def ssd_bwd(x, dt, A, B, C, D, dy, chunk, segment=None, init_state=None, dfinal_state=None, boundary_states=None,

@@ -392,3 +392,230 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
     }
     return SSD_OK;
 }
+
+// ---------------------------------------------------------------------------------------------------
+// A stack of whole blocks with residual adds, x_{j+1} = x_j + Block_j(x_j), on the two-axis grid of MA-GC
+// (Sec. 3.2/3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole sequence
+// (layer-axis checkpoints), the SSM and convolution states of every layer are kept every `segment` tokens
+// (sequence-axis checkpoints).  The backward pass walks the cells right to left and top to bottom: inside a
+// cell it first restores the inputs of the cell's layers from the layer checkpoint (forward calls from the
+// cell's state checkpoints), then back-propagates through the layers top down, each layer's two state
+// adjoints being handed to the cell on its left.  A cell's layer is one single-segment call of the block above.
+namespace ssdk {
+namespace {
+
+// dst = a + b, bf16, 16-byte vectors (n a multiple of 8)
+__global__ __launch_bounds__(256) void k_add_bf16(bf16_t* dst, const bf16_t* a, const bf16_t* b, int64_t n8) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n8; i += (int64_t)gridDim.x * 256) {
+        const b8 x = *(const b8*)((const __bf16*)a + i * 8), y = *(const b8*)((const __bf16*)b + i * 8);
+        b8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (__bf16)((float)x[e] + (float)y[e]);
+        *(b8*)((__bf16*)dst + i * 8) = o;
+    }
+}
+
+hipError_t add_bf16(void* dst, const void* a, const void* b, int64_t n, hipStream_t st) {
+    if (n == 0) return hipSuccess;
+    const int64_t n8 = n / 8, blocks = (n8 + 255) / 256;
+    hipLaunchKernelGGL(k_add_bf16, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st, (bf16_t*)dst, (const bf16_t*)a,
+                       (const bf16_t*)b, n8);
+    return hipGetLastError();
+}
+
+struct StackDims {
+    BlockDims b;
+    int NL, l, ngl;  // layers, layer interval, layer groups
+    size_t act, conv_state, conv_adj;
+};
+
+int check_stack(const magc_blockstack_shape_t* sh, StackDims* d) {
+    if (!sh) return SSD_ERR_NULL;
+    const int rc = check(&sh->block, &d->b);
+    if (rc != SSD_OK) return rc;
+    if (sh->nlayers <= 0 || sh->layer_interval <= 0 || sh->layer_interval > sh->nlayers) return SSD_ERR_SHAPE;
+    d->NL = sh->nlayers;
+    d->l = sh->layer_interval;
+    d->ngl = (d->NL + d->l - 1) / d->l;
+    d->act = (size_t)d->b.s * d->b.dm * 2;
+    d->conv_state = (size_t)3 * d->b.conv_dim * 2;
+    d->conv_adj = (size_t)3 * d->b.conv_dim * 4;
+    return SSD_OK;
+}
+
+magc_block_shape_t cell_shape(const magc_blockstack_shape_t* sh, int64_t rows) {
+    magc_block_shape_t c = sh->block;
+    c.seqlen = rows;  // one segment: the cell
+    return c;
+}
+
+struct StackWs {
+    size_t act[2], xs, dcur, du, dssm, dconv, fin_ssm, fin_conv, inner, inner_bytes, total;
+};
+
+StackWs stack_layout(const magc_blockstack_shape_t* sh, const StackDims& d, bool bwd) {
+    StackWs w;
+    memset(&w, 0, sizeof(w));
+    size_t off = 0;
+    auto take = [&](size_t bytes) {
+        const size_t o = off;
+        off += al(bytes);
+        return o;
+    };
+    w.act[0] = take(d.act);
+    w.act[1] = take(d.act);
+    w.fin_ssm = take(d.b.HPN * 4);
+    w.fin_conv = take(d.conv_state);
+    if (bwd) {
+        w.xs = take((size_t)d.l * d.act);
+        w.dcur = take(d.act);
+        w.du = take(d.act);
+        w.dssm = take((size_t)d.NL * 2 * d.b.HPN * 4);      // per layer, two buffers used alternately
+        w.dconv = take((size_t)d.NL * 2 * d.conv_adj);
+    }
+    const magc_block_shape_t c = cell_shape(sh, d.b.s);
+    size_t inner = magc_block_workspace_bytes(&c, bwd ? 1 : 0);
+    if (d.b.L % d.b.s) {  // the short last segment pads the scan: its scratch may differ
+        const magc_block_shape_t ct = cell_shape(sh, d.b.L % d.b.s);
+        const size_t t = magc_block_workspace_bytes(&ct, bwd ? 1 : 0);
+        inner = t > inner ? t : inner;
+    }
+    const size_t f = magc_block_workspace_bytes(&c, 0);  // the restore runs forward calls too
+    inner = f > inner ? f : inner;
+    w.inner = take(inner);
+    w.inner_bytes = inner;
+    w.total = off;
+    return w;
+}
+
+bool params_ok(const magc_block_params_t* p, int n) {
+    if (!p) return false;
+    for (int j = 0; j < n; ++j)
+        if (!p[j].W_in || !p[j].conv_w || !p[j].conv_b || !p[j].dt_bias || !p[j].A || !p[j].D || !p[j].norm_w || !p[j].W_out) return false;
+    return true;
+}
+
+}  // namespace
+}  // namespace ssdk
+
+extern "C" size_t magc_blockstack_workspace_bytes(const magc_blockstack_shape_t* sh, int32_t is_backward) {
+    StackDims d;
+    if (check_stack(sh, &d) != SSD_OK) return 0;
+    const magc_block_shape_t c = cell_shape(sh, d.b.s);
+    if (magc_block_workspace_bytes(&c, is_backward) == 0) return 0;
+    return stack_layout(sh, d, is_backward != 0).total;
+}
+
+extern "C" int magc_blockstack_fwd(const magc_blockstack_shape_t* sh, const magc_block_params_t* params, const void* x0, void* out,
+                                   void* l_ckpt, float* ssm_ckpt, void* conv_ckpt, void* workspace, size_t workspace_bytes,
+                                   void* hip_stream) {
+    StackDims d;
+    BLK_TRY(check_stack(sh, &d));
+    if (!params_ok(params, d.NL)) return SSD_ERR_NULL;
+    if (d.b.L == 0) return SSD_OK;
+    if (!x0 || !out || (d.ngl > 1 && !l_ckpt) || (d.b.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
+    const StackWs w = stack_layout(sh, d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const size_t row = (size_t)d.b.dm * 2;
+    for (int64_t k = 0; k < d.b.nseg; ++k) {
+        const int64_t t0 = k * d.b.s, rows = d.b.L - t0 < d.b.s ? d.b.L - t0 : d.b.s;
+        const magc_block_shape_t c = cell_shape(sh, rows);
+        const bool last = k + 1 == d.b.nseg;
+        const char* cur = (const char*)x0 + (size_t)t0 * row;
+        for (int j = 0; j < d.NL; ++j) {
+            if (j && j % d.l == 0) {  // layer-axis checkpoint: the input of layer j for these tokens
+                char* slot = (char*)l_ckpt + ((size_t)(j / d.l - 1) * d.b.L + t0) * row;
+                BLK_HIP(launch_copy_f32((float*)slot, (const float*)cur, (size_t)rows * d.b.dm / 2, st));  // bf16 pairs as words
+                cur = slot;
+            }
+            // sequence-axis checkpoints of layer j: slot k = the states entering segment k (slot 0 unused: zeros)
+            float* sj = ssm_ckpt ? ssm_ckpt + (size_t)j * d.b.nseg * d.b.HPN : nullptr;
+            char* cj = conv_ckpt ? (char*)conv_ckpt + (size_t)j * d.b.nseg * d.conv_state : nullptr;
+            const float* ssm_in = k ? sj + (size_t)k * d.b.HPN : nullptr;
+            const void* conv_in = k ? cj + (size_t)k * d.conv_state : nullptr;
+            float* ssm_out = last ? (float*)(ws + w.fin_ssm) : sj + (size_t)(k + 1) * d.b.HPN;
+            void* conv_out = last ? (void*)(ws + w.fin_conv) : (void*)(cj + (size_t)(k + 1) * d.conv_state);
+            char* y = ws + w.act[j & 1];
+            BLK_TRY(magc_block_fwd(&c, &params[j], cur, ssm_in, conv_in, y, nullptr, nullptr, ssm_out, conv_out, ws + w.inner,
+                                   w.inner_bytes, st));
+            char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
+            BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
+            cur = nxt;
+        }
+    }
+    return SSD_OK;
+}
+
+extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc_block_params_t* params, const void* x0, const void* dout,
+                                   const void* l_ckpt, const float* ssm_ckpt, const void* conv_ckpt, void* dx0,
+                                   const magc_block_grads_t* grads, void* workspace, size_t workspace_bytes, uint32_t flags,
+                                   void* hip_stream) {
+    StackDims d;
+    BLK_TRY(check_stack(sh, &d));
+    if (flags & ~(uint32_t)SSD_FLAG_ACCUM_PARAM) return SSD_ERR_ARG;
+    if (!params_ok(params, d.NL) || !grads) return SSD_ERR_NULL;
+    for (int j = 0; j < d.NL; ++j)
+        if (!grads[j].dW_in || !grads[j].dconv_w || !grads[j].dconv_b || !grads[j].ddt_bias || !grads[j].dA || !grads[j].dD ||
+            !grads[j].dnorm_w || !grads[j].dW_out)
+            return SSD_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    const size_t row = (size_t)d.b.dm * 2;
+    if (!(flags & SSD_FLAG_ACCUM_PARAM)) {  // every cell adds to the parameter gradients of its layers
+        for (int j = 0; j < d.NL; ++j) {
+            BLK_HIP(launch_fill_zero(grads[j].dW_in, (size_t)d.b.d_in_proj * d.b.dm, st));
+            BLK_HIP(launch_fill_zero(grads[j].dconv_w, (size_t)d.b.conv_dim * 4, st));
+            BLK_HIP(launch_fill_zero(grads[j].dconv_b, (size_t)d.b.conv_dim, st));
+            BLK_HIP(launch_fill_zero(grads[j].ddt_bias, (size_t)d.b.H, st));
+            BLK_HIP(launch_fill_zero(grads[j].dA, (size_t)d.b.H, st));
+            BLK_HIP(launch_fill_zero(grads[j].dD, (size_t)d.b.H, st));
+            BLK_HIP(launch_fill_zero(grads[j].dnorm_w, (size_t)d.b.d_inner, st));
+            BLK_HIP(launch_fill_zero(grads[j].dW_out, (size_t)d.b.dm * d.b.d_inner, st));
+        }
+    }
+    if (d.b.L == 0) return SSD_OK;
+    if (!x0 || !dout || !dx0 || (d.ngl > 1 && !l_ckpt) || (d.b.nseg > 1 && (!ssm_ckpt || !conv_ckpt))) return SSD_ERR_NULL;
+    const StackWs w = stack_layout(sh, d, true);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    for (int64_t k = d.b.nseg - 1; k >= 0; --k) {
+        const int64_t t0 = k * d.b.s, rows = d.b.L - t0 < d.b.s ? d.b.L - t0 : d.b.s;
+        const magc_block_shape_t c = cell_shape(sh, rows);
+        const bool last = k + 1 == d.b.nseg;
+        const char* dcur = (const char*)dout + (size_t)t0 * row;  // gradient of the stack output for these tokens
+        for (int m = d.ngl - 1; m >= 0; --m) {
+            const int j0 = m * d.l, j1 = (j0 + d.l < d.NL ? j0 + d.l : d.NL) - 1;
+            // restore the inputs of the cell's layers from its layer checkpoint (Recompute_Forward of Alg. 2)
+            const char* xin = m ? (const char*)l_ckpt + ((size_t)(m - 1) * d.b.L + t0) * row : (const char*)x0 + (size_t)t0 * row;
+            for (int j = j0; j < j1; ++j) {
+                const float* ssm_in = k ? ssm_ckpt + ((size_t)j * d.b.nseg + k) * d.b.HPN : nullptr;
+                const void* conv_in = k ? (const char*)conv_ckpt + ((size_t)j * d.b.nseg + k) * d.conv_state : nullptr;
+                char* y = ws + w.act[0];
+                BLK_TRY(magc_block_fwd(&c, &params[j], xin, ssm_in, conv_in, y, nullptr, nullptr, nullptr, nullptr, ws + w.inner,
+                                       w.inner_bytes, st));
+                char* nxt = ws + w.xs + (size_t)(j - j0 + 1) * d.act;
+                BLK_HIP(add_bf16(nxt, xin, y, rows * d.b.dm, st));
+                xin = nxt;
+            }
+            // back through the layers, top down: dx_j = dx_{j+1} + Block_j^T(dx_{j+1})
+            for (int j = j1; j >= j0; --j) {
+                const char* xj = j == j0 ? (m ? (const char*)l_ckpt + ((size_t)(m - 1) * d.b.L + t0) * row : (const char*)x0 + (size_t)t0 * row)
+                                         : ws + w.xs + (size_t)(j - j0) * d.act;
+                const float* ssm_in = k ? ssm_ckpt + ((size_t)j * d.b.nseg + k) * d.b.HPN : nullptr;
+                const void* conv_in = k ? (const char*)conv_ckpt + ((size_t)j * d.b.nseg + k) * d.conv_state : nullptr;
+                // this layer's state adjoints: written for segment k into buffer k % 2, read by segment k - 1 from it
+                float* dssm_w = (float*)(ws + w.dssm + ((size_t)j * 2 + (k & 1)) * d.b.HPN * 4);
+                float* dconv_w = (float*)(ws + w.dconv + ((size_t)j * 2 + (k & 1)) * d.conv_adj);
+                const float* dssm_r = last ? nullptr : (const float*)(ws + w.dssm + ((size_t)j * 2 + ((k + 1) & 1)) * d.b.HPN * 4);
+                const float* dconv_r = last ? nullptr : (const float*)(ws + w.dconv + ((size_t)j * 2 + ((k + 1) & 1)) * d.conv_adj);
+                BLK_TRY(magc_block_bwd(&c, &params[j], xj, ssm_in, conv_in, dcur, dssm_r, dconv_r, nullptr, nullptr, ws + w.du, &grads[j],
+                                       k ? dssm_w : nullptr, k ? dconv_w : nullptr, ws + w.inner, w.inner_bytes, SSD_FLAG_ACCUM_PARAM, st));
+                char* dnext = (j == 0) ? (char*)dx0 + (size_t)t0 * row : ws + w.dcur;
+                BLK_HIP(add_bf16(dnext, dcur, ws + w.du, rows * d.b.dm, st));
+                dcur = dnext;
+            }
+        }
+    }
+    return SSD_OK;
+}

@@ -74,3 +74,20 @@ def test_a_sequence_cut_in_two_and_restarted_from_both_states_is_the_whole_seque
             close(ga[k] + gb[k], gw[k], 1e-11)
         close(ga["dssm_state_in"], gw["dssm_state_in"], 1e-11)
         close(ga["dconv_state_in"], gw["dconv_state_in"], 1e-11)
+
+
+def test_stack_of_blocks_gradients_match_central_differences():
+    d0, d1 = draw(5, L=6), draw(6, L=6)
+    layers = [d0["p"], d1["p"]]
+    x0, dout = d0["u"], d0["dout"]
+    f = block_ref.stack_fwd(x0, layers, H, P, G, N, 1e-3)
+    b = block_ref.stack_bwd(f["xs"], layers, H, P, G, N, dout, 1e-3)
+    L = lambda x=None, lay=None: float(np.sum(block_ref.stack_fwd(x0 if x is None else x, layers if lay is None else lay, H, P, G, N, 1e-3)["out"] * dout))
+    close(b["dx0"], numgrad(lambda a: L(x=a), x0), 2e-7)
+    for j in range(2):
+        for key, name in (("W_in", "dW_in"), ("conv_b", "dconv_b"), ("A", "dA"), ("norm_w", "dnorm_w"), ("W_out", "dW_out")):
+            def with_param(a, j=j, key=key):
+                lay = [dict(p) for p in layers]
+                lay[j][key] = a
+                return L(lay=lay)
+            close(b["grads"][j][name], numgrad(with_param, layers[j][key]), 2e-7)

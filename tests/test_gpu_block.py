@@ -134,6 +134,52 @@ def test_block_state_adjoints_chain_two_calls():
         check(k, host(ga[k]), go[k], tol)
 
 
+@pytest.mark.parametrize("case", [
+    # layers, layer interval, L, segment      (d_model 128, 8 heads x 64, state 128, chunk 128)
+    (3, 2, 640, 256),     # two layer groups (2 + 1), three segments, the last one short
+    (4, 4, 512, 256),     # one layer group: only the stack input is kept on the layer axis
+    (3, 1, 384, 384),     # every layer input kept, one segment
+])
+def test_stack_of_blocks_on_the_two_axis_grid(case):
+    NL, l, L, seg = case
+    dm, H, P, G, N, Q = 128, 8, 64, 1, 128, 128
+    ds = [draw(10 + j, L, dm, H, P, G, N) for j in range(NL)]
+    layers_h = [x["p"] for x in ds]
+    x0h, douth = ds[0]["u"], ds[0]["dout"]
+    x0, dout, layers = dev_bf16(x0h), dev_bf16(douth), [to_dev(p) for p in layers_h]
+    f = pk.magc_blockstack_fwd(x0, layers, H, P, G, N, Q, seg, l)
+    g = pk.magc_blockstack_bwd(x0, layers, dout, f["l_ckpt"], f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg, l)
+    torch.cuda.synchronize()
+    fo = block_ref.stack_fwd(x0h, layers_h, H, P, G, N, 1e-5, store=synth.round_bf16)
+    go = block_ref.stack_bwd(fo["xs"], layers_h, H, P, G, N, douth, 1e-5, store=synth.round_bf16)
+    tol = 2 * TOL["bf16"]     # activations and their gradients are re-rounded to bf16 after every layer
+    rep = {}
+    check("out", host(f["out"]), fo["out"], tol, rep)
+    check("dx0", host(g["dx0"]), go["dx0"], tol, rep)
+    # Parameter gradients are sums over all tokens in which terms cancel; where rounding the stored bf16
+    # intermediates alone moves such a sum by more than the tolerance (seen for dt_bias of the lowest layer,
+    # whose gradient has crossed every layer above), that movement -- the oracle with and without the
+    # storage rounding -- is the bar: two correct evaluations that round in a different order differ by as much.
+    fe = block_ref.stack_fwd(x0h, layers_h, H, P, G, N, 1e-5)
+    ge = block_ref.stack_bwd(fe["xs"], layers_h, H, P, G, N, douth, 1e-5)
+    for j in range(NL):
+        for k in GRADS:
+            ref, exact = go["grads"][j][k], ge["grads"][j][k]
+            floor = float(np.max(np.abs(ref - exact))) / float(np.max(np.abs(exact)))
+            check(f"layer {j} {k}", host(g["grads"][j][k]), ref, max(tol, floor), rep)
+    print("stack of blocks, worst errors:", {k: f"{v:.2e}" for k, v in sorted(rep.items(), key=lambda kv: -kv[1])[:4]})
+    # the grid does not change the result: whole sequence as one segment, every layer input kept
+    f1 = pk.magc_blockstack_fwd(x0, layers, H, P, G, N, Q, None, 1)
+    g1 = pk.magc_blockstack_bwd(x0, layers, dout, f1["l_ckpt"], f1["ssm_ckpt"], f1["conv_ckpt"], H, P, G, N, Q, None, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(f1["out"], f["out"])
+    assert float((g1["dx0"].float() - g["dx0"].float()).abs().max()) <= 2.0 ** -6 * float(g1["dx0"].float().abs().max())
+    for j in range(NL):
+        for k in GRADS:
+            a, b = g["grads"][j][k], g1["grads"][j][k]
+            assert float((a - b).abs().max()) <= 2.0 ** -6 * float(b.abs().max()), (j, k)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
