@@ -465,6 +465,8 @@ def main():
                     help="time one whole Mamba-2 block (projections, convolution, scan, gated norm) under sequence checkpoints instead")
     ap.add_argument("--layers", type=int, default=1, help="with --block: a residual stack of this many blocks on the two-axis grid")
     ap.add_argument("--layer-interval", type=int, default=4, help="with --block --layers: layer inputs kept every this many layers")
+    ap.add_argument("--calibrate-mfma", action="store_true",
+                    help="run a register-only MFMA loop over the whole chip and print the rate it sustains")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -497,6 +499,23 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_mfma:
+        # sustained rate of the matrix cores on registers only: 1024 workgroups (four per compute unit in turn)
+        sink = torch.zeros(1, device=dev)
+        iters, wgs = 20000, 1024
+        out = {}
+        for label, n in (("short", 2000), ("long", iters)):
+            for _ in range(2):
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                rc = pk.lib().ssd_prof_mfma_peak(n, wgs, sink.data_ptr(), torch.cuda.current_stream().cuda_stream or None)
+                e1.record()
+                torch.cuda.synchronize()
+                assert rc == 0
+            ms = e0.elapsed_time(e1)
+            out[label] = {"ms": ms, "TFLOP/s": wgs * 4 * n * 16 * 32768.0 / (ms * 1e-3) / 1e12}
+        print(json.dumps({"calibration": "mfma_f32_32x32x16_bf16 on registers", "nominal_peak_TFLOP/s": MFMA_BF16_PEAK_TFLOPS, **out}))
+        return
     if args.block:
         block_bench(args, cfg, pk, torch, dev)
         return

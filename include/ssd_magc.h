@@ -434,6 +434,10 @@ int ssd_prof_enable(int32_t on);
 int ssd_prof_serialize(int32_t on);
 int ssd_prof_read(int32_t kernel_id, double* total_ms /*host*/, int64_t* launches /*host*/);
 const char* ssd_prof_kernel_name(int32_t kernel_id);
+/* Calibration of the matrix cores: `workgroups` workgroups of four waves, each wave `iters` rounds of sixteen
+ * independent 32 x 32 x 16 bf16 MFMAs on registers (no memory traffic): 16 * 32768 flop per wave and round.
+ * `sink` is one float of device memory (never written).  The caller times the launch. */
+int ssd_prof_mfma_peak(int32_t iters, int32_t workgroups, float* sink, void* hip_stream);
 
 /* Static, human-readable text for a status code (host pointer, never NULL). */
 const char* ssd_strerror(int status);

@@ -21,7 +21,7 @@ EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_b
            "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
            "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
            "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
-           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize")
+           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize", "ssd_prof_mfma_peak")
 
 
 class ssd_shape_t(ctypes.Structure):
@@ -135,6 +135,8 @@ def lib():
         L.magc_blockstack_fwd.argtypes = [sshp, bpar] + [vp] * 5 + [vp, sz, vp]
         L.magc_blockstack_bwd.restype = ctypes.c_int
         L.magc_blockstack_bwd.argtypes = [sshp, bpar] + [vp] * 6 + [bgr, vp, sz, u32, vp]
+        L.ssd_prof_mfma_peak.restype = ctypes.c_int
+        L.ssd_prof_mfma_peak.argtypes = [i32, i32, vp, vp]
         L.ssd_decode.restype = ctypes.c_int
         L.ssd_decode.argtypes = [shp] + [vp] * 8 + [u32, vp]
         L.magc_stack_workspace_bytes.restype = sz

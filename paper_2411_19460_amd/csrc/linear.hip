@@ -539,3 +539,37 @@ extern "C" int ssd_linear_bwd(int64_t rows, int32_t in_dim, int32_t out_dim, con
     }
     return SSD_OK;
 }
+
+// Calibration: what the matrix cores deliver when nothing else is in the way -- every wave issues
+// `iters` rounds of sixteen independent 32 x 32 x 16 bf16 MFMAs on registers (no memory traffic), four
+// waves per compute unit over the whole chip.  bench.py times it (--calibrate-mfma) to put the sustained
+// clock of the matrix pipes next to the nominal peak.
+namespace ssdk {
+namespace {
+__global__ __launch_bounds__(256, 1) void k_mfma_peak(int iters, float* sink) {
+    f32x16 acc[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[i] = zero16();
+    bf16x8 a, b;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        a[e] = (__bf16)(float)(threadIdx.x & 3);
+        b[e] = (__bf16)(float)(e & 1);
+    }
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[i] = mfma(a, b, acc[i]);
+    }
+    float s = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) s += acc[i][0];
+    if (s == -1.f) sink[0] = s;  // never true: keeps the products alive
+}
+}  // namespace
+}  // namespace ssdk
+
+extern "C" int ssd_prof_mfma_peak(int32_t iters, int32_t workgroups, float* sink, void* hip_stream) {
+    if (iters <= 0 || workgroups <= 0 || !sink) return SSD_ERR_ARG;
+    hipLaunchKernelGGL(k_mfma_peak, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, sink);
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+}
