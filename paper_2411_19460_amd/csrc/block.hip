@@ -237,12 +237,16 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         if ((expr) != hipSuccess) return SSD_ERR_LAUNCH; \
     } while (0)
 
-// Steps 1-5 of a segment (everything up to y and the normalised y), from the two states entering it.
-int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
-                    const void* u_seg, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out,
-                    hipStream_t st) {
-    char* zx = ws + w.zx;
-    BLK_TRY(ssd_linear_fwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, zx, 0, st));
+// The forward steps of a segment.  zx [rows, d_in_proj] and y [rows, d_inner] are given by the caller (the
+// block's own workspace, or the per-layer slots a grid cell keeps: they are the activations C_grid of App. C,
+// Tab. 7 counts); everything else lives in the workspace `ws` laid out by `w`.
+int seg_in_proj(const BlockDims& d, const magc_block_params_t* p, const void* u_seg, int64_t rows, char* zx, hipStream_t st) {
+    return ssd_linear_fwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, zx, 0, st);
+}
+
+// convolution + SiLU of the xBC columns, split into dense x / B / C, softplus of the dt columns
+int seg_mid(const BlockDims& d, const magc_block_params_t* p, char* ws, const BlockWs& w, const char* zx, int64_t rows,
+            const void* conv_in, void* conv_out, hipStream_t st) {
     const ssd_conv_shape_t cs = conv_shape(d, rows);
     BLK_TRY(ssd_conv1d_fwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.xbc, conv_out, st));
     BLK_HIP(copy_cols(ws + w.x, d.d_inner, ws + w.xbc, d.conv_dim, rows, d.d_inner, st));
@@ -251,18 +255,73 @@ int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc
     hipLaunchKernelGGL(k_dt_fwd, dim3((unsigned)((rows + DT_ROWS - 1) / DT_ROWS)), dim3(256), 0, st,
                        (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj, p->dt_bias, (bf16_t*)(ws + w.dt), rows, d.H);
     BLK_HIP(hipGetLastError());
+    return SSD_OK;
+}
+
+int seg_scan(const BlockDims& d, const magc_block_params_t* p, char* ws, const BlockWs& w, int64_t rows, const float* ssm_in,
+             float* ssm_out, char* y, hipStream_t st) {
     const ssd_shape_t ss = seg_shape(d, rows);
     if (rows <= DECODE_ROWS && ssm_out) {
         // a few tokens (generation): the recurrence token by token on the state itself instead of a padded chunk
         if (ssm_in != ssm_out)
             BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
-        BLK_TRY(ssd_decode(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, ws + w.y, 0, st));
-    } else {
-        BLK_TRY(ssd_fwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.y, ssm_out, nullptr, ws + w.inner,
-                        w.inner_bytes, 0, st));
+        return ssd_decode(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, y, 0, st);
     }
+    return ssd_fwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, y, ssm_out, nullptr, ws + w.inner, w.inner_bytes, 0, st);
+}
+
+int seg_norm(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w, const char* zx,
+             const char* y, int64_t rows, hipStream_t st) {
     const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
-    BLK_TRY(ssd_gated_norm_fwd(&ns, ws + w.y, zx, p->norm_w, ws + w.yn, st));
+    return ssd_gated_norm_fwd(&ns, y, zx, p->norm_w, ws + w.yn, st);
+}
+
+// All of them: everything up to y and the normalised y, from the two states entering the segment.
+int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
+                    char* zx, char* y, const void* u_seg, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out,
+                    void* conv_out, hipStream_t st) {
+    BLK_TRY(seg_in_proj(d, p, u_seg, rows, zx, st));
+    BLK_TRY(seg_mid(d, p, ws, w, zx, rows, conv_in, conv_out, st));
+    BLK_TRY(seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, y, st));
+    BLK_TRY(seg_norm(d, sh, p, ws, w, zx, y, rows, st));
+    return SSD_OK;
+}
+
+// The reverse of every step of a segment, given its forward activations (zx, y from the caller; x / B / C,
+// dt and the normalised y in the workspace): du of the segment, parameter gradients added to `g`, the
+// adjoints of the two states entering the segment.
+int backward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, const magc_block_grads_t* g,
+                     char* ws, const BlockWs& w, const char* zx, const char* y, const void* u_seg, const void* dout_seg, void* du_seg,
+                     int64_t rows, const float* ssm_in, const void* conv_in, const float* dssm_out, const float* dconv_out,
+                     float* dssm_in, float* dconv_in, hipStream_t st) {
+    const uint32_t acc = SSD_FLAG_ACCUM_PARAM;
+    char* dzx = ws + w.dzx;
+    // output projection
+    BLK_TRY(ssd_linear_bwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, dout_seg, 0, ws + w.dyn, 0, g->dW_out, acc, st));
+    // gated normalisation: dy, and dz straight into its columns of d zxbcdt
+    const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
+    BLK_TRY(ssd_gated_norm_bwd(&ns, y, zx, p->norm_w, ws + w.dyn, ws + w.dy, dzx, g->dnorm_w, ws + w.inner, w.inner_bytes, acc, st));
+    // scan
+    const ssd_shape_t ss = seg_shape(d, rows);
+    BLK_TRY(ssd_bwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.dy, dssm_out, nullptr, ws + w.dx, ws + w.ddt,
+                    g->dA, ws + w.dB, ws + w.dC, g->dD, dssm_in, ws + w.inner, w.inner_bytes, acc, st));
+    // softplus of dt: into the dt columns of d zxbcdt
+    const int ntile = (int)((rows + DT_ROWS - 1) / DT_ROWS);
+    hipLaunchKernelGGL(k_dt_bwd, dim3(ntile), dim3(256), 0, st, (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
+                       p->dt_bias, (const bf16_t*)(ws + w.ddt), (bf16_t*)(dzx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
+                       (float*)(ws + w.dtpart), rows, d.H);
+    BLK_HIP(hipGetLastError());
+    hipLaunchKernelGGL(k_colsum, dim3((d.H + 63) / 64), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H, g->ddt_bias, 1);
+    BLK_HIP(hipGetLastError());
+    // convolution: (dx | dB | dC) side by side, du into the xBC columns of d zxbcdt
+    BLK_HIP(copy_cols(ws + w.dxbc, d.conv_dim, ws + w.dx, d.d_inner, rows, d.d_inner, st));
+    BLK_HIP(copy_cols(ws + w.dxbc + (size_t)d.d_inner * 2, d.conv_dim, ws + w.dB, d.gn, rows, d.gn, st));
+    BLK_HIP(copy_cols(ws + w.dxbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, ws + w.dC, d.gn, rows, d.gn, st));
+    const ssd_conv_shape_t cs = conv_shape(d, rows);
+    BLK_TRY(ssd_conv1d_bwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.dxbc, dconv_out,
+                           dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
+    // input projection
+    BLK_TRY(ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, du_seg, 0, g->dW_in, acc, st));
     return SSD_OK;
 }
 
@@ -307,7 +366,8 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
         const void* conv_in = k == 0 ? init_conv : conv_ckpt ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : ws + w.cconv[k & 1];
         float* ssm_out = last ? final_ssm : ssm_ckpt ? ssm_ckpt + (size_t)(k + 1) * d.HPN : (float*)(ws + w.cssm[(k + 1) & 1]);
         void* conv_out = last ? final_conv : conv_ckpt ? (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes : ws + w.cconv[(k + 1) & 1];
-        BLK_TRY(forward_segment(d, sh, p, ws, w, (const char*)u + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, ssm_out, conv_out, st));
+        BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, (const char*)u + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, ssm_out,
+                                conv_out, st));
         BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (char*)out + (size_t)t0 * d.dm * 2, 0, st));
     }
     return SSD_OK;
@@ -344,10 +404,7 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
     const BlockWs w = layout(d, true);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
     char* ws = (char*)workspace;
-    char* zx = ws + w.zx;
-    char* dzx = ws + w.dzx;
     const size_t conv_state_bytes = (size_t)3 * d.conv_dim * 2;
-    const uint32_t acc = SSD_FLAG_ACCUM_PARAM;
     for (int64_t k = d.nseg - 1; k >= 0; --k) {
         const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
         const bool last = k + 1 == d.nseg;
@@ -360,35 +417,9 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
         float* dconv_in = k ? (float*)(ws + w.dconv[k & 1]) : dinit_conv;
         const void* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
         // Recompute_Forward: zxbcdt, (x | B | C), dt, y, normalised y of this segment
-        BLK_TRY(forward_segment(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, nullptr, nullptr, st));
-        // output projection
-        BLK_TRY(ssd_linear_bwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (const char*)dout + (size_t)t0 * d.dm * 2, 0, ws + w.dyn, 0,
-                               g->dW_out, acc, st));
-        // gated normalisation: dy, and dz straight into its columns of d zxbcdt
-        const ssd_norm_shape_t ns = norm_shape(d, rows, sh->eps);
-        BLK_TRY(ssd_gated_norm_bwd(&ns, ws + w.y, zx, p->norm_w, ws + w.dyn, ws + w.dy, dzx, g->dnorm_w, ws + w.inner, w.inner_bytes, acc, st));
-        // scan
-        const ssd_shape_t ss = seg_shape(d, rows);
-        BLK_TRY(ssd_bwd(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_in, ws + w.dy, dssm_out, nullptr, ws + w.dx,
-                        ws + w.ddt, g->dA, ws + w.dB, ws + w.dC, g->dD, dssm_in, ws + w.inner, w.inner_bytes, acc, st));
-        // softplus of dt: into the dt columns of d zxbcdt
-        const int ntile = (int)((rows + DT_ROWS - 1) / DT_ROWS);
-        hipLaunchKernelGGL(k_dt_bwd, dim3(ntile), dim3(256), 0, st, (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
-                           p->dt_bias, (const bf16_t*)(ws + w.ddt), (bf16_t*)(dzx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj,
-                           (float*)(ws + w.dtpart), rows, d.H);
-        BLK_HIP(hipGetLastError());
-        hipLaunchKernelGGL(k_colsum, dim3((d.H + 63) / 64), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H,
-                           g->ddt_bias, 1);
-        BLK_HIP(hipGetLastError());
-        // convolution: (dx | dB | dC) side by side, du into the xBC columns of d zxbcdt
-        BLK_HIP(copy_cols(ws + w.dxbc, d.conv_dim, ws + w.dx, d.d_inner, rows, d.d_inner, st));
-        BLK_HIP(copy_cols(ws + w.dxbc + (size_t)d.d_inner * 2, d.conv_dim, ws + w.dB, d.gn, rows, d.gn, st));
-        BLK_HIP(copy_cols(ws + w.dxbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, ws + w.dC, d.gn, rows, d.gn, st));
-        const ssd_conv_shape_t cs = conv_shape(d, rows);
-        BLK_TRY(ssd_conv1d_bwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.dxbc, dconv_out,
-                               dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
-        // input projection
-        BLK_TRY(ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, (char*)du + (size_t)t0 * d.dm * 2, 0, g->dW_in, acc, st));
+        BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, nullptr, nullptr, st));
+        BLK_TRY(backward_segment(d, sh, p, g, ws, w, ws + w.zx, ws + w.y, u_seg, (const char*)dout + (size_t)t0 * d.dm * 2,
+                                 (char*)du + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, dssm_out, dconv_out, dssm_in, dconv_in, st));
     }
     return SSD_OK;
 }
