@@ -429,9 +429,10 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
 // (Sec. 3.2/3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole sequence
 // (layer-axis checkpoints), the SSM and convolution states of every layer are kept every `segment` tokens
 // (sequence-axis checkpoints).  The backward pass walks the cells right to left and top to bottom: inside a
-// cell it first restores the inputs of the cell's layers from the layer checkpoint (forward calls from the
-// cell's state checkpoints), then back-propagates through the layers top down, each layer's two state
-// adjoints being handed to the cell on its left.  A cell's layer is one single-segment call of the block above.
+// cell it first restores, from the layer checkpoint and the cell's state checkpoints, the input of every layer
+// of the cell together with its zxbcdt and y (the per-token activations C_grid of App. C, Tab. 7 counts), then
+// back-propagates through the layers top down -- redoing only the cheap streaming steps of a layer -- each
+// layer's two state adjoints being handed to the cell on its left.
 namespace ssdk {
 namespace {
 
@@ -481,7 +482,8 @@ magc_block_shape_t cell_shape(const magc_blockstack_shape_t* sh, int64_t rows) {
 }
 
 struct StackWs {
-    size_t act[2], xs, dcur, du, dssm, dconv, fin_ssm, fin_conv, inner, inner_bytes, total;
+    size_t act[2], xs, zx, y, dcur, du, dssm, dconv, fin_ssm, fin_conv, inner, inner_bytes, total;
+    size_t zx_bytes, y_bytes;  // per layer of a cell
 };
 
 StackWs stack_layout(const magc_blockstack_shape_t* sh, const StackDims& d, bool bwd) {
@@ -497,8 +499,13 @@ StackWs stack_layout(const magc_blockstack_shape_t* sh, const StackDims& d, bool
     w.act[1] = take(d.act);
     w.fin_ssm = take(d.b.HPN * 4);
     w.fin_conv = take(d.conv_state);
+    w.zx_bytes = al((size_t)d.b.s * d.b.d_in_proj * 2);
+    w.y_bytes = al((size_t)d.b.s * d.b.d_inner * 2);
     if (bwd) {
         w.xs = take((size_t)d.l * d.act);
+        // what a cell keeps per layer and token besides the layer inputs: zxbcdt and y (C_grid of App. C, Tab. 7)
+        w.zx = take((size_t)d.l * w.zx_bytes);
+        w.y = take((size_t)d.l * w.y_bytes);
         w.dcur = take(d.act);
         w.du = take(d.act);
         w.dssm = take((size_t)d.NL * 2 * d.b.HPN * 4);      // per layer, two buffers used alternately
@@ -511,8 +518,12 @@ StackWs stack_layout(const magc_blockstack_shape_t* sh, const StackDims& d, bool
         const size_t t = magc_block_workspace_bytes(&ct, bwd ? 1 : 0);
         inner = t > inner ? t : inner;
     }
-    const size_t f = magc_block_workspace_bytes(&c, 0);  // the restore runs forward calls too
+    const size_t f = magc_block_workspace_bytes(&c, 0);  // the forward pass calls the block's forward entry point
     inner = f > inner ? f : inner;
+    if (bwd) {  // the backward pass lays a block workspace out in this region itself
+        const size_t own = layout(d.b, true).total;
+        inner = own > inner ? own : inner;
+    }
     w.inner = take(inner);
     w.inner_bytes = inner;
     w.total = off;
@@ -610,24 +621,39 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
     const StackWs w = stack_layout(sh, d, true);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
     char* ws = (char*)workspace;
+    // a cell's layer uses the block's own workspace layout inside the inner region (buffers of one segment;
+    // its scan scratch covers both a whole segment and the short last one)
+    const BlockWs bw = layout(d.b, true);
+    if (bw.total > w.inner_bytes) return SSD_ERR_WORKSPACE;
+    char* bws = ws + w.inner;
     for (int64_t k = d.b.nseg - 1; k >= 0; --k) {
         const int64_t t0 = k * d.b.s, rows = d.b.L - t0 < d.b.s ? d.b.L - t0 : d.b.s;
         const magc_block_shape_t c = cell_shape(sh, rows);
+        BlockDims dc;
+        BLK_TRY(check(&c, &dc));
         const bool last = k + 1 == d.b.nseg;
         const char* dcur = (const char*)dout + (size_t)t0 * row;  // gradient of the stack output for these tokens
         for (int m = d.ngl - 1; m >= 0; --m) {
             const int j0 = m * d.l, j1 = (j0 + d.l < d.NL ? j0 + d.l : d.NL) - 1;
-            // restore the inputs of the cell's layers from its layer checkpoint (Recompute_Forward of Alg. 2)
+            // Recompute_Forward of Alg. 2: from the cell's layer checkpoint and its layers' state checkpoints,
+            // the input x_j, zxbcdt_j and y_j of every layer of the cell
             const char* xin = m ? (const char*)l_ckpt + ((size_t)(m - 1) * d.b.L + t0) * row : (const char*)x0 + (size_t)t0 * row;
-            for (int j = j0; j < j1; ++j) {
+            for (int j = j0; j <= j1; ++j) {
                 const float* ssm_in = k ? ssm_ckpt + ((size_t)j * d.b.nseg + k) * d.b.HPN : nullptr;
                 const void* conv_in = k ? (const char*)conv_ckpt + ((size_t)j * d.b.nseg + k) * d.conv_state : nullptr;
-                char* y = ws + w.act[0];
-                BLK_TRY(magc_block_fwd(&c, &params[j], xin, ssm_in, conv_in, y, nullptr, nullptr, nullptr, nullptr, ws + w.inner,
-                                       w.inner_bytes, st));
-                char* nxt = ws + w.xs + (size_t)(j - j0 + 1) * d.act;
-                BLK_HIP(add_bf16(nxt, xin, y, rows * d.b.dm, st));
-                xin = nxt;
+                char* zx = ws + w.zx + (size_t)(j - j0) * w.zx_bytes;
+                char* y = ws + w.y + (size_t)(j - j0) * w.y_bytes;
+                BLK_TRY(seg_in_proj(dc, &params[j], xin, rows, zx, st));
+                BLK_TRY(seg_mid(dc, &params[j], bws, bw, zx, rows, conv_in, nullptr, st));
+                BLK_TRY(seg_scan(dc, &params[j], bws, bw, rows, ssm_in, nullptr, y, st));
+                if (j < j1) {  // the next layer's input
+                    BLK_TRY(seg_norm(dc, &c, &params[j], bws, bw, zx, y, rows, st));
+                    char* out = ws + w.act[0];
+                    BLK_TRY(ssd_linear_fwd(rows, d.b.d_inner, d.b.dm, bws + bw.yn, 0, params[j].W_out, out, 0, st));
+                    char* nxt = ws + w.xs + (size_t)(j - j0 + 1) * d.act;
+                    BLK_HIP(add_bf16(nxt, xin, out, rows * d.b.dm, st));
+                    xin = nxt;
+                }
             }
             // back through the layers, top down: dx_j = dx_{j+1} + Block_j^T(dx_{j+1})
             for (int j = j1; j >= j0; --j) {
@@ -635,13 +661,18 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
                                          : ws + w.xs + (size_t)(j - j0) * d.act;
                 const float* ssm_in = k ? ssm_ckpt + ((size_t)j * d.b.nseg + k) * d.b.HPN : nullptr;
                 const void* conv_in = k ? (const char*)conv_ckpt + ((size_t)j * d.b.nseg + k) * d.conv_state : nullptr;
+                const char* zx = ws + w.zx + (size_t)(j - j0) * w.zx_bytes;
+                const char* y = ws + w.y + (size_t)(j - j0) * w.y_bytes;
+                // the cheap steps again from zxbcdt_j and y_j: (x | B | C), dt, the normalised y
+                BLK_TRY(seg_mid(dc, &params[j], bws, bw, zx, rows, conv_in, nullptr, st));
+                BLK_TRY(seg_norm(dc, &c, &params[j], bws, bw, zx, y, rows, st));
                 // this layer's state adjoints: written for segment k into buffer k % 2, read by segment k - 1 from it
                 float* dssm_w = (float*)(ws + w.dssm + ((size_t)j * 2 + (k & 1)) * d.b.HPN * 4);
                 float* dconv_w = (float*)(ws + w.dconv + ((size_t)j * 2 + (k & 1)) * d.conv_adj);
                 const float* dssm_r = last ? nullptr : (const float*)(ws + w.dssm + ((size_t)j * 2 + ((k + 1) & 1)) * d.b.HPN * 4);
                 const float* dconv_r = last ? nullptr : (const float*)(ws + w.dconv + ((size_t)j * 2 + ((k + 1) & 1)) * d.conv_adj);
-                BLK_TRY(magc_block_bwd(&c, &params[j], xj, ssm_in, conv_in, dcur, dssm_r, dconv_r, nullptr, nullptr, ws + w.du, &grads[j],
-                                       k ? dssm_w : nullptr, k ? dconv_w : nullptr, ws + w.inner, w.inner_bytes, SSD_FLAG_ACCUM_PARAM, st));
+                BLK_TRY(backward_segment(dc, &c, &params[j], &grads[j], bws, bw, zx, y, xj, dcur, ws + w.du, rows, ssm_in, conv_in, dssm_r,
+                                         dconv_r, k ? dssm_w : nullptr, k ? dconv_w : nullptr, st));
                 char* dnext = (j == 0) ? (char*)dx0 + (size_t)t0 * row : ws + w.dcur;
                 BLK_HIP(add_bf16(dnext, dcur, ws + w.du, rows * d.b.dm, st));
                 dcur = dnext;
