@@ -4,15 +4,15 @@
 // grid-cell activations of App. C, Tab. 7, and the output projection behind the gated normalisation).
 // These are dense contractions far above the machine's flop/byte ridge: matrix-core bound.
 //
-// One kernel, C[M,N] = op(A) op(B)^T with fp32 accumulators in v_mfma_f32_32x32x16_bf16 tiles, for the three
+// One scheme, C[M,N] = op(A) op(B)^T with fp32 accumulators in v_mfma_f32_32x32x16_bf16 tiles, for the three
 // operand layouts the three products need: an operand is either stored with the contraction index
 // contiguous ("k-major": rows of x for the forward product) or with it as the row index (x and dout for
 // dw, w for dx).  Both kinds are staged in LDS exactly as they lie in memory (16-byte vectors); k-major
 // tiles are read back as plain 16-byte operands, the others through the transposing LDS read.
-// Workgroup tile 256 x 128, K step 64, four waves of 128 x 64 (4 x 2 MFMA tiles, 128 accumulator
-// registers): 6 operand reads per 8 MFMAs keeps the LDS below its bandwidth.  The next K step's global
-// loads are in flight while the current one is multiplied.  Workgroup ids are remapped so that each XCD
-// works on a compact block of the tile grid (its L2 then holds the A and B panels that block shares).
+// Two tilings: 256 x 256 per workgroup (four waves of 128 x 128: the whole accumulator file, one workgroup per
+// compute unit, hand-laid-out K step; k_gemm_big) wherever that yields enough tiles, else 256 x 128 (two
+// workgroups per compute unit; k_gemm).  Workgroup ids are remapped so that each XCD works on a compact
+// block of the tile grid (its L2 then holds the A and B panels that block shares).
 #include <stdlib.h>
 #include <string.h>
 
@@ -150,14 +150,16 @@ __device__ __forceinline__ void store_acc(const GemmParams& gp, const f32x16 (&a
     }
 }
 
-// WI x WJ MFMA tiles per wave, 2 x 2 waves: workgroup tile (64 WI) x (64 WJ).  DB: two LDS buffers, one
-// barrier per K step (the tile of step k+1 is written while step k is multiplied); otherwise one buffer
-// and two barriers, for configurations whose registers and LDS leave room for two workgroups per compute unit.
-template <bool AK, bool BK, int WI, int WJ, bool DB>
-__global__ __launch_bounds__(256, DB ? 1 : 2) void k_gemm(GemmParams gp) {
+// WI x WJ MFMA tiles per wave, 2 x 2 waves: workgroup tile (64 WI) x (64 WJ), one LDS buffer, two barriers per
+// K step; registers and LDS leave room for two workgroups per compute unit, which cover each other's waits.
+// Used where the large tiles below would be too few to fill the machine.
+template <bool AK, bool BK, int WI, int WJ>
+__global__ __launch_bounds__(256, 2) void k_gemm(GemmParams gp) {
     constexpr int BM = 64 * WI, BN = 64 * WJ;
-    constexpr int A_BYTES = tile_bytes<BM, AK>(), B_BYTES = tile_bytes<BN, BK>();
-    extern __shared__ __attribute__((aligned(16))) char lds[];  // (DB ? 2 : 1) x (A tile, B tile)
+    constexpr int A_BYTES = tile_bytes<BM, AK>();
+    extern __shared__ __attribute__((aligned(16))) char lds[];  // A tile, B tile
+    char* As = lds;
+    char* Bs = lds + A_BYTES;
     const int tid = threadIdx.x, lane = tid & 63, w = tid >> 6;
     const int wm = w >> 1, wn = w & 1;
     int tm, tn;
@@ -186,22 +188,11 @@ __global__ __launch_bounds__(256, DB ? 1 : 2) void k_gemm(GemmParams gp) {
         }
     };
     fetch(0);
-    if (DB) {
-        store_tile<BM, AK>(lds, tid, ra);
-        store_tile<BN, BK>(lds + A_BYTES, tid, rb);
-        __syncthreads();
-    }
-    int cur = 0;
     for (int k0 = 0; k0 < gp.K; k0 += BKK) {
-        char* As = lds + (DB ? cur * (A_BYTES + B_BYTES) : 0);
-        char* Bs = As + A_BYTES;
-        const bool more = k0 + BKK < gp.K;
-        if (!DB) {
-            store_tile<BM, AK>(As, tid, ra);
-            store_tile<BN, BK>(Bs, tid, rb);
-            __syncthreads();
-        }
-        if (more) fetch(k0 + BKK);  // next step's loads fly during the products
+        store_tile<BM, AK>(As, tid, ra);
+        store_tile<BN, BK>(Bs, tid, rb);
+        __syncthreads();
+        if (k0 + BKK < gp.K) fetch(k0 + BKK);  // next step's loads fly during the products
 #pragma unroll
         for (int kk = 0; kk < BKK; kk += 16) {
             bf16x8 a[WI], b[WJ];
@@ -214,18 +205,10 @@ __global__ __launch_bounds__(256, DB ? 1 : 2) void k_gemm(GemmParams gp) {
 #pragma unroll
                 for (int j = 0; j < WJ; ++j) acc[i][j] = mfma(b[j], a[i], acc[i][j]);
         }
-        if (DB) {
-            if (more) {
-                char* An = lds + (cur ^ 1) * (A_BYTES + B_BYTES);
-                store_tile<BM, AK>(An, tid, ra);
-                store_tile<BN, BK>(An + A_BYTES, tid, rb);
-            }
-            cur ^= 1;
-        }
         __syncthreads();
     }
 
-    store_acc<WI, WJ>(gp, acc, m0 + wm * 32 * WI, n0 + wn * 32 * WJ, lane, m0 + BM <= gp.M && n0 + BN <= gp.N);
+    store_acc<WI, WJ>(gp, acc, m0 + wm * 32 * WI, n0 + wn * 32 * WJ, lane, interior);
 }
 
 // 256 x 256 tile, four waves of 128 x 128 (4 x 4 MFMA tiles: the whole accumulator register file), one
@@ -411,14 +394,14 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(GemmParams gp) {
 
 bool ok_ptr(const void* p) { return p && ((uintptr_t)p & 15) == 0; }
 
-template <bool AK, bool BK, int WI, int WJ, bool DB>
+template <bool AK, bool BK, int WI, int WJ>
 hipError_t launch_cfg(GemmParams gp, hipStream_t st) {
     constexpr int BM = 64 * WI, BN = 64 * WJ;
-    constexpr int LDS = (DB ? 2 : 1) * (tile_bytes<BM, AK>() + tile_bytes<BN, BK>());
+    constexpr int LDS = tile_bytes<BM, AK>() + tile_bytes<BN, BK>();
     static_assert(LDS <= 65536, "beyond the default dynamic LDS limit");
     gp.tiles_m = (gp.M + BM - 1) / BM;
     gp.tiles_n = (gp.N + BN - 1) / BN;
-    hipLaunchKernelGGL((k_gemm<AK, BK, WI, WJ, DB>), dim3(gp.tiles_m * gp.tiles_n), dim3(256), LDS, st, gp);
+    hipLaunchKernelGGL((k_gemm<AK, BK, WI, WJ>), dim3(gp.tiles_m * gp.tiles_n), dim3(256), LDS, st, gp);
     return hipGetLastError();
 }
 
@@ -453,7 +436,7 @@ hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
     if (forced != 128 && forced != 256) {
         big = (int64_t)((gp.M + 255) / 256) * ((gp.N + 255) / 256) >= 128;
     }
-    return big ? launch_big<AK, BK>(gp, st) : launch_cfg<AK, BK, 4, 2, false>(gp, st);
+    return big ? launch_big<AK, BK>(gp, st) : launch_cfg<AK, BK, 4, 2>(gp, st);
 }
 
 int check(int64_t rows, int32_t in_dim, int32_t out_dim, int64_t ldx, int64_t ldo) {
