@@ -214,7 +214,7 @@ __global__ __launch_bounds__(256, 2) void k_gemm(GemmParams gp) {
 // 256 x 256 tile, four waves of 128 x 128 (4 x 4 MFMA tiles: the whole accumulator register file), one
 // workgroup per compute unit, two LDS buffers.  With a single wave per SIMD nothing else hides latency, so
 // the K step is laid out by hand as 16 units of four MFMAs (one A operand against the four B operands of
-// its k slice); behind each MFMA sit the LDS reads of later operands and (last four units) one vector of
+// its k slice); behind each MFMA sit the LDS reads of later operands and (last eight units) one vector of
 // the next tile's LDS writes with the global load that refills its register for the tile after that.
 // Registers thus hold the tile two K steps ahead of the one being multiplied: a vector is written to LDS
 // in the second half of a step and its register is refilled at once, so that a load has a whole step of
@@ -260,7 +260,7 @@ __device__ __forceinline__ void big_step(const BigCtx& cx, f32x16 (&acc)[4][4], 
             if (j == 0 && u + 1 < 16) aq[(u + 1) & 1] = operand<BM, AK>(As, cx.wm * 128 + ((u + 1) & 3) * 32, ((u + 1) >> 2) * 16, lane);
             if (i == 1 && kk < 3) bq[(kk + 1) & 1][j] = operand<BN, BK>(Bs, cx.wn * 128 + j * 32, (kk + 1) * 16, lane);
             if (STEADY) {
-                // units 12..15: one vector per MFMA goes to LDS and its register is refilled (A, A, B, B per unit)
+                // units 8..15: behind MFMA 0 a vector of A, behind MFMA 2 a vector of B goes to LDS and its register is refilled
 #define GEMM_PART(U, J, OP_A, V)                                                                  \
     if (u == U && j == J) {                                                                       \
         if (OP_A) {                                                                               \
@@ -271,10 +271,10 @@ __device__ __forceinline__ void big_step(const BigCtx& cx, f32x16 (&acc)[4][4], 
             load_tile<BN, BK, false, V, V + 1>(bo, cx.ldb, cx.vb, 0, 0, tid, rb);                 \
         }                                                                                         \
     }
-                GEMM_PART(12, 0, true, 0) GEMM_PART(12, 1, true, 1) GEMM_PART(12, 2, false, 0) GEMM_PART(12, 3, false, 1)
-                GEMM_PART(13, 0, true, 2) GEMM_PART(13, 1, true, 3) GEMM_PART(13, 2, false, 2) GEMM_PART(13, 3, false, 3)
-                GEMM_PART(14, 0, true, 4) GEMM_PART(14, 1, true, 5) GEMM_PART(14, 2, false, 4) GEMM_PART(14, 3, false, 5)
-                GEMM_PART(15, 0, true, 6) GEMM_PART(15, 1, true, 7) GEMM_PART(15, 2, false, 6) GEMM_PART(15, 3, false, 7)
+                GEMM_PART(8, 0, true, 0) GEMM_PART(8, 2, false, 0) GEMM_PART(9, 0, true, 1) GEMM_PART(9, 2, false, 1)
+                GEMM_PART(10, 0, true, 2) GEMM_PART(10, 2, false, 2) GEMM_PART(11, 0, true, 3) GEMM_PART(11, 2, false, 3)
+                GEMM_PART(12, 0, true, 4) GEMM_PART(12, 2, false, 4) GEMM_PART(13, 0, true, 5) GEMM_PART(13, 2, false, 5)
+                GEMM_PART(14, 0, true, 6) GEMM_PART(14, 2, false, 6) GEMM_PART(15, 0, true, 7) GEMM_PART(15, 2, false, 7)
 #undef GEMM_PART
             } else if (u == 8 && j == 0 && more) {
                 store_tile<BM, AK>(An, tid, ra);
@@ -330,12 +330,12 @@ __global__ __launch_bounds__(256, 1) void k_gemm_big(GemmParams gp) {
         // the same order of loads (A and B vector by vector) as inside the loop, so that the count of
         // loads still outstanding at the loop's first LDS write is the same on entry and on every repeat
 #define GEMM_PRO(P, KOFF)                                                                                          \
-    load_tile<BM, AK, false, P, P + 2>(cx.a_org + (int64_t)(KOFF) * cx.a_kstep, gp.lda, cx.va, 0, 0, tid, ra);      \
-    load_tile<BN, BK, false, P, P + 2>(cx.b_org + (int64_t)(KOFF) * cx.b_kstep, gp.ldb, cx.vb, 0, 0, tid, rb);
-        GEMM_PRO(0, 0) GEMM_PRO(2, 0) GEMM_PRO(4, 0) GEMM_PRO(6, 0)
+    load_tile<BM, AK, false, P, P + 1>(cx.a_org + (int64_t)(KOFF) * cx.a_kstep, gp.lda, cx.va, 0, 0, tid, ra);      \
+    load_tile<BN, BK, false, P, P + 1>(cx.b_org + (int64_t)(KOFF) * cx.b_kstep, gp.ldb, cx.vb, 0, 0, tid, rb);
+        GEMM_PRO(0, 0) GEMM_PRO(1, 0) GEMM_PRO(2, 0) GEMM_PRO(3, 0) GEMM_PRO(4, 0) GEMM_PRO(5, 0) GEMM_PRO(6, 0) GEMM_PRO(7, 0)
         store_tile<BM, AK>(lds, tid, ra);
         store_tile<BN, BK>(lds + A_BYTES, tid, rb);
-        GEMM_PRO(0, BKK) GEMM_PRO(2, BKK) GEMM_PRO(4, BKK) GEMM_PRO(6, BKK)
+        GEMM_PRO(0, BKK) GEMM_PRO(1, BKK) GEMM_PRO(2, BKK) GEMM_PRO(3, BKK) GEMM_PRO(4, BKK) GEMM_PRO(5, BKK) GEMM_PRO(6, BKK) GEMM_PRO(7, BKK)
 #undef GEMM_PRO
     } else {
         load_tile<BM, AK, true>(cx.a_org, gp.lda, cx.va, cx.rows_a, gp.K, tid, ra);
