@@ -191,6 +191,8 @@ int ssd_conv1d_bwd(const ssd_conv_shape_t* shape, const void* u, const float* w,
  *          SSD_FLAG_ACCUM_PARAM (the only flag)
  *   workspace: ssd_gated_norm_workspace_bytes(shape) bytes of device scratch, 256-byte aligned
  *          (partial sums of dw; backward only)
+ * z == NULL: no gate -- the plain RMS normalisation out = y / sqrt(mean y^2 + eps) * w (the layer's
+ * pre-norm); dz is then not written and may be NULL.
  * Tokens are independent: a segment of the sequence is a row range, no state is carried.  Inputs and
  * outputs must not overlap.  rows == 0 is allowed.
  * Errors: SSD_ERR_NULL, SSD_ERR_DTYPE, SSD_ERR_SHAPE (sizes, strides below dim), SSD_ERR_DIVISIBILITY
@@ -277,7 +279,10 @@ int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  *   dinit_ssm, dinit_conv: adjoints of the initial states (same shapes, fp32), may be NULL.  With them a
  *             caller can cut a sequence into pieces of its own and chain the calls, as the block does inside.
  *   params: W_in [d_in_proj, d_model] bf16, conv_w [conv_dim, 4], conv_b [conv_dim], dt_bias [H], A [H],
- *           D [H], norm_w [d_inner] fp32, W_out [d_model, d_inner] bf16
+ *           D [H], norm_w [d_inner] fp32, W_out [d_model, d_inner] bf16;
+ *           pre_norm_w [d_model] fp32 or NULL.  Not NULL: the block starts with the RMS normalisation that a
+ *           language-model layer puts in front of its mixer (same eps, one group), zxbcdt = RMSNorm(u) pre_norm_w
+ *           W_in^T; the normalised input is recomputed per segment, never kept.  grads.dpre_norm_w is then needed.
  *   grads:  the same shapes, all fp32, overwritten or added to under SSD_FLAG_ACCUM_PARAM (the only flag)
  *   workspace: magc_block_workspace_bytes bytes, 256-byte aligned; scales with `segment`, not seqlen
  * d_model, d_inner, G N and H must be multiples of 8 (SSD_ERR_DIVISIBILITY), segment a multiple of chunk;
@@ -297,6 +302,7 @@ typedef struct {
     const float* D;
     const float* norm_w;
     const void* W_out;
+    const float* pre_norm_w;   /* may be NULL */
 } magc_block_params_t;
 typedef struct {
     float* dW_in;
@@ -307,6 +313,7 @@ typedef struct {
     float* dD;
     float* dnorm_w;
     float* dW_out;
+    float* dpre_norm_w;        /* used only when params.pre_norm_w is given */
 } magc_block_grads_t;
 size_t magc_block_workspace_bytes(const magc_block_shape_t* shape, int32_t is_backward);
 int magc_block_fwd(const magc_block_shape_t* shape, const magc_block_params_t* params, const void* u,
@@ -319,8 +326,8 @@ int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* p
                    size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /*
- * A stack of whole blocks with residual adds, x_{j+1} = x_j + Block_j(x_j), on the two-axis grid of MA-GC
- * (Sec. 3.2 / 3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole
+ * A stack of whole blocks with residual adds, x_{j+1} = x_j + Block_j(x_j) (with pre_norm_w: the pre-norm
+ * residual layer of the language model), on the two-axis grid of MA-GC (Sec. 3.2 / 3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole
  * sequence, the SSM and convolution states of every layer every `segment` tokens (block.seqlen, block.segment);
  * the backward pass walks the grid cell by cell, restores a cell's layer inputs from its two kinds of
  * checkpoint and back-propagates through it.

@@ -7,11 +7,13 @@ defined next to this file, and of its reverse mode:
     dt     = softplus(dt_raw + dt_bias)
     y      = SSD(x, dt, A, B, C, D)   with (x | B | C) = xBC      (SSM state)
     out    = RMSNorm_G(y * silu(z)) * norm_w  W_out^T
+With the optional parameter pre_norm_w the projection reads RMSNorm(u) * pre_norm_w instead of u: together
+with the residual add of the stack below that is the pre-norm layer of the language model.
 
 Only tests, the smoke check and benchmark baselines may import this.
 
 `store`, if given, is the rounding of the storage dtype: every intermediate tensor that the device path
-keeps in memory between two steps (zxbcdt, xBC, dt, y, the normalised y, out, and in the backward sweep
+keeps in memory between two steps (the normalised input, zxbcdt, xBC, dt, y, the normalised y, out, and in the backward sweep
 the gradients of the same tensors) is rounded once where it is stored; with store=None everything stays fp64.
 One sequence (batch 1).
 """
@@ -33,11 +35,13 @@ def dims(p, H, P, G, N):
 
 
 def block_fwd(u, p, H, P, G, N, eps=1e-5, conv_state=None, ssm_state=None, store=None):
-    """u [L, d_model]; p: W_in, conv_w, conv_b, dt_bias, A, D, norm_w, W_out.  Returns dict with out and
+    """u [L, d_model]; p: W_in, conv_w, conv_b, dt_bias, A, D, norm_w, W_out and, optionally, pre_norm_w (then the
+    input projection reads RMSNorm(u) * pre_norm_w: the pre-norm of a language-model layer).  Returns dict with out and
     every intermediate (for the backward pass), plus the states leaving the sequence."""
     L = u.shape[0]
     d_inner, conv_dim, d_in_proj = dims(p, H, P, G, N)
-    zx = _st(store, linear_ref.linear_fwd(u, p["W_in"]))
+    un = u if p.get("pre_norm_w") is None else _st(store, norm_ref.gated_rmsnorm_fwd(u, None, p["pre_norm_w"], eps, 1))
+    zx = _st(store, linear_ref.linear_fwd(un, p["W_in"]))
     z, pre, dt_raw = zx[:, :d_inner], zx[:, d_inner:d_inner + conv_dim], zx[:, d_inner + conv_dim:]
     c = conv_ref.conv1d_silu_fwd(pre[None], p["conv_w"], p["conv_b"], None if conv_state is None else conv_state[None])
     xBC = _st(store, c["out"][0])
@@ -50,7 +54,7 @@ def block_fwd(u, p, H, P, G, N, eps=1e-5, conv_state=None, ssm_state=None, store
     y = _st(store, r["y"][0].reshape(L, d_inner))
     yn = _st(store, norm_ref.gated_rmsnorm_fwd(y, z, p["norm_w"], eps, G))
     out = _st(store, linear_ref.linear_fwd(yn, p["W_out"]))
-    return {"out": out, "zxbcdt": zx, "xBC": xBC, "dt": dt, "y": y, "yn": yn,
+    return {"out": out, "un": un, "zxbcdt": zx, "xBC": xBC, "dt": dt, "y": y, "yn": yn,
             "conv_state": c["state_out"][0], "ssm_state": r["final_state"][0]}
 
 
@@ -80,8 +84,12 @@ def block_bwd(u, p, H, P, G, N, dout, eps=1e-5, conv_state=None, ssm_state=None,
     gc = conv_ref.conv1d_silu_bwd(pre[None], p["conv_w"], p["conv_b"], None if conv_state is None else conv_state[None],
                                   dxBC[None], None if dconv_state is None else dconv_state[None])
     dzx = _st(store, np.concatenate([dz, gc["du"][0], draw], axis=1))
-    gi = linear_ref.linear_bwd(u, p["W_in"], dzx)
-    return {"du": _st(store, gi["dx"]), "dW_in": gi["dw"], "dconv_w": gc["dw"], "dconv_b": gc["dbias"],
+    gi = linear_ref.linear_bwd(f["un"], p["W_in"], dzx)
+    du, extra = _st(store, gi["dx"]), {}
+    if p.get("pre_norm_w") is not None:   # back through the normalisation in front of the projection
+        gp = norm_ref.gated_rmsnorm_bwd(u, None, p["pre_norm_w"], du, eps, 1)
+        du, extra = _st(store, gp["dy"]), {"dpre_norm_w": gp["dw"]}
+    return {**extra, "du": du, "dW_in": gi["dw"], "dconv_w": gc["dw"], "dconv_b": gc["dbias"],
             "ddt_bias": draw.sum(axis=0), "dA": gs["dA"], "dD": gs["dD"], "dnorm_w": gn["dw"], "dW_out": go["dw"],
             "dconv_state_in": gc["dstate_in"][0], "dssm_state_in": gs["dinit_state"][0]}
 

@@ -8,6 +8,7 @@ Only tests, the smoke check and benchmark baselines may import this.
     g = y * z * sigmoid(z)                                   (gate first, then normalise)
     out[t, c] = g[t, c] / sqrt(mean_{c' in group(c)} g[t, c']^2 + eps) * w[c]
 The channels are cut into `ngroups` contiguous groups of equal size, each normalised on its own.
+z=None takes the gate away (g = y): the plain RMS normalisation that stands in front of each block.
 """
 from __future__ import annotations
 
@@ -16,6 +17,8 @@ import numpy as np
 
 def _gate(y, z):
     y = np.asarray(y, dtype=np.float64)
+    if z is None:
+        return y, None, None, y
     z = np.asarray(z, dtype=np.float64)
     sig = 1.0 / (1.0 + np.exp(-z))
     return y, z, sig, y * z * sig
@@ -43,5 +46,7 @@ def gated_rmsnorm_bwd(y, z, w, dout, eps=1e-5, ngroups=1):
     dghat = (dout * w).reshape(T, ngroups, gs)
     # d/dg of ghat = g * (mean g^2 + eps)^(-1/2):  rstd * (dghat - ghat * mean(dghat * ghat))
     dg = (rstd * (dghat - ghat * np.mean(dghat * ghat, axis=2, keepdims=True))).reshape(T, C)
-    return {"dy": dg * z * sig, "dz": dg * y * sig * (1.0 + z * (1.0 - sig)),
-            "dw": np.sum(dout * ghat.reshape(T, C), axis=0)}
+    dw = np.sum(dout * ghat.reshape(T, C), axis=0)
+    if z is None:
+        return {"dy": dg, "dz": None, "dw": dw}
+    return {"dy": dg * z * sig, "dz": dg * y * sig * (1.0 + z * (1.0 - sig)), "dw": dw}

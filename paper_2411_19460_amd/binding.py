@@ -48,7 +48,7 @@ class magc_block_shape_t(ctypes.Structure):
                 ("segment", ctypes.c_int64)]
 
 
-BLOCK_PARAMS = ("W_in", "conv_w", "conv_b", "dt_bias", "A", "D", "norm_w", "W_out")
+BLOCK_PARAMS = ("W_in", "conv_w", "conv_b", "dt_bias", "A", "D", "norm_w", "W_out", "pre_norm_w")   # the last one is optional
 
 
 class magc_block_params_t(ctypes.Structure):
@@ -328,7 +328,7 @@ def ssd_conv1d_bwd(u, w, bias, state_in, dout, dstate_out=None, want_dstate=True
 def _norm_shape(y, z, ngroups, eps, *same_as):
     """y, z: [rows, dim] with unit stride along dim (rows may be a column slice of a wider tensor)."""
     import torch
-    for t in (y, z):
+    for t in (y,) if z is None else (y, z):
         if t.dim() != 2 or not t.is_cuda or (t.shape[1] > 1 and t.stride(1) != 1) or t.shape != y.shape or t.dtype != y.dtype:
             raise ValueError("y and z must be [rows, dim] device tensors of one dtype with unit stride along dim")
     for t, like in same_as:
@@ -338,7 +338,7 @@ def _norm_shape(y, z, ngroups, eps, *same_as):
     if dt == SSD_F32 and y.dtype != torch.float32:
         raise TypeError("dtype must be float32 or bfloat16")
     T, C = y.shape
-    return ssd_norm_shape_t(dt, C, ngroups, eps, T, y.stride(0) if T > 1 else C, z.stride(0) if T > 1 else C)
+    return ssd_norm_shape_t(dt, C, ngroups, eps, T, y.stride(0) if T > 1 else C, z.stride(0) if z is not None and T > 1 else C)
 
 
 def _norm_weight(w, C):
@@ -348,7 +348,7 @@ def _norm_weight(w, C):
 
 
 def ssd_gated_norm_fwd(y, z, w, eps=1e-5, ngroups=1):
-    """out = RMSNorm_groups(y * silu(z)) * w for y, z [rows, dim]; out is dense."""
+    """out = RMSNorm_groups(y * silu(z)) * w for y, z [rows, dim]; out is dense.  z=None: no gate."""
     import torch
     shape = _norm_shape(y, z, ngroups, eps)
     _norm_weight(w, y.shape[1])
@@ -360,13 +360,19 @@ def ssd_gated_norm_fwd(y, z, w, eps=1e-5, ngroups=1):
 
 
 def ssd_gated_norm_bwd(y, z, w, dout, eps=1e-5, ngroups=1, flags=0, dy=None, dz=None, dw=None):
-    """dict(dy, dz, dw) for the loss <dout, out>.  dy / dz may be given (laid out as y / z, e.g. column slices)."""
+    """dict(dy, dz, dw) for the loss <dout, out>.  dy / dz may be given (laid out as y / z, e.g. column slices).
+    z=None: no gate, dz stays None."""
     import torch
     if dy is None:
         dy = torch.empty_strided(y.shape, y.stride(), dtype=y.dtype, device=y.device)
-    if dz is None:
-        dz = torch.empty_strided(z.shape, z.stride(), dtype=z.dtype, device=z.device)
-    shape = _norm_shape(y, z, ngroups, eps, (dy, y), (dz, z))
+    if z is None:
+        if dz is not None:
+            raise ValueError("dz without z")
+        shape = _norm_shape(y, None, ngroups, eps, (dy, y))
+    else:
+        if dz is None:
+            dz = torch.empty_strided(z.shape, z.stride(), dtype=z.dtype, device=z.device)
+        shape = _norm_shape(y, z, ngroups, eps, (dy, y), (dz, z))
     _norm_weight(w, y.shape[1])
     if not dout.is_cuda or not dout.is_contiguous() or dout.shape != y.shape or dout.dtype != y.dtype:
         raise ValueError("dout must be a dense [rows, dim] device tensor of y's dtype")
@@ -437,13 +443,15 @@ def _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, ep
     want = {"W_in": ((d_in_proj, dm), torch.bfloat16), "conv_w": ((conv_dim, 4), torch.float32), "conv_b": ((conv_dim,), torch.float32),
             "dt_bias": ((nheads,), torch.float32), "A": ((nheads,), torch.float32), "D": ((nheads,), torch.float32),
             "norm_w": ((d_inner,), torch.float32), "W_out": ((dm, d_inner), torch.bfloat16)}
+    if params.get("pre_norm_w") is not None:
+        want["pre_norm_w"] = ((dm,), torch.float32)
     for k, (shp, dty) in want.items():
         t = params[k]
         if tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"params[{k!r}] must be a dense {dty} device tensor of shape {shp}")
     seg = segment if segment is not None else max(chunk, -(-L // chunk) * chunk)
     shape = magc_block_shape_t(dm, nheads, headdim, ngroups, dstate, chunk, eps, L, seg)
-    par = magc_block_params_t(*[_ptr(params[k]) for k in BLOCK_PARAMS])
+    par = magc_block_params_t(*[_ptr(params.get(k)) for k in BLOCK_PARAMS])
     nseg = max(1, -(-L // seg))
     return shape, par, want, nseg, conv_dim
 
@@ -479,7 +487,7 @@ def magc_block_fwd(u, params, nheads, headdim, ngroups, dstate, chunk, segment=N
 
 def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment=None, eps=1e-5,
                    flags=0, grads=None, init_ssm=None, init_conv=None, dfinal_ssm=None, dfinal_conv=None, want_dinit=False):
-    """dict(du, dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out[, dinit_ssm, dinit_conv]) for the loss
+    """dict(du, dW_in, dconv_w, dconv_b, ddt_bias, dA, dD, dnorm_w, dW_out[, dpre_norm_w][, dinit_ssm, dinit_conv]) for the loss
     <dout, out> + <dfinal_ssm, final_ssm> + <dfinal_conv, final_conv>."""
     import torch
     shape, par, want, nseg, conv_dim = _block_setup(u, params, nheads, headdim, ngroups, dstate, chunk, segment, eps)
@@ -491,10 +499,12 @@ def magc_block_bwd(u, params, dout, ssm_ckpt, conv_ckpt, nheads, headdim, ngroup
     if grads is None:
         grads = {"d" + k: torch.empty(shp, dtype=torch.float32, device=dev) for k, (shp, _) in want.items()}
     for k, (shp, _) in want.items():
-        t = grads["d" + k]
+        t = grads.get("d" + k)
+        if t is None:   # the library refuses a missing one
+            continue
         if tuple(t.shape) != shp or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
             raise ValueError(f"grads['d{k}'] must be a dense fp32 device tensor of shape {shp}")
-    gr = magc_block_grads_t(*[_ptr(grads["d" + k]) for k in BLOCK_PARAMS])
+    gr = magc_block_grads_t(*[_ptr(grads.get("d" + k)) for k in BLOCK_PARAMS])
     du = torch.empty_like(u)
     dinit_ssm = torch.empty((nheads, headdim, dstate), dtype=torch.float32, device=dev) if want_dinit else None
     dinit_conv = torch.empty((3, conv_dim), dtype=torch.float32, device=dev) if want_dinit else None
@@ -514,7 +524,9 @@ def _blockstack_setup(x0, layers, nheads, headdim, ngroups, dstate, chunk, segme
     shape, _, want, nseg, conv_dim = _block_setup(x0, layers[0], nheads, headdim, ngroups, dstate, chunk, segment, eps)
     for p in layers[1:]:
         _block_setup(x0, p, nheads, headdim, ngroups, dstate, chunk, segment, eps)
-    pars = (magc_block_params_t * len(layers))(*[magc_block_params_t(*[_ptr(p[k]) for k in BLOCK_PARAMS]) for p in layers])
+    if any((p.get("pre_norm_w") is None) != (layers[0].get("pre_norm_w") is None) for p in layers):
+        raise ValueError("either every layer has pre_norm_w or none")
+    pars = (magc_block_params_t * len(layers))(*[magc_block_params_t(*[_ptr(p.get(k)) for k in BLOCK_PARAMS]) for p in layers])
     sshape = magc_blockstack_shape_t(shape, len(layers), layer_interval)
     return sshape, pars, want, nseg, conv_dim
 
@@ -548,10 +560,12 @@ def magc_blockstack_bwd(x0, layers, dout, l_ckpt, ssm_ckpt, conv_ckpt, nheads, h
         grads = [{"d" + k: torch.empty(shp, dtype=torch.float32, device=dev) for k, (shp, _) in want.items()} for _ in layers]
     for g in grads:
         for k, (shp, _) in want.items():
-            t = g["d" + k]
+            t = g.get("d" + k)
+            if t is None:
+                continue
             if tuple(t.shape) != shp or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
                 raise ValueError(f"grads['d{k}'] must be a dense fp32 device tensor of shape {shp}")
-    grs = (magc_block_grads_t * len(layers))(*[magc_block_grads_t(*[_ptr(g["d" + k]) for k in BLOCK_PARAMS]) for g in grads])
+    grs = (magc_block_grads_t * len(layers))(*[magc_block_grads_t(*[_ptr(g.get("d" + k)) for k in BLOCK_PARAMS]) for g in grads])
     if dout.shape != x0.shape or dout.dtype != x0.dtype or not dout.is_cuda or not dout.is_contiguous():
         raise ValueError("dout must match x0")
     dx0 = torch.empty_like(x0)

@@ -2,6 +2,7 @@
 // Alg. 1/2 with one layer): per segment of `segment` tokens
 //     zxbcdt = u W_in^T = (z | xBC | dt_raw);   xBC = silu(conv4(xBC) + b);   dt = softplus(dt_raw + dt_bias)
 //     y = SSD(x, dt, A, B, C, D) with (x | B | C) = xBC;   out = RMSNorm_G(y silu(z)) norm_w  W_out^T
+// (with pre_norm_w the projection reads RMSNorm(u) pre_norm_w instead of u: the pre-norm of a language-model layer)
 // The forward pass keeps, per segment, only what a sequence checkpoint holds in App. C, Tab. 7: the SSM
 // state and the three-token convolution state entering the segment.  The backward pass walks the segments
 // right to left, redoes a segment's forward from its two states (Recompute_Forward of Alg. 2) into the
@@ -163,12 +164,24 @@ ssd_norm_shape_t norm_shape(const BlockDims& d, int64_t rows, float eps) {
     return n;
 }
 
+// the normalisation in front of the input projection: all of d_model is one group, dense rows
+ssd_norm_shape_t pre_norm_shape(const BlockDims& d, int64_t rows, float eps) {
+    ssd_norm_shape_t n;
+    memset(&n, 0, sizeof(n));
+    n.dtype = SSD_BF16;
+    n.dim = d.dm;
+    n.ngroups = 1;
+    n.eps = eps;
+    n.rows = rows;
+    return n;
+}
+
 size_t al(size_t n) { return (n + 255) & ~(size_t)255; }
 
 // Workspace: one segment's activations (and, backward, their gradients), the scratch of the inner calls.
 struct BlockWs {
-    size_t zx, xbc, x, B, C, dt, y, yn;                     // forward activations of the segment
-    size_t dyn, dy, dzx, dxbc, dx, dB, dC, ddt;             // backward
+    size_t un, zx, xbc, x, B, C, dt, y, yn;                 // forward activations of the segment
+    size_t dun, dyn, dy, dzx, dxbc, dx, dB, dC, ddt;        // backward
     size_t dssm[2], dconv[2], dtpart, inner, total;
     size_t cssm[2], cconv[2];                               // states handed from segment to segment when no checkpoints are kept
     size_t inner_bytes;
@@ -184,6 +197,7 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         return o;
     };
     const size_t s = (size_t)d.s;
+    w.un = take(s * d.dm * 2);
     w.zx = take(s * d.d_in_proj * 2);
     w.xbc = take(s * d.conv_dim * 2);
     w.x = take(s * d.d_inner * 2);
@@ -202,6 +216,7 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         inner = b > inner ? b : inner;
     }
     if (bwd) {
+        w.dun = take(s * d.dm * 2);
         w.dyn = take(s * d.d_inner * 2);
         w.dy = take(s * d.d_inner * 2);
         w.dzx = take(s * d.d_in_proj * 2);
@@ -215,9 +230,11 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         w.dtpart = take(((s + DT_ROWS - 1) / DT_ROWS) * d.H * 4);
         const ssd_conv_shape_t cs = conv_shape(d, d.s);
         const ssd_norm_shape_t ns = norm_shape(d, d.s, 0.f);
-        const size_t b = ssd_conv1d_workspace_bytes(&cs), c = ssd_gated_norm_workspace_bytes(&ns);
+        const ssd_norm_shape_t ps = pre_norm_shape(d, d.s, 0.f);
+        const size_t b = ssd_conv1d_workspace_bytes(&cs), c = ssd_gated_norm_workspace_bytes(&ns), e = ssd_gated_norm_workspace_bytes(&ps);
         inner = b > inner ? b : inner;
         inner = c > inner ? c : inner;
+        inner = e > inner ? e : inner;
     }
     for (int i = 0; i < 2; ++i) w.cssm[i] = take(d.HPN * 4);
     for (int i = 0; i < 2; ++i) w.cconv[i] = take((size_t)3 * d.conv_dim * 2);
@@ -240,8 +257,21 @@ BlockWs layout(const BlockDims& d, bool bwd) {
 // The forward steps of a segment.  zx [rows, d_in_proj] and y [rows, d_inner] are given by the caller (the
 // block's own workspace, or the per-layer slots a grid cell keeps: they are the activations C_grid of App. C,
 // Tab. 7 counts); everything else lives in the workspace `ws` laid out by `w`.
-int seg_in_proj(const BlockDims& d, const magc_block_params_t* p, const void* u_seg, int64_t rows, char* zx, hipStream_t st) {
-    return ssd_linear_fwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, zx, 0, st);
+// the input of the projection: u itself, or (pre_norm_w given) its RMS normalisation, written to the workspace
+int seg_pre_norm(const BlockDims& d, float eps, const magc_block_params_t* p, char* ws, const BlockWs& w, const void* u_seg,
+                 int64_t rows, const void** proj_in, hipStream_t st) {
+    *proj_in = u_seg;
+    if (!p->pre_norm_w) return SSD_OK;
+    const ssd_norm_shape_t ps = pre_norm_shape(d, rows, eps);
+    *proj_in = ws + w.un;
+    return ssd_gated_norm_fwd(&ps, u_seg, nullptr, p->pre_norm_w, ws + w.un, st);
+}
+
+int seg_in_proj(const BlockDims& d, float eps, const magc_block_params_t* p, char* ws, const BlockWs& w, const void* u_seg, int64_t rows,
+                char* zx, hipStream_t st) {
+    const void* in;
+    BLK_TRY(seg_pre_norm(d, eps, p, ws, w, u_seg, rows, &in, st));
+    return ssd_linear_fwd(rows, d.dm, d.d_in_proj, in, 0, p->W_in, zx, 0, st);
 }
 
 // convolution + SiLU of the xBC columns, split into dense x / B / C, softplus of the dt columns
@@ -280,7 +310,7 @@ int seg_norm(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_
 int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
                     char* zx, char* y, const void* u_seg, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out,
                     void* conv_out, hipStream_t st) {
-    BLK_TRY(seg_in_proj(d, p, u_seg, rows, zx, st));
+    BLK_TRY(seg_in_proj(d, sh->eps, p, ws, w, u_seg, rows, zx, st));
     BLK_TRY(seg_mid(d, p, ws, w, zx, rows, conv_in, conv_out, st));
     BLK_TRY(seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, y, st));
     BLK_TRY(seg_norm(d, sh, p, ws, w, zx, y, rows, st));
@@ -320,8 +350,15 @@ int backward_segment(const BlockDims& d, const magc_block_shape_t* sh, const mag
     const ssd_conv_shape_t cs = conv_shape(d, rows);
     BLK_TRY(ssd_conv1d_bwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.dxbc, dconv_out,
                            dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
-    // input projection
-    BLK_TRY(ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, du_seg, 0, g->dW_in, acc, st));
+    // input projection, and the normalisation in front of it (its output is cheap to redo and other layers of
+    // a grid cell may have used the buffer since this layer's forward steps)
+    if (!p->pre_norm_w) return ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, du_seg, 0, g->dW_in, acc, st);
+    const void* un;
+    BLK_TRY(seg_pre_norm(d, sh->eps, p, ws, w, u_seg, rows, &un, st));
+    BLK_TRY(ssd_linear_bwd(rows, d.dm, d.d_in_proj, un, 0, p->W_in, dzx, 0, ws + w.dun, 0, g->dW_in, acc, st));
+    const ssd_norm_shape_t ps = pre_norm_shape(d, rows, sh->eps);
+    BLK_TRY(ssd_gated_norm_bwd(&ps, u_seg, nullptr, p->pre_norm_w, ws + w.dun, du_seg, nullptr, g->dpre_norm_w, ws + w.inner, w.inner_bytes,
+                               acc, st));
     return SSD_OK;
 }
 
@@ -382,6 +419,7 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
     if (flags & ~(uint32_t)SSD_FLAG_ACCUM_PARAM) return SSD_ERR_ARG;
     if (!p || !p->W_in || !p->conv_w || !p->conv_b || !p->dt_bias || !p->A || !p->D || !p->norm_w || !p->W_out) return SSD_ERR_NULL;
     if (!g || !g->dW_in || !g->dconv_w || !g->dconv_b || !g->ddt_bias || !g->dA || !g->dD || !g->dnorm_w || !g->dW_out) return SSD_ERR_NULL;
+    if (p->pre_norm_w && !g->dpre_norm_w) return SSD_ERR_NULL;
     hipStream_t st = (hipStream_t)hip_stream;
     if (!(flags & SSD_FLAG_ACCUM_PARAM)) {  // every segment adds to the parameter gradients
         BLK_HIP(launch_fill_zero(g->dW_in, (size_t)d.d_in_proj * d.dm, st));
@@ -392,6 +430,7 @@ extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_par
         BLK_HIP(launch_fill_zero(g->dD, (size_t)d.H, st));
         BLK_HIP(launch_fill_zero(g->dnorm_w, (size_t)d.d_inner, st));
         BLK_HIP(launch_fill_zero(g->dW_out, (size_t)d.dm * d.d_inner, st));
+        if (p->pre_norm_w) BLK_HIP(launch_fill_zero(g->dpre_norm_w, (size_t)d.dm, st));
     }
     if (d.L == 0) {  // the state adjoints pass through
         if (dinit_ssm) BLK_HIP(dfinal_ssm ? launch_copy_f32(dinit_ssm, dfinal_ssm, d.HPN, st) : launch_fill_zero(dinit_ssm, d.HPN, st));
@@ -600,7 +639,7 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
     if (!params_ok(params, d.NL) || !grads) return SSD_ERR_NULL;
     for (int j = 0; j < d.NL; ++j)
         if (!grads[j].dW_in || !grads[j].dconv_w || !grads[j].dconv_b || !grads[j].ddt_bias || !grads[j].dA || !grads[j].dD ||
-            !grads[j].dnorm_w || !grads[j].dW_out)
+            !grads[j].dnorm_w || !grads[j].dW_out || (params[j].pre_norm_w && !grads[j].dpre_norm_w))
             return SSD_ERR_NULL;
     hipStream_t st = (hipStream_t)hip_stream;
     const size_t row = (size_t)d.b.dm * 2;
@@ -614,6 +653,7 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
             BLK_HIP(launch_fill_zero(grads[j].dD, (size_t)d.b.H, st));
             BLK_HIP(launch_fill_zero(grads[j].dnorm_w, (size_t)d.b.d_inner, st));
             BLK_HIP(launch_fill_zero(grads[j].dW_out, (size_t)d.b.dm * d.b.d_inner, st));
+            if (params[j].pre_norm_w) BLK_HIP(launch_fill_zero(grads[j].dpre_norm_w, (size_t)d.b.dm, st));
         }
     }
     if (d.b.L == 0) return SSD_OK;
@@ -643,7 +683,7 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
                 const void* conv_in = k ? (const char*)conv_ckpt + ((size_t)j * d.b.nseg + k) * d.conv_state : nullptr;
                 char* zx = ws + w.zx + (size_t)(j - j0) * w.zx_bytes;
                 char* y = ws + w.y + (size_t)(j - j0) * w.y_bytes;
-                BLK_TRY(seg_in_proj(dc, &params[j], xin, rows, zx, st));
+                BLK_TRY(seg_in_proj(dc, c.eps, &params[j], bws, bw, xin, rows, zx, st));
                 BLK_TRY(seg_mid(dc, &params[j], bws, bw, zx, rows, conv_in, nullptr, st));
                 BLK_TRY(seg_scan(dc, &params[j], bws, bw, rows, ssm_in, nullptr, y, st));
                 if (j < j1) {  // the next layer's input

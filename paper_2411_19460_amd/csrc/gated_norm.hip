@@ -83,7 +83,7 @@ __device__ __forceinline__ float wave_sum(float v) {
 // (4: the whole workgroup, for long segments; 1: one wave each, for short ones); the workgroup's 4 / WPS
 // slots walk the 64 rows of each of its tiles.  A thread owns the same channels in every row (vector
 // i * 64 * WPS + its index within the slot), so the weight and the weight-gradient sums stay in its registers.
-template <typename T, int VPL, int WPS, bool BWD>
+template <typename T, int VPL, int WPS, bool BWD, bool GATED>
 __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
     constexpr int V = Pk<T>::V;
     constexpr int NSLOT = 4 / WPS;
@@ -116,7 +116,7 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
             const int v = i * 64 * WPS + lid;
             if (v < nvec) {
                 yv[i] = Pk<T>::ld(np.y, r * np.y_rs + c_base + v * V);
-                zv[i] = Pk<T>::ld(np.z, r * np.z_rs + c_base + v * V);
+                if (GATED) zv[i] = Pk<T>::ld(np.z, r * np.z_rs + c_base + v * V);
                 if (BWD) dv[i] = Pk<T>::ld(np.dout, r * (int64_t)np.C + c_base + v * V);
             }
         }
@@ -134,7 +134,7 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
 #pragma unroll
             for (int i = 0; i < VPL; ++i) {
                 yv[i] = ny[i];
-                zv[i] = nz[i];
+                if (GATED) zv[i] = nz[i];
             }
             if (q + NSLOT < nrows_wg && row_of(q + NSLOT) < np.T) load_row(row_of(q + NSLOT), ny, nz, nd);
         } else {
@@ -149,9 +149,9 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
             if (i * 64 * WPS + lid < nvec) {
 #pragma unroll
                 for (int e = 0; e < V; ++e) {
-                    const float zz = Pk<T>::get(zv[i], e);
-                    const float sg = sigmoidf(zz);
-                    const float g = Pk<T>::get(yv[i], e) * zz * sg;
+                    const float zz = GATED ? Pk<T>::get(zv[i], e) : 0.f;
+                    const float sg = GATED ? sigmoidf(zz) : 1.f;
+                    const float g = GATED ? Pk<T>::get(yv[i], e) * zz * sg : Pk<T>::get(yv[i], e);  // no gate: plain RMS norm
                     gv[i][e] = g;
                     if (BWD) sv[i][e] = sg;
                     s1 = fmaf(g, g, s1);
@@ -184,11 +184,15 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
                     if (!BWD) {
                         Pk<T>::set(o1, e, ghat * wr[i][e]);
                     } else {
-                        const float zz = Pk<T>::get(zv[i], e), yy = Pk<T>::get(yv[i], e), sg = sv[i][e];
                         const float d = Pk<T>::get(dv[i], e);
                         const float dg = rstd * (d * wr[i][e] - ghat * m);
-                        Pk<T>::set(o1, e, dg * zz * sg);                              // dy
-                        Pk<T>::set(o2, e, dg * yy * sg * (1.f + zz * (1.f - sg)));    // dz
+                        if (GATED) {
+                            const float zz = Pk<T>::get(zv[i], e), yy = Pk<T>::get(yv[i], e), sg = sv[i][e];
+                            Pk<T>::set(o1, e, dg * zz * sg);                              // dy
+                            Pk<T>::set(o2, e, dg * yy * sg * (1.f + zz * (1.f - sg)));    // dz
+                        } else {
+                            Pk<T>::set(o1, e, dg);
+                        }
                         acc[i][e] = fmaf(d, ghat, acc[i][e]);
                     }
                 }
@@ -196,7 +200,7 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
                     Pk<T>::st(np.out, r * (int64_t)np.C + c_base + v * V, o1);
                 } else {
                     Pk<T>::st(np.dy, r * np.y_rs + c_base + v * V, o1);
-                    Pk<T>::st(np.dz, r * np.z_rs + c_base + v * V, o2);
+                    if (GATED) Pk<T>::st(np.dz, r * np.z_rs + c_base + v * V, o2);
                 }
             }
         }
@@ -217,7 +221,7 @@ __global__ __launch_bounds__(256) void k_gated_norm(NormParams np) {
 // Any group size, any alignment: one wave per (row, group), three passes over the segment through the
 // caches, element by element.  Same arithmetic in the same order per element; the sums over the segment
 // are taken in a different order than in the kernel above.
-template <typename T, bool BWD>
+template <typename T, bool BWD, bool GATED>
 __global__ __launch_bounds__(256) void k_gated_norm_any(NormParams np) {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int grp = blockIdx.y;
@@ -232,8 +236,8 @@ __global__ __launch_bounds__(256) void k_gated_norm_any(NormParams np) {
         if (r >= np.T) break;
         float s1 = 0.f, s2 = 0.f;
         for (int c = lane; c < np.gs; c += 64) {
-            const float zz = Pk<T>::ld1(np.z, r * np.z_rs + c_base + c);
-            const float g = Pk<T>::ld1(np.y, r * np.y_rs + c_base + c) * zz * sigmoidf(zz);
+            const float zz = GATED ? Pk<T>::ld1(np.z, r * np.z_rs + c_base + c) : 0.f;
+            const float g = Pk<T>::ld1(np.y, r * np.y_rs + c_base + c) * (GATED ? zz * sigmoidf(zz) : 1.f);
             s1 = fmaf(g, g, s1);
             if (BWD) s2 = fmaf(Pk<T>::ld1(np.dout, r * (int64_t)np.C + c_base + c) * np.w[c_base + c], g, s2);
         }
@@ -242,17 +246,17 @@ __global__ __launch_bounds__(256) void k_gated_norm_any(NormParams np) {
         float m = 0.f;
         if (BWD) m = wave_sum(s2) * inv_n * rstd;
         for (int c = lane; c < np.gs; c += 64) {
-            const float zz = Pk<T>::ld1(np.z, r * np.z_rs + c_base + c), yy = Pk<T>::ld1(np.y, r * np.y_rs + c_base + c);
-            const float sg = sigmoidf(zz);
-            const float ghat = yy * zz * sg * rstd;
+            const float zz = GATED ? Pk<T>::ld1(np.z, r * np.z_rs + c_base + c) : 0.f, yy = Pk<T>::ld1(np.y, r * np.y_rs + c_base + c);
+            const float sg = GATED ? sigmoidf(zz) : 1.f;
+            const float ghat = (GATED ? yy * zz * sg : yy) * rstd;
             const float wc = np.w[c_base + c];
             if (!BWD) {
                 Pk<T>::st1(np.out, r * (int64_t)np.C + c_base + c, ghat * wc);
             } else {
                 const float d = Pk<T>::ld1(np.dout, r * (int64_t)np.C + c_base + c);
                 const float dg = rstd * (d * wc - ghat * m);
-                Pk<T>::st1(np.dy, r * np.y_rs + c_base + c, dg * zz * sg);
-                Pk<T>::st1(np.dz, r * np.z_rs + c_base + c, dg * yy * sg * (1.f + zz * (1.f - sg)));
+                Pk<T>::st1(np.dy, r * np.y_rs + c_base + c, GATED ? dg * zz * sg : dg);
+                if (GATED) Pk<T>::st1(np.dz, r * np.z_rs + c_base + c, dg * yy * sg * (1.f + zz * (1.f - sg)));
                 part[c] = first ? d * ghat : fmaf(d, ghat, part[c]);
             }
         }
@@ -361,7 +365,7 @@ FastGrid fast_grid(const NormDims& d, bool bwd) {
     return g;
 }
 
-template <typename T, bool BWD>
+template <typename T, bool BWD, bool GATED>
 hipError_t launch_fast(const NormDims& d, const NormParams& np0, FastCfg f, hipStream_t st) {
     const FastGrid fg = fast_grid(d, BWD);
     NormParams np = np0;
@@ -370,7 +374,7 @@ hipError_t launch_fast(const NormDims& d, const NormParams& np0, FastCfg f, hipS
     const dim3 grid(fg.nwg, np.G), block(256);
 #define NORM_CASE(N, W)                                                                    \
     if (f.vpl == N && f.wps == W) {                                                        \
-        hipLaunchKernelGGL((k_gated_norm<T, N, W, BWD>), grid, block, 0, st, np);          \
+        hipLaunchKernelGGL((k_gated_norm<T, N, W, BWD, GATED>), grid, block, 0, st, np);   \
         return hipGetLastError();                                                          \
     }
     NORM_CASE(1, 1)
@@ -385,15 +389,21 @@ hipError_t launch_fast(const NormDims& d, const NormParams& np0, FastCfg f, hipS
     return hipErrorInvalidValue;
 }
 
-template <bool BWD>
-hipError_t launch(const NormDims& d, const NormParams& np, FastCfg f, hipStream_t st) {
-    if (f.vpl) return d.bf16 ? launch_fast<bf16_t, BWD>(d, np, f, st) : launch_fast<float, BWD>(d, np, f, st);
+template <bool BWD, bool GATED>
+hipError_t launch_g(const NormDims& d, const NormParams& np, FastCfg f, hipStream_t st) {
+    if (f.vpl) return d.bf16 ? launch_fast<bf16_t, BWD, GATED>(d, np, f, st) : launch_fast<float, BWD, GATED>(d, np, f, st);
     const dim3 grid(np.ntiles, np.G), block(256);
     if (d.bf16)
-        hipLaunchKernelGGL((k_gated_norm_any<bf16_t, BWD>), grid, block, 0, st, np);
+        hipLaunchKernelGGL((k_gated_norm_any<bf16_t, BWD, GATED>), grid, block, 0, st, np);
     else
-        hipLaunchKernelGGL((k_gated_norm_any<float, BWD>), grid, block, 0, st, np);
+        hipLaunchKernelGGL((k_gated_norm_any<float, BWD, GATED>), grid, block, 0, st, np);
     return hipGetLastError();
+}
+
+// np.z == NULL: no gate (plain RMS normalisation of y); the kernels then never touch z or dz
+template <bool BWD>
+hipError_t launch(const NormDims& d, const NormParams& np, FastCfg f, hipStream_t st) {
+    return np.z ? launch_g<BWD, true>(d, np, f, st) : launch_g<BWD, false>(d, np, f, st);
 }
 
 NormParams params(const NormDims& d, const ssd_norm_shape_t* sh) {
@@ -434,7 +444,7 @@ extern "C" int ssd_gated_norm_fwd(const ssd_norm_shape_t* sh, const void* y, con
     const int rc = check(sh, &d);
     if (rc != SSD_OK) return rc;
     if (d.T == 0) return SSD_OK;
-    if (!y || !z || !w || !out) return SSD_ERR_NULL;
+    if (!y || !w || !out) return SSD_ERR_NULL;  // z == NULL: no gate
     NormParams np = params(d, sh);
     np.y = y;
     np.z = z;
@@ -457,7 +467,7 @@ extern "C" int ssd_gated_norm_bwd(const ssd_norm_shape_t* sh, const void* y, con
         if (accumulate) return SSD_OK;
         return launch_fill_zero(dw, (size_t)d.C, st) == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
     }
-    if (!y || !z || !w || !dout || !dy || !dz) return SSD_ERR_NULL;
+    if (!y || !w || !dout || !dy || (z && !dz)) return SSD_ERR_NULL;  // z == NULL: no gate, dz is not written
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ssd_gated_norm_workspace_bytes(sh)) return SSD_ERR_WORKSPACE;
     NormParams np = params(d, sh);
     np.y = y;
@@ -465,9 +475,9 @@ extern "C" int ssd_gated_norm_bwd(const ssd_norm_shape_t* sh, const void* y, con
     np.w = w;
     np.dout = dout;
     np.dy = dy;
-    np.dz = dz;
+    np.dz = z ? dz : nullptr;
     np.part = (float*)workspace;
-    const FastCfg f = pick_fast(d, {y, z, dout, dy, dz});
+    const FastCfg f = pick_fast(d, {y, z, dout, dy, z ? dz : nullptr});
     const int64_t nparts = f.vpl ? (int64_t)fast_grid(d, true).nwg * (4 / f.wps) : (int64_t)d.ntiles * 4;
     if ((size_t)nparts * d.C * 4 > workspace_bytes) return SSD_ERR_WORKSPACE;  // cannot happen with the documented size
     if (launch<true>(d, np, f, st) != hipSuccess) return SSD_ERR_LAUNCH;

@@ -91,3 +91,32 @@ def test_stack_of_blocks_gradients_match_central_differences():
                 lay[j][key] = a
                 return L(lay=lay)
             close(b["grads"][j][name], numgrad(with_param, layers[j][key]), 2e-7)
+
+
+def test_with_the_pre_norm_gradients_still_match_central_differences():
+    d = draw(7)
+    r = np.random.default_rng(70)
+    d["p"]["pre_norm_w"] = 1.0 + 0.3 * r.standard_normal(DM)
+    g = block_ref.block_bwd(d["u"], d["p"], H, P, G, N, d["dout"], 1e-3, d["conv_state"], d["ssm_state"],
+                            d["dconv_state"], d["dssm_state"])
+    close(g["du"], numgrad(lambda a: loss(d, u=a), d["u"]), 2e-7)
+    for key, name in (("pre_norm_w", "dpre_norm_w"), ("W_in", "dW_in"), ("conv_w", "dconv_w"), ("norm_w", "dnorm_w")):
+        close(g[name], numgrad(lambda a: loss(d, p={**d["p"], key: a}), d["p"][key]), 2e-7)
+    # the normalised input does not see the scale of u (eps = 0): neither does anything behind it
+    f1 = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 0.0)
+    f2 = block_ref.block_fwd(13.0 * d["u"], d["p"], H, P, G, N, 0.0)
+    close(f2["out"], f1["out"], 1e-12)
+    # a two-layer pre-norm residual stack
+    d1 = draw(8)
+    d1["p"]["pre_norm_w"] = 1.0 + 0.3 * r.standard_normal(DM)
+    layers, x0, dout = [d["p"], d1["p"]], d["u"], d["dout"]
+    f = block_ref.stack_fwd(x0, layers, H, P, G, N, 1e-3)
+    b = block_ref.stack_bwd(f["xs"], layers, H, P, G, N, dout, 1e-3)
+    L = lambda x=None, lay=None: float(np.sum(block_ref.stack_fwd(x0 if x is None else x, layers if lay is None else lay, H, P, G, N, 1e-3)["out"] * dout))
+    close(b["dx0"], numgrad(lambda a: L(x=a), x0), 2e-7)
+    for j in range(2):
+        def with_param(a, j=j):
+            lay = [dict(p) for p in layers]
+            lay[j]["pre_norm_w"] = a
+            return L(lay=lay)
+        close(b["grads"][j]["dpre_norm_w"], numgrad(with_param, layers[j]["pre_norm_w"]), 2e-7)

@@ -15,7 +15,7 @@ BF = lambda a: np.asarray(synth.round_bf16(a), dtype=np.float64)
 F32 = lambda a: np.asarray(a, dtype=np.float32).astype(np.float64)
 
 
-def draw(seed, L, dm, H, P, G, N):
+def draw(seed, L, dm, H, P, G, N, pre=False):
     r = np.random.default_rng(4000 + seed)
     d_inner, conv_dim, d_in = block_ref.dims(None, H, P, G, N)
     dt0 = np.exp(r.uniform(np.log(1e-3), np.log(0.1), H))           # the step sizes the bias alone would give
@@ -23,7 +23,11 @@ def draw(seed, L, dm, H, P, G, N):
              conv_b=F32(r.standard_normal(conv_dim) * 0.2), dt_bias=F32(dt0 + np.log(-np.expm1(-dt0))),
              A=F32(-np.exp(r.uniform(0.0, np.log(16.0), H))), D=F32(r.standard_normal(H)),
              norm_w=F32(1.0 + 0.3 * r.standard_normal(d_inner)), W_out=BF(r.standard_normal((dm, d_inner)) / np.sqrt(d_inner)))
-    return dict(u=BF(r.standard_normal((L, dm))), dout=BF(r.standard_normal((L, dm))), p=p)
+    d = dict(u=BF(r.standard_normal((L, dm))), dout=BF(r.standard_normal((L, dm))), p=p)
+    if pre:   # drawn last: the other values do not depend on it
+        p["pre_norm_w"] = F32(1.0 + 0.3 * r.standard_normal(dm))
+        d["u"] = BF(d["u"] * np.exp(r.uniform(-1.0, 1.0, (L, 1))))     # rows of different size: the normalisation has work to do
+    return d
 
 
 def to_dev(p):
@@ -80,6 +84,37 @@ def test_block_forward_backward(case):
     torch.cuda.synchronize()
     for k in GRADS:
         check(k + " accumulated", host(g2[k]), 2 * host(g[k]), 1e-5)
+
+
+@pytest.mark.parametrize("case", [
+    (700, 128, 8, 64, 2, 128, 256, 256),      # ragged last segment
+    (1536, 2560, 80, 64, 1, 128, 256, 1024),  # the 2.7B widths
+])
+def test_block_with_the_pre_norm(case):
+    L, dm, H, P, G, N, Q, seg = case
+    d = draw(6, L, dm, H, P, G, N, pre=True)
+    u, dout, par = dev_bf16(d["u"]), dev_bf16(d["dout"]), to_dev(d["p"])
+    f = pk.magc_block_fwd(u, par, H, P, G, N, Q, seg)
+    g = pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg)
+    torch.cuda.synchronize()
+    fo = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 1e-5, store=synth.round_bf16)
+    go = block_ref.block_bwd(d["u"], d["p"], H, P, G, N, d["dout"], 1e-5, store=synth.round_bf16)
+    tol = TOL["bf16"]
+    rep = {}
+    check("out", host(f["out"]), fo["out"], tol, rep)
+    check("du", host(g["du"]), go["du"], tol, rep)
+    for k in GRADS + ("dpre_norm_w",):
+        check(k, host(g[k]), go[k], tol, rep)
+    print("pre-norm block errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+    # the parameter is what switches it on: without it the same call computes the plain block
+    plain = {k: v for k, v in par.items() if k != "pre_norm_w"}
+    f0 = pk.magc_block_fwd(u, plain, H, P, G, N, Q, seg)
+    check("plain out", host(f0["out"]), block_ref.block_fwd(d["u"], {k: v for k, v in d["p"].items() if k != "pre_norm_w"},
+                                                            H, P, G, N, 1e-5, store=synth.round_bf16)["out"], tol)
+    # a missing gradient slot for it is refused before anything runs
+    bad = {k: torch.empty_like(v) for k, v in g.items() if k in GRADS}
+    with pytest.raises(pk.SSDError):
+        pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg, grads=bad)
 
 
 def test_block_prefill_then_generation_without_checkpoints():
@@ -139,11 +174,14 @@ def test_block_state_adjoints_chain_two_calls():
     (3, 2, 640, 256),     # two layer groups (2 + 1), three segments, the last one short
     (4, 4, 512, 256),     # one layer group: only the stack input is kept on the layer axis
     (3, 1, 384, 384),     # every layer input kept, one segment
+    (3, 2, 640, 256, True),   # the first grid again, every layer with its pre-norm: the language model's residual layer
 ])
 def test_stack_of_blocks_on_the_two_axis_grid(case):
-    NL, l, L, seg = case
+    NL, l, L, seg = case[:4]
+    pre = len(case) > 4
+    GRADS = globals()["GRADS"] + (("dpre_norm_w",) if pre else ())
     dm, H, P, G, N, Q = 128, 8, 64, 1, 128, 128
-    ds = [draw(10 + j, L, dm, H, P, G, N) for j in range(NL)]
+    ds = [draw(10 + j, L, dm, H, P, G, N, pre) for j in range(NL)]
     layers_h = [x["p"] for x in ds]
     x0h, douth = ds[0]["u"], ds[0]["dout"]
     x0, dout, layers = dev_bf16(x0h), dev_bf16(douth), [to_dev(p) for p in layers_h]

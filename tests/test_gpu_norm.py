@@ -72,6 +72,24 @@ def test_gated_norm_forward_backward(case):
     check("dw accumulated", host(g2["dw"]), 2 * ref["dw"], tol)
 
 
+@pytest.mark.parametrize("case", [("bf16", 1000, 2560, 1), ("bf16", 37, 16392, 1), ("f32", 130, 96, 3)])
+def test_norm_without_a_gate(case):
+    """z == NULL: the plain RMS normalisation (a block's pre-norm at the 2.7B model width, the element-wise
+    kernel, fp32 with groups)."""
+    dtype, T, C, G = case
+    d = draw(5, dtype, T, C)
+    y, dout = dev(d["y"], dtype), dev(d["dout"], dtype)
+    w = dev(d["w"])
+    tol = TOL[dtype]
+    check("out", host(pk.ssd_gated_norm_fwd(y, None, w, 1e-5, G)), norm_ref.gated_rmsnorm_fwd(d["y"], None, d["w"], 1e-5, G), tol)
+    g = pk.ssd_gated_norm_bwd(y, None, w, dout, 1e-5, G)
+    torch.cuda.synchronize()
+    ref = norm_ref.gated_rmsnorm_bwd(d["y"], None, d["w"], d["dout"], 1e-5, G)
+    assert g["dz"] is None
+    for k in ("dy", "dw"):
+        check(k, host(g[k]), ref[k], tol)
+
+
 def test_gated_norm_empty_and_rejected_arguments():
     y = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.ones(64, device="cuda")

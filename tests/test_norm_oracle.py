@@ -58,3 +58,18 @@ def test_scale_invariance_unit_rms_and_orthogonality():
     # a closed form: one channel per group, eps = 0: out = sign(y z) w whatever the magnitudes
     t = norm_ref.gated_rmsnorm_fwd(d["y"], d["z"], d["w"], 0.0, 12)
     close(t, np.sign(d["y"] * d["z"]) * d["w"])
+
+
+def test_without_a_gate_it_is_the_library_rms_norm():
+    d = draw(3)
+    y, w = (torch.from_numpy(d[k]).requires_grad_() for k in ("y", "w"))
+    out = torch.nn.functional.rms_norm(y, (12,), weight=w, eps=1e-5)
+    (out * torch.from_numpy(d["dout"])).sum().backward()
+    close(norm_ref.gated_rmsnorm_fwd(d["y"], None, d["w"], 1e-5, 1), out.detach().numpy())
+    got = norm_ref.gated_rmsnorm_bwd(d["y"], None, d["w"], d["dout"], 1e-5, 1)
+    close(got["dy"], y.grad.numpy())
+    close(got["dw"], w.grad.numpy())
+    assert got["dz"] is None
+    # and the gated form with a gate whose silu is one (z * sigmoid(z) = 1 at z = 1.2784645...) gives the same
+    z1 = np.full_like(d["y"], 1.2784645427610738)
+    close(norm_ref.gated_rmsnorm_fwd(d["y"], z1, d["w"], 1e-5, 1), out.detach().numpy(), 1e-9)
