@@ -315,6 +315,8 @@ def block_bench(args, cfg, pk, torch, dev):
     par = {"W_in": (rn(d_in_proj, dm) / dm ** 0.5).to(torch.bfloat16), "conv_w": rn(conv_dim, 4) * 0.5, "conv_b": rn(conv_dim) * 0.2,
            "dt_bias": dt0 + torch.log(-torch.expm1(-dt0)), "A": -torch.exp(torch.empty(H, device=dev).uniform_(0.0, math.log(16.0), generator=g)),
            "D": rn(H), "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5).to(torch.bfloat16)}
+    if args.pre_norm:   # the language model's layer: RMS normalisation in front of the input projection
+        par["pre_norm_w"] = 1.0 + 0.3 * rn(dm)
     u, dout = rn(L, dm).to(torch.bfloat16), rn(L, dm).to(torch.bfloat16)
     if args.layers > 1:
         # a stack of such blocks with residual adds on the two-axis grid: layer inputs kept every
@@ -350,7 +352,7 @@ def block_bench(args, cfg, pk, torch, dev):
             "metric": "Mamba-2 block stack fwd+bwd tokens/sec/layer", "value": NL * L / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
             "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
             "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-            "config": {"workload": cfg.name + "_block_stack", "seqlen": L, "layers": NL, "layer_interval": li, "d_model": dm,
+            "config": {"workload": cfg.name + "_block_stack", "pre_norm": bool(args.pre_norm), "seqlen": L, "layers": NL, "layer_interval": li, "d_model": dm,
                        "segment": cfg.segment},
             "roofline": {"bound": "mfma", "achieved": None, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": None, "traffic": None,
                          "forward_ms": ms_f, "backward_ms": ms_b},
@@ -430,7 +432,7 @@ def block_bench(args, cfg, pk, torch, dev):
         "metric": "Mamba-2 block fwd+bwd tokens/sec/layer", "value": L / ((ms_f + ms_b) * 1e-3), "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_f + ms_b, "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": cfg.name + "_block", "seqlen": L, "d_model": dm, "nheads": H, "headdim": P, "ngroups": G, "dstate": N,
+        "config": {"workload": cfg.name + "_block", "pre_norm": bool(args.pre_norm), "seqlen": L, "d_model": dm, "nheads": H, "headdim": P, "ngroups": G, "dstate": N,
                    "chunk": cfg.chunk, "segment": cfg.segment},
         "roofline": {"bound": "mfma", "achieved": ach, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": ach / MFMA_BF16_PEAK_TFLOPS,
                      "traffic": None, "flop_per_token": flop_tok, "forward_ms": ms_f, "backward_ms": ms_b},
@@ -463,6 +465,7 @@ def main():
                     help="time the block's input and output projections (forward, input and weight gradients) instead")
     ap.add_argument("--block", action="store_true",
                     help="time one whole Mamba-2 block (projections, convolution, scan, gated norm) under sequence checkpoints instead")
+    ap.add_argument("--pre-norm", action="store_true", help="with --block: each block starts with an RMS normalisation of its input")
     ap.add_argument("--layers", type=int, default=1, help="with --block: a residual stack of this many blocks on the two-axis grid")
     ap.add_argument("--layer-interval", type=int, default=4, help="with --block --layers: layer inputs kept every this many layers")
     ap.add_argument("--calibrate-mfma", action="store_true",

@@ -31,6 +31,7 @@ def main():
     ap.add_argument("--max-log2", type=int, default=20)
     ap.add_argument("--step-log2", type=int, default=2)
     ap.add_argument("--budget-gb", type=float, default=200.0)
+    ap.add_argument("--pre-norm", action="store_true", help="with --blocks: every block starts with an RMS normalisation of its input")
     ap.add_argument("--blocks", action="store_true",
                     help="whole Mamba-2 blocks (projections, convolution, scan, gated norm) instead of bare SSD layers")
     args = ap.parse_args()
@@ -141,7 +142,8 @@ def blocks_sweep(args):
         return {"W_in": (rn(d_in_proj, dm) / dm ** 0.5).to(torch.bfloat16), "conv_w": rn(conv_dim, 4) * 0.5, "conv_b": rn(conv_dim) * 0.2,
                 "dt_bias": dt0 + torch.log(-torch.expm1(-dt0)),
                 "A": -torch.exp(torch.empty(H, device=dev).uniform_(0.0, math.log(16.0), generator=g)), "D": rn(H),
-                "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5 / nl ** 0.5).to(torch.bfloat16)}
+                "norm_w": 1.0 + 0.3 * rn(d_inner), "W_out": (rn(dm, d_inner) / d_inner ** 0.5 / nl ** 0.5).to(torch.bfloat16),
+                **({"pre_norm_w": 1.0 + 0.3 * rn(dm)} if args.pre_norm else {})}
 
     layers = [layer() for _ in range(nl)]
     grads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in layers[0].items()} for _ in range(nl)]
