@@ -94,15 +94,21 @@ def block_bwd(u, p, H, P, G, N, dout, eps=1e-5, conv_state=None, ssm_state=None,
             "dconv_state_in": gc["dstate_in"][0], "dssm_state_in": gs["dinit_state"][0]}
 
 
-def stack_fwd(x0, layers, H, P, G, N, eps=1e-5, store=None):
-    """Residual stack of blocks: x_{j+1} = x_j + Block_j(x_j), zero initial states; `layers` is a list of
-    parameter dicts.  Every x_{j+1} is rounded once by `store` where it is stored.  Returns dict(out, xs)."""
+def stack_fwd(x0, layers, H, P, G, N, eps=1e-5, store=None, conv_states=None, ssm_states=None):
+    """Residual stack of blocks: x_{j+1} = x_j + Block_j(x_j); `layers` is a list of parameter dicts, the
+    states entering the sequence are given per layer (None = zeros).  Every x_{j+1} is rounded once by
+    `store` where it is stored.  Returns dict(out, xs, conv_states, ssm_states): the last two are the states
+    of every layer behind the last token (what a later call continues from)."""
     x = np.asarray(x0, dtype=np.float64)
-    xs = []
-    for p in layers:
+    xs, cs, ss = [], [], []
+    for j, p in enumerate(layers):
         xs.append(x)
-        x = _st(store, x + block_fwd(x, p, H, P, G, N, eps, store=store)["out"])
-    return {"out": x, "xs": xs}
+        f = block_fwd(x, p, H, P, G, N, eps, None if conv_states is None else conv_states[j],
+                      None if ssm_states is None else ssm_states[j], store=store)
+        cs.append(f["conv_state"])
+        ss.append(f["ssm_state"])
+        x = _st(store, x + f["out"])
+    return {"out": x, "xs": xs, "conv_states": cs, "ssm_states": ss}
 
 
 def stack_bwd(xs, layers, H, P, G, N, dout, eps=1e-5, store=None):

@@ -120,3 +120,18 @@ def test_with_the_pre_norm_gradients_still_match_central_differences():
             lay[j]["pre_norm_w"] = a
             return L(lay=lay)
         close(b["grads"][j]["dpre_norm_w"], numgrad(with_param, layers[j]["pre_norm_w"]), 2e-7)
+
+
+def test_a_stack_continued_from_the_states_of_every_layer_is_the_whole_sequence():
+    d0, d1, d2 = draw(11, L=10), draw(12, L=10), draw(13, L=10)
+    layers, x0 = [d0["p"], d1["p"], d2["p"]], d0["u"]
+    whole = block_ref.stack_fwd(x0, layers, H, P, G, N)
+    outs, cs, ss, t = [], None, None, 0
+    for n in (4, 1, 1, 4):      # a prompt, two single tokens, the rest
+        f = block_ref.stack_fwd(x0[t:t + n], layers, H, P, G, N, conv_states=cs, ssm_states=ss)
+        outs.append(f["out"])
+        cs, ss, t = f["conv_states"], f["ssm_states"], t + n
+    close(np.concatenate(outs), whole["out"], 1e-12)
+    for j in range(3):
+        close(ss[j], whole["ssm_states"][j], 1e-12)
+        close(cs[j], whole["conv_states"][j], 1e-12)
