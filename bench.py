@@ -324,6 +324,58 @@ def block_bench(args, cfg, pk, torch, dev):
         NL, li = args.layers, args.layer_interval
         layers = [par] + [{k: (v + 0.01 * torch.randn(v.shape, device=dev, generator=g, dtype=torch.float32).to(v.dtype)) if k in ("W_in", "W_out") else v.clone()
                            for k, v in par.items()} for _ in range(NL - 1)]
+        if args.inference:
+            # forward only, nothing kept: the prompt through all layers segment by segment, then one token per call
+            st = {}
+
+            def prefill():
+                st.update(pk.magc_blockstack_infer(u, layers, H, P, G, N, cfg.chunk, cfg.segment, out=st.get("out"), workspace=st.get("workspace")))
+
+            for _ in range(args.warmup):
+                prefill()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(args.steps):
+                prefill()
+            torch.cuda.synchronize()
+            ms_p = (time.perf_counter() - t0) * 1e3 / args.steps
+            # generation: the C entry point called directly with arguments marshalled once
+            B = pk.binding
+            pars = (B.magc_block_params_t * NL)(*[B.magc_block_params_t(*[(p[k].data_ptr() if k in p else None) for k in B.BLOCK_PARAMS]) for p in layers])
+            one = B.magc_blockstack_shape_t(B.magc_block_shape_t(dm, H, P, G, N, cfg.chunk, 1e-5, 1, cfg.segment), NL, 1)
+            tok = u[:1].clone()
+            ws = torch.empty(int(pk.lib().magc_blockstack_workspace_bytes(ctypes.byref(one), 0)), dtype=torch.uint8, device=dev)
+            stream = torch.cuda.current_stream().cuda_stream or None
+            ntok = 32
+
+            def generate():
+                for _ in range(ntok):
+                    rc = pk.lib().magc_blockstack_infer(ctypes.byref(one), pars, tok.data_ptr(), tok.data_ptr(), st["ssm_state"].data_ptr(),
+                                                        st["conv_state"].data_ptr(), 0, ws.data_ptr(), ws.numel(), stream)
+                    assert rc == 0, rc
+            generate()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            generate()
+            torch.cuda.synchronize()
+            us_tok = (time.perf_counter() - t0) * 1e6 / ntok
+            wbytes = sum(v.numel() * v.element_size() for v in par.values()) * NL
+            print(json.dumps({
+                "metric": "Mamba-2 block stack prefill tokens/sec/layer", "value": NL * L / (ms_p * 1e-3), "unit": "tokens/s", "n_gpus": 1,
+                "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_p, "higher_is_better": True, "scaling": "weak",
+                "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+                "config": {"workload": cfg.name + "_block_stack_prefill", "pre_norm": bool(args.pre_norm), "seqlen": L, "layers": NL,
+                           "d_model": dm, "segment": cfg.segment},
+                "roofline": {"bound": "mfma", "achieved": 2.0 * (dm * d_in_proj + d_inner * dm) * NL * L / (ms_p * 1e-3) / 1e12,
+                             "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                             "frac": 2.0 * (dm * d_in_proj + d_inner * dm) * NL * L / (ms_p * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
+                "generation": {"us_per_token": us_tok, "us_per_token_per_layer": us_tok / NL, "tokens": ntok,
+                               "weights_and_states_bytes_per_token": wbytes + 2 * NL * H * P * N * 4,
+                               "hbm_floor_us": (wbytes + 2 * NL * H * P * N * 4) / HBM_PEAK_GBS / 1e3,
+                               "note": "one C call per token; every parameter read once and every SSM state read and written once per token"},
+                "workspace_bytes": int(ws.numel()),
+            }))
+            return
         grads = [{"d" + k: torch.empty(v.shape, dtype=torch.float32, device=dev) for k, v in par.items()} for _ in range(NL)]
         f = {}
 

@@ -327,8 +327,9 @@ int magc_block_bwd(const magc_block_shape_t* shape, const magc_block_params_t* p
 
 /*
  * A stack of whole blocks with residual adds, x_{j+1} = x_j + Block_j(x_j) (with pre_norm_w: the pre-norm
- * residual layer of the language model), on the two-axis grid of MA-GC (Sec. 3.2 / 3.3, Alg. 1 and 2): the input of every `layer_interval`-th layer is kept for the whole
- * sequence, the SSM and convolution states of every layer every `segment` tokens (block.seqlen, block.segment);
+ * residual layer of the language model), on the two-axis grid of MA-GC (Sec. 3.2 / 3.3, Alg. 1 and 2): the
+ * input of every `layer_interval`-th layer is kept for the whole sequence, the SSM and convolution states of
+ * every layer every `segment` tokens (block.seqlen, block.segment);
  * the backward pass walks the grid cell by cell, restores a cell's layer inputs from its two kinds of
  * checkpoint and back-propagates through it.
  *   params, grads: host arrays of `nlayers` structs of device pointers (one per layer)
@@ -353,6 +354,22 @@ int magc_blockstack_bwd(const magc_blockstack_shape_t* shape, const magc_block_p
                         const void* dout, const void* l_ckpt, const float* ssm_ckpt, const void* conv_ckpt, void* dx0,
                         const magc_block_grads_t* grads, void* workspace, size_t workspace_bytes, uint32_t flags,
                         void* hip_stream);
+
+/*
+ * The same stack, forward only and with nothing kept (inference over long inputs, Sec. 4: the memory taken
+ * does not depend on the length; then generation with the recurrence of Eq. 1).  The states of every layer
+ * live in two caller-owned device arrays,
+ *   ssm_state [nlayers, H, P, N] fp32 and conv_state [nlayers, 3, d_inner + 2 G N] bf16,
+ * which the call reads (fresh != 0: takes as zeros without reading them) and replaces by the states behind its
+ * last token: a prompt of any length (walked in pieces of block.segment tokens through all layers), then calls
+ * of one or a few tokens, continue one sequence.  x0, out [block.seqlen, d_model] bf16 (may be the same
+ * buffer); layer_interval is ignored (give any value in 1 .. nlayers).
+ *   workspace: magc_blockstack_workspace_bytes(shape, 0) bytes, 256-byte aligned
+ * Enqueued on hip_stream in order, nothing allocated, no other stream used.  Errors as for magc_blockstack_fwd.
+ */
+int magc_blockstack_infer(const magc_blockstack_shape_t* shape, const magc_block_params_t* params, const void* x0, void* out,
+                          float* ssm_state, void* conv_state, int32_t fresh, void* workspace, size_t workspace_bytes,
+                          void* hip_stream);
 
 /*
  * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the

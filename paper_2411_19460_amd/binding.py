@@ -20,7 +20,8 @@ EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_b
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
            "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
            "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
-           "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_stack_workspace_bytes", "magc_stack_fwd",
+           "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_blockstack_infer",
+           "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize", "ssd_prof_mfma_peak")
 
 
@@ -133,6 +134,8 @@ def lib():
         L.magc_blockstack_workspace_bytes.argtypes = [sshp, i32]
         L.magc_blockstack_fwd.restype = ctypes.c_int
         L.magc_blockstack_fwd.argtypes = [sshp, bpar] + [vp] * 5 + [vp, sz, vp]
+        L.magc_blockstack_infer.restype = ctypes.c_int
+        L.magc_blockstack_infer.argtypes = [sshp, bpar] + [vp] * 4 + [i32, vp, sz, vp]
         L.magc_blockstack_bwd.restype = ctypes.c_int
         L.magc_blockstack_bwd.argtypes = [sshp, bpar] + [vp] * 6 + [bgr, vp, sz, u32, vp]
         L.ssd_prof_mfma_peak.restype = ctypes.c_int
@@ -548,6 +551,37 @@ def magc_blockstack_fwd(x0, layers, nheads, headdim, ngroups, dstate, chunk, seg
     if rc != 0:
         raise SSDError(rc, "magc_blockstack_fwd")
     return {"out": out, "l_ckpt": l_ckpt, "ssm_ckpt": ssm_ckpt, "conv_ckpt": conv_ckpt}
+
+
+def magc_blockstack_infer(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, eps=1e-5, ssm_state=None, conv_state=None,
+                          out=None, workspace=None):
+    """The stack forward only with nothing kept, continuing from the per-layer states (None: a new sequence;
+    then they are allocated).  The states are updated in place.  Returns dict(out, ssm_state, conv_state, workspace);
+    hand the last three back in to continue the sequence without any allocation."""
+    import torch
+    sshape, pars, _, _, conv_dim = _blockstack_setup(x0, layers, nheads, headdim, ngroups, dstate, chunk, segment, 1, eps)
+    dev, NL = x0.device, len(layers)
+    if (ssm_state is None) != (conv_state is None):
+        raise ValueError("both states or none")
+    fresh = ssm_state is None
+    if fresh:
+        ssm_state = torch.empty((NL, nheads, headdim, dstate), dtype=torch.float32, device=dev)
+        conv_state = torch.empty((NL, 3, conv_dim), dtype=torch.bfloat16, device=dev)
+    for t, shp, dty in ((ssm_state, (NL, nheads, headdim, dstate), torch.float32), (conv_state, (NL, 3, conv_dim), torch.bfloat16)):
+        if tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"state tensor must be a dense {dty} device tensor of shape {shp}")
+    if out is None:
+        out = torch.empty_like(x0)
+    elif out.shape != x0.shape or out.dtype != x0.dtype or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must match x0")
+    need = int(lib().magc_blockstack_workspace_bytes(ctypes.byref(sshape), 0))
+    if workspace is None or workspace.numel() < need:
+        workspace = _workspace(need, dev)
+    rc = lib().magc_blockstack_infer(ctypes.byref(sshape), pars, _ptr(x0), _ptr(out), _ptr(ssm_state), _ptr(conv_state), 1 if fresh else 0,
+                                     _ptr(workspace), workspace.numel(), _stream(x0))
+    if rc != 0:
+        raise SSDError(rc, "magc_blockstack_infer")
+    return {"out": out, "ssm_state": ssm_state, "conv_state": conv_state, "workspace": workspace}
 
 
 def magc_blockstack_bwd(x0, layers, dout, l_ckpt, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment,

@@ -721,3 +721,49 @@ extern "C" int magc_blockstack_bwd(const magc_blockstack_shape_t* sh, const magc
     }
     return SSD_OK;
 }
+
+// Forward only, nothing kept: the stack as a language model runs it at inference.  The states of every layer
+// live in two caller-owned arrays and are replaced by the states behind the last token of the call, so a
+// prompt of any length (in segments: memory does not grow with it) and then single tokens are the same call.
+extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const magc_block_params_t* params, const void* x0, void* out,
+                                     float* ssm_state, void* conv_state, int32_t fresh, void* workspace, size_t workspace_bytes,
+                                     void* hip_stream) {
+    StackDims d;
+    BLK_TRY(check_stack(sh, &d));
+    if (!params_ok(params, d.NL) || !ssm_state || !conv_state) return SSD_ERR_NULL;
+    hipStream_t st = (hipStream_t)hip_stream;
+    if (d.b.L == 0) {
+        if (fresh) {
+            BLK_HIP(launch_fill_zero(ssm_state, (size_t)d.NL * d.b.HPN, st));
+            BLK_HIP(launch_fill_zero((float*)conv_state, (size_t)d.NL * d.conv_state / 4, st));
+        }
+        return SSD_OK;
+    }
+    if (!x0 || !out) return SSD_ERR_NULL;
+    const StackWs w = stack_layout(sh, d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    char* ws = (char*)workspace;
+    const size_t row = (size_t)d.b.dm * 2;
+    for (int64_t k = 0; k < d.b.nseg; ++k) {
+        const int64_t t0 = k * d.b.s, rows = d.b.L - t0 < d.b.s ? d.b.L - t0 : d.b.s;
+        const magc_block_shape_t c = cell_shape(sh, rows);
+        const bool zero = fresh && k == 0;
+        // a few tokens: the recurrence runs on the layer's SSM state itself; a segment: through a spare state
+        const bool in_place = rows <= DECODE_ROWS;
+        const char* cur = (const char*)x0 + (size_t)t0 * row;
+        for (int j = 0; j < d.NL; ++j) {
+            float* sj = ssm_state + (size_t)j * d.b.HPN;
+            char* cj = (char*)conv_state + (size_t)j * d.conv_state;
+            float* ssm_out = in_place ? sj : (float*)(ws + w.fin_ssm);
+            char* y = ws + w.act[j & 1];
+            BLK_TRY(magc_block_fwd(&c, &params[j], cur, zero ? nullptr : sj, zero ? nullptr : cj, y, nullptr, nullptr, ssm_out,
+                                   ws + w.fin_conv, ws + w.inner, w.inner_bytes, st));
+            if (!in_place) BLK_HIP(launch_copy_f32(sj, ssm_out, d.b.HPN, st));
+            BLK_HIP(launch_copy_f32((float*)cj, (const float*)(ws + w.fin_conv), d.conv_state / 4, st));  // bf16 pairs as words
+            char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
+            BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
+            cur = nxt;
+        }
+    }
+    return SSD_OK;
+}

@@ -218,6 +218,37 @@ def test_stack_of_blocks_on_the_two_axis_grid(case):
             assert float((a - b).abs().max()) <= 2.0 ** -6 * float(b.abs().max()), (j, k)
 
 
+@pytest.mark.parametrize("pre", [False, True])
+def test_stack_inference_prompt_then_tokens(pre):
+    # forward only, nothing kept: a prompt in segments (the last one short), then tokens one at a time and three
+    # at once, every call continuing from the per-layer states the previous one left -- against the oracle run
+    # over the whole sequence, outputs and the states of every layer
+    NL, L0, seg, gen = 3, 600, 256, [1, 1, 3, 1]
+    dm, H, P, G, N, Q = 128, 8, 64, 1, 128, 128
+    L = L0 + sum(gen)
+    ds = [draw(20 + j, L, dm, H, P, G, N, pre) for j in range(NL)]
+    layers_h, x0h = [x["p"] for x in ds], ds[0]["u"]
+    x0, layers = dev_bf16(x0h), [to_dev(p) for p in layers_h]
+    fo = block_ref.stack_fwd(x0h, layers_h, H, P, G, N, 1e-5, store=synth.round_bf16)
+    st = pk.magc_blockstack_infer(x0[:L0].contiguous(), layers, H, P, G, N, Q, seg)
+    # the training forward pass computes the same thing for the prompt
+    ft = pk.magc_blockstack_fwd(x0[:L0].contiguous(), layers, H, P, G, N, Q, seg, 2)
+    assert torch.equal(ft["out"], st["out"])
+    outs, t = [st["out"]], L0
+    for n in gen:
+        xin = x0[t:t + n].clone()
+        st = pk.magc_blockstack_infer(xin, layers, H, P, G, N, Q, seg, ssm_state=st["ssm_state"], conv_state=st["conv_state"],
+                                      out=xin, workspace=st["workspace"])      # output over the input
+        outs.append(st["out"])
+        t += n
+    torch.cuda.synchronize()
+    tol = 2 * TOL["bf16"]
+    check("out", host(torch.cat(outs)), fo["out"], tol)
+    for j in range(NL):
+        check(f"layer {j} ssm state", host(st["ssm_state"][j]), fo["ssm_states"][j], tol)
+        check(f"layer {j} conv state", host(st["conv_state"][j]), fo["conv_states"][j], tol)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
