@@ -5,7 +5,7 @@ import sys
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _ROOT = os.path.dirname(_HERE)
-SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "dual_kernel.hip", "grad_bc_kernels.hip", "stack.hip", "prof.hip", "decode.hip", "conv1d.hip", "gated_norm.hip", "linear.hip", "block.hip", "magc_plan.cpp"]
+SOURCES = ["api.hip", "generic_kernels.hip", "mfma_kernels.hip", "dual_kernel.hip", "grad_bc_kernels.hip", "stack.hip", "prof.hip", "decode.hip", "conv1d.hip", "gated_norm.hip", "linear.hip", "few_rows.hip", "block.hip", "magc_plan.cpp"]
 LIB = os.path.join(_HERE, "libssd_magc.so")
 
 

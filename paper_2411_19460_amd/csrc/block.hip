@@ -317,6 +317,79 @@ int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc
     return SSD_OK;
 }
 
+// A few tokens with both states handed on (generation): the whole block in three launches, the steps folded into
+// the two products and the recurrence kernel (few_rows.hip).  `res`, if given, is added to the output.
+bool few_path(const BlockDims& d, const magc_block_params_t* p, int64_t rows, const float* ssm_out, const void* u, const void* out) {
+    if (rows < 1 || rows > FEW_ROWS || !ssm_out || (size_t)2 * d.N * 4 > 48 * 1024) return false;
+    const void* ptrs[] = {u, out, p->W_in, p->W_out, p->norm_w, p->pre_norm_w};
+    for (const void* q : ptrs)
+        if ((uintptr_t)q & 15) return false;
+    return true;
+}
+
+int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
+                const void* u, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out, void* out,
+                const void* res, hipStream_t st) {
+    FewRowsJob in;
+    memset(&in, 0, sizeof(in));
+    in.rows = (int)rows;
+    in.K = d.dm;
+    in.N = d.d_in_proj;
+    in.mode = p->pre_norm_w ? 1 : 0;
+    in.x = u;
+    in.ldx = d.dm;
+    in.w = p->W_in;
+    in.out = ws + w.zx;
+    in.ldo = d.d_in_proj;
+    in.in_w = p->pre_norm_w;
+    in.eps = sh->eps;
+    BLK_HIP(launch_linear_few_rows(in, st));
+    if (ssm_in != ssm_out) BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
+    DecodeMidJob mid;
+    memset(&mid, 0, sizeof(mid));
+    mid.T = (int)rows;
+    mid.H = d.H;
+    mid.P = d.P;
+    mid.G = d.G;
+    mid.N = d.N;
+    mid.zx = ws + w.zx;
+    mid.ld = d.d_in_proj;
+    mid.conv_w = p->conv_w;
+    mid.conv_b = p->conv_b;
+    mid.dt_bias = p->dt_bias;
+    mid.A = p->A;
+    mid.D = p->D;
+    mid.cs_in = conv_in;
+    mid.cs_out = conv_out;
+    mid.state = ssm_out;
+    mid.y = ws + w.y;
+    BLK_HIP(launch_decode_mid(mid, st));
+    FewRowsJob o;
+    memset(&o, 0, sizeof(o));
+    o.rows = (int)rows;
+    o.K = d.d_inner;
+    o.N = d.dm;
+    o.w = p->W_out;
+    o.out = out;
+    o.ldo = d.dm;
+    o.ldx = d.d_inner;
+    o.res = res;
+    o.ldres = d.dm;
+    if (d.G == 1) {  // one group: the gated normalisation rides on the product
+        o.mode = 2;
+        o.x = ws + w.y;
+        o.in_w = p->norm_w;
+        o.z = ws + w.zx;
+        o.ldz = d.d_in_proj;
+        o.eps = sh->eps;
+    } else {
+        BLK_TRY(seg_norm(d, sh, p, ws, w, ws + w.zx, ws + w.y, rows, st));
+        o.x = ws + w.yn;
+    }
+    BLK_HIP(launch_linear_few_rows(o, st));
+    return SSD_OK;
+}
+
 // The reverse of every step of a segment, given its forward activations (zx, y from the caller; x / B / C,
 // dt and the normalised y in the workspace): du of the segment, parameter gradients added to `g`, the
 // adjoints of the two states entering the segment.
@@ -403,9 +476,14 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
         const void* conv_in = k == 0 ? init_conv : conv_ckpt ? (const char*)conv_ckpt + (size_t)k * conv_state_bytes : ws + w.cconv[k & 1];
         float* ssm_out = last ? final_ssm : ssm_ckpt ? ssm_ckpt + (size_t)(k + 1) * d.HPN : (float*)(ws + w.cssm[(k + 1) & 1]);
         void* conv_out = last ? final_conv : conv_ckpt ? (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes : ws + w.cconv[(k + 1) & 1];
-        BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, (const char*)u + (size_t)t0 * d.dm * 2, rows, ssm_in, conv_in, ssm_out,
-                                conv_out, st));
-        BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, (char*)out + (size_t)t0 * d.dm * 2, 0, st));
+        const char* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
+        char* out_seg = (char*)out + (size_t)t0 * d.dm * 2;
+        if (few_path(d, p, rows, ssm_out, u_seg, out_seg) && (!conv_out || conv_out != conv_in)) {
+            BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, st));
+            continue;
+        }
+        BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st));
+        BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, st));
     }
     return SSD_OK;
 }
@@ -747,6 +825,11 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
     for (int64_t k = 0; k < d.b.nseg; ++k) {
         const int64_t t0 = k * d.b.s, rows = d.b.L - t0 < d.b.s ? d.b.L - t0 : d.b.s;
         const magc_block_shape_t c = cell_shape(sh, rows);
+        BlockDims dc;
+        BLK_TRY(check(&c, &dc));
+        const BlockWs bw = layout(dc, false);  // for the few-token path, which lays a block workspace out itself
+        if (bw.total > w.inner_bytes) return SSD_ERR_WORKSPACE;
+        char* bws = ws + w.inner;
         const bool zero = fresh && k == 0;
         // a few tokens: the recurrence runs on the layer's SSM state itself; a segment: through a spare state
         const bool in_place = rows <= DECODE_ROWS;
@@ -756,12 +839,17 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
             char* cj = (char*)conv_state + (size_t)j * d.conv_state;
             float* ssm_out = in_place ? sj : (float*)(ws + w.fin_ssm);
             char* y = ws + w.act[j & 1];
-            BLK_TRY(magc_block_fwd(&c, &params[j], cur, zero ? nullptr : sj, zero ? nullptr : cj, y, nullptr, nullptr, ssm_out,
-                                   ws + w.fin_conv, ws + w.inner, w.inner_bytes, st));
+            char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
+            if (few_path(dc, &params[j], rows, ssm_out, cur, nxt)) {  // generation: the residual rides on the output product
+                BLK_TRY(forward_few(dc, &c, &params[j], bws, bw, cur, rows, zero ? nullptr : sj, zero ? nullptr : cj, ssm_out,
+                                    ws + w.fin_conv, nxt, cur, st));
+            } else {
+                BLK_TRY(magc_block_fwd(&c, &params[j], cur, zero ? nullptr : sj, zero ? nullptr : cj, y, nullptr, nullptr, ssm_out,
+                                       ws + w.fin_conv, ws + w.inner, w.inner_bytes, st));
+                BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
+            }
             if (!in_place) BLK_HIP(launch_copy_f32(sj, ssm_out, d.b.HPN, st));
             BLK_HIP(launch_copy_f32((float*)cj, (const float*)(ws + w.fin_conv), d.conv_state / 4, st));  // bf16 pairs as words
-            char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
-            BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
             cur = nxt;
         }
     }

@@ -1,0 +1,252 @@
+// Generation: a token or a few at a time through a block (the recurrence of Sec. 3.1, Eq. 1 around which the
+// block's other steps shrink to vectors).  At these row counts the matrix cores are of no use; every kernel
+// here is bound by reading each parameter once and the SSM state twice per token, so the block's steps are
+// folded into three launches that do exactly that:
+//   k_linear_few<1>  zxbcdt = RMSNorm(u) pre_norm_w W_in^T   (or plain u W_in^T)
+//   k_decode_mid     convolution + SiLU, softplus(dt), the state update and y = C h + D x, token by token
+//   k_linear_few<2>  out = RMSNorm(y silu(z)) norm_w W_out^T (+ the residual)
+#include "ssd_internal.h"
+
+namespace ssdk {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ float sigmoid_fast(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, 64);
+    return v;
+}
+
+// what storing a value in bf16 and reading it back leaves of it
+__device__ __forceinline__ float through_bf16(float v) { return (float)(__bf16)v; }
+
+struct FewParams {
+    const __bf16 *x, *w, *z, *res;
+    __bf16* out;
+    const float* in_w;
+    int64_t ldx, ldz, ldo, ldres;
+    int rows, K, N;
+    float eps;
+};
+
+constexpr int CPW = 2;  // output columns per wave: the input rows are fetched (and transformed) once for both
+
+// out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]) for r < rows <= R.  A wave owns CPW columns n and walks k
+// with 16-byte loads, so every weight is read once, in full cache lines; the few input rows come from the
+// caches.  MODE 0: f(x) = x.  MODE 1: f(x) = x / sqrt(mean x^2 + eps) * in_w.  MODE 2: the same of g = x z sigmoid(z).
+// A wave sees whole rows, so the mean comes out of the same loop and scales the finished sums.
+template <int MODE, int R>
+__global__ __launch_bounds__(256) void k_linear_few(FewParams fp) {
+    const int lane = threadIdx.x & 63;
+    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * CPW;
+    if (n0 >= fp.N) return;  // whole waves leave; the kernel has no barrier
+    float acc[R][CPW], ss[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        ss[r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) acc[r][c] = 0.f;
+    }
+    const __bf16* w0 = fp.w + (int64_t)n0 * fp.K;
+    for (int k = lane * 8; k < fp.K; k += 512) {
+        bf16x8 wv[CPW];
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) wv[c] = *(const bf16x8*)(w0 + (int64_t)c * fp.K + k);
+        float iw[8];
+        if (MODE) {
+            const f32x4 a = *(const f32x4*)(fp.in_w + k), b = *(const f32x4*)(fp.in_w + k + 4);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                iw[e] = a[e];
+                iw[4 + e] = b[e];
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < fp.rows) {
+                const bf16x8 xv = *(const bf16x8*)(fp.x + r * fp.ldx + k);
+                bf16x8 zv;
+                if (MODE == 2) zv = *(const bf16x8*)(fp.z + r * fp.ldz + k);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    float v = (float)xv[e];
+                    if (MODE == 2) {
+                        const float zz = (float)zv[e];
+                        v *= zz * sigmoid_fast(zz);
+                    }
+                    if (MODE) {
+                        ss[r] = fmaf(v, v, ss[r]);
+                        v *= iw[e];
+                    }
+#pragma unroll
+                    for (int c = 0; c < CPW; ++c) acc[r][c] = fmaf(v, (float)wv[c][e], acc[r][c]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        if (r < fp.rows) {
+            const float rstd = MODE ? rsqrtf(wave_sum(ss[r]) / (float)fp.K + fp.eps) : 1.f;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) {
+                float v = wave_sum(acc[r][c]) * rstd;
+                if (lane == 0) {
+                    if (fp.res) v += (float)fp.res[r * fp.ldres + n0 + c];
+                    fp.out[r * fp.ldo + n0 + c] = (__bf16)v;
+                }
+            }
+        }
+    }
+}
+
+template <int MODE>
+hipError_t launch_few(const FewParams& fp, hipStream_t st) {
+    const dim3 grid((unsigned)((fp.N / CPW + 3) / 4)), block(256);
+    if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1>), grid, block, 0, st, fp);
+    else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2>), grid, block, 0, st, fp);
+    else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4>), grid, block, 0, st, fp);
+    else if (fp.rows <= 8) hipLaunchKernelGGL((k_linear_few<MODE, 8>), grid, block, 0, st, fp);
+    else hipLaunchKernelGGL((k_linear_few<MODE, 16>), grid, block, 0, st, fp);
+    return hipGetLastError();
+}
+
+struct MidParams {
+    const __bf16* zx;   // [T, ld]: (z | xBC | dt_raw) of the tokens
+    int64_t ld;
+    const float *conv_w, *conv_b, *dt_bias, *A, *D;
+    const __bf16* cs_in;  // [3, conv_dim] or null: the convolution's inputs of the three tokens before
+    __bf16* cs_out;       // [3, conv_dim] or null; never the same buffer as cs_in
+    float* state;         // [H, P, N], updated in place
+    __bf16* y;            // [T, d_inner]
+    int T, H, P, G, N, hpg, d_inner, conv_dim, off_xbc, off_dt;
+};
+
+// input of the convolution, channel c, token `pos` of this call (negative: from the entering state)
+__device__ __forceinline__ float conv_input(const MidParams& mp, int pos, int c) {
+    if (pos >= 0) return (float)mp.zx[pos * mp.ld + mp.off_xbc + c];
+    return mp.cs_in ? (float)mp.cs_in[(3 + pos) * mp.conv_dim + c] : 0.f;
+}
+
+// silu(bias + four taps), rounded as the block stores it between its steps
+__device__ __forceinline__ float conv_output(const MidParams& mp, int t, int c) {
+    const float* w = mp.conv_w + (int64_t)c * 4;
+    const float pre = mp.conv_b[c] + w[0] * conv_input(mp, t - 3, c) + w[1] * conv_input(mp, t - 2, c) + w[2] * conv_input(mp, t - 1, c) +
+                      w[3] * conv_input(mp, t, c);
+    return through_bf16(pre * sigmoid_fast(pre));
+}
+
+// Workgroup (head h, z): wave w owns the state rows p = 4 z + w, + 4 gridDim.z, ...; lane l the columns
+// n = l, l + 64, ...  Per token the workgroup convolves the B and C channels of its group into LDS (every
+// workgroup of the group does: a few hundred channels against a state of P N elements), each wave the x
+// channel of its row; a lane only ever touches its own state elements.
+__global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
+    extern __shared__ float bc[];  // B[0..N), C[0..N) of the group, this token
+    const int h = blockIdx.x, g = h / mp.hpg;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const float Ah = mp.A[h], Dh = mp.D[h], bias_h = mp.dt_bias[h];
+    float* S = mp.state + (int64_t)h * mp.P * mp.N;
+    const int cB = mp.d_inner + g * mp.N, cC = mp.d_inner + (mp.G + g) * mp.N;
+    for (int t = 0; t < mp.T; ++t) {
+        for (int i = threadIdx.x; i < 2 * mp.N; i += 256) bc[i] = conv_output(mp, t, i < mp.N ? cB + i : cC + (i - mp.N));
+        const float v = (float)mp.zx[t * mp.ld + mp.off_dt + h] + bias_h;
+        const float dtv = through_bf16(fmaxf(v, 0.f) + log1pf(__expf(-fabsf(v))));  // softplus
+        const float a = __expf(dtv * Ah);
+        __syncthreads();
+        for (int p = 4 * blockIdx.z + w; p < mp.P; p += 4 * gridDim.z) {
+            const float xv = conv_output(mp, t, h * mp.P + p);
+            const float dx = dtv * xv;
+            float acc = 0.f;
+            for (int n = lane; n < mp.N; n += 64) {
+                const float hn = a * S[(int64_t)p * mp.N + n] + dx * bc[n];
+                S[(int64_t)p * mp.N + n] = hn;
+                acc += bc[mp.N + n] * hn;
+            }
+            acc = wave_sum(acc);
+            if (lane == 0) mp.y[(int64_t)t * mp.d_inner + h * mp.P + p] = (__bf16)(acc + Dh * xv);
+        }
+        __syncthreads();  // the next token's B and C replace these
+    }
+    if (mp.cs_out) {  // the last three inputs of [entering state ; this call's tokens]
+        for (int p = 4 * blockIdx.z + w; p < mp.P; p += 4 * gridDim.z)
+            if (lane < 3) mp.cs_out[lane * mp.conv_dim + h * mp.P + p] = (__bf16)conv_input(mp, mp.T - 3 + lane, h * mp.P + p);
+        if (h % mp.hpg == 0 && blockIdx.z == 0)  // the group's B and C channels: once
+            for (int i = threadIdx.x; i < 6 * mp.N; i += 256) {
+                const int j = i / (2 * mp.N), ii = i % (2 * mp.N);
+                const int c = ii < mp.N ? cB + ii : cC + (ii - mp.N);
+                mp.cs_out[j * mp.conv_dim + c] = (__bf16)conv_input(mp, mp.T - 3 + j, c);
+            }
+    }
+}
+
+bool al16(const void* p) { return ((uintptr_t)p & 15) == 0; }
+
+}  // namespace
+
+bool few_rows_supported(const FewRowsJob& j) {
+    if (j.rows < 1 || j.rows > FEW_ROWS || j.K <= 0 || j.N <= 0 || ((j.K | j.N) & 7)) return false;
+    if (!j.x || !j.w || !j.out || !al16(j.x) || !al16(j.w) || (j.ldx & 7) || j.ldx < j.K || j.ldo < j.N) return false;
+    if (j.mode < 0 || j.mode > 2) return false;
+    if (j.mode && (!j.in_w || !al16(j.in_w))) return false;
+    if (j.mode == 2 && (!j.z || !al16(j.z) || (j.ldz & 7) || j.ldz < j.K)) return false;
+    if (j.res && j.ldres < j.N) return false;
+    return true;
+}
+
+hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st) {
+    if (!few_rows_supported(j)) return hipErrorInvalidValue;
+    FewParams fp;
+    fp.x = (const __bf16*)j.x;
+    fp.w = (const __bf16*)j.w;
+    fp.z = (const __bf16*)j.z;
+    fp.res = (const __bf16*)j.res;
+    fp.out = (__bf16*)j.out;
+    fp.in_w = j.in_w;
+    fp.ldx = j.ldx;
+    fp.ldz = j.ldz;
+    fp.ldo = j.ldo;
+    fp.ldres = j.ldres;
+    fp.rows = j.rows;
+    fp.K = j.K;
+    fp.N = j.N;
+    fp.eps = j.eps;
+    return j.mode == 0 ? launch_few<0>(fp, st) : j.mode == 1 ? launch_few<1>(fp, st) : launch_few<2>(fp, st);
+}
+
+hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
+    if (j.T < 1 || j.T > FEW_ROWS || j.H <= 0 || j.H > 65535 || j.P <= 0 || j.G <= 0 || j.N <= 0 || j.H % j.G) return hipErrorInvalidValue;
+    if (!j.zx || !j.conv_w || !j.conv_b || !j.dt_bias || !j.A || !j.D || !j.state || !j.y || (j.cs_out && j.cs_out == j.cs_in))
+        return hipErrorInvalidValue;
+    if ((size_t)2 * j.N * sizeof(float) > 48 * 1024) return hipErrorInvalidValue;
+    MidParams mp;
+    mp.zx = (const __bf16*)j.zx;
+    mp.ld = j.ld;
+    mp.conv_w = j.conv_w;
+    mp.conv_b = j.conv_b;
+    mp.dt_bias = j.dt_bias;
+    mp.A = j.A;
+    mp.D = j.D;
+    mp.cs_in = (const __bf16*)j.cs_in;
+    mp.cs_out = (__bf16*)j.cs_out;
+    mp.state = j.state;
+    mp.y = (__bf16*)j.y;
+    mp.T = j.T;
+    mp.H = j.H;
+    mp.P = j.P;
+    mp.G = j.G;
+    mp.N = j.N;
+    mp.hpg = j.H / j.G;
+    mp.d_inner = j.H * j.P;
+    mp.conv_dim = mp.d_inner + 2 * j.G * j.N;
+    mp.off_xbc = mp.d_inner;
+    mp.off_dt = mp.d_inner + mp.conv_dim;
+    const int rows4 = (j.P + 3) / 4;
+    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, 1, rows4 < 64 ? rows4 : 64), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
+    return hipGetLastError();
+}
+
+}  // namespace ssdk

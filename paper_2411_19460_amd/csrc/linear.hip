@@ -461,6 +461,19 @@ extern "C" int ssd_linear_fwd(int64_t rows, int32_t in_dim, int32_t out_dim, con
     if (rows == 0) return SSD_OK;
     if (!x || !w || !out) return SSD_ERR_NULL;
     if (!ok_ptr(x) || !ok_ptr(w) || !ok_ptr(out)) return SSD_ERR_ARG;
+    if (rows <= FEW_ROWS) {  // a token or a few: bound by reading w once, not by the matrix cores
+        FewRowsJob j;
+        memset(&j, 0, sizeof(j));
+        j.rows = (int)rows;
+        j.K = in_dim;
+        j.N = out_dim;
+        j.x = x;
+        j.ldx = x_row_stride ? x_row_stride : in_dim;
+        j.w = w;
+        j.out = out;
+        j.ldo = out_row_stride ? out_row_stride : out_dim;
+        if (few_rows_supported(j)) return launch_linear_few_rows(j, (hipStream_t)hip_stream) == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+    }
     GemmParams gp;
     memset(&gp, 0, sizeof(gp));
     gp.A = (const bf16_t*)x;   // [rows, in]   k-major

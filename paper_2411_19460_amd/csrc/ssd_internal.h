@@ -200,4 +200,38 @@ hipError_t mfma_launch_grad_bc(const SegParams& sp, bool with_dual, hipStream_t 
 // Smallest divisor ns of heads_per_group with base * ns >= target workgroups (else heads_per_group).
 int pick_split(int heads_per_group, int64_t base, int target);
 
+// Generation (few_rows.hip): products and the block's middle steps for at most FEW_ROWS tokens, bf16 storage.
+constexpr int FEW_ROWS = 16;
+// out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]); w [N, K] dense.  mode 0: f = identity; 1: RMS normalisation
+// over all of K times in_w; 2: the same of x z sigmoid(z).  Row strides in elements.
+struct FewRowsJob {
+    int rows, K, N, mode;
+    const void* x;
+    int64_t ldx;
+    const void* w;
+    void* out;
+    int64_t ldo;
+    const float* in_w;
+    const void* z;
+    int64_t ldz;
+    float eps;
+    const void* res;
+    int64_t ldres;
+};
+bool few_rows_supported(const FewRowsJob& j);  // sizes, strides and 16-byte alignment the kernel relies on
+hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st);
+// zx [T, ld] = (z | xBC | dt_raw) of T tokens -> y [T, H P]; state [H, P, N] in place; cs_in / cs_out [3, H P + 2 G N]
+// (either may be null; never the same buffer)
+struct DecodeMidJob {
+    int T, H, P, G, N;
+    const void* zx;
+    int64_t ld;
+    const float *conv_w, *conv_b, *dt_bias, *A, *D;
+    const void* cs_in;
+    void* cs_out;
+    float* state;
+    void* y;
+};
+hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st);
+
 }  // namespace ssdk

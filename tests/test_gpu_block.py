@@ -117,13 +117,15 @@ def test_block_with_the_pre_norm(case):
         pk.magc_block_bwd(u, par, dout, f["ssm_ckpt"], f["conv_ckpt"], H, P, G, N, Q, seg, grads=bad)
 
 
-def test_block_prefill_then_generation_without_checkpoints():
+@pytest.mark.parametrize("variant", [(1, False), (2, True), (1, True)])
+def test_block_prefill_then_generation_without_checkpoints(variant):
     # forward only: a prompt in segments with no checkpoint kept, then tokens one at a time (and three at
     # once) from the states the previous call left -- against the oracle run over the whole sequence
-    L0, dm, H, P, G, N, Q, seg = 600, 128, 8, 64, 1, 128, 128, 256
-    gen = [1, 1, 1, 3, 1]
+    G, pre = variant     # groups (two: the gated normalisation runs as a step of its own), with / without the pre-norm
+    L0, dm, H, P, N, Q, seg = 600, 128, 8, 64, 128, 128, 256
+    gen = [1, 1, 1, 3, 1, 16, 2]
     L = L0 + sum(gen)
-    d = draw(3, L, dm, H, P, G, N)
+    d = draw(3, L, dm, H, P, G, N, pre)
     u, par = dev_bf16(d["u"]), to_dev(d["p"])
     fo = block_ref.block_fwd(d["u"], d["p"], H, P, G, N, 1e-5, store=synth.round_bf16)
     f = pk.magc_block_fwd(u[:L0].contiguous(), par, H, P, G, N, Q, seg, checkpoints=False)

@@ -67,6 +67,26 @@ def test_linear_forward_backward(case):
     check("dw accumulated", host(g2["dw"]), 2 * ref["dw"], 1e-4)
 
 
+@pytest.mark.parametrize("case", [(1, 2560, 10576, False), (1, 5120, 2560, False), (3, 136, 200, True), (16, 520, 72, True), (7, 8, 8, False)])
+def test_linear_forward_for_a_few_rows(case):
+    """A token or a few (generation): the product that reads the weights once, one wave per pair of columns."""
+    T, I, O, sliced = case
+    x, w, _ = draw(2, T, I, O)
+    xd, wd = dev(x), dev(w)
+    out = None
+    if sliced:
+        xd = in_wider(xd, I + 24, 8)
+        out = in_wider(torch.zeros((T, O), dtype=torch.bfloat16, device="cuda"), O + 16, 8)
+    out = pk.ssd_linear_fwd(xd, wd, out)
+    torch.cuda.synchronize()
+    check("out", host(out), linear_ref.linear_fwd(x, w), TOL["bf16"])
+    if sliced:
+        wide = out._base
+        mask = torch.ones(wide.shape, dtype=torch.bool, device=wide.device)
+        mask[:, 8:8 + O] = False
+        assert float(wide[mask].float().abs().max()) == 0.0
+
+
 def test_linear_empty_and_rejected_arguments():
     x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
     w = torch.ones((16, 64), dtype=torch.bfloat16, device="cuda")
