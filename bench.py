@@ -446,7 +446,7 @@ def block_bench(args, cfg, pk, torch, dev):
             "roofline": {"bound": "mfma", "achieved": 2.0 * (dm * d_in_proj + d_inner * dm) * L / (ms_p * 1e-3) / 1e12,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": 2.0 * (dm * d_in_proj + d_inner * dm) * L / (ms_p * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
-            "generation": {"us_per_token": us_tok, "tokens": ntok, "note": "one call per token from the host, ten launches each"},
+            "generation": {"us_per_token": us_tok, "tokens": ntok, "note": "one call per token from the host: two weight-streaming products and the recurrence kernel (plus one state copy)"},
             "workspace_bytes": int(pk.lib().magc_block_workspace_bytes(ctypes.byref(shp), 0)),
         }))
         return

@@ -320,7 +320,7 @@ int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc
 // A few tokens with both states handed on (generation): the whole block in three launches, the steps folded into
 // the two products and the recurrence kernel (few_rows.hip).  `res`, if given, is added to the output.
 bool few_path(const BlockDims& d, const magc_block_params_t* p, int64_t rows, const float* ssm_out, const void* u, const void* out) {
-    if (rows < 1 || rows > FEW_ROWS || !ssm_out || (size_t)2 * d.N * 4 > 48 * 1024) return false;
+    if (rows < 1 || rows > FEW_ROWS || !ssm_out || d.N > 512 || d.P > 256) return false;
     const void* ptrs[] = {u, out, p->W_in, p->W_out, p->norm_w, p->pre_norm_w};
     for (const void* q : ptrs)
         if ((uintptr_t)q & 15) return false;
@@ -329,7 +329,7 @@ bool few_path(const BlockDims& d, const magc_block_params_t* p, int64_t rows, co
 
 int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
                 const void* u, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out, void* out,
-                const void* res, hipStream_t st) {
+                const void* res, void* conv_final, hipStream_t st) {
     FewRowsJob in;
     memset(&in, 0, sizeof(in));
     in.rows = (int)rows;
@@ -375,6 +375,11 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     o.ldx = d.d_inner;
     o.res = res;
     o.ldres = d.dm;
+    if (conv_final) {  // the new convolution state moves to its place on the back of the last launch
+        o.copy_src = conv_out;
+        o.copy_dst = conv_final;
+        o.copy_bytes = (size_t)3 * d.conv_dim * 2;
+    }
     if (d.G == 1) {  // one group: the gated normalisation rides on the product
         o.mode = 2;
         o.x = ws + w.y;
@@ -479,7 +484,7 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
         const char* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
         char* out_seg = (char*)out + (size_t)t0 * d.dm * 2;
         if (few_path(d, p, rows, ssm_out, u_seg, out_seg) && (!conv_out || conv_out != conv_in)) {
-            BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, st));
+            BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, nullptr, st));
             continue;
         }
         BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st));
@@ -840,16 +845,19 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
             float* ssm_out = in_place ? sj : (float*)(ws + w.fin_ssm);
             char* y = ws + w.act[j & 1];
             char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
-            if (few_path(dc, &params[j], rows, ssm_out, cur, nxt)) {  // generation: the residual rides on the output product
+            bool conv_moved = false;
+            if (few_path(dc, &params[j], rows, ssm_out, cur, nxt)) {
+                // generation: the residual and the move of the convolution state ride on the output product
+                conv_moved = ((uintptr_t)cj & 15) == 0 && d.conv_state % 16 == 0 && d.conv_state / 16 <= (size_t)d.b.dm * 32;
                 BLK_TRY(forward_few(dc, &c, &params[j], bws, bw, cur, rows, zero ? nullptr : sj, zero ? nullptr : cj, ssm_out,
-                                    ws + w.fin_conv, nxt, cur, st));
+                                    ws + w.fin_conv, nxt, cur, conv_moved ? cj : nullptr, st));
             } else {
                 BLK_TRY(magc_block_fwd(&c, &params[j], cur, zero ? nullptr : sj, zero ? nullptr : cj, y, nullptr, nullptr, ssm_out,
                                        ws + w.fin_conv, ws + w.inner, w.inner_bytes, st));
                 BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
             }
             if (!in_place) BLK_HIP(launch_copy_f32(sj, ssm_out, d.b.HPN, st));
-            BLK_HIP(launch_copy_f32((float*)cj, (const float*)(ws + w.fin_conv), d.conv_state / 4, st));  // bf16 pairs as words
+            if (!conv_moved) BLK_HIP(launch_copy_f32((float*)cj, (const float*)(ws + w.fin_conv), d.conv_state / 4, st));  // bf16 pairs as words
             cur = nxt;
         }
     }

@@ -33,30 +33,27 @@ struct FewParams {
     float eps;
 };
 
-constexpr int CPW = 2;  // output columns per wave: the input rows are fetched (and transformed) once for both
-
 // out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]) for r < rows <= R.  A wave owns CPW columns n and walks k
 // with 16-byte loads, so every weight is read once, in full cache lines; the few input rows come from the
 // caches.  MODE 0: f(x) = x.  MODE 1: f(x) = x / sqrt(mean x^2 + eps) * in_w.  MODE 2: the same of g = x z sigmoid(z).
-// A wave sees whole rows, so the mean comes out of the same loop and scales the finished sums.
-template <int MODE, int R>
-__global__ __launch_bounds__(256) void k_linear_few(FewParams fp) {
-    const int lane = threadIdx.x & 63;
-    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * CPW;
-    if (n0 >= fp.N) return;  // whole waves leave; the kernel has no barrier
-    float acc[R][CPW], ss[R];
-#pragma unroll
-    for (int r = 0; r < R; ++r) {
-        ss[r] = 0.f;
-#pragma unroll
-        for (int c = 0; c < CPW; ++c) acc[r][c] = 0.f;
-    }
-    const __bf16* w0 = fp.w + (int64_t)n0 * fp.K;
-    for (int k = lane * 8; k < fp.K; k += 512) {
-        bf16x8 wv[CPW];
+// A wave sees whole rows, so the mean comes out of the same loop and scales the finished sums.  With few rows
+// the operands of two k steps are requested before either is used (twice the bytes in flight per wave).
+// The first workgroups also move `copy_n` 16-byte vectors from copy_src to copy_dst: a small state that the
+// kernel before this one still read in its old place.
+struct FewOperands {
+    const void* copy_src;
+    void* copy_dst;
+    int copy_n;
+};
+
+template <int MODE, int R, int CPW>
+struct FewStep {
+    bf16x8 wv[CPW], xv[R], zv[MODE == 2 ? R : 1];
+    float iw[MODE ? 8 : 1];
+
+    __device__ __forceinline__ void load(const FewParams& fp, const __bf16* w0, int k) {
 #pragma unroll
         for (int c = 0; c < CPW; ++c) wv[c] = *(const bf16x8*)(w0 + (int64_t)c * fp.K + k);
-        float iw[8];
         if (MODE) {
             const f32x4 a = *(const f32x4*)(fp.in_w + k), b = *(const f32x4*)(fp.in_w + k + 4);
 #pragma unroll
@@ -68,14 +65,21 @@ __global__ __launch_bounds__(256) void k_linear_few(FewParams fp) {
 #pragma unroll
         for (int r = 0; r < R; ++r) {
             if (r < fp.rows) {
-                const bf16x8 xv = *(const bf16x8*)(fp.x + r * fp.ldx + k);
-                bf16x8 zv;
-                if (MODE == 2) zv = *(const bf16x8*)(fp.z + r * fp.ldz + k);
+                xv[r] = *(const bf16x8*)(fp.x + r * fp.ldx + k);
+                if (MODE == 2) zv[r] = *(const bf16x8*)(fp.z + r * fp.ldz + k);
+            }
+        }
+    }
+
+    __device__ __forceinline__ void use(const FewParams& fp, float (&acc)[R][CPW], float (&ss)[R]) const {
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (r < fp.rows) {
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
-                    float v = (float)xv[e];
+                    float v = (float)xv[r][e];
                     if (MODE == 2) {
-                        const float zz = (float)zv[e];
+                        const float zz = (float)zv[r][e];
                         v *= zz * sigmoid_fast(zz);
                     }
                     if (MODE) {
@@ -87,6 +91,34 @@ __global__ __launch_bounds__(256) void k_linear_few(FewParams fp) {
                 }
             }
         }
+    }
+};
+
+template <int MODE, int R, int CPW>
+__global__ __launch_bounds__(256) void k_linear_few(FewParams fp, FewOperands fo) {
+    if (fo.copy_n) {
+        const int i = blockIdx.x * 256 + threadIdx.x;
+        if (i < fo.copy_n) ((f32x4*)fo.copy_dst)[i] = ((const f32x4*)fo.copy_src)[i];
+    }
+    const int lane = threadIdx.x & 63;
+    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * CPW;
+    if (n0 >= fp.N) return;  // whole waves leave; the kernel has no barrier
+    float acc[R][CPW], ss[R];
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
+        ss[r] = 0.f;
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) acc[r][c] = 0.f;
+    }
+    const __bf16* w0 = fp.w + (int64_t)n0 * fp.K;
+    constexpr bool TWO = R <= 4;
+    for (int k = lane * 8; k < fp.K; k += TWO ? 1024 : 512) {
+        FewStep<MODE, R, CPW> a, b;
+        const bool two = TWO && k + 512 < fp.K;
+        a.load(fp, w0, k);
+        if (two) b.load(fp, w0, k + 512);
+        a.use(fp, acc, ss);
+        if (two) b.use(fp, acc, ss);
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -104,15 +136,24 @@ __global__ __launch_bounds__(256) void k_linear_few(FewParams fp) {
     }
 }
 
-template <int MODE>
-hipError_t launch_few(const FewParams& fp, hipStream_t st) {
-    const dim3 grid((unsigned)((fp.N / CPW + 3) / 4)), block(256);
-    if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1>), grid, block, 0, st, fp);
-    else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2>), grid, block, 0, st, fp);
-    else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4>), grid, block, 0, st, fp);
-    else if (fp.rows <= 8) hipLaunchKernelGGL((k_linear_few<MODE, 8>), grid, block, 0, st, fp);
-    else hipLaunchKernelGGL((k_linear_few<MODE, 16>), grid, block, 0, st, fp);
+template <int MODE, int CPW>
+hipError_t launch_few_c(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
+    const int waves = (fp.N + CPW - 1) / CPW;
+    const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+    if ((int64_t)grid.x * 256 < fo.copy_n) return hipErrorInvalidValue;
+    if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1, CPW>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2, CPW>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4, CPW>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 8) hipLaunchKernelGGL((k_linear_few<MODE, 8, CPW>), grid, block, 0, st, fp, fo);
+    else hipLaunchKernelGGL((k_linear_few<MODE, 16, CPW>), grid, block, 0, st, fp, fo);
     return hipGetLastError();
+}
+
+// two columns per wave share the fetched (and transformed) input rows; narrow products take one column per
+// wave instead so that there are enough waves to keep the memory system busy
+template <int MODE>
+hipError_t launch_few(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
+    return fp.N >= 8192 ? launch_few_c<MODE, 2>(fp, fo, st) : launch_few_c<MODE, 1>(fp, fo, st);
 }
 
 struct MidParams {
@@ -140,40 +181,59 @@ __device__ __forceinline__ float conv_output(const MidParams& mp, int t, int c) 
     return through_bf16(pre * sigmoid_fast(pre));
 }
 
-// Workgroup (head h, z): wave w owns the state rows p = 4 z + w, + 4 gridDim.z, ...; lane l the columns
-// n = l, l + 64, ...  Per token the workgroup convolves the B and C channels of its group into LDS (every
-// workgroup of the group does: a few hundred channels against a state of P N elements), each wave the x
-// channel of its row; a lane only ever touches its own state elements.
+// Workgroup (head h, z): wave w owns the state row p = 4 z + w, lane l its columns n = l, l + 64, ..., which
+// stay in registers over the tokens of the call (requested first: nothing below waits for them until the first
+// update).  Per token the workgroup convolves the B and C channels of its group into LDS (every workgroup of
+// the group does: a few hundred channels against a state of P N elements), each wave the x channel of its row.
+constexpr int MID_NPL = 8;  // state columns per lane at most (N <= 512)
+
 __global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
     extern __shared__ float bc[];  // B[0..N), C[0..N) of the group, this token
     const int h = blockIdx.x, g = h / mp.hpg;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const int p = 4 * blockIdx.z + w;
+    const bool own = p < mp.P;
+    float* S = mp.state + ((int64_t)h * mp.P + (own ? p : 0)) * mp.N;
+    float s[MID_NPL];
+#pragma unroll
+    for (int i = 0; i < MID_NPL; ++i) {
+        const int n = lane + 64 * i;
+        s[i] = own && n < mp.N ? S[n] : 0.f;
+    }
     const float Ah = mp.A[h], Dh = mp.D[h], bias_h = mp.dt_bias[h];
-    float* S = mp.state + (int64_t)h * mp.P * mp.N;
     const int cB = mp.d_inner + g * mp.N, cC = mp.d_inner + (mp.G + g) * mp.N;
     for (int t = 0; t < mp.T; ++t) {
         for (int i = threadIdx.x; i < 2 * mp.N; i += 256) bc[i] = conv_output(mp, t, i < mp.N ? cB + i : cC + (i - mp.N));
         const float v = (float)mp.zx[t * mp.ld + mp.off_dt + h] + bias_h;
         const float dtv = through_bf16(fmaxf(v, 0.f) + log1pf(__expf(-fabsf(v))));  // softplus
         const float a = __expf(dtv * Ah);
+        const float xv = own ? conv_output(mp, t, h * mp.P + p) : 0.f;
         __syncthreads();
-        for (int p = 4 * blockIdx.z + w; p < mp.P; p += 4 * gridDim.z) {
-            const float xv = conv_output(mp, t, h * mp.P + p);
+        if (own) {
             const float dx = dtv * xv;
             float acc = 0.f;
-            for (int n = lane; n < mp.N; n += 64) {
-                const float hn = a * S[(int64_t)p * mp.N + n] + dx * bc[n];
-                S[(int64_t)p * mp.N + n] = hn;
-                acc += bc[mp.N + n] * hn;
+#pragma unroll
+            for (int i = 0; i < MID_NPL; ++i) {
+                const int n = lane + 64 * i;
+                if (n < mp.N) {
+                    s[i] = a * s[i] + dx * bc[n];
+                    acc += bc[mp.N + n] * s[i];
+                }
             }
             acc = wave_sum(acc);
             if (lane == 0) mp.y[(int64_t)t * mp.d_inner + h * mp.P + p] = (__bf16)(acc + Dh * xv);
         }
         __syncthreads();  // the next token's B and C replace these
     }
+    if (own) {
+#pragma unroll
+        for (int i = 0; i < MID_NPL; ++i) {
+            const int n = lane + 64 * i;
+            if (n < mp.N) S[n] = s[i];
+        }
+    }
     if (mp.cs_out) {  // the last three inputs of [entering state ; this call's tokens]
-        for (int p = 4 * blockIdx.z + w; p < mp.P; p += 4 * gridDim.z)
-            if (lane < 3) mp.cs_out[lane * mp.conv_dim + h * mp.P + p] = (__bf16)conv_input(mp, mp.T - 3 + lane, h * mp.P + p);
+        if (own && lane < 3) mp.cs_out[lane * mp.conv_dim + h * mp.P + p] = (__bf16)conv_input(mp, mp.T - 3 + lane, h * mp.P + p);
         if (h % mp.hpg == 0 && blockIdx.z == 0)  // the group's B and C channels: once
             for (int i = threadIdx.x; i < 6 * mp.N; i += 256) {
                 const int j = i / (2 * mp.N), ii = i % (2 * mp.N);
@@ -194,6 +254,9 @@ bool few_rows_supported(const FewRowsJob& j) {
     if (j.mode && (!j.in_w || !al16(j.in_w))) return false;
     if (j.mode == 2 && (!j.z || !al16(j.z) || (j.ldz & 7) || j.ldz < j.K)) return false;
     if (j.res && j.ldres < j.N) return false;
+    if (j.copy_bytes && (!j.copy_src || !j.copy_dst || !al16(j.copy_src) || !al16(j.copy_dst) || (j.copy_bytes & 15) ||
+                         j.copy_bytes / 16 > (size_t)j.N / 2 * 64))  // one vector per thread of the launch
+        return false;
     return true;
 }
 
@@ -214,14 +277,18 @@ hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st) {
     fp.K = j.K;
     fp.N = j.N;
     fp.eps = j.eps;
-    return j.mode == 0 ? launch_few<0>(fp, st) : j.mode == 1 ? launch_few<1>(fp, st) : launch_few<2>(fp, st);
+    FewOperands fo;
+    fo.copy_src = j.copy_src;
+    fo.copy_dst = j.copy_dst;
+    fo.copy_n = (int)(j.copy_bytes / 16);
+    return j.mode == 0 ? launch_few<0>(fp, fo, st) : j.mode == 1 ? launch_few<1>(fp, fo, st) : launch_few<2>(fp, fo, st);
 }
 
 hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
     if (j.T < 1 || j.T > FEW_ROWS || j.H <= 0 || j.H > 65535 || j.P <= 0 || j.G <= 0 || j.N <= 0 || j.H % j.G) return hipErrorInvalidValue;
     if (!j.zx || !j.conv_w || !j.conv_b || !j.dt_bias || !j.A || !j.D || !j.state || !j.y || (j.cs_out && j.cs_out == j.cs_in))
         return hipErrorInvalidValue;
-    if ((size_t)2 * j.N * sizeof(float) > 48 * 1024) return hipErrorInvalidValue;
+    if (j.N > 64 * MID_NPL || j.P > 256) return hipErrorInvalidValue;  // a state row in a wave's registers, a row per wave
     MidParams mp;
     mp.zx = (const __bf16*)j.zx;
     mp.ld = j.ld;
@@ -244,8 +311,7 @@ hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
     mp.conv_dim = mp.d_inner + 2 * j.G * j.N;
     mp.off_xbc = mp.d_inner;
     mp.off_dt = mp.d_inner + mp.conv_dim;
-    const int rows4 = (j.P + 3) / 4;
-    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, 1, rows4 < 64 ? rows4 : 64), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
+    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, 1, (j.P + 3) / 4), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
     return hipGetLastError();
 }
 

@@ -217,6 +217,10 @@ struct FewRowsJob {
     float eps;
     const void* res;
     int64_t ldres;
+    // optional: copy_bytes (a multiple of 16, at most 32 N) bytes moved from copy_src to copy_dst by the same launch
+    const void* copy_src;
+    void* copy_dst;
+    size_t copy_bytes;
 };
 bool few_rows_supported(const FewRowsJob& j);  // sizes, strides and 16-byte alignment the kernel relies on
 hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st);
