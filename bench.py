@@ -522,6 +522,8 @@ def main():
     ap.add_argument("--layer-interval", type=int, default=4, help="with --block --layers: layer inputs kept every this many layers")
     ap.add_argument("--calibrate-mfma", action="store_true",
                     help="run a register-only MFMA loop over the whole chip and print the rate it sustains")
+    ap.add_argument("--calibrate-clock", action="store_true",
+                    help="measure the shader clock while the projection GEMM, a register-only MFMA loop, a device copy and the scan run")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run only a device-to-device copy of 1 GiB, five times (reference for the HBM byte counters)")
     args = ap.parse_args()
@@ -554,6 +556,46 @@ def main():
         sys.exit(2)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.calibrate_clock:
+        # the shader clock while a kernel runs: a one-wave probe on a second stream counts shader cycles against
+        # the constant 100 MHz counter for 30 ms while the work fills the first stream
+        L = pk.lib()
+        L.ssd_prof_clock_probe.argtypes = [ctypes.c_uint64, ctypes.c_void_p, ctypes.c_void_p]
+        L.ssd_prof_mfma_peak.argtypes = [ctypes.c_int32, ctypes.c_int32, ctypes.c_void_p, ctypes.c_void_p]
+        s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+        out = torch.zeros(2, dtype=torch.int64, device=dev)
+        T, I, O = 65536, 2560, 10576
+        x = torch.randn(T, I, device=dev).to(torch.bfloat16)
+        w = (torch.randn(O, I, device=dev) / 50).to(torch.bfloat16)
+        y = torch.empty(T, O, dtype=torch.bfloat16, device=dev)
+        sink = torch.zeros(1, device=dev)
+        z = torch.empty(1 << 28, dtype=torch.float32, device=dev)
+        z2 = torch.empty_like(z)
+        d = synth.make_layer_inputs_device(cfg, dev)
+
+        def scan_step():
+            _, _, bs = pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, cfg.segment)
+            pk.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], cfg.chunk, cfg.segment, boundary_states=bs)
+        res = {}
+        for label, work in (("idle", lambda: None),
+                            ("input_projection_x12", lambda: [pk.ssd_linear_fwd(x, w, y) for _ in range(12)]),
+                            ("mfma_on_registers", lambda: L.ssd_prof_mfma_peak(30000, 1024, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)),
+                            ("device_copy_1GiB_x40", lambda: [z2.copy_(z) for _ in range(40)]),
+                            ("ssd_fwd_bwd_x8", lambda: [scan_step() for _ in range(8)])):
+            with torch.cuda.stream(s1):
+                work()   # warm
+            torch.cuda.synchronize()
+            assert L.ssd_prof_clock_probe(3000000, out.data_ptr(), s2.cuda_stream) == 0
+            t0 = time.perf_counter()
+            with torch.cuda.stream(s1):
+                work()
+            s1.synchronize()
+            ms = (time.perf_counter() - t0) * 1e3
+            torch.cuda.synchronize()
+            wt, cy = out.tolist()
+            res[label] = {"work_ms": ms, "probe_ms": wt / 1e5, "shader_clock_GHz": cy / (wt / 100.0) / 1e3}
+        print(json.dumps({"calibration": "shader clock beside the work (30 ms probe)", **res}))
+        return
     if args.calibrate_mfma:
         # sustained rate of the matrix cores on registers only: 1024 workgroups (four per compute unit in turn)
         sink = torch.zeros(1, device=dev)

@@ -462,6 +462,11 @@ const char* ssd_prof_kernel_name(int32_t kernel_id);
  * independent 32 x 32 x 16 bf16 MFMAs on registers (no memory traffic): 16 * 32768 flop per wave and round.
  * `sink` is one float of device memory (never written).  The caller times the launch. */
 int ssd_prof_mfma_peak(int32_t iters, int32_t workgroups, float* sink, void* hip_stream);
+/* Clock probe: a single wave that waits until the constant 100 MHz counter has advanced by `ticks` (at most 1e8:
+ * one second) and then writes out[0] = ticks elapsed, out[1] = shader-clock cycles elapsed (device memory, two
+ * 64-bit words).  Launched on a second stream of default priority beside the work under test it measures the
+ * clock that work runs at: out[1] / out[0] * 100 MHz. */
+int ssd_prof_clock_probe(uint64_t ticks, uint64_t* out, void* hip_stream);
 
 /* Static, human-readable text for a status code (host pointer, never NULL). */
 const char* ssd_strerror(int status);

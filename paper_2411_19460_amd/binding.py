@@ -22,7 +22,7 @@ EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_b
            "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
            "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_blockstack_infer",
            "magc_stack_workspace_bytes", "magc_stack_fwd",
-           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize", "ssd_prof_mfma_peak")
+           "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize", "ssd_prof_mfma_peak", "ssd_prof_clock_probe")
 
 
 class ssd_shape_t(ctypes.Structure):

@@ -569,3 +569,31 @@ extern "C" int ssd_prof_mfma_peak(int32_t iters, int32_t workgroups, float* sink
     hipLaunchKernelGGL(k_mfma_peak, dim3(workgroups), dim3(256), 0, (hipStream_t)hip_stream, iters, sink);
     return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
 }
+
+// Clock probe: one wave that sleeps until the constant 100 MHz counter has advanced by `ticks` and reports how
+// many shader-clock cycles went by meanwhile.  Launched on a second stream next to a kernel under test it
+// shows the clock that kernel really runs at (the power management lowers it under heavy load), which is what
+// a cycle count or a fraction of the nominal peak has to be read against.
+namespace ssdk {
+namespace {
+__global__ __launch_bounds__(64) void k_clock_probe(unsigned long long* out, unsigned long long ticks) {
+    const unsigned long long w0 = wall_clock64(), c0 = clock64();
+    unsigned long long w = w0;
+    // an iteration takes about a microsecond (100 ticks): the time limit ends the loop long before the count does
+    for (unsigned long long i = 0; i < ticks && w - w0 < ticks; ++i) {
+        __builtin_amdgcn_s_sleep(32);
+        w = wall_clock64();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = w - w0;
+        out[1] = clock64() - c0;
+    }
+}
+}  // namespace
+}  // namespace ssdk
+
+extern "C" int ssd_prof_clock_probe(uint64_t ticks, uint64_t* out, void* hip_stream) {
+    if (!out || ticks == 0 || ticks > 100000000ull) return SSD_ERR_ARG;  // at most a second
+    hipLaunchKernelGGL(k_clock_probe, dim3(1), dim3(64), 0, (hipStream_t)hip_stream, (unsigned long long*)out, (unsigned long long)ticks);
+    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+}
