@@ -8,8 +8,9 @@
 // right to left, redoes a segment's forward from its two states (Recompute_Forward of Alg. 2) into the
 // workspace -- zxbcdt and y are the per-token activations C_grid counts -- and then runs the reverse of
 // every step, handing the two state adjoints to the segment on the left.
-// Everything is a sequence of calls to the library's own entry points plus three small kernels (column
-// slices in and out of the (x | B | C) layout, and softplus of dt); all on the caller's stream.
+// Everything is a sequence of calls to the library's own entry points plus small kernels for softplus of dt
+// (the convolution writes x, B and C as the three dense tensors the scan reads, and reads their gradients
+// the same way); all on the caller's stream.
 #include <string.h>
 
 #include "ssd_internal.h"
@@ -18,25 +19,6 @@ namespace ssdk {
 namespace {
 
 typedef __bf16 b8 __attribute__((ext_vector_type(8)));
-
-// dst[r, 0..cols) = src[r, 0..cols) for r < rows; 16-byte vectors (cols, strides: multiples of 8 elements)
-__global__ __launch_bounds__(256) void k_copy_cols(bf16_t* dst, int64_t dst_rs, const bf16_t* src, int64_t src_rs, int64_t rows, int cols8) {
-    const int64_t n = rows * cols8;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) {
-        const int64_t r = i / cols8;
-        const int c = (int)(i - r * cols8) * 8;
-        *(b8*)((__bf16*)dst + r * dst_rs + c) = *(const b8*)((const __bf16*)src + r * src_rs + c);
-    }
-}
-
-hipError_t copy_cols(void* dst, int64_t dst_rs, const void* src, int64_t src_rs, int64_t rows, int cols, hipStream_t st) {
-    if (rows == 0 || cols == 0) return hipSuccess;
-    const int64_t n = rows * (cols / 8);
-    const int64_t blocks = (n + 255) / 256;
-    hipLaunchKernelGGL(k_copy_cols, dim3((unsigned)(blocks < 8192 ? blocks : 8192)), dim3(256), 0, st, (bf16_t*)dst, dst_rs,
-                       (const bf16_t*)src, src_rs, rows, cols / 8);
-    return hipGetLastError();
-}
 
 constexpr int DECODE_ROWS = 16;  // calls of at most this many tokens run the scan as the plain recurrence
 constexpr int DT_ROWS = 16;  // rows per workgroup of the dt kernels (granularity of the ddt_bias partial sums)
@@ -180,8 +162,8 @@ size_t al(size_t n) { return (n + 255) & ~(size_t)255; }
 
 // Workspace: one segment's activations (and, backward, their gradients), the scratch of the inner calls.
 struct BlockWs {
-    size_t un, zx, xbc, x, B, C, dt, y, yn;                 // forward activations of the segment
-    size_t dun, dyn, dy, dzx, dxbc, dx, dB, dC, ddt;        // backward
+    size_t un, zx, x, B, C, dt, y, yn;                      // forward activations of the segment
+    size_t dun, dyn, dy, dzx, dx, dB, dC, ddt;              // backward
     size_t dssm[2], dconv[2], dtpart, inner, total;
     size_t cssm[2], cconv[2];                               // states handed from segment to segment when no checkpoints are kept
     size_t inner_bytes;
@@ -199,7 +181,6 @@ BlockWs layout(const BlockDims& d, bool bwd) {
     const size_t s = (size_t)d.s;
     w.un = take(s * d.dm * 2);
     w.zx = take(s * d.d_in_proj * 2);
-    w.xbc = take(s * d.conv_dim * 2);
     w.x = take(s * d.d_inner * 2);
     w.B = take(s * d.gn * 2);
     w.C = take(s * d.gn * 2);
@@ -220,7 +201,6 @@ BlockWs layout(const BlockDims& d, bool bwd) {
         w.dyn = take(s * d.d_inner * 2);
         w.dy = take(s * d.d_inner * 2);
         w.dzx = take(s * d.d_in_proj * 2);
-        w.dxbc = take(s * d.conv_dim * 2);
         w.dx = take(s * d.d_inner * 2);
         w.dB = take(s * d.gn * 2);
         w.dC = take(s * d.gn * 2);
@@ -274,14 +254,12 @@ int seg_in_proj(const BlockDims& d, float eps, const magc_block_params_t* p, cha
     return ssd_linear_fwd(rows, d.dm, d.d_in_proj, in, 0, p->W_in, zx, 0, st);
 }
 
-// convolution + SiLU of the xBC columns, split into dense x / B / C, softplus of the dt columns
+// convolution + SiLU of the xBC columns into dense x / B / C, softplus of the dt columns
 int seg_mid(const BlockDims& d, const magc_block_params_t* p, char* ws, const BlockWs& w, const char* zx, int64_t rows,
             const void* conv_in, void* conv_out, hipStream_t st) {
     const ssd_conv_shape_t cs = conv_shape(d, rows);
-    BLK_TRY(ssd_conv1d_fwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.xbc, conv_out, st));
-    BLK_HIP(copy_cols(ws + w.x, d.d_inner, ws + w.xbc, d.conv_dim, rows, d.d_inner, st));
-    BLK_HIP(copy_cols(ws + w.B, d.gn, ws + w.xbc + (size_t)d.d_inner * 2, d.conv_dim, rows, d.gn, st));
-    BLK_HIP(copy_cols(ws + w.C, d.gn, ws + w.xbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, rows, d.gn, st));
+    const ConvSplit xbc = {{ws + w.x, ws + w.B, ws + w.C}, d.d_inner, d.d_inner + d.gn};  // each part dense, as the scan reads it
+    BLK_TRY(conv1d_fwd_split(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, xbc, conv_out, st));
     hipLaunchKernelGGL(k_dt_fwd, dim3((unsigned)((rows + DT_ROWS - 1) / DT_ROWS)), dim3(256), 0, st,
                        (const bf16_t*)(zx + (size_t)d.off_dt * 2), (int64_t)d.d_in_proj, p->dt_bias, (bf16_t*)(ws + w.dt), rows, d.H);
     BLK_HIP(hipGetLastError());
@@ -421,13 +399,11 @@ int backward_segment(const BlockDims& d, const magc_block_shape_t* sh, const mag
     BLK_HIP(hipGetLastError());
     hipLaunchKernelGGL(k_colsum, dim3((d.H + 63) / 64), dim3(256), 0, st, (const float*)(ws + w.dtpart), (int64_t)ntile, d.H, g->ddt_bias, 1);
     BLK_HIP(hipGetLastError());
-    // convolution: (dx | dB | dC) side by side, du into the xBC columns of d zxbcdt
-    BLK_HIP(copy_cols(ws + w.dxbc, d.conv_dim, ws + w.dx, d.d_inner, rows, d.d_inner, st));
-    BLK_HIP(copy_cols(ws + w.dxbc + (size_t)d.d_inner * 2, d.conv_dim, ws + w.dB, d.gn, rows, d.gn, st));
-    BLK_HIP(copy_cols(ws + w.dxbc + (size_t)(d.d_inner + d.gn) * 2, d.conv_dim, ws + w.dC, d.gn, rows, d.gn, st));
+    // convolution: reads dx, dB, dC where the scan left them, du into the xBC columns of d zxbcdt
     const ssd_conv_shape_t cs = conv_shape(d, rows);
-    BLK_TRY(ssd_conv1d_bwd(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, ws + w.dxbc, dconv_out,
-                           dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
+    const ConvSplit dxbc = {{ws + w.dx, ws + w.dB, ws + w.dC}, d.d_inner, d.d_inner + d.gn};
+    BLK_TRY(conv1d_bwd_split(&cs, zx + (size_t)d.off_xbc * 2, p->conv_w, p->conv_b, conv_in, dxbc, dconv_out,
+                             dzx + (size_t)d.off_xbc * 2, g->dconv_w, g->dconv_b, dconv_in, ws + w.inner, w.inner_bytes, acc, st));
     // input projection, and the normalisation in front of it (its output is cheap to redo and other layers of
     // a grid cell may have used the buffer since this layer's forward steps)
     if (!p->pre_norm_w) return ssd_linear_bwd(rows, d.dm, d.d_in_proj, u_seg, 0, p->W_in, dzx, 0, du_seg, 0, g->dW_in, acc, st);

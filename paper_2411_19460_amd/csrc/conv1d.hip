@@ -34,7 +34,39 @@ struct ConvParams {
     int64_t u_rs;           // elements between consecutive tokens of u / du (out / dout: C)
     int C, ntiles;
     int tt;             // tokens per thread of this launch
+    // out / dout as three dense tensors side by side instead of one: channels [cb[k], cb[k+1]) live in
+    // part[k] with rows cb[k+1] - cb[k] apart (the block's x | B | C, each the shape the scan wants)
+    int split;
+    int cb[4];
+    void* out3[3];
+    const void* dout3[3];
 };
+
+// Where this thread's channels c0.. of out / dout live: base pointer, batch and row stride, first column.
+struct OutSlot {
+    void* out;
+    const void* dout;
+    int64_t bs, rs;
+    int c;
+};
+__device__ __forceinline__ OutSlot out_slot(const ConvParams& cp, int c0) {
+    OutSlot o;
+    if (!cp.split) {
+        o.out = cp.out;
+        o.dout = cp.dout;
+        o.bs = cp.o_bs;
+        o.rs = cp.C;
+        o.c = c0;
+    } else {
+        const int k = c0 >= cp.cb[2] ? 2 : c0 >= cp.cb[1] ? 1 : 0;
+        o.out = cp.out3[k];
+        o.dout = cp.dout3[k];
+        o.rs = cp.cb[k + 1] - cp.cb[k];
+        o.bs = cp.L * o.rs;
+        o.c = c0 - cp.cb[k];
+    }
+    return o;
+}
 
 template <typename T, int V>
 struct Vec;
@@ -102,6 +134,7 @@ __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
     const int c0 = (blockIdx.x * 64 + threadIdx.x) * V;
     if (c0 >= cp.C) return;
     const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * cp.tt;
+    const OutSlot os = out_slot(cp, c0);
     float w[V][CONV_K], bias[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
@@ -131,7 +164,7 @@ __global__ __launch_bounds__(64) void k_conv_fwd(ConvParams cp) {
                 win[1][e] = win[2][e];
                 win[2][e] = cur[j][e];
             }
-            Vec<T, V>::st(cp.out, b * cp.o_bs + (t + j) * cp.C + c0, o);
+            Vec<T, V>::st(os.out, b * os.bs + (t + j) * os.rs + os.c, o);
         }
     }
     // the state leaving the segment: the last three rows of [state_in ; u]
@@ -149,6 +182,7 @@ __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
     const int c0 = (blockIdx.x * 64 + threadIdx.x) * V;
     if (c0 >= cp.C) return;
     const int64_t b = blockIdx.z, t0 = (int64_t)blockIdx.y * cp.tt;
+    const OutSlot os = out_slot(cp, c0);
     float w[V][CONV_K], bias[V];
 #pragma unroll
     for (int e = 0; e < V; ++e) {
@@ -235,7 +269,7 @@ __global__ __launch_bounds__(64) void k_conv_bwd(ConvParams cp) {
         float cur[V], dv[V];
         if (t < cp.L) {
             Vec<T, V>::ld(cp.u, b * cp.u_bs + t * cp.u_rs + c0, cur);
-            Vec<T, V>::ld(cp.dout, b * cp.o_bs + t * cp.C + c0, dv);
+            Vec<T, V>::ld(os.dout, b * os.bs + t * os.rs + os.c, dv);
         } else {
 #pragma unroll
             for (int e = 0; e < V; ++e) cur[e] = dv[e] = 0.f;
@@ -319,12 +353,39 @@ extern "C" size_t ssd_conv1d_workspace_bytes(const ssd_conv_shape_t* sh) {
     return (n + 255) & ~(size_t)255;
 }
 
-extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias,
-                              const void* state_in, void* out, void* state_out, void* hip_stream) {
+namespace ssdk {
+namespace {
+
+// split: the three-part form of out / dout; every boundary a multiple of the vector width or the kernels fall
+// back to one channel per thread
+bool bind_split(ConvParams& cp, const ConvSplit* sp, bool bwd) {
+    if (!sp) return true;
+    if (sp->c1 <= 0 || sp->c2 <= sp->c1 || sp->c2 >= cp.C) return false;
+    cp.split = 1;
+    cp.cb[0] = 0;
+    cp.cb[1] = sp->c1;
+    cp.cb[2] = sp->c2;
+    cp.cb[3] = cp.C;
+    for (int k = 0; k < 3; ++k) {
+        if (cp.L > 0 && !sp->p[k]) return false;
+        if (bwd) cp.dout3[k] = sp->p[k];
+        else cp.out3[k] = sp->p[k];
+    }
+    return true;
+}
+
+int vec_width(const ConvParams& cp, bool bf) {
+    int all = cp.C | (int)cp.u_rs;
+    if (cp.split) all |= cp.cb[1] | cp.cb[2];
+    return bf ? (all % 8 == 0 ? 8 : 1) : (all % 4 == 0 ? 4 : 1);
+}
+
+int conv_fwd_impl(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in, void* out,
+                  const ConvSplit* split, void* state_out, void* hip_stream) {
     int rc = check(sh);
     if (rc != SSD_OK) return rc;
     if (!w) return SSD_ERR_NULL;
-    if (sh->seqlen > 0 && (!u || !out)) return SSD_ERR_NULL;
+    if (sh->seqlen > 0 && (!u || (!out && !split))) return SSD_ERR_NULL;
     ConvParams cp;
     memset(&cp, 0, sizeof(cp));
     cp.u = u;
@@ -338,9 +399,10 @@ extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const f
     cp.u_rs = sh->u_row_stride ? sh->u_row_stride : sh->channels;
     cp.u_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * cp.u_rs;
     cp.o_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
+    if (!bind_split(cp, split, false)) return SSD_ERR_ARG;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = sh->dtype == SSD_BF16;
-    const int V = bf ? ((cp.C | cp.u_rs) % 8 == 0 ? 8 : 1) : ((cp.C | cp.u_rs) % 4 == 0 ? 4 : 1);
+    const int V = vec_width(cp, bf);
     // an empty sequence still hands the state on: one tile, whose token loop is empty
     cp.tt = pick_tt(sh, FWD_TT);
     const dim3 grid((cp.C / V + 63) / 64, (unsigned)(cp.L > 0 ? (cp.L + cp.tt - 1) / cp.tt : 1), (unsigned)sh->batch);
@@ -351,15 +413,14 @@ extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const f
     return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
 }
 
-extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias,
-                              const void* state_in, const void* dout, const float* dstate_out, void* du, float* dw,
-                              float* dbias, float* dstate_in, void* workspace, size_t workspace_bytes, uint32_t flags,
-                              void* hip_stream) {
+int conv_bwd_impl(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in, const void* dout,
+                  const ConvSplit* split, const float* dstate_out, void* du, float* dw, float* dbias, float* dstate_in, void* workspace,
+                  size_t workspace_bytes, uint32_t flags, void* hip_stream) {
     int rc = check(sh);
     if (rc != SSD_OK) return rc;
     if (flags & ~(uint32_t)SSD_FLAG_ACCUM_PARAM) return SSD_ERR_ARG;
     if (!w || !dw) return SSD_ERR_NULL;
-    if (sh->seqlen > 0 && (!u || !dout || !du)) return SSD_ERR_NULL;
+    if (sh->seqlen > 0 && (!u || (!dout && !split) || !du)) return SSD_ERR_NULL;
     if (sh->seqlen > 0 && du == dout) return SSD_ERR_ARG;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < ssd_conv1d_workspace_bytes(sh)) return SSD_ERR_WORKSPACE;
     ConvParams cp;
@@ -380,9 +441,10 @@ extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const f
     cp.o_bs = sh->batch_stride ? sh->batch_stride : sh->seqlen * sh->channels;
     cp.tt = pick_tt(sh, BWD_TT);
     cp.ntiles = ntiles_bwd(sh) > 0 ? ntiles_bwd(sh) : 1;
+    if (!bind_split(cp, split, true)) return SSD_ERR_ARG;
     hipStream_t st = (hipStream_t)hip_stream;
     const bool bf = sh->dtype == SSD_BF16;
-    const int V = bf ? ((cp.C | cp.u_rs) % 8 == 0 ? 8 : 1) : ((cp.C | cp.u_rs) % 4 == 0 ? 4 : 1);
+    const int V = vec_width(cp, bf);
     const dim3 grid((cp.C / V + 63) / 64, (unsigned)cp.ntiles, (unsigned)sh->batch);
     if (bf && V == 8) hipLaunchKernelGGL((k_conv_bwd<bf16_t, 8>), grid, dim3(64), 0, st, cp);
     else if (bf) hipLaunchKernelGGL((k_conv_bwd<bf16_t, 1>), grid, dim3(64), 0, st, cp);
@@ -392,4 +454,33 @@ extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const f
     hipLaunchKernelGGL(k_conv_reduce, dim3((5 * cp.C + 63) / 64), dim3(256), 0, st, cp.part, (int64_t)sh->batch * cp.ntiles,
                        cp.C, dw, dbias, (flags & SSD_FLAG_ACCUM_PARAM) ? 1 : 0);
     return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+}
+
+}  // namespace
+
+int conv1d_fwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in,
+                     const ConvSplit& out, void* state_out, hipStream_t st) {
+    return conv_fwd_impl(sh, u, w, bias, state_in, nullptr, &out, state_out, st);
+}
+
+int conv1d_bwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in,
+                     const ConvSplit& dout, const float* dstate_out, void* du, float* dw, float* dbias, float* dstate_in,
+                     void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t st) {
+    return conv_bwd_impl(sh, u, w, bias, state_in, nullptr, &dout, dstate_out, du, dw, dbias, dstate_in, workspace, workspace_bytes,
+                         flags, st);
+}
+
+}  // namespace ssdk
+
+extern "C" int ssd_conv1d_fwd(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias,
+                              const void* state_in, void* out, void* state_out, void* hip_stream) {
+    return conv_fwd_impl(sh, u, w, bias, state_in, out, nullptr, state_out, hip_stream);
+}
+
+extern "C" int ssd_conv1d_bwd(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias,
+                              const void* state_in, const void* dout, const float* dstate_out, void* du, float* dw,
+                              float* dbias, float* dstate_in, void* workspace, size_t workspace_bytes, uint32_t flags,
+                              void* hip_stream) {
+    return conv_bwd_impl(sh, u, w, bias, state_in, dout, nullptr, dstate_out, du, dw, dbias, dstate_in, workspace, workspace_bytes,
+                         flags, hip_stream);
 }

@@ -200,6 +200,20 @@ hipError_t mfma_launch_grad_bc(const SegParams& sp, bool with_dual, hipStream_t 
 // Smallest divisor ns of heads_per_group with base * ns >= target workgroups (else heads_per_group).
 int pick_split(int heads_per_group, int64_t base, int target);
 
+// The block's convolution with its output (forward) or the gradient of its output (backward) given as three
+// dense tensors side by side -- channels [0, c1), [c1, c2), [c2, C) with rows c1, c2 - c1, C - c2 apart: the
+// x | B | C operands of the scan and their gradients -- instead of one [L, C] tensor.  Otherwise as
+// ssd_conv1d_fwd / ssd_conv1d_bwd.
+struct ConvSplit {
+    void* p[3];
+    int c1, c2;
+};
+int conv1d_fwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in,
+                     const ConvSplit& out, void* state_out, hipStream_t st);
+int conv1d_bwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, const float* bias, const void* state_in,
+                     const ConvSplit& dout, const float* dstate_out, void* du, float* dw, float* dbias, float* dstate_in,
+                     void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t st);
+
 // Generation (few_rows.hip): products and the block's middle steps for at most FEW_ROWS tokens, bf16 storage.
 constexpr int FEW_ROWS = 16;
 // out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]); w [N, K] dense.  mode 0: f = identity; 1: RMS normalisation
