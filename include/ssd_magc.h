@@ -226,7 +226,12 @@ int ssd_gated_norm_bwd(const ssd_norm_shape_t* shape, const void* y, const void*
  *   dx or dw may be NULL (that product is skipped; w resp. x may then be NULL too).
  * in_dim, out_dim and the strides must be multiples of 8, all pointers 16-byte aligned (SSD_ERR_ARG);
  * rows is arbitrary (rows == 0: dw is zeroed or left).  No workspace.  Tokens are independent: a segment
- * is a row range.  Errors: SSD_ERR_NULL, SSD_ERR_SHAPE, SSD_ERR_DIVISIBILITY, SSD_ERR_ARG, SSD_ERR_LAUNCH.
+ * is a row range.  Up to 16 rows ssd_linear_fwd runs as a product that streams w once (generation).
+ * When ssd_linear_bwd computes both gradients, dw runs on a library-owned stream of default priority
+ * beside dx, forked from and joined into hip_stream with events like the segments of ssd_fwd (one per
+ * device: calls on one device must not overlap in time; SSD_MAGC_SERIAL=1 keeps both on hip_stream);
+ * dx and dw must not overlap x, w or dout.
+ * Errors: SSD_ERR_NULL, SSD_ERR_SHAPE, SSD_ERR_DIVISIBILITY, SSD_ERR_ARG, SSD_ERR_LAUNCH.
  */
 int ssd_linear_fwd(int64_t rows, int32_t in_dim, int32_t out_dim, const void* x, int64_t x_row_stride,
                    const void* w, void* out, int64_t out_row_stride, void* hip_stream);

@@ -269,12 +269,16 @@ static size_t shared_bytes(const Dims& d) { return 2 * align_up((size_t)d.Bt * d
 // timings are only meaningful when kernels do not overlap).
 static bool g_serial = false;  // ssd_prof_serialize
 
-static int lanes(const Dims& d, bool mfma) {
+bool serial_mode() {
     static const bool serial = [] {
         const char* v = getenv("SSD_MAGC_SERIAL");
         return v && v[0] == '1';
     }();
-    if (!mfma || serial || g_serial || d.nseg <= 1) return 1;
+    return serial || g_serial;
+}
+
+static int lanes(const Dims& d, bool mfma) {
+    if (!mfma || serial_mode() || d.nseg <= 1) return 1;
     return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
 }
 

@@ -439,6 +439,29 @@ hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
     return big ? launch_big<AK, BK>(gp, st) : launch_cfg<AK, BK, 4, 2>(gp, st);
 }
 
+// The two gradient products of a call are independent (both read dout; they write dx and dw).  One of them
+// alone often leaves compute units idle -- a segment of 4096 rows gives the input gradient of the 2.7B block's
+// input projection 160 tiles for 256 units -- so the weight gradient runs on a library stream of default
+// priority, forked from and joined into the caller's stream with events, and the two fill the machine together.
+struct Side {
+    hipStream_t st = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool ok = false;
+};
+Side* side_for_current_device() {
+    static Side sides[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    Side& s = sides[dev];
+    if (!s.ok) {
+        if (hipStreamCreateWithFlags(&s.st, hipStreamNonBlocking) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
+        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+        s.ok = true;
+    }
+    return &s;
+}
+
 int check(int64_t rows, int32_t in_dim, int32_t out_dim, int64_t ldx, int64_t ldo) {
     if (rows < 0 || rows > 0x7fffffff || in_dim <= 0 || out_dim <= 0) return SSD_ERR_SHAPE;
     if ((in_dim | out_dim) & 7) return SSD_ERR_DIVISIBILITY;  // 16-byte vectors of bf16
@@ -505,6 +528,14 @@ extern "C" int ssd_linear_bwd(int64_t rows, int32_t in_dim, int32_t out_dim, con
     if (!ok_ptr(dout) || (dx && (!ok_ptr(dx) || !ok_ptr(w))) || (dw && (!ok_ptr(x) || !ok_ptr(dw)))) return SSD_ERR_ARG;
     GemmParams gp;
     const int64_t ldd = dout_row_stride ? dout_row_stride : out_dim;
+    // both products wanted: the weight gradient goes to the side stream (see Side)
+    Side* side = dx && dw && !serial_mode() ? side_for_current_device() : nullptr;
+    hipStream_t st_w = st;
+    if (side) {
+        if (hipEventRecord(side->fork, st) != hipSuccess || hipStreamWaitEvent(side->st, side->fork, 0) != hipSuccess) return SSD_ERR_LAUNCH;
+        st_w = side->st;
+    }
+    int status = SSD_OK;
     if (dx) {  // dx[rows, in] = dout[rows, out] w[out, in]: contraction over out; w holds it as the row index
         memset(&gp, 0, sizeof(gp));
         gp.A = (const bf16_t*)dout;
@@ -516,9 +547,9 @@ extern "C" int ssd_linear_bwd(int64_t rows, int32_t in_dim, int32_t out_dim, con
         gp.M = (int)rows;
         gp.N = in_dim;
         gp.K = out_dim;
-        if (launch_gemm<true, false>(gp, st) != hipSuccess) return SSD_ERR_LAUNCH;
+        if (launch_gemm<true, false>(gp, st) != hipSuccess) status = SSD_ERR_LAUNCH;
     }
-    if (dw) {  // dw[out, in] = dout^T x: contraction over the rows, the row index of both operands
+    if (dw && status == SSD_OK) {  // dw[out, in] = dout^T x: contraction over the rows, the row index of both operands
         memset(&gp, 0, sizeof(gp));
         gp.A = (const bf16_t*)dout;
         gp.B = (const bf16_t*)x;
@@ -531,9 +562,11 @@ extern "C" int ssd_linear_bwd(int64_t rows, int32_t in_dim, int32_t out_dim, con
         gp.K = (int)rows;
         gp.c_f32 = 1;
         gp.accumulate = accumulate;
-        if (launch_gemm<false, false>(gp, st) != hipSuccess) return SSD_ERR_LAUNCH;
+        if (launch_gemm<false, false>(gp, st_w) != hipSuccess) status = SSD_ERR_LAUNCH;
     }
-    return SSD_OK;
+    // whatever reached the side stream ends before the caller's next work, also after a failed launch
+    if (side && (hipEventRecord(side->join, side->st) != hipSuccess || hipStreamWaitEvent(st, side->join, 0) != hipSuccess)) return SSD_ERR_LAUNCH;
+    return status;
 }
 
 // Calibration: what the matrix cores deliver when nothing else is in the way -- every wave issues

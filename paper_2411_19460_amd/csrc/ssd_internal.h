@@ -214,6 +214,9 @@ int conv1d_bwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, 
                      const ConvSplit& dout, const float* dstate_out, void* du, float* dw, float* dbias, float* dstate_in,
                      void* workspace, size_t workspace_bytes, uint32_t flags, hipStream_t st);
 
+// True when everything is to stay on the caller's stream (SSD_MAGC_SERIAL=1 in the environment, or ssd_prof_serialize).
+bool serial_mode();
+
 // Generation (few_rows.hip): products and the block's middle steps for at most FEW_ROWS tokens, bf16 storage.
 constexpr int FEW_ROWS = 16;
 // out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]); w [N, K] dense.  mode 0: f = identity; 1: RMS normalisation
