@@ -111,7 +111,7 @@ def test_stack_validation():
     assert pk.magc_stack_workspace_bytes(sh, 8, 8, True) > pk.magc_stack_workspace_bytes(sh, 8, 2, True)
 
 
-ERR_NULL, ERR_SHAPE, ERR_DIVISIBILITY, ERR_ARG = -1, -2, -3, -8   # as in include/ssd_magc.h
+ERR_NULL, ERR_SHAPE, ERR_DIVISIBILITY, ERR_WORKSPACE, ERR_ARG = -1, -2, -3, -5, -8   # as in include/ssd_magc.h
 
 
 def test_block_pieces_validate_before_any_launch():
@@ -146,6 +146,26 @@ def test_block_pieces_validate_before_any_launch():
     assert L.magc_block_fwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, fake, fake, None, None, fake, 1 << 40, None) == ERR_NULL
     assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, None, None, fake, fake, fake, ctypes.byref(gr), None, None, fake, 1 << 40, 0, None) \
         == ERR_NULL
+    # the stack: shapes, parameter structs and state arrays are checked before the workspace or a launch
+    ss = binding.magc_blockstack_shape_t(bs, 4, 2)
+    assert L.magc_blockstack_workspace_bytes(ctypes.byref(ss), 1) > L.magc_blockstack_workspace_bytes(ctypes.byref(ss), 0) > 0
+    assert L.magc_blockstack_workspace_bytes(ctypes.byref(binding.magc_blockstack_shape_t(bs, 4, 5)), 0) == 0     # interval above the layer count
+    pars = (binding.magc_block_params_t * 4)()
+    assert L.magc_blockstack_infer(ctypes.byref(ss), pars, fake, fake, fake, fake, 0, fake, 1 << 40, None) == ERR_NULL      # parameters missing
+    for k in binding.BLOCK_PARAMS[:-1]:
+        for j in range(4):
+            setattr(pars[j], k, 0x1000)
+    assert L.magc_blockstack_infer(ctypes.byref(ss), pars, fake, fake, None, fake, 0, fake, 1 << 40, None) == ERR_NULL      # no state array
+    assert L.magc_blockstack_infer(ctypes.byref(ss), pars, fake, fake, fake, fake, 0, None, 0, None) == ERR_WORKSPACE
+    assert L.magc_blockstack_infer(ctypes.byref(ss), pars, fake, fake, fake, fake, 0, ctypes.c_void_p(0x1010), 1 << 40, None) == ERR_WORKSPACE   # alignment
+    assert L.magc_blockstack_infer(ctypes.byref(binding.magc_blockstack_shape_t(bs, 0, 1)), pars, fake, fake, fake, fake, 0, fake, 1 << 40, None) == ERR_SHAPE
+    # the pre-norm needs its gradient slot
+    grs = (binding.magc_block_grads_t * 1)()
+    for k in binding.BLOCK_PARAMS[:-1]:
+        setattr(grs[0], "d" + k, 0x1000)
+    pars[0].pre_norm_w = 0x1000
+    assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(pars[0]), fake, None, None, fake, None, None, fake, fake, fake, ctypes.byref(grs[0]), None, None, fake,
+                            1 << 40, 64, None) == ERR_ARG       # unknown flag: refused first
 
 
 CASES = [
