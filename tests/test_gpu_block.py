@@ -251,6 +251,32 @@ def test_stack_inference_prompt_then_tokens(pre):
         check(f"layer {j} conv state", host(st["conv_state"][j]), fo["conv_states"][j], tol)
 
 
+@pytest.mark.parametrize("shape", [(128, 8, 64, 2, 128, 128), (64, 8, 16, 1, 16, 64), (64, 8, 20, 4, 24, 64)])
+def test_stack_generation_from_the_first_token(shape):
+    # a new sequence that starts with calls of a few tokens: the first call has no state to read (zeros), its
+    # convolution window reaches before the sequence; small and odd head and state sizes (rows of the state that
+    # do not fill a wave, heads that do not fill a workgroup), several groups
+    dm, H, P, G, N, Q = shape
+    NL, calls = 2, [2, 1, 5, 16, 1]
+    L = sum(calls)
+    ds = [draw(30 + j, L, dm, H, P, G, N, True) for j in range(NL)]
+    layers_h, x0h = [x["p"] for x in ds], ds[0]["u"]
+    x0, layers = dev_bf16(x0h), [to_dev(p) for p in layers_h]
+    fo = block_ref.stack_fwd(x0h, layers_h, H, P, G, N, 1e-5, store=synth.round_bf16)
+    st, outs, t = {}, [], 0
+    for n in calls:
+        st = pk.magc_blockstack_infer(x0[t:t + n].contiguous(), layers, H, P, G, N, Q, 4 * Q, ssm_state=st.get("ssm_state"),
+                                      conv_state=st.get("conv_state"), workspace=st.get("workspace"))
+        outs.append(st["out"])
+        t += n
+    torch.cuda.synchronize()
+    tol = 2 * TOL["bf16"]
+    check("out", host(torch.cat(outs)), fo["out"], tol)
+    for j in range(NL):
+        check(f"layer {j} ssm state", host(st["ssm_state"][j]), fo["ssm_states"][j], tol)
+        check(f"layer {j} conv state", host(st["conv_state"][j]), fo["conv_states"][j], tol)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
