@@ -449,6 +449,17 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
     const BlockWs w = layout(d, false);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
     char* ws = (char*)workspace;
+    // Several segments: a segment's output projection and the next segment's input projection do not depend on
+    // each other, and either alone leaves compute units idle (4096 rows: 160 and 672 tiles for 256 units), so
+    // the output projection goes to the library's side stream while the caller's stream runs ahead.
+    const int64_t tail_rows = d.L - (d.nseg - 1) * d.s;
+    SideStream* side = d.nseg > 1 && tail_rows > FEW_ROWS ? side_stream() : nullptr;
+    bool side_busy = false;
+    auto join_side = [&]() -> bool {  // the caller's stream waits for what the side stream was given
+        if (!side_busy) return true;
+        side_busy = false;
+        return hipStreamWaitEvent(st, side->join, 0) == hipSuccess;
+    };
     for (int64_t k = 0; k < d.nseg; ++k) {
         const int64_t t0 = k * d.s, rows = d.L - t0 < d.s ? d.L - t0 : d.s;
         const bool last = k + 1 == d.nseg;
@@ -463,9 +474,34 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
             BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, nullptr, st));
             continue;
         }
-        BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st));
-        BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, st));
+        if (!side) {
+            BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st));
+            BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, st));
+            continue;
+        }
+        int rc = SSD_OK;
+        if (k == 0) rc = seg_in_proj(d, sh->eps, p, ws, w, u_seg, rows, ws + w.zx, st);  // later ones were issued a segment ahead
+        if (rc == SSD_OK) rc = seg_mid(d, p, ws, w, ws + w.zx, rows, conv_in, conv_out, st);
+        if (rc == SSD_OK) rc = seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, ws + w.y, st);
+        if (!join_side() && rc == SSD_OK) rc = SSD_ERR_LAUNCH;  // the last output projection has read the normalised y
+        if (rc == SSD_OK) rc = seg_norm(d, sh, p, ws, w, ws + w.zx, ws + w.y, rows, st);
+        if (rc != SSD_OK) return rc;
+        BLK_HIP(hipEventRecord(side->fork, st));
+        BLK_HIP(hipStreamWaitEvent(side->st, side->fork, 0));
+        rc = ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, side->st);
+        side_busy = hipEventRecord(side->join, side->st) == hipSuccess;  // joined below whatever the product returned
+        if (!side_busy) (void)hipStreamSynchronize(side->st);
+        if (rc == SSD_OK && !last) {
+            // every reader of this segment's zxbcdt is already in the stream: the next one may replace it
+            const int64_t t1 = t0 + d.s, rows1 = d.L - t1 < d.s ? d.L - t1 : d.s;
+            rc = seg_in_proj(d, sh->eps, p, ws, w, (const char*)u + (size_t)t1 * d.dm * 2, rows1, ws + w.zx, st);
+        }
+        if (rc != SSD_OK) {
+            (void)join_side();
+            return rc;
+        }
     }
+    if (!join_side()) return SSD_ERR_LAUNCH;
     return SSD_OK;
 }
 

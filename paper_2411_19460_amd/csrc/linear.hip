@@ -446,6 +446,7 @@ hipError_t launch_gemm(const GemmParams& gp, hipStream_t st) {
 struct Side {
     hipStream_t st = nullptr;
     hipEvent_t fork = nullptr, join = nullptr;
+    SideStream outer;  // the same stream with a pair of events of its own, for callers inside the library
     bool ok = false;
 };
 Side* side_for_current_device() {
@@ -455,12 +456,24 @@ Side* side_for_current_device() {
     Side& s = sides[dev];
     if (!s.ok) {
         if (hipStreamCreateWithFlags(&s.st, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        if (hipEventCreateWithFlags(&s.join, hipEventDisableTiming) != hipSuccess) return nullptr;
+        hipEvent_t* evs[] = {&s.fork, &s.join, &s.outer.fork, &s.outer.join};
+        for (hipEvent_t* e : evs)
+            if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
+        s.outer.st = s.st;
         s.ok = true;
     }
     return &s;
 }
+
+}  // namespace
+
+SideStream* side_stream() {
+    if (serial_mode()) return nullptr;
+    Side* s = side_for_current_device();
+    return s ? &s->outer : nullptr;
+}
+
+namespace {
 
 int check(int64_t rows, int32_t in_dim, int32_t out_dim, int64_t ldx, int64_t ldo) {
     if (rows < 0 || rows > 0x7fffffff || in_dim <= 0 || out_dim <= 0) return SSD_ERR_SHAPE;

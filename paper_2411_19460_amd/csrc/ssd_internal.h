@@ -217,6 +217,16 @@ int conv1d_bwd_split(const ssd_conv_shape_t* sh, const void* u, const float* w, 
 // True when everything is to stay on the caller's stream (SSD_MAGC_SERIAL=1 in the environment, or ssd_prof_serialize).
 bool serial_mode();
 
+// The library's side stream of the current device (default priority, created on first use) with a pair of
+// events for the caller to fork it from and join it into its own stream; NULL in serial mode or on failure.
+// ssd_linear_bwd enqueues on the same stream with events of its own, so work given to it here and the
+// products of such a call run in the order they were enqueued.
+struct SideStream {
+    hipStream_t st;
+    hipEvent_t fork, join;
+};
+SideStream* side_stream();
+
 // Generation (few_rows.hip): products and the block's middle steps for at most FEW_ROWS tokens, bf16 storage.
 constexpr int FEW_ROWS = 16;
 // out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]); w [N, K] dense.  mode 0: f = identity; 1: RMS normalisation
