@@ -359,6 +359,23 @@ def block_bench(args, cfg, pk, torch, dev):
             generate()
             torch.cuda.synchronize()
             us_tok = (time.perf_counter() - t0) * 1e6 / ntok
+            # the same step for sixteen sequences at once: the parameters are read once for all of them
+            nseq = 16
+            ssm16 = torch.zeros((nseq, NL, H, P, N), dtype=torch.float32, device=dev)
+            conv16 = torch.zeros((nseq, NL, 3, conv_dim), dtype=torch.bfloat16, device=dev)
+            tok16 = u[:nseq].clone()
+
+            def generate16():
+                for _ in range(ntok):
+                    rc = pk.lib().magc_blockstack_decode(ctypes.byref(one), pars, nseq, tok16.data_ptr(), tok16.data_ptr(), ssm16.data_ptr(),
+                                                         conv16.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                    assert rc == 0, rc
+            generate16()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            generate16()
+            torch.cuda.synchronize()
+            us_step16 = (time.perf_counter() - t0) * 1e6 / ntok
             wbytes = sum(v.numel() * v.element_size() for v in par.values()) * NL
             print(json.dumps({
                 "metric": "Mamba-2 block stack prefill tokens/sec/layer", "value": NL * L / (ms_p * 1e-3), "unit": "tokens/s", "n_gpus": 1,
@@ -373,6 +390,10 @@ def block_bench(args, cfg, pk, torch, dev):
                                "weights_and_states_bytes_per_token": wbytes + 2 * NL * H * P * N * 4,
                                "hbm_floor_us": (wbytes + 2 * NL * H * P * N * 4) / HBM_PEAK_GBS / 1e3,
                                "note": "one C call per token; every parameter read once and every SSM state read and written once per token"},
+                "batched_generation": {"sequences": nseq, "us_per_step": us_step16, "us_per_step_per_layer": us_step16 / NL,
+                                       "tokens_per_s": nseq / (us_step16 * 1e-6),
+                                       "hbm_floor_us": (wbytes + 2 * nseq * NL * H * P * N * 4) / HBM_PEAK_GBS / 1e3,
+                                       "note": "one token for each of the sequences per call (magc_blockstack_decode)"},
                 "workspace_bytes": int(ws.numel()),
             }))
             return

@@ -377,6 +377,18 @@ int magc_blockstack_infer(const magc_blockstack_shape_t* shape, const magc_block
                           void* hip_stream);
 
 /*
+ * One generation step (Eq. 1) for `nseq` independent sequences at once, 0 <= nseq <= 16: every parameter is read
+ * once for all of them, which is what bounds generation.  x0, out [nseq, d_model] bf16: one token per sequence.
+ *   ssm_state [nseq, nlayers, H, P, N] fp32, conv_state [nseq, nlayers, 3, d_inner + 2 G N] bf16: sequence-major,
+ *   so the slice of one sequence is exactly what magc_blockstack_infer keeps for it (prefill each sequence with
+ *   that call, or start from zeros); read and replaced in place.
+ * block.seqlen and layer_interval are ignored; workspace as for magc_blockstack_infer.  Same stream rules.
+ */
+int magc_blockstack_decode(const magc_blockstack_shape_t* shape, const magc_block_params_t* params, int32_t nseq,
+                           const void* x0, void* out, float* ssm_state, void* conv_state, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
  * A stack of `nlayers` SSD layers with residual adds, x_{j+1} = x_j + SSD_j(x_j), run on the
  * MA-GC grid of Sec. 3.2/3.3: layer-axis checkpoints every `layer_interval` layers (l) and
  * sequence-axis checkpoints every shape->segment tokens (s).

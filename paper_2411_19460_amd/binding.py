@@ -20,7 +20,7 @@ EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_b
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
            "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
            "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
-           "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_blockstack_infer",
+           "magc_blockstack_workspace_bytes", "magc_blockstack_fwd", "magc_blockstack_bwd", "magc_blockstack_infer", "magc_blockstack_decode",
            "magc_stack_workspace_bytes", "magc_stack_fwd",
            "magc_stack_bwd", "magc_plan", "ssd_strerror", "ssd_prof_enable", "ssd_prof_read", "ssd_prof_kernel_name", "ssd_prof_serialize", "ssd_prof_mfma_peak", "ssd_prof_clock_probe")
 
@@ -136,6 +136,8 @@ def lib():
         L.magc_blockstack_fwd.argtypes = [sshp, bpar] + [vp] * 5 + [vp, sz, vp]
         L.magc_blockstack_infer.restype = ctypes.c_int
         L.magc_blockstack_infer.argtypes = [sshp, bpar] + [vp] * 4 + [i32, vp, sz, vp]
+        L.magc_blockstack_decode.restype = ctypes.c_int
+        L.magc_blockstack_decode.argtypes = [sshp, bpar, i32] + [vp] * 4 + [vp, sz, vp]
         L.magc_blockstack_bwd.restype = ctypes.c_int
         L.magc_blockstack_bwd.argtypes = [sshp, bpar] + [vp] * 6 + [bgr, vp, sz, u32, vp]
         L.ssd_prof_mfma_peak.restype = ctypes.c_int
@@ -582,6 +584,30 @@ def magc_blockstack_infer(x0, layers, nheads, headdim, ngroups, dstate, chunk, s
     if rc != 0:
         raise SSDError(rc, "magc_blockstack_infer")
     return {"out": out, "ssm_state": ssm_state, "conv_state": conv_state, "workspace": workspace}
+
+
+def magc_blockstack_decode(x, layers, nheads, headdim, ngroups, dstate, chunk, segment, ssm_state, conv_state, eps=1e-5, out=None,
+                           workspace=None):
+    """One token for each of x.shape[0] <= 16 independent sequences: x [nseq, d_model]; ssm_state [nseq, NL, H, P, N] fp32
+    and conv_state [nseq, NL, 3, conv_dim] bf16 are updated in place.  Returns dict(out, workspace)."""
+    import torch
+    sshape, pars, _, _, conv_dim = _blockstack_setup(x, layers, nheads, headdim, ngroups, dstate, chunk, segment, 1, eps)
+    dev, NL, nseq = x.device, len(layers), x.shape[0]
+    for t, shp, dty in ((ssm_state, (nseq, NL, nheads, headdim, dstate), torch.float32), (conv_state, (nseq, NL, 3, conv_dim), torch.bfloat16)):
+        if tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous():
+            raise ValueError(f"state tensor must be a dense {dty} device tensor of shape {shp}")
+    if out is None:
+        out = torch.empty_like(x)
+    elif out.shape != x.shape or out.dtype != x.dtype or not out.is_cuda or not out.is_contiguous():
+        raise ValueError("out must match x")
+    need = int(lib().magc_blockstack_workspace_bytes(ctypes.byref(sshape), 0))
+    if workspace is None or workspace.numel() < need:
+        workspace = _workspace(need, dev)
+    rc = lib().magc_blockstack_decode(ctypes.byref(sshape), pars, nseq, _ptr(x), _ptr(out), _ptr(ssm_state), _ptr(conv_state),
+                                      _ptr(workspace), workspace.numel(), _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "magc_blockstack_decode")
+    return {"out": out, "workspace": workspace}
 
 
 def magc_blockstack_bwd(x0, layers, dout, l_ckpt, ssm_ckpt, conv_ckpt, nheads, headdim, ngroups, dstate, chunk, segment,

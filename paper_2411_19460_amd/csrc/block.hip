@@ -305,16 +305,35 @@ bool few_path(const BlockDims& d, const magc_block_params_t* p, int64_t rows, co
     return true;
 }
 
+// Where the states of the sequences of a few-token call live.  One sequence: the strides are not used.  Several
+// (one token each, or a few): sequence b's SSM state is ssm + b ssm_bs floats (updated in place: ssm_in == ssm_out),
+// its convolution states conv_in + b conv_in_bs and conv_out + b conv_out_bs elements; conv_final, if given, is
+// where conv_out is moved to once the call's last kernel runs (sequence b: conv_final_bs bytes further on).
+struct FewSeqs {
+    int nb = 1;
+    int64_t ssm_bs = 0, conv_in_bs = 0, conv_out_bs = 0;
+    void* conv_final = nullptr;
+    size_t conv_final_bs = 0;
+};
+
 int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
-                const void* u, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out, void* out,
-                const void* res, void* conv_final, hipStream_t st) {
+                const void* u, int64_t tokens, const float* ssm_in, const void* conv_in, float* ssm_out, void* conv_out, void* out,
+                const void* res, const FewSeqs& sq, hipStream_t st) {
+    const int rows = (int)tokens * sq.nb;  // rows of every product: sequence-major, the tokens of a sequence in order
+    if (sq.nb > 1 && ssm_in != ssm_out) return SSD_ERR_ARG;
+    const bool fold = rows <= FEW_ROWS_VALU;  // few enough rows for the normalisations to ride on the products
     FewRowsJob in;
     memset(&in, 0, sizeof(in));
-    in.rows = (int)rows;
+    in.rows = rows;
     in.K = d.dm;
     in.N = d.d_in_proj;
-    in.mode = p->pre_norm_w ? 1 : 0;
+    in.mode = p->pre_norm_w && fold ? 1 : 0;
     in.x = u;
+    if (p->pre_norm_w && !fold) {
+        const void* un;
+        BLK_TRY(seg_pre_norm(d, sh->eps, p, ws, w, u, rows, &un, st));
+        in.x = un;
+    }
     in.ldx = d.dm;
     in.w = p->W_in;
     in.out = ws + w.zx;
@@ -325,7 +344,11 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     if (ssm_in != ssm_out) BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
     DecodeMidJob mid;
     memset(&mid, 0, sizeof(mid));
-    mid.T = (int)rows;
+    mid.nb = sq.nb;
+    mid.state_bs = sq.ssm_bs;
+    mid.cs_in_bs = sq.conv_in_bs;
+    mid.cs_out_bs = sq.conv_out_bs;
+    mid.T = (int)tokens;
     mid.H = d.H;
     mid.P = d.P;
     mid.G = d.G;
@@ -344,7 +367,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     BLK_HIP(launch_decode_mid(mid, st));
     FewRowsJob o;
     memset(&o, 0, sizeof(o));
-    o.rows = (int)rows;
+    o.rows = rows;
     o.K = d.d_inner;
     o.N = d.dm;
     o.w = p->W_out;
@@ -353,12 +376,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     o.ldx = d.d_inner;
     o.res = res;
     o.ldres = d.dm;
-    if (conv_final) {  // the new convolution state moves to its place on the back of the last launch
-        o.copy_src = conv_out;
-        o.copy_dst = conv_final;
-        o.copy_bytes = (size_t)3 * d.conv_dim * 2;
-    }
-    if (d.G == 1) {  // one group: the gated normalisation rides on the product
+    if (d.G == 1 && fold) {  // one group: the gated normalisation rides on the product
         o.mode = 2;
         o.x = ws + w.y;
         o.in_w = p->norm_w;
@@ -369,7 +387,28 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
         BLK_TRY(seg_norm(d, sh, p, ws, w, ws + w.zx, ws + w.y, rows, st));
         o.x = ws + w.yn;
     }
+    // the new convolution states move to their place on the back of the last launch where its threads suffice
+    const size_t cs_bytes = (size_t)3 * d.conv_dim * 2;
+    bool moved = false;
+    if (sq.conv_final) {
+        o.copy_src = conv_out;
+        o.copy_dst = sq.conv_final;
+        o.copy_bytes = cs_bytes;
+        o.copy_chunks = sq.nb;
+        o.copy_src_stride = (size_t)sq.conv_out_bs * 2;
+        o.copy_dst_stride = sq.conv_final_bs;
+        moved = few_rows_supported(o);
+        if (!moved) {
+            o.copy_src = o.copy_dst = nullptr;
+            o.copy_bytes = 0;
+            o.copy_chunks = 0;
+        }
+    }
     BLK_HIP(launch_linear_few_rows(o, st));
+    if (sq.conv_final && !moved)
+        for (int b = 0; b < sq.nb; ++b)  // bf16 pairs as words
+            BLK_HIP(launch_copy_f32((float*)((char*)sq.conv_final + b * sq.conv_final_bs),
+                                    (const float*)((const char*)conv_out + (size_t)b * sq.conv_out_bs * 2), cs_bytes / 4, st));
     return SSD_OK;
 }
 
@@ -471,7 +510,7 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
         const char* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
         char* out_seg = (char*)out + (size_t)t0 * d.dm * 2;
         if (few_path(d, p, rows, ssm_out, u_seg, out_seg) && (!conv_out || conv_out != conv_in)) {
-            BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, nullptr, st));
+            BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, FewSeqs(), st));
             continue;
         }
         if (!side) {
@@ -632,7 +671,7 @@ StackWs stack_layout(const magc_blockstack_shape_t* sh, const StackDims& d, bool
     w.act[0] = take(d.act);
     w.act[1] = take(d.act);
     w.fin_ssm = take(d.b.HPN * 4);
-    w.fin_conv = take(d.conv_state);
+    w.fin_conv = take((size_t)FEW_ROWS * d.conv_state);  // one per sequence of a batched generation step
     w.zx_bytes = al((size_t)d.b.s * d.b.d_in_proj * 2);
     w.y_bytes = al((size_t)d.b.s * d.b.d_inner * 2);
     if (bwd) {
@@ -860,9 +899,11 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
             bool conv_moved = false;
             if (few_path(dc, &params[j], rows, ssm_out, cur, nxt)) {
                 // generation: the residual and the move of the convolution state ride on the output product
-                conv_moved = ((uintptr_t)cj & 15) == 0 && d.conv_state % 16 == 0 && d.conv_state / 16 <= (size_t)d.b.dm * 32;
+                FewSeqs sq;
+                sq.conv_final = cj;
+                conv_moved = true;
                 BLK_TRY(forward_few(dc, &c, &params[j], bws, bw, cur, rows, zero ? nullptr : sj, zero ? nullptr : cj, ssm_out,
-                                    ws + w.fin_conv, nxt, cur, conv_moved ? cj : nullptr, st));
+                                    ws + w.fin_conv, nxt, cur, sq, st));
             } else {
                 BLK_TRY(magc_block_fwd(&c, &params[j], cur, zero ? nullptr : sj, zero ? nullptr : cj, y, nullptr, nullptr, ssm_out,
                                        ws + w.fin_conv, ws + w.inner, w.inner_bytes, st));
@@ -872,6 +913,54 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
             if (!conv_moved) BLK_HIP(launch_copy_f32((float*)cj, (const float*)(ws + w.fin_conv), d.conv_state / 4, st));  // bf16 pairs as words
             cur = nxt;
         }
+    }
+    return SSD_OK;
+}
+
+// One generation step for several independent sequences at once: every parameter is read once for all of them.
+extern "C" int magc_blockstack_decode(const magc_blockstack_shape_t* sh, const magc_block_params_t* params, int32_t nseq, const void* x0,
+                                      void* out, float* ssm_state, void* conv_state, void* workspace, size_t workspace_bytes,
+                                      void* hip_stream) {
+    StackDims d;
+    BLK_TRY(check_stack(sh, &d));
+    if (nseq < 0 || nseq > FEW_ROWS) return SSD_ERR_SHAPE;
+    if (!params_ok(params, d.NL)) return SSD_ERR_NULL;
+    if (nseq == 0) return SSD_OK;
+    if (!x0 || !out || !ssm_state || !conv_state) return SSD_ERR_NULL;
+    const StackWs w = stack_layout(sh, d, false);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < w.total) return SSD_ERR_WORKSPACE;
+    hipStream_t st = (hipStream_t)hip_stream;
+    char* ws = (char*)workspace;
+    const size_t row = (size_t)d.b.dm * 2;
+    const magc_block_shape_t c = cell_shape(sh, 1);  // a token per sequence
+    BlockDims dc;
+    BLK_TRY(check(&c, &dc));
+    const BlockWs bw = layout(dc, false);
+    if (bw.total > w.inner_bytes) return SSD_ERR_WORKSPACE;
+    bool batched = nseq <= d.b.s;  // the rows of all sequences fit the buffers of one segment
+    for (int j = 0; j < d.NL && batched; ++j) batched = few_path(dc, &params[j], nseq, ssm_state, x0, out);
+    if (!batched) {  // shapes or alignments the generation kernels do not take: sequence by sequence
+        magc_blockstack_shape_t one = *sh;
+        one.block.seqlen = 1;
+        for (int b = 0; b < nseq; ++b)
+            BLK_TRY(magc_blockstack_infer(&one, params, (const char*)x0 + b * row, (char*)out + b * row, ssm_state + (size_t)b * d.NL * d.b.HPN,
+                                          (char*)conv_state + (size_t)b * d.NL * d.conv_state, 0, workspace, workspace_bytes, hip_stream));
+        return SSD_OK;
+    }
+    const char* cur = (const char*)x0;
+    for (int j = 0; j < d.NL; ++j) {
+        float* sj = ssm_state + (size_t)j * d.b.HPN;             // sequence 0; sequence b: NL states further on
+        char* cj = (char*)conv_state + (size_t)j * d.conv_state;
+        char* nxt = j + 1 == d.NL ? (char*)out : ws + w.act[j & 1];
+        FewSeqs sq;
+        sq.nb = nseq;
+        sq.ssm_bs = (int64_t)d.NL * d.b.HPN;
+        sq.conv_in_bs = (int64_t)d.NL * 3 * d.b.conv_dim;
+        sq.conv_out_bs = (int64_t)3 * d.b.conv_dim;
+        sq.conv_final = cj;
+        sq.conv_final_bs = (size_t)d.NL * d.conv_state;
+        BLK_TRY(forward_few(dc, &c, &params[j], ws + w.inner, bw, cur, 1, sj, cj, sj, ws + w.fin_conv, nxt, cur, sq, st));
+        cur = nxt;
     }
     return SSD_OK;
 }

@@ -38,12 +38,13 @@ struct FewParams {
 // caches.  MODE 0: f(x) = x.  MODE 1: f(x) = x / sqrt(mean x^2 + eps) * in_w.  MODE 2: the same of g = x z sigmoid(z).
 // A wave sees whole rows, so the mean comes out of the same loop and scales the finished sums.  With few rows
 // the operands of two k steps are requested before either is used (twice the bytes in flight per wave).
-// The first workgroups also move `copy_n` 16-byte vectors from copy_src to copy_dst: a small state that the
-// kernel before this one still read in its old place.
+// The first workgroups also move `copy_chunks` pieces of `copy_n` 16-byte vectors from copy_src to copy_dst: a small
+// state (one piece per sequence) that the kernel before this one still read in its old place.
 struct FewOperands {
     const void* copy_src;
     void* copy_dst;
-    int copy_n;
+    int copy_n, copy_chunks;                   // vectors per chunk, chunks
+    int64_t copy_src_stride, copy_dst_stride;  // vectors between chunks
 };
 
 template <int MODE, int R, int CPW>
@@ -98,7 +99,10 @@ template <int MODE, int R, int CPW>
 __global__ __launch_bounds__(256) void k_linear_few(FewParams fp, FewOperands fo) {
     if (fo.copy_n) {
         const int i = blockIdx.x * 256 + threadIdx.x;
-        if (i < fo.copy_n) ((f32x4*)fo.copy_dst)[i] = ((const f32x4*)fo.copy_src)[i];
+        if (i < fo.copy_n * fo.copy_chunks) {
+            const int c = i / fo.copy_n, v = i - c * fo.copy_n;
+            ((f32x4*)fo.copy_dst)[c * fo.copy_dst_stride + v] = ((const f32x4*)fo.copy_src)[c * fo.copy_src_stride + v];
+        }
     }
     const int lane = threadIdx.x & 63;
     const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * CPW;
@@ -140,7 +144,7 @@ template <int MODE, int CPW>
 hipError_t launch_few_c(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
     const int waves = (fp.N + CPW - 1) / CPW;
     const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
-    if ((int64_t)grid.x * 256 < fo.copy_n) return hipErrorInvalidValue;
+    if ((int64_t)grid.x * 256 < (int64_t)fo.copy_n * fo.copy_chunks) return hipErrorInvalidValue;
     if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1, CPW>), grid, block, 0, st, fp, fo);
     else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2, CPW>), grid, block, 0, st, fp, fo);
     else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4, CPW>), grid, block, 0, st, fp, fo);
@@ -156,6 +160,69 @@ hipError_t launch_few(const FewParams& fp, const FewOperands& fo, hipStream_t st
     return fp.N >= 8192 ? launch_few_c<MODE, 2>(fp, fo, st) : launch_few_c<MODE, 1>(fp, fo, st);
 }
 
+// More than a few rows (several sequences generated together): the same product on the matrix cores.  A
+// workgroup owns 16 columns of w; its KS waves split k among themselves and each runs 16 x 16 x 32 MFMAs with the
+// (at most 16) input rows as the other operand, so the arithmetic is out of the way and the kernel again only
+// streams w; the partial tiles meet in LDS.  No input transform here (a normalisation in front runs as its own
+// small kernel: redoing it in every wave is what would bound the kernel).
+typedef float f32x4v __attribute__((ext_vector_type(4)));
+
+template <int KS>
+__global__ __launch_bounds__(KS * 64) void k_linear_few_mfma(FewParams fp, FewOperands fo) {
+    __shared__ float part[KS][256];
+    if (fo.copy_n) {
+        const int i = blockIdx.x * (KS * 64) + threadIdx.x;
+        if (i < fo.copy_n * fo.copy_chunks) {
+            const int c = i / fo.copy_n, v = i - c * fo.copy_n;
+            ((f32x4*)fo.copy_dst)[c * fo.copy_dst_stride + v] = ((const f32x4*)fo.copy_src)[c * fo.copy_src_stride + v];
+        }
+    }
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int n0 = blockIdx.x * 16;
+    const int col = lane & 15, kq = lane >> 4;  // the lane's row of x and column of w; its quarter of a 32-wide k step
+    const bool has_x = col < fp.rows, has_w = n0 + col < fp.N;
+    const __bf16* xr = fp.x + (int64_t)col * fp.ldx;
+    const __bf16* wr = fp.w + (int64_t)(n0 + col) * fp.K;
+    const int nsteps = (fp.K + 31) / 32, per = (nsteps + KS - 1) / KS;
+    const int s0 = wv * per, s1 = s0 + per < nsteps ? s0 + per : nsteps;
+    f32x4v acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll 4
+    for (int si = s0; si < s1; ++si) {
+        const int k = si * 32 + 8 * kq;  // K is a multiple of 8: a lane's eight values are inside or outside as a whole
+        bf16x8 a, b;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) a[e] = b[e] = (__bf16)0.f;
+        if (has_x && k < fp.K) a = *(const bf16x8*)(xr + k);
+        if (has_w && k < fp.K) b = *(const bf16x8*)(wr + k);
+        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);  // acc[i] = out[row 4 kq + i][column col]
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[wv][lane * 4 + i] = acc[i];
+    __syncthreads();
+    if (threadIdx.x < 256) {
+        float v = 0.f;
+#pragma unroll
+        for (int q = 0; q < KS; ++q) v += part[q][threadIdx.x];
+        const int l = threadIdx.x >> 2, i = threadIdx.x & 3;
+        const int r = 4 * (l >> 4) + i, n = n0 + (l & 15);
+        if (r < fp.rows && n < fp.N) {
+            if (fp.res) v += (float)fp.res[r * fp.ldres + n];
+            fp.out[r * fp.ldo + n] = (__bf16)v;
+        }
+    }
+}
+
+hipError_t launch_few_mfma(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
+    const int wgs = (fp.N + 15) / 16;
+    // enough waves to keep the memory system busy: the narrower the product, the more ways k is split
+    const int ks = wgs >= 512 ? 4 : wgs >= 256 ? 8 : 16;
+    if ((int64_t)wgs * ks * 64 < (int64_t)fo.copy_n * fo.copy_chunks) return hipErrorInvalidValue;
+    if (ks == 4) hipLaunchKernelGGL((k_linear_few_mfma<4>), dim3(wgs), dim3(256), 0, st, fp, fo);
+    else if (ks == 8) hipLaunchKernelGGL((k_linear_few_mfma<8>), dim3(wgs), dim3(512), 0, st, fp, fo);
+    else hipLaunchKernelGGL((k_linear_few_mfma<16>), dim3(wgs), dim3(1024), 0, st, fp, fo);
+    return hipGetLastError();
+}
+
 struct MidParams {
     const __bf16* zx;   // [T, ld]: (z | xBC | dt_raw) of the tokens
     int64_t ld;
@@ -165,6 +232,9 @@ struct MidParams {
     float* state;         // [H, P, N], updated in place
     __bf16* y;            // [T, d_inner]
     int T, H, P, G, N, hpg, d_inner, conv_dim, off_xbc, off_dt;
+    // several independent sequences in one launch (blockIdx.y): sequence b owns rows b T .. b T + T - 1 of zx and y
+    // and the states `b` strides (elements) further on
+    int64_t state_bs, cs_in_bs, cs_out_bs;
 };
 
 // input of the convolution, channel c, token `pos` of this call (negative: from the entering state)
@@ -189,6 +259,14 @@ constexpr int MID_NPL = 8;  // state columns per lane at most (N <= 512)
 
 __global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
     extern __shared__ float bc[];  // B[0..N), C[0..N) of the group, this token
+    {  // this workgroup's sequence
+        const int64_t b = blockIdx.y;
+        mp.zx += b * mp.T * mp.ld;
+        mp.y += b * mp.T * mp.d_inner;
+        mp.state += b * mp.state_bs;
+        if (mp.cs_in) mp.cs_in += b * mp.cs_in_bs;
+        if (mp.cs_out) mp.cs_out += b * mp.cs_out_bs;
+    }
     const int h = blockIdx.x, g = h / mp.hpg;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const int p = 4 * blockIdx.z + w;
@@ -254,9 +332,12 @@ bool few_rows_supported(const FewRowsJob& j) {
     if (j.mode && (!j.in_w || !al16(j.in_w))) return false;
     if (j.mode == 2 && (!j.z || !al16(j.z) || (j.ldz & 7) || j.ldz < j.K)) return false;
     if (j.res && j.ldres < j.N) return false;
-    if (j.copy_bytes && (!j.copy_src || !j.copy_dst || !al16(j.copy_src) || !al16(j.copy_dst) || (j.copy_bytes & 15) ||
-                         j.copy_bytes / 16 > (size_t)j.N / 2 * 64))  // one vector per thread of the launch
-        return false;
+    if (j.copy_bytes) {
+        const size_t chunks = j.copy_chunks > 0 ? j.copy_chunks : 1;
+        if (!j.copy_src || !j.copy_dst || !al16(j.copy_src) || !al16(j.copy_dst) || (j.copy_bytes & 15) || j.copy_chunks < 0 ||
+            ((j.copy_src_stride | j.copy_dst_stride) & 15) || j.copy_bytes / 16 * chunks > (size_t)j.N * 16)  // one vector per thread of the smallest launch these products use
+            return false;
+    }
     return true;
 }
 
@@ -281,10 +362,16 @@ hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st) {
     fo.copy_src = j.copy_src;
     fo.copy_dst = j.copy_dst;
     fo.copy_n = (int)(j.copy_bytes / 16);
+    fo.copy_chunks = j.copy_bytes ? (j.copy_chunks > 0 ? j.copy_chunks : 1) : 0;
+    fo.copy_src_stride = (int64_t)(j.copy_src_stride / 16);
+    fo.copy_dst_stride = (int64_t)(j.copy_dst_stride / 16);
+    if (j.mode == 0 && j.rows > FEW_ROWS_VALU) return launch_few_mfma(fp, fo, st);
     return j.mode == 0 ? launch_few<0>(fp, fo, st) : j.mode == 1 ? launch_few<1>(fp, fo, st) : launch_few<2>(fp, fo, st);
 }
 
 hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
+    const int nb = j.nb > 0 ? j.nb : 1;
+    if (nb > 65535 || (int64_t)nb * j.T > FEW_ROWS) return hipErrorInvalidValue;
     if (j.T < 1 || j.T > FEW_ROWS || j.H <= 0 || j.H > 65535 || j.P <= 0 || j.G <= 0 || j.N <= 0 || j.H % j.G) return hipErrorInvalidValue;
     if (!j.zx || !j.conv_w || !j.conv_b || !j.dt_bias || !j.A || !j.D || !j.state || !j.y || (j.cs_out && j.cs_out == j.cs_in))
         return hipErrorInvalidValue;
@@ -311,7 +398,10 @@ hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
     mp.conv_dim = mp.d_inner + 2 * j.G * j.N;
     mp.off_xbc = mp.d_inner;
     mp.off_dt = mp.d_inner + mp.conv_dim;
-    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, 1, (j.P + 3) / 4), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
+    mp.state_bs = j.state_bs;
+    mp.cs_in_bs = j.cs_in_bs;
+    mp.cs_out_bs = j.cs_out_bs;
+    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, nb, (j.P + 3) / 4), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
     return hipGetLastError();
 }
 

@@ -229,6 +229,9 @@ SideStream* side_stream();
 
 // Generation (few_rows.hip): products and the block's middle steps for at most FEW_ROWS tokens, bf16 storage.
 constexpr int FEW_ROWS = 16;
+// Up to this many rows the product runs on the vector ALUs with an optional normalisation of the rows folded in;
+// above, on the matrix cores (mode 0 only: the caller normalises first).
+constexpr int FEW_ROWS_VALU = 4;
 // out[r, n] = sum_k f(x)[r, k] w[n, k] (+ res[r, n]); w [N, K] dense.  mode 0: f = identity; 1: RMS normalisation
 // over all of K times in_w; 2: the same of x z sigmoid(z).  Row strides in elements.
 struct FewRowsJob {
@@ -244,16 +247,22 @@ struct FewRowsJob {
     float eps;
     const void* res;
     int64_t ldres;
-    // optional: copy_bytes (a multiple of 16, at most 32 N) bytes moved from copy_src to copy_dst by the same launch
+    // optional: copy_chunks (0 = 1) pieces of copy_bytes bytes (a multiple of 16; at most 16 N vectors in all), the
+    // pieces copy_src_stride / copy_dst_stride bytes apart, moved from copy_src to copy_dst by the same launch
     const void* copy_src;
     void* copy_dst;
     size_t copy_bytes;
+    int copy_chunks;
+    size_t copy_src_stride, copy_dst_stride;
 };
 bool few_rows_supported(const FewRowsJob& j);  // sizes, strides and 16-byte alignment the kernel relies on
 hipError_t launch_linear_few_rows(const FewRowsJob& j, hipStream_t st);
 // zx [T, ld] = (z | xBC | dt_raw) of T tokens -> y [T, H P]; state [H, P, N] in place; cs_in / cs_out [3, H P + 2 G N]
-// (either may be null; never the same buffer)
+// (either may be null; never the same buffer).  nb > 1: that many independent sequences of T tokens each (nb T <=
+// FEW_ROWS), sequence b in rows b T .. of zx and y, its states state_bs / cs_in_bs / cs_out_bs elements further on.
 struct DecodeMidJob {
+    int nb;
+    int64_t state_bs, cs_in_bs, cs_out_bs;
     int T, H, P, G, N;
     const void* zx;
     int64_t ld;

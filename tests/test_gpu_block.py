@@ -277,6 +277,45 @@ def test_stack_generation_from_the_first_token(shape):
         check(f"layer {j} conv state", host(st["conv_state"][j]), fo["conv_states"][j], tol)
 
 
+@pytest.mark.parametrize("shape", [(128, 8, 64, 1, 128, 128, True, 5), (128, 8, 64, 2, 128, 128, False, 16), (64, 8, 16, 1, 16, 64, True, 3)])
+def test_stack_generation_for_several_sequences_at_once(shape):
+    # sequences of different lengths, each prefilled on its own, then generated together one token per step:
+    # every sequence against the oracle run over that sequence alone (sixteen sequences of the wide-state shape:
+    # more convolution state than the last launch can move on the side, so it is copied per sequence)
+    dm, H, P, G, N, Q, pre, nseq = shape
+    NL, steps = 2, 3
+    lens = [70, 1, 300, 33, 150, 2, 5, 64, 129, 17, 3, 40, 90, 8, 256, 11][:nseq]
+    seg = 2 * Q
+    d_inner, conv_dim, _ = block_ref.dims(None, H, P, G, N)
+    base = [draw(40 + j, max(lens) + steps, dm, H, P, G, N, pre) for j in range(NL)]
+    layers_h = [x["p"] for x in base]
+    layers = [to_dev(p) for p in layers_h]
+    r = np.random.default_rng(77)
+    seqs_h = [BF(r.standard_normal((n + steps, dm)) * np.exp(r.uniform(-1.0, 1.0, (n + steps, 1)))) for n in lens]
+    ssm = torch.zeros((nseq, NL, H, P, N), dtype=torch.float32, device="cuda")
+    conv = torch.zeros((nseq, NL, 3, conv_dim), dtype=torch.bfloat16, device="cuda")
+    for i, n in enumerate(lens):     # prefill writes each sequence's slice of the two state arrays
+        xi = dev_bf16(seqs_h[i][:n])
+        st = pk.magc_blockstack_infer(xi, layers, H, P, G, N, Q, seg)
+        ssm[i].copy_(st["ssm_state"])
+        conv[i].copy_(st["conv_state"])
+    outs, ws = [], None
+    for t in range(steps):
+        x = dev_bf16(np.stack([seqs_h[i][lens[i] + t] for i in range(nseq)]))
+        o = pk.magc_blockstack_decode(x, layers, H, P, G, N, Q, seg, ssm, conv, workspace=ws)
+        ws = o["workspace"]
+        outs.append(o["out"])
+    torch.cuda.synchronize()
+    tol = 2 * TOL["bf16"]
+    for i, n in enumerate(lens):
+        fo = block_ref.stack_fwd(seqs_h[i], layers_h, H, P, G, N, 1e-5, store=synth.round_bf16)
+        got = torch.stack([outs[t][i] for t in range(steps)])
+        check(f"sequence {i} generated", host(got), fo["out"][n:], tol)
+        for j in range(NL):
+            check(f"sequence {i} layer {j} ssm state", host(ssm[i, j]), fo["ssm_states"][j], tol)
+            check(f"sequence {i} layer {j} conv state", host(conv[i, j]), fo["conv_states"][j], tol)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
