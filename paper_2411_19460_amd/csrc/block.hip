@@ -342,6 +342,31 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     in.eps = sh->eps;
     BLK_HIP(launch_linear_few_rows(in, st));
     if (ssm_in != ssm_out) BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
+    // many sequences, a token each, their convolution states updated where they are: two kernels (see ConvStepJob)
+    const bool split_mid = sq.nb > FEW_ROWS_VALU && tokens == 1 && conv_in && sq.conv_final == conv_in && sq.conv_final_bs == (size_t)sq.conv_in_bs * 2;
+    if (split_mid) {
+        ConvStepJob cj;
+        memset(&cj, 0, sizeof(cj));
+        cj.nb = sq.nb;
+        cj.H = d.H;
+        cj.P = d.P;
+        cj.G = d.G;
+        cj.N = d.N;
+        cj.zx = ws + w.zx;
+        cj.ld = d.d_in_proj;
+        cj.conv_w = p->conv_w;
+        cj.conv_b = p->conv_b;
+        cj.dt_bias = p->dt_bias;
+        cj.cs = sq.conv_final;
+        cj.cs_bs = sq.conv_in_bs;
+        cj.x = ws + w.x;
+        cj.B = ws + w.B;
+        cj.C = ws + w.C;
+        cj.dt = ws + w.dt;
+        BLK_HIP(launch_conv_step(cj, st));
+        BLK_HIP(launch_decode_strided(sq.nb, d.H, d.P, d.G, d.N, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, sq.ssm_bs,
+                                      ws + w.y, 4, st));
+    }
     DecodeMidJob mid;
     memset(&mid, 0, sizeof(mid));
     mid.nb = sq.nb;
@@ -364,7 +389,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     mid.cs_out = conv_out;
     mid.state = ssm_out;
     mid.y = ws + w.y;
-    BLK_HIP(launch_decode_mid(mid, st));
+    if (!split_mid) BLK_HIP(launch_decode_mid(mid, st));
     FewRowsJob o;
     memset(&o, 0, sizeof(o));
     o.rows = rows;
@@ -390,7 +415,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
     // the new convolution states move to their place on the back of the last launch where its threads suffice
     const size_t cs_bytes = (size_t)3 * d.conv_dim * 2;
     bool moved = false;
-    if (sq.conv_final) {
+    if (sq.conv_final && !split_mid) {
         o.copy_src = conv_out;
         o.copy_dst = sq.conv_final;
         o.copy_bytes = cs_bytes;
@@ -405,7 +430,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
         }
     }
     BLK_HIP(launch_linear_few_rows(o, st));
-    if (sq.conv_final && !moved)
+    if (sq.conv_final && !moved && !split_mid)
         for (int b = 0; b < sq.nb; ++b)  // bf16 pairs as words
             BLK_HIP(launch_copy_f32((float*)((char*)sq.conv_final + b * sq.conv_final_bs),
                                     (const float*)((const char*)conv_out + (size_t)b * sq.conv_out_bs * 2), cs_bytes / 4, st));

@@ -15,6 +15,7 @@ struct DecodeParams {
     float* state;
     void* y;
     int64_t T, xs_b, dts_b, bcs_b;
+    int64_t state_bs;  // floats between the states of consecutive batch entries (dense: H P N)
     int H, P, G, N, hpg;
     float skip_add;  // 1 under the residual flag: y = x + layer(x)
 };
@@ -40,7 +41,7 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams dp) {
     const int h = blockIdx.x, b = blockIdx.y, g = h / dp.hpg;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
     const float Ah = dp.A[h], Dh = dp.D[h] + dp.skip_add;
-    float* S = dp.state + ((int64_t)b * dp.H + h) * dp.P * dp.N;
+    float* S = dp.state + (int64_t)b * dp.state_bs + (int64_t)h * dp.P * dp.N;
     for (int64_t t = 0; t < dp.T; ++t) {
         const float dtv = ld<T>(dp.dt, (int64_t)b * dp.dts_b + t * dp.H + h);
         const float a = (dp.reset && dp.reset[(int64_t)b * dp.T + t]) ? 0.f : __expf(dtv * Ah);
@@ -62,6 +63,38 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams dp) {
 }
 
 }  // namespace
+
+// One token for each of `nb` sequences whose states lie state_bs floats apart (bf16 storage): x [nb, H, P],
+// dt [nb, H], B, C [nb, G, N] dense -> y [nb, H, P].  Each wave takes `rows_per_wave` state rows in turn.
+hipError_t launch_decode_strided(int nb, int H, int P, int G, int N, const void* x, const void* dt, const float* A, const void* B,
+                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, int rows_per_wave, hipStream_t st) {
+    if (nb <= 0 || nb > 65535 || H <= 0 || H > 65535 || P <= 0 || G <= 0 || N <= 0 || H % G || rows_per_wave <= 0) return hipErrorInvalidValue;
+    DecodeParams dp;
+    dp.x = x;
+    dp.dt = dt;
+    dp.Bm = B;
+    dp.Cm = C;
+    dp.A = A;
+    dp.D = D;
+    dp.state = state;
+    dp.reset = nullptr;
+    dp.y = y;
+    dp.T = 1;
+    dp.H = H;
+    dp.P = P;
+    dp.G = G;
+    dp.N = N;
+    dp.hpg = H / G;
+    dp.xs_b = (int64_t)H * P;
+    dp.dts_b = H;
+    dp.bcs_b = (int64_t)G * N;
+    dp.state_bs = state_bs;
+    dp.skip_add = 0.f;
+    const int per_wg = 4 * rows_per_wave, gz = (P + per_wg - 1) / per_wg;
+    hipLaunchKernelGGL(k_decode<bf16_t>, dim3(H, nb, gz < 64 ? gz : 64), dim3(256), 0, st, dp);
+    return hipGetLastError();
+}
+
 }  // namespace ssdk
 
 using namespace ssdk;
@@ -97,6 +130,7 @@ extern "C" int ssd_decode(const ssd_shape_t* sh, const void* x, const void* dt, 
     dp.dts_b = sh->dt_batch_stride ? sh->dt_batch_stride : dp.T * dp.H;
     dp.bcs_b = sh->bc_batch_stride ? sh->bc_batch_stride : dp.T * dp.G * dp.N;
     if (dp.xs_b < dp.T * dp.H * dp.P || dp.dts_b < dp.T * dp.H || dp.bcs_b < dp.T * dp.G * dp.N) return SSD_ERR_SHAPE;
+    dp.state_bs = (int64_t)dp.H * dp.P * dp.N;
     dp.skip_add = (flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f;
     hipStream_t s = (hipStream_t)hip_stream;
     const int rows4 = (dp.P + 3) / 4;

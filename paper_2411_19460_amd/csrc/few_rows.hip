@@ -251,12 +251,15 @@ __device__ __forceinline__ float conv_output(const MidParams& mp, int t, int c) 
     return through_bf16(pre * sigmoid_fast(pre));
 }
 
-// Workgroup (head h, z): wave w owns the state row p = 4 z + w, lane l its columns n = l, l + 64, ..., which
-// stay in registers over the tokens of the call (requested first: nothing below waits for them until the first
-// update).  Per token the workgroup convolves the B and C channels of its group into LDS (every workgroup of
-// the group does: a few hundred channels against a state of P N elements), each wave the x channel of its row.
+// Workgroup (head h, sequence b, z): wave w owns the RPW state rows p = (4 z + w) RPW + rr, lane l their columns
+// n = l, l + 64, ..., which stay in registers over the tokens of the call (requested first: nothing below waits
+// for them until the first update).  Per token the workgroup convolves the B and C channels of its group into
+// LDS (every workgroup of the group does: a few hundred channels against the P N elements of a head's state --
+// which is why several sequences at once take more rows per wave and fewer workgroups), each wave the x channels
+// of its rows.
 constexpr int MID_NPL = 8;  // state columns per lane at most (N <= 512)
 
+template <int RPW>
 __global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
     extern __shared__ float bc[];  // B[0..N), C[0..N) of the group, this token
     {  // this workgroup's sequence
@@ -269,15 +272,16 @@ __global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
     }
     const int h = blockIdx.x, g = h / mp.hpg;
     const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
-    const int p = 4 * blockIdx.z + w;
-    const bool own = p < mp.P;
-    float* S = mp.state + ((int64_t)h * mp.P + (own ? p : 0)) * mp.N;
-    float s[MID_NPL];
+    const int p0 = (4 * blockIdx.z + w) * RPW;
+    float* S = mp.state + (int64_t)h * mp.P * mp.N;
+    float s[RPW][MID_NPL];
 #pragma unroll
-    for (int i = 0; i < MID_NPL; ++i) {
-        const int n = lane + 64 * i;
-        s[i] = own && n < mp.N ? S[n] : 0.f;
-    }
+    for (int rr = 0; rr < RPW; ++rr)
+#pragma unroll
+        for (int i = 0; i < MID_NPL; ++i) {
+            const int n = lane + 64 * i;
+            s[rr][i] = p0 + rr < mp.P && n < mp.N ? S[(int64_t)(p0 + rr) * mp.N + n] : 0.f;
+        }
     const float Ah = mp.A[h], Dh = mp.D[h], bias_h = mp.dt_bias[h];
     const int cB = mp.d_inner + g * mp.N, cC = mp.d_inner + (mp.G + g) * mp.N;
     for (int t = 0; t < mp.T; ++t) {
@@ -285,39 +289,84 @@ __global__ __launch_bounds__(256) void k_decode_mid(MidParams mp) {
         const float v = (float)mp.zx[t * mp.ld + mp.off_dt + h] + bias_h;
         const float dtv = through_bf16(fmaxf(v, 0.f) + log1pf(__expf(-fabsf(v))));  // softplus
         const float a = __expf(dtv * Ah);
-        const float xv = own ? conv_output(mp, t, h * mp.P + p) : 0.f;
-        __syncthreads();
-        if (own) {
-            const float dx = dtv * xv;
-            float acc = 0.f;
+        float xv[RPW];
 #pragma unroll
-            for (int i = 0; i < MID_NPL; ++i) {
-                const int n = lane + 64 * i;
-                if (n < mp.N) {
-                    s[i] = a * s[i] + dx * bc[n];
-                    acc += bc[mp.N + n] * s[i];
+        for (int rr = 0; rr < RPW; ++rr) xv[rr] = p0 + rr < mp.P ? conv_output(mp, t, h * mp.P + p0 + rr) : 0.f;
+        __syncthreads();
+#pragma unroll
+        for (int rr = 0; rr < RPW; ++rr) {
+            if (p0 + rr < mp.P) {
+                const float dx = dtv * xv[rr];
+                float acc = 0.f;
+#pragma unroll
+                for (int i = 0; i < MID_NPL; ++i) {
+                    const int n = lane + 64 * i;
+                    if (n < mp.N) {
+                        s[rr][i] = a * s[rr][i] + dx * bc[n];
+                        acc += bc[mp.N + n] * s[rr][i];
+                    }
                 }
+                acc = wave_sum(acc);
+                if (lane == 0) mp.y[(int64_t)t * mp.d_inner + h * mp.P + p0 + rr] = (__bf16)(acc + Dh * xv[rr]);
             }
-            acc = wave_sum(acc);
-            if (lane == 0) mp.y[(int64_t)t * mp.d_inner + h * mp.P + p] = (__bf16)(acc + Dh * xv);
         }
         __syncthreads();  // the next token's B and C replace these
     }
-    if (own) {
+#pragma unroll
+    for (int rr = 0; rr < RPW; ++rr)
 #pragma unroll
         for (int i = 0; i < MID_NPL; ++i) {
             const int n = lane + 64 * i;
-            if (n < mp.N) S[n] = s[i];
+            if (p0 + rr < mp.P && n < mp.N) S[(int64_t)(p0 + rr) * mp.N + n] = s[rr][i];
         }
-    }
     if (mp.cs_out) {  // the last three inputs of [entering state ; this call's tokens]
-        if (own && lane < 3) mp.cs_out[lane * mp.conv_dim + h * mp.P + p] = (__bf16)conv_input(mp, mp.T - 3 + lane, h * mp.P + p);
+        for (int i = lane; i < 3 * RPW; i += 64) {
+            const int rr = i / 3, j = i - 3 * rr;
+            if (p0 + rr < mp.P) mp.cs_out[j * mp.conv_dim + h * mp.P + p0 + rr] = (__bf16)conv_input(mp, mp.T - 3 + j, h * mp.P + p0 + rr);
+        }
         if (h % mp.hpg == 0 && blockIdx.z == 0)  // the group's B and C channels: once
             for (int i = threadIdx.x; i < 6 * mp.N; i += 256) {
                 const int j = i / (2 * mp.N), ii = i % (2 * mp.N);
                 const int c = ii < mp.N ? cB + ii : cC + (ii - mp.N);
                 mp.cs_out[j * mp.conv_dim + c] = (__bf16)conv_input(mp, mp.T - 3 + j, c);
             }
+    }
+}
+
+// One token for each of several sequences: the convolution step by itself.  A thread owns one channel of one
+// sequence -- its window of the convolution state, which it replaces in place -- and writes the activated value
+// into the dense x, B or C row of its sequence; the threads behind the channels take softplus(dt) of the heads.
+struct ConvStepParams {
+    const __bf16* zx;  // [nb, ld]
+    int64_t ld;
+    const float *conv_w, *conv_b, *dt_bias;
+    __bf16* cs;        // sequence b: [3, conv_dim] at cs + b cs_bs, replaced in place
+    int64_t cs_bs;
+    __bf16 *x, *B, *C, *dt;  // [nb, d_inner], [nb, G N], [nb, G N], [nb, H]
+    int H, d_inner, gn, conv_dim, off_xbc, off_dt;
+};
+
+__global__ __launch_bounds__(256) void k_conv_step(ConvStepParams cp) {
+    const int c = blockIdx.x * 256 + threadIdx.x, b = blockIdx.y;
+    const __bf16* zx = cp.zx + (int64_t)b * cp.ld;
+    if (c < cp.conv_dim) {
+        __bf16* cs = cp.cs + (int64_t)b * cp.cs_bs;
+        const float s0 = (float)cs[c], s1 = (float)cs[cp.conv_dim + c], s2 = (float)cs[2 * cp.conv_dim + c];
+        const __bf16 ub = zx[cp.off_xbc + c];
+        const float u = (float)ub;
+        const float* w = cp.conv_w + (int64_t)c * 4;
+        const float pre = cp.conv_b[c] + w[0] * s0 + w[1] * s1 + w[2] * s2 + w[3] * u;
+        const __bf16 o = (__bf16)(pre * sigmoid_fast(pre));
+        if (c < cp.d_inner) cp.x[(int64_t)b * cp.d_inner + c] = o;
+        else if (c < cp.d_inner + cp.gn) cp.B[(int64_t)b * cp.gn + (c - cp.d_inner)] = o;
+        else cp.C[(int64_t)b * cp.gn + (c - cp.d_inner - cp.gn)] = o;
+        cs[c] = (__bf16)s1;
+        cs[cp.conv_dim + c] = (__bf16)s2;
+        cs[2 * cp.conv_dim + c] = ub;
+    } else if (c < cp.conv_dim + cp.H) {
+        const int h = c - cp.conv_dim;
+        const float v = (float)zx[cp.off_dt + h] + cp.dt_bias[h];
+        cp.dt[(int64_t)b * cp.H + h] = (__bf16)(fmaxf(v, 0.f) + log1pf(__expf(-fabsf(v))));  // softplus
     }
 }
 
@@ -401,7 +450,41 @@ hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st) {
     mp.state_bs = j.state_bs;
     mp.cs_in_bs = j.cs_in_bs;
     mp.cs_out_bs = j.cs_out_bs;
-    hipLaunchKernelGGL(k_decode_mid, dim3(j.H, nb, (j.P + 3) / 4), dim3(256), (size_t)2 * j.N * sizeof(float), st, mp);
+    // rows per wave: one where that gives few enough workgroups (every one of them convolves its group's B and C
+    // channels), else 4 or 16
+    const size_t lds = (size_t)2 * j.N * sizeof(float);
+    auto wgs = [&](int rpw) { return (int64_t)j.H * nb * ((j.P + 4 * rpw - 1) / (4 * rpw)); };
+    if (wgs(1) <= 8192)
+        hipLaunchKernelGGL(k_decode_mid<1>, dim3(j.H, nb, (j.P + 3) / 4), dim3(256), lds, st, mp);
+    else if (wgs(4) <= 2048)
+        hipLaunchKernelGGL(k_decode_mid<4>, dim3(j.H, nb, (j.P + 15) / 16), dim3(256), lds, st, mp);
+    else
+        hipLaunchKernelGGL(k_decode_mid<16>, dim3(j.H, nb, (j.P + 63) / 64), dim3(256), lds, st, mp);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_step(const ConvStepJob& j, hipStream_t st) {
+    if (j.nb < 1 || j.nb > 65535 || j.H <= 0 || j.P <= 0 || j.G <= 0 || j.N <= 0) return hipErrorInvalidValue;
+    if (!j.zx || !j.conv_w || !j.conv_b || !j.dt_bias || !j.cs || !j.x || !j.B || !j.C || !j.dt) return hipErrorInvalidValue;
+    ConvStepParams cp;
+    cp.zx = (const __bf16*)j.zx;
+    cp.ld = j.ld;
+    cp.conv_w = j.conv_w;
+    cp.conv_b = j.conv_b;
+    cp.dt_bias = j.dt_bias;
+    cp.cs = (__bf16*)j.cs;
+    cp.cs_bs = j.cs_bs;
+    cp.x = (__bf16*)j.x;
+    cp.B = (__bf16*)j.B;
+    cp.C = (__bf16*)j.C;
+    cp.dt = (__bf16*)j.dt;
+    cp.H = j.H;
+    cp.d_inner = j.H * j.P;
+    cp.gn = j.G * j.N;
+    cp.conv_dim = cp.d_inner + 2 * cp.gn;
+    cp.off_xbc = cp.d_inner;
+    cp.off_dt = cp.d_inner + cp.conv_dim;
+    hipLaunchKernelGGL(k_conv_step, dim3((cp.conv_dim + cp.H + 255) / 256, j.nb), dim3(256), 0, st, cp);
     return hipGetLastError();
 }
 

@@ -273,5 +273,21 @@ struct DecodeMidJob {
     void* y;
 };
 hipError_t launch_decode_mid(const DecodeMidJob& j, hipStream_t st);
+// The same for one token of each of nb sequences as two kernels (many sequences: a convolution per workgroup of
+// the recurrence kernel costs more than a launch): convolution + SiLU and softplus(dt) into dense x [nb, H P],
+// B, C [nb, G N], dt [nb, H], the convolution state cs (sequence b: cs_bs elements further on) replaced in place;
+// then the recurrence on states state_bs floats apart.
+struct ConvStepJob {
+    int nb, H, P, G, N;
+    const void* zx;
+    int64_t ld;
+    const float *conv_w, *conv_b, *dt_bias;
+    void* cs;
+    int64_t cs_bs;
+    void *x, *B, *C, *dt;
+};
+hipError_t launch_conv_step(const ConvStepJob& j, hipStream_t st);
+hipError_t launch_decode_strided(int nb, int H, int P, int G, int N, const void* x, const void* dt, const float* A, const void* B,
+                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, int rows_per_wave, hipStream_t st);
 
 }  // namespace ssdk
