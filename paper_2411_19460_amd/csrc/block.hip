@@ -365,7 +365,7 @@ int forward_few(const BlockDims& d, const magc_block_shape_t* sh, const magc_blo
         cj.dt = ws + w.dt;
         BLK_HIP(launch_conv_step(cj, st));
         BLK_HIP(launch_decode_strided(sq.nb, d.H, d.P, d.G, d.N, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, sq.ssm_bs,
-                                      ws + w.y, 4, st));
+                                      ws + w.y, st));
     }
     DecodeMidJob mid;
     memset(&mid, 0, sizeof(mid));

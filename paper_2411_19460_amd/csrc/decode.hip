@@ -1,8 +1,8 @@
 // Recurrent form of the layer (Sec. 3.1, Eq. 1 in the Mamba-2 form), token by token:
 //     state <- exp(dt_t A) state + dt_t x_t (x) B_t ;   y_t = C_t state + D x_t
 // the constant-memory step that continues a sequence after a prefill (ssd_fwd's final_state).
-// Any P, N, fp32 or bf16 storage; bound by the read-modify-write of the fp32 state
-// (8 bytes per state element and token).
+// Any P, N, fp32 or bf16 storage; bound by reading and writing the fp32 state: once per call where a state
+// row fits a wave's registers (N <= 256), else once per token.
 #include "ssd_internal.h"
 
 namespace ssdk {
@@ -62,13 +62,92 @@ __global__ __launch_bounds__(256) void k_decode(DecodeParams dp) {
     }
 }
 
+// The same for N <= 64 NPL with the wave's state rows in registers over all tokens of the call: U rows per wave
+// (p = 4 z + w + 4 u gridDim.z), all of them requested before the first is used, the B and C values of a token
+// fetched once for all rows.  The state is read once and written once per call instead of once per token.
+template <typename T, int NPL, int U>
+__global__ __launch_bounds__(256) void k_decode_reg(DecodeParams dp) {
+    const int h = blockIdx.x, b = blockIdx.y, g = h / dp.hpg;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6;
+    const float Ah = dp.A[h], Dh = dp.D[h] + dp.skip_add;
+    float* S = dp.state + (int64_t)b * dp.state_bs + (int64_t)h * dp.P * dp.N;
+    const int pstep = 4 * gridDim.z, p0 = 4 * blockIdx.z + w;
+    float s[U][NPL];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int p = p0 + u * pstep, n = lane + 64 * i;
+            s[u][i] = p < dp.P && n < dp.N ? S[(int64_t)p * dp.N + n] : 0.f;
+        }
+    for (int64_t t = 0; t < dp.T; ++t) {
+        const float dtv = ld<T>(dp.dt, (int64_t)b * dp.dts_b + t * dp.H + h);
+        const bool drop = dp.reset && dp.reset[(int64_t)b * dp.T + t];
+        const float a = drop ? 0.f : __expf(dtv * Ah);
+        const int64_t bc = (int64_t)b * dp.bcs_b + (t * dp.G + g) * dp.N;
+        const int64_t xo = (int64_t)b * dp.xs_b + (t * dp.H + h) * dp.P;
+        float bv[NPL], cv[NPL];
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int n = lane + 64 * i;
+            bv[i] = n < dp.N ? ld<T>(dp.Bm, bc + n) : 0.f;
+            cv[i] = n < dp.N ? ld<T>(dp.Cm, bc + n) : 0.f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + u * pstep;
+            if (p < dp.P) {
+                const float xv = ld<T>(dp.x, xo + p);
+                const float dx = dtv * xv;
+                float acc = 0.f;
+#pragma unroll
+                for (int i = 0; i < NPL; ++i) {
+                    s[u][i] = a * s[u][i] + dx * bv[i];
+                    acc += cv[i] * s[u][i];
+                }
+                for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);
+                if (lane == 0) st<T>(dp.y, xo + p, acc + Dh * xv);
+            }
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < NPL; ++i) {
+            const int p = p0 + u * pstep, n = lane + 64 * i;
+            if (p < dp.P && n < dp.N) S[(int64_t)p * dp.N + n] = s[u][i];
+        }
+}
+
+// Picks the kernel: state rows in registers when a row fits four values per lane, several rows per wave when
+// one per wave would make more workgroups than the machine holds at a time.
+template <typename T>
+hipError_t launch_decode_kernel(const DecodeParams& dp, int nb, hipStream_t s) {
+    const int rows4 = (dp.P + 3) / 4;
+    if (dp.N <= 256) {
+        const bool many = (int64_t)dp.H * nb * rows4 > 4096;
+        const int u = many ? 4 : 1, gz = (rows4 + u - 1) / u;
+        const dim3 grid(dp.H, nb, gz);
+        if (dp.N <= 128) {
+            if (many) hipLaunchKernelGGL((k_decode_reg<T, 2, 4>), grid, dim3(256), 0, s, dp);
+            else hipLaunchKernelGGL((k_decode_reg<T, 2, 1>), grid, dim3(256), 0, s, dp);
+        } else {
+            if (many) hipLaunchKernelGGL((k_decode_reg<T, 4, 4>), grid, dim3(256), 0, s, dp);
+            else hipLaunchKernelGGL((k_decode_reg<T, 4, 1>), grid, dim3(256), 0, s, dp);
+        }
+    } else {
+        hipLaunchKernelGGL(k_decode<T>, dim3(dp.H, nb, rows4 < 64 ? rows4 : 64), dim3(256), 0, s, dp);
+    }
+    return hipGetLastError();
+}
+
 }  // namespace
 
 // One token for each of `nb` sequences whose states lie state_bs floats apart (bf16 storage): x [nb, H, P],
-// dt [nb, H], B, C [nb, G, N] dense -> y [nb, H, P].  Each wave takes `rows_per_wave` state rows in turn.
+// dt [nb, H], B, C [nb, G, N] dense -> y [nb, H, P].
 hipError_t launch_decode_strided(int nb, int H, int P, int G, int N, const void* x, const void* dt, const float* A, const void* B,
-                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, int rows_per_wave, hipStream_t st) {
-    if (nb <= 0 || nb > 65535 || H <= 0 || H > 65535 || P <= 0 || G <= 0 || N <= 0 || H % G || rows_per_wave <= 0) return hipErrorInvalidValue;
+                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, hipStream_t st) {
+    if (nb <= 0 || nb > 65535 || H <= 0 || H > 65535 || P <= 0 || G <= 0 || N <= 0 || H % G) return hipErrorInvalidValue;
     DecodeParams dp;
     dp.x = x;
     dp.dt = dt;
@@ -90,9 +169,7 @@ hipError_t launch_decode_strided(int nb, int H, int P, int G, int N, const void*
     dp.bcs_b = (int64_t)G * N;
     dp.state_bs = state_bs;
     dp.skip_add = 0.f;
-    const int per_wg = 4 * rows_per_wave, gz = (P + per_wg - 1) / per_wg;
-    hipLaunchKernelGGL(k_decode<bf16_t>, dim3(H, nb, gz < 64 ? gz : 64), dim3(256), 0, st, dp);
-    return hipGetLastError();
+    return launch_decode_kernel<bf16_t>(dp, nb, st);
 }
 
 }  // namespace ssdk
@@ -133,11 +210,6 @@ extern "C" int ssd_decode(const ssd_shape_t* sh, const void* x, const void* dt, 
     dp.state_bs = (int64_t)dp.H * dp.P * dp.N;
     dp.skip_add = (flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f;
     hipStream_t s = (hipStream_t)hip_stream;
-    const int rows4 = (dp.P + 3) / 4;
-    const dim3 grid(dp.H, (unsigned)sh->batch, rows4 < 64 ? rows4 : 64);
-    if (sh->dtype == SSD_BF16)
-        hipLaunchKernelGGL(k_decode<bf16_t>, grid, dim3(256), 0, s, dp);
-    else
-        hipLaunchKernelGGL(k_decode<float>, grid, dim3(256), 0, s, dp);
-    return hipGetLastError() == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
+    const hipError_t e = sh->dtype == SSD_BF16 ? launch_decode_kernel<bf16_t>(dp, (int)sh->batch, s) : launch_decode_kernel<float>(dp, (int)sh->batch, s);
+    return e == hipSuccess ? SSD_OK : SSD_ERR_LAUNCH;
 }

@@ -288,6 +288,6 @@ struct ConvStepJob {
 };
 hipError_t launch_conv_step(const ConvStepJob& j, hipStream_t st);
 hipError_t launch_decode_strided(int nb, int H, int P, int G, int N, const void* x, const void* dt, const float* A, const void* B,
-                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, int rows_per_wave, hipStream_t st);
+                                 const void* C, const float* D, float* state, int64_t state_bs, void* y, hipStream_t st);
 
 }  // namespace ssdk
