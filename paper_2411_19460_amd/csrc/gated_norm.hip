@@ -354,7 +354,9 @@ FastGrid fast_grid(const NormDims& d, bool bwd) {
     const int target = 256 * per_cu / d.G > 0 ? 256 * per_cu / d.G : 1;
     // fewer rows per tile when the call is short (a segment at a time), so that it still fills the machine
     g.tile_rows = bwd ? ROWS_PER_WG : ROWS_PER_WG_FWD;
-    while (g.tile_rows > 4 && (d.T + g.tile_rows - 1) / g.tile_rows < target) g.tile_rows >>= 1;
+    // (down to single rows forward -- a handful of tokens in generation; the backward pass keeps four, its
+    // partial sums of dw are per workgroup)
+    while (g.tile_rows > (bwd ? 4 : 1) && (d.T + g.tile_rows - 1) / g.tile_rows < target) g.tile_rows >>= 1;
     g.ntiles = (int)((d.T + g.tile_rows - 1) / g.tile_rows);
     if (g.ntiles <= target) {
         g.nwg = g.ntiles;
