@@ -167,9 +167,9 @@ hipError_t launch_few(const FewParams& fp, const FewOperands& fo, hipStream_t st
 // small kernel: redoing it in every wave is what would bound the kernel).
 typedef float f32x4v __attribute__((ext_vector_type(4)));
 
-template <int KS>
+template <int KS, int CG>
 __global__ __launch_bounds__(KS * 64) void k_linear_few_mfma(FewParams fp, FewOperands fo) {
-    __shared__ float part[KS][256];
+    __shared__ float part[KS][CG * 256];
     if (fo.copy_n) {
         const int i = blockIdx.x * (KS * 64) + threadIdx.x;
         if (i < fo.copy_n * fo.copy_chunks) {
@@ -178,33 +178,50 @@ __global__ __launch_bounds__(KS * 64) void k_linear_few_mfma(FewParams fp, FewOp
         }
     }
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
-    const int n0 = blockIdx.x * 16;
+    const int n0 = blockIdx.x * (16 * CG);
     const int col = lane & 15, kq = lane >> 4;  // the lane's row of x and column of w; its quarter of a 32-wide k step
-    const bool has_x = col < fp.rows, has_w = n0 + col < fp.N;
+    const bool has_x = col < fp.rows;
     const __bf16* xr = fp.x + (int64_t)col * fp.ldx;
     const __bf16* wr = fp.w + (int64_t)(n0 + col) * fp.K;
     const int nsteps = (fp.K + 31) / 32, per = (nsteps + KS - 1) / KS;
     const int s0 = wv * per, s1 = s0 + per < nsteps ? s0 + per : nsteps;
-    f32x4v acc = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll 4
-    for (int si = s0; si < s1; ++si) {
-        const int k = si * 32 + 8 * kq;  // K is a multiple of 8: a lane's eight values are inside or outside as a whole
-        bf16x8 a, b;
+    f32x4v acc[CG];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) a[e] = b[e] = (__bf16)0.f;
-        if (has_x && k < fp.K) a = *(const bf16x8*)(xr + k);
-        if (has_w && k < fp.K) b = *(const bf16x8*)(wr + k);
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, acc, 0, 0, 0);  // acc[i] = out[row 4 kq + i][column col]
+    for (int c = 0; c < CG; ++c) acc[c] = f32x4v{0.f, 0.f, 0.f, 0.f};
+    constexpr int UN = CG > 1 ? 2 : 4;  // k steps whose operands are requested together
+    for (int sb = s0; sb < s1; sb += UN) {
+        bf16x8 a[UN], b[UN][CG];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int k = (sb + u) * 32 + 8 * kq;  // K is a multiple of 8: a lane's eight values are inside or outside as a whole
+            const bool in = sb + u < s1 && k < fp.K;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) a[u][e] = (__bf16)0.f;
+            if (has_x && in) a[u] = *(const bf16x8*)(xr + k);
+#pragma unroll
+            for (int c = 0; c < CG; ++c) {
+#pragma unroll
+                for (int e = 0; e < 8; ++e) b[u][c][e] = (__bf16)0.f;
+                if (in && n0 + 16 * c + col < fp.N) b[u][c] = *(const bf16x8*)(wr + (int64_t)(16 * c) * fp.K + k);
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
+#pragma unroll
+            for (int c = 0; c < CG; ++c)  // acc[c][i] = out[row 4 kq + i][column n0 + 16 c + col]
+                acc[c] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a[u], b[u][c], acc[c], 0, 0, 0);
     }
 #pragma unroll
-    for (int i = 0; i < 4; ++i) part[wv][lane * 4 + i] = acc[i];
+    for (int c = 0; c < CG; ++c)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[wv][c * 256 + lane * 4 + i] = acc[c][i];
     __syncthreads();
-    if (threadIdx.x < 256) {
+    for (int t = threadIdx.x; t < CG * 256; t += KS * 64) {
         float v = 0.f;
 #pragma unroll
-        for (int q = 0; q < KS; ++q) v += part[q][threadIdx.x];
-        const int l = threadIdx.x >> 2, i = threadIdx.x & 3;
-        const int r = 4 * (l >> 4) + i, n = n0 + (l & 15);
+        for (int q = 0; q < KS; ++q) v += part[q][t];
+        const int c = t >> 8, l = (t & 255) >> 2, i = t & 3;
+        const int r = 4 * (l >> 4) + i, n = n0 + 16 * c + (l & 15);
         if (r < fp.rows && n < fp.N) {
             if (fp.res) v += (float)fp.res[r * fp.ldres + n];
             fp.out[r * fp.ldo + n] = (__bf16)v;
@@ -213,13 +230,17 @@ __global__ __launch_bounds__(KS * 64) void k_linear_few_mfma(FewParams fp, FewOp
 }
 
 hipError_t launch_few_mfma(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
-    const int wgs = (fp.N + 15) / 16;
-    // enough waves to keep the memory system busy: the narrower the product, the more ways k is split
-    const int ks = wgs >= 512 ? 4 : wgs >= 256 ? 8 : 16;
+    // wide products: 64 columns per workgroup (the input rows are fetched once for four column groups), k split 16
+    // ways; narrow ones: 16 columns, and the narrower the product, the more ways k is split -- enough waves either
+    // way to keep the memory system busy
+    const bool wide = fp.N >= 4096;
+    const int wgs = wide ? (fp.N + 63) / 64 : (fp.N + 15) / 16;
+    const int ks = wide ? 16 : wgs >= 1024 ? 4 : wgs >= 512 ? 8 : 16;
     if ((int64_t)wgs * ks * 64 < (int64_t)fo.copy_n * fo.copy_chunks) return hipErrorInvalidValue;
-    if (ks == 4) hipLaunchKernelGGL((k_linear_few_mfma<4>), dim3(wgs), dim3(256), 0, st, fp, fo);
-    else if (ks == 8) hipLaunchKernelGGL((k_linear_few_mfma<8>), dim3(wgs), dim3(512), 0, st, fp, fo);
-    else hipLaunchKernelGGL((k_linear_few_mfma<16>), dim3(wgs), dim3(1024), 0, st, fp, fo);
+    if (wide) hipLaunchKernelGGL((k_linear_few_mfma<16, 4>), dim3(wgs), dim3(1024), 0, st, fp, fo);
+    else if (ks == 4) hipLaunchKernelGGL((k_linear_few_mfma<4, 1>), dim3(wgs), dim3(256), 0, st, fp, fo);
+    else if (ks == 8) hipLaunchKernelGGL((k_linear_few_mfma<8, 1>), dim3(wgs), dim3(512), 0, st, fp, fo);
+    else hipLaunchKernelGGL((k_linear_few_mfma<16, 1>), dim3(wgs), dim3(1024), 0, st, fp, fo);
     return hipGetLastError();
 }
 
