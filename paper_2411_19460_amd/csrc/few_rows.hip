@@ -1,10 +1,13 @@
 // Generation: a token or a few at a time through a block (the recurrence of Sec. 3.1, Eq. 1 around which the
-// block's other steps shrink to vectors).  At these row counts the matrix cores are of no use; every kernel
-// here is bound by reading each parameter once and the SSM state twice per token, so the block's steps are
-// folded into three launches that do exactly that:
+// block's other steps shrink to vectors).  Every kernel here is bound by reading each parameter once and the
+// SSM state twice per call.  Up to four rows (a sequence on its own) the block's steps are folded into three
+// launches that do exactly that, on the vector ALUs:
 //   k_linear_few<1>  zxbcdt = RMSNorm(u) pre_norm_w W_in^T   (or plain u W_in^T)
 //   k_decode_mid     convolution + SiLU, softplus(dt), the state update and y = C h + D x, token by token
 //   k_linear_few<2>  out = RMSNorm(y silu(z)) norm_w W_out^T (+ the residual)
+// With more rows (several sequences generated together) the per-row arithmetic would bound those kernels:
+// the products then run as small MFMAs (k_linear_few_mfma), the normalisations as the library's own kernels,
+// the convolution as a step of its own (k_conv_step) in front of the recurrence kernel of decode.hip.
 #include "ssd_internal.h"
 
 namespace ssdk {
