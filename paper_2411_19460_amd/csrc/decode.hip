@@ -119,12 +119,104 @@ __global__ __launch_bounds__(256) void k_decode_reg(DecodeParams dp) {
         }
 }
 
+// Four consecutive values of B, C (storage type) as floats; 8- or 16-byte loads.
+template <typename T>
+__device__ __forceinline__ void ld4(const void* p, int64_t i, float (&v)[4]);
+template <>
+__device__ __forceinline__ void ld4<float>(const void* p, int64_t i, float (&v)[4]) {
+    const float4 t = *(const float4*)((const float*)p + i);
+    v[0] = t.x; v[1] = t.y; v[2] = t.z; v[3] = t.w;
+}
+template <>
+__device__ __forceinline__ void ld4<bf16_t>(const void* p, int64_t i, float (&v)[4]) {
+    const uint2 t = *(const uint2*)((const bf16_t*)p + i);
+    v[0] = __uint_as_float(t.x << 16); v[1] = __uint_as_float(t.x & 0xffff0000u);
+    v[2] = __uint_as_float(t.y << 16); v[3] = __uint_as_float(t.y & 0xffff0000u);
+}
+
+// The same again with 16-byte accesses to the state (N a multiple of 4, N <= 128 NV): half a wave owns a row,
+// lane l of the half the columns 4 l .. 4 l + 3 (+ 128 i); a wave walks U pairs of rows.
+template <typename T, int NV, int U>
+__global__ __launch_bounds__(256) void k_decode_reg4(DecodeParams dp) {
+    const int h = blockIdx.x, b = blockIdx.y, g = h / dp.hpg;
+    const int lane = threadIdx.x & 63, w = threadIdx.x >> 6, half = lane >> 5, l32 = lane & 31;
+    const float Ah = dp.A[h], Dh = dp.D[h] + dp.skip_add;
+    float* S = dp.state + (int64_t)b * dp.state_bs + (int64_t)h * dp.P * dp.N;
+    const int p0 = (4 * blockIdx.z + w) * 2 * U + half;  // rows p0, p0 + 2, ...
+    float4 s[U][NV];
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int p = p0 + 2 * u, n = 4 * l32 + 128 * i;
+            s[u][i] = p < dp.P && n < dp.N ? *(const float4*)(S + (int64_t)p * dp.N + n) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+    for (int64_t t = 0; t < dp.T; ++t) {
+        const float dtv = ld<T>(dp.dt, (int64_t)b * dp.dts_b + t * dp.H + h);
+        const bool drop = dp.reset && dp.reset[(int64_t)b * dp.T + t];
+        const float a = drop ? 0.f : __expf(dtv * Ah);
+        const int64_t bc = (int64_t)b * dp.bcs_b + (t * dp.G + g) * dp.N;
+        const int64_t xo = (int64_t)b * dp.xs_b + (t * dp.H + h) * dp.P;
+        float bv[NV][4], cv[NV][4];
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int n = 4 * l32 + 128 * i;
+            if (n < dp.N) {
+                ld4<T>(dp.Bm, bc + n, bv[i]);
+                ld4<T>(dp.Cm, bc + n, cv[i]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) bv[i][e] = cv[i][e] = 0.f;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int p = p0 + 2 * u;
+            const bool live = p < dp.P;
+            const float xv = live ? ld<T>(dp.x, xo + p) : 0.f;
+            const float dx = dtv * xv;
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < NV; ++i) {
+                s[u][i].x = a * s[u][i].x + dx * bv[i][0];
+                s[u][i].y = a * s[u][i].y + dx * bv[i][1];
+                s[u][i].z = a * s[u][i].z + dx * bv[i][2];
+                s[u][i].w = a * s[u][i].w + dx * bv[i][3];
+                acc += cv[i][0] * s[u][i].x + cv[i][1] * s[u][i].y + cv[i][2] * s[u][i].z + cv[i][3] * s[u][i].w;
+            }
+            for (int off = 16; off > 0; off >>= 1) acc += __shfl_xor(acc, off, 64);  // within the half wave
+            if (live && l32 == 0) st<T>(dp.y, xo + p, acc + Dh * xv);
+        }
+    }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int i = 0; i < NV; ++i) {
+            const int p = p0 + 2 * u, n = 4 * l32 + 128 * i;
+            if (p < dp.P && n < dp.N) *(float4*)(S + (int64_t)p * dp.N + n) = s[u][i];
+        }
+}
+
 // Picks the kernel: state rows in registers when a row fits four values per lane, several rows per wave when
 // one per wave would make more workgroups than the machine holds at a time.
 template <typename T>
 hipError_t launch_decode_kernel(const DecodeParams& dp, int nb, hipStream_t s) {
     const int rows4 = (dp.P + 3) / 4;
-    if (dp.N <= 256) {
+    const bool vec_ok = dp.N % 4 == 0 && ((uintptr_t)dp.state & 15) == 0 && dp.state_bs % 4 == 0 && ((uintptr_t)dp.Bm & 15) == 0 &&
+                        ((uintptr_t)dp.Cm & 15) == 0 && dp.bcs_b % 4 == 0;
+    if (dp.N <= 256 && vec_ok) {  // 16-byte state accesses
+        const int rows8 = (dp.P + 7) / 8;
+        const bool many = (int64_t)dp.H * nb * rows8 > 4096;
+        const int u = many ? 4 : 1, gz = (rows8 + u - 1) / u;
+        const dim3 grid(dp.H, nb, gz);
+        if (dp.N <= 128) {
+            if (many) hipLaunchKernelGGL((k_decode_reg4<T, 1, 4>), grid, dim3(256), 0, s, dp);
+            else hipLaunchKernelGGL((k_decode_reg4<T, 1, 1>), grid, dim3(256), 0, s, dp);
+        } else {
+            if (many) hipLaunchKernelGGL((k_decode_reg4<T, 2, 4>), grid, dim3(256), 0, s, dp);
+            else hipLaunchKernelGGL((k_decode_reg4<T, 2, 1>), grid, dim3(256), 0, s, dp);
+        }
+    } else if (dp.N <= 256) {
         const bool many = (int64_t)dp.H * nb * rows4 > 4096;
         const int u = many ? 4 : 1, gz = (rows4 + u - 1) / u;
         const dim3 grid(dp.H, nb, gz);
