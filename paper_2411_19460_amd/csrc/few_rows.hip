@@ -98,8 +98,12 @@ struct FewStep {
     }
 };
 
-template <int MODE, int R, int CPW>
+// KS waves of a workgroup share a wave's columns and take every KS-th k step each (a wave that walks all of a
+// long row alone waits for one load after the other: more, shorter waves keep more bytes in flight); their
+// partial sums meet in LDS.
+template <int MODE, int R, int CPW, int KS>
 __global__ __launch_bounds__(256) void k_linear_few(FewParams fp, FewOperands fo) {
+    __shared__ float red[4][R * (CPW + 1)];
     if (fo.copy_n) {
         const int i = blockIdx.x * 256 + threadIdx.x;
         if (i < fo.copy_n * fo.copy_chunks) {
@@ -107,9 +111,10 @@ __global__ __launch_bounds__(256) void k_linear_few(FewParams fp, FewOperands fo
             ((f32x4*)fo.copy_dst)[c * fo.copy_dst_stride + v] = ((const f32x4*)fo.copy_src)[c * fo.copy_src_stride + v];
         }
     }
-    const int lane = threadIdx.x & 63;
-    const int n0 = (blockIdx.x * 4 + (threadIdx.x >> 6)) * CPW;
-    if (n0 >= fp.N) return;  // whole waves leave; the kernel has no barrier
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int slot = wv / KS, kp = wv % KS;  // which columns of the workgroup, which share of k
+    const int n0 = (blockIdx.x * (4 / KS) + slot) * CPW;
+    const bool live = n0 < fp.N;
     float acc[R][CPW], ss[R];
 #pragma unroll
     for (int r = 0; r < R; ++r) {
@@ -119,48 +124,84 @@ __global__ __launch_bounds__(256) void k_linear_few(FewParams fp, FewOperands fo
     }
     const __bf16* w0 = fp.w + (int64_t)n0 * fp.K;
     constexpr bool TWO = R <= 4;
-    for (int k = lane * 8; k < fp.K; k += TWO ? 1024 : 512) {
-        FewStep<MODE, R, CPW> a, b;
-        const bool two = TWO && k + 512 < fp.K;
-        a.load(fp, w0, k);
-        if (two) b.load(fp, w0, k + 512);
-        a.use(fp, acc, ss);
-        if (two) b.use(fp, acc, ss);
+    constexpr int STEP = 512 * KS;  // k between a wave's consecutive steps
+    if (live) {
+        for (int k = lane * 8 + 512 * kp; k < fp.K; k += TWO ? 2 * STEP : STEP) {
+            FewStep<MODE, R, CPW> a, b;
+            const bool two = TWO && k + STEP < fp.K;
+            a.load(fp, w0, k);
+            if (two) b.load(fp, w0, k + STEP);
+            a.use(fp, acc, ss);
+            if (two) b.use(fp, acc, ss);
+        }
     }
 #pragma unroll
     for (int r = 0; r < R; ++r) {
+        if (MODE) ss[r] = wave_sum(ss[r]);
+#pragma unroll
+        for (int c = 0; c < CPW; ++c) acc[r][c] = wave_sum(acc[r][c]);
+    }
+    if (KS > 1) {
+        if (lane == 0) {
+#pragma unroll
+            for (int r = 0; r < R; ++r) {
+                red[wv][r * (CPW + 1) + CPW] = ss[r];
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) red[wv][r * (CPW + 1) + c] = acc[r][c];
+            }
+        }
+        __syncthreads();
+        if (kp != 0) return;
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            ss[r] = 0.f;
+#pragma unroll
+            for (int c = 0; c < CPW; ++c) acc[r][c] = 0.f;
+#pragma unroll
+            for (int q = 0; q < KS; ++q) {  // fixed order: the result does not depend on which wave finished first
+                ss[r] += red[slot * KS + q][r * (CPW + 1) + CPW];
+#pragma unroll
+                for (int c = 0; c < CPW; ++c) acc[r][c] += red[slot * KS + q][r * (CPW + 1) + c];
+            }
+        }
+    }
+    if (!live || lane != 0) return;
+#pragma unroll
+    for (int r = 0; r < R; ++r) {
         if (r < fp.rows) {
-            const float rstd = MODE ? rsqrtf(wave_sum(ss[r]) / (float)fp.K + fp.eps) : 1.f;
+            const float rstd = MODE ? rsqrtf(ss[r] / (float)fp.K + fp.eps) : 1.f;
 #pragma unroll
             for (int c = 0; c < CPW; ++c) {
-                float v = wave_sum(acc[r][c]) * rstd;
-                if (lane == 0) {
-                    if (fp.res) v += (float)fp.res[r * fp.ldres + n0 + c];
-                    fp.out[r * fp.ldo + n0 + c] = (__bf16)v;
-                }
+                float v = acc[r][c] * rstd;
+                if (fp.res) v += (float)fp.res[r * fp.ldres + n0 + c];
+                fp.out[r * fp.ldo + n0 + c] = (__bf16)v;
             }
         }
     }
 }
 
-template <int MODE, int CPW>
-hipError_t launch_few_c(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
-    const int waves = (fp.N + CPW - 1) / CPW;
-    const dim3 grid((unsigned)((waves + 3) / 4)), block(256);
+template <int MODE, int CPW, int KS>
+hipError_t launch_few_ck(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
+    const int slots = (fp.N + CPW - 1) / CPW;  // groups of CPW columns
+    const dim3 grid((unsigned)((slots + 4 / KS - 1) / (4 / KS))), block(256);
     if ((int64_t)grid.x * 256 < (int64_t)fo.copy_n * fo.copy_chunks) return hipErrorInvalidValue;
-    if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1, CPW>), grid, block, 0, st, fp, fo);
-    else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2, CPW>), grid, block, 0, st, fp, fo);
-    else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4, CPW>), grid, block, 0, st, fp, fo);
-    else if (fp.rows <= 8) hipLaunchKernelGGL((k_linear_few<MODE, 8, CPW>), grid, block, 0, st, fp, fo);
-    else hipLaunchKernelGGL((k_linear_few<MODE, 16, CPW>), grid, block, 0, st, fp, fo);
+    if (fp.rows <= 1) hipLaunchKernelGGL((k_linear_few<MODE, 1, CPW, KS>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 2) hipLaunchKernelGGL((k_linear_few<MODE, 2, CPW, KS>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 4) hipLaunchKernelGGL((k_linear_few<MODE, 4, CPW, KS>), grid, block, 0, st, fp, fo);
+    else if (fp.rows <= 8) hipLaunchKernelGGL((k_linear_few<MODE, 8, CPW, KS>), grid, block, 0, st, fp, fo);
+    else hipLaunchKernelGGL((k_linear_few<MODE, 16, CPW, KS>), grid, block, 0, st, fp, fo);
     return hipGetLastError();
 }
 
-// two columns per wave share the fetched (and transformed) input rows; narrow products take one column per
-// wave instead so that there are enough waves to keep the memory system busy
+// Long rows (the block's two products): four columns per wave share the fetched (and transformed) input rows --
+// with one column per wave the input rows, re-read by every wave, are more cache traffic than the weights --
+// and k is split over the four waves of the workgroup, which keeps as many waves as there are columns.  Short
+// rows: no split.
 template <int MODE>
 hipError_t launch_few(const FewParams& fp, const FewOperands& fo, hipStream_t st) {
-    return fp.N >= 8192 ? launch_few_c<MODE, 2>(fp, fo, st) : launch_few_c<MODE, 1>(fp, fo, st);
+    if (fp.N >= 8192) return fp.K >= 2048 ? launch_few_ck<MODE, 4, 4>(fp, fo, st) : launch_few_ck<MODE, 2, 1>(fp, fo, st);
+    if (fp.N >= 4096) return fp.K >= 2048 ? launch_few_ck<MODE, 1, 2>(fp, fo, st) : launch_few_ck<MODE, 1, 1>(fp, fo, st);
+    return fp.K >= 2048 ? launch_few_ck<MODE, 4, 4>(fp, fo, st) : launch_few_ck<MODE, 1, 1>(fp, fo, st);
 }
 
 // More than a few rows (several sequences generated together): the same product on the matrix cores.  A
