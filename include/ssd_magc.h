@@ -290,7 +290,8 @@ int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  *           W_in^T; the normalised input is recomputed per segment, never kept.  grads.dpre_norm_w is then needed.
  *   grads:  the same shapes, all fp32, overwritten or added to under SSD_FLAG_ACCUM_PARAM (the only flag)
  *   workspace: magc_block_workspace_bytes bytes, 256-byte aligned; scales with `segment`, not seqlen
- * d_model, d_inner, G N and H must be multiples of 8 (SSD_ERR_DIVISIBILITY), segment a multiple of chunk;
+ * d_model, d_inner, G N and H must be multiples of 8 (SSD_ERR_DIVISIBILITY), segment a multiple of chunk,
+ * headdim and dstate at most 256, chunk at most 1024 (SSD_ERR_SHAPE: the scan's limits);
  * seqlen is arbitrary.  Everything is enqueued on hip_stream; nothing is allocated.  Errors as elsewhere.
  */
 typedef struct {
@@ -382,7 +383,8 @@ int magc_blockstack_infer(const magc_blockstack_shape_t* shape, const magc_block
  *   ssm_state [nseq, nlayers, H, P, N] fp32, conv_state [nseq, nlayers, 3, d_inner + 2 G N] bf16: sequence-major,
  *   so the slice of one sequence is exactly what magc_blockstack_infer keeps for it (prefill each sequence with
  *   that call, or start from zeros); read and replaced in place.
- * block.seqlen and layer_interval are ignored; workspace as for magc_blockstack_infer.  Same stream rules.
+ * block.seqlen and layer_interval are ignored; workspace: magc_blockstack_workspace_bytes(shape, 0) of the shape
+ * with block.seqlen = 1, 256-byte aligned.  Same stream rules as magc_blockstack_infer.
  */
 int magc_blockstack_decode(const magc_blockstack_shape_t* shape, const magc_block_params_t* params, int32_t nseq,
                            const void* x0, void* out, float* ssm_state, void* conv_state, void* workspace,

@@ -592,6 +592,7 @@ def magc_blockstack_decode(x, layers, nheads, headdim, ngroups, dstate, chunk, s
     and conv_state [nseq, NL, 3, conv_dim] bf16 are updated in place.  Returns dict(out, workspace)."""
     import torch
     sshape, pars, _, _, conv_dim = _blockstack_setup(x, layers, nheads, headdim, ngroups, dstate, chunk, segment, 1, eps)
+    sshape.block.seqlen = 1      # a token per sequence: the shape the workspace is sized for
     dev, NL, nseq = x.device, len(layers), x.shape[0]
     for t, shp, dty in ((ssm_state, (nseq, NL, nheads, headdim, dstate), torch.float32), (conv_state, (nseq, NL, 3, conv_dim), torch.bfloat16)):
         if tuple(t.shape) != shp or t.dtype != dty or not t.is_cuda or not t.is_contiguous():

@@ -87,6 +87,7 @@ int check(const magc_block_shape_t* sh, BlockDims* d) {
     if (sh->nheads % sh->ngroups) return SSD_ERR_DIVISIBILITY;
     if (sh->segment % sh->chunk) return SSD_ERR_DIVISIBILITY;
     if (!(sh->eps >= 0.f)) return SSD_ERR_ARG;
+    if (sh->chunk > 1024 || sh->headdim > 256 || sh->dstate > 256) return SSD_ERR_SHAPE;  // the limits of the scan
     d->L = sh->seqlen;
     d->s = sh->segment;
     d->nseg = sh->seqlen > 0 ? (sh->seqlen + sh->segment - 1) / sh->segment : 0;
@@ -943,9 +944,13 @@ extern "C" int magc_blockstack_infer(const magc_blockstack_shape_t* sh, const ma
 }
 
 // One generation step for several independent sequences at once: every parameter is read once for all of them.
-extern "C" int magc_blockstack_decode(const magc_blockstack_shape_t* sh, const magc_block_params_t* params, int32_t nseq, const void* x0,
+extern "C" int magc_blockstack_decode(const magc_blockstack_shape_t* sh_in, const magc_block_params_t* params, int32_t nseq, const void* x0,
                                       void* out, float* ssm_state, void* conv_state, void* workspace, size_t workspace_bytes,
                                       void* hip_stream) {
+    if (!sh_in) return SSD_ERR_NULL;
+    magc_blockstack_shape_t one = *sh_in;  // a token per sequence whatever block.seqlen says: sizes the workspace
+    one.block.seqlen = 1;
+    const magc_blockstack_shape_t* sh = &one;
     StackDims d;
     BLK_TRY(check_stack(sh, &d));
     if (nseq < 0 || nseq > FEW_ROWS) return SSD_ERR_SHAPE;
@@ -965,8 +970,6 @@ extern "C" int magc_blockstack_decode(const magc_blockstack_shape_t* sh, const m
     bool batched = nseq <= d.b.s;  // the rows of all sequences fit the buffers of one segment
     for (int j = 0; j < d.NL && batched; ++j) batched = few_path(dc, &params[j], nseq, ssm_state, x0, out);
     if (!batched) {  // shapes or alignments the generation kernels do not take: sequence by sequence
-        magc_blockstack_shape_t one = *sh;
-        one.block.seqlen = 1;
         for (int b = 0; b < nseq; ++b)
             BLK_TRY(magc_blockstack_infer(&one, params, (const char*)x0 + b * row, (char*)out + b * row, ssm_state + (size_t)b * d.NL * d.b.HPN,
                                           (char*)conv_state + (size_t)b * d.NL * d.conv_state, 0, workspace, workspace_bytes, hip_stream));

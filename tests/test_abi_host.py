@@ -142,6 +142,9 @@ def test_block_pieces_validate_before_any_launch():
     assert L.magc_block_workspace_bytes(ctypes.byref(bs), 0) < w_seg
     assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 4, 64, 1, 128, 256, 1e-5, 1024, 512)), 1) == 0   # H % 8
     assert L.magc_block_workspace_bytes(ctypes.byref(binding.magc_block_shape_t(2560, 80, 64, 1, 128, 256, 1e-5, 1024, 300)), 1) == 0  # segment % chunk
+    wide = binding.magc_block_shape_t(64, 8, 8, 1, 520, 64, 1e-5, 70, 128)                               # state wider than the scan takes
+    assert L.magc_block_workspace_bytes(ctypes.byref(wide), 0) == 0
+    assert L.magc_block_fwd(ctypes.byref(wide), None, fake, None, None, fake, None, None, None, None, fake, 1 << 40, None) == ERR_SHAPE
     par, gr = binding.magc_block_params_t(), binding.magc_block_grads_t()
     assert L.magc_block_fwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, fake, fake, None, None, fake, 1 << 40, None) == ERR_NULL
     assert L.magc_block_bwd(ctypes.byref(bs), ctypes.byref(par), fake, None, None, fake, None, None, fake, fake, fake, ctypes.byref(gr), None, None, fake, 1 << 40, 0, None) \

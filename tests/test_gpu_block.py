@@ -277,7 +277,8 @@ def test_stack_generation_from_the_first_token(shape):
         check(f"layer {j} conv state", host(st["conv_state"][j]), fo["conv_states"][j], tol)
 
 
-@pytest.mark.parametrize("shape", [(128, 8, 64, 1, 128, 128, True, 5), (128, 8, 64, 2, 128, 128, False, 16), (64, 8, 16, 1, 16, 64, True, 3)])
+@pytest.mark.parametrize("shape", [(128, 8, 64, 1, 128, 128, True, 5), (128, 8, 64, 2, 128, 128, False, 16), (64, 8, 16, 1, 16, 64, True, 3),
+                                   (64, 8, 16, 1, 16, 4, True, 16)])     # more sequences than a segment has rows: sequence by sequence
 def test_stack_generation_for_several_sequences_at_once(shape):
     # sequences of different lengths, each prefilled on its own, then generated together one token per step:
     # every sequence against the oracle run over that sequence alone (sixteen sequences of the wide-state shape:
