@@ -268,10 +268,10 @@ int seg_mid(const BlockDims& d, const magc_block_params_t* p, char* ws, const Bl
 }
 
 int seg_scan(const BlockDims& d, const magc_block_params_t* p, char* ws, const BlockWs& w, int64_t rows, const float* ssm_in,
-             float* ssm_out, char* y, hipStream_t st) {
+             float* ssm_out, char* y, hipStream_t st, bool recur_ok = false) {
     const ssd_shape_t ss = seg_shape(d, rows);
-    if (rows <= DECODE_ROWS && ssm_out) {
-        // a few tokens (generation): the recurrence token by token on the state itself instead of a padded chunk
+    if (recur_ok && rows <= DECODE_ROWS && ssm_out) {
+        // a few tokens (inference only: see block_fwd): the recurrence token by token on the state itself instead of a padded chunk
         if (ssm_in != ssm_out)
             BLK_HIP(ssm_in ? launch_copy_f32(ssm_out, ssm_in, d.HPN, st) : launch_fill_zero(ssm_out, d.HPN, st));
         return ssd_decode(&ss, ws + w.x, ws + w.dt, p->A, ws + w.B, ws + w.C, p->D, ssm_out, y, 0, st);
@@ -288,10 +288,10 @@ int seg_norm(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_
 // All of them: everything up to y and the normalised y, from the two states entering the segment.
 int forward_segment(const BlockDims& d, const magc_block_shape_t* sh, const magc_block_params_t* p, char* ws, const BlockWs& w,
                     char* zx, char* y, const void* u_seg, int64_t rows, const float* ssm_in, const void* conv_in, float* ssm_out,
-                    void* conv_out, hipStream_t st) {
+                    void* conv_out, hipStream_t st, bool recur_ok = false) {
     BLK_TRY(seg_in_proj(d, sh->eps, p, ws, w, u_seg, rows, zx, st));
     BLK_TRY(seg_mid(d, p, ws, w, zx, rows, conv_in, conv_out, st));
-    BLK_TRY(seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, y, st));
+    BLK_TRY(seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, y, st, recur_ok));
     BLK_TRY(seg_norm(d, sh, p, ws, w, zx, y, rows, st));
     return SSD_OK;
 }
@@ -494,9 +494,12 @@ extern "C" size_t magc_block_workspace_bytes(const magc_block_shape_t* sh, int32
     return layout(d, is_backward != 0).total;
 }
 
-extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
-                              const void* init_conv, void* out, float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv,
-                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+// few_ok: calls of a few tokens may take the generation kernels.  Not while a training pass records checkpoints:
+// those kernels round at other places than the chunked path that the backward pass recomputes the segment with,
+// and the result would depend (in its last bits) on how the sequence is cut into segments.
+static int block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
+                     const void* init_conv, void* out, float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv,
+                     void* workspace, size_t workspace_bytes, bool few_ok, void* hip_stream) {
     BlockDims d;
     BLK_TRY(check(sh, &d));
     if (!p || !p->W_in || !p->conv_w || !p->conv_b || !p->dt_bias || !p->A || !p->D || !p->norm_w || !p->W_out) return SSD_ERR_NULL;
@@ -518,7 +521,7 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
     // each other, and either alone leaves compute units idle (4096 rows: 160 and 672 tiles for 256 units), so
     // the output projection goes to the library's side stream while the caller's stream runs ahead.
     const int64_t tail_rows = d.L - (d.nseg - 1) * d.s;
-    SideStream* side = d.nseg > 1 && tail_rows > FEW_ROWS ? side_stream() : nullptr;
+    SideStream* side = d.nseg > 1 && (tail_rows > FEW_ROWS || !few_ok) ? side_stream() : nullptr;
     bool side_busy = false;
     auto join_side = [&]() -> bool {  // the caller's stream waits for what the side stream was given
         if (!side_busy) return true;
@@ -535,19 +538,19 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
         void* conv_out = last ? final_conv : conv_ckpt ? (char*)conv_ckpt + (size_t)(k + 1) * conv_state_bytes : ws + w.cconv[(k + 1) & 1];
         const char* u_seg = (const char*)u + (size_t)t0 * d.dm * 2;
         char* out_seg = (char*)out + (size_t)t0 * d.dm * 2;
-        if (few_path(d, p, rows, ssm_out, u_seg, out_seg) && (!conv_out || conv_out != conv_in)) {
+        if (few_ok && few_path(d, p, rows, ssm_out, u_seg, out_seg) && (!conv_out || conv_out != conv_in)) {
             BLK_TRY(forward_few(d, sh, p, ws, w, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, out_seg, nullptr, FewSeqs(), st));
             continue;
         }
         if (!side) {
-            BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st));
+            BLK_TRY(forward_segment(d, sh, p, ws, w, ws + w.zx, ws + w.y, u_seg, rows, ssm_in, conv_in, ssm_out, conv_out, st, few_ok));
             BLK_TRY(ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, st));
             continue;
         }
         int rc = SSD_OK;
         if (k == 0) rc = seg_in_proj(d, sh->eps, p, ws, w, u_seg, rows, ws + w.zx, st);  // later ones were issued a segment ahead
         if (rc == SSD_OK) rc = seg_mid(d, p, ws, w, ws + w.zx, rows, conv_in, conv_out, st);
-        if (rc == SSD_OK) rc = seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, ws + w.y, st);
+        if (rc == SSD_OK) rc = seg_scan(d, p, ws, w, rows, ssm_in, ssm_out, ws + w.y, st, few_ok);
         if (!join_side() && rc == SSD_OK) rc = SSD_ERR_LAUNCH;  // the last output projection has read the normalised y
         if (rc == SSD_OK) rc = seg_norm(d, sh, p, ws, w, ws + w.zx, ws + w.y, rows, st);
         if (rc != SSD_OK) return rc;
@@ -568,6 +571,14 @@ extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_par
     }
     if (!join_side()) return SSD_ERR_LAUNCH;
     return SSD_OK;
+}
+
+extern "C" int magc_block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
+                              const void* init_conv, void* out, float* ssm_ckpt, void* conv_ckpt, float* final_ssm, void* final_conv,
+                              void* workspace, size_t workspace_bytes, void* hip_stream) {
+    // no checkpoint store: inference (prefill, generation)
+    return block_fwd(sh, p, u, init_ssm, init_conv, out, ssm_ckpt, conv_ckpt, final_ssm, final_conv, workspace, workspace_bytes,
+                     ssm_ckpt == nullptr, hip_stream);
 }
 
 extern "C" int magc_block_bwd(const magc_block_shape_t* sh, const magc_block_params_t* p, const void* u, const float* init_ssm,
@@ -779,8 +790,8 @@ extern "C" int magc_blockstack_fwd(const magc_blockstack_shape_t* sh, const magc
             float* ssm_out = last ? (float*)(ws + w.fin_ssm) : sj + (size_t)(k + 1) * d.b.HPN;
             void* conv_out = last ? (void*)(ws + w.fin_conv) : (void*)(cj + (size_t)(k + 1) * d.conv_state);
             char* y = ws + w.act[j & 1];
-            BLK_TRY(magc_block_fwd(&c, &params[j], cur, ssm_in, conv_in, y, nullptr, nullptr, ssm_out, conv_out, ws + w.inner,
-                                   w.inner_bytes, st));
+            BLK_TRY(block_fwd(&c, &params[j], cur, ssm_in, conv_in, y, nullptr, nullptr, ssm_out, conv_out, ws + w.inner, w.inner_bytes,
+                              false, st));
             char* nxt = j + 1 == d.NL ? (char*)out + (size_t)t0 * row : y;  // x_{j+1} = x_j + Block_j(x_j)
             BLK_HIP(add_bf16(nxt, cur, y, rows * d.b.dm, st));
             cur = nxt;

@@ -51,6 +51,7 @@ GRADS = ("dW_in", "dconv_w", "dconv_b", "ddt_bias", "dA", "dD", "dnorm_w", "dW_o
     (700, 128, 8, 64, 2, 128, 256, 256),      # two groups; ragged: the last segment has 188 tokens
     (300, 64, 8, 16, 1, 16, 64, 128),         # small heads and states: the scan's shape-generic kernels
     (1536, 2560, 80, 64, 1, 128, 256, 1024),  # the 2.7B block at its real widths (10576-wide projection), 1.5 segments
+    (517, 128, 8, 64, 1, 128, 128, 256),      # a last segment of five tokens: forward takes the generation kernels, backward recomputes it as a chunk
 ])
 def test_block_forward_backward(case):
     L, dm, H, P, G, N, Q, seg = case
