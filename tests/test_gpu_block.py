@@ -318,6 +318,46 @@ def test_stack_generation_for_several_sequences_at_once(shape):
             check(f"sequence {i} layer {j} conv state", host(conv[i, j]), fo["conv_states"][j], tol)
 
 
+def test_generation_step_replays_as_a_graph():
+    """A generation step enqueues kernels only (no memset, no allocation with buffers given, one stream): captured
+    once, each replay advances the sequence by the token in the static input buffer exactly as an eager call does."""
+    NL, L0, ngen = 2, 100, 4
+    dm, H, P, G, N, Q, seg = 128, 8, 64, 1, 128, 128, 256
+    ds = [draw(50 + j, L0 + ngen, dm, H, P, G, N, True) for j in range(NL)]
+    layers = [to_dev(x["p"]) for x in ds]
+    x = dev_bf16(ds[0]["u"])
+    st = pk.magc_blockstack_infer(x[:L0].contiguous(), layers, H, P, G, N, Q, seg)
+    ssm0, conv0 = st["ssm_state"].clone(), st["conv_state"].clone()
+    # eager reference: one call per token from copies of the states
+    ssm, conv, want, ws = ssm0.clone(), conv0.clone(), [], None
+    for t in range(ngen):
+        o = pk.magc_blockstack_infer(x[L0 + t:L0 + t + 1].contiguous(), layers, H, P, G, N, Q, seg, ssm_state=ssm, conv_state=conv, workspace=ws)
+        ws = o["workspace"]
+        want.append(o["out"].clone())
+    torch.cuda.synchronize()
+    want_ssm, want_conv = ssm.clone(), conv.clone()
+    # the same step captured once on static buffers
+    ssm.copy_(ssm0)
+    conv.copy_(conv0)
+    tok, out = torch.empty((1, dm), dtype=torch.bfloat16, device="cuda"), torch.empty((1, dm), dtype=torch.bfloat16, device="cuda")
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            pk.magc_blockstack_infer(tok, layers, H, P, G, N, Q, seg, ssm_state=ssm, conv_state=conv, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    scratch = torch.zeros(1 << 16, device="cuda")
+    for t in range(ngen):
+        tok.copy_(x[L0 + t:L0 + t + 1])
+        scratch.add_(1.0)                     # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want[t]), t
+    assert torch.equal(ssm, want_ssm) and torch.equal(conv, want_conv)
+
+
 def test_block_rejects_bad_shapes():
     u = torch.zeros((64, 64), dtype=torch.bfloat16, device="cuda")
     d = draw(2, 64, 64, 4, 16, 1, 16)       # four heads: the projection's width is not a multiple of 8
