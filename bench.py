@@ -359,6 +359,23 @@ def block_bench(args, cfg, pk, torch, dev):
             generate()
             torch.cuda.synchronize()
             us_tok = (time.perf_counter() - t0) * 1e6 / ntok
+            # the same step captured once in a graph and replayed (it enqueues kernels only)
+            graph = torch.cuda.CUDAGraph()
+            cap = torch.cuda.Stream()
+            cap.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(cap):
+                with torch.cuda.graph(graph, stream=cap):
+                    rc = pk.lib().magc_blockstack_infer(ctypes.byref(one), pars, tok.data_ptr(), tok.data_ptr(), st["ssm_state"].data_ptr(),
+                                                        st["conv_state"].data_ptr(), 0, ws.data_ptr(), ws.numel(), cap.cuda_stream)
+                    assert rc == 0, rc
+            torch.cuda.synchronize()
+            for rep in range(2):
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(ntok):
+                    graph.replay()
+                torch.cuda.synchronize()
+                us_tok_graph = (time.perf_counter() - t0) * 1e6 / ntok
             # the same step for sixteen sequences at once: the parameters are read once for all of them
             nseq = 16
             ssm16 = torch.zeros((nseq, NL, H, P, N), dtype=torch.float32, device=dev)
@@ -387,6 +404,7 @@ def block_bench(args, cfg, pk, torch, dev):
                              "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                              "frac": 2.0 * (dm * d_in_proj + d_inner * dm) * NL * L / (ms_p * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, "traffic": None},
                 "generation": {"us_per_token": us_tok, "us_per_token_per_layer": us_tok / NL, "tokens": ntok,
+                               "us_per_token_graph_replay": us_tok_graph,
                                "weights_and_states_bytes_per_token": wbytes + 2 * NL * H * P * N * 4,
                                "hbm_floor_us": (wbytes + 2 * NL * H * P * N * 4) / HBM_PEAK_GBS / 1e3,
                                "note": "one C call per token; every parameter read once and every SSM state read and written once per token"},
