@@ -31,6 +31,7 @@ def main():
     ap.add_argument("--max-log2", type=int, default=20)
     ap.add_argument("--step-log2", type=int, default=2)
     ap.add_argument("--budget-gb", type=float, default=200.0)
+    ap.add_argument("--pareto", default="", help="with --blocks: comma-separated memory budgets in GB; runs the planner's budget mode for each instead of the three grids")
     ap.add_argument("--pre-norm", action="store_true", help="with --blocks: every block starts with an RMS normalisation of its input")
     ap.add_argument("--blocks", action="store_true",
                     help="whole Mamba-2 blocks (projections, convolution, scan, gated norm) instead of bare SSD layers")
@@ -162,11 +163,20 @@ def blocks_sweep(args):
         rc, plan = pk.magc_plan(nl, S, c_l, c_s, c_grid, c_state, s_multiple=Q, integer_counts=True)
         s_plan = min(S, max(Q, 1 << int(round(math.log2(plan["s"])))))
         grids = [("per-layer", 1, S), ("sqrt-L", max(1, int(round(math.sqrt(nl)))), S), ("MA-GC", plan["l"], s_plan)]
+        if args.pareto:
+            # the planner's other mode: for each memory budget the grid with the least recomputation that fits
+            # (largest s, then largest l) -- the time / memory trade-off between the minimum-memory grid and no
+            # sequence checkpoints at all
+            grids = [("MA-GC min", plan["l"], plan["s"])]
+            for gb in (float(v) for v in args.pareto.split(",")):
+                rcb, pb = pk.magc_plan(nl, S, c_l, c_s, c_grid, c_state, s_multiple=Q, budget=gb * 1e9, integer_counts=True)
+                if rcb == 0:
+                    grids.append((f"budget {gb:g} GB", pb["l"], pb["s"]))
         x0 = dout = None
         for name, l, s in grids:
             sh = sshape(S, s, l)
             ngl = (nl + l - 1) // l
-            ckpt = nl * (S // s) * c_s + (ngl - 1) * S * c_l
+            ckpt = nl * -(-S // s) * c_s + (ngl - 1) * S * c_l
             ws = max(int(pk.lib().magc_blockstack_workspace_bytes(ctypes.byref(sh), 0)), int(pk.lib().magc_blockstack_workspace_bytes(ctypes.byref(sh), 1)))
             row = {"S": S, "grid": name, "l": l, "s": s, "s_planned": plan["s"] if name == "MA-GC" else None, "checkpoint_bytes": ckpt,
                    "workspace_bytes": ws, "kept_bytes": ckpt + ws, "ran": False}
