@@ -172,6 +172,10 @@ def blocks_sweep(args):
                 rcb, pb = pk.magc_plan(nl, S, c_l, c_s, c_grid, c_state, s_multiple=Q, budget=gb * 1e9, integer_counts=True)
                 if rcb == 0:
                     grids.append((f"budget {gb:g} GB", pb["l"], pb["s"]))
+        # for scale: no checkpointing at all would keep, per layer and token, everything its backward reads -- the layer
+        # input, zxbcdt, the activated xBC, dt, y and the normalised y (not run: the library always recomputes)
+        c_all = (dm + d_in_proj + conv_dim + H + 2 * d_inner) * 2
+        rows.append({"S": S, "grid": "none", "l": 0, "s": S, "kept_bytes": nl * S * c_all, "ran": False, "predicted_only": True})
         x0 = dout = None
         for name, l, s in grids:
             sh = sshape(S, s, l)
@@ -217,6 +221,8 @@ def blocks_sweep(args):
         if r["ran"]:
             print(f"| 2^{int(math.log2(r['S']))} | {r['grid']} | {r['l']} | {r['s']} | {kept} | "
                   f"{r['peak_beyond_inputs_bytes'] / 1e9:.2f} GB | {r['ms'] / 1e3:.2f} | {r['tokens_per_s_per_layer'] / 1e6:.2f} |")
+        elif r.get("predicted_only"):
+            print(f"| 2^{int(math.log2(r['S']))} | no checkpointing | - | - | {kept} (every activation kept; not run) | - | - | - |")
         else:
             print(f"| 2^{int(math.log2(r['S']))} | {r['grid']} | {r['l']} | {r['s']} | {kept} (predicted, over budget) | - | - | - |")
 
