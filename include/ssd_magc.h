@@ -278,7 +278,9 @@ int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  *             Both NULL in magc_block_fwd: no checkpoint is kept (inference; the states travel from segment
  *             to segment inside the workspace, memory does not grow with seqlen) -- prefill of a long
  *             sequence, and with seqlen of a few tokens and init = the previous call's final states,
- *             generation (calls of at most 16 tokens run the scan as the plain recurrence of Eq. 1).
+ *             generation (such calls of at most 16 tokens run on kernels of their own: the scan as the plain
+ *             recurrence of Eq. 1, the projections as products that stream the weights once; with a checkpoint
+ *             store every call, however short, takes the chunked path that magc_block_bwd recomputes).
  *             magc_block_bwd needs them unless nseg == 1.
  *   dfinal_ssm [H,P,N], dfinal_conv [3, d_inner + 2 G N] fp32: adjoints of the final states, NULL = zeros;
  *   dinit_ssm, dinit_conv: adjoints of the initial states (same shapes, fp32), may be NULL.  With them a
