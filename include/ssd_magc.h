@@ -130,6 +130,31 @@ int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
             void* hip_stream);
 
 /*
+ * ssd_fwd for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as ssd_fwd
+ * minus the workspace: the per-segment scratch is a device array inside the library,
+ * SSD_STATIC_SCRATCH_MIB MiB per GPU, held by every GPU the library runs on until the process ends.
+ *   - A shape whose scratch (ssd_fwd_static_bytes; one segment at a time) exceeds the array is rejected
+ *     with SSD_ERR_WORKSPACE before anything is launched: use ssd_fwd with a workspace instead.  The
+ *     2.7B layer shape with 4096-token segments fits.
+ *   - The call allocates nothing, frees nothing, creates no stream or event and never synchronises; every
+ *     kernel is enqueued on hip_stream, one segment after the other.  The array's device address is
+ *     looked up on the first call on each device (or by ssd_init with that device current); make that
+ *     first call, or ssd_init, outside graph capture.
+ *   - All calls on one GPU share that GPU's array, which keeps the previous call's contents (nothing in it
+ *     has to start at zero: each part is written before it is read within a call).  Calls that overlap
+ *     in time on one GPU -- from different streams or host threads -- race on it and give wrong results;
+ *     calls ordered on one stream, or on different GPUs, are fine.
+ * ssd_init: optional, idempotent, thread-safe set-up for the current device; returns SSD_OK or SSD_ERR_LAUNCH.
+ */
+#define SSD_STATIC_SCRATCH_MIB 40
+int ssd_init(void);
+size_t ssd_fwd_static_bytes(const ssd_shape_t* shape, uint32_t flags); /* 0 for an invalid shape */
+int ssd_fwd_static(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                   const void* C, const float* D, const float* init_state, void* y, float* final_state,
+                   void* boundary_states, uint32_t flags, void* hip_stream);
+
+/*
  * Recurrent form (Sec. 3.1, Eq. 1, token by token): for t = 0 .. seqlen-1
  *     state <- exp(dt_t A) state + dt_t x_t (x) B_t ;   y_t = C_t state + D x_t
  * The constant-memory step that continues a sequence after a prefill by ssd_fwd (whose

@@ -17,6 +17,7 @@ SSD_F32, SSD_BF16 = 0, 1
 SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16_CHECKPOINTS = 1, 2, 4, 8
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
+           "ssd_init", "ssd_fwd_static_bytes", "ssd_fwd_static",
            "ssd_conv1d_workspace_bytes", "ssd_conv1d_fwd", "ssd_conv1d_bwd",
            "ssd_gated_norm_workspace_bytes", "ssd_gated_norm_fwd", "ssd_gated_norm_bwd", "ssd_linear_fwd", "ssd_linear_bwd",
            "magc_block_workspace_bytes", "magc_block_fwd", "magc_block_bwd",
@@ -103,6 +104,12 @@ def lib():
         L.ssd_fwd.argtypes = [shp] + [vp] * 10 + [vp, sz, u32, vp]
         L.ssd_bwd.restype = ctypes.c_int
         L.ssd_bwd.argtypes = [shp] + [vp] * 17 + [vp, sz, u32, vp]
+        L.ssd_init.restype = ctypes.c_int
+        L.ssd_init.argtypes = []
+        L.ssd_fwd_static_bytes.restype = sz
+        L.ssd_fwd_static_bytes.argtypes = [shp, u32]
+        L.ssd_fwd_static.restype = ctypes.c_int
+        L.ssd_fwd_static.argtypes = [shp] + [vp] * 10 + [u32, vp]
         cshp = ctypes.POINTER(ssd_conv_shape_t)
         L.ssd_conv1d_workspace_bytes.restype = sz
         L.ssd_conv1d_workspace_bytes.argtypes = [cshp]
@@ -255,6 +262,30 @@ def ssd_fwd(x, dt, A, B, C, D, chunk, segment=None, init_state=None, flags=0, wo
     if rc != 0:
         raise SSDError(rc, "ssd_fwd")
     return y, final, bnd
+
+
+def ssd_init() -> None:
+    rc = lib().ssd_init()
+    if rc != 0:
+        raise SSDError(rc, "ssd_init")
+
+
+def ssd_fwd_static_bytes(shape: ssd_shape_t, flags: int = 0) -> int:
+    return int(lib().ssd_fwd_static_bytes(ctypes.byref(shape), flags))
+
+
+def ssd_fwd_static(x, dt, A, B, C, D, chunk, segment, out, init_state=None, flags=0, seq_reset=None):
+    """ssd_fwd without a workspace (the library's own device array): `out` must carry the preallocated
+    tensors y and, optionally, final_state and boundary_states; nothing is allocated here or in the library."""
+    _check_inputs(x, dt, A, B, C, D, init_state)
+    shape = make_shape(x, B, chunk, segment, seq_reset)
+    bnd = out.get("boundary_states")
+    _check_boundary(bnd, flags)
+    rc = lib().ssd_fwd_static(ctypes.byref(shape), _ptr(x), _ptr(dt), _ptr(A), _ptr(B), _ptr(C), _ptr(D), _ptr(init_state),
+                              _ptr(out["y"]), _ptr(out.get("final_state")), _ptr(bnd), flags, _stream(x))
+    if rc != 0:
+        raise SSDError(rc, "ssd_fwd_static")
+    return out["y"], out.get("final_state"), bnd
 
 
 def ssd_decode(x, dt, A, B, C, D, state, flags=0, out=None, seq_reset=None):

@@ -3,6 +3,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "ssd_internal.h"
 
 namespace ssdk {
@@ -277,8 +279,8 @@ bool serial_mode() {
     return serial || g_serial;
 }
 
-static int lanes(const Dims& d, bool mfma) {
-    if (!mfma || serial_mode() || d.nseg <= 1) return 1;
+static int lanes(const Dims& d, bool mfma, bool one_stream = false) {
+    if (!mfma || one_stream || serial_mode() || d.nseg <= 1) return 1;
     return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
 }
 
@@ -320,10 +322,11 @@ extern "C" size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backw
     return ssd_workspace_bytes_flags(shape, is_backward, 0);
 }
 
-extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
-                       const void* C, const float* D, const float* init_state, void* y, float* final_state,
-                       void* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
-                       void* hip_stream) {
+// one_stream: everything stays on the caller's stream (no library stream or event is touched).
+static int fwd_impl(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                    const void* C, const float* D, const float* init_state, void* y, float* final_state,
+                    void* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+                    void* hip_stream, bool one_stream) {
     Dims d;
     int rc = check_shape(shape, &d);
     if (rc != SSD_OK) return rc;
@@ -344,7 +347,7 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     }
     if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
-    const int nl = lanes(d, mfma);
+    const int nl = lanes(d, mfma, one_stream);
     const WsLayout w = ws_layout(d, false, mfma, wg_target(nl));
     const size_t block = align_up(w.total);
     const TailStage ts = tail_stage(d, false);
@@ -438,6 +441,69 @@ extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     }
     if (!join_lanes(pp, nl, st)) return SSD_ERR_LAUNCH;
     return SSD_OK;
+}
+
+extern "C" int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                       const void* C, const float* D, const float* init_state, void* y, float* final_state,
+                       void* boundary_states, void* workspace, size_t workspace_bytes, uint32_t flags,
+                       void* hip_stream) {
+    return fwd_impl(shape, x, dt, A, B, C, D, init_state, y, final_state, boundary_states, workspace, workspace_bytes,
+                    flags, hip_stream, false);
+}
+
+// ---- forward pass for callers that cannot allocate -------------------------------------------------
+// The per-segment scratch lives in a file-scope device array instead of a caller's workspace.  Every
+// device the library runs on holds its own copy of the array, at its own address, until the process ends;
+// the address is looked up once per device (hipGetSymbolAddress with that device current) and only that
+// pointer -- never the array's name, which in host code is a stand-in and not a device address -- is
+// handed to the kernels.
+namespace ssdk {
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)SSD_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[STATIC_SCRATCH_BYTES];
+
+static std::mutex g_scratch_mu;
+static void* g_scratch_ptr[64] = {};
+
+// The array's address on the current device (looked up on first use there), or NULL on failure.
+static void* static_scratch() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return nullptr;
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+
+// Scratch bytes of a forward call that stays on one stream.
+static size_t fwd_bytes_one_stream(const ssd_shape_t* shape, uint32_t flags) {
+    Dims d;
+    if (check_shape(shape, &d) != SSD_OK) return 0;
+    const bool mfma = use_mfma(*shape, flags);
+    const size_t t = align_up(ws_layout(d, false, mfma, wg_target(1)).total) + carry_bytes(d) + tail_stage(d, false).total;
+    return t ? t : 256;
+}
+}  // namespace ssdk
+
+extern "C" int ssd_init(void) { return static_scratch() ? SSD_OK : SSD_ERR_LAUNCH; }
+
+extern "C" size_t ssd_fwd_static_bytes(const ssd_shape_t* shape, uint32_t flags) { return fwd_bytes_one_stream(shape, flags); }
+
+extern "C" int ssd_fwd_static(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
+                              const void* C, const float* D, const float* init_state, void* y, float* final_state,
+                              void* boundary_states, uint32_t flags, void* hip_stream) {
+    Dims d;
+    const int rc = check_shape(shape, &d);
+    if (rc != SSD_OK) return rc;
+    const size_t need = fwd_bytes_one_stream(shape, flags);
+    if (need > STATIC_SCRATCH_BYTES) return SSD_ERR_WORKSPACE;  // beyond the array: use ssd_fwd with a workspace
+    void* ws = static_scratch();
+    if (!ws) return SSD_ERR_LAUNCH;
+    // Nothing in the scratch has to start at zero: every array in it is written by the kernel that
+    // precedes its first reader within the same call.
+    return fwd_impl(shape, x, dt, A, B, C, D, init_state, y, final_state, boundary_states, ws, need, flags, hip_stream, true);
 }
 
 extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, const float* A, const void* B,
