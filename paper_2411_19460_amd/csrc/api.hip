@@ -148,6 +148,9 @@ void base_params(SegParams& sp, const Dims& d, uint32_t flags) {
     sp.flags = flags;
     sp.nc_total = d.nc;
     sp.wg_target = 256;
+#ifdef SSDK_STAMPS
+    sp.stamps = g_stamps;
+#endif
 }
 
 static inline const void* off(const void* p, int64_t elems, size_t esz) { return p ? (const char*)p + elems * (int64_t)esz : nullptr; }
@@ -306,6 +309,13 @@ static bool join_lanes(Pipe* pp, int n, hipStream_t st) {
 }  // namespace ssdk
 
 using namespace ssdk;
+
+#ifdef SSDK_STAMPS
+namespace ssdk {
+unsigned long long* g_stamps = nullptr;
+}
+extern "C" void ssd_debug_stamps(void* p) { ssdk::g_stamps = (unsigned long long*)p; }
+#endif
 
 extern "C" size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, uint32_t flags) {
     Dims d;

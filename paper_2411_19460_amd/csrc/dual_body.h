@@ -58,6 +58,7 @@ struct Pre {
     float sc[DualCfg<Q>::XV], sc2[DualCfg<Q>::XV];  // per-token scale factors, multiplied at staging time
     bf16x8 sv[DualCfg<Q>::SV];
     float cum, dtf, fac;
+    float Dh;       // D of the head
     bf16x8 own[4];  // reverse: the wave's own 32 rows of x as whole rows (for the epilogue's dot products)
 };
 
@@ -104,6 +105,7 @@ __device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b,
         pr.dtf = sp.dtf[cbase + tid];
         pr.fac = REV ? sp.eout[cbase + tid] : sp.ein[cbase + tid];
     }
+    pr.Dh = sp.D[h];
     if (REV) {  // lane -> (row lane / 8, 16-byte piece lane % 8) of each 8-row group of the wave's tile
         const bf16_t* xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + ((int64_t)c * Q * sp.H + h) * P_;
         const uint32_t ooff = (uint32_t)((tid >> 3) & 7) * rowbytes + (uint32_t)(tid & 7) * 16;
@@ -176,17 +178,32 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     char* priv = L.priv[w];
     const float lane_c2 = L.cum2[tok], lane_fac = L.fac[tok];
     f32x16 acc0 = zero16(), acc1 = zero16();
+    // Operand reads from LDS run one contraction step ahead of the MFMAs that use them (the scheduling
+    // barriers keep the compiler from sinking a read next to its use, where every MFMA would wait a full
+    // LDS latency).
     // term through the chunk's entering state (forward) / leaving adjoint (reverse)
+    {
+        bf16x8 a0 = frag_lds_rows(L.st, BPITCH, 0, 0, lane), a1 = frag_lds_rows(L.st, BPITCH, 32, 0, lane);
 #pragma unroll
-    for (int ks = 0; ks < RF_N; ++ks) {
-        acc0 = mfma(frag_lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ks], acc0);
-        acc1 = mfma(frag_lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ks], acc1);
+        for (int ks = 0; ks < RF_N; ++ks) {
+            bf16x8 n0 = a0, n1 = a1;
+            if (ks + 1 < RF_N) {
+                n0 = frag_lds_rows(L.st, BPITCH, 0, 16 * (ks + 1), lane);
+                n1 = frag_lds_rows(L.st, BPITCH, 32, 16 * (ks + 1), lane);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            acc0 = mfma(a0, rf[ks], acc0);
+            acc1 = mfma(a1, rf[ks], acc1);
+            a0 = n0;
+            a1 = n1;
+        }
     }
     // off-diagonal 64-token blocks, Horner in the block decays (forward: K = 0 .. I-1; reverse: K = NB-1 .. I+1)
 #pragma unroll
     for (int n = 0; n < NB - 1; ++n) {
         const int K = REV ? NB - 1 - n : n;
         if (REV ? K > I : K < I) {
+            bf16x8 a0 = frag_tr(L.scl, XPITCH, K * BLK, 0, lane), a1 = frag_tr(L.scl, XPITCH, K * BLK, 32, lane);
             const float sK = __builtin_amdgcn_exp2f(L.cum2[K * BLK + BLK - 1] - (K > 0 ? L.cum2[K * BLK - 1] : 0.f));
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
@@ -195,10 +212,17 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
             }
 #pragma unroll
             for (int ks = 0; ks < BLK / 16; ++ks) {
-                const int k0 = K * BLK + 16 * ks;
+                bf16x8 n0 = a0, n1 = a1;
+                if (ks + 1 < BLK / 16) {
+                    n0 = frag_tr(L.scl, XPITCH, K * BLK + 16 * (ks + 1), 0, lane);
+                    n1 = frag_tr(L.scl, XPITCH, K * BLK + 16 * (ks + 1), 32, lane);
+                }
+                __builtin_amdgcn_sched_barrier(0);
                 const bf16x8 fb = go[4 * (REV ? K - 1 : K) + ks];
-                acc0 = mfma(frag_tr(L.scl, XPITCH, k0, 0, lane), fb, acc0);
-                acc1 = mfma(frag_tr(L.scl, XPITCH, k0, 32, lane), fb, acc1);
+                acc0 = mfma(a0, fb, acc0);
+                acc1 = mfma(a1, fb, acc1);
+                a0 = n0;
+                a1 = n1;
             }
         }
     }
@@ -208,21 +232,24 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
         acc1[r] *= lane_fac;
     }
     // diagonal block: the mask and the decay (and, forward, dt_j) are evaluated per element.  Forward,
-    // an even tile stops after its own 32 tokens; reverse, an odd tile starts at its own.
+    // an even tile stops after its own 32 tokens; reverse, an odd tile starts at its own.  The operand
+    // reads of a step are issued before the arithmetic that builds its masked scores.
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
         if (REV ? (odd && ks < 2) : (!odd && ks >= 2)) continue;
         const int k0 = I * BLK + 16 * ks;
+        const bf16x8 a0 = frag_tr(L.raw, XPITCH, k0, 0, lane), a1 = frag_tr(L.raw, XPITCH, k0, 32, lane);
         const bf16x8 gv = gd[ks];
         const int kk0 = k0 + 8 * (lane >> 5);
         const float4 ca = *(const float4*)(L.cum2 + kk0), cb = *(const float4*)(L.cum2 + kk0 + 4);
-        const float cv[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
-        float dv[8];
+        float4 da = make_float4(0.f, 0.f, 0.f, 0.f), db = da;
         if (!REV) {
-            const float4 da = *(const float4*)(L.dtl + kk0), db = *(const float4*)(L.dtl + kk0 + 4);
-            dv[0] = da.x; dv[1] = da.y; dv[2] = da.z; dv[3] = da.w;
-            dv[4] = db.x; dv[5] = db.y; dv[6] = db.z; dv[7] = db.w;
+            da = *(const float4*)(L.dtl + kk0);
+            db = *(const float4*)(L.dtl + kk0 + 4);
         }
+        __builtin_amdgcn_sched_barrier(0);
+        const float cv[8] = {ca.x, ca.y, ca.z, ca.w, cb.x, cb.y, cb.z, cb.w};
+        const float dv[8] = {da.x, da.y, da.z, da.w, db.x, db.y, db.z, db.w};
         bf16x8 fb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
@@ -233,8 +260,8 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
             if (!REV) f *= dv[e];
             fb[e] = (__bf16)(ok ? f : 0.f);
         }
-        acc0 = mfma(frag_tr(L.raw, XPITCH, k0, 0, lane), fb, acc0);
-        acc1 = mfma(frag_tr(L.raw, XPITCH, k0, 32, lane), fb, acc1);
+        acc0 = mfma(a0, fb, acc0);
+        acc1 = mfma(a1, fb, acc1);
     }
     // whole-row global accesses of the epilogue: lane -> (row lane / 8, 16-byte piece lane % 8) of an 8-row group
     const uint32_t rowoff = ((uint32_t)(lane >> 3) * (uint32_t)cx.xt + (uint32_t)(lane & 7) * 8) * 2;
@@ -293,6 +320,7 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
     constexpr bool REV = EPI == 2;
     // workgroups that share a (chunk, group) -- hence G, C, B -- get consecutive logical ids and, when the
     // grid divides evenly, land on the same XCD (hardware deals workgroup ids round-robin over 8 XCDs)
+    [[maybe_unused]] const int zlog = z;
     if ((nblk & 7) == 0) z = (z & 7) * (nblk >> 3) + (z >> 3);
     const int ns = sp.dual_split, slice = z % ns;
     z /= ns;
@@ -318,10 +346,16 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
         // for every head instead of being kept in registers across the whole loop
         int tv = tid;
         asm volatile("" : "+v"(tv));
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 0);
         __syncthreads();  // every wave is done with the previous head's tiles
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 1);
+        cx.Dh = pr.Dh + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
         store_pre<Q, REV>(pr, L, tv, w);
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 2);
         __syncthreads();
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 3);
         if (hh + 1 < hps) load_pre<Q, REV>(pr, sp, b, c, h + 1, tv, 32 * T);
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 4);
         const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
         const int64_t xrow = ((int64_t)c * Q * sp.H + h) * P_;
         cx.xg = (const bf16_t*)sp.x + (int64_t)b * sp.xs_b + xrow;
@@ -330,8 +364,8 @@ __device__ __forceinline__ void dual_body(const SegParams& sp, DualLds<Q>& L, in
         cx.fterm = sp.fterm + cbase;
         cx.dDrow = sp.dDrow + cbase;
         cx.xt = xt;
-        cx.Dh = sp.D[h] + ((sp.flags & SSD_FLAG_RESIDUAL) ? 1.f : 0.f);
         tile_compute<Q, EPI>(go, gd, rf, L, cx, T, lane, w);
+        SSDK_STAMP(EPI == 2 ? 0 : 3, 5);
     }
 }
 

@@ -150,8 +150,17 @@ __device__ __forceinline__ void dg_tile(f32x16& acc, f32x16& rowacc, int ti, int
     const char* pa = L.dy + (32 * ti + (lane & 31)) * XPITCH + 16 * (lane >> 5);
     const char* pb = L.x + (32 * tj + (lane & 31)) * XPITCH + 16 * (lane >> 5);
     f32x16 t = zero16();
+    {   // all eight operand reads in flight before the first MFMA (one LDS latency per tile instead of four)
+        bf16x8 fa[4], fb[4];
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) t = mfma(*(const bf16x8*)(pa + 32 * ks), *(const bf16x8*)(pb + 32 * ks), t);
+        for (int ks = 0; ks < 4; ++ks) {
+            fa[ks] = *(const bf16x8*)(pa + 32 * ks);
+            fb[ks] = *(const bf16x8*)(pb + 32 * ks);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) t = mfma(fa[ks], fb[ks], t);
+    }
     const int j = 32 * tj + (lane & 31);
     const float* rowp = (ti != tj ? L.rowf : L.c2) + 32 * ti + 4 * (lane >> 5);
     if (ti != tj) {
@@ -292,6 +301,7 @@ template <int Q>
 __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z, int nblk) {
     typedef DgMap<Q> M;
     constexpr int MAXT = M::MAXT;
+    [[maybe_unused]] const int zlog = z;
     if ((nblk & 7) == 0) z = (z & 7) * (nblk >> 3) + (z >> 3);
     const int ns = sp.dg_split, slice = z % ns;
     z /= ns;
@@ -322,11 +332,16 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
     DgPre<Q> pr;
     dg_load<Q>(pr, sp, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
+        SSDK_STAMP(1, 0);
         __syncthreads();
+        SSDK_STAMP(1, 1);
         if (hh > 0) dg_emit_sums<Q>(sp, L, rsrc, b, c, h0 + hh - 1, w, lane);
         dg_store<Q>(pr, L, tid);
+        SSDK_STAMP(1, 2);
         __syncthreads();
+        SSDK_STAMP(1, 3);
         if (hh + 1 < hps) dg_load<Q>(pr, sp, b, c, h0 + hh + 1, tid);
+        SSDK_STAMP(1, 4);
         f32x16 rowacc = zero16();
         int prev = M::ti(w, 0), run = 0;
 #pragma unroll
@@ -345,6 +360,7 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
                 dg_tile<Q>(acc[k], rowacc, ti, tj, slot0 + k, L, lane);
             }
         row_reduce_store(rowacc, L.rsum[w][run], lane);
+        SSDK_STAMP(1, 5);
     }
     __syncthreads();
     dg_emit_sums<Q>(sp, L, rsrc, b, c, h0 + hps - 1, w, lane);
@@ -442,6 +458,7 @@ template <int Q>
 __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, int z, int nblk) {
     typedef PartCfg<Q> CF;
     constexpr int RT = CF::RT;
+    [[maybe_unused]] const int zlog = z;
     if ((nblk & 7) == 0) z = (z & 7) * (nblk >> 3) + (z >> 3);
     const int ns = sp.part_split, slice = z % ns;
     z /= ns;
@@ -466,10 +483,15 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, in
     PartPre<Q> pr;
     part_load<Q>(pr, sp, role, b, c, h0, tid);
     for (int hh = 0; hh < hps; ++hh) {
+        SSDK_STAMP(2, 0);
         __syncthreads();
+        SSDK_STAMP(2, 1);
         part_store<Q>(pr, L, role, tid);
+        SSDK_STAMP(2, 2);
         __syncthreads();
+        SSDK_STAMP(2, 3);
         if (hh + 1 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 1, tid);
+        SSDK_STAMP(2, 4);
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
             const bf16x8 fb0 = frag_tr(L.st, BPITCH, 16 * ks, 64 * nh, lane);
@@ -502,6 +524,7 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, in
             sdot += __shfl_xor(sdot, 32, 64);
             if (lane < 32) (role ? sp.sterm : sp.gterm)[(((int64_t)b * sp.H + h0 + hh) * sp.nc + c) * Q + tok] = sdot;
         }
+        SSDK_STAMP(2, 5);
     }
     float* part = sp.dbc_part + (((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * 2 + role) * ((int64_t)Q * N_);
 #pragma unroll

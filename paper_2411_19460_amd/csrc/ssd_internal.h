@@ -118,7 +118,25 @@ struct SegParams {
     // optional cross-stream ordering of the state scans (consecutive segments run on different streams):
     // the scan waits for ev_wait and records ev_record when it has been enqueued
     hipEvent_t ev_wait, ev_record;
+#ifdef SSDK_STAMPS
+    unsigned long long* stamps;  // diagnostics build: cycle stamps of the head loops (see SSDK_STAMP)
+#endif
 };
+
+// Diagnostics build (-DSSDK_STAMPS): wave 0 of the first eight workgroups of a head-walking kernel writes the
+// shader cycle counter at six points of every head iteration, slot (body, workgroup, head, point).
+#ifdef SSDK_STAMPS
+extern unsigned long long* g_stamps;
+#define SSDK_STAMP(body, id)                                                                              \
+    do {                                                                                                  \
+        if (sp.stamps && lane == 0 && w == 0 && zlog < 8 && hh < 64)                                      \
+            sp.stamps[((((body)) * 8 + zlog) * 64 + hh) * 16 + (id)] = __builtin_readcyclecounter();      \
+    } while (0)
+#else
+#define SSDK_STAMP(body, id) \
+    do {                     \
+    } while (0)
+#endif
 
 // Validated dimensions of one call.
 struct Dims {
