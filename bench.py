@@ -98,27 +98,22 @@ def measured_traffic(kernel, workload):
         return None
 
 
-def cpu_baseline(cfg, seconds_target=15.0):
-    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload."""
-    import numpy as np
+def cpu_baseline(cfg):
+    """The fp64 oracle, as it stands, timed on this host on a bounded sample of the same workload: the first
+    65536 tokens of every head (all of config 2), forward + backward, one run (about 10-20 s on 16 cores)."""
     from oracle import ssd_ref
     from paper_2411_19460_amd import synth
     threads = int(os.environ.get("OMP_NUM_THREADS", "0")) or (os.cpu_count() or 1)
-    hs = min(cfg.nheads, max(1, threads))
     Ls = min(cfg.seqlen, 65536)
-    sub = cfg.scaled(seqlen=Ls, nheads=hs, segment=min(cfg.segment, Ls), name=cfg.name + "_sample")
+    sub = cfg.scaled(seqlen=Ls, segment=min(cfg.segment, Ls), name=cfg.name + "_sample")
     d = synth.make_layer_inputs(sub)
-    best = None
-    for _ in range(2):
-        t0 = time.perf_counter()
-        ssd_ref.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], None, sub.segment)
-        ssd_ref.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"])
-        dtm = time.perf_counter() - t0
-        best = dtm if best is None else min(best, dtm)
-    tok_s = sub.batch * Ls / best * (hs / cfg.nheads)
-    return {"value": tok_s, "unit": "tokens/s", "cores": min(threads, hs), "kind": "oracle",
-            "sample": f"first {Ls} tokens, heads 0..{hs - 1} of {cfg.nheads}, fwd+bwd fp64, best of 2, "
-                      f"scaled by {hs}/{cfg.nheads} to all heads"}
+    t0 = time.perf_counter()
+    ssd_ref.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], None, sub.segment)
+    ssd_ref.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"])
+    dtm = time.perf_counter() - t0
+    return {"value": sub.batch * Ls / dtm, "unit": "tokens/s", "cores": min(threads, cfg.nheads), "kind": "oracle",
+            "seconds": dtm,
+            "sample": f"first {Ls} tokens, all {cfg.nheads} heads, fwd+bwd fp64, one run (OpenMP over heads)"}
 
 
 def inference_bench(args, cfg, pk, synth, torch, dev):
@@ -534,6 +529,174 @@ def block_bench(args, cfg, pk, torch, dev):
     }))
 
 
+# Kernel -> the part of the path whose inputs and outputs it moves.  The algorithmic bytes of a part are the
+# tensors the method must read and write there once per token (bf16 storage: x-shaped tensors H*P*e, dt-shaped
+# H*e, B/C-shaped G*N*e): forward reads x, dt, B, C and writes y; the restore of a segment re-reads x, dt, B, C;
+# backward reads x, dt, B, C, dy and writes dx, ddt, dB, dC.
+KERNEL_GROUP = {"cumsum": "fwd", "mfma_cb": "fwd", "cb": "fwd", "mfma_chunk_state": "fwd", "chunk_state": "fwd",
+                "state_scan_fwd": "fwd", "mfma_chunk_out": "fwd", "chunk_out": "fwd",
+                "mfma_dstate_local": "restore", "dstate_local": "restore",
+                "state_scan_bwd": "bwd", "mfma_bwd_trio": "bwd", "mfma_bwd_main": "bwd", "bwd_main": "bwd", "mfma_dG": "bwd",
+                "dG": "bwd", "mfma_dBC": "bwd", "dBC": "bwd", "mfma_dBC_final": "bwd", "ddt_finalize": "bwd"}
+
+
+def group_bytes(cfg):
+    H, P, N, G = cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
+    e = 2 if cfg.dtype == "bf16" else 4
+    X, d, b = H * P * e, H * e, G * N * e
+    return {"fwd": 2 * X + d + 2 * b, "restore": X + d + 2 * b, "bwd": 3 * X + 2 * d + 4 * b}
+
+
+def measured_peak(torch, fn):
+    """Device bytes allocated at the peak of fn() beyond what was allocated when it started, and fn's result."""
+    torch.cuda.synchronize()
+    base = torch.cuda.memory_allocated()
+    torch.cuda.reset_peak_memory_stats()
+    out = fn()
+    torch.cuda.synchronize()
+    return torch.cuda.max_memory_allocated() - base, out
+
+
+def layer_bench(cfg, steps, warmup, flags, pk, synth, torch, dev, per_kernel):
+    """ssd_fwd + ssd_bwd of one layer on inputs resident in HBM: wall clock over exactly `steps` steps, the
+    median over the steps (an event between steps), the measured peak of device memory beyond inputs and
+    outputs for MA-GC and for one segment = the whole sequence, and, on request, the per-kernel table."""
+    d = synth.make_layer_inputs_device(cfg, dev)
+    ck_dtype = torch.bfloat16 if flags & pk.SSD_FLAG_BF16_CHECKPOINTS else torch.float32
+    Bt, L, H, P, N = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate
+    nseg = -(-L // cfg.segment)
+    out_f = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev)}
+    out_b = {"dx": torch.empty_like(d["x"]), "ddt": torch.empty_like(d["dt"]), "dB": torch.empty_like(d["B"]),
+             "dC": torch.empty_like(d["C"]), "dinit_state": torch.empty((Bt, H, P, N), device=dev)}
+    dA = torch.empty(H, device=dev)
+    dD = torch.empty(H, device=dev)
+
+    def one_pass(segment):
+        # everything beyond the inputs and the outputs is allocated inside: checkpoints and both workspaces
+        _, _, bnd = pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, segment, None, flags, None, out=out_f)
+        pk.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], cfg.chunk, segment, None, None, bnd, flags,
+                   None, dA, dD, out=out_b)
+
+    one_pass(cfg.segment)          # warm: library streams and events exist, code objects are loaded
+    peak_magc, _ = measured_peak(torch, lambda: one_pass(cfg.segment))
+    peak_full, _ = measured_peak(torch, lambda: one_pass(None))
+    torch.cuda.empty_cache()
+    shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
+    peak_hbm = {"magc_bytes": peak_magc, "full_activation_bytes": peak_full,
+                "magc_formula_bytes": pk.ssd_workspace_bytes(shape, True, flags) + nseg * Bt * H * P * N * (2 if ck_dtype == torch.bfloat16 else 4),
+                "note": "torch.cuda.max_memory_allocated during ssd_fwd + ssd_bwd minus what was allocated before (inputs "
+                        "and outputs): checkpoints + workspaces.  MA-GC (checkpoint every segment, scratch of the segments "
+                        "in flight) vs one segment = the whole sequence (every chunk state of the sequence alive)"}
+
+    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False, flags), dtype=torch.uint8, device=dev)
+    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True, flags), dtype=torch.uint8, device=dev)
+    out_f["boundary_states"] = torch.empty((Bt, nseg, H, P, N), dtype=ck_dtype, device=dev)
+
+    def step():
+        pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, cfg.segment, None, flags, ws_f, out=out_f)
+        pk.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], cfg.chunk, cfg.segment, None, None,
+                   out_f["boundary_states"], flags, ws_b, dA, dD, out=out_b)
+
+    for _ in range(warmup):
+        step()
+    # the timed region: exactly `steps` steps, nothing but the calls and one event record between steps
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    marks[0].record()
+    for i in range(steps):
+        step()
+        marks[i + 1].record()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / steps
+    step_ms = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    median = step_ms[len(step_ms) // 2] if len(step_ms) % 2 else 0.5 * (step_ms[len(step_ms) // 2 - 1] + step_ms[len(step_ms) // 2])
+    res = {"tokens_per_s": Bt * L / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "median_ms_per_step": median,
+           "step_ms": step_ms, "peak_hbm": peak_hbm}
+    if not per_kernel:
+        return res
+    # Untimed pass 1: every segment on one stream, HIP events around every launch: the per-kernel table.
+    pk.ssd_prof_serialize(True)
+    pk.ssd_prof_enable(True)
+    nser = 3
+    for _ in range(nser):
+        step()
+    torch.cuda.synchronize()
+    prof_all = pk.ssd_prof_read()
+    pk.ssd_prof_enable(False)
+    pk.ssd_prof_serialize(False)
+    models = kernel_models(cfg, Bt * cfg.segment, bool(flags & pk.SSD_FLAG_GENERIC_KERNELS))
+    kernels = {}
+    for name, (ms, n) in prof_all.items():
+        ent = {"ms_per_step": ms / nser, "launches_per_step": n // nser, "avg_us": ms * 1e3 / n}
+        if name in models:
+            fl, by = models[name]
+            sec = ms / n * 1e-3
+            ent["operand_gbs"] = by / sec / 1e9       # operands and results of this kernel alone (states and scores included)
+            if fl:
+                ent["tflops"] = fl / sec / 1e12
+        kernels[name] = ent
+    dom = max((k for k in kernels if k in models), key=lambda k: kernels[k]["ms_per_step"])
+    # Untimed pass 2: as the timed region (segments in flight), events around the dominant kernel only.
+    step()
+    pk.ssd_prof_enable(True, only=dom)
+    for _ in range(nser):
+        step()
+    torch.cuda.synchronize()
+    pd = pk.ssd_prof_read()
+    pk.ssd_prof_enable(False)
+    res.update({"kernels_serialized": kernels, "dominant": dom,
+                "dominant_in_flight_us": pd[dom][0] * 1e3 / pd[dom][1] if dom in pd else None})
+    return res
+
+
+def stack_bench(cfg, steps, warmup, pk, synth, torch, dev):
+    """The 16-layer residual stack on its MA-GC grid (all layers x cfg.segment tokens per cell): forward + backward
+    tokens/s per layer and the measured peak of device memory beyond inputs and outputs, against the same stack
+    under layer-only checkpointing (every layer's input kept for the whole sequence, no sequence checkpoints)."""
+    layers = []
+    for j in range(cfg.nlayers):
+        lay = synth.make_layer_inputs_device(cfg, dev, layer=j, with_dy=(j == 0))
+        if j == 0:
+            x0, dout = lay["x"], lay["dy"]
+        layers.append({k: lay[k] for k in ("dt", "A", "B", "C", "D")})
+        del lay
+    stk = [torch.stack([l[k] for l in layers]).contiguous() for k in ("dt", "A", "B", "C", "D")]
+    del layers
+    torch.cuda.empty_cache()
+    nl, L = cfg.nlayers, cfg.seqlen
+
+    def one(segment, interval):
+        f = pk.magc_stack_fwd(x0, *stk, cfg.chunk, segment, interval, want_final=False)
+        b = pk.magc_stack_bwd(x0, *stk, dout, f["s_ckpt"], f["l_ckpt"], cfg.chunk, segment, interval)
+        return f["out"].numel() * f["out"].element_size() + sum(v.numel() * v.element_size() for v in b.values())
+
+    def arm(segment, interval):
+        for _ in range(warmup):
+            one(segment, interval)
+        peak, out_bytes = measured_peak(torch, lambda: one(segment, interval))
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one(segment, interval)
+        torch.cuda.synchronize()
+        ms = (time.perf_counter() - t0) * 1e3 / steps
+        torch.cuda.empty_cache()
+        # the outputs (out, dx0 and the per-layer gradients) are allocated inside the call: not part of the figure
+        return {"ms_per_step": ms, "tokens_per_s_per_layer": nl * cfg.batch * L / (ms * 1e-3), "peak_bytes": peak - out_bytes}
+
+    grid = arm(cfg.segment, nl)
+    layer_only = arm(L, 1)
+    return {"nlayers": nl, "seqlen": L, "segment": cfg.segment, "layer_interval": nl,
+            "tokens_per_s_per_layer": grid["tokens_per_s_per_layer"], "ms_per_step": grid["ms_per_step"],
+            "peak_hbm": {"magc_grid_bytes": grid["peak_bytes"], "layer_only_bytes": layer_only["peak_bytes"],
+                         "note": "torch.cuda.max_memory_allocated during magc_stack_fwd + magc_stack_bwd minus inputs and "
+                                 "outputs: checkpoints + workspace.  Grid of all layers x segment tokens vs every layer input "
+                                 "kept for the whole sequence with one segment = the whole sequence"},
+            "layer_only": {"tokens_per_s_per_layer": layer_only["tokens_per_s_per_layer"], "ms_per_step": layer_only["ms_per_step"]}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -544,6 +707,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--bf16-checkpoints", action="store_true", help="keep the segment checkpoints in bf16 (half the bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the L = 2^20 layer and the 16-layer stack (configs_extra)")
     ap.add_argument("--inference", action="store_true",
                     help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
                          "token-by-token recurrent step (us per token) at the same layer shape")
@@ -670,105 +834,31 @@ def main():
     if args.block:
         block_bench(args, cfg, pk, torch, dev)
         return
-    d = synth.make_layer_inputs_device(cfg, dev)
     flags = pk.SSD_FLAG_GENERIC_KERNELS if args.generic else 0
     if args.bf16_checkpoints:
         flags |= pk.SSD_FLAG_BF16_CHECKPOINTS
-    ck_dtype = torch.bfloat16 if args.bf16_checkpoints else torch.float32
-    shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
     Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
-    nseg = L // cfg.segment
-    ws_f = torch.empty(pk.ssd_workspace_bytes(shape, False, flags), dtype=torch.uint8, device=dev)
-    ws_b = torch.empty(pk.ssd_workspace_bytes(shape, True, flags), dtype=torch.uint8, device=dev)
-    out_f = {"y": torch.empty_like(d["x"]), "final_state": torch.empty((Bt, H, P, N), device=dev),
-             "boundary_states": torch.empty((Bt, nseg, H, P, N), dtype=ck_dtype, device=dev)}
-    out_b = {"dx": torch.empty_like(d["x"]), "ddt": torch.empty_like(d["dt"]), "dB": torch.empty_like(d["B"]),
-             "dC": torch.empty_like(d["C"]), "dinit_state": torch.empty((Bt, H, P, N), device=dev)}
-    dA = torch.empty(H, device=dev)
-    dD = torch.empty(H, device=dev)
-
-    def step():
-        pk.ssd_fwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], cfg.chunk, cfg.segment, None, flags, ws_f, out=out_f)
-        pk.ssd_bwd(d["x"], d["dt"], d["A"], d["B"], d["C"], d["D"], d["dy"], cfg.chunk, cfg.segment, None, None,
-                   out_f["boundary_states"], flags, ws_b, dA, dD, out=out_b)
-
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
-    # Pass 1 (not the timed region): HIP events around every kernel launch, with every segment kept on
-    # one stream so that kernels do not overlap: the per-kernel table, and the dominant kernel.  Event
-    # records between kernels cost several microseconds each, so this pass is slower than the real thing.
-    pk.ssd_prof_serialize(True)
-    pk.ssd_prof_enable(True)
-    for _ in range(max(1, min(args.steps, 3))):
-        step()
-    torch.cuda.synchronize()
-    prof_all = pk.ssd_prof_read()
-    pk.ssd_prof_enable(False)
-    pk.ssd_prof_serialize(False)
-    for _ in range(max(1, args.warmup)):
-        step()
-    torch.cuda.synchronize()
-    models = kernel_models(cfg, Bt * cfg.segment, args.generic)
-    dom = max((k for k in prof_all if k in models), key=lambda k: prof_all[k][0])
-    # Pass 2, the timed region: exactly `steps` steps, up to four segments in flight, events only around
-    # the dominant kernel (its launches then share the GPU with kernels of the other segments).
-    pk.ssd_prof_enable(True, only=dom)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    torch.cuda.synchronize()
-    t1 = time.perf_counter()
-    prof_dom = pk.ssd_prof_read()
-    pk.ssd_prof_enable(False)
-    ms_per_step = (t1 - t0) * 1e3 / args.steps
-    tok_s = Bt * L / (ms_per_step * 1e-3)
-
-    def bound_of(name):
-        """The roofline that binds a kernel: the matrix cores (fp32 vector ALUs for the shape-generic
-        kernels) if its flop/byte is above the machine's ridge for that unit, HBM otherwise."""
-        fl, by = models[name]
-        peak_fl = MFMA_BF16_PEAK_TFLOPS if name.startswith("mfma_") else VALU_FP32_PEAK_TFLOPS
-        if fl and fl / by >= peak_fl * 1e12 / (HBM_PEAK_GBS * 1e9):
-            return ("mfma" if name.startswith("mfma_") else "alu"), peak_fl, "TFLOP/s", fl / 1e12
-        return "hbm", HBM_PEAK_GBS, "GB/s", by / 1e9
-
-    def entry(name, ms, n, nsteps):
-        ent = {"ms_per_step": ms / nsteps, "launches_per_step": n // nsteps, "avg_us": ms * 1e3 / n}
-        if name in models:
-            bound, peak, unit, amount = bound_of(name)
-            sec = ms / n * 1e-3
-            ent.update({"bound": bound, "achieved": amount / sec, "unit": unit, "frac": amount / sec / peak})
-            fl, by = models[name]
-            if fl:
-                ent["tflops"] = fl / sec / 1e12
-            ent["algorithmic_gbs"] = by / sec / 1e9
-        return ent
-
-    nsteps1 = max(1, min(args.steps, 3))
-    kernels = {name: entry(name, ms, n, nsteps1) for name, (ms, n) in prof_all.items()}
-    dment = entry(dom, prof_dom[dom][0], prof_dom[dom][1], args.steps)   # from the timed region
-    bound, peak, unit, _ = bound_of(dom)
-    roofline = {"kernel": dom, "bound": bound, "achieved": dment["achieved"], "peak": peak, "unit": unit,
-                "frac": dment["frac"], "traffic": measured_traffic(dom, cfg.name),
-                "avg_launch_us": dment["avg_us"], "share_of_step": dment["ms_per_step"] / ms_per_step,
-                "serialized_avg_launch_us": kernels[dom]["avg_us"], "serialized_frac": kernels[dom]["frac"]}
+    main = layer_bench(cfg, args.steps, args.warmup, flags, pk, synth, torch, dev, per_kernel=True)
+    tok_s, ms_per_step = main["tokens_per_s"], main["ms_per_step"]
+    kernels, dom = main["kernels_serialized"], main["dominant"]
+    group = KERNEL_GROUP.get(dom, "bwd")
+    gbytes = group_bytes(cfg)[group] * Bt * cfg.segment      # algorithmic bytes of the kernel's group per launch (one segment)
+    dsec = kernels[dom]["avg_us"] * 1e-6
+    roofline = {"kernel": dom, "bound": "hbm", "achieved": gbytes / dsec / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": gbytes / dsec / 1e9 / HBM_PEAK_GBS, "traffic": measured_traffic(dom, cfg.name),
+                "algorithmic_bytes_per_launch": gbytes, "avg_launch_us": kernels[dom]["avg_us"],
+                "duration": "kernel alone on the GPU (every segment on one stream), HIP events around each launch, "
+                            "untimed pass after the timed region",
+                "bytes": f"{group} group of the path per token ({group_bytes(cfg)[group]:.0f} B: inputs read once, outputs "
+                         f"written once) x {Bt * cfg.segment} tokens per launch",
+                "in_flight_avg_launch_us": main["dominant_in_flight_us"],
+                "share_of_kernel_time": kernels[dom]["ms_per_step"] / sum(k["ms_per_step"] for k in kernels.values()),
+                "tflops": kernels[dom].get("tflops"), "frac_mfma": (kernels[dom].get("tflops") or 0.0) / MFMA_BF16_PEAK_TFLOPS}
     pfl, pby = path_model(cfg)
     roofline_path = {"bound": "hbm" if pfl / pby < MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9) else "mfma",
                      "algorithmic_bytes_per_token": pby, "algorithmic_flop_per_token": pfl,
                      "achieved_gbs": pby * tok_s / 1e9, "frac_hbm": pby * tok_s / 1e9 / HBM_PEAK_GBS,
                      "achieved_tflops": pfl * tok_s / 1e12, "frac_mfma": pfl * tok_s / 1e12 / MFMA_BF16_PEAK_TFLOPS}
-
-    full = pk.make_shape(d["x"], d["B"], cfg.chunk, None)
-    state_bytes = Bt * H * P * N * (2 if args.bf16_checkpoints else 4)
-    peak_hbm = {
-        "magc_bytes": pk.ssd_workspace_bytes(shape, True, flags) + nseg * state_bytes,
-        "full_activation_bytes": pk.ssd_workspace_bytes(full, True, flags),
-        "note": "scratch + checkpoints beyond the inputs/outputs: MA-GC (segment checkpoints + one segment's "
-                "chunk states) vs keeping every chunk state of the sequence alive (segment = L)",
-    }
-
     res = {
         "metric": "SSD fwd+bwd tokens/sec/layer", "value": tok_s, "unit": "tokens/s", "n_gpus": 1,
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step, "higher_is_better": True,
@@ -777,9 +867,22 @@ def main():
                    "ngroups": G, "chunk": cfg.chunk, "segment": cfg.segment,
                    "checkpoints": "bf16" if args.bf16_checkpoints else "f32",
                    "kernels": "generic" if args.generic or not any(k.startswith("mfma_") for k in kernels) else "mfma",
-                   "segments_in_flight": min(4, nseg) if not args.generic else 1},
-        "roofline": roofline, "roofline_path": roofline_path, "kernels_serialized": kernels, "peak_hbm": peak_hbm,
+                   "segments_in_flight": min(4, L // cfg.segment) if not args.generic else 1},
+        "median_ms_per_step": main["median_ms_per_step"], "step_ms": main["step_ms"],
+        "roofline": roofline, "roofline_path": roofline_path, "kernels_serialized": kernels, "peak_hbm": main["peak_hbm"],
     }
+    if not args.no_extras and args.config == 2 and not args.segment and not args.generic:
+        del main
+        torch.cuda.empty_cache()
+        extra = {}
+        c3 = synth.CONFIGS[3]
+        r3 = layer_bench(c3, 3, 1, flags, pk, synth, torch, dev, per_kernel=False)
+        extra[c3.name] = {"tokens_per_s": r3["tokens_per_s"], "ms_per_step": r3["ms_per_step"],
+                          "median_ms_per_step": r3["median_ms_per_step"], "segment": c3.segment, "peak_hbm": r3["peak_hbm"]}
+        del r3
+        torch.cuda.empty_cache()
+        extra[synth.CONFIGS[4].name] = stack_bench(synth.CONFIGS[4], 2, 1, pk, synth, torch, dev)
+        res["configs_extra"] = extra
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(cfg)
     print(json.dumps(res))
