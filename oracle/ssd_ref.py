@@ -115,11 +115,12 @@ def ssd_bwd(x, dt, A, B, C, D, dy, init_state=None, dfinal_state=None, head_grou
     return {"dx": dx, "ddt": ddt, "dA": dA, "dB": dB, "dC": dC, "dD": dD, "dinit_state": dinit}
 
 
-def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None, store=None):
+def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None, store=None, progress=None):
     """Residual stack: x_{j+1} = x_j + SSD_j(x_j).  `layers` is a list of dicts with
     dt, A, B, C, D.  `store`, if given, is the rounding of the storage dtype (e.g. round to
     bf16): the stack keeps its activations in that dtype, so every x_{j+1} is rounded once
     when it is stored; with store=None everything stays in fp64 between layers.
+    `progress`, if given, is called with a short text after every layer (long runs report their steps).
     Returns dict(out, xs=[x_0..x_{n-1}], final_states, boundary_states)."""
     x = _f64(x0)
     xs, fins, bnds = [], [], []
@@ -132,17 +133,21 @@ def stack_fwd(x0, layers, init_states=None, segment=None, head_group=None, store
             x = _f64(store(x))
         fins.append(r["final_state"])
         bnds.append(r["boundary_states"])
+        if progress is not None:
+            progress(f"stack oracle: forward layer {j} done")
     return {"out": x, "xs": xs, "final_states": fins, "boundary_states": bnds}
 
 
-def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group=None, store=None):
+def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group=None, store=None, progress=None):
     """Backward of stack_fwd given the layer inputs xs[j]: dx_j = dx_{j+1} + VJP_j(dx_{j+1}),
     each dx_j rounded once by `store` (the storage dtype of the activation gradients) if given.
-    Returns dict(dx0, grads=[per-layer dict of ddt, dA, dB, dC, dD, dinit_state])."""
+    Returns dict(dx0, grads=[per-layer dict of ddt, dA, dB, dC, dD, dinit_state], dys=[gradient entering layer j])."""
     g = _f64(dout)
     grads = [None] * len(layers)
+    dys = [None] * len(layers)
     for j in range(len(layers) - 1, -1, -1):
         lay = layers[j]
+        dys[j] = g
         r = ssd_bwd(xs[j], lay["dt"], lay["A"], lay["B"], lay["C"], lay["D"], g,
                     None if init_states is None else init_states[j],
                     None if dfinal_states is None else dfinal_states[j], head_group)
@@ -150,4 +155,6 @@ def stack_bwd(xs, layers, dout, init_states=None, dfinal_states=None, head_group
         if store is not None:
             g = _f64(store(g))
         grads[j] = r
-    return {"dx0": g, "grads": grads}
+        if progress is not None:
+            progress(f"stack oracle: backward layer {j} done")
+    return {"dx0": g, "grads": grads, "dys": dys}

@@ -9,6 +9,38 @@ from oracle import ssd_ref
 TOL = {"f32": 1e-3, "bf16": 2e-2}   # max |gpu - ref| / max |ref| per tensor
 
 
+def stack_tol(dtype, nlayers):
+    """Tolerance for the output of a residual stack of `nlayers` layers.  TOL is the bar for one layer.  A layer
+    adds its own error (measured: 3-5e-3 of the largest magnitude in bf16, a quarter of TOL) to a residual stream
+    that carries the errors of the layers below with the same gain as the signal, so the error after n layers grows
+    like that of a random walk, sqrt(n) times the single-layer error: with the single layer allowed TOL / 2 of
+    head room before the stack is, the bar is TOL * sqrt(n) / 2, never below TOL (n = 16: 2 TOL)."""
+    return TOL[dtype] * max(1.0, nlayers ** 0.5 / 2.0)
+
+
+def check_dot_gradient(name, got, ref, a, b, tol, report=None):
+    """A gradient that is a plain dot product sum_i a_i b_i of two stored tensors (dD = sum dy x): when the
+    two are nearly uncorrelated the sum is the small remainder of a large cancellation, and rounding each factor
+    once (relative error delta) already moves it by delta * sqrt(sum_i (a_i b_i)^2), however small the sum itself
+    is.  The error is therefore measured against max(|ref|, sqrt(sum_i (a_i b_i)^2)): a missing or misplaced
+    part of the sum changes it by a multiple of that scale, a rounding order does not."""
+    scale = max(abs(float(ref)), float(np.sqrt(np.sum((np.asarray(a, dtype=np.float64) * np.asarray(b, dtype=np.float64)) ** 2))))
+    e = abs(float(got) - float(ref)) / (scale if scale > 0 else 1.0)
+    if report is not None:
+        report[name] = max(report.get(name, 0.0), e)
+    assert np.isfinite(e) and e <= tol, f"{name}: |gpu - ref| / scale = {e:.3e} > {tol:.1e} (gpu {float(got):.4g}, ref {float(ref):.4g})"
+
+
+def progress(text):
+    """A step of a long test is done: one line into gpurun_out/pytest_progress.log under the repository root when
+    that folder exists (where a runner that watches for output looks while pytest holds stdout back), else nothing."""
+    import os
+    folder = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "gpurun_out")
+    if os.path.isdir(folder):
+        with open(os.path.join(folder, "pytest_progress.log"), "a") as f:
+            f.write(text + "\n")
+
+
 def to_dev(a, dtype):
     t = torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
     return t.to(torch.bfloat16) if dtype == "bf16" else t
