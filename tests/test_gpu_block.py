@@ -197,17 +197,12 @@ def test_stack_of_blocks_on_the_two_axis_grid(case):
     rep = {}
     check("out", host(f["out"]), fo["out"], tol, rep)
     check("dx0", host(g["dx0"]), go["dx0"], tol, rep)
-    # Parameter gradients are sums over all tokens in which terms cancel; where rounding the stored bf16
-    # intermediates alone moves such a sum by more than the tolerance (seen for dt_bias of the lowest layer,
-    # whose gradient has crossed every layer above), that movement -- the oracle with and without the
-    # storage rounding -- is the bar: two correct evaluations that round in a different order differ by as much.
-    fe = block_ref.stack_fwd(x0h, layers_h, H, P, G, N, 1e-5)
-    ge = block_ref.stack_bwd(fe["xs"], layers_h, H, P, G, N, douth, 1e-5)
+    # Parameter gradients: fixed bars.  Largest errors seen on these four grids: ddt_bias of the lowest layer
+    # 5.0e-2 (a sum over every token of terms that cancel, reached by a gradient that has crossed every layer
+    # above: bar 3 TOL), dA 3.7e-2, dW_in 3.3e-2, everything else below 2.2e-2 (bar 2 TOL, as for out and dx0).
     for j in range(NL):
         for k in GRADS:
-            ref, exact = go["grads"][j][k], ge["grads"][j][k]
-            floor = float(np.max(np.abs(ref - exact))) / float(np.max(np.abs(exact)))
-            check(f"layer {j} {k}", host(g["grads"][j][k]), ref, max(tol, floor), rep)
+            check(f"layer {j} {k}", host(g["grads"][j][k]), go["grads"][j][k], 3 * TOL["bf16"] if k == "ddt_bias" else tol, rep)
     print("stack of blocks, worst errors:", {k: f"{v:.2e}" for k, v in sorted(rep.items(), key=lambda kv: -kv[1])[:4]})
     # the grid does not change the result: whole sequence as one segment, every layer input kept
     f1 = pk.magc_blockstack_fwd(x0, layers, H, P, G, N, Q, None, 1)
