@@ -23,7 +23,8 @@
  *     All work is ordered after what is already in `hip_stream` (a hipStream_t passed as void*;
  *     NULL = the default stream) and before anything enqueued there after the call returns; with
  *     more than one segment part of it runs on a library-owned stream of default priority, forked
- *     from and joined back into `hip_stream` with events (created on the first such call).
+ *     from and joined back into `hip_stream` with events (created, under a lock, on the first such call
+ *     on a device or by ssd_init; make that first call outside stream capture).
  *     Setting SSD_MAGC_SERIAL=1 in the environment keeps everything on `hip_stream` (diagnostics).
  *     Those streams and events exist once per device: calls on one device must not overlap in time
  *     across host threads (calls on different devices, or one after the other, are fine).
@@ -35,7 +36,9 @@
  *     Arithmetic accumulates in fp32; outputs are rounded once (nearest-even).
  *   - Every entry point returns 0 on success or a negative ssd_status_t.  Arguments are
  *     validated before anything is launched; on a validation error nothing was enqueued and no
- *     output was touched.  SSD_ERR_LAUNCH reports a HIP launch error (outputs undefined).
+ *     output was touched.  SSD_ERR_LAUNCH reports a failed HIP call (outputs undefined; work already
+ *     enqueued, possibly on a library stream, may still be running: synchronise the device before
+ *     releasing the buffers of that call).
  *     No C++ exception crosses this boundary.
  */
 #ifndef SSD_MAGC_H
@@ -145,7 +148,8 @@ int ssd_fwd(const ssd_shape_t* shape, const void* x, const void* dt, const float
  *     has to start at zero: each part is written before it is read within a call).  Calls that overlap
  *     in time on one GPU -- from different streams or host threads -- race on it and give wrong results;
  *     calls ordered on one stream, or on different GPUs, are fine.
- * ssd_init: optional, idempotent, thread-safe set-up for the current device; returns SSD_OK or SSD_ERR_LAUNCH.
+ * ssd_init: optional, idempotent, thread-safe set-up for the current device (the array's address and the
+ * library's own streams and events); returns SSD_OK or SSD_ERR_LAUNCH.
  */
 #define SSD_STATIC_SCRATCH_MIB 40
 int ssd_init(void);

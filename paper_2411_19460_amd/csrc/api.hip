@@ -205,20 +205,35 @@ struct Pipe {
     bool ok = false;
 };
 
+// Created on the first call that needs them on a device (or by ssd_init), under a lock; a partial failure
+// releases what was created and leaves the entry unset, so that a later call tries again.
+static std::mutex g_pipe_mu;
+
 static Pipe* pipe_for_current_device() {
     static Pipe pipes[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_pipe_mu);
     Pipe& p = pipes[dev];
-    if (!p.ok) {
-        if (hipEventCreateWithFlags(&p.fork, hipEventDisableTiming) != hipSuccess) return nullptr;
-        for (int i = 0; i < NPIPE; ++i) {
-            if (i > 0 && hipStreamCreateWithFlags(&p.aux[i], hipStreamNonBlocking) != hipSuccess) return nullptr;
-            if (hipEventCreateWithFlags(&p.join[i], hipEventDisableTiming) != hipSuccess) return nullptr;
-            if (hipEventCreateWithFlags(&p.scan[i], hipEventDisableTiming) != hipSuccess) return nullptr;
-        }
-        p.ok = true;
+    if (p.ok) return &p;
+    Pipe q;
+    bool good = hipEventCreateWithFlags(&q.fork, hipEventDisableTiming) == hipSuccess;
+    for (int i = 0; good && i < NPIPE; ++i) {
+        if (i > 0) good = hipStreamCreateWithFlags(&q.aux[i], hipStreamNonBlocking) == hipSuccess;
+        good = good && hipEventCreateWithFlags(&q.join[i], hipEventDisableTiming) == hipSuccess;
+        good = good && hipEventCreateWithFlags(&q.scan[i], hipEventDisableTiming) == hipSuccess;
     }
+    if (!good) {
+        if (q.fork) (void)hipEventDestroy(q.fork);
+        for (int i = 0; i < NPIPE; ++i) {
+            if (q.aux[i]) (void)hipStreamDestroy(q.aux[i]);
+            if (q.join[i]) (void)hipEventDestroy(q.join[i]);
+            if (q.scan[i]) (void)hipEventDestroy(q.scan[i]);
+        }
+        return nullptr;
+    }
+    q.ok = true;
+    p = q;
     return &p;
 }
 
@@ -497,7 +512,13 @@ static size_t fwd_bytes_one_stream(const ssd_shape_t* shape, uint32_t flags) {
 }
 }  // namespace ssdk
 
-extern "C" int ssd_init(void) { return static_scratch() ? SSD_OK : SSD_ERR_LAUNCH; }
+extern "C" int ssd_init(void) {
+    // everything the library creates lazily on a device: the scratch array's address, the streams and events of
+    // the segments in flight, the side stream of the projections
+    const bool a = static_scratch() != nullptr, b = pipe_for_current_device() != nullptr;
+    const bool c = serial_mode() || side_stream() != nullptr;
+    return a && b && c ? SSD_OK : SSD_ERR_LAUNCH;
+}
 
 extern "C" size_t ssd_fwd_static_bytes(const ssd_shape_t* shape, uint32_t flags) { return fwd_bytes_one_stream(shape, flags); }
 

@@ -558,7 +558,7 @@ static int block_fwd(const magc_block_shape_t* sh, const magc_block_params_t* p,
         BLK_HIP(hipStreamWaitEvent(side->st, side->fork, 0));
         rc = ssd_linear_fwd(rows, d.d_inner, d.dm, ws + w.yn, 0, p->W_out, out_seg, 0, side->st);
         side_busy = hipEventRecord(side->join, side->st) == hipSuccess;  // joined below whatever the product returned
-        if (!side_busy) (void)hipStreamSynchronize(side->st);
+        if (!side_busy) return SSD_ERR_LAUNCH;  // no event to wait for: the host is not blocked, the error is reported
         if (rc == SSD_OK && !last) {
             // every reader of this segment's zxbcdt is already in the stream: the next one may replace it
             const int64_t t1 = t0 + d.s, rows1 = d.L - t1 < d.s ? d.L - t1 : d.s;

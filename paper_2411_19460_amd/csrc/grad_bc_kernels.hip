@@ -400,9 +400,14 @@ struct PartCfg {
 };
 
 template <int Q>
-struct PartLds {
+struct PartBuf {
     char tile[Q * XPITCH];  // weight * dY or weight * x, token-major
     char st[P_ * BPITCH];   // Hprev or dHnext, [p][n] bf16
+};
+// Two buffers: a head is contracted out of one while the next head is staged into the other (one barrier per head).
+template <int Q>
+struct PartLds {
+    PartBuf<Q> b[2];
 };
 
 template <int Q>
@@ -439,7 +444,7 @@ __device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, i
 }
 
 template <int Q>
-__device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, int role, int tid) {
+__device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartBuf<Q>& L, int role, int tid) {
     typedef PartCfg<Q> CF;
 #pragma unroll
     for (int k = 0; k < CF::TV; ++k) {
@@ -455,7 +460,7 @@ __device__ __forceinline__ void part_store(const PartPre<Q>& pr, PartLds<Q>& L, 
 }
 
 template <int Q>
-__device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, int z, int nblk) {
+__device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& LL, int z, int nblk) {
     typedef PartCfg<Q> CF;
     constexpr int RT = CF::RT;
     [[maybe_unused]] const int zlog = z;
@@ -482,34 +487,57 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, in
     }
     PartPre<Q> pr;
     part_load<Q>(pr, sp, role, b, c, h0, tid);
+    part_store<Q>(pr, LL.b[0], role, tid);
+    if (hps > 1) part_load<Q>(pr, sp, role, b, c, h0 + 1, tid);
+    __syncthreads();
     for (int hh = 0; hh < hps; ++hh) {
         SSDK_STAMP(2, 0);
-        __syncthreads();
-        SSDK_STAMP(2, 1);
-        part_store<Q>(pr, L, role, tid);
-        SSDK_STAMP(2, 2);
-        __syncthreads();
-        SSDK_STAMP(2, 3);
-        if (hh + 1 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 1, tid);
-        SSDK_STAMP(2, 4);
+        const PartBuf<Q>& L = LL.b[hh & 1];
+        {   // operand reads run one contraction step ahead of their MFMAs
+            bf16x8 fb0 = frag_tr(L.st, BPITCH, 0, 64 * nh, lane), fb1 = frag_tr(L.st, BPITCH, 0, 64 * nh + 32, lane);
+            bf16x8 fa[RT];
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            const bf16x8 fb0 = frag_tr(L.st, BPITCH, 16 * ks, 64 * nh, lane);
-            const bf16x8 fb1 = frag_tr(L.st, BPITCH, 16 * ks, 64 * nh + 32, lane);
+            for (int rt = 0; rt < RT; ++rt) fa[rt] = lds_rows(L.tile, XPITCH, 32 * (rg * RT + rt), 0, lane);
 #pragma unroll
-            for (int rt = 0; rt < RT; ++rt) {
-                const bf16x8 fa = lds_rows(L.tile, XPITCH, 32 * (rg * RT + rt), 16 * ks, lane);
-                acc[rt][0] = mfma(fa, fb0, acc[rt][0]);
-                acc[rt][1] = mfma(fa, fb1, acc[rt][1]);
+            for (int ks = 0; ks < 4; ++ks) {
+                bf16x8 nb0 = fb0, nb1 = fb1, na[RT];
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) na[rt] = fa[rt];
+                if (ks + 1 < 4) {
+                    nb0 = frag_tr(L.st, BPITCH, 16 * (ks + 1), 64 * nh, lane);
+                    nb1 = frag_tr(L.st, BPITCH, 16 * (ks + 1), 64 * nh + 32, lane);
+#pragma unroll
+                    for (int rt = 0; rt < RT; ++rt) na[rt] = lds_rows(L.tile, XPITCH, 32 * (rg * RT + rt), 16 * (ks + 1), lane);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) {
+                    acc[rt][0] = mfma(fa[rt], fb0, acc[rt][0]);
+                    acc[rt][1] = mfma(fa[rt], fb1, acc[rt][1]);
+                }
+                fb0 = nb0;
+                fb1 = nb1;
+#pragma unroll
+                for (int rt = 0; rt < RT; ++rt) fa[rt] = na[rt];
             }
         }
+        SSDK_STAMP(2, 1);
         if (has_dots) {
             // z^T[p][i] = (state C_i)[p] (role 1: (state B_j)[p]); the staged tile already carries the token's weight
             f32x16 z0 = zero16(), z1 = zero16();
+            bf16x8 a0 = lds_rows(L.st, BPITCH, 0, 0, lane), a1 = lds_rows(L.st, BPITCH, 32, 0, lane);
 #pragma unroll
             for (int ks = 0; ks < N_ / 16; ++ks) {
-                z0 = mfma(lds_rows(L.st, BPITCH, 0, 16 * ks, lane), rf[ks], z0);
-                z1 = mfma(lds_rows(L.st, BPITCH, 32, 16 * ks, lane), rf[ks], z1);
+                bf16x8 n0 = a0, n1 = a1;
+                if (ks + 1 < N_ / 16) {
+                    n0 = lds_rows(L.st, BPITCH, 0, 16 * (ks + 1), lane);
+                    n1 = lds_rows(L.st, BPITCH, 32, 16 * (ks + 1), lane);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                z0 = mfma(a0, rf[ks], z0);
+                z1 = mfma(a1, rf[ks], z1);
+                a0 = n0;
+                a1 = n1;
             }
             const int tok = 32 * w + (lane & 31);
             float sdot = 0.f;
@@ -524,6 +552,13 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& L, in
             sdot += __shfl_xor(sdot, 32, 64);
             if (lane < 32) (role ? sp.sterm : sp.gterm)[(((int64_t)b * sp.H + h0 + hh) * sp.nc + c) * Q + tok] = sdot;
         }
+        SSDK_STAMP(2, 2);
+        // the next head: its loads were issued a whole head ago; stage it into the other buffer, then ask for the one after
+        if (hh + 1 < hps) part_store<Q>(pr, LL.b[(hh + 1) & 1], role, tid);
+        SSDK_STAMP(2, 3);
+        if (hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 2, tid);
+        SSDK_STAMP(2, 4);
+        __syncthreads();
         SSDK_STAMP(2, 5);
     }
     float* part = sp.dbc_part + (((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * 2 + role) * ((int64_t)Q * N_);

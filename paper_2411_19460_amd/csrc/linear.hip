@@ -16,6 +16,8 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "mfma_common.h"
 
 namespace ssdk {
@@ -449,19 +451,29 @@ struct Side {
     SideStream outer;  // the same stream with a pair of events of its own, for callers inside the library
     bool ok = false;
 };
+std::mutex g_side_mu;
+
+// Created on first use on a device (or by ssd_init), under a lock; a partial failure releases what was created.
 Side* side_for_current_device() {
     static Side sides[64];
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_side_mu);
     Side& s = sides[dev];
-    if (!s.ok) {
-        if (hipStreamCreateWithFlags(&s.st, hipStreamNonBlocking) != hipSuccess) return nullptr;
-        hipEvent_t* evs[] = {&s.fork, &s.join, &s.outer.fork, &s.outer.join};
+    if (s.ok) return &s;
+    Side q;
+    bool good = hipStreamCreateWithFlags(&q.st, hipStreamNonBlocking) == hipSuccess;
+    hipEvent_t* evs[] = {&q.fork, &q.join, &q.outer.fork, &q.outer.join};
+    for (hipEvent_t* e : evs) good = good && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+    if (!good) {
         for (hipEvent_t* e : evs)
-            if (hipEventCreateWithFlags(e, hipEventDisableTiming) != hipSuccess) return nullptr;
-        s.outer.st = s.st;
-        s.ok = true;
+            if (*e) (void)hipEventDestroy(*e);
+        if (q.st) (void)hipStreamDestroy(q.st);
+        return nullptr;
     }
+    q.outer.st = q.st;
+    q.ok = true;
+    s = q;
     return &s;
 }
 

@@ -104,8 +104,8 @@ __global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
 // for every head of the slice.  Per head the token-major tile (x or dY, weighted per token) is
 // prefetched in registers during the previous head, staged in LDS and read with transpose loads.
 template <int Q>
-struct OuterLds {
-    char bc[Q * BPITCH];  // B or C rows of the chunk (prologue only)
+union OuterLds {
+    char bc[Q * BPITCH];  // B or C rows of the chunk (prologue only: each wave takes its fragments, then the space is xt)
     char xt[Q * XPITCH];  // weight * x or weight * dY
 };
 
@@ -146,8 +146,10 @@ __device__ __forceinline__ float outer_weight(const OuterPre<Q>& pr, int role, i
     return role == 0 ? __expf(pr.T - pr.cv[k]) * pr.dv[k] : __expf(pr.cv[k]);
 }
 
+// Two workgroups per compute unit (70 KB of LDS, at most 128 registers): one stages its next head while the
+// other contracts.
 template <int Q>
-__global__ __launch_bounds__(OUTER_THR) void mk_chunk_outer(SegParams sp, int nroles) {
+__global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int nroles) {
     constexpr int KS = Q / 16;
     __shared__ __attribute__((aligned(16))) OuterLds<Q> L;
     int z = blockIdx.x;
