@@ -93,8 +93,15 @@ enum {
     SSD_FLAG_RESIDUAL = 1,        /* fwd: y = x + SSD(x);  bwd: dx = dy + VJP(dy)  (the residual stack's layer) */
     SSD_FLAG_ACCUM_PARAM = 2,     /* bwd: dA, dD are added to instead of overwritten */
     SSD_FLAG_GENERIC_KERNELS = 4, /* force the shape-generic fp32-FMA kernels even where the MFMA path applies */
-    SSD_FLAG_BF16_CHECKPOINTS = 8 /* boundary_states holds bf16 instead of fp32 elements: half the S-checkpoint
+    SSD_FLAG_BF16_CHECKPOINTS = 8, /* boundary_states holds bf16 instead of fp32 elements: half the S-checkpoint
                                      term of App. C (Tab. 7 counts an fp32 state element as two); see ssd_fwd */
+    SSD_FLAG_FP32_CHUNK_STATES = 16 /* matrix-core kernels only (ignored by the shape-generic ones, which always do):
+                                     the per-chunk states and local state adjoints that feed the two state scans
+                                     are kept in fp32 inside the workspace (App. C: SSM states in fp32).  Default:
+                                     bf16, rounded once from the fp32 accumulators -- the running state of a scan
+                                     is fp32 in registers either way, and the states the contractions read are
+                                     bf16 matrix-core operands either way.  Costs 4 more bytes per state element
+                                     and chunk in each direction; ssd_workspace_bytes_flags accounts for it. */
 };
 
 /* Bytes of scratch the call needs for this shape (device memory, 256-byte aligned, contents
@@ -106,7 +113,7 @@ enum {
  * SSD_FLAG_GENERIC_KERNELS needs ssd_workspace_bytes_flags (the shape-generic kernels keep their
  * chunk states in fp32 and lay the scratch out differently). */
 size_t ssd_workspace_bytes(const ssd_shape_t* shape, int32_t is_backward);
-/* The same for a call made with `flags` (only SSD_FLAG_GENERIC_KERNELS changes the result). */
+/* The same for a call made with `flags` (SSD_FLAG_GENERIC_KERNELS and SSD_FLAG_FP32_CHUNK_STATES change the result). */
 size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is_backward, uint32_t flags);
 
 /*

@@ -14,7 +14,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libssd_magc.so")
 
 SSD_F32, SSD_BF16 = 0, 1
-SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16_CHECKPOINTS = 1, 2, 4, 8
+SSD_FLAG_RESIDUAL, SSD_FLAG_ACCUM_PARAM, SSD_FLAG_GENERIC_KERNELS, SSD_FLAG_BF16_CHECKPOINTS, SSD_FLAG_FP32_CHUNK_STATES = 1, 2, 4, 8, 16
 
 EXPORTS = ("ssd_workspace_bytes", "ssd_workspace_bytes_flags", "ssd_fwd", "ssd_bwd", "ssd_decode",
            "ssd_init", "ssd_fwd_static_bytes", "ssd_fwd_static",

@@ -57,7 +57,7 @@ int check_shape(const ssd_shape_t* sh, Dims* d) {
     return SSD_OK;
 }
 
-WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target) {
+WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target, bool fp32cs) {
     WsLayout w;
     memset(&w, 0, sizeof(w));
     size_t off = 0;
@@ -73,6 +73,7 @@ WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target) {
     w.dtf = take(tok);
     w.states = w.states_bf = w.dstates = w.dstates_bf = w.dbc_part = WS_NONE;  // present on one path only
     if (!mfma) w.states = take((size_t)d.Bt * (d.nc + 1) * d.H * PN * 4);
+    if (mfma && fp32cs) w.states = take((size_t)d.Bt * d.nc * d.H * PN * 4);  // slot c: chunk state c (scan input)
     w.Gm = take((size_t)d.Bt * d.nc * d.G * d.Q * d.Q * 4);
     w.ein = take(tok);
     w.eout = take(tok);
@@ -81,7 +82,7 @@ WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target) {
     w.dg_split = pick_split(d.hpg, groups, wg_target);
     w.part_split = pick_split(d.hpg, groups * 2, wg_target);
     if (bwd) {
-        if (!mfma) w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
+        if (!mfma || fp32cs) w.dstates = take((size_t)d.Bt * d.nc * d.H * PN * 4);
         if (mfma) w.dstates_bf = take((size_t)d.Bt * d.nc * d.H * PN * 2);
         {   // fp32 head sum (generic kernels) or one bf16 partial sum per head slice (MFMA kernels)
             const size_t per = mfma ? (size_t)d.Q * d.Q * 2 * w.dg_split : (size_t)d.Q * d.Q * 4;
@@ -338,7 +339,7 @@ extern "C" size_t ssd_workspace_bytes_flags(const ssd_shape_t* shape, int32_t is
     // never 0 for a valid shape, so that 0 unambiguously means "invalid"
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
-    const size_t block = align_up(ws_layout(d, is_backward != 0, mfma, wg_target(nl)).total);
+    const size_t block = align_up(ws_layout(d, is_backward != 0, mfma, wg_target(nl), (flags & SSD_FLAG_FP32_CHUNK_STATES) != 0).total);
     const size_t t = nl * block + (is_backward ? shared_bytes(d) : carry_bytes(d)) + tail_stage(d, is_backward != 0).total;
     return t ? t : 256;
 }
@@ -355,7 +356,7 @@ static int fwd_impl(const ssd_shape_t* shape, const void* x, const void* dt, con
     Dims d;
     int rc = check_shape(shape, &d);
     if (rc != SSD_OK) return rc;
-    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS))
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS | SSD_FLAG_FP32_CHUNK_STATES))
         return SSD_ERR_ARG;
     const bool ck16 = (flags & SSD_FLAG_BF16_CHECKPOINTS) && boundary_states;
     float* bnd32 = ck16 ? nullptr : (float*)boundary_states;
@@ -373,7 +374,7 @@ static int fwd_impl(const ssd_shape_t* shape, const void* x, const void* dt, con
     if (!x || !dt || !A || !B || !C || !D || !y) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma, one_stream);
-    const WsLayout w = ws_layout(d, false, mfma, wg_target(nl));
+    const WsLayout w = ws_layout(d, false, mfma, wg_target(nl), (flags & SSD_FLAG_FP32_CHUNK_STATES) != 0);
     const size_t block = align_up(w.total);
     const TailStage ts = tail_stage(d, false);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + carry_bytes(d) + ts.total) return SSD_ERR_WORKSPACE;
@@ -507,7 +508,7 @@ static size_t fwd_bytes_one_stream(const ssd_shape_t* shape, uint32_t flags) {
     Dims d;
     if (check_shape(shape, &d) != SSD_OK) return 0;
     const bool mfma = use_mfma(*shape, flags);
-    const size_t t = align_up(ws_layout(d, false, mfma, wg_target(1)).total) + carry_bytes(d) + tail_stage(d, false).total;
+    const size_t t = align_up(ws_layout(d, false, mfma, wg_target(1), (flags & SSD_FLAG_FP32_CHUNK_STATES) != 0).total) + carry_bytes(d) + tail_stage(d, false).total;
     return t ? t : 256;
 }
 }  // namespace ssdk
@@ -545,7 +546,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     Dims d;
     int rc = check_shape(shape, &d);
     if (rc != SSD_OK) return rc;
-    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS))
+    if (flags & ~(uint32_t)(SSD_FLAG_RESIDUAL | SSD_FLAG_GENERIC_KERNELS | SSD_FLAG_ACCUM_PARAM | SSD_FLAG_BF16_CHECKPOINTS | SSD_FLAG_FP32_CHUNK_STATES))
         return SSD_ERR_ARG;
     const bool ck16 = (flags & SSD_FLAG_BF16_CHECKPOINTS) && boundary_states;
     if (!dA || !dD) return SSD_ERR_NULL;
@@ -567,7 +568,7 @@ extern "C" int ssd_bwd(const ssd_shape_t* shape, const void* x, const void* dt, 
     if (!boundary_states && d.nseg > 1) return SSD_ERR_NULL;
     const bool mfma = use_mfma(*shape, flags);
     const int nl = lanes(d, mfma);
-    const WsLayout w = ws_layout(d, true, mfma, wg_target(nl));
+    const WsLayout w = ws_layout(d, true, mfma, wg_target(nl), (flags & SSD_FLAG_FP32_CHUNK_STATES) != 0);
     const size_t block = align_up(w.total);
     const TailStage ts = tail_stage(d, true);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < nl * block + shared_bytes(d) + ts.total) return SSD_ERR_WORKSPACE;

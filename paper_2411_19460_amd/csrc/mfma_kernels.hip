@@ -187,10 +187,17 @@ __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int
         f32x16 acc = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma(frag_tr(L.xt, XPITCH, 16 * ks, 32 * ph, lane), fb[ks], acc);
-        // bf16, into the slot where the scan will put the state entering the chunk (total adjoint leaving it)
-        __bf16* out = (__bf16*)(role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+        const int64_t so = (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
+        if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES) {  // fp32 scan input, in an array of its own
+            float* out = (role == 0 ? sp.states : sp.dstates) + so;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = (__bf16)acc[r];
+            for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = acc[r];
+        } else {
+            // bf16, into the slot where the scan will put the state entering the chunk (total adjoint leaving it)
+            __bf16* out = (__bf16*)(role == 0 ? sp.states_bf : sp.dstates_bf) + so;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = (__bf16)acc[r];
+        }
     }
 }
 
@@ -216,6 +223,7 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     if (sp.bnd_write) *(float4*)(sp.bnd_write + (int64_t)b * sp.bnd_write_bs + bh) = hc;
     if (sp.bnd_write16) *(bf16x4*)(sp.bnd_write16 + (int64_t)b * sp.bnd_write_bs + bh) = to_bf16x4(hc);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    const bool f32in = sp.flags & SSD_FLAG_FP32_CHUNK_STATES;
     constexpr int U = 8;  // chunks whose loads are in flight together (the recurrence itself is serial)
     for (int c0 = 0; c0 < sp.nc; c0 += U) {
         float4 sv[U];
@@ -223,9 +231,12 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 + u < sp.nc ? c0 + u : sp.nc - 1;
-            // chunk state (bf16), about to be replaced in place by the state entering the chunk
-            const bf16x4 sb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
-            sv[u] = make_float4((float)sb[0], (float)sb[1], (float)sb[2], (float)sb[3]);
+            if (f32in) {  // chunk state kept in fp32 (an array of its own)
+                sv[u] = *(const float4*)(sp.states + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+            } else {      // chunk state (bf16), about to be replaced in place by the state entering the chunk
+                const bf16x4 sb = *(const bf16x4*)(sp.states_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+                sv[u] = make_float4((float)sb[0], (float)sb[1], (float)sb[2], (float)sb[3]);
+            }
             av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
         }
 #pragma unroll
@@ -254,6 +265,7 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
     const int64_t ce = ((int64_t)b * sp.H + h) * PN + e;
     float4 g = *(const float4*)(sp.dcarry + ce);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
+    const bool f32in = sp.flags & SSD_FLAG_FP32_CHUNK_STATES;
     constexpr int U = 4;  // chunks whose loads are in flight together
     for (int c0 = sp.nc - 1; c0 >= 0; c0 -= U) {
         float4 lv[U], hv[U];
@@ -261,9 +273,12 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             const int c = c0 - u >= 0 ? c0 - u : 0;
-            // local adjoint (bf16), about to be replaced in place by the total adjoint leaving the chunk
-            const bf16x4 lb = *(const bf16x4*)(sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
-            lv[u] = make_float4((float)lb[0], (float)lb[1], (float)lb[2], (float)lb[3]);
+            if (f32in) {  // local adjoint kept in fp32 (an array of its own)
+                lv[u] = *(const float4*)(sp.dstates + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+            } else {      // local adjoint (bf16), about to be replaced in place by the total adjoint leaving the chunk
+                const bf16x4 lb = *(const bf16x4*)(sp.dstates_bf + (((int64_t)b * sp.nc + c) * sp.H + h) * PN + e);
+                lv[u] = make_float4((float)lb[0], (float)lb[1], (float)lb[2], (float)lb[3]);
+            }
             av[u] = cum[(int64_t)c * sp.Q + sp.Q - 1];
             // state entering chunk c (bf16 copy)
             {

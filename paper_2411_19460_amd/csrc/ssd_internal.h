@@ -167,7 +167,8 @@ struct WsLayout {
 int check_shape(const ssd_shape_t* sh, Dims* d);
 // mfma: the layout for the matrix-core kernels, which keep the chunk states and their adjoints in
 // bf16 only (the fp32 arrays of the shape-generic kernels are left out).
-WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target = 256);
+// fp32cs: the matrix-core layout keeps fp32 chunk states / local adjoints beside the bf16 operand copies.
+WsLayout ws_layout(const Dims& d, bool bwd, bool mfma, int wg_target = 256, bool fp32cs = false);
 void bind_workspace(SegParams& sp, const WsLayout& w, void* workspace, bool bwd);
 void base_params(SegParams& sp, const Dims& d, uint32_t flags);
 bool use_mfma(const ssd_shape_t& sh, uint32_t flags);

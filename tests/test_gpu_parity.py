@@ -289,6 +289,19 @@ def test_bf16_checkpoints(case):
                    dv.get("dfinal_state"), bnd32, fl | pk.SSD_FLAG_BF16_CHECKPOINTS)
 
 
+def test_fp32_chunk_states_flag():
+    """SSD_FLAG_FP32_CHUNK_STATES: the scans read their per-chunk inputs in fp32 (App. C keeps SSM states in fp32)
+    instead of the default bf16 copies; same results within the same bar, every tensor, states entering and
+    leaving the sequence included; and nothing but rounding separates the two variants."""
+    d = small_inputs(21, "bf16", 2, 1536, 4, 64, 2, 128)
+    rep = {}
+    dv, (y, fin, bnd, g) = compare_all(d, "bf16", 256, 512, flags=pk.SSD_FLAG_FP32_CHUNK_STATES, report=rep)
+    print("fp32 chunk states, errors:", {k: f"{v:.2e}" for k, v in rep.items()})
+    y0, fin0, bnd0, g0 = run_gpu(dv, 256, 512)
+    for a, b in ((y, y0), (fin, fin0), (g["dx"], g0["dx"]), (g["dB"], g0["dB"]), (g["dinit_state"], g0["dinit_state"])):
+        assert float((a.float() - b.float()).abs().max()) <= 2.0 ** -6 * float(b.float().abs().max())
+
+
 def test_forward_and_backward_can_be_captured_in_a_graph():
     """The calls enqueue only kernels and event record/wait pairs (no memset, no allocation, no host
     synchronisation), on the caller's stream and on the library's own streams forked from it: a stream
