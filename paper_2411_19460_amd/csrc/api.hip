@@ -298,9 +298,15 @@ bool serial_mode() {
     return serial || g_serial;
 }
 
+// SSD_MAGC_LANES=n (1 .. NPIPE) in the environment caps the segments in flight (measurements; the default is NPIPE).
 static int lanes(const Dims& d, bool mfma, bool one_stream = false) {
+    static const int cap = [] {
+        const char* v = getenv("SSD_MAGC_LANES");
+        const int n = v ? atoi(v) : NPIPE;
+        return n < 1 ? 1 : (n > NPIPE ? NPIPE : n);
+    }();
     if (!mfma || one_stream || serial_mode() || d.nseg <= 1) return 1;
-    return d.nseg < NPIPE ? (int)d.nseg : NPIPE;
+    return d.nseg < cap ? (int)d.nseg : cap;
 }
 
 // Workgroups a launch should have at least.  One segment at a time: one per compute unit.  Several

@@ -162,8 +162,15 @@ __device__ __forceinline__ void tile_load(bf16x8 (&go)[GO_MAX], bf16x8 (&gd)[4],
             for (int ks = 0; ks < 4; ++ks) go[4 * n + ks] = frag_rows(Mat, Q, tok0, 16 * (4 * K + ks), lane);
         }
     }
+    // the diagonal block carries the causal mask already (it does not depend on the head): scores of the
+    // contraction tokens beyond the lane's own token (forward) / before it (reverse) are zero
 #pragma unroll
-    for (int ks = 0; ks < 4; ++ks) gd[ks] = frag_rows(Mat, Q, tok0, 16 * (4 * I + ks), lane);
+    for (int ks = 0; ks < 4; ++ks) {
+        const bf16x8 v = frag_rows(Mat, Q, tok0, 16 * (4 * I + ks), lane);
+        const int kk0 = 16 * (4 * I + ks) + 8 * (lane >> 5), tok = tok0 + (lane & 31);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) gd[ks][e] = (REV ? kk0 + e >= tok : kk0 + e <= tok) ? v[e] : (__bf16)0.f;
+    }
 #pragma unroll
     for (int ks = 0; ks < RF_N; ++ks) rf[ks] = frag_rows(rowop, bt, tok0, 16 * ks, lane);
 }
@@ -253,12 +260,11 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
         bf16x8 fb;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const int kk = kk0 + e;
+            // masked scores are zero; the clamp keeps their factor finite (it is <= 0 wherever the score is not masked)
             const float diff = REV ? cv[e] - lane_c2 : lane_c2 - cv[e];
-            const bool ok = REV ? kk >= tok : kk <= tok;
             float f = (float)gv[e] * __builtin_amdgcn_exp2f(fminf(diff, 0.f));
             if (!REV) f *= dv[e];
-            fb[e] = (__bf16)(ok ? f : 0.f);
+            fb[e] = (__bf16)f;
         }
         acc0 = mfma(a0, fb, acc0);
         acc1 = mfma(a1, fb, acc1);

@@ -620,9 +620,11 @@ __global__ __launch_bounds__(512) void mk_bwd_trio(SegParams sp, int n_dual, int
 template <int Q>
 struct FinLds {
     char tiles[Q / 32][32 * TP];
-    char slab[Q * BPITCH];
+    char slab[64 * BPITCH];  // rows of B / C along the contraction, 64 at a time
 };
 
+// Small footprint on purpose (37 KB of LDS, few registers): the kernel only streams partial sums, and
+// several workgroups per compute unit keep enough loads in flight to do that at memory speed.
 template <int Q>
 __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
     constexpr int NT = Q / 32;
@@ -641,7 +643,11 @@ __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
     const int k_lo = role == 0 ? 0 : R, k_hi = role == 0 ? R : NT - 1;  // tiles along the contraction
     const int ns = sp.dg_split;
     const bf16_t* dg = (const bf16_t*)sp.dG + bcg * ns * ((int64_t)Q * Q);
-    // sum the slices of the needed dG tiles
+    // the head sums of this workgroup's rows: every slice's 16 values per lane asked for first, summed at the end
+    const int ps = sp.part_split;
+    const float* part = sp.dbc_part + (bcg * ps * 2 + role) * ((int64_t)Q * N_);
+    f32x16 acc = zero16();
+    // sum the slices of the needed dG tiles (one 16-byte piece of a tile per lane and pass, eight slices in flight)
     for (int tk = k_lo + w; tk <= k_hi; tk += NTH / 64) {
         const int ti = role == 0 ? R : tk, tj = role == 0 ? tk : R;
 #pragma unroll
@@ -652,12 +658,12 @@ __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) s[e] = 0.f;
             int sl = 0;
-            for (; sl + 4 <= ns; sl += 4) {  // four loads in flight; summation order stays slice 0, 1, 2, ...
-                bf16x8 vv[4];
+            for (; sl + 8 <= ns; sl += 8) {  // summation order stays slice 0, 1, 2, ...
+                bf16x8 vv[8];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) vv[u] = *(const bf16x8*)(src + (int64_t)(sl + u) * Q * Q);
+                for (int u = 0; u < 8; ++u) vv[u] = *(const bf16x8*)(src + (int64_t)(sl + u) * Q * Q);
 #pragma unroll
-                for (int u = 0; u < 4; ++u)
+                for (int u = 0; u < 8; ++u)
 #pragma unroll
                     for (int e = 0; e < 8; ++e) s[e] += (float)vv[u][e];
             }
@@ -672,26 +678,31 @@ __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
             *(bf16x8*)(L.tiles[tk] + row * TP + seg * 16) = o;
         }
     }
-    // rows of B (role 0) / C (role 1) along the contraction
-    for (int v = tid; v < (k_hi - k_lo + 1) * 32 * 16; v += NTH) {
-        const int row = 32 * k_lo + (v >> 4), seg = v & 15;
-        *(bf16x8*)(L.slab + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)row * bt + seg * 8);
-    }
-    __syncthreads();
-    f32x16 acc = zero16();
-    for (int tk = k_lo; tk <= k_hi; ++tk) {
+    // contraction with the rows of B (role 0) / C (role 1), 64 rows (two tiles) per step
+    const int p_lo = k_lo >> 1, p_hi = k_hi >> 1;  // pairs of tiles
+    for (int pr = p_lo; pr <= p_hi; ++pr) {
+        if (pr > p_lo) __syncthreads();  // every wave is done with the previous rows
+        for (int v = tid; v < 64 * 16; v += NTH) {
+            const int row = v >> 4, seg = v & 15;
+            *(bf16x8*)(L.slab + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)(64 * pr + row) * bt + seg * 8);
+        }
+        __syncthreads();  // the rows (and, the first time, the summed tiles) are in place
+        const char* slab = L.slab;
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            // role 0: tile is [i][j], operand rows i, contraction j: plain rows.
-            // role 1: tile is [i][j], operand rows j, contraction i: transpose load.
-            const bf16x8 fa = role == 0 ? lds_rows(L.tiles[tk], TP, 0, 16 * ks, lane) : frag_tr(L.tiles[tk], TP, 16 * ks, 0, lane);
-            const bf16x8 fb = frag_tr(L.slab, BPITCH, 32 * tk + 16 * ks, 32 * w, lane);
-            acc = mfma(fa, fb, acc);
+        for (int t2 = 0; t2 < 2; ++t2) {
+            const int tk = 2 * pr + t2;
+            if (tk < k_lo || tk > k_hi) continue;
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                // role 0: tile is [i][j], operand rows i, contraction j: plain rows.
+                // role 1: tile is [i][j], operand rows j, contraction i: transpose load.
+                const bf16x8 fa = role == 0 ? lds_rows(L.tiles[tk], TP, 0, 16 * ks, lane) : frag_tr(L.tiles[tk], TP, 16 * ks, 0, lane);
+                const bf16x8 fb = frag_tr(slab, BPITCH, 32 * t2 + 16 * ks, 32 * w, lane);
+                acc = mfma(fa, fb, acc);
+            }
         }
     }
     bf16_t* out = (role == 0 ? (bf16_t*)sp.dC : (bf16_t*)sp.dB) + bbase;
-    const int ps = sp.part_split;
-    const float* part = sp.dbc_part + (bcg * ps * 2 + role) * ((int64_t)Q * N_);
     // the head sums arrive slice by slice, all 16 rows of a slice in flight at once
     for (int s = 0; s < ps; ++s) {
         float pv[16];

@@ -148,7 +148,7 @@ __device__ __forceinline__ float outer_weight(const OuterPre<Q>& pr, int role, i
 
 // Two workgroups per compute unit (70 KB of LDS, at most 128 registers): one stages its next head while the
 // other contracts.
-template <int Q>
+template <int Q, bool F32OUT>
 __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int nroles) {
     constexpr int KS = Q / 16;
     __shared__ __attribute__((aligned(16))) OuterLds<Q> L;
@@ -188,7 +188,7 @@ __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma(frag_tr(L.xt, XPITCH, 16 * ks, 32 * ph, lane), fb[ks], acc);
         const int64_t so = (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
-        if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES) {  // fp32 scan input, in an array of its own
+        if (F32OUT) {  // fp32 scan input, in an array of its own
             float* out = (role == 0 ? sp.states : sp.dstates) + so;
 #pragma unroll
             for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = acc[r];
@@ -211,6 +211,7 @@ __device__ __forceinline__ bf16x4 to_bf16x4(const float4 v) {
     return r;
 }
 
+template <bool F32IN>  // F32IN: the chunk states arrive in fp32 (SSD_FLAG_FP32_CHUNK_STATES), else as bf16 in place
 __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
@@ -223,7 +224,7 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
     if (sp.bnd_write) *(float4*)(sp.bnd_write + (int64_t)b * sp.bnd_write_bs + bh) = hc;
     if (sp.bnd_write16) *(bf16x4*)(sp.bnd_write16 + (int64_t)b * sp.bnd_write_bs + bh) = to_bf16x4(hc);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
-    const bool f32in = sp.flags & SSD_FLAG_FP32_CHUNK_STATES;
+    constexpr bool f32in = F32IN;
     constexpr int U = 8;  // chunks whose loads are in flight together (the recurrence itself is serial)
     for (int c0 = 0; c0 < sp.nc; c0 += U) {
         float4 sv[U];
@@ -259,13 +260,14 @@ __global__ __launch_bounds__(NTH) void mk_scan_fwd(SegParams sp) {
 // Reverse pass over the chunk-state adjoints; emits the bf16 copies and the per-wave partial sums
 // of exp(T_c) <dHnext_c, Hprev_c>, the gradient of the chunk's total decay through the carried state
 // (fixed summation order).
+template <bool F32IN>
 __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
     constexpr int PN = P_ * N_;
     const int e = (blockIdx.x * NTH + threadIdx.x) * 4, h = blockIdx.y, b = blockIdx.z;
     const int64_t ce = ((int64_t)b * sp.H + h) * PN + e;
     float4 g = *(const float4*)(sp.dcarry + ce);
     const float* cum = sp.cum + ((int64_t)b * sp.H + h) * sp.nc * sp.Q;
-    const bool f32in = sp.flags & SSD_FLAG_FP32_CHUNK_STATES;
+    constexpr bool f32in = F32IN;
     constexpr int U = 4;  // chunks whose loads are in flight together
     for (int c0 = sp.nc - 1; c0 >= 0; c0 -= U) {
         float4 lv[U], hv[U];
@@ -315,12 +317,18 @@ hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
         SegParams so = sp;
         const int nroles = need_y ? 1 : 2;
         so.outer_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G * nroles, sp.wg_target);
-        SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, mk_chunk_outer<Q>, dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
+        if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES)
+            SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, (mk_chunk_outer<Q, true>), dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
+        else
+            SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, (mk_chunk_outer<Q, false>), dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
     }
     SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
     // the scan is the only step that needs the previous segment (its leaving state)
     if (need_y && sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
-    SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES)
+        SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd<true>, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    else
+        SSDK_LAUNCH(K_SCAN_FWD, st, mk_scan_fwd<false>, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
     if (need_y && sp.ev_record && hipEventRecord(sp.ev_record, st) != hipSuccess) return hipErrorUnknown;
     if (need_y) {
         hipError_t e = mfma_launch_dual(sp, 0, st);
@@ -335,7 +343,10 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     sp.nslice = P_ * N_ / 4 / 64;  // partial sums written by mk_scan_bwd: one per wave
     // the reverse scan is the only step that needs the segment to the right (its entering-state adjoint)
     if (sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
-    SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES)
+        SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd<true>, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
+    else
+        SSDK_LAUNCH(K_SCAN_BWD, st, mk_scan_bwd<false>, dim3(P_ * N_ / 4 / NTH, sp.H, sp.Bt), dim3(NTH), sp);
     if (sp.ev_record && hipEventRecord(sp.ev_record, st) != hipSuccess) return hipErrorUnknown;
     // dx, dG and the dB / dC head sums (which also write the chunk-local part of the gradient of cum
     // and the state dot products): one launch when the three share a workgroup size
