@@ -557,7 +557,7 @@ def measured_peak(torch, fn):
     return torch.cuda.max_memory_allocated() - base, out
 
 
-def layer_bench(cfg, steps, warmup, flags, pk, synth, torch, dev, per_kernel):
+def layer_bench(cfg, steps, warmup, flags, pk, synth, torch, dev, per_kernel, measure_peak=True):
     """ssd_fwd + ssd_bwd of one layer on inputs resident in HBM: wall clock over exactly `steps` steps, the
     median over the steps (an event between steps), the measured peak of device memory beyond inputs and
     outputs for MA-GC and for one segment = the whole sequence, and, on request, the per-kernel table."""
@@ -578,8 +578,10 @@ def layer_bench(cfg, steps, warmup, flags, pk, synth, torch, dev, per_kernel):
                    None, dA, dD, out=out_b)
 
     one_pass(cfg.segment)          # warm: library streams and events exist, code objects are loaded
-    peak_magc, _ = measured_peak(torch, lambda: one_pass(cfg.segment))
-    peak_full, _ = measured_peak(torch, lambda: one_pass(None))
+    peak_magc = peak_full = None
+    if measure_peak:
+        peak_magc, _ = measured_peak(torch, lambda: one_pass(cfg.segment))
+        peak_full, _ = measured_peak(torch, lambda: one_pass(None))
     torch.cuda.empty_cache()
     shape = pk.make_shape(d["x"], d["B"], cfg.chunk, cfg.segment)
     peak_hbm = {"magc_bytes": peak_magc, "full_activation_bytes": peak_full,
@@ -707,6 +709,7 @@ def main():
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
     ap.add_argument("--bf16-checkpoints", action="store_true", help="keep the segment checkpoints in bf16 (half the bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-peak", action="store_true", help="skip the two passes that measure peak memory (profiler runs: every launch of the run then has the benchmark's shape)")
     ap.add_argument("--no-extras", action="store_true", help="skip the L = 2^20 layer and the 16-layer stack (configs_extra)")
     ap.add_argument("--inference", action="store_true",
                     help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
@@ -838,7 +841,7 @@ def main():
     if args.bf16_checkpoints:
         flags |= pk.SSD_FLAG_BF16_CHECKPOINTS
     Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
-    main = layer_bench(cfg, args.steps, args.warmup, flags, pk, synth, torch, dev, per_kernel=True)
+    main = layer_bench(cfg, args.steps, args.warmup, flags, pk, synth, torch, dev, per_kernel=True, measure_peak=not args.no_peak)
     tok_s, ms_per_step = main["tokens_per_s"], main["ms_per_step"]
     kernels, dom = main["kernels_serialized"], main["dominant"]
     group = KERNEL_GROUP.get(dom, "bwd")

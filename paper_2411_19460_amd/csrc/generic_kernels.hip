@@ -16,6 +16,7 @@
 //     da_r   = sum_{i>=r} (dY_i . yhat_i - dt_i x_i . u_i) + <dHnext, Hnext>
 //     ddt_j  = A da_j + x_j . u_j,  dA += sum_j dt_j da_j,  dD += sum dY . x
 // Every exponent is formed from a difference that is <= 0, so nothing overflows.
+#include "ddt_finalize.h"
 #include "ssd_internal.h"
 
 namespace ssdk {
@@ -355,69 +356,7 @@ template <typename T>
 __global__ void k_ddt_finalize(SegParams sp) {
     __shared__ float s[1024];
     __shared__ float s2[1024];
-    const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
-    const int Q = sp.Q;
-    const int64_t cbase = (((int64_t)b * sp.H + h) * sp.nc + c) * Q;
-    // reverse order so that an inclusive forward scan yields the suffix sums
-    const int ri = Q - 1 - i;
-    // Matrix-core path: the gradient of cum_i arrives as gterm_i + gintra_i - sterm_i, and the gradient of
-    // cum at the chunk end carries + sum_j sterm_j (the chunk state depends on T - cum_j): the very same
-    // sterm values enter with both signs, so their cancellation in the suffix sums is exact.
-    float gt = 0.f, st_sum = 0.f;
-    const bool split = sp.flags & SSD_INTERNAL_SPLIT_GTERM;
-    if (i < Q) {
-        gt = sp.gterm[cbase + ri];
-        if (split) {
-            const float sv = sp.sterm[cbase + ri];
-            gt += sp.gintra[cbase + ri] - sv;
-            st_sum = sv;
-        }
-    }
-    if (split) {
-        s2[i] = st_sum;
-        __syncthreads();
-        for (int off = blockDim.x >> 1; off > 0; off >>= 1) {
-            if (i < off) s2[i] += s2[i + off];
-            __syncthreads();
-        }
-        st_sum = s2[0];
-        __syncthreads();
-    }
-    s[i] = gt;
-    __syncthreads();
-    for (int off = 1; off < (int)blockDim.x; off <<= 1) {
-        const float v = (i >= off) ? s[i - off] : 0.f;
-        __syncthreads();
-        s[i] += v;
-        __syncthreads();
-    }
-    float tail = 0.f;
-    const float* tp = sp.tail_part + ((((int64_t)b * sp.H + h) * sp.nc + c)) * sp.nslice;
-    for (int k = 0; k < sp.nslice; ++k) tail += tp[k];
-    tail += st_sum;
-    float pa = 0.f, pd = 0.f;
-    if (i < Q) {
-        const float da = s[i] + tail;  // belongs to token ri
-        const float d = sp.dtf[cbase + ri];
-        IO<T>::st(sp.ddt, (int64_t)b * sp.dts_b + ((int64_t)c * Q + ri) * sp.H + h, sp.A[h] * da + sp.fterm[cbase + ri]);
-        pa = d * da;
-        pd = sp.dDrow[cbase + ri];
-    }
-    __syncthreads();
-    s[i] = pa;
-    s2[i] = pd;
-    __syncthreads();
-    for (int off = blockDim.x >> 1; off > 0; off >>= 1) {
-        if (i < off) {
-            s[i] += s[i + off];
-            s2[i] += s2[i + off];
-        }
-        __syncthreads();
-    }
-    if (i == 0) {
-        sp.dA_part[((int64_t)b * sp.nc_total + sp.chunk0 + c) * sp.H + h] = s[0];
-        sp.dD_part[((int64_t)b * sp.nc_total + sp.chunk0 + c) * sp.H + h] = s2[0];
-    }
+    ddt_finalize_body(sp, s, s2, blockIdx.x, blockIdx.y, blockIdx.z, [&](int64_t idx, float v) { IO<T>::st(sp.ddt, idx, v); });
 }
 
 // One block per head: strided partial sums, then a fixed-shape tree (deterministic).

@@ -16,6 +16,7 @@
 //   mk_dBC_final: sums the slices, contracts dG with B / dG^T with C, adds the head sums, rounds once.
 // The decay of an off-diagonal tile is the product of a per-row factor, a per-column factor and a
 // per-tile scalar, all <= 1 (32-token granularity); diagonal tiles evaluate exp() per element.
+#include "ddt_finalize.h"
 #include "dual_body.h"
 #include "mfma_common.h"
 
@@ -626,10 +627,8 @@ struct FinLds {
 // Small footprint on purpose (37 KB of LDS, few registers): the kernel only streams partial sums, and
 // several workgroups per compute unit keep enough loads in flight to do that at memory speed.
 template <int Q>
-__global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
+__device__ __forceinline__ void final_body(const SegParams& sp, FinLds<Q>& L, int z) {
     constexpr int NT = Q / 32;
-    __shared__ __attribute__((aligned(16))) FinLds<Q> L;
-    int z = blockIdx.x;
     const int R = z % NT;
     z /= NT;
     const int role = z & 1;
@@ -718,6 +717,34 @@ __global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
 }
 
 template <int Q>
+__global__ __launch_bounds__(NTH) void mk_dBC_final(SegParams sp) {
+    __shared__ __attribute__((aligned(16))) FinLds<Q> L;
+    final_body<Q>(sp, L, blockIdx.x);
+}
+
+// The two steps behind the head-walking passes -- dB / dC from the partial sums, and ddt with the chunk's dA / dD
+// partial sums from the per-token scalars -- as one launch (chunk 256: both run 256 threads per workgroup): the
+// first n_final workgroups do the former, the rest one (chunk, head) of the latter each.
+union FinDdtLds {
+    FinLds<256> fin;
+    float s[2][256];
+};
+
+__global__ __launch_bounds__(NTH) void mk_final_ddt(SegParams sp, int n_final) {
+    __shared__ __attribute__((aligned(16))) FinDdtLds L;
+    int z = blockIdx.x;
+    if (z < n_final) {
+        final_body<256>(sp, L.fin, z);
+    } else {
+        z -= n_final;
+        const int c = z % sp.nc;
+        z /= sp.nc;
+        ddt_finalize_body(sp, L.s[0], L.s[1], c, z % sp.H, z / sp.H,
+                          [&](int64_t idx, float v) { ((bf16_t*)sp.ddt)[idx] = float_to_bf16(v); });
+    }
+}
+
+template <int Q>
 hipError_t grad_bc_q(const SegParams& sp0, bool with_dual, hipStream_t st) {
     SegParams sp = sp0;
     const int n_dg = sp.Bt * sp.nc * sp.G * sp.dg_split, n_part = sp.Bt * sp.nc * sp.G * 2 * sp.part_split;
@@ -730,7 +757,11 @@ hipError_t grad_bc_q(const SegParams& sp0, bool with_dual, hipStream_t st) {
         SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(n_dg), dim3(64 * DgMap<Q>::NWV), sp);
         SSDK_LAUNCH(K_MFMA_DBC, st, mk_dBC_part<Q>, dim3(n_part), dim3(PartCfg<Q>::NTHR), sp);
     }
-    SSDK_LAUNCH(K_MFMA_DBC_FINAL, st, mk_dBC_final<Q>, dim3(sp.Bt * sp.nc * sp.G * 2 * (Q / 32)), dim3(NTH), sp);
+    const int n_final = sp.Bt * sp.nc * sp.G * 2 * (Q / 32);
+    if (Q == 256 && (sp.flags & SSD_INTERNAL_SPLIT_GTERM))  // the caller has asked for the scalar step in the same launch
+        SSDK_LAUNCH(K_MFMA_FINAL_DDT, st, mk_final_ddt, dim3(n_final + sp.nc * sp.H * sp.Bt), dim3(NTH), sp, n_final);
+    else
+        SSDK_LAUNCH(K_MFMA_DBC_FINAL, st, mk_dBC_final<Q>, dim3(n_final), dim3(NTH), sp);
     return hipSuccess;
 }
 

@@ -29,9 +29,8 @@ using namespace mf;
 // ---------------------------------------------------------------------------------------------
 // Decay preparation: cum (chunk-local inclusive cumsum of dt*A), dt in fp32, ein, eout.
 template <int Q>
-__global__ __launch_bounds__(Q) void mk_prep(SegParams sp) {
-    __shared__ float s[Q];
-    const int i = threadIdx.x, c = blockIdx.x, h = blockIdx.y, b = blockIdx.z;
+__device__ __forceinline__ void prep_body(const SegParams& sp, float* s, int c, int h, int b) {
+    const int i = threadIdx.x;
     const float d = bf16_to_float(((const bf16_t*)sp.dt)[(int64_t)b * sp.dts_b + ((int64_t)c * Q + i) * sp.H + h]);
     s[i] = d * sp.A[h] + ((sp.reset && sp.reset[(int64_t)b * sp.reset_bs + (int64_t)c * Q + i]) ? RESET_LOG_DECAY : 0.f);
     __syncthreads();
@@ -50,14 +49,20 @@ __global__ __launch_bounds__(Q) void mk_prep(SegParams sp) {
     sp.eout[o] = __expf(s[bs + BLK - 1] - s[i]);
 }
 
+template <int Q>
+__global__ __launch_bounds__(Q) void mk_prep(SegParams sp) {
+    __shared__ float s[Q];
+    prep_body<Q>(sp, s, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
 // ---------------------------------------------------------------------------------------------
 // Scores of one chunk and group: G[i][j] = C_i . B_j and its transpose, bf16, for the 64 x 64 blocks
 // on and below the diagonal.  Layout in the scratch area: G [Q][Q] then GT [Q][Q].
 template <int Q>
-__global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
+__device__ __forceinline__ void cb_body(const SegParams& sp, int z, int pair) {
     constexpr int NB = Q / BLK;
-    const int z = blockIdx.x, g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
-    int I = 0, rem = blockIdx.y;  // blockIdx.y enumerates the block pairs (I, J <= I)
+    const int g = z % sp.G, c = (z / sp.G) % sp.nc, b = z / (sp.G * sp.nc);
+    int I = 0, rem = pair;  // pair enumerates the block pairs (I, J <= I)
     while (rem > I) {
         rem -= I + 1;
         ++I;
@@ -90,6 +95,28 @@ __global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
         const int rr = 8 * q + 4 * (lane >> 5);
         *(bf16x4*)(GTd + (int64_t)(j0 + (lane & 31)) * Q + i0 + rr) = v1;
         *(bf16x4*)(Gd + (int64_t)(i0 + (lane & 31)) * Q + j0 + rr) = v2;
+    }
+}
+
+template <int Q>
+__global__ __launch_bounds__(NTH) void mk_cb(SegParams sp) {
+    cb_body<Q>(sp, blockIdx.x, blockIdx.y);
+}
+
+// The two steps that need nothing but the inputs -- decay preparation and scores -- as one launch (chunk 256: both
+// run 256 threads per workgroup): the first n_prep workgroups do one (chunk, head) of the former each, the rest one
+// 64 x 64 block pair of the latter.
+__global__ __launch_bounds__(NTH) void mk_prep_cb(SegParams sp, int n_prep) {
+    constexpr int Q = 256, NPAIR = (Q / BLK) * (Q / BLK + 1) / 2;
+    __shared__ float s[Q];
+    int z = blockIdx.x;
+    if (z < n_prep) {
+        const int c = z % sp.nc;
+        z /= sp.nc;
+        prep_body<Q>(sp, s, c, z % sp.H, z / sp.H);
+    } else {
+        z -= n_prep;
+        cb_body<Q>(sp, z / NPAIR, z % NPAIR);
     }
 }
 
@@ -312,7 +339,11 @@ __global__ __launch_bounds__(NTH) void mk_scan_bwd(SegParams sp) {
 template <int Q>
 hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
     constexpr int NB = Q / BLK;
-    SSDK_LAUNCH(K_CUMSUM, st, mk_prep<Q>, dim3(sp.nc, sp.H, sp.Bt), dim3(Q), sp);
+    const int n_prep = sp.nc * sp.H * sp.Bt, n_cb = sp.Bt * sp.nc * sp.G * (NB * (NB + 1) / 2);
+    if (Q == 256)
+        SSDK_LAUNCH(K_MFMA_PREP_CB, st, mk_prep_cb, dim3(n_prep + n_cb), dim3(NTH), sp, n_prep);
+    else
+        SSDK_LAUNCH(K_CUMSUM, st, mk_prep<Q>, dim3(sp.nc, sp.H, sp.Bt), dim3(Q), sp);
     {   // chunk states; on the backward path (need_y false) the local state adjoints ride in the same launch
         SegParams so = sp;
         const int nroles = need_y ? 1 : 2;
@@ -322,7 +353,7 @@ hipError_t fwd_q(const SegParams& sp, bool need_y, hipStream_t st) {
         else
             SSDK_LAUNCH(need_y ? K_MFMA_CHUNK_STATE : K_MFMA_DSTATE, st, (mk_chunk_outer<Q, false>), dim3(sp.Bt * sp.nc * sp.G * nroles * so.outer_split), dim3(OUTER_THR), so, nroles);
     }
-    SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
+    if (Q != 256) SSDK_LAUNCH(K_MFMA_CB, st, mk_cb<Q>, dim3(sp.Bt * sp.nc * sp.G, NB * (NB + 1) / 2), dim3(NTH), sp);
     // the scan is the only step that needs the previous segment (its leaving state)
     if (need_y && sp.ev_wait && hipStreamWaitEvent(st, sp.ev_wait, 0) != hipSuccess) return hipErrorUnknown;
     if (sp.flags & SSD_FLAG_FP32_CHUNK_STATES)
@@ -353,11 +384,16 @@ hipError_t bwd_q(const SegParams& sp0, hipStream_t st) {
     const bool trio = Q == 256;
     hipError_t e = trio ? hipSuccess : mfma_launch_dual(sp, 2, st);
     if (e != hipSuccess) return e;
-    e = mfma_launch_grad_bc(sp, trio, st);
+    sp.flags |= SSD_INTERNAL_SPLIT_GTERM;  // the gradient of cum arrives in three pieces
+    e = mfma_launch_grad_bc(sp, trio, st);   // chunk 256: ddt and the dA / dD partial sums ride in its last launch
     if (e != hipSuccess) return e;
-    sp.flags |= SSD_INTERNAL_SPLIT_GTERM;
-    e = generic_backward_scalars(sp, st);
-    if (e != hipSuccess) return e;
+    if (Q != 256) {
+        e = generic_backward_scalars(sp, st);
+        if (e != hipSuccess) return e;
+    } else if (!sp.defer_param) {
+        e = launch_param_reduce(sp, st);
+        if (e != hipSuccess) return e;
+    }
     return hipSuccess;
 }
 

@@ -19,7 +19,7 @@ std::vector<hipEvent_t> g_pool;
 const char* const g_names[K_COUNT] = {
     "cumsum", "cb", "chunk_state", "state_scan_fwd", "chunk_out", "dstate_local", "state_scan_bwd", "bwd_main",
     "ddt_finalize", "param_reduce", "dG", "dBC", "fill", "copy",
-    "mfma_cb", "mfma_chunk_state", "mfma_chunk_out", "mfma_dstate_local", "mfma_bwd_main", "mfma_dG", "mfma_dBC", "mfma_dBC_final", "mfma_bwd_trio"};
+    "mfma_cb", "mfma_chunk_state", "mfma_chunk_out", "mfma_dstate_local", "mfma_bwd_main", "mfma_dG", "mfma_dBC", "mfma_dBC_final", "mfma_bwd_trio", "mfma_prep_cb", "mfma_final_ddt"};
 
 hipEvent_t take_event() {
     if (!g_pool.empty()) {

@@ -177,7 +177,7 @@ bool use_mfma(const ssd_shape_t& sh, uint32_t flags);
 enum KernelId {
     K_CUMSUM, K_CB, K_CHUNK_STATE, K_SCAN_FWD, K_CHUNK_OUT, K_DSTATE, K_SCAN_BWD, K_BWD_MAIN, K_DDT, K_PARAM, K_DG, K_DBC,
     K_FILL, K_COPY, K_MFMA_CB, K_MFMA_CHUNK_STATE, K_MFMA_CHUNK_OUT, K_MFMA_DSTATE, K_MFMA_BWD_MAIN, K_MFMA_DG,
-    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_MFMA_BWD_TRIO, K_COUNT
+    K_MFMA_DBC, K_MFMA_DBC_FINAL, K_MFMA_BWD_TRIO, K_MFMA_PREP_CB, K_MFMA_FINAL_DDT, K_COUNT
 };
 // When timing of kernel `kid` is enabled: a pair of events for the launch to fill in (kernel start
 // and end, as the command processor stamps them -- the time the launch waits behind other work is
