@@ -710,6 +710,7 @@ def main():
     ap.add_argument("--bf16-checkpoints", action="store_true", help="keep the segment checkpoints in bf16 (half the bytes)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-peak", action="store_true", help="skip the two passes that measure peak memory (profiler runs: every launch of the run then has the benchmark's shape)")
+    ap.add_argument("--timed-only", action="store_true", help="profiler runs: warm-up and the timed steps only, no per-kernel passes")
     ap.add_argument("--no-extras", action="store_true", help="skip the L = 2^20 layer and the 16-layer stack (configs_extra)")
     ap.add_argument("--inference", action="store_true",
                     help="instead of the training step: forward-only prefill without checkpoints (tokens/s) and the "
@@ -841,7 +842,13 @@ def main():
     if args.bf16_checkpoints:
         flags |= pk.SSD_FLAG_BF16_CHECKPOINTS
     Bt, L, H, P, N, G = cfg.batch, cfg.seqlen, cfg.nheads, cfg.headdim, cfg.dstate, cfg.ngroups
-    main = layer_bench(cfg, args.steps, args.warmup, flags, pk, synth, torch, dev, per_kernel=True, measure_peak=not args.no_peak)
+    main = layer_bench(cfg, args.steps, args.warmup, flags, pk, synth, torch, dev, per_kernel=not args.timed_only,
+                       measure_peak=not args.no_peak)
+    if args.timed_only:   # profiler runs that want nothing but launches of the timed configuration
+        print(json.dumps({"metric": "SSD fwd+bwd tokens/sec/layer", "value": main["tokens_per_s"], "unit": "tokens/s",
+                          "ms_per_step": main["ms_per_step"], "median_ms_per_step": main["median_ms_per_step"],
+                          "config": {"workload": cfg.name}, "note": "timed region only (no per-kernel pass, no roofline)"}))
+        return
     tok_s, ms_per_step = main["tokens_per_s"], main["ms_per_step"]
     kernels, dom = main["kernels_serialized"], main["dominant"]
     group = KERNEL_GROUP.get(dom, "bwd")

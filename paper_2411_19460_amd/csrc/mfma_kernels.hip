@@ -180,6 +180,7 @@ __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int
     constexpr int KS = Q / 16;
     __shared__ __attribute__((aligned(16))) OuterLds<Q> L;
     int z = blockIdx.x;
+    [[maybe_unused]] const int zlog = z;
     if ((gridDim.x & 7) == 0) z = (z & 7) * (gridDim.x >> 3) + (z >> 3);
     const int ns = sp.outer_split, slice = z % ns;
     z /= ns;
@@ -203,14 +204,19 @@ __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int
     for (int ks = 0; ks < KS; ++ks) fb[ks] = frag_tr(L.bc, BPITCH, 16 * ks, 32 * nt, lane);
     for (int hh = 0; hh < hps; ++hh) {
         const int h = h0 + hh;
+        SSDK_STAMP(4, 0);
         __syncthreads();
+        SSDK_STAMP(4, 1);
 #pragma unroll
         for (int k = 0; k < OuterPre<Q>::NV; ++k) {
             const int v = tid + OUTER_THR * k, row = v >> 3, seg = v & 7;
             if (v < Q * 8) *(bf16x8*)(L.xt + row * XPITCH + seg * 16) = scale8(pr.t[k], outer_weight<Q>(pr, role, k));
         }
+        SSDK_STAMP(4, 2);
         __syncthreads();
+        SSDK_STAMP(4, 3);
         if (hh + 1 < hps) outer_load<Q>(pr, sp, role, b, c, h + 1, tid);
+        SSDK_STAMP(4, 4);
         f32x16 acc = zero16();
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks) acc = mfma(frag_tr(L.xt, XPITCH, 16 * ks, 32 * ph, lane), fb[ks], acc);
@@ -225,6 +231,7 @@ __global__ __launch_bounds__(OUTER_THR, 2) void mk_chunk_outer(SegParams sp, int
 #pragma unroll
             for (int r = 0; r < 16; ++r) out[(32 * ph + acc_row(r, lane)) * N_ + 32 * nt + (lane & 31)] = (__bf16)acc[r];
         }
+        SSDK_STAMP(4, 5);
     }
 }
 
