@@ -486,10 +486,16 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& LL, i
 #pragma unroll
         for (int ks = 0; ks < N_ / 16; ++ks) rf[ks] = frag_rows(rowop, bt, 32 * w, 16 * ks, lane);
     }
+    // Order of the heads.  When this pass runs beside the other two head-walking passes with half as many slices
+    // (twice the heads per workgroup, at about twice their pace per head), it alternates between the two half
+    // slices -- heads 0, n/2, 1, n/2 + 1, ... -- so that it reads a head's x / dY tile while the two workgroups of
+    // the other passes that walk those halves are on it too and the tile is still in the L2 slice they share.
+    const bool alt = sp.part_alternate && (hps & 1) == 0;
+    auto head_at = [&](int i) { return h0 + (alt ? (i >> 1) + (i & 1) * (hps >> 1) : i); };
     PartPre<Q> pr;
-    part_load<Q>(pr, sp, role, b, c, h0, tid);
+    part_load<Q>(pr, sp, role, b, c, head_at(0), tid);
     part_store<Q>(pr, LL.b[0], role, tid);
-    if (hps > 1) part_load<Q>(pr, sp, role, b, c, h0 + 1, tid);
+    if (hps > 1) part_load<Q>(pr, sp, role, b, c, head_at(1), tid);
     __syncthreads();
     for (int hh = 0; hh < hps; ++hh) {
         SSDK_STAMP(2, 0);
@@ -551,13 +557,13 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& LL, i
                     for (int e = 0; e < 4; ++e) sdot += (float)o[e] * (pt ? z1 : z0)[4 * q + e];
                 }
             sdot += __shfl_xor(sdot, 32, 64);
-            if (lane < 32) (role ? sp.sterm : sp.gterm)[(((int64_t)b * sp.H + h0 + hh) * sp.nc + c) * Q + tok] = sdot;
+            if (lane < 32) (role ? sp.sterm : sp.gterm)[(((int64_t)b * sp.H + head_at(hh)) * sp.nc + c) * Q + tok] = sdot;
         }
         SSDK_STAMP(2, 2);
         // the next head: its loads were issued a whole head ago; stage it into the other buffer, then ask for the one after
         if (hh + 1 < hps) part_store<Q>(pr, LL.b[(hh + 1) & 1], role, tid);
         SSDK_STAMP(2, 3);
-        if (hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, h0 + hh + 2, tid);
+        if (hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, head_at(hh + 2), tid);
         SSDK_STAMP(2, 4);
         __syncthreads();
         SSDK_STAMP(2, 5);
@@ -752,6 +758,7 @@ hipError_t grad_bc_q(const SegParams& sp0, bool with_dual, hipStream_t st) {
         if (Q != 256) return hipErrorInvalidValue;
         sp.dual_split = pick_split(sp.hpg, (int64_t)sp.Bt * sp.nc * sp.G, sp.wg_target);
         const int n_dual = sp.Bt * sp.nc * sp.G * sp.dual_split;
+        sp.part_alternate = sp.dual_split == 2 * sp.part_split && sp.dg_split == sp.dual_split;
         SSDK_LAUNCH(K_MFMA_BWD_TRIO, st, mk_bwd_trio<256>, dim3(n_dual + n_dg + n_part), dim3(512), sp, n_dual, n_dg, n_part);
     } else {
         SSDK_LAUNCH(K_MFMA_DG, st, mk_dG<Q>, dim3(n_dg), dim3(64 * DgMap<Q>::NWV), sp);

@@ -90,6 +90,7 @@ struct SegParams {
     int dual_split;      // number of head slices per (batch, chunk, group) in the dual-form kernels
     int part_split;      // number of head slices of the dB / dC head sums
     int outer_split;     // number of head slices of the chunk-state / local-adjoint kernel
+    int part_alternate;  // the head-sum pass alternates between the halves of its slice (see part_body)
     int wg_target;       // least number of workgroups a persistent-over-heads launch should have
     float* dbc_part;     // [Bt][nc][G][part_split][2][Q][N] per-slice head terms of dC (0) and dB (1)
     // state plumbing for the scans (all fp32, element strides between batches)
