@@ -365,14 +365,15 @@ __device__ __forceinline__ void dg_body(const SegParams& sp, DgLds<Q>& L, int z,
     }
     __syncthreads();
     dg_emit_sums<Q>(sp, L, rsrc, b, c, h0 + hps - 1, w, lane);
-    // partial sum of this slice, bf16 [Q][Q] row-major (tiles above the diagonal are never touched)
+    // partial sum of this slice, bf16, tile by tile: tile (ti, tj) is the 32 x 32 row-major block number ti NT + tj,
+    // so that the pass that sums the slices reads whole cache lines (tiles above the diagonal are never touched)
     __bf16* out = (__bf16*)sp.dG + ((((int64_t)b * sp.nc + c) * sp.G + g) * ns + slice) * ((int64_t)Q * Q);
 #pragma unroll
     for (int k = 0; k < MAXT; ++k)
         if (k < cnt) {
-            __bf16* o = out + (int64_t)(32 * M::ti(w, k) + 4 * (lane >> 5)) * Q + 32 * M::tj(w, k) + (lane & 31);
+            __bf16* o = out + ((M::ti(w, k) * M::NT + M::tj(w, k)) * 32 + 4 * (lane >> 5)) * 32 + (lane & 31);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[(int64_t)(8 * (r >> 2) + (r & 3)) * Q] = (__bf16)acc[k][r];
+            for (int r = 0; r < 16; ++r) o[(8 * (r >> 2) + (r & 3)) * 32] = (__bf16)acc[k][r];
         }
 }
 
@@ -623,15 +624,15 @@ __global__ __launch_bounds__(512) void mk_bwd_trio(SegParams sp, int n_dual, int
 // dC rows (role 0) / dB rows (role 1) of one 32-token tile R of one (chunk, group):
 //   role 0: out[i][n] = sum_{tj <= R} dG[R-tile rows][tj-tile cols] B[tj-tile rows][n] + head sums
 //   role 1: out[j][n] = sum_{ti >= R} dG[ti-tile rows][R-tile cols]^T C[ti-tile rows][n] + head sums
-// Wave w sums the slices of tiles w, w + 4 into LDS (bf16); then every wave owns 32 state columns.
+// The waves share out the halves of the needed dG tiles and sum their slices into LDS (bf16); then every wave
+// owns 32 state columns of the contraction.
 template <int Q>
 struct FinLds {
     char tiles[Q / 32][32 * TP];
     char slab[64 * BPITCH];  // rows of B / C along the contraction, 64 at a time
 };
 
-// Small footprint on purpose (37 KB of LDS, few registers): the kernel only streams partial sums, and
-// several workgroups per compute unit keep enough loads in flight to do that at memory speed.
+// Small footprint on purpose (37 KB of LDS): the kernel only streams partial sums.
 template <int Q>
 __device__ __forceinline__ void final_body(const SegParams& sp, FinLds<Q>& L, int z) {
     constexpr int NT = Q / 32;
@@ -648,48 +649,93 @@ __device__ __forceinline__ void final_body(const SegParams& sp, FinLds<Q>& L, in
     const int k_lo = role == 0 ? 0 : R, k_hi = role == 0 ? R : NT - 1;  // tiles along the contraction
     const int ns = sp.dg_split;
     const bf16_t* dg = (const bf16_t*)sp.dG + bcg * ns * ((int64_t)Q * Q);
-    // the head sums of this workgroup's rows: every slice's 16 values per lane asked for first, summed at the end
     const int ps = sp.part_split;
     const float* part = sp.dbc_part + (bcg * ps * 2 + role) * ((int64_t)Q * N_);
     f32x16 acc = zero16();
-    // sum the slices of the needed dG tiles (one 16-byte piece of a tile per lane and pass, eight slices in flight)
-    for (int tk = k_lo + w; tk <= k_hi; tk += NTH / 64) {
-        const int ti = role == 0 ? R : tk, tj = role == 0 ? tk : R;
+    // Everything below is a chain of memory round trips on a workgroup that has the compute unit almost to itself,
+    // so each step asks for what the next one needs before it works: the first rows of B / C before the tile sums,
+    // the head sums before the contraction.
+    const int p_lo = k_lo >> 1, p_hi = k_hi >> 1;  // pairs of tiles along the contraction
+    constexpr int SV = 64 * 16 / NTH;              // 16-byte pieces of a 64-row slab per thread
+    bf16x8 sv[SV];
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
+    for (int k = 0; k < SV; ++k) {
+        const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
+        sv[k] = *(const bf16x8*)(rhs + (int64_t)(64 * p_lo + row) * bt + seg * 8);
+    }
+    // sum the slices of the needed dG tiles: items (tile, half of its rows), two items and eight slices of each in
+    // flight per wave; one 16-byte piece per lane and item
+    const int nitems = 2 * (k_hi - k_lo + 1);
+    for (int it = w; it < nitems; it += 2 * (NTH / 64)) {
+        const bf16_t* src[2];
+        char* dst[2];
+        const bool two = it + NTH / 64 < nitems;
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const int item = q == 0 || two ? it + q * (NTH / 64) : it;
+            const int tk = k_lo + (item >> 1), half = item & 1;
+            const int ti = role == 0 ? R : tk, tj = role == 0 ? tk : R;
             const int v = lane + 64 * half, row = v >> 2, seg = v & 3;
-            const bf16_t* src = dg + (int64_t)(32 * ti + row) * Q + 32 * tj + seg * 8;
-            float s[8];
+            src[q] = dg + ((ti * NT + tj) * 32 + row) * 32 + seg * 8;  // tile-major, see dg_body
+            dst[q] = L.tiles[tk] + row * TP + seg * 16;
+        }
+        float sm[2][8];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) s[e] = 0.f;
-            int sl = 0;
-            for (; sl + 8 <= ns; sl += 8) {  // summation order stays slice 0, 1, 2, ...
-                bf16x8 vv[8];
+        for (int q = 0; q < 2; ++q)
 #pragma unroll
-                for (int u = 0; u < 8; ++u) vv[u] = *(const bf16x8*)(src + (int64_t)(sl + u) * Q * Q);
+            for (int e = 0; e < 8; ++e) sm[q][e] = 0.f;
+        int sl = 0;
+        for (; sl + 8 <= ns; sl += 8) {  // summation order stays slice 0, 1, 2, ...
+            bf16x8 vv[2][8];
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
+#pragma unroll
+                for (int u = 0; u < 8; ++u) vv[q][u] = *(const bf16x8*)(src[q] + (int64_t)(sl + u) * Q * Q);
+#pragma unroll
+            for (int q = 0; q < 2; ++q)
 #pragma unroll
                 for (int u = 0; u < 8; ++u)
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) s[e] += (float)vv[u][e];
-            }
-            for (; sl < ns; ++sl) {
-                const bf16x8 vv = *(const bf16x8*)(src + (int64_t)sl * Q * Q);
+                    for (int e = 0; e < 8; ++e) sm[q][e] += (float)vv[q][u][e];
+        }
+        for (; sl < ns; ++sl) {
 #pragma unroll
-                for (int e = 0; e < 8; ++e) s[e] += (float)vv[e];
+            for (int q = 0; q < 2; ++q) {
+                const bf16x8 vv = *(const bf16x8*)(src[q] + (int64_t)sl * Q * Q);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) sm[q][e] += (float)vv[e];
             }
+        }
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
             bf16x8 o;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) o[e] = (__bf16)s[e];
-            *(bf16x8*)(L.tiles[tk] + row * TP + seg * 16) = o;
+            for (int e = 0; e < 8; ++e) o[e] = (__bf16)sm[q][e];
+            if (q == 0 || two) *(bf16x8*)dst[q] = o;
         }
     }
+    // the head sums of this workgroup's rows, up to four slices asked for now and added after the contraction
+    constexpr int PSR = 4;
+    float pv[PSR][16];
+#pragma unroll
+    for (int s4 = 0; s4 < PSR; ++s4)
+#pragma unroll
+        for (int r = 0; r < 16; ++r)
+            pv[s4][r] = s4 < ps ? part[(int64_t)s4 * 2 * Q * N_ + (int64_t)(32 * R + acc_row(r, lane)) * N_ + 32 * w + (lane & 31)] : 0.f;
     // contraction with the rows of B (role 0) / C (role 1), 64 rows (two tiles) per step
-    const int p_lo = k_lo >> 1, p_hi = k_hi >> 1;  // pairs of tiles
     for (int pr = p_lo; pr <= p_hi; ++pr) {
         if (pr > p_lo) __syncthreads();  // every wave is done with the previous rows
-        for (int v = tid; v < 64 * 16; v += NTH) {
-            const int row = v >> 4, seg = v & 15;
-            *(bf16x8*)(L.slab + row * BPITCH + seg * 16) = *(const bf16x8*)(rhs + (int64_t)(64 * pr + row) * bt + seg * 8);
+#pragma unroll
+        for (int k = 0; k < SV; ++k) {
+            const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
+            *(bf16x8*)(L.slab + row * BPITCH + seg * 16) = sv[k];
+        }
+        if (pr < p_hi) {
+#pragma unroll
+            for (int k = 0; k < SV; ++k) {
+                const int v = tid + NTH * k, row = v >> 4, seg = v & 15;
+                sv[k] = *(const bf16x8*)(rhs + (int64_t)(64 * (pr + 1) + row) * bt + seg * 8);
+            }
         }
         __syncthreads();  // the rows (and, the first time, the summed tiles) are in place
         const char* slab = L.slab;
@@ -708,14 +754,17 @@ __device__ __forceinline__ void final_body(const SegParams& sp, FinLds<Q>& L, in
         }
     }
     bf16_t* out = (role == 0 ? (bf16_t*)sp.dC : (bf16_t*)sp.dB) + bbase;
-    // the head sums arrive slice by slice, all 16 rows of a slice in flight at once
-    for (int s = 0; s < ps; ++s) {
-        float pv[16];
+#pragma unroll
+    for (int s4 = 0; s4 < PSR; ++s4)  // slice order 0, 1, 2, ...
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[r] += pv[s4][r];
+    for (int s = PSR; s < ps; ++s) {
+        float pw[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r)
-            pv[r] = part[(int64_t)s * 2 * Q * N_ + (int64_t)(32 * R + acc_row(r, lane)) * N_ + 32 * w + (lane & 31)];
+            pw[r] = part[(int64_t)s * 2 * Q * N_ + (int64_t)(32 * R + acc_row(r, lane)) * N_ + 32 * w + (lane & 31)];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) acc[r] += pv[r];
+        for (int r = 0; r < 16; ++r) acc[r] += pw[r];
     }
 #pragma unroll
     for (int r = 0; r < 16; ++r)

@@ -70,7 +70,7 @@ struct SegParams {
     float* states;     // generic path only: [Bt][nc+1][H][P][N]  slot c: state entering chunk c; slot nc: state leaving the segment
     float* dstates;    // generic path only: [Bt][nc][H][P][N]    slot c: adjoint of the state leaving chunk c
     float* Gm;         // [Bt][nc][G][Q][Q]    C_i . B_j   (generic path: fp32)
-    float* dG;         // generic path: [Bt][nc][G][Q][Q] fp32 head-summed masked dY X^T; MFMA path: [Bt][nc][G][dg_split][Q][Q] bf16 per-slice sums
+    float* dG;         // generic path: [Bt][nc][G][Q][Q] fp32 head-summed masked dY X^T; MFMA path: [Bt][nc][G][dg_split][Q/32][Q/32][32][32] bf16 per-slice sums, tile by tile
     float* gterm;      // [Bt][H][nc][Q]  gradient of cum, per token (MFMA path: the part through the entering state)
     float* sterm;      // [Bt][H][nc][Q]  MFMA path: dt_j x_j . (part of u_j through the leaving adjoint); subtracted
     float* gintra;     // [Bt][H][nc][Q]  MFMA path: chunk-local part (row sums minus column sums of E); added
