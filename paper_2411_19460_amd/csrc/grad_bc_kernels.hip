@@ -498,9 +498,17 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& LL, i
     part_store<Q>(pr, LL.b[0], role, tid);
     if (hps > 1) part_load<Q>(pr, sp, role, b, c, head_at(1), tid);
     __syncthreads();
+    // The two waves of a SIMD (w and w + NWV / 2) take the phases of a head in different orders -- the later one stages the
+    // next head (vector ALU work) first, the other last -- so that one is on the vector ALUs while the other feeds the
+    // matrix core.  The next head goes into the other LDS buffer, which nobody reads during this iteration.
+    const bool stage_first = w >= CF::NWV / 2;
     for (int hh = 0; hh < hps; ++hh) {
         SSDK_STAMP(2, 0);
         const PartBuf<Q>& L = LL.b[hh & 1];
+        if (stage_first) {
+            if (hh + 1 < hps) part_store<Q>(pr, LL.b[(hh + 1) & 1], role, tid);
+            if (hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, head_at(hh + 2), tid);
+        }
         {   // operand reads run one contraction step ahead of their MFMAs
             bf16x8 fb0 = frag_tr(L.st, BPITCH, 0, 64 * nh, lane), fb1 = frag_tr(L.st, BPITCH, 0, 64 * nh + 32, lane);
             bf16x8 fa[RT];
@@ -562,9 +570,9 @@ __device__ __forceinline__ void part_body(const SegParams& sp, PartLds<Q>& LL, i
         }
         SSDK_STAMP(2, 2);
         // the next head: its loads were issued a whole head ago; stage it into the other buffer, then ask for the one after
-        if (hh + 1 < hps) part_store<Q>(pr, LL.b[(hh + 1) & 1], role, tid);
+        if (!stage_first && hh + 1 < hps) part_store<Q>(pr, LL.b[(hh + 1) & 1], role, tid);
         SSDK_STAMP(2, 3);
-        if (hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, head_at(hh + 2), tid);
+        if (!stage_first && hh + 2 < hps) part_load<Q>(pr, sp, role, b, c, head_at(hh + 2), tid);
         SSDK_STAMP(2, 4);
         __syncthreads();
         SSDK_STAMP(2, 5);
