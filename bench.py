@@ -702,8 +702,8 @@ def stack_bench(cfg, steps, warmup, pk, synth, torch, dev):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=6)
-    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--config", type=int, default=2, help="index into the benchmark's config list (default: 2.7B shape, L=65536)")
     ap.add_argument("--segment", type=int, default=0, help="checkpoint interval in tokens (default: the config's)")
     ap.add_argument("--generic", action="store_true", help="force the shape-generic kernels")
