@@ -98,8 +98,9 @@ __device__ __forceinline__ void load_pre(Pre<Q>& pr, const SegParams& sp, int b,
     }
     const bf16_t* S = (REV ? sp.dstates_bf : sp.states_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
     const uint32_t soff = (uint32_t)tid * 16;
+    // the state tile has this one reader: streaming load
 #pragma unroll
-    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff);
+    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = __builtin_nontemporal_load((const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff));
     if (tid < Q) {
         pr.cum = sp.cum[cbase + tid];
         pr.dtf = sp.dtf[cbase + tid];
@@ -308,7 +309,8 @@ __device__ __forceinline__ void tile_compute(const bf16x8 (&go)[GO_MAX], const b
     for (int it = 0; it < 4; ++it) {
         const int row = (lane >> 3) + 8 * it;
         const bf16x8 v = *(const bf16x8*)(priv + row * XPITCH + (lane & 7) * 16);
-        *(bf16x8*)((char*)(cx.outp + (int64_t)(tok0 + 8 * it) * cx.xt) + (size_t)rowoff) = v;
+        // written once and not read again by this step: a streaming store leaves the L2 to the tiles the passes share
+        __builtin_nontemporal_store(v, (bf16x8*)((char*)(cx.outp + (int64_t)(tok0 + 8 * it) * cx.xt) + (size_t)rowoff));
     }
     if (EPI != 0) {
         s_a += __shfl_xor(s_a, 32, 64);

@@ -441,8 +441,9 @@ __device__ __forceinline__ void part_load(PartPre<Q>& pr, const SegParams& sp, i
     }
     const bf16_t* S = (role == 0 ? sp.states_bf : sp.dstates_bf) + (((int64_t)b * sp.nc + c) * sp.H + h) * (P_ * N_);
     const uint32_t soff = (uint32_t)tid * 16;
+    // the state tile has this one reader: streaming load (the token tile above is shared with the other passes)
 #pragma unroll
-    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = *(const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff);
+    for (int k = 0; k < CF::SV; ++k) pr.sv[k] = __builtin_nontemporal_load((const bf16x8*)((const char*)S + (size_t)k * CF::NTHR * 16 + (size_t)soff));
 }
 
 template <int Q>

@@ -162,7 +162,8 @@ __device__ __forceinline__ void outer_load(OuterPre<Q>& pr, const SegParams& sp,
     const uint32_t roff = (uint32_t)(t8 >> 3) * 4;
 #pragma unroll
     for (int k = 0; k < OuterPre<Q>::NV; ++k) {
-        pr.t[k] = *(const bf16x8*)((const char*)src + (size_t)k * (OUTER_THR / 8) * rowbytes + (size_t)off);
+        // one reader per launch: streaming load (keeps the L2 for the kernels of other segments that do share tiles)
+        pr.t[k] = __builtin_nontemporal_load((const bf16x8*)((const char*)src + (size_t)k * (OUTER_THR / 8) * rowbytes + (size_t)off));
         pr.cv[k] = *(const float*)((const char*)(sp.cum + cbase + k * (OUTER_THR / 8)) + (size_t)roff);
         pr.dv[k] = *(const float*)((const char*)(sp.dtf + cbase + k * (OUTER_THR / 8)) + (size_t)roff);
     }
