@@ -214,49 +214,35 @@ __device__ __forceinline__ float xor16_f(float v) {  // lane ^ 16 (bit-mask swiz
     return __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));
 }
 
-// Sum of each of the 16 registers over the 32 lanes of a half wave, by recursive halving: at every
-// step a lane keeps half of its registers, hands the other half to a partner whose matching lane bit
-// differs, and adds what it receives.  Partners: lane ^ 16, lane ^ 8 (row_ror:8), lane ^ 7
-// (row_half_mirror: bit 2 differs, and the pairs of the last two steps still cover every lane once),
-// lane ^ 2, lane ^ 1 (quad_perm).  After the five steps lane l holds the total of the register selected
-// by bits 4..1 of l.  The result goes to dst[row], row being the tile-local row of that register for
-// the lane's half (even lanes write).
-// (sel() hides its operands from the optimiser for a moment: a select between two elements of one
-// register vector would otherwise be rewritten as a dynamically indexed element, i.e. a chain of
+// Sum of each of the 16 registers over the 32 lanes of a half wave.  First step across the two rows of 16 lanes
+// (lane ^ 16, ds_swizzle): afterwards the lanes of the even row keep the sums of registers 0..7, those of the odd
+// row the sums of registers 8..15.  Then a butterfly inside the row of 16 lanes with DPP adds (lane ^ 1, lane ^ 2,
+// mirror of 8, mirror of 16): every lane of a row ends with the eight totals of its row's registers, and the first
+// lane of each row writes them, dst[row] being the tile-local row of the register for the lane's half.
+// (The two candidates of the first step are pinned in registers for a moment: a select between sums of two
+// elements of one register vector would otherwise be rewritten as a dynamically indexed element, i.e. a chain of
 // sixteen compare-and-select instructions.)
-__device__ __forceinline__ float sel(bool c, float a, float b) {
-    asm volatile("" : "+v"(a), "+v"(b));
-    return c ? a : b;
-}
-
 __device__ __forceinline__ void row_reduce_store(const f32x16& v, float* dst, int lane) {
-    float a[8], b4[4], c2[2], d1;
+    float a[8];
+    const bool odd_row = lane & 16;
 #pragma unroll
     for (int r = 0; r < 8; ++r) {
-        const bool hi = lane & 16;
-        const float keep = sel(hi, v[r + 8], v[r]), send = sel(hi, v[r], v[r + 8]);
-        a[r] = keep + xor16_f(send);
+        float lo = v[r] + xor16_f(v[r]), hi = v[r + 8] + xor16_f(v[r + 8]);
+        asm volatile("" : "+v"(lo), "+v"(hi));
+        a[r] = odd_row ? hi : lo;
     }
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const bool hi = lane & 8;
-        const float keep = sel(hi, a[r + 4], a[r]), send = sel(hi, a[r], a[r + 4]);
-        b4[r] = keep + dpp_f<0x128>(send);
+    for (int r = 0; r < 8; ++r) {
+        a[r] += dpp_f<0xB1>(a[r]);   // lane ^ 1
+        a[r] += dpp_f<0x4E>(a[r]);   // lane ^ 2
+        a[r] += dpp_f<0x141>(a[r]);  // the other quad of the same 8 lanes (row_half_mirror)
+        a[r] += dpp_f<0x140>(a[r]);  // the other 8 lanes of the row (row_mirror)
     }
-#pragma unroll
-    for (int r = 0; r < 2; ++r) {
-        const bool hi = lane & 4;
-        const float keep = sel(hi, b4[r + 2], b4[r]), send = sel(hi, b4[r], b4[r + 2]);
-        c2[r] = keep + dpp_f<0x141>(send);
+    if ((lane & 15) == 0) {  // registers R = 8 (odd row) + r: tile-local row 8 (R / 4) + 4 (lane / 32) + R % 4
+        float* o = dst + (odd_row ? 16 : 0) + 4 * (lane >> 5);
+        *(float4*)o = make_float4(a[0], a[1], a[2], a[3]);
+        *(float4*)(o + 8) = make_float4(a[4], a[5], a[6], a[7]);
     }
-    {
-        const bool hi = lane & 2;
-        const float keep = sel(hi, c2[1], c2[0]), send = sel(hi, c2[0], c2[1]);
-        d1 = keep + dpp_f<0x4E>(send);
-    }
-    d1 += dpp_f<0xB1>(d1);
-    const int r = ((lane >> 4) & 1) * 8 + ((lane >> 3) & 1) * 4 + ((lane >> 2) & 1) * 2 + ((lane >> 1) & 1);
-    if (!(lane & 1)) dst[8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)] = d1;
 }
 
 // Where the partial sums of one tile row lie in LDS (wave-uniform; worked out once per workgroup).
